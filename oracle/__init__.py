@@ -1,0 +1,215 @@
+"""ctypes front end of the CPU oracle (``cmpq_oracle.c``).
+
+TEST INFRASTRUCTURE ONLY: imported by ``tests/``, by ``__graft_entry__.smoke``
+and by the ``cpu_baseline`` leg of ``bench.py``.  The product package never
+imports this module, and this module never imports the product package.
+
+All arrays are NumPy, host resident, in the paper's orientation
+(Sec. 3.2.1): ``W[d_in, d_out]``, row ``i`` = input channel ``i``.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Optional, Sequence, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "cmpq_oracle.c")
+_LIB = os.path.join(_HERE, "libcmpq_oracle.so")
+
+KMAX = 16
+PROTECTED = 16
+SCORE_RESIDUAL = 0
+SCORE_MAGNITUDE = 1
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc.  No fast-math and no FMA contraction, so
+    every operation rounds the way the source reads."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-ffp-contract=off", "-fno-fast-math",
+               "-shared", "-fPIC", "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+        subprocess.check_call(cmd)
+    return _LIB
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        _lib = ctypes.CDLL(build())
+        _lib.orc_count_ppm.restype = ctypes.c_int64
+        _lib.orc_count_ppm.argtypes = [ctypes.c_int64, ctypes.c_int64]
+        _lib.orc_pack.restype = ctypes.c_int64
+        _lib.orc_f32_to_f16.restype = ctypes.c_uint16
+        _lib.orc_f32_to_f16.argtypes = [ctypes.c_float]
+        _lib.orc_f16_to_f64.restype = ctypes.c_double
+        _lib.orc_f16_to_f64.argtypes = [ctypes.c_uint16]
+    return _lib
+
+
+def _p(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _dtype_code(a: np.ndarray) -> int:
+    if a.dtype == np.float16:
+        return 0
+    if a.dtype == np.float32:
+        return 1
+    raise TypeError(f"oracle takes float16 or float32, got {a.dtype}")
+
+
+def _c(a, dtype=None) -> np.ndarray:
+    a = np.ascontiguousarray(a) if dtype is None else np.ascontiguousarray(a, dtype=dtype)
+    return a
+
+
+def count_ppm(ppm: int, n: int) -> int:
+    return int(lib().orc_count_ppm(int(ppm), int(n)))
+
+
+def f32_to_f16_bits(x: float) -> int:
+    return int(lib().orc_f32_to_f16(ctypes.c_float(x)))
+
+
+def f16_bits_to_f64(h: int) -> float:
+    return float(lib().orc_f16_to_f64(ctypes.c_uint16(h)))
+
+
+def act_stats(X: np.ndarray, acc: Optional[np.ndarray] = None) -> Tuple[np.ndarray, np.ndarray]:
+    """Returns ``(acc float64[d_in], sumsq float32[d_in])``; pass ``acc`` back in to add tokens."""
+    X = _c(X)
+    n, d_in = X.shape
+    acc = np.zeros(d_in, np.float64) if acc is None else _c(acc, np.float64).copy()
+    sumsq = np.zeros(d_in, np.float32)
+    rc = lib().orc_act_stats(_p(X), _dtype_code(X), ctypes.c_int64(n), ctypes.c_int64(d_in),
+                             ctypes.c_int64(d_in), _p(acc), _p(sumsq))
+    assert rc == 0, rc
+    return acc, sumsq
+
+
+def top_channels(sumsq: np.ndarray, k: int) -> Tuple[np.ndarray, np.ndarray]:
+    sumsq = _c(sumsq, np.float32)
+    d_in = sumsq.shape[0]
+    idx = np.zeros(max(k, 1), np.int32)
+    mask = np.zeros(d_in, np.uint8)
+    rc = lib().orc_top_channels(_p(sumsq), ctypes.c_int64(d_in), ctypes.c_int64(k), _p(idx), _p(mask))
+    assert rc == 0, rc
+    return idx[:k], mask
+
+
+def allocate_bits(sumsq: np.ndarray, chan_mask: Optional[np.ndarray], bit_set: Sequence[int],
+                  avg_bits: float) -> Tuple[np.ndarray, np.ndarray]:
+    sumsq = _c(sumsq, np.float32)
+    d_in = sumsq.shape[0]
+    bs = np.asarray(bit_set, np.int32)
+    bits = np.zeros(d_in, np.uint8)
+    counts = np.zeros(len(bs), np.int64)
+    cm = None if chan_mask is None else _c(chan_mask, np.uint8)
+    rc = lib().orc_allocate_bits(_p(sumsq), ctypes.c_int64(d_in), _p(cm), _p(bs), len(bs),
+                                 ctypes.c_double(avg_bits), _p(bits), _p(counts))
+    if rc != 0:
+        raise ValueError(f"orc_allocate_bits rc={rc}")
+    return bits, counts
+
+
+def kmeans(W: np.ndarray, bits: np.ndarray, out_idx: Optional[np.ndarray] = None,
+           elem_weight: Optional[np.ndarray] = None, iters: int = 20, trace: bool = False):
+    """Returns ``(centroids float32[d_in,16], codes uint8[d_in,d_out][, sse float64[d_in,iters+1]])``."""
+    W = _c(W)
+    d_in, d_out = W.shape
+    bits = _c(bits, np.uint8)
+    oi = None if out_idx is None else _c(out_idx, np.int64)
+    ew = None if elem_weight is None else _c(elem_weight, np.float32)
+    cent = np.zeros((d_in, KMAX), np.float32)
+    codes = np.zeros((d_in, d_out), np.uint8)
+    sse = np.zeros((d_in, iters + 1), np.float64) if trace else None
+    rc = lib().orc_kmeans(_p(W), _dtype_code(W), ctypes.c_int64(d_in), ctypes.c_int64(d_out),
+                          ctypes.c_int64(d_out), _p(bits), _p(oi),
+                          ctypes.c_int64(0 if oi is None else oi.shape[0]), _p(ew),
+                          int(iters), _p(cent), _p(codes), _p(sse))
+    assert rc == 0, rc
+    return (cent, codes, sse) if trace else (cent, codes)
+
+
+def weight_outliers(W: np.ndarray, centroids: Optional[np.ndarray], codes: Optional[np.ndarray],
+                    bits: np.ndarray, k: int, score: int = SCORE_RESIDUAL):
+    """Returns ``(idx int64[k] ascending, val uint16[k] = FP16 bit patterns)``."""
+    W = _c(W)
+    d_in, d_out = W.shape
+    bits = _c(bits, np.uint8)
+    cent = None if centroids is None else _c(centroids, np.float32)
+    cd = None if codes is None else _c(codes, np.uint8)
+    idx = np.zeros(max(k, 1), np.int64)
+    val = np.zeros(max(k, 1), np.uint16)
+    rc = lib().orc_weight_outliers(_p(W), _dtype_code(W), ctypes.c_int64(d_in), ctypes.c_int64(d_out),
+                                   ctypes.c_int64(d_out), _p(cent), _p(cd), _p(bits), int(score),
+                                   ctypes.c_int64(k), _p(idx), _p(val))
+    if rc != 0:
+        raise ValueError(f"orc_weight_outliers rc={rc}")
+    return idx[:k], val[:k]
+
+
+def pack(codes: np.ndarray, bits: np.ndarray, centroids: np.ndarray, b: int):
+    """Returns ``(packed uint32[rows, ceil(d_out*b/32)], chan_idx int32[rows], lut uint16[rows, 2^b])``."""
+    codes = _c(codes, np.uint8)
+    d_in, d_out = codes.shape
+    bits = _c(bits, np.uint8)
+    cent = _c(centroids, np.float32)
+    rows = int((bits == b).sum())
+    wpr = (d_out * b + 31) // 32
+    packed = np.zeros((max(rows, 1), max(wpr, 1)), np.uint32)
+    chan = np.zeros(max(rows, 1), np.int32)
+    lut = np.zeros((max(rows, 1), 1 << b), np.uint16)
+    r = lib().orc_pack(_p(codes), ctypes.c_int64(d_in), ctypes.c_int64(d_out), _p(bits), _p(cent),
+                       int(b), _p(packed), _p(chan), _p(lut))
+    assert r == rows, (r, rows)
+    return packed[:rows, :wpr], chan[:rows], lut[:rows]
+
+
+def dequant_error(W: np.ndarray, centroids: np.ndarray, codes: np.ndarray, bits: np.ndarray,
+                  out_idx: Optional[np.ndarray] = None, sumsq: Optional[np.ndarray] = None):
+    """Returns ``(err_ch float64[d_in], totals float64[2] = [activation weighted, plain])``."""
+    W = _c(W)
+    d_in, d_out = W.shape
+    oi = None if out_idx is None else _c(out_idx, np.int64)
+    ss = None if sumsq is None else _c(sumsq, np.float32)
+    err = np.zeros(d_in, np.float64)
+    tot = np.zeros(2, np.float64)
+    rc = lib().orc_dequant_error(_p(W), _dtype_code(W), ctypes.c_int64(d_in), ctypes.c_int64(d_out),
+                                 ctypes.c_int64(d_out), _p(_c(centroids, np.float32)),
+                                 _p(_c(codes, np.uint8)), _p(_c(bits, np.uint8)), _p(oi),
+                                 ctypes.c_int64(0 if oi is None else oi.shape[0]), _p(ss),
+                                 _p(err), _p(tot))
+    assert rc == 0, rc
+    return err, tot
+
+
+def quantize_layer(W: np.ndarray, X: np.ndarray, bit_set: Sequence[int], avg_bits: float,
+                   rho_act_ppm: int = 4500, rho_q_ppm: int = 500, iters: int = 20,
+                   sumsq: Optional[np.ndarray] = None, score: int = SCORE_RESIDUAL) -> dict:
+    """The whole path of Sec. 3.2, step by step, on one layer.
+
+    ``W`` is ``[d_in, d_out]`` (paper orientation), ``X`` is ``[n, d_in]``.
+    """
+    d_in, d_out = W.shape
+    if sumsq is None:
+        _, sumsq = act_stats(X)
+    k_act = count_ppm(rho_act_ppm, d_in)
+    act_idx, chan_mask = top_channels(sumsq, k_act)                      # O_act
+    bits, counts = allocate_bits(sumsq, chan_mask, bit_set, avg_bits)     # Algorithm 1 on W'
+    cent1, codes1 = kmeans(W, bits, iters=iters)                          # W'_q
+    k_q = count_ppm(rho_q_ppm, d_in * d_out)
+    out_idx, out_val = weight_outliers(W, cent1, codes1, bits, k_q, score)  # O_q
+    cent, codes = kmeans(W, bits, out_idx=out_idx, iters=iters)           # W_q
+    packs = {b: pack(codes, bits, cent, b) for b in bit_set}
+    err_ch, totals = dequant_error(W, cent, codes, bits, out_idx, sumsq)
+    return dict(sumsq=sumsq, act_idx=act_idx, chan_mask=chan_mask, bits=bits, counts=counts,
+                cent1=cent1, codes1=codes1, out_idx=out_idx, out_val=out_val, centroids=cent,
+                codes=codes, packs=packs, err_ch=err_ch, totals=totals)

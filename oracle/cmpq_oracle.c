@@ -1,0 +1,488 @@
+/*
+ * CPU oracle for the CMPQ quantization path (arXiv 2410.13056).
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain statement of what
+ * the path computes, written from the paper.  Nothing in the product path may
+ * call it; it shares no code with the HIP kernels.  Floating point is fp64
+ * throughout, loops run in index order, and the only parallelism is an OpenMP
+ * "parallel for" over independent input channels (or columns).
+ *
+ * Orientation follows the paper (Sec. 3.2.1): W is d_in x d_out and
+ * "channel i" is the row W[i,:] (all weights that multiply input feature i).
+ * Tensors are row-major with an explicit leading dimension.
+ *
+ * Steps, in the order of Sec. 3.2.1 / 3.2.2:
+ *   orc_act_stats        a_i^2 = sum_t X[t,i]^2           (Sec. 3.2.1, "per-channel L2-norm of X")
+ *   orc_top_channels     O_act: channels with the largest a (Sec. 3.2.2)
+ *   orc_allocate_bits    Algorithm 1, integer-budget reading
+ *   orc_kmeans           per-channel K-means, K = 2^c_i      (Sec. 3.2.1; Sec. 3 eq. Q(x))
+ *   orc_weight_outliers  O_q: largest |W' - W'_q|           (Sec. 3.2.2)
+ *   orc_pack             per-width code matrices + FP16 look-up tables (Sec. 5.1, Fig. 4)
+ *   orc_dequant_error    W_hat = W_q + O and ||X (W - W_hat)|| (Sec. 3.2.2; App. B.3 eq. Delta Y)
+ *
+ * Parity pins (tests/ -m "not gpu") cover every function here; none is
+ * "parity unpinned" except the k-means trajectory on large inputs, which is
+ * fixed by the readings stated at orc_kmeans and pinned through invariants
+ * and brute force on small cases.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define ORC_F16 0
+#define ORC_F32 1
+#define ORC_KMAX 16
+#define ORC_PROTECTED 16 /* value of bits[i] for a channel kept in FP16 */
+
+/* ---- IEEE binary16 <-> double, written out bit by bit ---------------------------------- */
+
+static double half_to_double(uint16_t h) {
+    int sign = (h >> 15) & 1;
+    int e = (h >> 10) & 0x1f;
+    int m = h & 0x3ff;
+    double v;
+    if (e == 0)
+        v = ldexp((double)m, -24); /* subnormal: m * 2^-24 */
+    else if (e == 31)
+        v = m ? NAN : INFINITY;
+    else
+        v = ldexp((double)(m + 1024), e - 25); /* (1 + m/1024) * 2^(e-15) */
+    return sign ? -v : v;
+}
+
+/* round-to-nearest-even conversion of a double to binary16 */
+static uint16_t double_to_half(double d) {
+    uint16_t sign = (uint16_t)(signbit(d) ? 0x8000 : 0);
+    double a = fabs(d);
+    if (isnan(d)) return (uint16_t)(sign | 0x7e00);
+    if (a >= 65520.0) return (uint16_t)(sign | 0x7c00); /* rounds to infinity */
+    if (a < ldexp(1.0, -25)) return sign;               /* below half the smallest subnormal */
+    int ex;
+    (void)frexp(a, &ex); /* a = f * 2^ex, f in [0.5,1) ; unbiased exponent = ex-1 */
+    int e = ex - 1;
+    if (e < -14) e = -14;                /* subnormal range: quantum 2^-24 */
+    double q = ldexp(1.0, e - 10);       /* spacing of half values near a */
+    double r = nearbyint(a / q);         /* ties to even (default rounding mode) */
+    double v = r * q;
+    /* re-encode v exactly */
+    if (v < ldexp(1.0, -14)) return (uint16_t)(sign | (uint16_t)(v / ldexp(1.0, -24)));
+    (void)frexp(v, &ex);
+    e = ex - 1;
+    int m = (int)(v / ldexp(1.0, e - 10)) - 1024;
+    return (uint16_t)(sign | ((e + 15) << 10) | m);
+}
+
+static double load_elem(const void *p, int dtype, int64_t off) {
+    if (dtype == ORC_F16) return half_to_double(((const uint16_t *)p)[off]);
+    return (double)((const float *)p)[off];
+}
+
+uint16_t orc_f32_to_f16(float f) { return double_to_half((double)f); }
+double orc_f16_to_f64(uint16_t h) { return half_to_double(h); }
+
+/* ---- Sec. 3.2.1: per-channel activation statistic --------------------------------------- */
+
+/*
+ * acc[i] += sum_t X[t,i]^2 over the n rows given; sumsq[i] = (float)acc[i].
+ * The paper ranks channels by the L2 norm a_i = sqrt(acc[i]); the square is
+ * kept instead (same order, no extra rounding), and doubles as the channel
+ * weight of the output error (App. B.3).  acc is in/out so that X can arrive
+ * in chunks of tokens.
+ */
+int orc_act_stats(const void *X, int dtype, int64_t n, int64_t d_in, int64_t ldx,
+                  double *acc, float *sumsq) {
+    if (!X || !acc || n < 0 || d_in < 0 || ldx < d_in) return -1;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < d_in; ++i) {
+        double s = acc[i];
+        for (int64_t t = 0; t < n; ++t) {
+            double x = load_elem(X, dtype, t * ldx + i);
+            s += x * x;
+        }
+        acc[i] = s;
+        if (sumsq) sumsq[i] = (float)s;
+    }
+    return 0;
+}
+
+/* ---- ranking with a total order ----------------------------------------------------------- */
+
+typedef struct {
+    uint32_t key;
+    int64_t idx;
+} keyidx_t;
+
+/* larger key first; equal keys: smaller index first */
+static int cmp_keyidx(const void *a, const void *b) {
+    const keyidx_t *x = (const keyidx_t *)a, *y = (const keyidx_t *)b;
+    if (x->key != y->key) return x->key > y->key ? -1 : 1;
+    if (x->idx != y->idx) return x->idx < y->idx ? -1 : 1;
+    return 0;
+}
+
+static int cmp_i64(const void *a, const void *b) {
+    int64_t x = *(const int64_t *)a, y = *(const int64_t *)b;
+    return x < y ? -1 : (x > y ? 1 : 0);
+}
+
+static uint32_t float_bits(float f) {
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    return u;
+}
+
+/*
+ * Sec. 3.2.2, O_act: the k channels with the largest activation statistic stay
+ * in FP16.  Order: larger value first, equal values by smaller channel index.
+ * idx_out[k] ascending; chan_mask[i] = 1 for a selected channel.
+ * The statistic is non-negative, so its fp32 bit pattern orders like the value.
+ */
+int orc_top_channels(const float *sumsq, int64_t d_in, int64_t k, int32_t *idx_out,
+                     uint8_t *chan_mask) {
+    if (!sumsq || k < 0 || k > d_in) return -1;
+    keyidx_t *r = (keyidx_t *)malloc(sizeof(keyidx_t) * (size_t)(d_in ? d_in : 1));
+    for (int64_t i = 0; i < d_in; ++i) {
+        r[i].key = float_bits(sumsq[i] == 0.0f ? 0.0f : sumsq[i]);
+        r[i].idx = i;
+    }
+    qsort(r, (size_t)d_in, sizeof(keyidx_t), cmp_keyidx);
+    if (chan_mask) memset(chan_mask, 0, (size_t)d_in);
+    int64_t *sel = (int64_t *)malloc(sizeof(int64_t) * (size_t)(k ? k : 1));
+    for (int64_t j = 0; j < k; ++j) sel[j] = r[j].idx;
+    qsort(sel, (size_t)k, sizeof(int64_t), cmp_i64);
+    for (int64_t j = 0; j < k; ++j) {
+        if (idx_out) idx_out[j] = (int32_t)sel[j];
+        if (chan_mask) chan_mask[sel[j]] = 1;
+    }
+    free(sel);
+    free(r);
+    return 0;
+}
+
+/*
+ * Algorithm 1 (channel-wise precision allocation), generalised from base
+ * precision 3 and the set {2,3,4} to any run of consecutive widths S, and
+ * read with an integer budget so that the average is hit exactly:
+ *
+ *   d_eff = number of channels not in O_act (those are budgeted apart, Sec. 4.1);
+ *   T     = floor(b * d_eff + 1e-9) bits to spend per output row.
+ *   s < b < s+1 (both in S): the n_hi = T - s*d_eff channels with the largest
+ *       statistic get s+1 bits, the others s.  For S = {2,3,4} these are the
+ *       two outer branches of Algorithm 1 (the quantile of a at level 1-(b-3),
+ *       resp. 3-b, with a strict inequality), up to one channel of
+ *       interpolation slack.
+ *   b equal to a level s with both neighbours in S (the paper's b = 3 branch,
+ *       1st / 99th percentile): m = ceil(0.01*(d_eff-1)) lowest channels get
+ *       s-1, the m highest s+1; m is what a linearly interpolated percentile
+ *       with a strict inequality selects on tie-free data.  Without both
+ *       neighbours every channel gets s.
+ *
+ * bits[i] = ORC_PROTECTED for channels of O_act.  counts[j] = number of
+ * channels at width S[j].  Ranking order as in orc_top_channels.
+ */
+int orc_allocate_bits(const float *sumsq, int64_t d_in, const uint8_t *chan_mask,
+                      const int32_t *bit_set, int n_set, double avg_bits, uint8_t *bits,
+                      int64_t *counts) {
+    if (!sumsq || !bit_set || !bits || n_set < 1 || n_set > 4) return -1;
+    for (int j = 0; j < n_set; ++j) {
+        if (bit_set[j] < 1 || bit_set[j] > 4) return -2;
+        if (j && bit_set[j] != bit_set[j - 1] + 1) return -2;
+    }
+    if (avg_bits < bit_set[0] - 1e-9 || avg_bits > bit_set[n_set - 1] + 1e-9) return -2;
+
+    keyidx_t *r = (keyidx_t *)malloc(sizeof(keyidx_t) * (size_t)(d_in ? d_in : 1));
+    int64_t d_eff = 0;
+    for (int64_t i = 0; i < d_in; ++i) {
+        if (chan_mask && chan_mask[i]) {
+            bits[i] = ORC_PROTECTED;
+            continue;
+        }
+        r[d_eff].key = float_bits(sumsq[i] == 0.0f ? 0.0f : sumsq[i]);
+        r[d_eff].idx = i;
+        ++d_eff;
+    }
+    qsort(r, (size_t)d_eff, sizeof(keyidx_t), cmp_keyidx); /* r[0] = most salient */
+    if (counts)
+        for (int j = 0; j < n_set; ++j) counts[j] = 0;
+
+    double nearest = floor(avg_bits + 0.5);
+    int at_level = fabs(avg_bits - nearest) < 1e-9;
+    if (at_level) {
+        int s = (int)nearest, js = s - bit_set[0];
+        int64_t m = 0;
+        if (js - 1 >= 0 && js + 1 < n_set && d_eff > 0) {
+            m = (int64_t)ceil(0.01 * (double)(d_eff - 1) - 1e-12);
+            if (2 * m > d_eff) m = d_eff / 2;
+        }
+        for (int64_t p = 0; p < d_eff; ++p) {
+            int w = s;
+            if (p < m) w = s + 1;
+            else if (p >= d_eff - m) w = s - 1;
+            bits[r[p].idx] = (uint8_t)w;
+            if (counts) counts[w - bit_set[0]]++;
+        }
+    } else {
+        int s = (int)floor(avg_bits);
+        int64_t T = (int64_t)floor(avg_bits * (double)d_eff + 1e-9);
+        int64_t n_hi = T - (int64_t)s * d_eff;
+        for (int64_t p = 0; p < d_eff; ++p) {
+            int w = p < n_hi ? s + 1 : s;
+            bits[r[p].idx] = (uint8_t)w;
+            if (counts) counts[w - bit_set[0]]++;
+        }
+    }
+    free(r);
+    return 0;
+}
+
+/* ---- Sec. 3.2.1: per-channel non-uniform quantizer (K-means) ------------------------------ */
+
+static int cmp_f64(const void *a, const void *b) {
+    double x = *(const double *)a, y = *(const double *)b;
+    return x < y ? -1 : (x > y ? 1 : 0);
+}
+
+/* Sec. 3, eq. Q(x): nearest level; equal distances go to the smaller index. */
+static int nearest_level(double x, const float *c, int K) {
+    int best = 0;
+    double bd = fabs(x - (double)c[0]);
+    for (int j = 1; j < K; ++j) {
+        double d = fabs(x - (double)c[j]);
+        if (d < bd) {
+            bd = d;
+            best = j;
+        }
+    }
+    return best;
+}
+
+/*
+ * For every channel i with bits[i] in 1..4: K = 2^bits[i] levels by Lloyd's
+ * algorithm on the d_out weights W[i,:] (Sec. 3.2.1), then each weight is coded
+ * by its nearest level (Sec. 3 eq. Q(x)).
+ *
+ * Points the paper leaves open, and the reading taken:
+ *   weights      m[o] = elem_weight[i,o] (1 if the pointer is null); entries
+ *                listed in out_idx (linear index i*d_out+o, any order) have
+ *                m = 0: they are "removed" before clustering (Sec. 3.2.2) but
+ *                still receive a code.
+ *   start        K order statistics of the values with m > 0, sorted
+ *                ascending: level j starts at sorted[floor((2j+1)*M/(2K))],
+ *                M = their count; all zero when M = 0.
+ *   rounds       exactly `iters` times (assign, update); no early stop.
+ *   assign       argmin_j |x - q_j| evaluated in fp64 (exact for fp16 / fp32
+ *                operands of comparable scale), ties to the smaller j.
+ *   update       q_j = (sum m*x) / (sum m) over its members, accumulated in
+ *                fp64 in index order, rounded once to fp32; a level with no
+ *                mass keeps its value.
+ *   -0.0         read as +0.0.
+ *
+ * centroids[i*16 + j] for j < K, +infinity for j >= K and for every slot of a
+ * channel with bits[i] outside 1..4 (its codes are 0).  codes[i*d_out + o].
+ * sse_trace (nullable) [d_in*(iters+1)]: the weighted squared error
+ * sum m (x - q_code)^2 measured at every assignment, the final one included.
+ */
+int orc_kmeans(const void *W, int dtype, int64_t d_in, int64_t d_out, int64_t ldw,
+               const uint8_t *bits, const int64_t *out_idx, int64_t n_out,
+               const float *elem_weight, int iters, float *centroids, uint8_t *codes,
+               double *sse_trace) {
+    if (!W || !bits || !centroids || !codes || iters < 0 || ldw < d_out) return -1;
+    /* excluded entries as a dense 0/1 map */
+    uint8_t *excl = (uint8_t *)calloc((size_t)(d_in * d_out > 0 ? d_in * d_out : 1), 1);
+    for (int64_t j = 0; j < n_out; ++j) {
+        if (out_idx[j] < 0 || out_idx[j] >= d_in * d_out) {
+            free(excl);
+            return -1;
+        }
+        excl[out_idx[j]] = 1;
+    }
+#pragma omp parallel for schedule(dynamic, 4)
+    for (int64_t i = 0; i < d_in; ++i) {
+        float *c = centroids + i * ORC_KMAX;
+        uint8_t *code = codes + i * d_out;
+        for (int j = 0; j < ORC_KMAX; ++j) c[j] = INFINITY;
+        if (bits[i] < 1 || bits[i] > 4) {
+            memset(code, 0, (size_t)d_out);
+            if (sse_trace)
+                for (int r = 0; r <= iters; ++r) sse_trace[i * (iters + 1) + r] = 0.0;
+            continue;
+        }
+        int K = 1 << bits[i];
+        double *x = (double *)malloc(sizeof(double) * (size_t)(d_out ? d_out : 1));
+        double *m = (double *)malloc(sizeof(double) * (size_t)(d_out ? d_out : 1));
+        double *srt = (double *)malloc(sizeof(double) * (size_t)(d_out ? d_out : 1));
+        int64_t M = 0;
+        for (int64_t o = 0; o < d_out; ++o) {
+            double v = load_elem(W, dtype, i * ldw + o);
+            if (v == 0.0) v = 0.0; /* -0 -> +0 */
+            x[o] = v;
+            m[o] = excl[i * d_out + o] ? 0.0
+                                       : (elem_weight ? (double)elem_weight[i * d_out + o] : 1.0);
+            if (m[o] > 0.0) srt[M++] = v;
+        }
+        qsort(srt, (size_t)M, sizeof(double), cmp_f64);
+        for (int j = 0; j < K; ++j)
+            c[j] = M ? (float)srt[((int64_t)(2 * j + 1) * M) / (2 * K)] : 0.0f;
+
+        for (int r = 0; r <= iters; ++r) {
+            double sum[ORC_KMAX], mass[ORC_KMAX], sse = 0.0;
+            for (int j = 0; j < K; ++j) sum[j] = mass[j] = 0.0;
+            for (int64_t o = 0; o < d_out; ++o) {
+                int j = nearest_level(x[o], c, K);
+                code[o] = (uint8_t)j;
+                double e = x[o] - (double)c[j];
+                sse += m[o] * e * e;
+                sum[j] += m[o] * x[o];
+                mass[j] += m[o];
+            }
+            if (sse_trace) sse_trace[i * (iters + 1) + r] = sse;
+            if (r == iters) break; /* last pass only assigns */
+            for (int j = 0; j < K; ++j)
+                if (mass[j] > 0.0) c[j] = (float)(sum[j] / mass[j]);
+        }
+        free(x);
+        free(m);
+        free(srt);
+    }
+    free(excl);
+    return 0;
+}
+
+/* ---- Sec. 3.2.2: quantization-aware outliers O_q ------------------------------------------ */
+
+#define ORC_SCORE_RESIDUAL 0  /* |W' - W'_q|, the paper's criterion            */
+#define ORC_SCORE_MAGNITUDE 1 /* |W'|, the "conventional approach" it contrasts */
+
+/*
+ * The k entries of W' (channels with bits in 1..4, i.e. outside O_act) with the
+ * largest score, over the whole layer.  Score = |w - q_code| rounded to fp32
+ * (its bit pattern is the ranking key); larger first, equal scores by smaller
+ * linear index i*d_out+o.  idx_out[k] ascending, val_out[k] = the weight in FP16.
+ */
+int orc_weight_outliers(const void *W, int dtype, int64_t d_in, int64_t d_out, int64_t ldw,
+                        const float *centroids, const uint8_t *codes, const uint8_t *bits,
+                        int score, int64_t k, int64_t *idx_out, uint16_t *val_out) {
+    if (!W || !bits || k < 0) return -1;
+    if (score == ORC_SCORE_RESIDUAL && (!centroids || !codes)) return -1;
+    int64_t cap = d_in * d_out, cnt = 0;
+    keyidx_t *r = (keyidx_t *)malloc(sizeof(keyidx_t) * (size_t)(cap ? cap : 1));
+    for (int64_t i = 0; i < d_in; ++i) {
+        if (bits[i] < 1 || bits[i] > 4) continue;
+        for (int64_t o = 0; o < d_out; ++o) {
+            double w = load_elem(W, dtype, i * ldw + o);
+            double s = score == ORC_SCORE_RESIDUAL
+                           ? fabs(w - (double)centroids[i * ORC_KMAX + codes[i * d_out + o]])
+                           : fabs(w);
+            r[cnt].key = float_bits((float)s);
+            r[cnt].idx = i * d_out + o;
+            ++cnt;
+        }
+    }
+    if (k > cnt) {
+        free(r);
+        return -3;
+    }
+    qsort(r, (size_t)cnt, sizeof(keyidx_t), cmp_keyidx);
+    int64_t *sel = (int64_t *)malloc(sizeof(int64_t) * (size_t)(k ? k : 1));
+    for (int64_t j = 0; j < k; ++j) sel[j] = r[j].idx;
+    qsort(sel, (size_t)k, sizeof(int64_t), cmp_i64);
+    for (int64_t j = 0; j < k; ++j) {
+        if (idx_out) idx_out[j] = sel[j];
+        if (val_out) {
+            int64_t i = sel[j] / d_out, o = sel[j] % d_out;
+            val_out[j] = double_to_half(load_elem(W, dtype, i * ldw + o));
+        }
+    }
+    free(sel);
+    free(r);
+    return 0;
+}
+
+/* ---- Sec. 5.1 / Fig. 4: stored format ------------------------------------------------------ */
+
+/*
+ * One code matrix per width b (Fig. 4 splits the weight by precision): the
+ * channels with bits == b, in ascending channel index (chan_idx), one row
+ * each.  A row is a little-endian bit stream: the code of output o sits in
+ * stream bits [o*b, (o+1)*b); stream bit s is bit (s mod 32) of word (s / 32);
+ * rows are padded with zero bits to words_per_row = ceil(d_out*b/32) words.
+ * lut[row*2^b + j] = level j in FP16 (round to nearest even): the "cluster
+ * centers (look-up-table)" of Sec. 5.1.  Called once per width; returns the
+ * number of rows, or < 0.
+ */
+int64_t orc_pack(const uint8_t *codes, int64_t d_in, int64_t d_out, const uint8_t *bits,
+                 const float *centroids, int b, uint32_t *packed, int32_t *chan_idx,
+                 uint16_t *lut) {
+    if (!codes || !bits || b < 1 || b > 4) return -1;
+    int64_t wpr = (d_out * b + 31) / 32, row = 0;
+    for (int64_t i = 0; i < d_in; ++i) {
+        if (bits[i] != b) continue;
+        if (chan_idx) chan_idx[row] = (int32_t)i;
+        if (packed) {
+            uint32_t *dst = packed + row * wpr;
+            memset(dst, 0, (size_t)wpr * 4);
+            for (int64_t o = 0; o < d_out; ++o) {
+                uint32_t cval = codes[i * d_out + o];
+                for (int t = 0; t < b; ++t) {
+                    int64_t s = o * b + t;
+                    if ((cval >> t) & 1u) dst[s / 32] |= 1u << (s % 32);
+                }
+            }
+        }
+        if (lut && centroids)
+            for (int j = 0; j < (1 << b); ++j)
+                lut[row * (1 << b) + j] = double_to_half((double)centroids[i * ORC_KMAX + j]);
+        ++row;
+    }
+    return row;
+}
+
+/* ---- Sec. 3.2.2 reconstruction and App. B.3 output error ----------------------------------- */
+
+/*
+ * W_hat[i,o] = q_{code}          for a quantized entry,
+ *            = fp16(W[i,o])      for an entry of O = O_act + O_q
+ *                                (channels with bits outside 1..4, and the entries of
+ *                                out_idx).  The paper writes W_q + O; a table
+ *                                look-up cannot store an exact zero, so an outlier
+ *                                overrides the level instead of adding to it.
+ * err_ch[i]  = sum_o (W[i,o] - W_hat[i,o])^2
+ * totals[0]  = sum_i sumsq[i] * err_ch[i]   the squared Frobenius norm of
+ *              Delta Y = X (W - W_hat) when cross-channel products of X are
+ *              dropped (exact for orthogonal columns);  sumsq null => weight 1.
+ * totals[1]  = sum_i err_ch[i]
+ */
+int orc_dequant_error(const void *W, int dtype, int64_t d_in, int64_t d_out, int64_t ldw,
+                      const float *centroids, const uint8_t *codes, const uint8_t *bits,
+                      const int64_t *out_idx, int64_t n_out, const float *sumsq,
+                      double *err_ch, double *totals) {
+    if (!W || !centroids || !codes || !bits) return -1;
+    uint8_t *excl = (uint8_t *)calloc((size_t)(d_in * d_out > 0 ? d_in * d_out : 1), 1);
+    for (int64_t j = 0; j < n_out; ++j) excl[out_idx[j]] = 1;
+    double tw = 0.0, tu = 0.0;
+    for (int64_t i = 0; i < d_in; ++i) {
+        double e = 0.0;
+        int prot = bits[i] < 1 || bits[i] > 4;
+        for (int64_t o = 0; o < d_out; ++o) {
+            double w = load_elem(W, dtype, i * ldw + o), what;
+            if (prot || excl[i * d_out + o])
+                what = half_to_double(double_to_half(w));
+            else
+                what = (double)centroids[i * ORC_KMAX + codes[i * d_out + o]];
+            e += (w - what) * (w - what);
+        }
+        if (err_ch) err_ch[i] = e;
+        tw += (sumsq ? (double)sumsq[i] : 1.0) * e;
+        tu += e;
+    }
+    if (totals) {
+        totals[0] = tw;
+        totals[1] = tu;
+    }
+    free(excl);
+    return 0;
+}
+
+/* Counts are integers derived from parts-per-million fractions, rounding half up. */
+int64_t orc_count_ppm(int64_t ppm, int64_t n) { return (ppm * n + 500000) / 1000000; }

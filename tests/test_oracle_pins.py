@@ -1,0 +1,541 @@
+"""Pins of the CPU oracle against what the paper and the mathematics fix.
+
+Nothing here touches the HIP path.  Each test names the passage of the paper
+(arXiv 2410.13056) or the textbook fact it checks the oracle against, and is
+chosen so that a plausible slip in the oracle (dropped term, wrong sign or
+index, transposed operand, wrong tie rule) fails it.
+"""
+import itertools
+import os
+
+import numpy as np
+import pytest
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _rows(name):
+    out = []
+    with open(os.path.join(GOLDEN, name)) as f:
+        for line in f:
+            line = line.strip()
+            if line and not line.startswith("#"):
+                out.append(line.split())
+    return out
+
+
+# ----------------------------------------------------------------------------- fp16 codec
+
+def test_half_codec_matches_numpy_on_every_pattern(orc):
+    bits = np.arange(65536, dtype=np.uint16)
+    ref = bits.view(np.float16).astype(np.float64)
+    got = np.array([orc.f16_bits_to_f64(int(b)) for b in bits])
+    fin = np.isfinite(ref)
+    assert np.array_equal(got[fin], ref[fin])
+    assert np.array_equal(np.isnan(got), np.isnan(ref))
+    assert np.array_equal(np.isinf(got), np.isinf(ref))
+
+
+def test_float_to_half_rounds_to_nearest_even_like_numpy(orc):
+    rng = np.random.default_rng(1)
+    xs = np.concatenate([
+        rng.normal(0, 1, 4000), rng.normal(0, 1e-3, 2000), rng.normal(0, 1e-6, 2000),
+        rng.normal(0, 3e4, 1000), np.array([0.0, -0.0, 65504.0, 65519.9, 65520.0, 1e-8, 2.0 ** -25,
+                                             2.0 ** -25 * 1.0001, 2.0 ** -24 * 1.5, 2.0 ** -24 * 2.5])
+    ]).astype(np.float32)
+    # exact half-way cases between neighbouring halves
+    h = rng.integers(0, 0x7BFF, 3000).astype(np.uint16)
+    mid = ((h.view(np.float16).astype(np.float64) + (h + 1).astype(np.uint16).view(np.float16).astype(np.float64)) / 2)
+    xs = np.concatenate([xs, mid.astype(np.float32), -mid.astype(np.float32)])
+    with np.errstate(over="ignore"):
+        ref = xs.astype(np.float16).view(np.uint16)
+    got = np.array([orc.f32_to_f16_bits(float(x)) for x in xs], dtype=np.uint16)
+    assert np.array_equal(got, ref)
+
+
+# ----------------------------------------------------------------------------- Sec. 3.2.1 statistics
+
+def test_act_stats_is_squared_column_norm(orc):
+    rng = np.random.default_rng(2)
+    for dt in (np.float16, np.float32):
+        X = rng.normal(0, 1, (301, 77)).astype(dt)
+        acc, sumsq = orc.act_stats(X)
+        ref = np.linalg.norm(X.astype(np.float64), axis=0) ** 2
+        assert np.allclose(acc, ref, rtol=1e-12, atol=0)
+        assert np.array_equal(sumsq, acc.astype(np.float32))
+
+
+def test_act_stats_constant_column_chunks_and_permutation(orc):
+    rng = np.random.default_rng(3)
+    n, d = 500, 33
+    X = rng.normal(0, 2, (n, d)).astype(np.float32)
+    X[:, 5] = 0.75                                   # closed form n * v^2
+    acc, _ = orc.act_stats(X)
+    assert acc[5] == n * 0.75 ** 2
+    a1, _ = orc.act_stats(X[:123])
+    a2, s2 = orc.act_stats(X[123:], acc=a1)          # streaming tokens
+    assert np.allclose(a2, acc, rtol=1e-14)
+    accp, _ = orc.act_stats(X[rng.permutation(n)])   # token order is irrelevant
+    assert np.allclose(accp, acc, rtol=1e-13)
+    accs, _ = orc.act_stats((X * 4).astype(np.float32))
+    assert np.allclose(accs, 16 * acc, rtol=1e-14)   # power-of-two scaling is exact
+    # a transposed-operand slip would reduce over the wrong axis
+    assert acc.shape == (d,)
+
+
+# ----------------------------------------------------------------------------- Sec. 3.2.2 O_act
+
+def _rank_order(keys):
+    """indices sorted by (key descending, index ascending) - the textbook definition."""
+    return sorted(range(len(keys)), key=lambda i: (-float(keys[i]), i))
+
+
+def test_top_channels_equals_full_sort_with_ties(orc):
+    rng = np.random.default_rng(4)
+    d = 400
+    s = rng.integers(0, 40, d).astype(np.float32)      # many ties
+    for k in (0, 1, 7, 123, d):
+        idx, mask = orc.top_channels(s, k)
+        ref = sorted(_rank_order(s)[:k])
+        assert list(idx) == ref
+        assert mask.sum() == k and set(np.flatnonzero(mask)) == set(ref)
+
+
+def test_outlier_counts_follow_printed_fractions(orc):
+    ppm = {r[0]: int(r[1]) for r in _rows("sec3_2_2_outlier_fractions.txt")}
+    assert ppm["rho_act"] + ppm["rho_q"] == ppm["rho_total"]
+    # counts the scope table quotes for the LLaMA shapes
+    for d_in, k in [(256, 1), (4096, 18), (11008, 50), (5120, 23), (13824, 62), (8192, 37), (28672, 129)]:
+        assert orc.count_ppm(ppm["rho_act"], d_in) == k
+    assert orc.count_ppm(5000, 512 * 256) == 655
+    assert orc.count_ppm(ppm["rho_q"], 4096 * 4096) == 8389
+    assert orc.count_ppm(5000, 4096 * 4096) == 83886
+
+
+# ----------------------------------------------------------------------------- Algorithm 1
+
+def _literal_alg1(a, b):
+    """Algorithm 1 as printed, with numpy's linearly interpolated quantile."""
+    c = np.full(a.shape, 3)
+    if b > 3:
+        c[a > np.quantile(a, 1 - (b - 3))] = 4
+    elif b < 3:
+        c[a < np.quantile(a, 3 - b)] = 2
+    else:
+        c[a < np.quantile(a, 0.01)] = 2
+        c[a > np.quantile(a, 0.99)] = 4
+    return c
+
+
+def test_allocation_against_printed_algorithm_rows(orc):
+    rng = np.random.default_rng(5)
+    for b, d, n2, n3, n4 in _rows("alg1_branches.txt"):
+        b, d, want = float(b), int(d), (int(n2), int(n3), int(n4))
+        a = rng.permutation(d).astype(np.float32) + 1.0          # tie free
+        lit = _literal_alg1(a.astype(np.float64), b)
+        assert tuple(int((lit == w).sum()) for w in (2, 3, 4)) == want   # the fixture is Algorithm 1
+        bits, counts = orc.allocate_bits(a, None, (2, 3, 4), b)
+        got = tuple(int((bits == w).sum()) for w in (2, 3, 4))
+        assert tuple(counts) == got
+        assert all(abs(g - w) <= 1 for g, w in zip(got, want)), (got, want)
+        # same channels, not just same counts: at most one channel differs per threshold
+        assert int((bits != lit).sum()) <= 2
+
+
+@pytest.mark.parametrize("bit_set", [(2, 3), (2, 3, 4), (3, 4), (1, 2, 3, 4)])
+def test_allocation_budget_is_exact_and_monotone(orc, bit_set):
+    rng = np.random.default_rng(6)
+    for d in (7, 256, 1000, 4096):
+        a = rng.lognormal(0, 1, d).astype(np.float32)
+        a[rng.integers(0, d, d // 10)] = a[0]                    # ties
+        for b in np.linspace(bit_set[0], bit_set[-1], 23):
+            bits, counts = orc.allocate_bits(a, None, bit_set, float(b))
+            assert counts.sum() == d and set(np.unique(bits)) <= set(bit_set)
+            total = int(bits.astype(np.int64).sum())
+            if abs(b - round(b)) < 1e-9:
+                assert total == round(b) * d                     # symmetric branch: average exactly b
+                assert len(np.unique(bits)) in (1, 3)
+            else:
+                T = int(np.floor(b * d + 1e-9))
+                assert total == T and T / d <= b < T / d + 1.0 / d
+                assert len(np.unique(bits)) <= 2
+            order = _rank_order(a)                               # more salient => never fewer bits
+            assert all(bits[order[j]] >= bits[order[j + 1]] for j in range(d - 1))
+
+
+def test_allocation_closed_forms_and_protection(orc):
+    a = np.arange(1, 257, dtype=np.float32)
+    bits, counts = orc.allocate_bits(a, None, (2, 3), 2.5)
+    assert list(counts) == [128, 128] and (bits[128:] == 3).all() and (bits[:128] == 2).all()
+    a = np.arange(1, 4097, dtype=np.float32)
+    _, mask = orc.top_channels(a, 18)
+    bits, counts = orc.allocate_bits(a, mask, (2, 3, 4), 3.0)    # d_eff = 4078
+    assert list(counts) == [41, 3996, 41]
+    assert (bits[mask == 1] == orc.PROTECTED).all() and (bits[-18:] == orc.PROTECTED).all()
+    assert (bits[:41] == 2).all() and (bits[4096 - 18 - 41:4096 - 18] == 4).all()
+    for b, w in ((2.0, 2), (4.0, 4)):                            # ends of the range: uniform
+        bits, _ = orc.allocate_bits(a, None, (2, 3, 4), b)
+        assert (bits == w).all()
+    bits, _ = orc.allocate_bits(a, None, (2, 3), 3.0)            # no neighbour above: uniform
+    assert (bits == 3).all()
+    with pytest.raises(ValueError):
+        orc.allocate_bits(a, None, (2, 3), 3.5)
+    with pytest.raises(ValueError):
+        orc.allocate_bits(a, None, (2, 4), 3.0)
+
+
+def test_scaling_activations_leaves_integer_outputs_unchanged(orc):
+    rng = np.random.default_rng(7)
+    X = rng.normal(0, 1, (64, 300)).astype(np.float32) * rng.lognormal(0, 1, 300).astype(np.float32)
+    _, s1 = orc.act_stats(X)
+    _, s2 = orc.act_stats(X * np.float32(8.0))
+    for b in (2.3, 3.0, 3.7):
+        i1, m1 = orc.top_channels(s1, 3)
+        i2, m2 = orc.top_channels(s2, 3)
+        assert np.array_equal(i1, i2)
+        assert np.array_equal(orc.allocate_bits(s1, m1, (2, 3, 4), b)[0],
+                              orc.allocate_bits(s2, m2, (2, 3, 4), b)[0])
+
+
+# ----------------------------------------------------------------------------- K-means (Sec. 3.2.1)
+
+def _optimal_sse(x, K):
+    """Exact optimum of 1-D K-clustering by dynamic programming over the sorted values."""
+    x = np.sort(np.asarray(x, np.float64))
+    m = len(x)
+    p1 = np.concatenate([[0.0], np.cumsum(x)])
+    p2 = np.concatenate([[0.0], np.cumsum(x * x)])
+
+    def cost(i, j):  # cluster x[i:j]
+        s, q, n = p1[j] - p1[i], p2[j] - p2[i], j - i
+        return max(q - s * s / n, 0.0)
+
+    INF = float("inf")
+    D = np.full((K + 1, m + 1), INF)
+    D[0, 0] = 0.0
+    for k in range(1, K + 1):
+        for j in range(1, m + 1):
+            D[k, j] = min([D[k - 1, i] + cost(i, j) for i in range(k - 1, j) if D[k - 1, i] < INF],
+                          default=INF)
+    return min(D[k, m] for k in range(1, K + 1))
+
+
+def _sorted_lloyd(x, w, K, iters):
+    """Independent second implementation of the oracle's K-means: works on the
+    sorted values with prefix sums; a cell is the run of values closer to its
+    level than to any other (ties to the smaller level index)."""
+    x = np.asarray(x, np.float64).copy()
+    x[x == 0] = 0.0
+    w = np.asarray(w, np.float64)
+    inc = np.sort(x[w > 0])
+    M = len(inc)
+    c = np.array([inc[((2 * j + 1) * M) // (2 * K)] if M else 0.0 for j in range(K)], np.float32)
+    order = np.argsort(x, kind="stable")
+    xs, ws = x[order], w[order]
+    pw = np.concatenate([[0.0], np.cumsum(ws)])
+
+    def assign(c):
+        # distinct level values, each owned by its smallest index
+        cd = c.astype(np.float64)
+        owners = {}
+        for j in range(K):
+            owners.setdefault(cd[j], j)
+        vals = sorted(owners)
+        edges = [0]
+        for lo, hi in zip(vals[:-1], vals[1:]):
+            mid = (lo + hi) / 2.0
+            side = "right" if owners[lo] < owners[hi] else "left"   # tie -> smaller index
+            edges.append(int(np.searchsorted(xs, mid, side=side)))
+        edges.append(len(xs))
+        code_sorted = np.empty(len(xs), np.int64)
+        for t, v in enumerate(vals):
+            code_sorted[edges[t]:edges[t + 1]] = owners[v]
+        return code_sorted
+
+    for _ in range(iters):
+        cs = assign(c)
+        for j in range(K):
+            sel = cs == j
+            mass = ws[sel].sum()
+            if mass > 0:
+                # same summation order as index order is not needed: these test inputs are fp16-exact
+                c[j] = np.float32((ws[sel] * xs[sel]).sum() / mass)
+    cs = assign(c)
+    codes = np.empty(len(x), np.int64)
+    codes[order] = cs
+    return c, codes
+
+
+def test_kmeans_never_beats_and_sometimes_reaches_the_optimum(orc):
+    rng = np.random.default_rng(8)
+    d_in, d_out = 24, 48
+    W = rng.normal(0, 1, (d_in, d_out)).astype(np.float16)
+    bits = rng.integers(1, 4, d_in).astype(np.uint8)            # K in {2,4,8}
+    cent, codes, sse = orc.kmeans(W, bits, iters=30, trace=True)
+    for i in range(d_in):
+        K = 1 << int(bits[i])
+        opt = _optimal_sse(W[i].astype(np.float64), K)
+        assert sse[i, -1] >= opt - 1e-9
+    # well separated planted clusters: Lloyd from quantile starts lands on the optimum
+    K = 4
+    centers = np.array([-3.0, -1.0, 1.0, 3.0])
+    # equal-sized groups so that the order-statistic start hits every group
+    Wp = np.stack([np.concatenate([c + rng.normal(0, 0.01, 16) for c in centers]) for _ in range(6)]).astype(np.float16)
+    cent, codes, sse = orc.kmeans(Wp, np.full(6, 2, np.uint8), iters=5, trace=True)
+    for i in range(6):
+        assert abs(sse[i, -1] - _optimal_sse(Wp[i].astype(np.float64), K)) < 1e-9
+
+
+def test_kmeans_lloyd_invariants(orc):
+    rng = np.random.default_rng(9)
+    d_in, d_out = 40, 333
+    W = (rng.standard_t(3, (d_in, d_out)) * 0.05).astype(np.float32)
+    bits = rng.integers(1, 5, d_in).astype(np.uint8)
+    cent, codes, sse = orc.kmeans(W, bits, iters=60, trace=True)
+    # the error never goes up from one assignment to the next
+    assert (np.diff(sse, axis=1) <= 1e-12 * (1 + sse[:, :-1])).all()
+    for i in range(d_in):
+        K = 1 << int(bits[i])
+        c = cent[i, :K].astype(np.float64)
+        assert np.isinf(cent[i, K:]).all() and (cent[i, K:] > 0).all()
+        assert (np.diff(c) >= 0).all()                            # levels stay ordered
+        x = W[i].astype(np.float64)
+        d = np.abs(x[:, None] - c[None, :])
+        assert np.array_equal(codes[i], d.argmin(axis=1))          # nearest level, first on ties
+    # after convergence every level is the mean of its members (fixed point)
+    cent2, codes2 = orc.kmeans(W, bits, iters=61)
+    conv = np.flatnonzero(sse[:, -1] == sse[:, -2])
+    assert len(conv) > d_in // 2
+    for i in conv:
+        K = 1 << int(bits[i])
+        for j in range(K):
+            mem = W[i][codes2[i] == j].astype(np.float64)
+            if len(mem):
+                assert abs(mem.mean() - cent2[i, j]) <= 2e-7 * max(1e-3, abs(mem.mean()))
+
+
+def test_kmeans_matches_independent_sorted_implementation(orc):
+    rng = np.random.default_rng(10)
+    d_in, d_out = 30, 257
+    W = (rng.normal(0, 0.02, (d_in, d_out))).astype(np.float16)
+    W[rng.random((d_in, d_out)) < 0.01] *= 20
+    W[3, :] = W[3, 0]                                 # one distinct value
+    W[4, 100:] = 0.0                                  # heavy duplicates -> duplicate starts
+    W[5, ::2] = -W[5, ::2]
+    W[6, :40] = np.float16(-0.0)
+    bits = rng.integers(1, 5, d_in).astype(np.uint8)
+    excl = np.sort(rng.choice(d_in * d_out, 200, replace=False)).astype(np.int64)
+    for out_idx in (None, excl):
+        cent, codes = orc.kmeans(W, bits, out_idx=out_idx, iters=12)
+        for i in range(d_in):
+            K = 1 << int(bits[i])
+            w = np.ones(d_out)
+            if out_idx is not None:
+                loc = out_idx[(out_idx >= i * d_out) & (out_idx < (i + 1) * d_out)] - i * d_out
+                w[loc] = 0.0
+            c_ref, code_ref = _sorted_lloyd(W[i].astype(np.float64), w, K, 12)
+            assert np.array_equal(cent[i, :K], c_ref), i
+            assert np.array_equal(codes[i], code_ref), i
+
+
+def test_kmeans_importance_weights(orc):
+    rng = np.random.default_rng(11)
+    d_in, d_out = 12, 200
+    W = rng.normal(0, 1, (d_in, d_out)).astype(np.float16)
+    bits = np.full(d_in, 3, np.uint8)
+    ew = rng.integers(0, 4, (d_in, d_out)).astype(np.float32)         # integer weights = repeated points
+    cent, codes = orc.kmeans(W, bits, elem_weight=ew, iters=8)
+    for i in range(d_in):
+        c_ref, code_ref = _sorted_lloyd(W[i].astype(np.float64), ew[i].astype(np.float64), 8, 8)
+        assert np.allclose(cent[i, :8], c_ref, rtol=1e-6, atol=0)
+        assert np.array_equal(codes[i], code_ref)
+    # weight 0 == listing the entry as excluded
+    zero = np.flatnonzero(ew.reshape(-1) == 0).astype(np.int64)
+    ones = (ew > 0).astype(np.float32)
+    c1, k1 = orc.kmeans(W, bits, elem_weight=ones, iters=8)
+    c2, k2 = orc.kmeans(W, bits, out_idx=zero, iters=8)
+    assert np.array_equal(c1, c2) and np.array_equal(k1, k2)
+
+
+def test_kmeans_few_distinct_values_and_affine_equivariance(orc):
+    rng = np.random.default_rng(12)
+    vals = np.array([-0.5, -0.125, 0.0, 0.25, 0.375, 1.0, 2.0], np.float32)
+    # 16 copies of each value: the order-statistic start then lands on all seven
+    W = np.stack([rng.permutation(np.repeat(vals, 16)) for _ in range(10)])
+    cent, codes, sse = orc.kmeans(W, np.full(10, 3, np.uint8), iters=20, trace=True)
+    assert (sse[:, -1] == 0).all()                     # #distinct <= K: exact representation
+    for i in range(10):
+        assert np.array_equal(cent[i][codes[i]], W[i])
+    # x -> 4x + 0.5 (exact in fp32 for these inputs): levels follow, codes unchanged
+    Wn = (rng.integers(-2000, 2000, (6, 90)) / 1024.0).astype(np.float32)
+    c1, k1 = orc.kmeans(Wn, np.full(6, 2, np.uint8), iters=1)
+    c2, k2 = orc.kmeans((4 * Wn + 0.5).astype(np.float32), np.full(6, 2, np.uint8), iters=1)
+    assert np.array_equal(k1, k2)
+    assert np.allclose(c2[:, :4], 4 * c1[:, :4].astype(np.float64) + 0.5, rtol=3e-7)
+
+
+def test_kmeans_protected_channels_and_empty_channel(orc):
+    W = np.linspace(-1, 1, 5 * 64).reshape(5, 64).astype(np.float16)
+    bits = np.array([2, 16, 3, 0, 4], np.uint8)
+    cent, codes = orc.kmeans(W, bits, iters=3)
+    assert np.isinf(cent[1]).all() and np.isinf(cent[3]).all()
+    assert (codes[1] == 0).all() and (codes[3] == 0).all()
+    all_out = np.arange(64, dtype=np.int64)            # channel 0 entirely excluded
+    cent, codes = orc.kmeans(W, bits, out_idx=all_out, iters=3)
+    assert (cent[0, :4] == 0).all() and (codes[0] == 0).all()
+
+
+# ----------------------------------------------------------------------------- O_q (Sec. 3.2.2)
+
+def test_weight_outliers_equal_full_sort(orc):
+    rng = np.random.default_rng(13)
+    d_in, d_out = 20, 96
+    W = (rng.integers(-30, 30, (d_in, d_out)) / 64.0).astype(np.float16)   # coarse grid: many tied residuals
+    bits = rng.integers(2, 4, d_in).astype(np.uint8)
+    bits[[2, 11]] = orc.PROTECTED
+    cent, codes = orc.kmeans(W, bits, iters=5)
+    w64 = W.astype(np.float64)
+    resid = np.abs(w64 - np.take_along_axis(cent.astype(np.float64), codes.astype(np.int64), axis=1)).astype(np.float32)
+    keep = np.repeat((bits <= 4)[:, None], d_out, axis=1).reshape(-1)
+    for score, key in ((orc.SCORE_RESIDUAL, resid), (orc.SCORE_MAGNITUDE, np.abs(W).astype(np.float32))):
+        flat = key.reshape(-1)
+        cand = [i for i in range(d_in * d_out) if keep[i]]
+        order = sorted(cand, key=lambda i: (-float(flat[i]), i))
+        for k in (0, 1, 10, 97, len(cand)):
+            idx, val = orc.weight_outliers(W, cent, codes, bits, k, score)
+            assert list(idx) == sorted(order[:k])
+            assert np.array_equal(val, W.reshape(-1)[idx].view(np.uint16))
+            assert not set(idx // d_out) & {2, 11}            # nothing from O_act channels
+    with pytest.raises(ValueError):
+        orc.weight_outliers(W, cent, codes, bits, len(cand) + 1)
+
+
+def test_residual_score_finds_planted_distorters_not_just_big_weights(orc):
+    """Sec. 3.2.2: the criterion is the quantization residual, not the magnitude.  A lone
+    far value in a tight channel has a large residual; a channel whose values are
+    all large but exactly representable has none."""
+    rng = np.random.default_rng(14)
+    d_in, d_out = 8, 256
+    W = rng.normal(0, 0.01, (d_in, d_out)).astype(np.float32)
+    W[7] = np.float32(5.0) * np.sign(rng.normal(size=d_out)).astype(np.float32)     # big, two exact levels
+    planted = [(0, 17), (1, 200), (3, 3)]
+    for i, o in planted:
+        W[i, o] = 0.4
+    bits = np.full(d_in, 1, np.uint8)                   # two levels: a lone point cannot own one
+    cent, codes = orc.kmeans(W, bits, iters=3)
+    idx, _ = orc.weight_outliers(W, cent, codes, bits, 3, orc.SCORE_RESIDUAL)
+    assert sorted(idx) == sorted(i * d_out + o for i, o in planted)
+    idxm, _ = orc.weight_outliers(W, cent, codes, bits, 3, orc.SCORE_MAGNITUDE)
+    assert all(i // d_out == 7 for i in idxm)
+
+
+# ----------------------------------------------------------------------------- storage (Sec. 5.1, Fig. 4)
+
+def _unpack(row_words, b, d_out):
+    """Independent reader of the packed layout: big Python integer as the bit stream."""
+    stream = 0
+    for w, word in enumerate(row_words):
+        stream |= int(word) << (32 * w)
+    return [(stream >> (o * b)) & ((1 << b) - 1) for o in range(d_out)], stream >> (d_out * b)
+
+
+@pytest.mark.parametrize("d_out", [1, 31, 32, 33, 100, 512])
+def test_pack_roundtrip_layout_and_padding(orc, d_out):
+    rng = np.random.default_rng(15)
+    d_in = 37
+    bits = rng.integers(1, 5, d_in).astype(np.uint8)
+    bits[[4, 9]] = orc.PROTECTED
+    codes = np.stack([rng.integers(0, 1 << min(int(b), 4), d_out) for b in bits]).astype(np.uint8)
+    cent = rng.normal(0, 1, (d_in, 16)).astype(np.float32)
+    seen = 0
+    for b in (1, 2, 3, 4):
+        packed, chan, lut = orc.pack(codes, bits, cent, b)
+        want = np.flatnonzero(bits == b)
+        assert np.array_equal(chan, want)                          # ascending channel index
+        assert packed.shape == (len(want), (d_out * b + 31) // 32)
+        for r, i in enumerate(want):
+            got, pad = _unpack(packed[r], b, d_out)
+            assert got == list(codes[i]) and pad == 0
+            assert np.array_equal(lut[r], cent[i, :1 << b].astype(np.float16).view(np.uint16))
+        seen += len(want)
+    assert seen == d_in - 2                                         # protected channels store no row
+
+
+def test_storage_overhead_reproduces_printed_example(orc):
+    for d, b, lut_bits, kind, printed in _rows("sec5_1_storage_overhead.txt"):
+        d, b, lut_bits, printed = int(d), int(b), int(lut_bits), float(printed)
+        codes = np.zeros((1, d), np.uint8)
+        packed, chan, lut = orc.pack(codes, np.array([b], np.uint8), np.zeros((1, 16), np.float32), b)
+        assert packed.size * 32 == d * b                            # payload: exactly b bits per weight
+        meta_bits = 4 + lut.shape[1] * lut_bits                     # one 4-bit width + 2^b table entries
+        per_weight = meta_bits / d
+        if kind == "approx":
+            assert lut.dtype == np.uint16 and lut_bits == 16
+            assert abs(per_weight - printed) < 0.005 and round(per_weight, 2) == printed
+        else:
+            assert per_weight < printed
+
+
+# ----------------------------------------------------------------------------- reconstruction / error
+
+def test_error_is_zero_with_all_outliers_restored(orc):
+    rng = np.random.default_rng(16)
+    W = rng.normal(0, 1, (9, 70)).astype(np.float16)
+    bits = np.full(9, 2, np.uint8)
+    cent, codes = orc.kmeans(W, bits, iters=2)
+    err, tot = orc.dequant_error(W, cent, codes, bits, np.arange(9 * 70, dtype=np.int64), None)
+    assert (err == 0).all() and (tot == 0).all()
+    err, tot = orc.dequant_error(W, cent, codes, np.full(9, orc.PROTECTED, np.uint8), None, None)
+    assert (err == 0).all()
+    # fp32 weights restored through FP16 keep exactly the FP16 rounding error
+    W32 = rng.normal(0, 1, (4, 50)).astype(np.float32)
+    b4 = np.full(4, 2, np.uint8)
+    c, k = orc.kmeans(W32, b4, iters=1)
+    err, _ = orc.dequant_error(W32, c, k, b4, np.arange(200, dtype=np.int64), None)
+    ref = ((W32.astype(np.float64) - W32.astype(np.float16).astype(np.float64)) ** 2).sum(axis=1)
+    assert np.allclose(err, ref, rtol=1e-12)
+
+
+def test_error_matches_dense_definition_and_delta_y(orc):
+    rng = np.random.default_rng(17)
+    d_in, d_out, n = 16, 40, 64
+    W = rng.normal(0, 1, (d_in, d_out)).astype(np.float32)
+    # orthogonal columns: scaled columns of a random orthogonal matrix
+    Q, _ = np.linalg.qr(rng.normal(size=(n, d_in)))
+    X = (Q * rng.lognormal(0, 1, d_in)).astype(np.float32)
+    _, sumsq = orc.act_stats(X)
+    bits = rng.integers(2, 4, d_in).astype(np.uint8)
+    bits[5] = orc.PROTECTED
+    cent, codes = orc.kmeans(W, bits, iters=4)
+    out_idx = np.sort(rng.choice(d_in * d_out, 25, replace=False)).astype(np.int64)
+    err, tot = orc.dequant_error(W, cent, codes, bits, out_idx, sumsq)
+    What = np.take_along_axis(cent.astype(np.float64), codes.astype(np.int64), axis=1)
+    w16 = W.astype(np.float16).astype(np.float64)
+    What[5] = w16[5]
+    What.reshape(-1)[out_idx] = w16.reshape(-1)[out_idx]
+    dW = W.astype(np.float64) - What
+    assert np.allclose(err, (dW ** 2).sum(axis=1), rtol=1e-12)
+    assert np.isclose(tot[1], (dW ** 2).sum(), rtol=1e-12)
+    assert np.isclose(tot[0], (sumsq.astype(np.float64)[:, None] * dW ** 2).sum(), rtol=1e-12)
+    # App. B.3: Delta Y = X (W - W_hat); for orthogonal columns its squared norm is the weighted sum
+    dY = X.astype(np.float64) @ dW
+    assert np.isclose(tot[0], (dY ** 2).sum(), rtol=1e-5)
+
+
+def test_more_levels_never_hurt_and_outlier_removal_helps(orc):
+    """End-to-end sanity of the path of Sec. 3.2 on a small layer."""
+    rng = np.random.default_rng(18)
+    d_in, d_out = 64, 128
+    W = rng.normal(0, 0.02, (d_in, d_out)).astype(np.float16)
+    W[rng.random(W.shape) < 0.005] = np.float16(0.3)
+    X = (rng.normal(0, 1, (96, d_in)) * rng.lognormal(0, 0.5, d_in)).astype(np.float16)
+    e = {}
+    for b in (2.0, 2.5, 3.0):
+        e[b] = orc.quantize_layer(W.copy(), X, (2, 3), b, 4500, 5000, 15)["totals"][0]
+    assert e[2.0] > e[2.5] > e[3.0]
+    r0 = orc.quantize_layer(W.copy(), X, (2, 3), 2.5, 0, 0, 15)
+    r1 = orc.quantize_layer(W.copy(), X, (2, 3), 2.5, 4500, 5000, 15)
+    assert r1["totals"][0] < r0["totals"][0]
+    assert len(r1["out_idx"]) == orc.count_ppm(5000, d_in * d_out)
+    assert r1["chan_mask"].sum() == orc.count_ppm(4500, d_in) == len(r1["act_idx"])
+    assert not set(r1["out_idx"] // d_out) & set(r1["act_idx"])
