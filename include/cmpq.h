@@ -1,0 +1,213 @@
+/*
+ * cmpq.h - C ABI of the CMPQ quantization path for AMD MI355X (gfx950).
+ *
+ * CMPQ = Channel-Wise Mixed-Precision Quantization (arXiv 2410.13056).  The
+ * library turns one linear layer's weight W and calibration activations X into
+ * the paper's stored format: a bit-width per input channel, a look-up table of
+ * 2^bits FP16 levels per channel, bit-packed codes grouped by width, and two
+ * kinds of FP16 outliers.
+ *
+ * Orientation and notation follow the paper (Sec. 3.2.1):
+ *   W in R^{d_in x d_out}, row-major with leading dimension ldw >= d_out;
+ *   "channel i" is the row W[i,:], the d_out weights that multiply input
+ *   feature i.  A framework that stores weights as [d_out, d_in] converts with
+ *   cmpq_transpose first.  X in R^{n x d_in} (tokens by channels), row-major.
+ *   The linear index of a weight is i*d_out + o and must stay below 2^31.
+ *
+ * Conventions for every entry point:
+ *   - returns CMPQ_OK (0) or a negative CMPQ_E* code; cmpq_strerror names it.
+ *     Argument errors are detected on the host before anything is enqueued.
+ *   - every data pointer is a DEVICE pointer owned by the caller unless the
+ *     comment says "host".  The library keeps nothing between calls and
+ *     allocates no device memory: scratch comes from the caller's workspace
+ *     `ws` of `ws_bytes` bytes (256-byte aligned), at least
+ *     cmpq_workspace_bytes(op, d_in, d_out, n) large, else CMPQ_EWORKSPACE.
+ *   - work is enqueued on `stream` (a hipStream_t passed as void*, null = the
+ *     default stream) and the call returns without waiting for it.
+ *   - `status` (nullable device int32) receives bit flags OR-ed in by the
+ *     kernels: CMPQ_STATUS_NONFINITE when an input held NaN or infinity.
+ *   - results are bit-for-bit reproducible from run to run: no floating-point
+ *     atomics, every cross-workgroup reduction has a fixed order.
+ */
+#ifndef CMPQ_H
+#define CMPQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define CMPQ_OK 0
+#define CMPQ_EINVAL (-1)     /* null pointer, negative size, unknown enum value            */
+#define CMPQ_ESHAPE (-2)     /* leading dimension too small, size beyond a documented limit */
+#define CMPQ_EBUDGET (-3)    /* bit set not consecutive within 1..4, or avg_bits outside it */
+#define CMPQ_ECOUNT (-4)     /* asked for more outliers than there are candidates           */
+#define CMPQ_EWORKSPACE (-5) /* workspace missing, misaligned or too small                  */
+#define CMPQ_EHIP (-6)       /* the HIP runtime refused a launch                            */
+
+#define CMPQ_F16 0 /* IEEE binary16 */
+#define CMPQ_F32 1 /* IEEE binary32 */
+
+#define CMPQ_KMAX 16      /* levels per channel at the widest setting (4 bits)   */
+#define CMPQ_PROTECTED 16 /* bits[i] of a channel of O_act: kept whole in FP16   */
+
+#define CMPQ_STATUS_NONFINITE 1
+
+/* `op` of cmpq_workspace_bytes */
+#define CMPQ_OP_ACT_STATS 0        /* n = tokens in the call                     */
+#define CMPQ_OP_ALLOCATE_BITS 1    /* n ignored                                  */
+#define CMPQ_OP_OUTLIER_CHANNELS 2 /* n = k                                      */
+#define CMPQ_OP_OUTLIER_WEIGHTS 3  /* n = k                                      */
+#define CMPQ_OP_KMEANS 4           /* n ignored                                  */
+#define CMPQ_OP_PACK 5             /* n ignored                                  */
+#define CMPQ_OP_DEQUANT_ERROR 6    /* n ignored                                  */
+
+/* `mode` / `score` of cmpq_extract_outliers */
+#define CMPQ_OUTLIER_CHANNELS 0
+#define CMPQ_OUTLIER_WEIGHTS 1
+#define CMPQ_SCORE_RESIDUAL 0  /* |W' - W'_q|: the criterion of Sec. 3.2.2           */
+#define CMPQ_SCORE_MAGNITUDE 1 /* |W'|: the magnitude rule Sec. 3.2.2 contrasts with */
+
+/* `init` of cmpq_kmeans_quantize */
+#define CMPQ_INIT_QUANTILE 0
+
+size_t cmpq_workspace_bytes(int op, int64_t d_in, int64_t d_out, int64_t n);
+const char *cmpq_strerror(int code);
+
+/* Outlier counts are integers: round_half_up(ppm * n / 1e6) in integer arithmetic
+ * (Sec. 3.2.2 prints the fractions 0.45 % and 0.05 %, i.e. 4500 and 500 ppm). */
+int64_t cmpq_count_ppm(int64_t ppm, int64_t n);
+
+/*
+ * Sec. 3.2.1, "per-channel L2-norm of X": acc[i] (+)= sum_t X[t,i]^2 in fp64 and
+ * sumsq[i] = (float)acc[i].  The square of the paper's a_i is kept: it ranks
+ * channels identically and is the channel weight of the output error (App. B.3).
+ *   X      [n, d_in], dtype CMPQ_F16 or CMPQ_F32, leading dimension ldx >= d_in.
+ *   acc    [d_in] fp64, in/out.  accumulate = 0 overwrites it (tokens of a first
+ *          chunk), accumulate != 0 adds to it (later chunks); n = 0 is allowed.
+ *   sumsq  [d_in] fp32, out, nullable.
+ * Workspace: CMPQ_OP_ACT_STATS.  Status: CMPQ_STATUS_NONFINITE.
+ */
+int cmpq_act_stats(const void *X, int dtype, int64_t n, int64_t d_in, int64_t ldx, double *acc,
+                   float *sumsq, int accumulate, void *ws, size_t ws_bytes, int32_t *status,
+                   void *stream);
+
+/*
+ * Orientation helper for Sec. 3.2.1's W in R^{d_in x d_out}: dst[c, r] = src[r, c].
+ * src is [rows, cols] with ld_src >= cols, dst is [cols, rows] with ld_dst >= rows,
+ * both of `dtype`; they must not overlap.  No workspace.
+ */
+int cmpq_transpose(const void *src, int dtype, int64_t rows, int64_t cols, int64_t ld_src,
+                   void *dst, int64_t ld_dst, void *stream);
+
+/*
+ * Algorithm 1 (channel-wise precision allocation) with an integer budget.
+ *   sumsq      [d_in] channel statistic (non-negative, finite).
+ *   chan_mask  [d_in] nullable; 1 marks a channel of O_act.  Such channels get
+ *              bits = CMPQ_PROTECTED and are left out of the ranking and the budget.
+ *   n_protected  number of ones in chan_mask (the caller chose it; 0 when null).
+ *   bit_set    host, n_set consecutive widths within 1..4, ascending (the paper: {2,3,4}).
+ *   avg_bits   b, within [bit_set[0], bit_set[n_set-1]].
+ * With d_eff = d_in - n_protected and T = floor(b*d_eff + 1e-9):
+ *   s < b < s+1: the T - s*d_eff channels with the largest statistic get s+1, the rest s
+ *     (for {2,3,4} these are the b > 3 and b < 3 branches of Algorithm 1);
+ *   b = s with s-1 and s+1 in the set (the b = 3 branch): the ceil(0.01*(d_eff-1)) lowest
+ *     get s-1 and as many highest get s+1; otherwise every channel gets s.
+ * Ranking: larger statistic first, equal statistics by smaller channel index.
+ *   bits        [d_in] out.
+ *   counts_host host, [n_set] out, nullable: channels per width, written before returning
+ *               (they follow from the sizes alone).
+ * Workspace: CMPQ_OP_ALLOCATE_BITS.
+ */
+int cmpq_allocate_bits(const float *sumsq, int64_t d_in, const uint8_t *chan_mask,
+                       int64_t n_protected, const int32_t *bit_set, int n_set, double avg_bits,
+                       uint8_t *bits, int64_t *counts_host, void *ws, size_t ws_bytes,
+                       void *stream);
+
+/*
+ * The two outlier extractions of Sec. 3.2.2.  Both pick the k largest keys under the
+ * order "larger key first, equal keys by smaller index" and return indices ascending.
+ *
+ * mode CMPQ_OUTLIER_CHANNELS (O_act): keys are sumsq[d_in].
+ *   idx_out [k] int32 channel indices; chan_mask_out [d_in] (nullable) 1 = selected.
+ *   W, centroids, codes, bits, val_out are ignored.  k <= d_in.
+ *
+ * mode CMPQ_OUTLIER_WEIGHTS (O_q): candidates are the entries of channels with bits in
+ *   1..4 (W' = W - O_act).  Key = fp32 |w - centroids[i][codes[i,o]]| for
+ *   CMPQ_SCORE_RESIDUAL (needs centroids [d_in,16] and codes [d_in,d_out] from a first
+ *   cmpq_kmeans_quantize), or fp32 |w| for CMPQ_SCORE_MAGNITUDE.  The selection is over
+ *   the whole layer.  idx_out [k] int32 linear indices i*d_out+o; val_out [k] (nullable)
+ *   the weights as FP16 bit patterns.  k above the number of candidates: CMPQ_ECOUNT.
+ *   sumsq and chan_mask_out are ignored.
+ * Workspace: CMPQ_OP_OUTLIER_CHANNELS / CMPQ_OP_OUTLIER_WEIGHTS.
+ */
+int cmpq_extract_outliers(int mode, int score, const float *sumsq, const void *W, int dtype,
+                          int64_t d_in, int64_t d_out, int64_t ldw, const float *centroids,
+                          const uint8_t *codes, const uint8_t *bits, int64_t k, int32_t *idx_out,
+                          uint16_t *val_out, uint8_t *chan_mask_out, void *ws, size_t ws_bytes,
+                          void *stream);
+
+/*
+ * Sec. 3.2.1, channel-wise non-uniform quantization: for every channel with bits[i] in
+ * 1..4, K = 2^bits[i] levels by Lloyd's algorithm on W[i,:], then each weight is coded by
+ * its nearest level (Sec. 3 eq. Q(x)).
+ *   out_idx     [n_out] int32 nullable: linear indices, ascending, of entries removed
+ *               before clustering (O_q, Sec. 3.2.2); they weigh 0 but still get a code.
+ *   elem_weight [d_in, d_out] fp32 nullable, leading dimension d_out: importance of each
+ *               entry in the level update (null = 1).  Must be >= 0 and finite.
+ *   iters       rounds of (assign, update), run in full; then one more assignment.
+ *   init        CMPQ_INIT_QUANTILE: level j starts at the order statistic
+ *               floor((2j+1)*M/(2K)) of the M entries with positive weight; 0 when M = 0.
+ *   centroids   [d_in, 16] fp32 out: K levels, then +infinity; all +infinity for a channel
+ *               with bits outside 1..4.
+ *   codes       [d_in, d_out] uint8 out (0 for such a channel).
+ * Assignment: the nearest level in exact arithmetic, equal distances to the smaller level
+ * index.  Update: level = sum(m*x)/sum(m) of its members, accumulated in fp64 and rounded
+ * once to fp32; a level without members keeps its value.  -0.0 reads as +0.0.
+ * Limits: d_out <= 32768 for CMPQ_F16, <= 16384 for CMPQ_F32 (CMPQ_ESHAPE beyond).
+ * Workspace: CMPQ_OP_KMEANS.  Status: CMPQ_STATUS_NONFINITE.
+ */
+int cmpq_kmeans_quantize(const void *W, int dtype, int64_t d_in, int64_t d_out, int64_t ldw,
+                         const uint8_t *bits, const int32_t *out_idx, int64_t n_out,
+                         const float *elem_weight, int iters, int init, float *centroids,
+                         uint8_t *codes, void *ws, size_t ws_bytes, int32_t *status,
+                         void *stream);
+
+/*
+ * Sec. 5.1 / Fig. 4, the stored format: one code matrix per width.  For j < n_set and
+ * b = bit_set[j], the channels with bits == b in ascending index form the rows:
+ *   chan_idx[j] [counts_host[j]] int32             channel of each row;
+ *   packed[j]   [counts_host[j], ceil(d_out*b/32)] uint32; a row is a little-endian bit
+ *               stream, code of output o in stream bits [o*b, (o+1)*b), stream bit s =
+ *               bit (s mod 32) of word (s / 32), zero padded to whole words;
+ *   lut[j]      [counts_host[j], 2^b] FP16 bit patterns of the levels (round to nearest even).
+ * packed, chan_idx, lut are HOST arrays of n_set DEVICE pointers; bit_set and counts_host
+ * (from cmpq_allocate_bits) are host arrays.  Channels of O_act store no row.
+ * Workspace: CMPQ_OP_PACK.
+ */
+int cmpq_pack(const uint8_t *codes, int64_t d_in, int64_t d_out, const uint8_t *bits,
+              const float *centroids, const int32_t *bit_set, int n_set,
+              const int64_t *counts_host, uint32_t *const *packed, int32_t *const *chan_idx,
+              uint16_t *const *lut, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Reconstruction W_hat = W_q + O (Sec. 3.2.2) and the output error of App. B.3,
+ * Delta Y = X (W - W_hat), with cross-channel products of X dropped:
+ *   W_hat[i,o] = fp16(W[i,o]) for channels with bits outside 1..4 and for the entries of
+ *                out_idx [n_out] (ascending linear indices, nullable), else
+ *                centroids[i][codes[i,o]];
+ *   err_ch[i]     = sum_o (W - W_hat)^2                    [d_in] fp64 out
+ *   err_total[0]  = sum_i sumsq[i] * err_ch[i]  (sumsq null: weight 1);  err_total[1] = sum_i err_ch[i].
+ * Workspace: CMPQ_OP_DEQUANT_ERROR.
+ */
+int cmpq_dequant_error(const void *W, int dtype, int64_t d_in, int64_t d_out, int64_t ldw,
+                       const float *centroids, const uint8_t *codes, const uint8_t *bits,
+                       const int32_t *out_idx, int64_t n_out, const float *sumsq, double *err_ch,
+                       double *err_total, void *ws, size_t ws_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CMPQ_H */

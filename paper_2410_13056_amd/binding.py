@@ -1,0 +1,218 @@
+"""Thin Python binding of libcmpq.so: same names as include/cmpq.h, argument
+marshalling only.  Torch tensors supply device memory and the current stream;
+every step of the path runs in the library's HIP kernels.  There is no fallback:
+if the library is missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libcmpq.so")
+
+OK = 0
+F16, F32 = 0, 1
+KMAX = 16
+PROTECTED = 16
+STATUS_NONFINITE = 1
+OP_ACT_STATS, OP_ALLOCATE_BITS, OP_OUTLIER_CHANNELS, OP_OUTLIER_WEIGHTS, OP_KMEANS, OP_PACK, \
+    OP_DEQUANT_ERROR = range(7)
+OUTLIER_CHANNELS, OUTLIER_WEIGHTS = 0, 1
+SCORE_RESIDUAL, SCORE_MAGNITUDE = 0, 1
+INIT_QUANTILE = 0
+
+EXPORTS = ("cmpq_workspace_bytes", "cmpq_strerror", "cmpq_count_ppm", "cmpq_act_stats",
+           "cmpq_transpose", "cmpq_allocate_bits", "cmpq_extract_outliers",
+           "cmpq_kmeans_quantize", "cmpq_pack", "cmpq_dequant_error")
+
+_i64, _i32, _int, _vp, _dbl, _sz = (ctypes.c_int64, ctypes.c_int32, ctypes.c_int, ctypes.c_void_p,
+                                    ctypes.c_double, ctypes.c_size_t)
+_lib = None
+
+
+class CmpqError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {strerror(code)} ({code})")
+
+
+def lib() -> ctypes.CDLL:
+    """Loads the built library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2410_13056_amd.build`")
+        L = ctypes.CDLL(LIB_PATH)
+        L.cmpq_workspace_bytes.restype = _sz
+        L.cmpq_workspace_bytes.argtypes = [_int, _i64, _i64, _i64]
+        L.cmpq_strerror.restype = ctypes.c_char_p
+        L.cmpq_strerror.argtypes = [_int]
+        L.cmpq_count_ppm.restype = _i64
+        L.cmpq_count_ppm.argtypes = [_i64, _i64]
+        L.cmpq_act_stats.argtypes = [_vp, _int, _i64, _i64, _i64, _vp, _vp, _int, _vp, _sz, _vp, _vp]
+        L.cmpq_transpose.argtypes = [_vp, _int, _i64, _i64, _i64, _vp, _i64, _vp]
+        L.cmpq_allocate_bits.argtypes = [_vp, _i64, _vp, _i64, _vp, _int, _dbl, _vp, _vp, _vp, _sz, _vp]
+        L.cmpq_extract_outliers.argtypes = [_int, _int, _vp, _vp, _int, _i64, _i64, _i64, _vp, _vp,
+                                            _vp, _i64, _vp, _vp, _vp, _vp, _sz, _vp]
+        L.cmpq_kmeans_quantize.argtypes = [_vp, _int, _i64, _i64, _i64, _vp, _vp, _i64, _vp, _int,
+                                           _int, _vp, _vp, _vp, _sz, _vp, _vp]
+        L.cmpq_pack.argtypes = [_vp, _i64, _i64, _vp, _vp, _vp, _int, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+        L.cmpq_dequant_error.argtypes = [_vp, _int, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _i64, _vp,
+                                         _vp, _vp, _vp, _sz, _vp]
+        for name in EXPORTS[3:]:
+            getattr(L, name).restype = _int
+        _lib = L
+    return _lib
+
+
+def strerror(code: int) -> str:
+    return lib().cmpq_strerror(int(code)).decode()
+
+
+def count_ppm(ppm: int, n: int) -> int:
+    return int(lib().cmpq_count_ppm(int(ppm), int(n)))
+
+
+def workspace_bytes(op: int, d_in: int, d_out: int = 0, n: int = 0) -> int:
+    return int(lib().cmpq_workspace_bytes(int(op), int(d_in), int(d_out), int(n)))
+
+
+def _dtype(t: torch.Tensor) -> int:
+    if t.dtype == torch.float16:
+        return F16
+    if t.dtype == torch.float32:
+        return F32
+    raise TypeError(f"cmpq takes float16 or float32 tensors, got {t.dtype}")
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError("cmpq entry points take device tensors")
+    return t.data_ptr()
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _rows(t: torch.Tensor):
+    """(rows, cols, leading dimension) of a 2-D tensor whose rows are contiguous."""
+    if t.dim() != 2 or (t.shape[1] > 1 and t.stride(1) != 1):
+        raise ValueError("expected a 2-D tensor with unit stride along its rows")
+    ld = t.stride(0) if t.shape[0] > 1 else max(t.shape[1], 1)
+    return t.shape[0], t.shape[1], ld
+
+
+class Workspace:
+    """A growable device buffer handed to the library as its scratch space."""
+
+    def __init__(self, device="cuda"):
+        self.device = device
+        self.buf = torch.empty(0, dtype=torch.uint8, device=device)
+
+    def get(self, nbytes: int) -> torch.Tensor:
+        if self.buf.numel() < nbytes:
+            self.buf = torch.empty(int(nbytes), dtype=torch.uint8, device=self.device)
+        return self.buf
+
+
+def _check(rc: int, where: str):
+    if rc != OK:
+        raise CmpqError(rc, where)
+
+
+def act_stats(X: torch.Tensor, acc: torch.Tensor, sumsq: Optional[torch.Tensor], accumulate: bool,
+              ws: Workspace, status: Optional[torch.Tensor] = None) -> None:
+    n, d_in, ldx = _rows(X)
+    buf = ws.get(workspace_bytes(OP_ACT_STATS, d_in, 0, n))
+    _check(lib().cmpq_act_stats(_ptr(X), _dtype(X), n, d_in, ldx, _ptr(acc), _ptr(sumsq),
+                                int(bool(accumulate)), _ptr(buf), buf.numel(), _ptr(status), _stream()),
+           "cmpq_act_stats")
+
+
+def transpose(src: torch.Tensor, dst: torch.Tensor) -> None:
+    rows, cols, ld_src = _rows(src)
+    r2, c2, ld_dst = _rows(dst)
+    if (r2, c2) != (cols, rows) or src.dtype != dst.dtype:
+        raise ValueError("dst must be the transposed shape and the same dtype")
+    _check(lib().cmpq_transpose(_ptr(src), _dtype(src), rows, cols, ld_src, _ptr(dst), ld_dst, _stream()),
+           "cmpq_transpose")
+
+
+def allocate_bits(sumsq: torch.Tensor, chan_mask: Optional[torch.Tensor], n_protected: int,
+                  bit_set: Sequence[int], avg_bits: float, bits: torch.Tensor, ws: Workspace):
+    d_in = sumsq.numel()
+    bs = (_i32 * len(bit_set))(*bit_set)
+    counts = (_i64 * len(bit_set))()
+    buf = ws.get(workspace_bytes(OP_ALLOCATE_BITS, d_in))
+    _check(lib().cmpq_allocate_bits(_ptr(sumsq), d_in, _ptr(chan_mask), int(n_protected), bs, len(bit_set),
+                                    float(avg_bits), _ptr(bits), counts, _ptr(buf), buf.numel(), _stream()),
+           "cmpq_allocate_bits")
+    return [int(c) for c in counts]
+
+
+def extract_channel_outliers(sumsq: torch.Tensor, k: int, idx_out: torch.Tensor,
+                             chan_mask_out: Optional[torch.Tensor], ws: Workspace) -> None:
+    d_in = sumsq.numel()
+    buf = ws.get(workspace_bytes(OP_OUTLIER_CHANNELS, d_in, 0, k))
+    _check(lib().cmpq_extract_outliers(OUTLIER_CHANNELS, SCORE_RESIDUAL, _ptr(sumsq), None, F16, d_in, 0, 0,
+                                       None, None, None, int(k), _ptr(idx_out), None, _ptr(chan_mask_out),
+                                       _ptr(buf), buf.numel(), _stream()),
+           "cmpq_extract_outliers(channels)")
+
+
+def extract_weight_outliers(W: torch.Tensor, centroids: Optional[torch.Tensor], codes: Optional[torch.Tensor],
+                            bits: torch.Tensor, k: int, idx_out: torch.Tensor, val_out: Optional[torch.Tensor],
+                            ws: Workspace, score: int = SCORE_RESIDUAL) -> None:
+    d_in, d_out, ldw = _rows(W)
+    buf = ws.get(workspace_bytes(OP_OUTLIER_WEIGHTS, d_in, d_out, k))
+    _check(lib().cmpq_extract_outliers(OUTLIER_WEIGHTS, int(score), None, _ptr(W), _dtype(W), d_in, d_out, ldw,
+                                       _ptr(centroids), _ptr(codes), _ptr(bits), int(k), _ptr(idx_out),
+                                       _ptr(val_out), None, _ptr(buf), buf.numel(), _stream()),
+           "cmpq_extract_outliers(weights)")
+
+
+def kmeans_quantize(W: torch.Tensor, bits: torch.Tensor, out_idx: Optional[torch.Tensor], n_out: int,
+                    elem_weight: Optional[torch.Tensor], iters: int, centroids: torch.Tensor,
+                    codes: torch.Tensor, ws: Workspace, status: Optional[torch.Tensor] = None,
+                    init: int = INIT_QUANTILE) -> None:
+    d_in, d_out, ldw = _rows(W)
+    buf = ws.get(workspace_bytes(OP_KMEANS, d_in, d_out))
+    _check(lib().cmpq_kmeans_quantize(_ptr(W), _dtype(W), d_in, d_out, ldw, _ptr(bits), _ptr(out_idx), int(n_out),
+                                      _ptr(elem_weight), int(iters), int(init), _ptr(centroids), _ptr(codes),
+                                      _ptr(buf), buf.numel(), _ptr(status), _stream()),
+           "cmpq_kmeans_quantize")
+
+
+def pack(codes: torch.Tensor, bits: torch.Tensor, centroids: torch.Tensor, bit_set: Sequence[int],
+         counts: Sequence[int], packed: Sequence[Optional[torch.Tensor]],
+         chan_idx: Sequence[Optional[torch.Tensor]], lut: Sequence[Optional[torch.Tensor]], ws: Workspace) -> None:
+    d_in, d_out = codes.shape
+    n = len(bit_set)
+    bs = (_i32 * n)(*bit_set)
+    cn = (_i64 * n)(*counts)
+    pk = (_vp * n)(*[_ptr(t) for t in packed])
+    ci = (_vp * n)(*[_ptr(t) for t in chan_idx])
+    lt = (_vp * n)(*[_ptr(t) for t in lut])
+    buf = ws.get(workspace_bytes(OP_PACK, d_in, d_out))
+    _check(lib().cmpq_pack(_ptr(codes), d_in, d_out, _ptr(bits), _ptr(centroids), bs, n, cn, pk, ci, lt,
+                           _ptr(buf), buf.numel(), _stream()),
+           "cmpq_pack")
+
+
+def dequant_error(W: torch.Tensor, centroids: torch.Tensor, codes: torch.Tensor, bits: torch.Tensor,
+                  out_idx: Optional[torch.Tensor], n_out: int, sumsq: Optional[torch.Tensor],
+                  err_ch: torch.Tensor, err_total: torch.Tensor, ws: Workspace) -> None:
+    d_in, d_out, ldw = _rows(W)
+    buf = ws.get(workspace_bytes(OP_DEQUANT_ERROR, d_in, d_out))
+    _check(lib().cmpq_dequant_error(_ptr(W), _dtype(W), d_in, d_out, ldw, _ptr(centroids), _ptr(codes),
+                                    _ptr(bits), _ptr(out_idx), int(n_out), _ptr(sumsq), _ptr(err_ch),
+                                    _ptr(err_total), _ptr(buf), buf.numel(), _stream()),
+           "cmpq_dequant_error")

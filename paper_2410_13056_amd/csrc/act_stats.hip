@@ -1,0 +1,192 @@
+// cmpq_act_stats: per-channel sum of squares of the calibration activations
+// (Sec. 3.2.1 of arXiv 2410.13056, the "per-channel L2-norm of X", kept squared).
+//
+// HBM bound: every element of X is read once.  Each lane streams 16-byte
+// pieces of a row (8 halves or 4 floats), a wave covers 1 KiB of one row, the
+// four waves of a workgroup take consecutive rows, and the grid tiles X into
+// (column block) x (row split) so that a few thousand workgroups are in flight.
+// Squares are accumulated in fp64 (x*x is exact there for both input types), so
+// the result does not depend on how rows are split beyond the last fp64 bit.
+// Row splits leave fp64 partials in the workspace; a second kernel adds them in
+// split order, which makes the whole reduction reproducible.
+#include "common.h"
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kWaves = kThreads / CMPQ_WAVE;
+
+template <typename T>
+struct Vec;
+template <>
+struct Vec<__half> {
+    static constexpr int N = 8;
+    __device__ static void load(const __half *p, float (&f)[8]) {
+        const uint4 raw = *reinterpret_cast<const uint4 *>(p);
+        const __half2 *h = reinterpret_cast<const __half2 *>(&raw);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            float2 t = __half22float2(h[j]);
+            f[2 * j] = t.x;
+            f[2 * j + 1] = t.y;
+        }
+    }
+};
+template <>
+struct Vec<float> {
+    static constexpr int N = 4;
+    __device__ static void load(const float *p, float (&f)[4]) {
+        const float4 raw = *reinterpret_cast<const float4 *>(p);
+        f[0] = raw.x;
+        f[1] = raw.y;
+        f[2] = raw.z;
+        f[3] = raw.w;
+    }
+};
+
+// partial[split * d_in + col] = sum over the rows of this split of X[row, col]^2
+template <typename T>
+__global__ __launch_bounds__(kThreads) void act_stats_vec_kernel(const T *__restrict__ X, int64_t n,
+                                                                  int64_t d_in, int64_t ldx,
+                                                                  int64_t rows_per_split,
+                                                                  double *__restrict__ partial) {
+    constexpr int V = Vec<T>::N;
+    constexpr int kCols = CMPQ_WAVE * V;  // columns per workgroup
+    __shared__ double red[kWaves][kCols];
+    const int lane = threadIdx.x & (CMPQ_WAVE - 1), wave = threadIdx.x / CMPQ_WAVE;
+    const int64_t col0 = (int64_t)blockIdx.x * kCols + (int64_t)lane * V;
+    const int64_t r_begin = (int64_t)blockIdx.y * rows_per_split;
+    const int64_t r_end = min(n, r_begin + rows_per_split);
+    double s[V];
+#pragma unroll
+    for (int v = 0; v < V; ++v) s[v] = 0.0;
+    if (col0 < d_in) {
+        const T *p = X + col0;
+        int64_t r = r_begin + wave;
+        // four rows in flight per wave
+        for (; r + 3 * kWaves < r_end; r += 4 * kWaves) {
+            float f[4][V];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) Vec<T>::load(p + (r + u * kWaves) * ldx, f[u]);
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int v = 0; v < V; ++v) {
+                    double d = (double)f[u][v];
+                    s[v] = fma(d, d, s[v]);
+                }
+        }
+        for (; r < r_end; r += kWaves) {
+            float f[V];
+            Vec<T>::load(p + r * ldx, f);
+#pragma unroll
+            for (int v = 0; v < V; ++v) {
+                double d = (double)f[v];
+                s[v] = fma(d, d, s[v]);
+            }
+        }
+    }
+#pragma unroll
+    for (int v = 0; v < V; ++v) red[wave][lane * V + v] = s[v];
+    __syncthreads();
+    for (int c = threadIdx.x; c < kCols; c += kThreads) {
+        const int64_t col = (int64_t)blockIdx.x * kCols + c;
+        if (col < d_in) {
+            double t = red[0][c];
+#pragma unroll
+            for (int w = 1; w < kWaves; ++w) t += red[w][c];
+            partial[(int64_t)blockIdx.y * d_in + col] = t;
+        }
+    }
+}
+
+// Any alignment: one thread per column, threads of a wave read neighbouring columns.
+template <typename T>
+__global__ __launch_bounds__(kThreads) void act_stats_any_kernel(const T *__restrict__ X, int64_t n,
+                                                                  int64_t d_in, int64_t ldx,
+                                                                  int64_t rows_per_split,
+                                                                  double *__restrict__ partial) {
+    const int64_t col = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (col >= d_in) return;
+    const int64_t r_begin = (int64_t)blockIdx.y * rows_per_split;
+    const int64_t r_end = min(n, r_begin + rows_per_split);
+    double s = 0.0;
+    for (int64_t r = r_begin; r < r_end; ++r) {
+        double d = (double)load_as_f32<T>(X, r * ldx + col);
+        s = fma(d, d, s);
+    }
+    partial[(int64_t)blockIdx.y * d_in + col] = s;
+}
+
+__global__ __launch_bounds__(kThreads) void act_stats_finish_kernel(
+    const double *__restrict__ partial, int splits, int64_t d_in, double *__restrict__ acc,
+    float *__restrict__ sumsq, int accumulate, int32_t *__restrict__ status) {
+    const int64_t col = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (col >= d_in) return;
+    double t = accumulate ? acc[col] : 0.0;
+    for (int sidx = 0; sidx < splits; ++sidx) t += partial[(int64_t)sidx * d_in + col];
+    acc[col] = t;
+    if (sumsq) sumsq[col] = (float)t;
+    if (status && !isfinite(t)) atomicOr(status, CMPQ_STATUS_NONFINITE);
+}
+
+int64_t pick_splits(int64_t n, int64_t col_blocks) {
+    if (n <= 0) return 0;
+    int64_t want = cdiv(4096, col_blocks);       // ~16 workgroups per compute unit
+    int64_t cap = cdiv(n, 16 * kWaves);           // at least 16 rows per wave
+    int64_t s = want < cap ? want : cap;
+    return s < 1 ? 1 : s;
+}
+
+}  // namespace
+
+size_t cmpq_ws_act_stats(int64_t d_in, int64_t n) {
+    // the widest column block gives the fewest column blocks, hence the most row splits
+    int64_t col_blocks = cdiv(d_in, 512) > 0 ? cdiv(d_in, 512) : 1;
+    int64_t s = pick_splits(n, col_blocks);
+    return align_up((size_t)(s > 0 ? s : 1) * (size_t)(d_in > 0 ? d_in : 1) * sizeof(double), 256);
+}
+
+extern "C" int cmpq_act_stats(const void *X, int dtype, int64_t n, int64_t d_in, int64_t ldx,
+                              double *acc, float *sumsq, int accumulate, void *ws, size_t ws_bytes,
+                              int32_t *status, void *stream) {
+    if (!acc || n < 0 || d_in < 0 || (dtype != CMPQ_F16 && dtype != CMPQ_F32)) return CMPQ_EINVAL;
+    if (n > 0 && !X) return CMPQ_EINVAL;
+    if (ldx < d_in) return CMPQ_ESHAPE;
+    if (d_in == 0) return CMPQ_OK;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int vec = dtype == CMPQ_F16 ? 8 : 4;
+    const bool aligned = n > 0 && d_in % vec == 0 && ldx % vec == 0 &&
+                         reinterpret_cast<uintptr_t>(X) % 16 == 0;
+    const int64_t col_blocks = aligned ? cdiv(d_in, CMPQ_WAVE * vec) : cdiv(d_in, kThreads);
+    const int64_t splits = pick_splits(n, col_blocks);
+    double *partial = static_cast<double *>(ws);
+    if (splits > 0) {
+        if (!ws || reinterpret_cast<uintptr_t>(ws) % 256 != 0 ||
+            ws_bytes < (size_t)splits * d_in * sizeof(double))
+            return CMPQ_EWORKSPACE;
+        if (splits > 65535) return CMPQ_ESHAPE;
+        const int64_t rps = cdiv(n, splits);
+        dim3 grid((unsigned)col_blocks, (unsigned)splits);
+        if (aligned) {
+            if (dtype == CMPQ_F16)
+                act_stats_vec_kernel<__half><<<grid, kThreads, 0, st>>>(
+                    static_cast<const __half *>(X), n, d_in, ldx, rps, partial);
+            else
+                act_stats_vec_kernel<float><<<grid, kThreads, 0, st>>>(
+                    static_cast<const float *>(X), n, d_in, ldx, rps, partial);
+        } else {
+            if (dtype == CMPQ_F16)
+                act_stats_any_kernel<__half><<<grid, kThreads, 0, st>>>(
+                    static_cast<const __half *>(X), n, d_in, ldx, rps, partial);
+            else
+                act_stats_any_kernel<float><<<grid, kThreads, 0, st>>>(
+                    static_cast<const float *>(X), n, d_in, ldx, rps, partial);
+        }
+        CMPQ_LAUNCH_CHECK();
+    }
+    act_stats_finish_kernel<<<(unsigned)cdiv(d_in, kThreads), kThreads, 0, st>>>(
+        partial, (int)splits, d_in, acc, sumsq, accumulate, status);
+    CMPQ_LAUNCH_CHECK();
+    return CMPQ_OK;
+}

@@ -1,0 +1,93 @@
+// Small entry points of libcmpq: error names, counts, workspace sizes, and the
+// orientation helper that turns a framework's [d_out, d_in] weight into the
+// d_in x d_out matrix of Sec. 3.2.1 (arXiv 2410.13056), one row per input channel.
+#include "common.h"
+
+size_t cmpq_ws_act_stats(int64_t d_in, int64_t n);
+size_t cmpq_ws_allocate_bits(int64_t d_in);
+size_t cmpq_ws_outlier_channels(int64_t d_in);
+size_t cmpq_ws_outlier_weights(int64_t d_in, int64_t d_out);
+size_t cmpq_ws_kmeans(int64_t d_in, int64_t d_out);
+size_t cmpq_ws_pack(int64_t d_in);
+size_t cmpq_ws_dequant_error(int64_t d_in);
+
+extern "C" size_t cmpq_workspace_bytes(int op, int64_t d_in, int64_t d_out, int64_t n) {
+    if (d_in < 0 || d_out < 0 || n < 0) return 0;
+    switch (op) {
+        case CMPQ_OP_ACT_STATS: return cmpq_ws_act_stats(d_in, n);
+        case CMPQ_OP_ALLOCATE_BITS: return cmpq_ws_allocate_bits(d_in);
+        case CMPQ_OP_OUTLIER_CHANNELS: return cmpq_ws_outlier_channels(d_in);
+        case CMPQ_OP_OUTLIER_WEIGHTS: return cmpq_ws_outlier_weights(d_in, d_out);
+        case CMPQ_OP_KMEANS: return cmpq_ws_kmeans(d_in, d_out);
+        case CMPQ_OP_PACK: return cmpq_ws_pack(d_in);
+        case CMPQ_OP_DEQUANT_ERROR: return cmpq_ws_dequant_error(d_in);
+        default: return 0;
+    }
+}
+
+extern "C" const char *cmpq_strerror(int code) {
+    switch (code) {
+        case CMPQ_OK: return "ok";
+        case CMPQ_EINVAL: return "invalid argument (null pointer, negative size or unknown enum)";
+        case CMPQ_ESHAPE: return "shape not supported (leading dimension or size limit)";
+        case CMPQ_EBUDGET: return "bit set must be consecutive within 1..4 and hold avg_bits";
+        case CMPQ_ECOUNT: return "more outliers requested than candidates";
+        case CMPQ_EWORKSPACE: return "workspace missing, misaligned or too small";
+        case CMPQ_EHIP: return "HIP launch failed";
+        default: return "unknown cmpq error";
+    }
+}
+
+extern "C" int64_t cmpq_count_ppm(int64_t ppm, int64_t n) {
+    return (int64_t)(((unsigned __int128)ppm * (unsigned __int128)n + 500000u) / 1000000u);
+}
+
+namespace {
+
+constexpr int kTile = 64;
+
+// dst[c, r] = src[r, c]; a 64x64 tile goes through LDS so that both the read
+// and the write touch whole rows.  256 threads, each moves 16 elements.
+template <typename T>
+__global__ __launch_bounds__(256) void transpose_kernel(const T *__restrict__ src, int64_t rows,
+                                                         int64_t cols, int64_t ld_src,
+                                                         T *__restrict__ dst, int64_t ld_dst) {
+    __shared__ T tile[kTile][kTile + (sizeof(T) == 2 ? 2 : 1)];
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    const int64_t r0 = (int64_t)blockIdx.y * kTile, c0 = (int64_t)blockIdx.x * kTile;
+#pragma unroll
+    for (int k = 0; k < kTile; k += 4) {
+        const int64_t r = r0 + ty + k, c = c0 + tx;
+        if (r < rows && c < cols) tile[ty + k][tx] = src[r * ld_src + c];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < kTile; k += 4) {
+        const int64_t c = c0 + ty + k, r = r0 + tx;
+        if (c < cols && r < rows) dst[c * ld_dst + r] = tile[tx][ty + k];
+    }
+}
+
+}  // namespace
+
+extern "C" int cmpq_transpose(const void *src, int dtype, int64_t rows, int64_t cols,
+                              int64_t ld_src, void *dst, int64_t ld_dst, void *stream) {
+    if (rows < 0 || cols < 0 || (dtype != CMPQ_F16 && dtype != CMPQ_F32)) return CMPQ_EINVAL;
+    if (rows == 0 || cols == 0) return CMPQ_OK;
+    if (!src || !dst) return CMPQ_EINVAL;
+    if (ld_src < cols || ld_dst < rows) return CMPQ_ESHAPE;
+    const int64_t gx = cdiv(cols, kTile), gy = cdiv(rows, kTile);
+    if (gy > 65535) return CMPQ_ESHAPE;
+    dim3 grid((unsigned)gx, (unsigned)gy);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (dtype == CMPQ_F16)
+        transpose_kernel<uint16_t><<<grid, 256, 0, st>>>(static_cast<const uint16_t *>(src), rows,
+                                                         cols, ld_src, static_cast<uint16_t *>(dst),
+                                                         ld_dst);
+    else
+        transpose_kernel<uint32_t><<<grid, 256, 0, st>>>(static_cast<const uint32_t *>(src), rows,
+                                                         cols, ld_src, static_cast<uint32_t *>(dst),
+                                                         ld_dst);
+    CMPQ_LAUNCH_CHECK();
+    return CMPQ_OK;
+}

@@ -1,0 +1,102 @@
+// Internal helpers shared by the HIP translation units of libcmpq (gfx950 only).
+#pragma once
+
+#include <hip/hip_fp16.h>
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <type_traits>
+
+#include "cmpq.h"
+
+#define CMPQ_WAVE 64
+
+#define CMPQ_LAUNCH_CHECK()                                   \
+    do {                                                      \
+        if (hipGetLastError() != hipSuccess) return CMPQ_EHIP; \
+    } while (0)
+
+static inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
+static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+__device__ __forceinline__ size_t align_up_dev(size_t x) { return (x + 15) & ~(size_t)15; }
+
+// Carves aligned pieces out of the caller's workspace; `need` ends up as the total.
+struct WsCarver {
+    char *base;
+    size_t off = 0;
+    explicit WsCarver(void *p) : base(static_cast<char *>(p)) {}
+    template <typename T>
+    T *take(size_t count) {
+        off = align_up(off, 256);
+        T *p = reinterpret_cast<T *>(base + off);
+        off += count * sizeof(T);
+        return p;
+    }
+    size_t need() const { return align_up(off, 256); }
+};
+
+__device__ __forceinline__ double wave_sum_f64(double v) {
+#pragma unroll
+    for (int s = 32; s > 0; s >>= 1) v += __shfl_down(v, s, CMPQ_WAVE);
+    return v;
+}
+
+__device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v) {
+#pragma unroll
+    for (int s = 32; s > 0; s >>= 1) v += __shfl_down(v, s, CMPQ_WAVE);
+    return v;
+}
+
+// Inclusive scan over the lanes of a wave.
+__device__ __forceinline__ uint32_t wave_scan_incl_u32(uint32_t v) {
+    const int lane = threadIdx.x & (CMPQ_WAVE - 1);
+#pragma unroll
+    for (int s = 1; s < CMPQ_WAVE; s <<= 1) {
+        uint32_t t = __shfl_up(v, s, CMPQ_WAVE);
+        if (lane >= s) v += t;
+    }
+    return v;
+}
+
+// Exclusive scan of one value per thread over a block of up to 1024 threads.
+// `scratch` holds at least 17 uint32 in LDS.  Returns the exclusive prefix and
+// leaves the block total in *total.  Contains barriers: call from all threads.
+__device__ __forceinline__ uint32_t block_scan_excl_u32(uint32_t v, uint32_t *scratch,
+                                                        uint32_t *total) {
+    const int lane = threadIdx.x & (CMPQ_WAVE - 1), wave = threadIdx.x / CMPQ_WAVE;
+    const int nwave = (blockDim.x + CMPQ_WAVE - 1) / CMPQ_WAVE;
+    uint32_t incl = wave_scan_incl_u32(v);
+    __syncthreads();  // scratch may still be read from a previous call
+    if (lane == CMPQ_WAVE - 1) scratch[wave] = incl;
+    __syncthreads();
+    if (wave == 0) {
+        uint32_t w = lane < nwave ? scratch[lane] : 0;
+        uint32_t wi = wave_scan_incl_u32(w);
+        if (lane < nwave) scratch[lane] = wi - w;
+        if (lane == nwave - 1) scratch[16] = wi;
+    }
+    __syncthreads();
+    *total = scratch[16];
+    return scratch[wave] + incl - v;
+}
+
+// fp32 bit pattern -> unsigned key with the same order as the value.
+__device__ __forceinline__ uint32_t f32_ordered_key(float f) {
+    uint32_t u = __float_as_uint(f);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ __forceinline__ float f32_from_ordered_key(uint32_t k) {
+    uint32_t u = (k & 0x80000000u) ? (k & 0x7fffffffu) : ~k;
+    return __uint_as_float(u);
+}
+
+template <typename T>
+__device__ __forceinline__ float load_as_f32(const T *p, int64_t i);
+template <>
+__device__ __forceinline__ float load_as_f32<__half>(const __half *p, int64_t i) {
+    return __half2float(p[i]);
+}
+template <>
+__device__ __forceinline__ float load_as_f32<float>(const float *p, int64_t i) {
+    return p[i];
+}

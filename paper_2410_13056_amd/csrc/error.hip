@@ -1,0 +1,139 @@
+// cmpq_dequant_error: rebuilds W_hat = W_q + O (Sec. 3.2.2 of arXiv 2410.13056) on the
+// fly and measures the output error of App. B.3, Delta Y = X (W - W_hat), channel by
+// channel: err_ch[i] = sum_o (W[i,o] - W_hat[i,o])^2, weighted by the activation
+// statistic for the layer total.
+//
+// HBM bound: 2 (or 4) bytes of W and 1 byte of code per weight.  One workgroup per
+// channel; the slice of the outlier list that falls in the channel is expanded into
+// an LDS bitmap first, so the main loop is a plain streaming pass.  Sums are fp64
+// per lane, reduced in a fixed order.
+#include "common.h"
+
+namespace {
+
+constexpr int kT = 256;
+
+template <typename TW>
+__global__ __launch_bounds__(kT) void dequant_error_kernel(
+    const TW *__restrict__ W, int64_t d_out, int64_t ldw, const float *__restrict__ centroids,
+    const uint8_t *__restrict__ codes, const uint8_t *__restrict__ bits,
+    const int32_t *__restrict__ out_idx, int64_t n_out, double *__restrict__ err_ch) {
+    extern __shared__ uint32_t restored[];  // one bit per entry of the channel
+    __shared__ float lut[CMPQ_KMAX];
+    __shared__ double red[kT / CMPQ_WAVE];
+    __shared__ int seg[2];
+    const int64_t i = blockIdx.x;
+    const int tid = threadIdx.x;
+    const int b = bits[i];
+    const bool whole = b < 1 || b > 4;  // a channel of O_act: every entry restored
+    const int words = (int)((d_out + 31) / 32);
+    for (int w = tid; w < words; w += kT) restored[w] = 0;
+    if (tid < CMPQ_KMAX) lut[tid] = centroids[i * CMPQ_KMAX + tid];
+    if (tid == 0) {
+        const int64_t first = i * d_out, last = first + d_out;
+        int64_t lo = 0, hi = n_out;
+        while (lo < hi) {
+            const int64_t mid = (lo + hi) >> 1;
+            if (out_idx[mid] < first) lo = mid + 1; else hi = mid;
+        }
+        seg[0] = (int)lo;
+        hi = n_out;
+        while (lo < hi) {
+            const int64_t mid = (lo + hi) >> 1;
+            if (out_idx[mid] < last) lo = mid + 1; else hi = mid;
+        }
+        seg[1] = (int)lo;
+    }
+    __syncthreads();
+    for (int e = seg[0] + tid; e < seg[1]; e += kT) {
+        const int o = (int)(out_idx[e] - i * d_out);
+        atomicOr(&restored[o >> 5], 1u << (o & 31));
+    }
+    __syncthreads();
+    const TW *wrow = W + i * ldw;
+    const uint8_t *crow = codes + i * d_out;
+    double s = 0.0;
+    for (int64_t o = tid; o < d_out; o += kT) {
+        const float w = load_as_f32<TW>(wrow, o);
+        float what;
+        if (whole || ((restored[o >> 5] >> (o & 31)) & 1u))
+            what = __half2float(__float2half_rn(w));
+        else
+            what = lut[crow[o] & 15];
+        const double e = (double)w - (double)what;
+        s = fma(e, e, s);
+    }
+    s = wave_sum_f64(s);
+    if ((tid & 63) == 0) red[tid >> 6] = s;
+    __syncthreads();
+    if (tid == 0) {
+        double t = 0.0;
+        for (int w = 0; w < kT / CMPQ_WAVE; ++w) t += red[w];
+        err_ch[i] = t;
+    }
+}
+
+// totals[0] = sum_i sumsq[i]*err_ch[i], totals[1] = sum_i err_ch[i]; one workgroup,
+// fixed order.
+__global__ __launch_bounds__(1024) void error_totals_kernel(const double *__restrict__ err_ch,
+                                                            const float *__restrict__ sumsq,
+                                                            int64_t d_in,
+                                                            double *__restrict__ totals) {
+    __shared__ double red[2][16];
+    double tw = 0.0, tu = 0.0;
+    for (int64_t i = threadIdx.x; i < d_in; i += blockDim.x) {
+        const double e = err_ch[i];
+        tw = fma(sumsq ? (double)sumsq[i] : 1.0, e, tw);
+        tu += e;
+    }
+    tw = wave_sum_f64(tw);
+    tu = wave_sum_f64(tu);
+    if ((threadIdx.x & 63) == 0) {
+        red[0][threadIdx.x >> 6] = tw;
+        red[1][threadIdx.x >> 6] = tu;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double a = 0.0, c = 0.0;
+        for (int w = 0; w < 16; ++w) {
+            a += red[0][w];
+            c += red[1][w];
+        }
+        totals[0] = a;
+        totals[1] = c;
+    }
+}
+
+}  // namespace
+
+size_t cmpq_ws_dequant_error(int64_t) { return 256; }
+
+extern "C" int cmpq_dequant_error(const void *W, int dtype, int64_t d_in, int64_t d_out,
+                                  int64_t ldw, const float *centroids, const uint8_t *codes,
+                                  const uint8_t *bits, const int32_t *out_idx, int64_t n_out,
+                                  const float *sumsq, double *err_ch, double *err_total, void *ws,
+                                  size_t ws_bytes, void *stream) {
+    (void)ws;
+    (void)ws_bytes;
+    if (d_in < 0 || d_out < 0 || n_out < 0) return CMPQ_EINVAL;
+    if (dtype != CMPQ_F16 && dtype != CMPQ_F32) return CMPQ_EINVAL;
+    if (!bits || !centroids || !err_ch || !err_total || (n_out > 0 && !out_idx)) return CMPQ_EINVAL;
+    if (d_in > 0 && d_out > 0 && (!W || !codes)) return CMPQ_EINVAL;
+    if (ldw < d_out) return CMPQ_ESHAPE;
+    if (d_in > 0 && d_out > ((int64_t)1 << 31) / d_in) return CMPQ_ESHAPE;
+    if (d_out > 1 << 20) return CMPQ_ESHAPE;  // the per-channel bitmap lives in LDS
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (d_in > 0) {
+        const size_t lds = (size_t)cdiv(d_out > 0 ? d_out : 1, 32) * 4;
+        if (dtype == CMPQ_F16)
+            dequant_error_kernel<__half><<<(unsigned)d_in, kT, lds, s>>>(
+                static_cast<const __half *>(W), d_out, ldw, centroids, codes, bits, out_idx, n_out, err_ch);
+        else
+            dequant_error_kernel<float><<<(unsigned)d_in, kT, lds, s>>>(
+                static_cast<const float *>(W), d_out, ldw, centroids, codes, bits, out_idx, n_out, err_ch);
+        CMPQ_LAUNCH_CHECK();
+    }
+    error_totals_kernel<<<1, 1024, 0, s>>>(err_ch, sumsq, d_in, err_total);
+    CMPQ_LAUNCH_CHECK();
+    return CMPQ_OK;
+}

@@ -1,0 +1,126 @@
+"""Host driver of the CMPQ quantization path: the order of Sec. 3.2 of
+arXiv 2410.13056, one C-ABI call per step.  Nothing is computed here; the code
+allocates outputs, derives integer counts from shapes and chains the calls on the
+current stream without synchronising.
+"""
+from __future__ import annotations
+
+import dataclasses
+from typing import Dict, List, Optional, Sequence
+
+import torch
+
+from . import binding as B
+
+
+@dataclasses.dataclass
+class LayerResult:
+    """Everything the path produces for one linear layer (device tensors)."""
+    d_in: int
+    d_out: int
+    bit_set: Sequence[int]
+    counts: List[int]                 # channels per width
+    sumsq: torch.Tensor               # [d_in] fp32 activation statistic
+    act_idx: torch.Tensor             # [k_act] int32: channels of O_act
+    chan_mask: torch.Tensor           # [d_in] uint8
+    bits: torch.Tensor                # [d_in] uint8 (16 = O_act channel)
+    centroids: torch.Tensor           # [d_in,16] fp32 levels of the final quantizer
+    codes: torch.Tensor               # [d_in,d_out] uint8
+    out_idx: torch.Tensor             # [k_q] int32 linear indices i*d_out+o of O_q
+    out_val: torch.Tensor             # [k_q] fp16 values of O_q
+    packed: List[Optional[torch.Tensor]]    # per width: [rows, ceil(d_out*b/32)] int32 words
+    chan_idx: List[Optional[torch.Tensor]]  # per width: [rows] int32
+    lut: List[Optional[torch.Tensor]]       # per width: [rows, 2^b] fp16
+    centroids_prelim: Optional[torch.Tensor] = None
+    codes_prelim: Optional[torch.Tensor] = None
+    err_ch: Optional[torch.Tensor] = None
+    err_total: Optional[torch.Tensor] = None
+    W_t: Optional[torch.Tensor] = None      # the d_in x d_out copy the steps ran on
+
+
+def activation_stats(X: torch.Tensor, ws: B.Workspace, acc: Optional[torch.Tensor] = None,
+                     status: Optional[torch.Tensor] = None):
+    """Sec. 3.2.1: per-channel sum of squares of X [n, d_in]; pass `acc` to add more tokens."""
+    d_in = X.shape[1]
+    first = acc is None
+    if first:
+        acc = torch.empty(d_in, dtype=torch.float64, device=X.device)
+    sumsq = torch.empty(d_in, dtype=torch.float32, device=X.device)
+    B.act_stats(X, acc, sumsq, not first, ws, status)
+    return acc, sumsq
+
+
+def quantize_layer(W: torch.Tensor, sumsq: torch.Tensor, bit_set: Sequence[int], avg_bits: float,
+                   rho_act_ppm: int = 4500, rho_q_ppm: int = 500, iters: int = 20,
+                   ws: Optional[B.Workspace] = None, score: int = B.SCORE_RESIDUAL,
+                   with_error: bool = False, keep_prelim: bool = False,
+                   status: Optional[torch.Tensor] = None, transposed: bool = False) -> LayerResult:
+    """Quantizes one layer.  `W` is the framework's [d_out, d_in] weight (or already
+    d_in x d_out with ``transposed=True``); `sumsq` comes from `activation_stats`."""
+    ws = ws or B.Workspace(W.device)
+    dev = W.device
+    if transposed:
+        Wt = W
+        d_in, d_out = W.shape
+    else:
+        d_out, d_in = W.shape
+        Wt = torch.empty((d_in, d_out), dtype=W.dtype, device=dev)
+        B.transpose(W, Wt)
+    # O_act (Sec. 3.2.2)
+    k_act = B.count_ppm(rho_act_ppm, d_in)
+    act_idx = torch.empty(k_act, dtype=torch.int32, device=dev)
+    chan_mask = torch.empty(d_in, dtype=torch.uint8, device=dev)
+    B.extract_channel_outliers(sumsq, k_act, act_idx, chan_mask, ws)
+    # Algorithm 1 on W' = W - O_act
+    bits = torch.empty(d_in, dtype=torch.uint8, device=dev)
+    counts = B.allocate_bits(sumsq, chan_mask, k_act, bit_set, avg_bits, bits, ws)
+    # preliminary quantization W'_q
+    cent1 = torch.empty((d_in, B.KMAX), dtype=torch.float32, device=dev)
+    codes1 = torch.empty((d_in, d_out), dtype=torch.uint8, device=dev)
+    B.kmeans_quantize(Wt, bits, None, 0, None, iters, cent1, codes1, ws, status)
+    # O_q: largest |W' - W'_q|
+    k_q = B.count_ppm(rho_q_ppm, d_in * d_out)
+    out_idx = torch.empty(k_q, dtype=torch.int32, device=dev)
+    out_val = torch.empty(k_q, dtype=torch.float16, device=dev)
+    B.extract_weight_outliers(Wt, cent1, codes1, bits, k_q, out_idx, out_val, ws, score)
+    # final quantization of W - O
+    cent = torch.empty((d_in, B.KMAX), dtype=torch.float32, device=dev)
+    codes = torch.empty((d_in, d_out), dtype=torch.uint8, device=dev)
+    B.kmeans_quantize(Wt, bits, out_idx, k_q, None, iters, cent, codes, ws, status)
+    # stored format
+    packed, chan_idx, lut = [], [], []
+    for b, c in zip(bit_set, counts):
+        if c == 0:
+            packed.append(None), chan_idx.append(None), lut.append(None)
+            continue
+        packed.append(torch.empty((c, (d_out * b + 31) // 32), dtype=torch.int32, device=dev))
+        chan_idx.append(torch.empty(c, dtype=torch.int32, device=dev))
+        lut.append(torch.empty((c, 1 << b), dtype=torch.float16, device=dev))
+    B.pack(codes, bits, cent, bit_set, counts, packed, chan_idx, lut, ws)
+    res = LayerResult(d_in, d_out, tuple(bit_set), counts, sumsq, act_idx, chan_mask, bits, cent, codes,
+                      out_idx, out_val, packed, chan_idx, lut, W_t=Wt)
+    if keep_prelim:
+        res.centroids_prelim, res.codes_prelim = cent1, codes1
+    if with_error:
+        res.err_ch = torch.empty(d_in, dtype=torch.float64, device=dev)
+        res.err_total = torch.empty(2, dtype=torch.float64, device=dev)
+        B.dequant_error(Wt, cent, codes, bits, out_idx, k_q, sumsq, res.err_ch, res.err_total, ws)
+    return res
+
+
+def quantize_block(weights: Dict[str, torch.Tensor], acts: Dict[str, torch.Tensor], layers, bit_set,
+                   avg_bits: float, rho_act_ppm: int, rho_q_ppm: int, iters: int,
+                   ws: Optional[B.Workspace] = None, with_error: bool = False,
+                   status: Optional[torch.Tensor] = None) -> Dict[str, LayerResult]:
+    """One pass of the whole path over a decoder block: statistics once per distinct
+    input, then every linear layer.  `layers` lists (name, x_key) pairs."""
+    some = next(iter(weights.values()))
+    ws = ws or B.Workspace(some.device)
+    stats = {}
+    out = {}
+    for name, x_key in layers:
+        if x_key not in stats:
+            stats[x_key] = activation_stats(acts[x_key], ws, status=status)[1]
+        out[name] = quantize_layer(weights[name], stats[x_key], bit_set, avg_bits, rho_act_ppm,
+                                   rho_q_ppm, iters, ws, with_error=with_error, status=status)
+    return out
