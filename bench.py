@@ -1,0 +1,141 @@
+#!/usr/bin/env python3
+"""Throughput of the CMPQ quantization path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload block70b]
+
+A step is one pass of the whole path over one decoder block (or layer) of synthetic
+input already resident in HBM: activation statistics for every distinct input, then for
+each linear layer the orientation copy, O_act, Algorithm 1, preliminary k-means, O_q,
+final k-means, packing and the reconstruction error.  Prints ONE JSON line:
+Mparams/s, the roofline figures of the dominant kernel (k-means, measured with events
+on the launch stream inside the timed steps) and the CPU oracle timed on a bounded
+sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+# MI355X: 256 compute units x 64 lanes x 2.4 GHz, one plain fp32 result (compare, add,
+# select) per lane and clock.  The datasheet's 157.3 TFLOP/s counts an FMA as two and a
+# packed pair as two more; a compare is neither.
+ALU_PEAK_TFLOPS = 256 * 64 * 2.4e9 / 1e12
+HBM_PEAK_GBS = 8000.0
+
+
+def credited_kmeans_flops(result, iters):
+    """Per weight and Lloyd round: K-1 nearest-level compares and 2 accumulations; the
+    final coding K-1 compares.  Summed over the channels that are quantized."""
+    total = 0
+    for b, c in zip(result.bit_set, result.counts):
+        K = 1 << b
+        total += c * result.d_out * (iters * (K + 1) + (K - 1))
+    return total
+
+
+def cpu_baseline(wl, weights, acts):
+    """The oracle, as it stands, on a bounded sample: the first layer cut to as many input
+    channels as keep the run to roughly 10-30 s, and 2048 calibration tokens."""
+    import numpy as np
+    import oracle
+    oracle.build()
+    layer = wl.layers[0]
+    target_params = 24_000_000 if len(wl.layers) > 1 else 16_800_000
+    ch = max(8, min(layer.d_in, target_params // layer.d_out))
+    tok = min(2048, wl.x_shapes[layer.x_key][0])
+    W = weights[layer.name][:, :ch].t().contiguous().cpu().numpy()          # [ch, d_out]
+    X = acts[layer.x_key][:tok, :ch].contiguous().cpu().numpy()
+    t0 = time.perf_counter()
+    oracle.quantize_layer(W, X, wl.bit_set, wl.avg_bits, wl.rho_act_ppm, wl.rho_q_ppm, wl.iters)
+    dt = time.perf_counter() - t0
+    return {"value": ch * layer.d_out / dt / 1e6, "unit": "Mparams/s", "cores": oracle.num_threads(),
+            "kind": "oracle", "seconds": round(dt, 2),
+            "sample": f"{layer.name} cut to its first {ch} of {layer.d_in} input channels "
+                      f"({ch}x{layer.d_out} weights), {tok} of {wl.x_shapes[layer.x_key][0]} tokens, "
+                      f"whole path incl. both k-means passes"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="block70b",
+                    help="block70b (default, the headline target), block13b, block7b, q7b, tiny")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU; every box here has one, and the path needs no "
+              "collective (layers are independent).  Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2410_13056_amd import binding as B, pipeline as P, synth
+    B.lib()                                       # no library, no benchmark
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    wl = synth.workload(args.workload)
+    weights, acts = synth.materialize(wl, dev)
+    layers = [(l.name, l.x_key) for l in wl.layers]
+    ws = B.Workspace(dev)
+    status = torch.zeros(1, dtype=torch.int32, device=dev)
+
+    def step(timer=None):
+        return P.quantize_block(weights, acts, layers, wl.bit_set, wl.avg_bits, wl.rho_act_ppm,
+                                wl.rho_q_ppm, wl.iters, ws, with_error=True, status=status, timer=timer)
+
+    for _ in range(args.warmup):
+        out = step()
+        del out
+    torch.cuda.synchronize()
+    timer = P.StageTimer()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        out = step(timer)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    assert status.item() == 0, "non-finite input flagged"
+
+    stages = timer.totals()
+    flops = sum(credited_kmeans_flops(r, wl.iters) for r in out.values()) * 2      # two passes per layer
+    n_km, ms_km = stages["kmeans"]
+    launches_per_step = n_km // args.steps
+    avg_launch_s = ms_km / 1e3 / n_km
+    achieved = flops / launches_per_step / avg_launch_s / 1e12
+    x_bytes = sum(acts[k].numel() * acts[k].element_size() for k in acts)
+    n_st, ms_st = stages["act_stats"]
+    line = {
+        "metric": "Mparams/s quantized (whole CMPQ path, both k-means passes) at the target average bits",
+        "value": wl.params * args.steps / dt / 1e6,
+        "unit": "Mparams/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": dt / args.steps * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32 compares, f64 sums" if wl.dtype == "f16" else "f32 compares, f64 sums (f32 weights)",
+        "data": "synthetic",
+        "config": {"workload": wl.name, "params": wl.params, "layers": len(wl.layers),
+                   "weights": wl.dtype, "bit_set": list(wl.bit_set), "avg_bits": wl.avg_bits,
+                   "rho_act_ppm": wl.rho_act_ppm, "rho_q_ppm": wl.rho_q_ppm, "iters": wl.iters,
+                   "tokens": {k: v[0] for k, v in wl.x_shapes.items()}},
+        "roofline": {"kernel": "kmeans_kernel", "bound": "alu", "achieved": achieved,
+                     "peak": ALU_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": achieved / ALU_PEAK_TFLOPS,
+                     "traffic": None, "launches_per_step": launches_per_step,
+                     "avg_launch_ms": avg_launch_s * 1e3, "credited_flop_per_launch": flops / launches_per_step},
+        "stages_ms_per_step": {k: round(v[1] / args.steps, 4) for k, v in sorted(stages.items())},
+        "act_stats_hbm": {"achieved_GBs": x_bytes * args.steps / (ms_st / 1e3) / 1e9, "peak_GBs": HBM_PEAK_GBS,
+                          "frac": x_bytes * args.steps / (ms_st / 1e3) / 1e9 / HBM_PEAK_GBS},
+    }
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(wl, weights, acts)
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

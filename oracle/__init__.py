@@ -74,6 +74,10 @@ def count_ppm(ppm: int, n: int) -> int:
     return int(lib().orc_count_ppm(int(ppm), int(n)))
 
 
+def num_threads() -> int:
+    return int(lib().orc_num_threads())
+
+
 def f32_to_f16_bits(x: float) -> int:
     return int(lib().orc_f32_to_f16(ctypes.c_float(x)))
 

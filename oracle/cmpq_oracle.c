@@ -26,6 +26,9 @@
  * and brute force on small cases.
  */
 #include <math.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
@@ -482,6 +485,15 @@ int orc_dequant_error(const void *W, int dtype, int64_t d_in, int64_t d_out, int
     }
     free(excl);
     return 0;
+}
+
+/* Threads the "parallel for" loops above will use (reported beside oracle timings). */
+int orc_num_threads(void) {
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
 }
 
 /* Counts are integers derived from parts-per-million fractions, rounding half up. */

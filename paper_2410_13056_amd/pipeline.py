@@ -5,12 +5,37 @@ current stream without synchronising.
 """
 from __future__ import annotations
 
+import contextlib
 import dataclasses
 from typing import Dict, List, Optional, Sequence
 
 import torch
 
 from . import binding as B
+
+
+class StageTimer:
+    """Brackets each C-ABI call with a pair of events on the stream the call is
+    enqueued on; `totals()` returns {stage: (calls, milliseconds)} once they ran."""
+
+    def __init__(self):
+        self.pairs: Dict[str, list] = {}
+
+    @contextlib.contextmanager
+    def stage(self, name: str):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        yield
+        b.record()
+        self.pairs.setdefault(name, []).append((a, b))
+
+    def totals(self) -> Dict[str, tuple]:
+        torch.cuda.synchronize()
+        return {k: (len(v), sum(a.elapsed_time(b) for a, b in v)) for k, v in self.pairs.items()}
+
+
+def _stage(timer: Optional[StageTimer], name: str):
+    return timer.stage(name) if timer is not None else contextlib.nullcontext()
 
 
 @dataclasses.dataclass
@@ -39,14 +64,15 @@ class LayerResult:
 
 
 def activation_stats(X: torch.Tensor, ws: B.Workspace, acc: Optional[torch.Tensor] = None,
-                     status: Optional[torch.Tensor] = None):
+                     status: Optional[torch.Tensor] = None, timer: Optional[StageTimer] = None):
     """Sec. 3.2.1: per-channel sum of squares of X [n, d_in]; pass `acc` to add more tokens."""
     d_in = X.shape[1]
     first = acc is None
     if first:
         acc = torch.empty(d_in, dtype=torch.float64, device=X.device)
     sumsq = torch.empty(d_in, dtype=torch.float32, device=X.device)
-    B.act_stats(X, acc, sumsq, not first, ws, status)
+    with _stage(timer, "act_stats"):
+        B.act_stats(X, acc, sumsq, not first, ws, status)
     return acc, sumsq
 
 
@@ -54,7 +80,8 @@ def quantize_layer(W: torch.Tensor, sumsq: torch.Tensor, bit_set: Sequence[int],
                    rho_act_ppm: int = 4500, rho_q_ppm: int = 500, iters: int = 20,
                    ws: Optional[B.Workspace] = None, score: int = B.SCORE_RESIDUAL,
                    with_error: bool = False, keep_prelim: bool = False,
-                   status: Optional[torch.Tensor] = None, transposed: bool = False) -> LayerResult:
+                   status: Optional[torch.Tensor] = None, transposed: bool = False,
+                   timer: Optional[StageTimer] = None) -> LayerResult:
     """Quantizes one layer.  `W` is the framework's [d_out, d_in] weight (or already
     d_in x d_out with ``transposed=True``); `sumsq` comes from `activation_stats`."""
     ws = ws or B.Workspace(W.device)
@@ -65,28 +92,34 @@ def quantize_layer(W: torch.Tensor, sumsq: torch.Tensor, bit_set: Sequence[int],
     else:
         d_out, d_in = W.shape
         Wt = torch.empty((d_in, d_out), dtype=W.dtype, device=dev)
-        B.transpose(W, Wt)
+        with _stage(timer, "transpose"):
+            B.transpose(W, Wt)
     # O_act (Sec. 3.2.2)
     k_act = B.count_ppm(rho_act_ppm, d_in)
     act_idx = torch.empty(k_act, dtype=torch.int32, device=dev)
     chan_mask = torch.empty(d_in, dtype=torch.uint8, device=dev)
-    B.extract_channel_outliers(sumsq, k_act, act_idx, chan_mask, ws)
+    with _stage(timer, "outlier_channels"):
+        B.extract_channel_outliers(sumsq, k_act, act_idx, chan_mask, ws)
     # Algorithm 1 on W' = W - O_act
     bits = torch.empty(d_in, dtype=torch.uint8, device=dev)
-    counts = B.allocate_bits(sumsq, chan_mask, k_act, bit_set, avg_bits, bits, ws)
+    with _stage(timer, "allocate_bits"):
+        counts = B.allocate_bits(sumsq, chan_mask, k_act, bit_set, avg_bits, bits, ws)
     # preliminary quantization W'_q
     cent1 = torch.empty((d_in, B.KMAX), dtype=torch.float32, device=dev)
     codes1 = torch.empty((d_in, d_out), dtype=torch.uint8, device=dev)
-    B.kmeans_quantize(Wt, bits, None, 0, None, iters, cent1, codes1, ws, status)
+    with _stage(timer, "kmeans"):
+        B.kmeans_quantize(Wt, bits, None, 0, None, iters, cent1, codes1, ws, status)
     # O_q: largest |W' - W'_q|
     k_q = B.count_ppm(rho_q_ppm, d_in * d_out)
     out_idx = torch.empty(k_q, dtype=torch.int32, device=dev)
     out_val = torch.empty(k_q, dtype=torch.float16, device=dev)
-    B.extract_weight_outliers(Wt, cent1, codes1, bits, k_q, out_idx, out_val, ws, score)
+    with _stage(timer, "outlier_weights"):
+        B.extract_weight_outliers(Wt, cent1, codes1, bits, k_q, out_idx, out_val, ws, score)
     # final quantization of W - O
     cent = torch.empty((d_in, B.KMAX), dtype=torch.float32, device=dev)
     codes = torch.empty((d_in, d_out), dtype=torch.uint8, device=dev)
-    B.kmeans_quantize(Wt, bits, out_idx, k_q, None, iters, cent, codes, ws, status)
+    with _stage(timer, "kmeans"):
+        B.kmeans_quantize(Wt, bits, out_idx, k_q, None, iters, cent, codes, ws, status)
     # stored format
     packed, chan_idx, lut = [], [], []
     for b, c in zip(bit_set, counts):
@@ -96,7 +129,8 @@ def quantize_layer(W: torch.Tensor, sumsq: torch.Tensor, bit_set: Sequence[int],
         packed.append(torch.empty((c, (d_out * b + 31) // 32), dtype=torch.int32, device=dev))
         chan_idx.append(torch.empty(c, dtype=torch.int32, device=dev))
         lut.append(torch.empty((c, 1 << b), dtype=torch.float16, device=dev))
-    B.pack(codes, bits, cent, bit_set, counts, packed, chan_idx, lut, ws)
+    with _stage(timer, "pack"):
+        B.pack(codes, bits, cent, bit_set, counts, packed, chan_idx, lut, ws)
     res = LayerResult(d_in, d_out, tuple(bit_set), counts, sumsq, act_idx, chan_mask, bits, cent, codes,
                       out_idx, out_val, packed, chan_idx, lut, W_t=Wt)
     if keep_prelim:
@@ -104,14 +138,16 @@ def quantize_layer(W: torch.Tensor, sumsq: torch.Tensor, bit_set: Sequence[int],
     if with_error:
         res.err_ch = torch.empty(d_in, dtype=torch.float64, device=dev)
         res.err_total = torch.empty(2, dtype=torch.float64, device=dev)
-        B.dequant_error(Wt, cent, codes, bits, out_idx, k_q, sumsq, res.err_ch, res.err_total, ws)
+        with _stage(timer, "dequant_error"):
+            B.dequant_error(Wt, cent, codes, bits, out_idx, k_q, sumsq, res.err_ch, res.err_total, ws)
     return res
 
 
 def quantize_block(weights: Dict[str, torch.Tensor], acts: Dict[str, torch.Tensor], layers, bit_set,
                    avg_bits: float, rho_act_ppm: int, rho_q_ppm: int, iters: int,
                    ws: Optional[B.Workspace] = None, with_error: bool = False,
-                   status: Optional[torch.Tensor] = None) -> Dict[str, LayerResult]:
+                   status: Optional[torch.Tensor] = None,
+                   timer: Optional[StageTimer] = None) -> Dict[str, LayerResult]:
     """One pass of the whole path over a decoder block: statistics once per distinct
     input, then every linear layer.  `layers` lists (name, x_key) pairs."""
     some = next(iter(weights.values()))
@@ -120,7 +156,8 @@ def quantize_block(weights: Dict[str, torch.Tensor], acts: Dict[str, torch.Tenso
     out = {}
     for name, x_key in layers:
         if x_key not in stats:
-            stats[x_key] = activation_stats(acts[x_key], ws, status=status)[1]
+            stats[x_key] = activation_stats(acts[x_key], ws, status=status, timer=timer)[1]
         out[name] = quantize_layer(weights[name], stats[x_key], bit_set, avg_bits, rho_act_ppm,
-                                   rho_q_ppm, iters, ws, with_error=with_error, status=status)
+                                   rho_q_ppm, iters, ws, with_error=with_error, status=status,
+                                   timer=timer)
     return out

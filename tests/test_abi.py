@@ -1,0 +1,114 @@
+"""The C-ABI library loads, exports every symbol include/cmpq.h declares, and rejects bad
+arguments on the host before anything is launched (so none of this needs a GPU)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "cmpq.h")
+
+
+@pytest.fixture(scope="module")
+def L():
+    from paper_2410_13056_amd import binding
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2410_13056_amd import build
+        build.build()
+    return binding.lib()
+
+
+def _declared():
+    text = re.sub(r"/\*.*?\*/", "", open(HEADER).read(), flags=re.S)
+    return sorted(set(re.findall(r"\b(cmpq_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(L):
+    names = _declared()
+    assert {"cmpq_act_stats", "cmpq_allocate_bits", "cmpq_extract_outliers", "cmpq_kmeans_quantize",
+            "cmpq_pack", "cmpq_dequant_error"} <= set(names)
+    for n in names:
+        assert getattr(L, n) is not None
+    from paper_2410_13056_amd import binding
+    assert set(binding.EXPORTS) == set(names)
+
+
+def test_header_is_plain_c():
+    src = os.path.join(ROOT, "tests", "_hdr_check.c")
+    with open(src, "w") as f:
+        f.write('#include "cmpq.h"\nint main(void){return CMPQ_OK;}\n')
+    try:
+        assert os.system(f"gcc -std=c99 -pedantic -Wall -Werror -I{ROOT}/include -fsyntax-only {src}") == 0
+    finally:
+        os.remove(src)
+
+
+def test_counts_and_messages(L):
+    from paper_2410_13056_amd import binding as B
+    assert B.count_ppm(4500, 4096) == 18 and B.count_ppm(500, 4096 * 4096) == 8389
+    assert B.count_ppm(10000, 28672 * 8192) == 2348810
+    assert B.count_ppm(4500, 111) == 0 and B.count_ppm(4500, 112) == 1      # half rounds up
+    for code in range(0, -7, -1):
+        assert B.strerror(code) and "unknown cmpq" not in B.strerror(code)
+    assert "unknown cmpq" in B.strerror(-99)
+    for op in range(7):
+        assert B.workspace_bytes(op, 4096, 4096, 1000) % 256 == 0
+        assert B.workspace_bytes(op, 4096, 4096, 1000) >= 256
+    assert B.workspace_bytes(99, 1, 1, 1) == 0
+
+
+def test_host_side_argument_errors(L):
+    from paper_2410_13056_amd import binding as B
+    i32, i64 = ctypes.c_int32, ctypes.c_int64
+    fake = ctypes.c_void_p(256)          # never dereferenced: every call below fails on the host
+    bs = (i32 * 3)(2, 3, 4)
+    # null pointers / bad enums
+    assert L.cmpq_act_stats(fake, 0, 4, 8, 8, None, None, 0, fake, 1 << 20, None, None) == -1
+    assert L.cmpq_act_stats(fake, 7, 4, 8, 8, fake, None, 0, fake, 1 << 20, None, None) == -1
+    assert L.cmpq_act_stats(fake, 0, 4, 8, 4, fake, None, 0, fake, 1 << 20, None, None) == -2   # ldx < d_in
+    assert L.cmpq_act_stats(fake, 0, 4, 8, 8, fake, None, 0, None, 0, None, None) == -5          # no workspace
+    assert L.cmpq_act_stats(fake, 0, 4, 8, 8, fake, None, 0, ctypes.c_void_p(257), 1 << 20, None, None) == -5
+    assert L.cmpq_transpose(None, 0, 4, 4, 4, fake, 4, None) == -1
+    assert L.cmpq_transpose(fake, 0, 4, 4, 3, fake, 4, None) == -2
+    # budget errors
+    cnt = (i64 * 3)()
+    assert L.cmpq_allocate_bits(fake, 16, None, 0, bs, 3, ctypes.c_double(4.5), fake, cnt, fake, 256, None) == -3
+    assert L.cmpq_allocate_bits(fake, 16, None, 0, bs, 3, ctypes.c_double(1.5), fake, cnt, fake, 256, None) == -3
+    assert L.cmpq_allocate_bits(fake, 16, None, 0, (i32 * 2)(2, 4), 2, ctypes.c_double(3.0), fake, cnt, fake, 256, None) == -3
+    assert L.cmpq_allocate_bits(fake, 16, None, 0, (i32 * 2)(4, 5), 2, ctypes.c_double(4.0), fake, cnt, fake, 256, None) == -3
+    assert L.cmpq_allocate_bits(fake, 16, None, 3, bs, 3, ctypes.c_double(3.0), fake, cnt, fake, 256, None) == -1
+    # outliers
+    assert L.cmpq_extract_outliers(0, 0, fake, None, 0, 16, 0, 0, None, None, None, 17, fake, None, None, fake, 256, None) == -4
+    assert L.cmpq_extract_outliers(1, 0, None, fake, 0, 4, 4, 4, fake, fake, fake, 17, fake, None, None, fake, 1 << 20, None) == -4
+    assert L.cmpq_extract_outliers(1, 0, None, fake, 0, 4, 4, 4, None, fake, fake, 1, fake, None, None, fake, 1 << 20, None) == -1
+    assert L.cmpq_extract_outliers(1, 0, None, fake, 0, 4, 4, 4, fake, fake, fake, 1, fake, None, None, fake, 16, None) == -5
+    assert L.cmpq_extract_outliers(5, 0, None, fake, 0, 4, 4, 4, fake, fake, fake, 1, fake, None, None, fake, 1 << 20, None) == -1
+    assert L.cmpq_extract_outliers(1, 0, None, fake, 0, 1 << 20, 1 << 20, 1 << 20, fake, fake, fake, 1, fake, None, None, fake, 1 << 20, None) == -2
+    # k-means
+    assert L.cmpq_kmeans_quantize(fake, 0, 4, 40000, 40000, fake, None, 0, None, 5, 0, fake, fake, fake, 256, None, None) == -2
+    assert L.cmpq_kmeans_quantize(fake, 1, 4, 20000, 20000, fake, None, 0, None, 5, 0, fake, fake, fake, 256, None, None) == -2
+    assert L.cmpq_kmeans_quantize(fake, 0, 4, 64, 64, fake, None, 0, None, -1, 0, fake, fake, fake, 256, None, None) == -1
+    assert L.cmpq_kmeans_quantize(fake, 0, 4, 64, 64, fake, None, 0, None, 5, 3, fake, fake, fake, 256, None, None) == -1
+    assert L.cmpq_kmeans_quantize(fake, 0, 4, 64, 64, fake, None, 2, None, 5, 0, fake, fake, fake, 256, None, None) == -1
+    assert L.cmpq_kmeans_quantize(fake, 0, 4, 64, 32, fake, None, 0, None, 5, 0, fake, fake, fake, 256, None, None) == -2
+    # pack / error
+    ptrs = (ctypes.c_void_p * 3)(256, 256, 256)
+    assert L.cmpq_pack(fake, 4, 64, fake, fake, bs, 3, None, ptrs, ptrs, ptrs, fake, 256, None) == -1
+    assert L.cmpq_pack(fake, 4, 64, fake, fake, (i32 * 2)(3, 2), 2, cnt, ptrs, ptrs, ptrs, fake, 256, None) == -3
+    cnt2 = (i64 * 3)(1, 1, 2)
+    assert L.cmpq_pack(fake, 4, 64, fake, fake, bs, 3, cnt2, ptrs, ptrs, ptrs, None, 0, None) == -5
+    assert L.cmpq_dequant_error(fake, 0, 4, 64, 64, fake, fake, fake, None, 0, None, None, fake, fake, 256, None) == -1
+    assert L.cmpq_dequant_error(fake, 0, 4, 64, 8, fake, fake, fake, None, 0, None, fake, fake, fake, 256, None) == -2
+
+
+def test_product_package_does_not_reach_the_oracle():
+    """The HIP path must stand alone: no file of the package mentions the oracle."""
+    pkg = os.path.join(ROOT, "paper_2410_13056_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "import oracle" not in text and "from oracle" not in text and "orc_" not in text, f
+    src = open(os.path.join(ROOT, "oracle", "__init__.py")).read() + open(os.path.join(ROOT, "oracle", "cmpq_oracle.c")).read()
+    assert "paper_2410_13056_amd" not in src and "cmpq.h" not in src

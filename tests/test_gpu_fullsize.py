@@ -1,0 +1,153 @@
+"""Parity at the full sizes of the named configurations, in the launch configuration
+bench.py times.  Where the oracle can afford the whole layer (the 4096x4096 layer) every
+output is compared; for the 70B-shaped layers the oracle recomputes sampled channels one by
+one and the global selections are checked through properties that hold at any size."""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda"
+
+
+@pytest.fixture(scope="module")
+def env(orc):
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2410_13056_amd import binding as B, pipeline as P, synth
+    B.lib()
+    return dict(B=B, P=P, synth=synth, ws=B.Workspace(DEV), orc=orc)
+
+
+def _np(t):
+    return t.detach().cpu().numpy()
+
+
+def _sampled_stats_check(env, X, sumsq, n_cols=48, seed=0):
+    cols = np.sort(np.random.default_rng(seed).choice(X.shape[1], n_cols, replace=False))
+    sub = _np(X[:, torch.from_numpy(cols).to(DEV)].contiguous())
+    _, osum = env["orc"].act_stats(sub)
+    assert np.array_equal(_np(sumsq)[cols], osum)
+
+
+def test_q7b_layer_full_size(env):
+    """4096x4096 fp16 layer, 262144 tokens, bits {2,3,4} avg 3.0, 0.5 % weight outliers, 20 rounds."""
+    P, synth, ws, orc = env["P"], env["synth"], env["ws"], env["orc"]
+    wl = synth.workload("q7b")
+    wts, xs = synth.materialize(wl, DEV)
+    W, X = wts["q_proj"], xs["x"]
+    assert X.shape == (262144, 4096)
+    status = torch.zeros(1, dtype=torch.int32, device=DEV)
+    _, sumsq = P.activation_stats(X, ws, status=status)
+    _sampled_stats_check(env, X, sumsq)
+    del X, xs
+    r = P.quantize_layer(W, sumsq, wl.bit_set, wl.avg_bits, wl.rho_act_ppm, wl.rho_q_ppm, wl.iters, ws,
+                         with_error=True, keep_prelim=True, status=status)
+    o = orc.quantize_layer(_np(W).T.copy(), None, wl.bit_set, wl.avg_bits, wl.rho_act_ppm, wl.rho_q_ppm,
+                           wl.iters, sumsq=_np(sumsq))
+    assert status.item() == 0
+    assert r.counts == list(o["counts"]) and np.array_equal(_np(r.bits), o["bits"])
+    assert np.array_equal(_np(r.act_idx), o["act_idx"])
+    assert np.array_equal(_np(r.centroids_prelim), o["cent1"])
+    assert np.array_equal(_np(r.codes_prelim), o["codes1"])
+    assert len(o["out_idx"]) == 83886
+    assert np.array_equal(_np(r.out_idx).astype(np.int64), o["out_idx"])
+    assert np.array_equal(_np(r.out_val).view(np.uint16), o["out_val"])
+    assert np.array_equal(_np(r.centroids), o["centroids"])      # bar 1e-5 relative; identical in fact
+    assert np.array_equal(_np(r.codes), o["codes"])
+    for j, b in enumerate(wl.bit_set):
+        opk, och, olut = o["packs"][b]
+        assert np.array_equal(_np(r.packed[j]).view(np.uint32), opk)
+        assert np.array_equal(_np(r.chan_idx[j]), och)
+        assert np.array_equal(_np(r.lut[j]).view(np.uint16), olut)
+    tot = _np(r.err_total)
+    assert abs(tot[0] - o["totals"][0]) <= 1e-4 * o["totals"][0]
+
+
+def _selection_properties(Wt, cent1, codes1, bits, out_idx, out_val, k):
+    """What makes the top-k set unique: size, order, membership, threshold, tie rule."""
+    d_in, d_out = Wt.shape
+    live = (bits >= 1) & (bits <= 4)
+    key = (Wt.float() - torch.gather(cent1, 1, codes1.long())).abs()
+    key[~live] = -1.0                                            # O_act channels are no candidates
+    key = key.reshape(-1)
+    idx = out_idx.long()
+    assert idx.numel() == k
+    assert bool((idx[1:] > idx[:-1]).all())                      # ascending, no repeats
+    assert bool((key[idx] >= 0).all())
+    assert torch.equal(out_val, Wt.reshape(-1)[idx].half())
+    T = key[idx].min()
+    sel = torch.zeros_like(key, dtype=torch.bool)
+    sel[idx] = True
+    assert bool((key[~sel] <= T).all())                          # nothing larger was left behind
+    tie_in = torch.nonzero(sel & (key == T)).flatten()
+    tie_out = torch.nonzero(~sel & (key == T)).flatten()
+    if tie_in.numel() and tie_out.numel():
+        assert int(tie_in.max()) < int(tie_out.min())            # equal scores: smaller index first
+
+
+@pytest.mark.parametrize("layer", ["gate_proj", "down_proj", "k_proj"])
+def test_block70b_layers_full_size(env, layer):
+    """70B-shaped layers at full size (8192->28672, 28672->8192, 8192->1024), bits {2,3,4} avg 3.5,
+    1 % weight outliers, 20 rounds."""
+    P, synth, ws, orc, B = env["P"], env["synth"], env["ws"], env["orc"], env["B"]
+    wl = synth.workload("block70b")
+    spec = next(l for l in wl.layers if l.name == layer)
+    j = wl.layers.index(spec)
+    W = synth.make_weight(spec.d_out, spec.d_in, wl.dtype, seed=wl.seed * 1000 + j, device=DEV)
+    n_tok = wl.x_shapes[spec.x_key][0]
+    X = synth.make_activations(n_tok, spec.d_in, wl.dtype, seed=77, device=DEV, hot_frac=wl.hot_frac,
+                               hot_scale=wl.hot_scale, gated=wl.x_gated[spec.x_key])
+    status = torch.zeros(1, dtype=torch.int32, device=DEV)
+    _, sumsq = P.activation_stats(X, ws, status=status)
+    _sampled_stats_check(env, X, sumsq, n_cols=24)
+    del X
+    r = P.quantize_layer(W, sumsq, wl.bit_set, wl.avg_bits, wl.rho_act_ppm, wl.rho_q_ppm, wl.iters, ws,
+                         with_error=True, keep_prelim=True, status=status)
+    torch.cuda.synchronize()
+    assert status.item() == 0
+    d_in, d_out = spec.d_in, spec.d_out
+    assert torch.equal(r.W_t, W.t().contiguous())
+    # rankings over d_in keys: the oracle does them whole
+    s = _np(sumsq)
+    oact, omask = orc.top_channels(s, B.count_ppm(wl.rho_act_ppm, d_in))
+    obits, ocounts = orc.allocate_bits(s, omask, wl.bit_set, wl.avg_bits)
+    assert np.array_equal(_np(r.act_idx), oact) and np.array_equal(_np(r.bits), obits)
+    assert r.counts == list(ocounts)
+    # global selection of O_q: properties
+    k_q = B.count_ppm(wl.rho_q_ppm, d_in * d_out)
+    _selection_properties(r.W_t, r.centroids_prelim, r.codes_prelim, r.bits, r.out_idx, r.out_val, k_q)
+    # k-means of both passes, coding, packing, error: sampled channels, recomputed one by one
+    rng = np.random.default_rng(5)
+    sample = np.sort(np.concatenate([rng.choice(d_in, 40, replace=False), oact[:2]]))
+    sample = np.unique(sample)
+    st = torch.from_numpy(sample).to(DEV)
+    Ws = _np(r.W_t[st])
+    bs = obits[sample]
+    c1, k1 = orc.kmeans(Ws, bs, iters=wl.iters)
+    assert np.array_equal(_np(r.centroids_prelim[st]), c1) and np.array_equal(_np(r.codes_prelim[st]), k1)
+    oi = _np(r.out_idx).astype(np.int64)
+    local = []
+    for t, i in enumerate(sample):
+        seg = oi[(oi >= i * d_out) & (oi < (i + 1) * d_out)] - i * d_out
+        local.append(seg + t * d_out)
+    local = np.concatenate(local)
+    c2, k2 = orc.kmeans(Ws, bs, out_idx=local, iters=wl.iters)
+    assert np.array_equal(_np(r.centroids[st]), c2) and np.array_equal(_np(r.codes[st]), k2)
+    for jw, b in enumerate(wl.bit_set):
+        opk, och, olut = orc.pack(k2, bs, c2, b)
+        if r.counts[jw] == 0:
+            assert len(och) == 0 and not (obits == b).any()
+            continue
+        chan = _np(r.chan_idx[jw])
+        assert np.array_equal(chan, np.flatnonzero(obits == b))
+        rows = np.searchsorted(chan, sample[och])
+        assert np.array_equal(_np(r.packed[jw][torch.from_numpy(rows).to(DEV)]).view(np.uint32), opk)
+        assert np.array_equal(_np(r.lut[jw][torch.from_numpy(rows).to(DEV)]).view(np.uint16), olut)
+    oerr, _ = orc.dequant_error(Ws, c2, k2, bs, local, None)
+    got = _np(r.err_ch[st])
+    assert np.allclose(got, oerr, rtol=1e-12, atol=0)
+    tot = _np(r.err_total)
+    ref_w = float((r.err_ch * sumsq.double()).sum())
+    assert abs(tot[0] - ref_w) <= 1e-9 * ref_w

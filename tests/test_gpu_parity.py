@@ -1,0 +1,389 @@
+"""GPU-vs-oracle parity of every step of the path, element by element, through the C ABI.
+
+Bars (stated where used): integer outputs - bits, outlier index sets and values, codes
+given identical levels, packed words - are bit-exact.  Levels agree within 1e-5 relative
+(they are in fact bit-identical for fp16 inputs, whose fp64 sums are exact); per-layer
+activation-weighted error within 1e-4 relative; the activation statistic within 1e-5
+relative of the fp64 oracle (observed: ~1e-15).
+"""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda"
+
+
+@pytest.fixture(scope="module")
+def env(orc):
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2410_13056_amd import binding as B, pipeline as P, synth
+    B.lib()                                   # fails loudly when the library has not been built
+    return dict(B=B, P=P, synth=synth, ws=B.Workspace(DEV), orc=orc)
+
+
+def _np(t):
+    return t.detach().cpu().numpy()
+
+
+def _dev(a, dtype=None):
+    t = torch.from_numpy(np.ascontiguousarray(a))
+    return t.to(DEV) if dtype is None else t.to(DEV).to(dtype)
+
+
+def _rel(a, b):
+    a, b = np.asarray(a, np.float64), np.asarray(b, np.float64)
+    fin = np.isfinite(a) & np.isfinite(b)
+    assert np.array_equal(np.isfinite(a), np.isfinite(b))
+    if not fin.any():
+        return 0.0
+    den = np.maximum(np.abs(b[fin]), 1e-30)
+    return float(np.max(np.abs(a[fin] - b[fin]) / den))
+
+
+# ------------------------------------------------------------------ statistics
+
+@pytest.mark.parametrize("dtype", [np.float16, np.float32])
+@pytest.mark.parametrize("n,d_in", [(1, 8), (7, 77), (300, 512), (1031, 1000), (4096, 1536), (33, 8200)])
+def test_act_stats_parity(env, dtype, n, d_in):
+    rng = np.random.default_rng(n * 131 + d_in)
+    X = (rng.normal(0, 1, (n, d_in)) * rng.lognormal(0, 1, d_in)).astype(dtype)
+    acc, sumsq = env["P"].activation_stats(_dev(X), env["ws"])
+    oacc, osum = env["orc"].act_stats(X)
+    assert _rel(_np(acc), oacc) < 1e-12
+    assert _rel(_np(sumsq), osum) <= 1e-5          # the stated bar; in practice bit-identical
+    assert np.array_equal(_np(sumsq), osum)
+
+
+def test_act_stats_strided_chunked_empty_and_status(env):
+    B, P, ws, orc = env["B"], env["P"], env["ws"], env["orc"]
+    rng = np.random.default_rng(0)
+    big = rng.normal(0, 2, (500, 640)).astype(np.float16)
+    Xd = _dev(big)[:, 64:64 + 264]                  # leading dimension 640 > d_in, 16-byte aligned start
+    acc, sumsq = P.activation_stats(Xd, ws)
+    oacc, _ = orc.act_stats(big[:, 64:64 + 264])
+    assert _rel(_np(acc), oacc) < 1e-12
+    Xo = _dev(big)[:, 3:3 + 100]                    # odd offset: the unaligned path
+    acc, _ = P.activation_stats(Xo, ws)
+    assert _rel(_np(acc), orc.act_stats(big[:, 3:103])[0]) < 1e-12
+    # tokens arriving in chunks give the one-shot result
+    full = _dev(big)
+    a1, _ = P.activation_stats(full[:123], ws)
+    a2, s2 = P.activation_stats(full[123:], ws, acc=a1)
+    a0, s0 = P.activation_stats(full, ws)
+    assert _rel(_np(a2), _np(a0)) < 1e-13 and np.array_equal(_np(s2), _np(s0))
+    # no tokens: accumulator untouched when adding, zero when starting
+    a3 = a0.clone()
+    B.act_stats(full[:0], a3, None, True, ws)
+    assert torch.equal(a3, a0)
+    B.act_stats(full[:0], a3, None, False, ws)
+    assert (a3 == 0).all()
+    # NaN / infinity in X raises the status flag
+    bad = big.copy()
+    bad[17, 5] = np.inf
+    st = torch.zeros(1, dtype=torch.int32, device=DEV)
+    P.activation_stats(_dev(bad), ws, status=st)
+    assert st.item() & B.STATUS_NONFINITE
+    st.zero_()
+    P.activation_stats(full, ws, status=st)
+    assert st.item() == 0
+
+
+def test_act_stats_is_reproducible(env):
+    X = env["synth"].make_activations(20000, 2048, "f16", 5, DEV)
+    a1, _ = env["P"].activation_stats(X, env["ws"])
+    a2, _ = env["P"].activation_stats(X, env["ws"])
+    assert torch.equal(a1, a2)
+
+
+@pytest.mark.parametrize("dtype", [torch.float16, torch.float32])
+@pytest.mark.parametrize("rows,cols", [(1, 1), (64, 64), (65, 63), (512, 256), (1000, 3), (7, 900)])
+def test_transpose(env, dtype, rows, cols):
+    src = torch.randn(rows, cols, device=DEV).to(dtype)
+    dst = torch.empty(cols, rows, dtype=dtype, device=DEV)
+    env["B"].transpose(src, dst)
+    assert torch.equal(dst, src.t().contiguous())
+    wide = torch.zeros(cols, rows + 5, dtype=dtype, device=DEV)
+    env["B"].transpose(src, wide[:, :rows])          # leading dimension of dst > rows
+    assert torch.equal(wide[:, :rows], src.t()) and (wide[:, rows:] == 0).all()
+
+
+# ------------------------------------------------------------------ rankings
+
+@pytest.mark.parametrize("d_in", [1, 5, 256, 1000, 4096, 28672])
+def test_channel_outliers_and_allocation_parity(env, d_in):
+    B, ws, orc = env["B"], env["ws"], env["orc"]
+    rng = np.random.default_rng(d_in)
+    s = rng.lognormal(0, 1, d_in).astype(np.float32)
+    if d_in > 4:
+        s[rng.integers(0, d_in, d_in // 5)] = s[0]          # exact ties
+        s[rng.integers(0, d_in, 3)] = 0.0
+    sd = _dev(s)
+    for k in sorted({0, 1, B.count_ppm(4500, d_in), d_in // 3, d_in}):
+        idx = torch.full((max(k, 1),), -7, dtype=torch.int32, device=DEV)
+        mask = torch.empty(d_in, dtype=torch.uint8, device=DEV)
+        B.extract_channel_outliers(sd, k, idx, mask, ws)
+        oidx, omask = orc.top_channels(s, k)
+        assert np.array_equal(_np(idx)[:k], oidx) and np.array_equal(_np(mask), omask)
+        for bit_set in ((2, 3), (2, 3, 4), (1, 2, 3, 4)):
+            for b in (bit_set[0], bit_set[0] + 0.2, 2.5, 3.0, bit_set[-1] - 0.37, bit_set[-1]):
+                if not bit_set[0] <= b <= bit_set[-1]:
+                    continue
+                bits = torch.empty(d_in, dtype=torch.uint8, device=DEV)
+                counts = B.allocate_bits(sd, mask, k, bit_set, b, bits, ws)
+                obits, ocounts = orc.allocate_bits(s, omask, bit_set, b)
+                assert np.array_equal(_np(bits), obits), (d_in, k, bit_set, b)
+                assert counts == list(ocounts)
+    bits = torch.empty(d_in, dtype=torch.uint8, device=DEV)          # no mask at all
+    B.allocate_bits(sd, None, 0, (2, 3, 4), 3.3, bits, ws)
+    assert np.array_equal(_np(bits), orc.allocate_bits(s, None, (2, 3, 4), 3.3)[0])
+
+
+# ------------------------------------------------------------------ k-means
+
+def _kmeans_gpu(env, W, bits, out_idx=None, ew=None, iters=20, status=None):
+    B, ws = env["B"], env["ws"]
+    Wd = _dev(W)
+    d_in, d_out = W.shape
+    cent = torch.empty((d_in, 16), dtype=torch.float32, device=DEV)
+    codes = torch.full((d_in, d_out), 255, dtype=torch.uint8, device=DEV)
+    oi = None if out_idx is None else _dev(out_idx.astype(np.int32))
+    B.kmeans_quantize(Wd, _dev(bits), oi, 0 if out_idx is None else len(out_idx),
+                      None if ew is None else _dev(ew), iters, cent, codes, ws, status)
+    return _np(cent), _np(codes)
+
+
+def _check_kmeans(cent, codes, ocent, ocodes, exact):
+    if exact:
+        assert np.array_equal(cent, ocent)
+        assert np.array_equal(codes, ocodes)
+    else:
+        assert _rel(cent, ocent) <= 1e-5                       # bar on levels
+        assert (codes != ocodes).mean() <= 1e-4                # bar on assignments
+
+
+@pytest.mark.parametrize("dtype", [np.float16, np.float32])
+@pytest.mark.parametrize("d_out", [1, 2, 63, 64, 257, 1000, 4096 + 7])
+def test_kmeans_parity_ragged_sizes(env, dtype, d_out):
+    rng = np.random.default_rng(d_out)
+    d_in = 40
+    W = rng.normal(0, 0.02, (d_in, d_out))
+    W[rng.random(W.shape) < 0.01] *= 15
+    W = W.astype(dtype)
+    bits = rng.integers(1, 5, d_in).astype(np.uint8)
+    bits[[3, 17]] = 16
+    bits[5] = 0
+    cent, codes = _kmeans_gpu(env, W, bits, iters=12)
+    ocent, ocodes = env["orc"].kmeans(W, bits, iters=12)
+    _check_kmeans(cent, codes, ocent, ocodes, exact=dtype == np.float16)
+
+
+def test_kmeans_parity_degenerate_channels(env):
+    rng = np.random.default_rng(1)
+    d_in, d_out = 24, 300
+    W = rng.normal(0, 1, (d_in, d_out)).astype(np.float16)
+    W[0, :] = W[0, 0]                                   # one distinct value
+    W[1, 50:] = 0.0                                     # most of the channel equal: duplicate starts
+    W[2, :] = np.float16(-0.0)
+    W[3, ::2] = np.float16(-0.0)
+    W[3, 1::2] = np.float16(0.0)
+    W[4] = np.repeat(np.array([-1, 0.5, 2], np.float16), 100)     # fewer values than levels
+    W[5, :150] = 1.0
+    W[5, 150:] = -1.0
+    W[6] = np.float16(65504.0) * np.sign(rng.normal(size=d_out)).astype(np.float16)   # largest finite halves
+    W[7] = (rng.integers(0, 3, d_out) * 2.0 ** -24).astype(np.float16)               # subnormals
+    W[8, :4] = [3.0, 1.0, 2.0, 1.0]
+    for nb in (1, 2, 3, 4):
+        bits = np.full(d_in, nb, np.uint8)
+        for iters in (0, 1, 7):
+            cent, codes = _kmeans_gpu(env, W, bits, iters=iters)
+            ocent, ocodes = env["orc"].kmeans(W, bits, iters=iters)
+            _check_kmeans(cent, codes, ocent, ocodes, exact=True)
+
+
+def test_kmeans_parity_with_removed_entries_and_weights(env):
+    rng = np.random.default_rng(2)
+    d_in, d_out = 32, 777
+    W = (rng.standard_t(3, (d_in, d_out)) * 0.03).astype(np.float16)
+    bits = rng.integers(2, 5, d_in).astype(np.uint8)
+    bits[9] = 16
+    excl = np.sort(rng.choice(d_in * d_out, 600, replace=False)).astype(np.int64)
+    excl = np.concatenate([excl, np.arange(4 * d_out, 5 * d_out)])      # channel 4 removed entirely
+    excl = np.unique(excl)
+    cent, codes = _kmeans_gpu(env, W, bits, out_idx=excl, iters=9)
+    ocent, ocodes = env["orc"].kmeans(W, bits, out_idx=excl, iters=9)
+    _check_kmeans(cent, codes, ocent, ocodes, exact=True)
+    assert (cent[4, :1 << bits[4]] == 0).all()
+    # importance weights: integer weights keep the fp64 sums exact -> still bit-identical
+    ew = rng.integers(0, 5, (d_in, d_out)).astype(np.float32)
+    cent, codes = _kmeans_gpu(env, W, bits, ew=ew, iters=9)
+    ocent, ocodes = env["orc"].kmeans(W, bits, elem_weight=ew, iters=9)
+    _check_kmeans(cent, codes, ocent, ocodes, exact=True)
+    # real-valued weights and both mechanisms together: within the stated bars
+    ew = rng.lognormal(0, 1, (d_in, d_out)).astype(np.float32)
+    cent, codes = _kmeans_gpu(env, W, bits, out_idx=excl, ew=ew, iters=9)
+    ocent, ocodes = env["orc"].kmeans(W, bits, out_idx=excl, elem_weight=ew, iters=9)
+    _check_kmeans(cent, codes, ocent, ocodes, exact=False)
+
+
+def test_kmeans_flags_nonfinite_weights_and_is_reproducible(env):
+    rng = np.random.default_rng(3)
+    W = rng.normal(0, 1, (8, 500)).astype(np.float16)
+    bits = np.full(8, 3, np.uint8)
+    st = torch.zeros(1, dtype=torch.int32, device=DEV)
+    c1, k1 = _kmeans_gpu(env, W, bits, status=st)
+    c2, k2 = _kmeans_gpu(env, W, bits, status=st)
+    assert st.item() == 0 and np.array_equal(c1, c2) and np.array_equal(k1, k2)
+    W[2, 7] = np.nan
+    _kmeans_gpu(env, W, bits, status=st)
+    assert st.item() & env["B"].STATUS_NONFINITE
+
+
+# ------------------------------------------------------------------ O_q
+
+@pytest.mark.parametrize("dtype", [np.float16, np.float32])
+@pytest.mark.parametrize("d_in,d_out", [(3, 5), (20, 96), (16, 2048 + 40), (70, 333)])
+def test_weight_outliers_parity(env, dtype, d_in, d_out):
+    B, ws, orc = env["B"], env["ws"], env["orc"]
+    rng = np.random.default_rng(d_in * 7 + d_out)
+    W = (rng.integers(-40, 40, (d_in, d_out)) / 64.0).astype(dtype)      # coarse grid: tied scores
+    bits = rng.integers(1, 4, d_in).astype(np.uint8)
+    bits[rng.integers(0, d_in)] = 16
+    ocent, ocodes = orc.kmeans(W, bits, iters=3)
+    live = int((bits <= 4).sum()) * d_out
+    Wd, cd, kd, bd = _dev(W), _dev(ocent), _dev(ocodes), _dev(bits)
+    for score in (B.SCORE_RESIDUAL, B.SCORE_MAGNITUDE):
+        for k in sorted({0, 1, 9, live // 50 + 1, live // 2, live}):
+            idx = torch.full((max(k, 1),), -7, dtype=torch.int32, device=DEV)
+            val = torch.zeros(max(k, 1), dtype=torch.float16, device=DEV)
+            B.extract_weight_outliers(Wd, cd, kd, bd, k, idx, val, ws, score)
+            oidx, oval = orc.weight_outliers(W, ocent, ocodes, bits, k, score)
+            assert np.array_equal(_np(idx)[:k].astype(np.int64), oidx), (score, k)
+            assert np.array_equal(_np(val)[:k].view(np.uint16), oval)
+    # asking for more than the candidates: every candidate, then -1
+    k = live + 5
+    idx = torch.full((k,), -7, dtype=torch.int32, device=DEV)
+    B.extract_weight_outliers(Wd, cd, kd, bd, k, idx, None, ws)
+    got = _np(idx)
+    assert (got[live:] == -1).all() and len(np.unique(got[:live])) == live and (got[:live] >= 0).all()
+
+
+# ------------------------------------------------------------------ storage and error
+
+@pytest.mark.parametrize("d_out", [1, 31, 32, 33, 100, 512, 4096 + 16])
+def test_pack_parity(env, d_out):
+    B, ws, orc = env["B"], env["ws"], env["orc"]
+    rng = np.random.default_rng(d_out)
+    d_in = 53
+    for bit_set in ((2, 3), (2, 3, 4), (1, 2, 3, 4)):
+        bits = rng.choice(np.array(bit_set + (16,), np.uint8), d_in)
+        codes = np.stack([rng.integers(0, 1 << min(int(b), 4), d_out) for b in bits]).astype(np.uint8)
+        cent = rng.normal(0, 1, (d_in, 16)).astype(np.float32)
+        counts = [int((bits == b).sum()) for b in bit_set]
+        packed = [torch.full((c, (d_out * b + 31) // 32), -1, dtype=torch.int32, device=DEV) if c else None
+                  for b, c in zip(bit_set, counts)]
+        chan = [torch.empty(c, dtype=torch.int32, device=DEV) if c else None for c in counts]
+        lut = [torch.empty((c, 1 << b), dtype=torch.float16, device=DEV) if c else None
+               for b, c in zip(bit_set, counts)]
+        B.pack(_dev(codes), _dev(bits), _dev(cent), bit_set, counts, packed, chan, lut, ws)
+        for j, b in enumerate(bit_set):
+            opk, och, olut = orc.pack(codes, bits, cent, b)
+            if counts[j] == 0:
+                assert opk.shape[0] == 0
+                continue
+            assert np.array_equal(_np(packed[j]).view(np.uint32), opk)
+            assert np.array_equal(_np(chan[j]), och)
+            assert np.array_equal(_np(lut[j]).view(np.uint16), olut)
+
+
+@pytest.mark.parametrize("dtype", [np.float16, np.float32])
+def test_dequant_error_parity(env, dtype):
+    B, ws, orc = env["B"], env["ws"], env["orc"]
+    rng = np.random.default_rng(4)
+    d_in, d_out = 45, 1234
+    W = rng.normal(0, 0.05, (d_in, d_out)).astype(dtype)
+    bits = rng.integers(2, 5, d_in).astype(np.uint8)
+    bits[[1, 30]] = 16
+    cent, codes = orc.kmeans(W, bits, iters=4)
+    sumsq = rng.lognormal(3, 1, d_in).astype(np.float32)
+    out_idx = np.sort(rng.choice(d_in * d_out, 500, replace=False)).astype(np.int64)
+    for oi in (None, out_idx):
+        for ss in (None, sumsq):
+            err = torch.empty(d_in, dtype=torch.float64, device=DEV)
+            tot = torch.empty(2, dtype=torch.float64, device=DEV)
+            B.dequant_error(_dev(W), _dev(cent), _dev(codes), _dev(bits),
+                            None if oi is None else _dev(oi.astype(np.int32)), 0 if oi is None else len(oi),
+                            None if ss is None else _dev(ss), err, tot, ws)
+            oerr, otot = orc.dequant_error(W, cent, codes, bits, oi, ss)
+            assert _rel(_np(err), oerr) < 1e-12
+            assert _rel(_np(tot), otot) < 1e-12                 # bar: 1e-4 relative on the layer total
+    # every entry restored: zero error for fp16 weights ("reconstruction with all outliers restored")
+    if dtype == np.float16:
+        all_idx = _dev(np.arange(d_in * d_out, dtype=np.int32))
+        err = torch.empty(d_in, dtype=torch.float64, device=DEV)
+        tot = torch.empty(2, dtype=torch.float64, device=DEV)
+        B.dequant_error(_dev(W), _dev(cent), _dev(codes), _dev(bits), all_idx, d_in * d_out, None, err, tot, ws)
+        assert (err == 0).all() and (tot == 0).all()
+
+
+# ------------------------------------------------------------------ the whole path, free running
+
+def _compare_layer(env, r, o, bit_set, exact_levels):
+    assert r.counts == list(o["counts"])
+    assert np.array_equal(_np(r.act_idx), o["act_idx"])
+    assert np.array_equal(_np(r.chan_mask), o["chan_mask"])
+    assert np.array_equal(_np(r.bits), o["bits"])                                  # bit-exact
+    _check_kmeans(_np(r.centroids_prelim), _np(r.codes_prelim), o["cent1"], o["codes1"], exact_levels)
+    assert np.array_equal(_np(r.out_idx).astype(np.int64), o["out_idx"])           # bit-exact set
+    assert np.array_equal(_np(r.out_val).view(np.uint16), o["out_val"])
+    _check_kmeans(_np(r.centroids), _np(r.codes), o["centroids"], o["codes"], exact_levels)
+    if np.array_equal(_np(r.codes), o["codes"]):
+        for j, b in enumerate(bit_set):
+            opk, och, olut = o["packs"][b]
+            if r.counts[j]:
+                assert np.array_equal(_np(r.packed[j]).view(np.uint32), opk)
+                assert np.array_equal(_np(r.chan_idx[j]), och)
+                assert np.array_equal(_np(r.lut[j]).view(np.uint16), olut)
+    assert _rel(_np(r.err_total), o["totals"]) <= 1e-4                             # bar on the layer error
+
+
+def test_end_to_end_tiny_config(env):
+    """The smallest configuration at its full size: 512x256 fp32, 256 tokens, {2,3} avg 2.5, 10 rounds."""
+    P, synth, ws, orc = env["P"], env["synth"], env["ws"], env["orc"]
+    wl = synth.workload("tiny")
+    wts, xs = synth.materialize(wl, "cpu")
+    W, X = wts["linear"], xs["x"]
+    _, sumsq = P.activation_stats(X.to(DEV), ws)
+    r = P.quantize_layer(W.to(DEV), sumsq, wl.bit_set, wl.avg_bits, wl.rho_act_ppm, wl.rho_q_ppm, wl.iters,
+                         ws, with_error=True, keep_prelim=True)
+    o = orc.quantize_layer(W.numpy().T.copy(), X.numpy(), wl.bit_set, wl.avg_bits, wl.rho_act_ppm,
+                           wl.rho_q_ppm, wl.iters)
+    assert np.array_equal(_np(r.sumsq), o["sumsq"])
+    _compare_layer(env, r, o, wl.bit_set, exact_levels=False)
+
+
+@pytest.mark.parametrize("name,shrink,tokens", [("q7b", 8, 2048), ("block7b", 16, 1024),
+                                                ("block13b", 16, 1024), ("block70b", 32, 512)])
+def test_end_to_end_scaled_workloads(env, name, shrink, tokens):
+    """Every configuration's structure (layer mix, budget, outlier fractions, rounds) at a size the
+    oracle finishes in seconds; dimensions stay multiples of 8, several tiles and ragged tails."""
+    P, synth, ws, orc = env["P"], env["synth"], env["ws"], env["orc"]
+    wl = synth.scaled(synth.workload(name), tokens=tokens, shrink=shrink)
+    wts, xs = synth.materialize(wl, DEV)
+    status = torch.zeros(1, dtype=torch.int32, device=DEV)
+    stats = {}
+    for layer in wl.layers:
+        if layer.x_key not in stats:
+            stats[layer.x_key] = P.activation_stats(xs[layer.x_key], ws, status=status)[1]
+            _, osum = orc.act_stats(_np(xs[layer.x_key]))
+            assert np.array_equal(_np(stats[layer.x_key]), osum)
+        W = wts[layer.name]
+        r = P.quantize_layer(W, stats[layer.x_key], wl.bit_set, wl.avg_bits, wl.rho_act_ppm, wl.rho_q_ppm,
+                             wl.iters, ws, with_error=True, keep_prelim=True, status=status)
+        assert torch.equal(r.W_t, W.t().contiguous())
+        o = orc.quantize_layer(_np(W).T.copy(), None, wl.bit_set, wl.avg_bits, wl.rho_act_ppm, wl.rho_q_ppm,
+                               wl.iters, sumsq=_np(stats[layer.x_key]))
+        _compare_layer(env, r, o, wl.bit_set, exact_levels=True)
+    assert status.item() == 0
