@@ -16,25 +16,12 @@
 // table in LDS, the table is reduced per cell in a fixed order, and the new level is
 // the fp64 quotient rounded once to fp32.  For fp16 inputs with 0/1 weights these
 // sums are exact, so the result does not depend on the lane layout.
-#include "common.h"
+#include "kmeans_args.h"
 
 namespace {
 
 constexpr int kT = 256;  // threads per workgroup
 constexpr int kWavesPerBlock = kT / CMPQ_WAVE;
-
-struct KmArgs {
-    const void *W;
-    int64_t d_in, d_out, ldw;
-    const uint8_t *bits;
-    const int32_t *out_idx;
-    int64_t n_out;
-    const float *ew;
-    int iters;
-    float *centroids;
-    uint8_t *codes;
-    int32_t *status;
-};
 
 struct KmSmall {
     float cent[CMPQ_KMAX];   // levels, by level index
@@ -263,6 +250,7 @@ __global__ __launch_bounds__(kT) void kmeans_kernel(KmArgs a) {
     const int d_out = (int)a.d_out;
     const int b = a.bits[i];
     float *crow = a.centroids + i * CMPQ_KMAX;
+    if (a.deferred && !a.deferred[i]) return;  // already done by the fixed-point kernel
     if (b < 1 || b > 4) {  // a channel of O_act: no levels, no codes
         if (tid < CMPQ_KMAX) crow[tid] = INFINITY;
         for (int o = tid; o < d_out; o += kT) a.codes[i * a.d_out + o] = 0;
@@ -364,15 +352,15 @@ int launch_kmeans(const KmArgs &a, hipStream_t s) {
 
 }  // namespace
 
-size_t cmpq_ws_kmeans(int64_t, int64_t) { return 256; }
+size_t cmpq_ws_kmeans(int64_t d_in, int64_t) {
+    return align_up((size_t)(d_in > 0 ? d_in : 1), 256);
+}
 
 extern "C" int cmpq_kmeans_quantize(const void *W, int dtype, int64_t d_in, int64_t d_out,
                                     int64_t ldw, const uint8_t *bits, const int32_t *out_idx,
                                     int64_t n_out, const float *elem_weight, int iters, int init,
                                     float *centroids, uint8_t *codes, void *ws, size_t ws_bytes,
                                     int32_t *status, void *stream) {
-    (void)ws;
-    (void)ws_bytes;
     if (d_in < 0 || d_out < 0 || n_out < 0 || iters < 0) return CMPQ_EINVAL;
     if (dtype != CMPQ_F16 && dtype != CMPQ_F32) return CMPQ_EINVAL;
     if (init != CMPQ_INIT_QUANTILE) return CMPQ_EINVAL;
@@ -396,7 +384,16 @@ extern "C" int cmpq_kmeans_quantize(const void *W, int dtype, int64_t d_in, int6
     a.centroids = centroids;
     a.codes = codes;
     a.status = status;
+    a.deferred = nullptr;
     hipStream_t s = static_cast<hipStream_t>(stream);
+    if (kmeans_fast_eligible(a, dtype)) {
+        if (!ws || reinterpret_cast<uintptr_t>(ws) % 256 != 0 || ws_bytes < cmpq_ws_kmeans(d_in, d_out))
+            return CMPQ_EWORKSPACE;
+        a.deferred = static_cast<uint8_t *>(ws);
+        const int rc = launch_kmeans_fast(a, s);
+        if (rc != CMPQ_OK) return rc;
+        return launch_kmeans<__half, false>(a, s);  // only the channels the first kernel deferred
+    }
     if (dtype == CMPQ_F16)
         return elem_weight ? launch_kmeans<__half, true>(a, s) : launch_kmeans<__half, false>(a, s);
     return elem_weight ? launch_kmeans<float, true>(a, s) : launch_kmeans<float, false>(a, s);

@@ -1,0 +1,24 @@
+// Argument block shared by the two k-means kernels of libcmpq.
+#pragma once
+#include "common.h"
+
+struct KmArgs {
+    const void *W;
+    int64_t d_in, d_out, ldw;
+    const uint8_t *bits;
+    const int32_t *out_idx;
+    int64_t n_out;
+    const float *ew;
+    int iters;
+    float *centroids;
+    uint8_t *codes;
+    int32_t *status;
+    // One byte per channel in the workspace.  The fixed-point kernel raises it for a
+    // channel it cannot hold (a magnitude of 128 or more, or a non-finite value); the
+    // general kernel, launched after it, then handles exactly those channels.
+    uint8_t *deferred;
+};
+
+// Fixed-point k-means for fp16 weights with unit importance (kmeans_fast.hip).
+int launch_kmeans_fast(const KmArgs &a, hipStream_t s);
+bool kmeans_fast_eligible(const KmArgs &a, int dtype);
