@@ -124,7 +124,7 @@ def main():
                    "weights": wl.dtype, "bit_set": list(wl.bit_set), "avg_bits": wl.avg_bits,
                    "rho_act_ppm": wl.rho_act_ppm, "rho_q_ppm": wl.rho_q_ppm, "iters": wl.iters,
                    "tokens": {k: v[0] for k, v in wl.x_shapes.items()}},
-        "roofline": {"kernel": "kmeans_fast_kernel", "bound": "alu", "achieved": achieved,
+        "roofline": {"kernel": "kmeans_bucket_kernel", "bound": "alu", "achieved": achieved,
                      "peak": ALU_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": achieved / ALU_PEAK_TFLOPS,
                      "traffic": None, "launches_per_step": launches_per_step,
                      "avg_launch_ms": avg_launch_s * 1e3, "credited_flop_per_launch": flops / launches_per_step},

@@ -73,6 +73,10 @@ extern "C" {
 /* `init` of cmpq_kmeans_quantize */
 #define CMPQ_INIT_QUANTILE 0
 
+/* argument of cmpq_set_kmeans_algorithm */
+#define CMPQ_KMEANS_HISTOGRAM 0 /* rounds read cumulative tables of the channel (default)   */
+#define CMPQ_KMEANS_DIRECT 1    /* rounds revisit every weight: K-1 compares, 2 accumulations */
+
 size_t cmpq_workspace_bytes(int op, int64_t d_in, int64_t d_out, int64_t n);
 const char *cmpq_strerror(int code);
 
@@ -153,7 +157,7 @@ int cmpq_extract_outliers(int mode, int score, const float *sumsq, const void *W
  * Sec. 3.2.1, channel-wise non-uniform quantization: for every channel with bits[i] in
  * 1..4, K = 2^bits[i] levels by Lloyd's algorithm on W[i,:], then each weight is coded by
  * its nearest level (Sec. 3 eq. Q(x)).
- *   out_idx     [n_out] int32 nullable: linear indices, ascending, of entries removed
+ *   out_idx     [n_out] int32 nullable: linear indices, strictly ascending, of entries removed
  *               before clustering (O_q, Sec. 3.2.2); they weigh 0 but still get a code.
  *   elem_weight [d_in, d_out] fp32 nullable, leading dimension d_out: importance of each
  *               entry in the level update (null = 1).  Must be >= 0 and finite.
@@ -174,6 +178,14 @@ int cmpq_kmeans_quantize(const void *W, int dtype, int64_t d_in, int64_t d_out, 
                          const float *elem_weight, int iters, int init, float *centroids,
                          uint8_t *codes, void *ws, size_t ws_bytes, int32_t *status,
                          void *stream);
+
+/*
+ * Process-wide choice between the two implementations of the Lloyd rounds of Sec. 3.2.1
+ * for fp16 weights with unit importance.  Both produce identical levels and codes; the
+ * direct one exists for measurements against the plain ALU roofline.  Host only; takes
+ * effect at the next cmpq_kmeans_quantize call.  Returns CMPQ_EINVAL for another value.
+ */
+int cmpq_set_kmeans_algorithm(int algorithm);
 
 /*
  * Sec. 5.1 / Fig. 4, the stored format: one code matrix per width.  For j < n_set and

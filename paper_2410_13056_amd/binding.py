@@ -24,10 +24,11 @@ OP_ACT_STATS, OP_ALLOCATE_BITS, OP_OUTLIER_CHANNELS, OP_OUTLIER_WEIGHTS, OP_KMEA
 OUTLIER_CHANNELS, OUTLIER_WEIGHTS = 0, 1
 SCORE_RESIDUAL, SCORE_MAGNITUDE = 0, 1
 INIT_QUANTILE = 0
+KMEANS_HISTOGRAM, KMEANS_DIRECT = 0, 1
 
 EXPORTS = ("cmpq_workspace_bytes", "cmpq_strerror", "cmpq_count_ppm", "cmpq_act_stats",
            "cmpq_transpose", "cmpq_allocate_bits", "cmpq_extract_outliers",
-           "cmpq_kmeans_quantize", "cmpq_pack", "cmpq_dequant_error")
+           "cmpq_kmeans_quantize", "cmpq_pack", "cmpq_dequant_error", "cmpq_set_kmeans_algorithm")
 
 _i64, _i32, _int, _vp, _dbl, _sz = (ctypes.c_int64, ctypes.c_int32, ctypes.c_int, ctypes.c_void_p,
                                     ctypes.c_double, ctypes.c_size_t)
@@ -64,6 +65,7 @@ def lib() -> ctypes.CDLL:
         L.cmpq_pack.argtypes = [_vp, _i64, _i64, _vp, _vp, _vp, _int, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
         L.cmpq_dequant_error.argtypes = [_vp, _int, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _i64, _vp,
                                          _vp, _vp, _vp, _sz, _vp]
+        L.cmpq_set_kmeans_algorithm.argtypes = [_int]
         for name in EXPORTS[3:]:
             getattr(L, name).restype = _int
         _lib = L
@@ -76,6 +78,10 @@ def strerror(code: int) -> str:
 
 def count_ppm(ppm: int, n: int) -> int:
     return int(lib().cmpq_count_ppm(int(ppm), int(n)))
+
+
+def set_kmeans_algorithm(algorithm: int) -> None:
+    _check(lib().cmpq_set_kmeans_algorithm(int(algorithm)), "cmpq_set_kmeans_algorithm")
 
 
 def workspace_bytes(op: int, d_in: int, d_out: int = 0, n: int = 0) -> int:

@@ -352,6 +352,14 @@ int launch_kmeans(const KmArgs &a, hipStream_t s) {
 
 }  // namespace
 
+static int g_kmeans_algorithm = CMPQ_KMEANS_HISTOGRAM;
+
+extern "C" int cmpq_set_kmeans_algorithm(int algorithm) {
+    if (algorithm != CMPQ_KMEANS_HISTOGRAM && algorithm != CMPQ_KMEANS_DIRECT) return CMPQ_EINVAL;
+    g_kmeans_algorithm = algorithm;
+    return CMPQ_OK;
+}
+
 size_t cmpq_ws_kmeans(int64_t d_in, int64_t) {
     return align_up((size_t)(d_in > 0 ? d_in : 1), 256);
 }
@@ -390,7 +398,8 @@ extern "C" int cmpq_kmeans_quantize(const void *W, int dtype, int64_t d_in, int6
         if (!ws || reinterpret_cast<uintptr_t>(ws) % 256 != 0 || ws_bytes < cmpq_ws_kmeans(d_in, d_out))
             return CMPQ_EWORKSPACE;
         a.deferred = static_cast<uint8_t *>(ws);
-        const int rc = launch_kmeans_fast(a, s);
+        const int rc = g_kmeans_algorithm == CMPQ_KMEANS_DIRECT ? launch_kmeans_fast(a, s)
+                                                                : launch_kmeans_hist(a, s);
         if (rc != CMPQ_OK) return rc;
         return launch_kmeans<__half, false>(a, s);  // only the channels the first kernel deferred
     }

@@ -19,6 +19,8 @@ struct KmArgs {
     uint8_t *deferred;
 };
 
-// Fixed-point k-means for fp16 weights with unit importance (kmeans_fast.hip).
+// Histogram k-means (kmeans_hist.hip) and fixed-point brute-force k-means
+// (kmeans_fast.hip), both for fp16 weights with unit importance.
+int launch_kmeans_hist(const KmArgs &a, hipStream_t s);
 int launch_kmeans_fast(const KmArgs &a, hipStream_t s);
 bool kmeans_fast_eligible(const KmArgs &a, int dtype);
