@@ -31,6 +31,20 @@
 // general kernel.
 #include "kmeans_args.h"
 
+#ifdef CMPQ_KM_PROFILE
+__device__ unsigned long long g_km_prof[16];
+extern "C" void cmpq_debug_read(unsigned long long *out) {
+    (void)hipMemcpyFromSymbol(out, HIP_SYMBOL(g_km_prof), sizeof(g_km_prof));
+    unsigned long long z[16] = {0};
+    (void)hipMemcpyToSymbol(HIP_SYMBOL(g_km_prof), z, sizeof(z));
+}
+#define KM_T(i) do { if (threadIdx.x == 0 && (blockIdx.x & 63) == 0) { unsigned long long t_ = wall_clock64(); atomicAdd(&g_km_prof[i], t_ - t_prof); t_prof = t_; } } while (0)
+#define KM_T0() unsigned long long t_prof = wall_clock64()
+#else
+#define KM_T(i) do { } while (0)
+#define KM_T0() do { } while (0)
+#endif
+
 namespace {
 
 constexpr int kLowBits = 6;
@@ -39,16 +53,15 @@ constexpr int kLows = 1 << kLowBits;
 constexpr uint32_t kKeyInf = 0xffffu;  // boundary above every key
 
 struct BucketShared {
-    long long scum[kBuckets + 1];   // exclusive prefix over buckets of sum(x * 2^24)
-    uint32_t ncum[kBuckets + 1];    // counts, then their exclusive prefix
-    uint32_t thr[CMPQ_KMAX];        // boundary keys by sorted position
-    uint32_t part_n[CMPQ_KMAX];     // per boundary: kept weights of its bucket not above it
-    uint32_t part_l[CMPQ_KMAX];     //               and the sum of their places
+    long long scum[kBuckets + 1];   // count << 32 | sum of places; then the exclusive prefix
+                                    // over buckets of sum(x * 2^24)
+    uint32_t ncum[kBuckets + 1];    // exclusive prefix over buckets of the counts
+    uint32_t part_n[2][CMPQ_KMAX];  // by round parity, per boundary: kept weights of its bucket
+    uint32_t part_l[2][CMPQ_KMAX];  //   not above it, and the sum of their places
     float cent[CMPQ_KMAX];          // levels by level index
-    int perm[CMPQ_KMAX];            // sorted position -> level index
     uint32_t scan32[17];
     unsigned long long scan64[17];
-    int seg_lo, n_excl, identity, done;
+    int seg_lo, n_excl;
 };
 
 __device__ __forceinline__ uint32_t key_of_half(uint32_t h) {
@@ -62,11 +75,34 @@ __device__ __forceinline__ float value_of_key(uint32_t k) {
 }
 
 // x*2^24 of the first key of bucket b, and the step per place inside the bucket.
+// For a normal half (e >= 1) x*2^24 = (1024 + m) << (e - 1); a subnormal gives m.
 __device__ __forceinline__ void bucket_affine(uint32_t b, long long &q0, long long &step) {
-    const uint32_t key0 = b << kLowBits;
-    const uint32_t e = (half_of_key(key0) >> 10) & 31u;
-    step = 1ll << ((e > 1 ? e : 1) - 1);
-    q0 = (long long)((double)value_of_key(key0) * 16777216.0);
+    const uint32_t h = half_of_key(b << kLowBits);
+    const uint32_t e = (h >> 10) & 31u, m = h & 1023u;
+    const uint32_t sh = (e > 1 ? e : 1) - 1;
+    step = 1ll << sh;
+    const long long mag = (long long)((e ? 1024u : 0u) + m) << sh;
+    q0 = (h & 0x8000u) ? -mag : mag;
+}
+
+// Value of the lane below / above inside a row of 16 lanes; 0 at the row's edge.
+__device__ __forceinline__ uint32_t row_from_below(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x111, 0xF, 0xF, true);  // row_shr:1
+}
+__device__ __forceinline__ uint32_t row_from_above(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x101, 0xF, 0xF, true);  // row_shl:1
+}
+
+// Sum over aligned groups of L lanes (L a power of two, 4..64); every lane gets its group's sum.
+template <int L>
+__device__ __forceinline__ uint32_t group_sum(uint32_t v) {
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xF, 0xF, false);   // quad_perm [1,0,3,2]
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x4E, 0xF, 0xF, false);   // quad_perm [2,3,0,1]
+    if constexpr (L >= 8) v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x141, 0xF, 0xF, false);  // row_half_mirror
+    if constexpr (L >= 16) v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x140, 0xF, 0xF, false); // row_mirror
+    if constexpr (L >= 32) v += __shfl_xor(v, 16, CMPQ_WAVE);
+    if constexpr (L >= 64) v += __shfl_xor(v, 32, CMPQ_WAVE);
+    return v;
 }
 
 __device__ __forceinline__ unsigned long long wave_scan_incl_u64(unsigned long long v) {
@@ -79,24 +115,40 @@ __device__ __forceinline__ unsigned long long wave_scan_incl_u64(unsigned long l
     return v;
 }
 
-__device__ __forceinline__ unsigned long long block_scan_excl_u64(unsigned long long v,
-                                                                  unsigned long long *scratch,
-                                                                  unsigned long long *total) {
+// Exclusive scan of a (count, sum) pair per thread over the workgroup, one set of
+// barriers for both.  scratch32 / scratch64 hold 17 entries each.
+__device__ __forceinline__ void block_scan_excl_pair(uint32_t n, unsigned long long v, uint32_t *scratch32,
+                                                     unsigned long long *scratch64, uint32_t &n_excl,
+                                                     unsigned long long &v_excl, uint32_t &n_total,
+                                                     unsigned long long &v_total) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int nwave = (blockDim.x + 63) >> 6;
-    const unsigned long long incl = wave_scan_incl_u64(v);
-    __syncthreads();
-    if (lane == 63) scratch[wave] = incl;
-    __syncthreads();
-    if (wave == 0) {
-        const unsigned long long w = lane < nwave ? scratch[lane] : 0ull;
-        const unsigned long long wi = wave_scan_incl_u64(w);
-        if (lane < nwave) scratch[lane] = wi - w;
-        if (lane == nwave - 1) scratch[16] = wi;
+    const uint32_t n_incl = wave_scan_incl_u32(n);
+    const unsigned long long v_incl = wave_scan_incl_u64(v);
+    if (lane == 63) {
+        scratch32[wave] = n_incl;
+        scratch64[wave] = v_incl;
     }
     __syncthreads();
-    *total = scratch[16];
-    return scratch[wave] + incl - v;
+    if (wave == 0) {
+        const uint32_t wn = lane < nwave ? scratch32[lane] : 0u;
+        const unsigned long long wv = lane < nwave ? scratch64[lane] : 0ull;
+        const uint32_t wni = wave_scan_incl_u32(wn);
+        const unsigned long long wvi = wave_scan_incl_u64(wv);
+        if (lane < nwave) {
+            scratch32[lane] = wni - wn;
+            scratch64[lane] = wvi - wv;
+        }
+        if (lane == nwave - 1) {
+            scratch32[16] = wni;
+            scratch64[16] = wvi;
+        }
+    }
+    __syncthreads();
+    n_total = scratch32[16];
+    v_total = scratch64[16];
+    n_excl = scratch32[wave] + n_incl - n;
+    v_excl = scratch64[wave] + v_incl - v;
 }
 
 // Number of boundary keys below `key` (boundaries ascending, repeats allowed).
@@ -199,185 +251,177 @@ __device__ __forceinline__ uint32_t elem_key(const uint32_t (&keys)[2 * G], int 
     return (keys[2 * k + (e >> 1)] >> (16 * (e & 1))) & 0xffffu;
 }
 
-// One wavefront: among the keys arr[begin, end), how many are <= tk, and the sum of
-// their places.  Result valid in every lane.
-__device__ __forceinline__ void scan_bucket(const unsigned short *arr, uint32_t begin, uint32_t end,
-                                            uint32_t tk, uint32_t &n, uint32_t &l) {
-    const int lane = threadIdx.x & 63;
+// A group of L lanes: among the places arr[begin, end) of one bucket, how many are <= pl,
+// and their sum.  Result valid in every lane of the group.
+template <int L>
+__device__ __forceinline__ void scan_bucket(const unsigned char *arr, uint32_t begin, uint32_t end,
+                                            uint32_t pl, uint32_t &n, uint32_t &l) {
+    const int sub = threadIdx.x & (L - 1);
     uint32_t cn = 0, cl = 0;
-    for (uint32_t j = begin + lane; j < end; j += 64) {
-        const uint32_t key = arr[j];
-        const bool in = key <= tk;
-        cn += in;
-        cl += in ? (key & (kLows - 1)) : 0u;
-    }
+    for (uint32_t j = begin + sub; j < end; j += 4 * L) {  // four reads in flight
+        uint32_t place[4];
 #pragma unroll
-    for (int s = 32; s > 0; s >>= 1) {
-        cn += __shfl_xor(cn, s, CMPQ_WAVE);
-        cl += __shfl_xor(cl, s, CMPQ_WAVE);
+        for (int u = 0; u < 4; ++u) place[u] = j + u * L < end ? arr[j + u * L] : 0xffu;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const bool in = place[u] <= pl;
+            cn += in;
+            cl += in ? place[u] : 0u;
+        }
     }
-    n = cn;
-    l = cl;
+    n = group_sum<L>(cn);
+    l = group_sum<L>(cl);
 }
 
-template <int G, int K>
+template <int G, int K, int T>
 __device__ __forceinline__ void lloyd_bucket(const KmArgs &a, int64_t i, BucketShared &sm,
-                                             const unsigned short *arr, uint32_t *fine,
+                                             const unsigned char *arr,
                                              const uint32_t (&keys)[2 * G], int n_groups, uint32_t M) {
-    const int T = blockDim.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nw = T >> 6;
+    constexpr int L = T / 16;  // lanes that share one boundary in a round
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    KM_T0();
 
     // ---- start-up: level j = order statistic floor((2j+1)M/(2K)) of the kept weights.
-    //      A wavefront per rank: locate the bucket by its prefix, count its 64 places.
-    for (int j = wave; j < K; j += nw) {
-        float c = 0.0f;
-        if (M > 0) {
-            const uint32_t r = (uint32_t)(((uint64_t)(2 * j + 1) * M) / (uint64_t)(2 * K));
-            int lo = 0, hi_b = kBuckets - 1;  // largest b with ncum[b] <= r
-            while (lo < hi_b) {
-                const int mid = (lo + hi_b + 1) >> 1;
-                if (sm.ncum[mid] <= r) lo = mid; else hi_b = mid - 1;
+    //      L lanes per rank: locate the bucket by its prefix, then bisect on the place
+    //      with counting scans of that bucket.
+    {
+        const int j = tid / L, sub = tid & (L - 1);
+        if (j < K) {
+            float c = 0.0f;
+            if (M > 0) {
+                const uint32_t r = (uint32_t)(((uint64_t)(2 * j + 1) * M) / (uint64_t)(2 * K));
+                int lo = 0, hi_b = kBuckets - 1;  // largest b with ncum[b] <= r
+                while (lo < hi_b) {
+                    const int mid = (lo + hi_b + 1) >> 1;
+                    if (sm.ncum[mid] <= r) lo = mid; else hi_b = mid - 1;
+                }
+                const uint32_t b = (uint32_t)lo, r_in = r - sm.ncum[b];
+                const uint32_t begin = sm.ncum[b], end = sm.ncum[b + 1];
+                int pl = 0, ph = kLows - 1;  // smallest place with more than r_in weights at or below it
+                while (pl < ph) {
+                    const int mid = (pl + ph) >> 1;
+                    uint32_t n, l;
+                    scan_bucket<L>(arr, begin, end, (uint32_t)mid, n, l);
+                    if (n > r_in) ph = mid; else pl = mid + 1;
+                }
+                c = value_of_key((b << kLowBits) | (uint32_t)pl);
             }
-            const uint32_t b = (uint32_t)lo, r_in = r - sm.ncum[lo];
-            uint32_t *f = fine + wave * kLows;
-            f[lane] = 0;
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-            __builtin_amdgcn_wave_barrier();
-            for (uint32_t e = sm.ncum[b] + lane; e < sm.ncum[b + 1]; e += 64)
-                atomicAdd(&f[arr[e] & (kLows - 1)], 1u);
-            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
-            __builtin_amdgcn_wave_barrier();
-            const uint32_t incl = wave_scan_incl_u32(f[lane]);
-            // smallest place whose inclusive count exceeds the rank inside the bucket
-            const unsigned long long over = __ballot(incl > r_in);
-            const int place = __ffsll((long long)over) - 1;
-            c = value_of_key((b << kLowBits) | (uint32_t)place);
+            if (sub == 0) sm.cent[j] = c;
         }
-        if (lane == 0) sm.cent[j] = c;
     }
     __syncthreads();
+    KM_T(6);
 
-    // ---- wave 0 state: lane p = sorted position p
-    float c_sorted = INFINITY, hi = INFINITY;
-    int own = lane, owner_lo = lane, owner_hi = 0;
-    bool have_hi = false;
+    // ---- every wavefront keeps the same state: lane p = sorted position p.  Only the
+    //      per-boundary bucket scans are shared out; one barrier per round publishes them.
+    float c_sorted, hi;
+    int own, owner_lo, owner_hi;
+    bool have_hi;
+    rank_levels<K>(lane < K ? sm.cent[lane] : INFINITY, c_sorted, own, hi, owner_lo, owner_hi, have_hi);
     uint32_t tk = kKeyInf, tk_prev = 0xffffffffu;
-    if (wave == 0) {
-        const float c = lane < K ? sm.cent[lane] : INFINITY;
-        rank_levels<K>(c, c_sorted, own, hi, owner_lo, owner_hi, have_hi);
-    }
+    const int p_mine = tid / L;  // the boundary this lane helps with
 
     for (int round = 0;; ++round) {
-        if (wave == 0) {
-            tk = kKeyInf;
-            if (have_hi) tk = boundary_key(c_sorted, hi, owner_lo, owner_hi);
-            // no boundary moved: the iteration sits on its fixed point
-            const unsigned long long moved = __ballot(lane < K - 1 && tk != tk_prev);
-            tk_prev = tk;
-            if (lane < K) {
-                sm.thr[lane] = tk;
-                sm.perm[lane] = own;
-                sm.cent[own] = c_sorted;
-            }
-            const unsigned long long shuffled = __ballot(lane < K && own != lane);
-            if (lane == 0) {
-                sm.identity = shuffled == 0ull;
-                sm.done = round == a.iters || moved == 0ull;
-            }
-        }
-        __syncthreads();
-        if (sm.done) break;
-        // a wavefront per boundary: the part of its bucket that lies below it
-        for (int p = wave; p < K - 1; p += nw) {
-            const uint32_t t = sm.thr[p];
+        tk = kKeyInf;
+        if (have_hi) tk = boundary_key(c_sorted, hi, owner_lo, owner_hi);
+        // no boundary moved: the iteration sits on its fixed point
+        const bool moved = __ballot(lane < K - 1 && tk != tk_prev) != 0ull;
+        tk_prev = tk;
+        if (round == a.iters || !moved) break;
+        // L lanes per boundary: the part of its bucket that lies below it
+        const uint32_t t = __shfl(tk, p_mine, CMPQ_WAVE);
+        if (p_mine < K - 1) {
             uint32_t n = 0, l = 0;
             if (t != kKeyInf) {
                 const uint32_t b = t >> kLowBits;
-                scan_bucket(arr, sm.ncum[b], sm.ncum[b + 1], t, n, l);
+                scan_bucket<L>(arr, sm.ncum[b], sm.ncum[b + 1], t & (kLows - 1), n, l);
             }
-            if (lane == 0) {
-                sm.part_n[p] = n;
-                sm.part_l[p] = l;
+            if ((tid & (L - 1)) == 0) {
+                sm.part_n[round & 1][p_mine] = n;
+                sm.part_l[round & 1][p_mine] = l;
             }
         }
         __syncthreads();
-        if (wave == 0) {
-            // cumulative count and sum at each boundary; the last position takes everything
-            uint32_t n_below = M;
-            long long s_below = sm.scum[kBuckets];
-            if (lane < K - 1 && tk != kKeyInf) {
-                const uint32_t b = tk >> kLowBits;
-                const uint32_t cnt = sm.part_n[lane];
-                long long q0, step;
-                bucket_affine(b, q0, step);
-                n_below = sm.ncum[b] + cnt;
-                s_below = sm.scum[b] + (long long)cnt * q0 + step * (long long)sm.part_l[lane];
-            }
-            uint32_t n_prev = __shfl_up(n_below, 1, CMPQ_WAVE);
-            long long s_prev = __shfl_up(s_below, 1, CMPQ_WAVE);
-            if (lane == 0) {
-                n_prev = 0;
-                s_prev = 0;
-            }
-            const uint32_t n_cell = n_below - n_prev;
-            const long long s_cell = s_below - s_prev;
-            float c = c_sorted;
-            if (lane < K && n_cell > 0)
-                c = (float)(((double)s_cell * 5.9604644775390625e-08) / (double)n_cell);
-            // usual case: the levels are still strictly ascending in the old order
-            const float c_up = __shfl_down(c, 1, CMPQ_WAVE);
-            const int own_up = __shfl_down(own, 1, CMPQ_WAVE);
-            const unsigned long long bad = __ballot(lane < K - 1 && !(c < c_up));
-            if (bad == 0ull) {
-                c_sorted = c;
-                hi = c_up;
-                owner_lo = own;
-                owner_hi = own_up;
-                have_hi = lane < K - 1;
-            } else {
-                // bring the values back to level order and rank them again
-                float c_level = INFINITY;
+        // cumulative count and sum at each boundary; the last position takes everything
+        uint32_t n_below = M;
+        long long s_below = sm.scum[kBuckets];
+        if (lane < K - 1 && tk != kKeyInf) {
+            const uint32_t b = tk >> kLowBits;
+            const uint32_t cnt = sm.part_n[round & 1][lane];
+            long long q0, step;
+            bucket_affine(b, q0, step);
+            n_below = sm.ncum[b] + cnt;
+            s_below = sm.scum[b] + (long long)cnt * q0 + step * (long long)sm.part_l[round & 1][lane];
+        }
+        // sorted positions live in lanes 0..15, one DPP row: neighbours come by row shifts
+        const uint32_t n_prev = row_from_below(n_below);
+        const long long s_prev = (long long)(((unsigned long long)row_from_below((uint32_t)((unsigned long long)s_below >> 32)) << 32) |
+                                             row_from_below((uint32_t)s_below));
+        const uint32_t n_cell = n_below - n_prev;
+        const long long s_cell = s_below - s_prev;
+        float c = c_sorted;
+        if (lane < K && n_cell > 0)
+            c = (float)(((double)s_cell * 5.9604644775390625e-08) / (double)n_cell);
+        // usual case: the levels are still strictly ascending in the old order
+        const float c_up = __uint_as_float(row_from_above(__float_as_uint(c)));
+        const int own_up = (int)row_from_above((uint32_t)own);
+        const unsigned long long bad = __ballot(lane < K - 1 && !(c < c_up));
+        if (bad == 0ull) {
+            c_sorted = c;
+            hi = c_up;
+            owner_lo = own;
+            owner_hi = own_up;
+            have_hi = lane < K - 1;
+        } else {
+            // bring the values back to level order and rank them again
+            float c_level = INFINITY;
 #pragma unroll
-                for (int l = 0; l < K; ++l) {
-                    const int ol = __shfl(own, l, CMPQ_WAVE);
-                    const float cl = __shfl(c, l, CMPQ_WAVE);
-                    if (ol == lane) c_level = cl;
-                }
-                rank_levels<K>(c_level, c_sorted, own, hi, owner_lo, owner_hi, have_hi);
+            for (int l = 0; l < K; ++l) {
+                const int ol = __shfl(own, l, CMPQ_WAVE);
+                const float cl = __shfl(c, l, CMPQ_WAVE);
+                if (ol == lane) c_level = cl;
             }
+            rank_levels<K>(c_level, c_sorted, own, hi, owner_lo, owner_hi, have_hi);
         }
     }
+    if (wave == 0 && lane < K) sm.cent[own] = c_sorted;  // read back by the caller after a barrier
+    KM_T(7);
 
-    // ---- final coding: 4 codes per lane and store
+    // ---- final coding: 4 codes per lane and store.  Boundaries and the position -> level
+    //      map come out of this wavefront's own lanes.
     uint32_t thr[CMPQ_KMAX];
 #pragma unroll
-    for (int p = 0; p < K - 1; ++p) thr[p] = sm.thr[p];
+    for (int p = 0; p < K - 1; ++p) thr[p] = (uint32_t)__builtin_amdgcn_readlane((int)tk, p);
+    const bool ident = __ballot(lane < K && own != lane) == 0ull;
     uint32_t *crow = reinterpret_cast<uint32_t *>(a.codes + i * a.d_out);
-    const bool ident = sm.identity;
 #pragma unroll
     for (int k = 0; k < G; ++k) {
         const int g = k * T + tid;
-        if (g < n_groups) {
-            uint32_t word = 0;
+        uint32_t word = 0;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                uint32_t pos = cell_of<K>(elem_key<G>(keys, k, e), thr);
-                if (!ident) pos = (uint32_t)sm.perm[pos];
-                word |= pos << (8 * e);
-            }
-            crow[g] = word;
+        for (int e = 0; e < 4; ++e) {  // all lanes take part: the level look-up crosses lanes
+            uint32_t pos = cell_of<K>(elem_key<G>(keys, k, e), thr);
+            if (!ident) pos = (uint32_t)__shfl(own, (int)pos, CMPQ_WAVE);
+            word |= pos << (8 * e);
         }
+        if (g < n_groups) crow[g] = word;
     }
+    __syncthreads();
+    KM_T(8);
 }
 
-template <int G, int TMAX>
-__global__ __launch_bounds__(TMAX) void kmeans_bucket_kernel(KmArgs a) {
-    // dynamic LDS: keys ordered by bucket | removed-entry bitmap (one bit per weight) |
-    // a table used three times in a row: per-bucket sums of places, then the scatter
-    // cursors, then one 64-entry table per wavefront for the start-up
+#ifndef CMPQ_KM_WAVES
+#define CMPQ_KM_WAVES 6
+#endif
+template <int G, int T>
+__global__ __launch_bounds__(T) __attribute__((amdgpu_waves_per_eu(T <= 256 ? CMPQ_KM_WAVES : 4, 8))) void kmeans_bucket_kernel(KmArgs a) {
+    // dynamic LDS: places of the kept weights, ordered by bucket (a byte each; the bucket
+    // follows from the position) | removed-entry bitmap (one bit per weight) | the scatter
+    // cursors
     extern __shared__ __align__(16) unsigned char dyn[];
     __shared__ BucketShared sm;
     const int64_t i = blockIdx.x;
-    const int T = blockDim.x, tid = threadIdx.x;
+    const int tid = threadIdx.x;
     const int d_out = (int)a.d_out, n_groups = d_out >> 2;
     const int b = a.bits[i];
     float *crow = a.centroids + i * CMPQ_KMAX;
@@ -389,11 +433,11 @@ __global__ __launch_bounds__(TMAX) void kmeans_bucket_kernel(KmArgs a) {
         return;
     }
     const int K = 1 << b;
-    unsigned short *arr = reinterpret_cast<unsigned short *>(dyn);
-    uint32_t *removed = reinterpret_cast<uint32_t *>(dyn + (((size_t)d_out * 2 + 15) & ~(size_t)15));
+    KM_T0();
+    unsigned char *arr = dyn;
+    uint32_t *removed = reinterpret_cast<uint32_t *>(dyn + (((size_t)d_out + 15) & ~(size_t)15));
     const int n_words = (d_out + 31) >> 5;
-    uint32_t *fine = removed + ((n_words + 3) & ~3);
-    uint32_t *lsum = fine;
+    uint32_t *cursor = removed + ((n_words + 3) & ~3);
 
     // ---- load: lane owns groups g = k*T + tid of 4 weights, kept as packed 16-bit keys
     const uint2 *wrow = reinterpret_cast<const uint2 *>(static_cast<const __half *>(a.W) + i * a.ldw);
@@ -430,9 +474,9 @@ __global__ __launch_bounds__(TMAX) void kmeans_bucket_kernel(KmArgs a) {
         }
         sm.n_excl = (int)lo - sm.seg_lo;
     }
-    for (int s = tid; s <= kBuckets; s += T) sm.ncum[s] = 0;
-    for (int s = tid; s < kBuckets; s += T) lsum[s] = 0;
+    for (int s = tid; s < kBuckets; s += T) sm.scum[s] = 0;  // first: count << 32 | sum of places
     for (int s = tid; s < n_words; s += T) removed[s] = 0;
+    KM_T(0);
     if (!__syncthreads_and(finite)) {  // leave the channel to the general kernel
         if (tid == 0) a.deferred[i] = 1;
         return;
@@ -447,6 +491,7 @@ __global__ __launch_bounds__(TMAX) void kmeans_bucket_kernel(KmArgs a) {
     }
     __syncthreads();
 
+    KM_T(1);
     // ---- bucket tables: counts and sums of places of the kept weights
     uint32_t kept[G];  // 4 bits per group: which of its weights are kept
 #pragma unroll
@@ -459,13 +504,14 @@ __global__ __launch_bounds__(TMAX) void kmeans_bucket_kernel(KmArgs a) {
             for (int e = 0; e < 4; ++e) {
                 if ((kept[k] >> e) & 1u) {
                     const uint32_t key = elem_key<G>(keys, k, e);
-                    atomicAdd(&sm.ncum[key >> kLowBits], 1u);
-                    atomicAdd(&lsum[key >> kLowBits], key & (kLows - 1));
+                    atomicAdd(reinterpret_cast<unsigned long long *>(&sm.scum[key >> kLowBits]),
+                              (1ull << 32) | (key & (kLows - 1)));
                 }
             }
         }
     }
     __syncthreads();
+    KM_T(2);
     // ---- exclusive prefixes over buckets of count and exact sum; scatter cursors
     {
         const int per = kBuckets / T > 0 ? kBuckets / T : 1;  // T is a power of two <= 1024
@@ -474,25 +520,26 @@ __global__ __launch_bounds__(TMAX) void kmeans_bucket_kernel(KmArgs a) {
         long long s_loc = 0;
         if (b0 < kBuckets) {
             for (int r = 0; r < per; ++r) {
-                const uint32_t n = sm.ncum[b0 + r];
+                const unsigned long long packed = (unsigned long long)sm.scum[b0 + r];
                 long long q0, step;
                 bucket_affine((uint32_t)(b0 + r), q0, step);
-                n_loc += n;
-                s_loc += (long long)n * q0 + step * (long long)lsum[b0 + r];
+                n_loc += (uint32_t)(packed >> 32);
+                s_loc += (long long)(packed >> 32) * q0 + step * (long long)(packed & 0xffffffffu);
             }
         }
-        uint32_t n_tot;
-        unsigned long long s_tot;
-        uint32_t n_run = block_scan_excl_u32(n_loc, sm.scan32, &n_tot);
-        long long s_run = (long long)block_scan_excl_u64((unsigned long long)s_loc, sm.scan64, &s_tot);
+        uint32_t n_run, n_tot;
+        unsigned long long s_run_u, s_tot;
+        block_scan_excl_pair(n_loc, (unsigned long long)s_loc, sm.scan32, sm.scan64, n_run, s_run_u, n_tot, s_tot);
+        long long s_run = (long long)s_run_u;
         if (b0 < kBuckets) {
             for (int r = 0; r < per; ++r) {
-                const uint32_t n = sm.ncum[b0 + r];
+                const unsigned long long packed = (unsigned long long)sm.scum[b0 + r];
+                const uint32_t n = (uint32_t)(packed >> 32);
                 long long q0, step;
                 bucket_affine((uint32_t)(b0 + r), q0, step);
-                const long long sb = (long long)n * q0 + step * (long long)lsum[b0 + r];
+                const long long sb = (long long)n * q0 + step * (long long)(packed & 0xffffffffu);
                 sm.ncum[b0 + r] = n_run;
-                lsum[b0 + r] = n_run;  // from here on: where the next key of the bucket goes
+                cursor[b0 + r] = n_run;  // where the next place of the bucket goes
                 sm.scum[b0 + r] = s_run;
                 n_run += n;
                 s_run += sb;
@@ -505,6 +552,7 @@ __global__ __launch_bounds__(TMAX) void kmeans_bucket_kernel(KmArgs a) {
     }
     __syncthreads();
     const uint32_t M = sm.ncum[kBuckets];
+    KM_T(3);
     // ---- scatter the kept keys, ordered by bucket
 #pragma unroll
     for (int k = 0; k < G; ++k) {
@@ -512,33 +560,34 @@ __global__ __launch_bounds__(TMAX) void kmeans_bucket_kernel(KmArgs a) {
         for (int e = 0; e < 4; ++e) {
             if ((kept[k] >> e) & 1u) {
                 const uint32_t key = elem_key<G>(keys, k, e);
-                const uint32_t pos = atomicAdd(&lsum[key >> kLowBits], 1u);
-                arr[pos] = (unsigned short)key;
+                const uint32_t pos = atomicAdd(&cursor[key >> kLowBits], 1u);
+                arr[pos] = (unsigned char)(key & (kLows - 1));
             }
         }
     }
     __syncthreads();
+    KM_T(4);
 
     switch (K) {
-        case 2: lloyd_bucket<G, 2>(a, i, sm, arr, fine, keys, n_groups, M); break;
-        case 4: lloyd_bucket<G, 4>(a, i, sm, arr, fine, keys, n_groups, M); break;
-        case 8: lloyd_bucket<G, 8>(a, i, sm, arr, fine, keys, n_groups, M); break;
-        default: lloyd_bucket<G, 16>(a, i, sm, arr, fine, keys, n_groups, M); break;
+        case 2: lloyd_bucket<G, 2, T>(a, i, sm, arr, keys, n_groups, M); break;
+        case 4: lloyd_bucket<G, 4, T>(a, i, sm, arr, keys, n_groups, M); break;
+        case 8: lloyd_bucket<G, 8, T>(a, i, sm, arr, keys, n_groups, M); break;
+        default: lloyd_bucket<G, 16, T>(a, i, sm, arr, keys, n_groups, M); break;
     }
+    KM_T(5);
     if (tid < CMPQ_KMAX) crow[tid] = tid < K ? sm.cent[tid] : INFINITY;
 }
 
 size_t bucket_dyn_lds(int64_t d_out, int64_t T) {
-    size_t b = ((size_t)d_out * 2 + 15) & ~(size_t)15;
+    size_t b = ((size_t)d_out + 15) & ~(size_t)15;
     b += (size_t)((((d_out + 31) >> 5) + 3) & ~3) * 4;
-    const size_t table = (size_t)(T / 64) * kLows;
-    b += (table > (size_t)kBuckets ? table : (size_t)kBuckets) * 4;
+    b += (size_t)kBuckets * 4;
     return b;
 }
 
-template <int G, int TMAX>
-int launch_variant(const KmArgs &a, int64_t T, hipStream_t s) {
-    auto kern = kmeans_bucket_kernel<G, TMAX>;
+template <int G, int T>
+int launch_variant(const KmArgs &a, hipStream_t s) {
+    auto kern = kmeans_bucket_kernel<G, T>;
     const size_t lds = bucket_dyn_lds(a.d_out, T);
     if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
@@ -553,17 +602,24 @@ int launch_variant(const KmArgs &a, int64_t T, hipStream_t s) {
 }  // namespace
 
 int launch_kmeans_hist(const KmArgs &a, hipStream_t s) {
-    // a power-of-two workgroup with at most 32 weights per lane
+    // A power-of-two workgroup of at most 512 lanes: up to 32 weights per lane, 64 for the
+    // longest channels (two workgroups of 512 share a compute unit where one of 1024
+    // would leave it idle at every barrier).
     const int64_t groups = a.d_out / 4;
     int64_t T = 64;
-    while (T < 1024 && T * 8 < groups) T <<= 1;
-    if (T * 8 < groups) return CMPQ_ESHAPE;
+    while (T < 512 && T * 8 < groups) T <<= 1;
     const int64_t per_lane = cdiv(groups, T);
+    if (per_lane > 16) return CMPQ_ESHAPE;
+    if (per_lane > 8) return launch_variant<16, 512>(a, s);
     if (per_lane > 4) {
-        if (T > 256) return launch_variant<8, 1024>(a, T, s);
-        return launch_variant<8, 256>(a, T, s);
+        switch (T) {
+            case 512: return launch_variant<8, 512>(a, s);
+            case 256: return launch_variant<8, 256>(a, s);
+            case 128: return launch_variant<8, 128>(a, s);
+            default: return launch_variant<8, 64>(a, s);
+        }
     }
-    if (per_lane > 2) return launch_variant<4, 64>(a, T, s);
-    if (per_lane > 1) return launch_variant<2, 64>(a, T, s);
-    return launch_variant<1, 64>(a, T, s);
+    if (per_lane > 2) return launch_variant<4, 64>(a, s);
+    if (per_lane > 1) return launch_variant<2, 64>(a, s);
+    return launch_variant<1, 64>(a, s);
 }
