@@ -80,6 +80,39 @@ __device__ __forceinline__ uint32_t block_scan_excl_u32(uint32_t v, uint32_t *sc
     return scratch[wave] + incl - v;
 }
 
+// Exclusive scan of two values per thread at once (one set of barriers).  `scratch`
+// holds at least 34 uint32 in LDS.  Contains barriers: call from all threads.
+__device__ __forceinline__ void block_scan_excl_2xu32(uint32_t a, uint32_t b, uint32_t *scratch,
+                                                      uint32_t &a_excl, uint32_t &b_excl,
+                                                      uint32_t &a_total, uint32_t &b_total) {
+    const int lane = threadIdx.x & (CMPQ_WAVE - 1), wave = threadIdx.x / CMPQ_WAVE;
+    const int nwave = (blockDim.x + CMPQ_WAVE - 1) / CMPQ_WAVE;
+    const uint32_t ai = wave_scan_incl_u32(a), bi = wave_scan_incl_u32(b);
+    __syncthreads();  // scratch may still be read from a previous call
+    if (lane == CMPQ_WAVE - 1) {
+        scratch[wave] = ai;
+        scratch[17 + wave] = bi;
+    }
+    __syncthreads();
+    if (wave == 0) {
+        const uint32_t wa = lane < nwave ? scratch[lane] : 0, wb = lane < nwave ? scratch[17 + lane] : 0;
+        const uint32_t wai = wave_scan_incl_u32(wa), wbi = wave_scan_incl_u32(wb);
+        if (lane < nwave) {
+            scratch[lane] = wai - wa;
+            scratch[17 + lane] = wbi - wb;
+        }
+        if (lane == nwave - 1) {
+            scratch[16] = wai;
+            scratch[33] = wbi;
+        }
+    }
+    __syncthreads();
+    a_total = scratch[16];
+    b_total = scratch[33];
+    a_excl = scratch[wave] + ai - a;
+    b_excl = scratch[17 + wave] + bi - b;
+}
+
 // fp32 bit pattern -> unsigned key with the same order as the value.
 __device__ __forceinline__ uint32_t f32_ordered_key(float f) {
     uint32_t u = __float_as_uint(f);

@@ -15,7 +15,7 @@ constexpr int kSelThreads = 1024;
 
 struct SelShared {
     uint32_t hist[256];
-    uint32_t scan[17];
+    uint32_t scan[34];
     uint32_t prefix, rem;
 };
 
@@ -48,15 +48,17 @@ __device__ void block_kth_largest(const float *__restrict__ keys, const uint8_t 
             if ((key & have_mask) == prefix) atomicAdd(&sh.hist[(key >> shift) & 255u], 1u);
         }
         __syncthreads();
-        if (threadIdx.x == 0) {
-            uint32_t rem = sh.rem, cum = 0;
-            int b = 255;
-            for (; b > 0; --b) {
-                if (cum + sh.hist[b] >= rem) break;
-                cum += sh.hist[b];
+        {
+            // walk the digits from the largest down, all at once: thread t looks at digit
+            // 255 - t and owns it when the rank falls inside its count
+            const uint32_t rem = sh.rem;
+            const uint32_t v = threadIdx.x < 256 ? sh.hist[255 - threadIdx.x] : 0u;
+            uint32_t total;
+            const uint32_t before = block_scan_excl_u32(v, sh.scan, &total);
+            if (threadIdx.x < 256 && v && before < rem && rem <= before + v) {
+                sh.rem = rem - before;  // rank inside the chosen digit
+                sh.prefix = prefix | ((uint32_t)(255 - threadIdx.x) << shift);
             }
-            sh.rem = rem - cum;  // rank inside the chosen digit
-            sh.prefix = prefix | ((uint32_t)b << shift);
         }
         have_mask |= 255u << shift;
         __syncthreads();
@@ -78,13 +80,17 @@ __global__ __launch_bounds__(kSelThreads) void top_channels_kernel(
         uint32_t key = 0;
         const bool in = i < d_in;
         if (in) key = stat_key(sumsq[i]);
-        const uint32_t tie = in && key == T;
-        uint32_t tie_total, sel_total;
-        const uint32_t tie_rank = tie_base + block_scan_excl_u32(tie, sh.scan, &tie_total);
-        const uint32_t sel = in && (key > T || (tie && tie_rank < need));
-        const uint32_t pos = out_base + block_scan_excl_u32(sel, sh.scan, &sel_total);
+        const uint32_t tie = in && key == T, gt = in && key > T;
+        // ties are taken in index order until `need` are in, so the number of taken ties
+        // before a position is min(ties before it, need): one scan gives both offsets
+        uint32_t tie_excl, gt_excl, tie_total, gt_total;
+        block_scan_excl_2xu32(tie, gt, sh.scan, tie_excl, gt_excl, tie_total, gt_total);
+        const uint32_t tie_rank = tie_base + tie_excl;
+        const uint32_t sel = gt || (tie && tie_rank < need);
+        const uint32_t pos = out_base + gt_excl + (min(tie_rank, need) - min(tie_base, need));
         if (sel && idx_out) idx_out[pos] = (int32_t)i;
         if (in && mask_out) mask_out[i] = (uint8_t)sel;
+        const uint32_t sel_total = gt_total + (min(tie_base + tie_total, need) - min(tie_base, need));
         tie_base += tie_total;
         out_base += sel_total;
     }
@@ -109,9 +115,9 @@ __global__ __launch_bounds__(kSelThreads) void allocate_bits_kernel(
         uint32_t key = 0;
         if (live) key = stat_key(sumsq[i]);
         const uint32_t tie1 = live && key == T1, tie2 = live && !all_mid && key == T2;
-        uint32_t t1_total, t2_total;
-        const uint32_t r1 = tie1_base + block_scan_excl_u32(tie1, sh.scan, &t1_total);
-        const uint32_t r2 = tie2_base + block_scan_excl_u32(tie2, sh.scan, &t2_total);
+        uint32_t t1_excl, t2_excl, t1_total, t2_total;
+        block_scan_excl_2xu32(tie1, tie2, sh.scan, t1_excl, t2_excl, t1_total, t2_total);
+        const uint32_t r1 = tie1_base + t1_excl, r2 = tie2_base + t2_excl;
         if (in) {
             int w;
             if (prot)
@@ -238,16 +244,23 @@ __global__ void wsel_init_kernel(WselState *st, uint32_t *hist, uint64_t k, int3
 }
 
 // PASS 0: digit = key >> 21 (11 bits), PASS 1: (key >> 10) & 2047, PASS 2: key & 1023.
+// The last pass also leaves, per workgroup, how many of its keys lie above the 22-bit
+// prefix and its own histogram of the last digit: once the threshold is known, the
+// counts that ordered compaction needs follow from these without another pass.
 template <typename TW, int PASS>
 __global__ __launch_bounds__(kWThreads) void wsel_hist_kernel(WselArgs a, const WselState *st,
-                                                               uint32_t *__restrict__ hist) {
+                                                               uint32_t *__restrict__ hist,
+                                                               uint32_t *__restrict__ above,
+                                                               uint32_t *__restrict__ local_last) {
     __shared__ uint32_t lh[kBins];
     __shared__ float lut[CMPQ_KMAX];
+    __shared__ uint32_t red[kWThreads / CMPQ_WAVE];
     for (int b = threadIdx.x; b < kBins; b += kWThreads) lh[b] = 0;
     const uint32_t prefix = PASS == 0 ? 0u : st->prefix;
     const int64_t q0 = (int64_t)blockIdx.x * a.chunks_per_block;
     const int64_t q1 = min(a.total_chunks, q0 + a.chunks_per_block);
     int64_t cur = -1;
+    uint32_t n_above = 0;
     for (int64_t q = q0; q < q1; ++q) {
         const int64_t i = q / a.chunks_per_channel, c = q % a.chunks_per_channel;
         if (!channel_live(a, i)) continue;
@@ -267,12 +280,24 @@ __global__ __launch_bounds__(kWThreads) void wsel_hist_kernel(WselArgs a, const 
                 if ((key[j] >> 21) == (prefix >> 21)) atomicAdd(&lh[(key[j] >> 10) & 2047u], 1u);
             } else {
                 if ((key[j] >> 10) == (prefix >> 10)) atomicAdd(&lh[key[j] & 1023u], 1u);
+                n_above += (key[j] >> 10) > (prefix >> 10);
             }
         }
     }
     __syncthreads();
     for (int b = threadIdx.x; b < kBins; b += kWThreads)
         if (lh[b]) atomicAdd(&hist[PASS * kBins + b], lh[b]);
+    if (PASS == 2) {
+        for (int b = threadIdx.x; b < 1024; b += kWThreads) local_last[(int64_t)blockIdx.x * 1024 + b] = lh[b];
+        n_above = wave_sum_u32(n_above);
+        if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = n_above;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            uint32_t t = 0;
+            for (int w = 0; w < kWThreads / CMPQ_WAVE; ++w) t += red[w];
+            above[blockIdx.x] = t;
+        }
+    }
 }
 
 // One workgroup of 1024 threads, two bins each: find the digit holding rank `rem`.
@@ -318,50 +343,28 @@ __global__ __launch_bounds__(1024) void wsel_pick_kernel(WselState *st, const ui
     }
 }
 
-template <typename TW>
-__global__ __launch_bounds__(kWThreads) void wsel_count_kernel(WselArgs a, const WselState *st,
+// Per workgroup of the passes: keys above the threshold and keys equal to it, from the
+// tables the last histogram pass left.
+__global__ __launch_bounds__(kWThreads) void wsel_count_kernel(const WselState *st,
+                                                                const uint32_t *__restrict__ above,
+                                                                const uint32_t *__restrict__ local_last,
                                                                 uint32_t *__restrict__ cnt_gt,
                                                                 uint32_t *__restrict__ cnt_eq) {
-    __shared__ float lut[CMPQ_KMAX];
-    __shared__ uint32_t red[2][kWThreads / CMPQ_WAVE];
-    const uint32_t T = st->T;
-    const int64_t q0 = (int64_t)blockIdx.x * a.chunks_per_block;
-    const int64_t q1 = min(a.total_chunks, q0 + a.chunks_per_block);
-    uint32_t gt = 0, eq = 0;
-    int64_t cur = -1;
-    for (int64_t q = q0; q < q1; ++q) {
-        const int64_t i = q / a.chunks_per_channel, c = q % a.chunks_per_channel;
-        if (!channel_live(a, i)) continue;
-        if (i != cur) {
-            stage_lut(a, i, lut);
-            cur = i;
-        }
-        uint32_t key[8];
-        float wv[8];
-        const uint32_t valid = load_keys8<TW>(a, i, c * kChunk + threadIdx.x * kWPerThread, lut, key, wv);
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const bool v = (valid >> j) & 1u;
-            gt += v && key[j] > T;
-            eq += v && key[j] == T;
-        }
-    }
+    __shared__ uint32_t red[kWThreads / CMPQ_WAVE];
+    const uint32_t digit = st->T & 1023u;
+    const bool everything = st->need == ~0ull;  // more asked than there is: every candidate counts
+    const uint32_t *h = local_last + (int64_t)blockIdx.x * 1024;
+    uint32_t gt = 0;
+    for (int b = threadIdx.x; b < 1024; b += kWThreads)
+        if (everything ? b > 0 : (uint32_t)b > digit) gt += h[b];
     gt = wave_sum_u32(gt);
-    eq = wave_sum_u32(eq);
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    if (lane == 0) {
-        red[0][wave] = gt;
-        red[1][wave] = eq;
-    }
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = gt;
     __syncthreads();
     if (threadIdx.x == 0) {
-        uint32_t g = 0, e = 0;
-        for (int w = 0; w < kWThreads / CMPQ_WAVE; ++w) {
-            g += red[0][w];
-            e += red[1][w];
-        }
+        uint32_t g = above[blockIdx.x];
+        for (int w = 0; w < kWThreads / CMPQ_WAVE; ++w) g += red[w];
         cnt_gt[blockIdx.x] = g;
-        cnt_eq[blockIdx.x] = e;
+        cnt_eq[blockIdx.x] = h[everything ? 0 : digit];
     }
 }
 
@@ -398,7 +401,7 @@ __global__ __launch_bounds__(kWThreads) void wsel_write_kernel(
     const uint64_t *__restrict__ out_base, int64_t k, int32_t *__restrict__ idx_out,
     uint16_t *__restrict__ val_out) {
     __shared__ float lut[CMPQ_KMAX];
-    __shared__ uint32_t scan[17];
+    __shared__ uint32_t scan[34];
     const uint32_t T = st->T;
     const uint64_t need = st->need;
     uint64_t ties = tie_base[blockIdx.x], outp = out_base[blockIdx.x];
@@ -416,27 +419,29 @@ __global__ __launch_bounds__(kWThreads) void wsel_write_kernel(
         float wv[8];
         const int64_t o0 = c * kChunk + threadIdx.x * kWPerThread;
         const uint32_t valid = load_keys8<TW>(a, i, o0, lut, key, wv);
-        uint32_t n_eq = 0;
+        uint32_t n_eq = 0, n_gt = 0;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) n_eq += ((valid >> j) & 1u) && key[j] == T;
-        uint32_t eq_total, sel_total;
-        uint64_t my_tie = ties + block_scan_excl_u32(n_eq, scan, &eq_total);
-        uint32_t sel = 0, n_sel = 0;
+        for (int j = 0; j < 8; ++j) {
+            const bool v = (valid >> j) & 1u;
+            n_eq += v && key[j] == T;
+            n_gt += v && key[j] > T;
+        }
+        // ties are taken in index order until `need` are in: the number of taken ties before
+        // a position is min(ties before it, need), so one scan places everything
+        uint32_t eq_excl, gt_excl, eq_total, gt_total;
+        block_scan_excl_2xu32(n_eq, n_gt, scan, eq_excl, gt_excl, eq_total, gt_total);
+        uint64_t my_tie = ties + eq_excl;
+        const uint64_t taken_before = (my_tie < need ? my_tie : need) - (ties < need ? ties : need);
+        uint64_t pos = outp + gt_excl + taken_before;
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             if (!((valid >> j) & 1u)) continue;
-            bool s = key[j] > T;
+            bool sel = key[j] > T;
             if (key[j] == T) {
-                s = my_tie < need;
+                sel = my_tie < need;
                 ++my_tie;
             }
-            sel |= (uint32_t)s << j;
-            n_sel += s;
-        }
-        uint64_t pos = outp + block_scan_excl_u32(n_sel, scan, &sel_total);
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            if ((sel >> j) & 1u) {
+            if (sel) {
                 if ((int64_t)pos < k) {
                     idx_out[pos] = (int32_t)(i * a.d_out + o0 + j);
                     if (val_out) val_out[pos] = __half_as_ushort(__float2half_rn(wv[j]));
@@ -444,6 +449,9 @@ __global__ __launch_bounds__(kWThreads) void wsel_write_kernel(
                 ++pos;
             }
         }
+        const uint64_t ties_after = ties + eq_total;
+        const uint32_t sel_total =
+            gt_total + (uint32_t)((ties_after < need ? ties_after : need) - (ties < need ? ties : need));
         ties += eq_total;
         outp += sel_total;
     }
@@ -477,14 +485,16 @@ int launch_weight_select(const WselArgs &a, const WselPlan &p, int64_t k, int32_
     uint32_t *cnt_eq = carve.take<uint32_t>(kMaxBlocks);
     uint64_t *tie_base = carve.take<uint64_t>(kMaxBlocks);
     uint64_t *out_base = carve.take<uint64_t>(kMaxBlocks);
+    uint32_t *above = carve.take<uint32_t>(kMaxBlocks);
+    uint32_t *local_last = carve.take<uint32_t>((size_t)kMaxBlocks * 1024);
     wsel_init_kernel<<<64, 256, 0, s>>>(st, hist, (uint64_t)k, idx_out, k);
-    wsel_hist_kernel<TW, 0><<<p.nblocks, kWThreads, 0, s>>>(a, st, hist);
+    wsel_hist_kernel<TW, 0><<<p.nblocks, kWThreads, 0, s>>>(a, st, hist, above, local_last);
     wsel_pick_kernel<0><<<1, 1024, 0, s>>>(st, hist);
-    wsel_hist_kernel<TW, 1><<<p.nblocks, kWThreads, 0, s>>>(a, st, hist);
+    wsel_hist_kernel<TW, 1><<<p.nblocks, kWThreads, 0, s>>>(a, st, hist, above, local_last);
     wsel_pick_kernel<1><<<1, 1024, 0, s>>>(st, hist);
-    wsel_hist_kernel<TW, 2><<<p.nblocks, kWThreads, 0, s>>>(a, st, hist);
+    wsel_hist_kernel<TW, 2><<<p.nblocks, kWThreads, 0, s>>>(a, st, hist, above, local_last);
     wsel_pick_kernel<2><<<1, 1024, 0, s>>>(st, hist);
-    wsel_count_kernel<TW><<<p.nblocks, kWThreads, 0, s>>>(a, st, cnt_gt, cnt_eq);
+    wsel_count_kernel<<<p.nblocks, kWThreads, 0, s>>>(st, above, local_last, cnt_gt, cnt_eq);
     wsel_offsets_kernel<<<1, 1024, 0, s>>>(st, p.nblocks, cnt_gt, cnt_eq, tie_base, out_base);
     wsel_write_kernel<TW><<<p.nblocks, kWThreads, 0, s>>>(a, st, tie_base, out_base, k, idx_out, val_out);
     CMPQ_LAUNCH_CHECK();
@@ -503,6 +513,8 @@ size_t cmpq_ws_outlier_weights(int64_t, int64_t) {
     carve.take<uint32_t>(kMaxBlocks);
     carve.take<uint64_t>(kMaxBlocks);
     carve.take<uint64_t>(kMaxBlocks);
+    carve.take<uint32_t>(kMaxBlocks);
+    carve.take<uint32_t>((size_t)kMaxBlocks * 1024);
     return carve.need();
 }
 
