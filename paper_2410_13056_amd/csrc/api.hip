@@ -68,6 +68,42 @@ __global__ __launch_bounds__(256) void transpose_kernel(const T *__restrict__ sr
     }
 }
 
+// 2-byte elements, every dimension and leading dimension a multiple of 4, 8-byte aligned
+// bases: a lane moves 4 elements (8 bytes) per access on both sides of the LDS tile.
+__global__ __launch_bounds__(256) void transpose16_vec_kernel(const uint16_t *__restrict__ src,
+                                                              int64_t rows, int64_t cols,
+                                                              int64_t ld_src,
+                                                              uint16_t *__restrict__ dst,
+                                                              int64_t ld_dst) {
+    __shared__ uint16_t tile[kTile][kTile + 2];  // row stride 33 words: column reads spread over banks
+    const int t = threadIdx.x, q = t & 15, p = t >> 4;  // q: group of 4 along the fast axis
+    const int64_t r0 = (int64_t)blockIdx.y * kTile, c0 = (int64_t)blockIdx.x * kTile;
+    uint2 v[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const int64_t r = r0 + p + 16 * k, c = c0 + 4 * q;
+        v[k] = make_uint2(0, 0);
+        if (r < rows && c < cols) v[k] = *reinterpret_cast<const uint2 *>(src + r * ld_src + c);
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        uint32_t *w = reinterpret_cast<uint32_t *>(&tile[p + 16 * k][4 * q]);
+        w[0] = v[k].x;
+        w[1] = v[k].y;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const int c = p + 16 * k;  // row of dst inside the tile
+        const int64_t orow = c0 + c, ocol = r0 + 4 * q;
+        if (orow < cols && ocol < rows) {
+            const uint32_t a0 = tile[4 * q][c], a1 = tile[4 * q + 1][c];
+            const uint32_t a2 = tile[4 * q + 2][c], a3 = tile[4 * q + 3][c];
+            *reinterpret_cast<uint2 *>(dst + orow * ld_dst + ocol) = make_uint2(a0 | (a1 << 16), a2 | (a3 << 16));
+        }
+    }
+}
+
 }  // namespace
 
 extern "C" int cmpq_transpose(const void *src, int dtype, int64_t rows, int64_t cols,
@@ -80,7 +116,13 @@ extern "C" int cmpq_transpose(const void *src, int dtype, int64_t rows, int64_t 
     if (gy > 65535) return CMPQ_ESHAPE;
     dim3 grid((unsigned)gx, (unsigned)gy);
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (dtype == CMPQ_F16)
+    const bool vec = dtype == CMPQ_F16 && rows % 4 == 0 && cols % 4 == 0 && ld_src % 4 == 0 &&
+                     ld_dst % 4 == 0 && reinterpret_cast<uintptr_t>(src) % 8 == 0 &&
+                     reinterpret_cast<uintptr_t>(dst) % 8 == 0;
+    if (vec)
+        transpose16_vec_kernel<<<grid, 256, 0, st>>>(static_cast<const uint16_t *>(src), rows, cols,
+                                                     ld_src, static_cast<uint16_t *>(dst), ld_dst);
+    else if (dtype == CMPQ_F16)
         transpose_kernel<uint16_t><<<grid, 256, 0, st>>>(static_cast<const uint16_t *>(src), rows,
                                                          cols, ld_src, static_cast<uint16_t *>(dst),
                                                          ld_dst);

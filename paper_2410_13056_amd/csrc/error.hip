@@ -13,11 +13,55 @@ namespace {
 
 constexpr int kT = 256;
 
+// Eight consecutive weights of one channel and their codes, by vector loads when the
+// addresses allow it.  Returns the mask of entries that exist (o0 + j < d_out).
+template <typename TW>
+__device__ __forceinline__ uint32_t load8(const TW *__restrict__ wrow, const uint8_t *__restrict__ crow,
+                                          int64_t o0, int64_t d_out, bool vec_ok, float (&w)[8],
+                                          uint32_t (&c)[8]) {
+    if (vec_ok && o0 + 8 <= d_out) {
+        if constexpr (sizeof(TW) == 2) {
+            const uint4 raw = *reinterpret_cast<const uint4 *>(wrow + o0);
+            const __half2 *h = reinterpret_cast<const __half2 *>(&raw);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const float2 t = __half22float2(h[j]);
+                w[2 * j] = t.x;
+                w[2 * j + 1] = t.y;
+            }
+        } else {
+            const float4 r0 = *reinterpret_cast<const float4 *>(wrow + o0);
+            const float4 r1 = *reinterpret_cast<const float4 *>(wrow + o0 + 4);
+            w[0] = r0.x, w[1] = r0.y, w[2] = r0.z, w[3] = r0.w;
+            w[4] = r1.x, w[5] = r1.y, w[6] = r1.z, w[7] = r1.w;
+        }
+        const uint2 cr = *reinterpret_cast<const uint2 *>(crow + o0);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            c[j] = (cr.x >> (8 * j)) & 0xffu;
+            c[4 + j] = (cr.y >> (8 * j)) & 0xffu;
+        }
+        return 0xffu;
+    }
+    uint32_t valid = 0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        w[j] = 0.f;
+        c[j] = 0;
+        if (o0 + j < d_out) {
+            valid |= 1u << j;
+            w[j] = load_as_f32<TW>(wrow, o0 + j);
+            c[j] = crow[o0 + j];
+        }
+    }
+    return valid;
+}
+
 template <typename TW>
 __global__ __launch_bounds__(kT) void dequant_error_kernel(
     const TW *__restrict__ W, int64_t d_out, int64_t ldw, const float *__restrict__ centroids,
     const uint8_t *__restrict__ codes, const uint8_t *__restrict__ bits,
-    const int32_t *__restrict__ out_idx, int64_t n_out, double *__restrict__ err_ch) {
+    const int32_t *__restrict__ out_idx, int64_t n_out, double *__restrict__ err_ch, int vec_ok) {
     extern __shared__ uint32_t restored[];  // one bit per entry of the channel
     __shared__ float lut[CMPQ_KMAX];
     __shared__ double red[kT / CMPQ_WAVE];
@@ -53,15 +97,30 @@ __global__ __launch_bounds__(kT) void dequant_error_kernel(
     const TW *wrow = W + i * ldw;
     const uint8_t *crow = codes + i * d_out;
     double s = 0.0;
-    for (int64_t o = tid; o < d_out; o += kT) {
-        const float w = load_as_f32<TW>(wrow, o);
-        float what;
-        if (whole || ((restored[o >> 5] >> (o & 31)) & 1u))
-            what = __half2float(__float2half_rn(w));
-        else
-            what = lut[crow[o] & 15];
-        const double e = (double)w - (double)what;
-        s = fma(e, e, s);
+    // a lane takes 8 consecutive weights per step, two steps in flight
+    for (int64_t o0 = (int64_t)tid * 8; o0 < d_out; o0 += 2 * kT * 8) {
+        float w[2][8];
+        uint32_t c[2][8], valid[2];
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int64_t o = o0 + (int64_t)u * kT * 8;
+            valid[u] = o < d_out ? load8<TW>(wrow, crow, o, d_out, vec_ok, w[u], c[u]) : 0u;
+        }
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int64_t o = o0 + (int64_t)u * kT * 8;
+            if (!valid[u]) continue;
+            // o is a multiple of 8: the 8 flags sit in one byte of the bitmap
+            const uint32_t back = whole ? 0xffu : (restored[o >> 5] >> (o & 31)) & 0xffu;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                if (!((valid[u] >> j) & 1u)) continue;
+                const float what = ((back >> j) & 1u) ? __half2float(__float2half_rn(w[u][j]))
+                                                      : lut[c[u][j] & 15u];
+                const double e = (double)w[u][j] - (double)what;
+                s = fma(e, e, s);
+            }
+        }
     }
     s = wave_sum_f64(s);
     if ((tid & 63) == 0) red[tid >> 6] = s;
@@ -125,12 +184,15 @@ extern "C" int cmpq_dequant_error(const void *W, int dtype, int64_t d_in, int64_
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (d_in > 0) {
         const size_t lds = (size_t)cdiv(d_out > 0 ? d_out : 1, 32) * 4;
+        const int esz = dtype == CMPQ_F16 ? 2 : 4;
+        const int vec_ok = reinterpret_cast<uintptr_t>(W) % 16 == 0 && (ldw * esz) % 16 == 0 &&
+                           reinterpret_cast<uintptr_t>(codes) % 8 == 0 && d_out % 8 == 0;
         if (dtype == CMPQ_F16)
             dequant_error_kernel<__half><<<(unsigned)d_in, kT, lds, s>>>(
-                static_cast<const __half *>(W), d_out, ldw, centroids, codes, bits, out_idx, n_out, err_ch);
+                static_cast<const __half *>(W), d_out, ldw, centroids, codes, bits, out_idx, n_out, err_ch, vec_ok);
         else
             dequant_error_kernel<float><<<(unsigned)d_in, kT, lds, s>>>(
-                static_cast<const float *>(W), d_out, ldw, centroids, codes, bits, out_idx, n_out, err_ch);
+                static_cast<const float *>(W), d_out, ldw, centroids, codes, bits, out_idx, n_out, err_ch, vec_ok);
         CMPQ_LAUNCH_CHECK();
     }
     error_totals_kernel<<<1, 1024, 0, s>>>(err_ch, sumsq, d_in, err_total);

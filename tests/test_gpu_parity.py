@@ -99,7 +99,7 @@ def test_act_stats_is_reproducible(env):
 
 
 @pytest.mark.parametrize("dtype", [torch.float16, torch.float32])
-@pytest.mark.parametrize("rows,cols", [(1, 1), (64, 64), (65, 63), (512, 256), (1000, 3), (7, 900)])
+@pytest.mark.parametrize("rows,cols", [(1, 1), (64, 64), (65, 63), (512, 256), (1000, 3), (7, 900), (100, 260), (4, 8), (68, 4), (1024, 8192)])
 def test_transpose(env, dtype, rows, cols):
     src = torch.randn(rows, cols, device=DEV).to(dtype)
     dst = torch.empty(cols, rows, dtype=dtype, device=DEV)
