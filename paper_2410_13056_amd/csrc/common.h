@@ -20,6 +20,10 @@ static inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 __device__ __forceinline__ size_t align_up_dev(size_t x) { return (x + 15) & ~(size_t)15; }
 
+// seg[i] = number of entries of the ascending list idx[0..n) below i*d_out, i = 0..d_in.
+int launch_segment_offsets(const int32_t *idx, int64_t n, int64_t d_in, int64_t d_out, int32_t *seg,
+                           hipStream_t s);
+
 // Carves aligned pieces out of the caller's workspace; `need` ends up as the total.
 struct WsCarver {
     char *base;

@@ -61,7 +61,8 @@ template <typename TW>
 __global__ __launch_bounds__(kT) void dequant_error_kernel(
     const TW *__restrict__ W, int64_t d_out, int64_t ldw, const float *__restrict__ centroids,
     const uint8_t *__restrict__ codes, const uint8_t *__restrict__ bits,
-    const int32_t *__restrict__ out_idx, int64_t n_out, double *__restrict__ err_ch, int vec_ok) {
+    const int32_t *__restrict__ out_idx, const int32_t *__restrict__ slices,
+    double *__restrict__ err_ch, int vec_ok) {
     extern __shared__ uint32_t restored[];  // one bit per entry of the channel
     __shared__ float lut[CMPQ_KMAX];
     __shared__ double red[kT / CMPQ_WAVE];
@@ -74,19 +75,8 @@ __global__ __launch_bounds__(kT) void dequant_error_kernel(
     for (int w = tid; w < words; w += kT) restored[w] = 0;
     if (tid < CMPQ_KMAX) lut[tid] = centroids[i * CMPQ_KMAX + tid];
     if (tid == 0) {
-        const int64_t first = i * d_out, last = first + d_out;
-        int64_t lo = 0, hi = n_out;
-        while (lo < hi) {
-            const int64_t mid = (lo + hi) >> 1;
-            if (out_idx[mid] < first) lo = mid + 1; else hi = mid;
-        }
-        seg[0] = (int)lo;
-        hi = n_out;
-        while (lo < hi) {
-            const int64_t mid = (lo + hi) >> 1;
-            if (out_idx[mid] < last) lo = mid + 1; else hi = mid;
-        }
-        seg[1] = (int)lo;
+        seg[0] = slices ? slices[i] : 0;
+        seg[1] = slices ? slices[i + 1] : 0;
     }
     __syncthreads();
     for (int e = seg[0] + tid; e < seg[1]; e += kT) {
@@ -165,15 +155,15 @@ __global__ __launch_bounds__(1024) void error_totals_kernel(const double *__rest
 
 }  // namespace
 
-size_t cmpq_ws_dequant_error(int64_t) { return 256; }
+size_t cmpq_ws_dequant_error(int64_t d_in) {
+    return align_up((size_t)(d_in + 1) * sizeof(int32_t), 256);  // slice offsets of out_idx
+}
 
 extern "C" int cmpq_dequant_error(const void *W, int dtype, int64_t d_in, int64_t d_out,
                                   int64_t ldw, const float *centroids, const uint8_t *codes,
                                   const uint8_t *bits, const int32_t *out_idx, int64_t n_out,
                                   const float *sumsq, double *err_ch, double *err_total, void *ws,
                                   size_t ws_bytes, void *stream) {
-    (void)ws;
-    (void)ws_bytes;
     if (d_in < 0 || d_out < 0 || n_out < 0) return CMPQ_EINVAL;
     if (dtype != CMPQ_F16 && dtype != CMPQ_F32) return CMPQ_EINVAL;
     if (!bits || !centroids || !err_ch || !err_total || (n_out > 0 && !out_idx)) return CMPQ_EINVAL;
@@ -182,6 +172,14 @@ extern "C" int cmpq_dequant_error(const void *W, int dtype, int64_t d_in, int64_
     if (d_in > 0 && d_out > ((int64_t)1 << 31) / d_in) return CMPQ_ESHAPE;
     if (d_out > 1 << 20) return CMPQ_ESHAPE;  // the per-channel bitmap lives in LDS
     hipStream_t s = static_cast<hipStream_t>(stream);
+    const int32_t *slices = nullptr;
+    if (d_in > 0 && n_out > 0) {
+        if (!ws || reinterpret_cast<uintptr_t>(ws) % 256 != 0 || ws_bytes < cmpq_ws_dequant_error(d_in))
+            return CMPQ_EWORKSPACE;
+        const int rc = launch_segment_offsets(out_idx, n_out, d_in, d_out, static_cast<int32_t *>(ws), s);
+        if (rc != CMPQ_OK) return rc;
+        slices = static_cast<const int32_t *>(ws);
+    }
     if (d_in > 0) {
         const size_t lds = (size_t)cdiv(d_out > 0 ? d_out : 1, 32) * 4;
         const int esz = dtype == CMPQ_F16 ? 2 : 4;
@@ -189,10 +187,10 @@ extern "C" int cmpq_dequant_error(const void *W, int dtype, int64_t d_in, int64_
                            reinterpret_cast<uintptr_t>(codes) % 8 == 0 && d_out % 8 == 0;
         if (dtype == CMPQ_F16)
             dequant_error_kernel<__half><<<(unsigned)d_in, kT, lds, s>>>(
-                static_cast<const __half *>(W), d_out, ldw, centroids, codes, bits, out_idx, n_out, err_ch, vec_ok);
+                static_cast<const __half *>(W), d_out, ldw, centroids, codes, bits, out_idx, slices, err_ch, vec_ok);
         else
             dequant_error_kernel<float><<<(unsigned)d_in, kT, lds, s>>>(
-                static_cast<const float *>(W), d_out, ldw, centroids, codes, bits, out_idx, n_out, err_ch, vec_ok);
+                static_cast<const float *>(W), d_out, ldw, centroids, codes, bits, out_idx, slices, err_ch, vec_ok);
         CMPQ_LAUNCH_CHECK();
     }
     error_totals_kernel<<<1, 1024, 0, s>>>(err_ch, sumsq, d_in, err_total);

@@ -289,18 +289,8 @@ __global__ __launch_bounds__(kT) void kmeans_kernel(KmArgs a) {
     if (bad) sm.nonfinite = 1;
     // entries removed before clustering: the slice of out_idx that falls in this channel
     if (tid == 0) {
-        const int64_t first = i * a.d_out, last = first + a.d_out;
-        int64_t lo = 0, hi = a.n_out;
-        while (lo < hi) {
-            const int64_t mid = (lo + hi) >> 1;
-            if (a.out_idx[mid] < first) lo = mid + 1; else hi = mid;
-        }
-        sm.seg_lo = (int)lo;
-        hi = a.n_out;
-        while (lo < hi) {
-            const int64_t mid = (lo + hi) >> 1;
-            if (a.out_idx[mid] < last) lo = mid + 1; else hi = mid;
-        }
+        sm.seg_lo = a.seg ? a.seg[i] : 0;
+        const int64_t lo = a.seg ? a.seg[i + 1] : 0;
         sm.seg_hi = (int)lo;
     }
     __syncthreads();
@@ -361,7 +351,8 @@ extern "C" int cmpq_set_kmeans_algorithm(int algorithm) {
 }
 
 size_t cmpq_ws_kmeans(int64_t d_in, int64_t) {
-    return align_up((size_t)(d_in > 0 ? d_in : 1), 256);
+    // one byte per channel (deferred flags) | d_in + 1 slice offsets of out_idx
+    return align_up((size_t)(d_in > 0 ? d_in : 1), 256) + align_up((size_t)(d_in + 1) * sizeof(int32_t), 256);
 }
 
 extern "C" int cmpq_kmeans_quantize(const void *W, int dtype, int64_t d_in, int64_t d_out,
@@ -393,10 +384,17 @@ extern "C" int cmpq_kmeans_quantize(const void *W, int dtype, int64_t d_in, int6
     a.codes = codes;
     a.status = status;
     a.deferred = nullptr;
+    a.seg = nullptr;
     hipStream_t s = static_cast<hipStream_t>(stream);
+    if (!ws || reinterpret_cast<uintptr_t>(ws) % 256 != 0 || ws_bytes < cmpq_ws_kmeans(d_in, d_out))
+        return CMPQ_EWORKSPACE;
+    if (n_out > 0) {
+        int32_t *seg = reinterpret_cast<int32_t *>(static_cast<char *>(ws) + align_up((size_t)d_in, 256));
+        const int rc = launch_segment_offsets(out_idx, n_out, d_in, d_out, seg, s);
+        if (rc != CMPQ_OK) return rc;
+        a.seg = seg;
+    }
     if (kmeans_fast_eligible(a, dtype)) {
-        if (!ws || reinterpret_cast<uintptr_t>(ws) % 256 != 0 || ws_bytes < cmpq_ws_kmeans(d_in, d_out))
-            return CMPQ_EWORKSPACE;
         a.deferred = static_cast<uint8_t *>(ws);
         const int rc = g_kmeans_algorithm == CMPQ_KMEANS_DIRECT ? launch_kmeans_fast(a, s)
                                                                 : launch_kmeans_hist(a, s);

@@ -17,6 +17,8 @@ struct KmArgs {
     // channel it cannot hold (a magnitude of 128 or more, or a non-finite value); the
     // general kernel, launched after it, then handles exactly those channels.
     uint8_t *deferred;
+    // seg[i]..seg[i+1]: the slice of out_idx inside channel i (null when n_out is 0).
+    const int32_t *seg;
 };
 
 // Histogram k-means (kmeans_hist.hip) and fixed-point brute-force k-means

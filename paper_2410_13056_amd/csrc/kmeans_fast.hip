@@ -280,18 +280,8 @@ __global__ __launch_bounds__(1024) void kmeans_fast_kernel(KmArgs a) {
     }
     // ---- the slice of out_idx inside this channel
     if (tid == 0) {
-        const int64_t first = i * a.d_out, last = first + a.d_out;
-        int64_t lo = 0, hi = a.n_out;
-        while (lo < hi) {
-            const int64_t mid = (lo + hi) >> 1;
-            if (a.out_idx[mid] < first) lo = mid + 1; else hi = mid;
-        }
-        sm.seg_lo = (int)lo;
-        hi = a.n_out;
-        while (lo < hi) {
-            const int64_t mid = (lo + hi) >> 1;
-            if (a.out_idx[mid] < last) lo = mid + 1; else hi = mid;
-        }
+        sm.seg_lo = a.seg ? a.seg[i] : 0;
+        const int64_t lo = a.seg ? a.seg[i + 1] : 0;
         sm.n_excl = (int)lo - sm.seg_lo;
     }
     if (!__syncthreads_and(fits)) {  // leave the channel to the general kernel

@@ -460,18 +460,8 @@ __global__ __launch_bounds__(T) __attribute__((amdgpu_waves_per_eu(T <= 256 ? CM
         keys[2 * k + 1] = ky[2] | (ky[3] << 16);
     }
     if (tid == 0) {  // the slice of out_idx inside this channel
-        const int64_t first = i * a.d_out, last = first + a.d_out;
-        int64_t lo = 0, hi = a.n_out;
-        while (lo < hi) {
-            const int64_t mid = (lo + hi) >> 1;
-            if (a.out_idx[mid] < first) lo = mid + 1; else hi = mid;
-        }
-        sm.seg_lo = (int)lo;
-        hi = a.n_out;
-        while (lo < hi) {
-            const int64_t mid = (lo + hi) >> 1;
-            if (a.out_idx[mid] < last) lo = mid + 1; else hi = mid;
-        }
+        sm.seg_lo = a.seg ? a.seg[i] : 0;
+        const int64_t lo = a.seg ? a.seg[i + 1] : 0;
         sm.n_excl = (int)lo - sm.seg_lo;
     }
     for (int s = tid; s < kBuckets; s += T) sm.scum[s] = 0;  // first: count << 32 | sum of places
