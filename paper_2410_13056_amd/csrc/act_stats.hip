@@ -63,13 +63,13 @@ __global__ __launch_bounds__(kThreads) void act_stats_vec_kernel(const T *__rest
     if (col0 < d_in) {
         const T *p = X + col0;
         int64_t r = r_begin + wave;
-        // four rows in flight per wave
-        for (; r + 3 * kWaves < r_end; r += 4 * kWaves) {
-            float f[4][V];
+        // eight rows in flight per wave
+        for (; r + 7 * kWaves < r_end; r += 8 * kWaves) {
+            float f[8][V];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) Vec<T>::load(p + (r + u * kWaves) * ldx, f[u]);
+            for (int u = 0; u < 8; ++u) Vec<T>::load(p + (r + u * kWaves) * ldx, f[u]);
 #pragma unroll
-            for (int u = 0; u < 4; ++u)
+            for (int u = 0; u < 8; ++u)
 #pragma unroll
                 for (int v = 0; v < V; ++v) {
                     double d = (double)f[u][v];
@@ -118,21 +118,34 @@ __global__ __launch_bounds__(kThreads) void act_stats_any_kernel(const T *__rest
     partial[(int64_t)blockIdx.y * d_in + col] = s;
 }
 
+// 64 columns per workgroup; the four wavefronts each add a quarter of the row splits
+// (in split order), then the quarters are added in order: a fixed summation tree.
 __global__ __launch_bounds__(kThreads) void act_stats_finish_kernel(
     const double *__restrict__ partial, int splits, int64_t d_in, double *__restrict__ acc,
     float *__restrict__ sumsq, int accumulate, int32_t *__restrict__ status) {
-    const int64_t col = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    if (col >= d_in) return;
-    double t = accumulate ? acc[col] : 0.0;
-    for (int sidx = 0; sidx < splits; ++sidx) t += partial[(int64_t)sidx * d_in + col];
-    acc[col] = t;
-    if (sumsq) sumsq[col] = (float)t;
-    if (status && !isfinite(t)) atomicOr(status, CMPQ_STATUS_NONFINITE);
+    __shared__ double red[kWaves][CMPQ_WAVE];
+    const int lane = threadIdx.x & (CMPQ_WAVE - 1), wave = threadIdx.x / CMPQ_WAVE;
+    const int64_t col = (int64_t)blockIdx.x * CMPQ_WAVE + lane;
+    const int per = (splits + kWaves - 1) / kWaves;
+    const int s0 = wave * per, s1 = min(splits, s0 + per);
+    double t = 0.0;
+    if (col < d_in)
+        for (int sidx = s0; sidx < s1; ++sidx) t += partial[(int64_t)sidx * d_in + col];
+    red[wave][lane] = t;
+    __syncthreads();
+    if (wave == 0 && col < d_in) {
+        double r = accumulate ? acc[col] : 0.0;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) r += red[w][lane];
+        acc[col] = r;
+        if (sumsq) sumsq[col] = (float)r;
+        if (status && !isfinite(r)) atomicOr(status, CMPQ_STATUS_NONFINITE);
+    }
 }
 
 int64_t pick_splits(int64_t n, int64_t col_blocks) {
     if (n <= 0) return 0;
-    int64_t want = cdiv(4096, col_blocks);       // ~16 workgroups per compute unit
+    int64_t want = cdiv(2048, col_blocks);       // ~8 workgroups per compute unit
     int64_t cap = cdiv(n, 16 * kWaves);           // at least 16 rows per wave
     int64_t s = want < cap ? want : cap;
     return s < 1 ? 1 : s;
@@ -185,7 +198,7 @@ extern "C" int cmpq_act_stats(const void *X, int dtype, int64_t n, int64_t d_in,
         }
         CMPQ_LAUNCH_CHECK();
     }
-    act_stats_finish_kernel<<<(unsigned)cdiv(d_in, kThreads), kThreads, 0, st>>>(
+    act_stats_finish_kernel<<<(unsigned)cdiv(d_in, CMPQ_WAVE), kThreads, 0, st>>>(
         partial, (int)splits, d_in, acc, sumsq, accumulate, status);
     CMPQ_LAUNCH_CHECK();
     return CMPQ_OK;

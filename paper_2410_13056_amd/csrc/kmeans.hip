@@ -242,15 +242,11 @@ __device__ void quantile_start(KmSmall &sm, int K, int d_out, const TW *xs, cons
 }
 
 template <typename TW, bool WEIGHTED>
-__global__ __launch_bounds__(kT) void kmeans_kernel(KmArgs a) {
-    extern __shared__ __align__(16) unsigned char lds[];
-    __shared__ KmSmall sm;
-    const int64_t i = blockIdx.x;
+__device__ void kmeans_channel(const KmArgs &a, int64_t i, unsigned char *lds, KmSmall &sm) {
     const int tid = threadIdx.x, lane = tid & 63;
     const int d_out = (int)a.d_out;
     const int b = a.bits[i];
     float *crow = a.centroids + i * CMPQ_KMAX;
-    if (a.deferred && !a.deferred[i]) return;  // already done by the fixed-point kernel
     if (b < 1 || b > 4) {  // a channel of O_act: no levels, no codes
         if (tid < CMPQ_KMAX) crow[tid] = INFINITY;
         for (int o = tid; o < d_out; o += kT) a.codes[i * a.d_out + o] = 0;
@@ -318,6 +314,23 @@ __global__ __launch_bounds__(kT) void kmeans_kernel(KmArgs a) {
     if (tid < CMPQ_KMAX) crow[tid] = tid < K ? sm.cent[tid] : INFINITY;
 }
 
+// Without a `deferred` list: workgroup i takes channel i.  With one: a small grid walks
+// the list and takes the channels the first kernel left behind (usually none).
+template <typename TW, bool WEIGHTED>
+__global__ __launch_bounds__(kT) void kmeans_kernel(KmArgs a) {
+    extern __shared__ __align__(16) unsigned char lds[];
+    __shared__ KmSmall sm;
+    if (!a.deferred) {
+        kmeans_channel<TW, WEIGHTED>(a, blockIdx.x, lds, sm);
+        return;
+    }
+    for (int64_t i = blockIdx.x; i < a.d_in; i += gridDim.x) {
+        if (!a.deferred[i]) continue;
+        __syncthreads();  // LDS of the previous channel is no longer in use
+        kmeans_channel<TW, WEIGHTED>(a, i, lds, sm);
+    }
+}
+
 size_t kmeans_lds_bytes(int64_t d_out, size_t esz, bool weighted) {
     size_t b = align_up((size_t)d_out * esz, 16);
     b += align_up((size_t)cdiv(d_out, 64) * 8, 16);
@@ -335,7 +348,8 @@ int launch_kmeans(const KmArgs &a, hipStream_t s) {
         (void)hipGetLastError();
         return CMPQ_EHIP;
     }
-    kern<<<(unsigned)a.d_in, kT, lds, s>>>(a);
+    const int64_t grid = a.deferred ? (a.d_in < 256 ? a.d_in : 256) : a.d_in;
+    kern<<<(unsigned)grid, kT, lds, s>>>(a);
     CMPQ_LAUNCH_CHECK();
     return CMPQ_OK;
 }

@@ -47,12 +47,14 @@ extern "C" void cmpq_debug_read(unsigned long long *out) {
 
 namespace {
 
-constexpr int kLowBits = 6;
-constexpr int kBuckets = 1 << (16 - kLowBits);
-constexpr int kLows = 1 << kLowBits;
+// A key splits into bucket (top 16 - LB bits) and place (low LB bits).  LB = 6 (1024
+// buckets of 64 places) suits long channels; short ones take LB = 7 (512 buckets): the
+// tables shrink and more workgroups share a compute unit.
 constexpr uint32_t kKeyInf = 0xffffu;  // boundary above every key
 
+template <int LB>
 struct BucketShared {
+    static constexpr int kBuckets = 1 << (16 - LB);
     long long scum[kBuckets + 1];   // count << 32 | sum of places; then the exclusive prefix
                                     // over buckets of sum(x * 2^24)
     uint32_t ncum[kBuckets + 1];    // exclusive prefix over buckets of the counts
@@ -76,8 +78,9 @@ __device__ __forceinline__ float value_of_key(uint32_t k) {
 
 // x*2^24 of the first key of bucket b, and the step per place inside the bucket.
 // For a normal half (e >= 1) x*2^24 = (1024 + m) << (e - 1); a subnormal gives m.
+template <int LB>
 __device__ __forceinline__ void bucket_affine(uint32_t b, long long &q0, long long &step) {
-    const uint32_t h = half_of_key(b << kLowBits);
+    const uint32_t h = half_of_key(b << LB);
     const uint32_t e = (h >> 10) & 31u, m = h & 1023u;
     const uint32_t sh = (e > 1 ? e : 1) - 1;
     step = 1ll << sh;
@@ -273,11 +276,12 @@ __device__ __forceinline__ void scan_bucket(const unsigned char *arr, uint32_t b
     l = group_sum<L>(cl);
 }
 
-template <int G, int K, int T>
-__device__ __forceinline__ void lloyd_bucket(const KmArgs &a, int64_t i, BucketShared &sm,
+template <int G, int K, int T, int LB>
+__device__ __forceinline__ void lloyd_bucket(const KmArgs &a, int64_t i, BucketShared<LB> &sm,
                                              const unsigned char *arr,
                                              const uint32_t (&keys)[2 * G], int n_groups, uint32_t M) {
     constexpr int L = T / 16;  // lanes that share one boundary in a round
+    constexpr int kLowBits = LB, kLows = 1 << LB, kBuckets = 1 << (16 - LB);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     KM_T0();
 
@@ -349,7 +353,7 @@ __device__ __forceinline__ void lloyd_bucket(const KmArgs &a, int64_t i, BucketS
             const uint32_t b = tk >> kLowBits;
             const uint32_t cnt = sm.part_n[round & 1][lane];
             long long q0, step;
-            bucket_affine(b, q0, step);
+            bucket_affine<LB>(b, q0, step);
             n_below = sm.ncum[b] + cnt;
             s_below = sm.scum[b] + (long long)cnt * q0 + step * (long long)sm.part_l[round & 1][lane];
         }
@@ -413,13 +417,14 @@ __device__ __forceinline__ void lloyd_bucket(const KmArgs &a, int64_t i, BucketS
 #ifndef CMPQ_KM_WAVES
 #define CMPQ_KM_WAVES 6
 #endif
-template <int G, int T>
+template <int G, int T, int LB>
 __global__ __launch_bounds__(T) __attribute__((amdgpu_waves_per_eu(T <= 256 ? CMPQ_KM_WAVES : 4, 8))) void kmeans_bucket_kernel(KmArgs a) {
+    constexpr int kLowBits = LB, kLows = 1 << LB, kBuckets = 1 << (16 - LB);
     // dynamic LDS: places of the kept weights, ordered by bucket (a byte each; the bucket
     // follows from the position) | removed-entry bitmap (one bit per weight) | the scatter
     // cursors
     extern __shared__ __align__(16) unsigned char dyn[];
-    __shared__ BucketShared sm;
+    __shared__ BucketShared<LB> sm;
     const int64_t i = blockIdx.x;
     const int tid = threadIdx.x;
     const int d_out = (int)a.d_out, n_groups = d_out >> 2;
@@ -512,7 +517,7 @@ __global__ __launch_bounds__(T) __attribute__((amdgpu_waves_per_eu(T <= 256 ? CM
             for (int r = 0; r < per; ++r) {
                 const unsigned long long packed = (unsigned long long)sm.scum[b0 + r];
                 long long q0, step;
-                bucket_affine((uint32_t)(b0 + r), q0, step);
+                bucket_affine<LB>((uint32_t)(b0 + r), q0, step);
                 n_loc += (uint32_t)(packed >> 32);
                 s_loc += (long long)(packed >> 32) * q0 + step * (long long)(packed & 0xffffffffu);
             }
@@ -526,7 +531,7 @@ __global__ __launch_bounds__(T) __attribute__((amdgpu_waves_per_eu(T <= 256 ? CM
                 const unsigned long long packed = (unsigned long long)sm.scum[b0 + r];
                 const uint32_t n = (uint32_t)(packed >> 32);
                 long long q0, step;
-                bucket_affine((uint32_t)(b0 + r), q0, step);
+                bucket_affine<LB>((uint32_t)(b0 + r), q0, step);
                 const long long sb = (long long)n * q0 + step * (long long)(packed & 0xffffffffu);
                 sm.ncum[b0 + r] = n_run;
                 cursor[b0 + r] = n_run;  // where the next place of the bucket goes
@@ -559,26 +564,26 @@ __global__ __launch_bounds__(T) __attribute__((amdgpu_waves_per_eu(T <= 256 ? CM
     KM_T(4);
 
     switch (K) {
-        case 2: lloyd_bucket<G, 2, T>(a, i, sm, arr, keys, n_groups, M); break;
-        case 4: lloyd_bucket<G, 4, T>(a, i, sm, arr, keys, n_groups, M); break;
-        case 8: lloyd_bucket<G, 8, T>(a, i, sm, arr, keys, n_groups, M); break;
-        default: lloyd_bucket<G, 16, T>(a, i, sm, arr, keys, n_groups, M); break;
+        case 2: lloyd_bucket<G, 2, T, LB>(a, i, sm, arr, keys, n_groups, M); break;
+        case 4: lloyd_bucket<G, 4, T, LB>(a, i, sm, arr, keys, n_groups, M); break;
+        case 8: lloyd_bucket<G, 8, T, LB>(a, i, sm, arr, keys, n_groups, M); break;
+        default: lloyd_bucket<G, 16, T, LB>(a, i, sm, arr, keys, n_groups, M); break;
     }
     KM_T(5);
     if (tid < CMPQ_KMAX) crow[tid] = tid < K ? sm.cent[tid] : INFINITY;
 }
 
-size_t bucket_dyn_lds(int64_t d_out, int64_t T) {
+size_t bucket_dyn_lds(int64_t d_out, int lb) {
     size_t b = ((size_t)d_out + 15) & ~(size_t)15;
     b += (size_t)((((d_out + 31) >> 5) + 3) & ~3) * 4;
-    b += (size_t)kBuckets * 4;
+    b += ((size_t)1 << (16 - lb)) * 4;
     return b;
 }
 
-template <int G, int T>
+template <int G, int T, int LB>
 int launch_variant(const KmArgs &a, hipStream_t s) {
-    auto kern = kmeans_bucket_kernel<G, T>;
-    const size_t lds = bucket_dyn_lds(a.d_out, T);
+    auto kern = kmeans_bucket_kernel<G, T, LB>;
+    const size_t lds = bucket_dyn_lds(a.d_out, LB);
     if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
         (void)hipGetLastError();
@@ -600,16 +605,16 @@ int launch_kmeans_hist(const KmArgs &a, hipStream_t s) {
     while (T < 512 && T * 8 < groups) T <<= 1;
     const int64_t per_lane = cdiv(groups, T);
     if (per_lane > 16) return CMPQ_ESHAPE;
-    if (per_lane > 8) return launch_variant<16, 512>(a, s);
+    if (per_lane > 8) return launch_variant<16, 512, 6>(a, s);
     if (per_lane > 4) {
         switch (T) {
-            case 512: return launch_variant<8, 512>(a, s);
-            case 256: return launch_variant<8, 256>(a, s);
-            case 128: return launch_variant<8, 128>(a, s);
-            default: return launch_variant<8, 64>(a, s);
+            case 512: return launch_variant<8, 512, 6>(a, s);
+            case 256: return launch_variant<8, 256, 6>(a, s);
+            case 128: return launch_variant<8, 128, 6>(a, s);
+            default: return launch_variant<8, 64, 7>(a, s);
         }
     }
-    if (per_lane > 2) return launch_variant<4, 64>(a, s);
-    if (per_lane > 1) return launch_variant<2, 64>(a, s);
-    return launch_variant<1, 64>(a, s);
+    if (per_lane > 2) return launch_variant<4, 64, 7>(a, s);
+    if (per_lane > 1) return launch_variant<2, 64, 7>(a, s);
+    return launch_variant<1, 64, 7>(a, s);
 }
