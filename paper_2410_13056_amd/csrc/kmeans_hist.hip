@@ -61,6 +61,9 @@ struct BucketShared {
     uint32_t part_n[2][CMPQ_KMAX];  // by round parity, per boundary: kept weights of its bucket
     uint32_t part_l[2][CMPQ_KMAX];  //   not above it, and the sum of their places
     float cent[CMPQ_KMAX];          // levels by level index
+    uint32_t tk[2][CMPQ_KMAX];      // by round parity: boundary keys by sorted position
+    uint32_t code_of[CMPQ_KMAX];    // level index that each sorted position stands for
+    int go[2];                      // by round parity: another round follows
     uint32_t scan32[17];
     unsigned long long scan64[17];
     int seg_lo, n_excl;
@@ -249,6 +252,21 @@ __device__ __forceinline__ void rank_levels(float c, float &sorted, int &own, fl
     if (j >= K - 1) have_hi = false;
 }
 
+// Packed keys of a group of 4 weights (two per word); -0 reads as +0.  `finite` is cleared
+// when one of them is NaN or infinite.
+__device__ __forceinline__ void group_keys(uint2 raw, uint32_t &k01, uint32_t &k23, int &finite) {
+    uint32_t h[4] = {raw.x & 0xffffu, raw.x >> 16, raw.y & 0xffffu, raw.y >> 16};
+    uint32_t ky[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        finite &= (h[e] & 0x7c00u) != 0x7c00u;
+        if (h[e] == 0x8000u) h[e] = 0;
+        ky[e] = key_of_half(h[e]);
+    }
+    k01 = ky[0] | (ky[1] << 16);
+    k23 = ky[2] | (ky[3] << 16);
+}
+
 template <int G>
 __device__ __forceinline__ uint32_t elem_key(const uint32_t (&keys)[2 * G], int k, int e) {
     return (keys[2 * k + (e >> 1)] >> (16 * (e & 1))) & 0xffffu;
@@ -278,7 +296,7 @@ __device__ __forceinline__ void scan_bucket(const unsigned char *arr, uint32_t b
 
 template <int G, int K, int T, int LB>
 __device__ __forceinline__ void lloyd_bucket(const KmArgs &a, int64_t i, BucketShared<LB> &sm,
-                                             const unsigned char *arr,
+                                             const unsigned char *arr, uint32_t *tbl,
                                              const uint32_t (&keys)[2 * G], int n_groups, uint32_t M) {
     constexpr int L = T / 16;  // lanes that share one boundary in a round
     constexpr int kLowBits = LB, kLows = 1 << LB, kBuckets = 1 << (16 - LB);
@@ -316,46 +334,63 @@ __device__ __forceinline__ void lloyd_bucket(const KmArgs &a, int64_t i, BucketS
     __syncthreads();
     KM_T(6);
 
-    // ---- every wavefront keeps the same state: lane p = sorted position p.  Only the
-    //      per-boundary bucket scans are shared out; one barrier per round publishes them.
-    float c_sorted, hi;
-    int own, owner_lo, owner_hi;
-    bool have_hi;
-    rank_levels<K>(lane < K ? sm.cent[lane] : INFINITY, c_sorted, own, hi, owner_lo, owner_hi, have_hi);
-    uint32_t tk = kKeyInf, tk_prev = 0xffffffffu;
+    // ---- rounds.  Wavefront 0 alone carries the levels (lane p = sorted position p) and
+    //      does the serial part of a round; the others only join in the per-boundary bucket
+    //      scans and otherwise sleep at the two barriers, leaving the issue slots to the
+    //      other workgroups of the compute unit.
+    float c_sorted = 0.0f, hi = 0.0f;
+    int own = lane, owner_lo = 0, owner_hi = 0;
+    bool have_hi = false;
+    if (wave == 0)
+        rank_levels<K>(lane < K ? sm.cent[lane] : INFINITY, c_sorted, own, hi, owner_lo, owner_hi, have_hi);
+    uint32_t tk_prev = 0xffffffffu;
     const int p_mine = tid / L;  // the boundary this lane helps with
+    int par = 0;
 
     for (int round = 0;; ++round) {
-        tk = kKeyInf;
-        if (have_hi) tk = boundary_key(c_sorted, hi, owner_lo, owner_hi);
-        // no boundary moved: the iteration sits on its fixed point
-        const bool moved = __ballot(lane < K - 1 && tk != tk_prev) != 0ull;
-        tk_prev = tk;
-        if (round == a.iters || !moved) break;
+        par = round & 1;
+        if (wave == 0) {
+            uint32_t tk = kKeyInf;
+            if (have_hi) tk = boundary_key(c_sorted, hi, owner_lo, owner_hi);
+            // no boundary moved: the iteration sits on its fixed point
+            const bool moved = __ballot(lane < K - 1 && tk != tk_prev) != 0ull;
+            tk_prev = tk;
+            const bool go = round != a.iters && moved;
+            if (lane < CMPQ_KMAX) sm.tk[par][lane] = tk;
+            if (lane == 0) sm.go[par] = go;
+            if (!go) {  // results: the position -> level map and the levels by level index
+                if (lane < CMPQ_KMAX) sm.code_of[lane] = (uint32_t)own;
+                if (lane < K) sm.cent[own] = c_sorted;
+            }
+        }
+        __syncthreads();
+        if (!sm.go[par]) break;
         // L lanes per boundary: the part of its bucket that lies below it
-        const uint32_t t = __shfl(tk, p_mine, CMPQ_WAVE);
         if (p_mine < K - 1) {
+            const uint32_t t = sm.tk[par][p_mine];
             uint32_t n = 0, l = 0;
             if (t != kKeyInf) {
                 const uint32_t b = t >> kLowBits;
                 scan_bucket<L>(arr, sm.ncum[b], sm.ncum[b + 1], t & (kLows - 1), n, l);
             }
             if ((tid & (L - 1)) == 0) {
-                sm.part_n[round & 1][p_mine] = n;
-                sm.part_l[round & 1][p_mine] = l;
+                sm.part_n[par][p_mine] = n;
+                sm.part_l[par][p_mine] = l;
             }
         }
         __syncthreads();
+        if (wave != 0) continue;
         // cumulative count and sum at each boundary; the last position takes everything
+        const uint32_t tk = tk_prev;
         uint32_t n_below = M;
         long long s_below = sm.scum[kBuckets];
         if (lane < K - 1 && tk != kKeyInf) {
             const uint32_t b = tk >> kLowBits;
-            const uint32_t cnt = sm.part_n[round & 1][lane];
+            const uint32_t cnt = sm.part_n[par][lane];
             long long q0, step;
             bucket_affine<LB>(b, q0, step);
             n_below = sm.ncum[b] + cnt;
-            s_below = sm.scum[b] + (long long)cnt * q0 + step * (long long)sm.part_l[round & 1][lane];
+            s_below = sm.scum[b] + (long long)cnt * q0 + step * (long long)sm.part_l[par][lane];
         }
         // sorted positions live in lanes 0..15, one DPP row: neighbours come by row shifts
         const uint32_t n_prev = row_from_below(n_below);
@@ -388,27 +423,81 @@ __device__ __forceinline__ void lloyd_bucket(const KmArgs &a, int64_t i, BucketS
             rank_levels<K>(c_level, c_sorted, own, hi, owner_lo, owner_hi, have_hi);
         }
     }
-    if (wave == 0 && lane < K) sm.cent[own] = c_sorted;  // read back by the caller after a barrier
     KM_T(7);
 
-    // ---- final coding: 4 codes per lane and store.  Boundaries and the position -> level
-    //      map come out of this wavefront's own lanes.
+    // ---- final coding: 4 codes per lane and store.  Every wavefront fetches the final
+    //      boundaries and the position -> level map left by wavefront 0.
+    const uint32_t tk_fin = sm.tk[par][lane & (CMPQ_KMAX - 1)];
+    const int own_fin = (int)sm.code_of[lane & (CMPQ_KMAX - 1)];
     uint32_t thr[CMPQ_KMAX];
 #pragma unroll
-    for (int p = 0; p < K - 1; ++p) thr[p] = (uint32_t)__builtin_amdgcn_readlane((int)tk, p);
-    const bool ident = __ballot(lane < K && own != lane) == 0ull;
+    for (int p = 0; p < K - 1; ++p) thr[p] = (uint32_t)__builtin_amdgcn_readlane((int)tk_fin, p);
     uint32_t *crow = reinterpret_cast<uint32_t *>(a.codes + i * a.d_out);
+    // Many weights per lane and many levels: a table over the buckets replaces the search.
+    // A bucket with no boundary inside has one code; with one boundary, a code on either
+    // side of the boundary's place; with more (rare) the entry sends the weight to the search.
+    constexpr bool kTable = K >= 8 && G * T >= 2 * kBuckets;
+    // The longest channels fetch their weights again here (from cache) instead of holding
+    // them in registers through the rounds: a third workgroup then fits a compute unit.
+    constexpr bool kReload = G >= 16;
+    const uint2 *wrow = reinterpret_cast<const uint2 *>(static_cast<const __half *>(a.W) + i * a.ldw);
+    uint32_t again[2 * G];
+    if constexpr (kReload) {
+        int unused = 1;
 #pragma unroll
-    for (int k = 0; k < G; ++k) {
-        const int g = k * T + tid;
-        uint32_t word = 0;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {  // all lanes take part: the level look-up crosses lanes
-            uint32_t pos = cell_of<K>(elem_key<G>(keys, k, e), thr);
-            if (!ident) pos = (uint32_t)__shfl(own, (int)pos, CMPQ_WAVE);
-            word |= pos << (8 * e);
+        for (int k = 0; k < G; ++k) {
+            const int g = k * T + tid;
+            uint2 raw = make_uint2(0, 0);
+            if (g < n_groups) raw = wrow[g];
+            group_keys(raw, again[2 * k], again[2 * k + 1], unused);
         }
-        if (g < n_groups) crow[g] = word;
+    }
+    auto key_at = [&](int k, int e) -> uint32_t {
+        if constexpr (kReload) return elem_key<G>(again, k, e);
+        else return elem_key<G>(keys, k, e);
+    };
+    if constexpr (kTable) {
+        for (int bk = tid; bk < kBuckets; bk += T) {
+            const uint32_t first = (uint32_t)bk << kLowBits;
+            const uint32_t p0 = cell_of<K>(first, thr), p1 = cell_of<K>(first + kLows - 1, thr);
+            uint32_t ent = sm.code_of[p0] | (sm.code_of[p1] << 4);
+            if (p1 == p0) {
+                ent |= 0xff00u;  // no place lies above this one
+            } else {
+                ent |= (sm.tk[par][p0] & (kLows - 1)) << 8;
+                if (p1 > p0 + 1) ent |= 0x10000u;
+            }
+            tbl[bk] = ent;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < G; ++k) {
+            const int g = k * T + tid;
+            uint32_t word = 0;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const uint32_t key = key_at(k, e);
+                const uint32_t ent = tbl[key >> kLowBits];
+                uint32_t code = (key & (kLows - 1)) > ((ent >> 8) & 0xffu) ? (ent >> 4) & 15u : ent & 15u;
+                if (ent & 0x10000u) code = sm.code_of[cell_of<K>(key, thr)];
+                word |= code << (8 * e);
+            }
+            if (g < n_groups) crow[g] = word;
+        }
+    } else {
+        const bool ident = __ballot(lane < K && own_fin != lane) == 0ull;
+#pragma unroll
+        for (int k = 0; k < G; ++k) {
+            const int g = k * T + tid;
+            uint32_t word = 0;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {  // all lanes take part: the level look-up crosses lanes
+                uint32_t pos = cell_of<K>(key_at(k, e), thr);
+                if (!ident) pos = (uint32_t)__shfl(own_fin, (int)pos, CMPQ_WAVE);
+                word |= pos << (8 * e);
+            }
+            if (g < n_groups) crow[g] = word;
+        }
     }
     __syncthreads();
     KM_T(8);
@@ -417,8 +506,11 @@ __device__ __forceinline__ void lloyd_bucket(const KmArgs &a, int64_t i, BucketS
 #ifndef CMPQ_KM_WAVES
 #define CMPQ_KM_WAVES 6
 #endif
+#ifndef CMPQ_KM_WAVES_BIG
+#define CMPQ_KM_WAVES_BIG 6
+#endif
 template <int G, int T, int LB>
-__global__ __launch_bounds__(T) __attribute__((amdgpu_waves_per_eu(T <= 256 ? CMPQ_KM_WAVES : 4, 8))) void kmeans_bucket_kernel(KmArgs a) {
+__global__ __launch_bounds__(T) __attribute__((amdgpu_waves_per_eu(T <= 256 ? CMPQ_KM_WAVES : CMPQ_KM_WAVES_BIG, 8))) void kmeans_bucket_kernel(KmArgs a) {
     constexpr int kLowBits = LB, kLows = 1 << LB, kBuckets = 1 << (16 - LB);
     // dynamic LDS: places of the kept weights, ordered by bucket (a byte each; the bucket
     // follows from the position) | removed-entry bitmap (one bit per weight) | the scatter
@@ -453,16 +545,7 @@ __global__ __launch_bounds__(T) __attribute__((amdgpu_waves_per_eu(T <= 256 ? CM
         const int g = k * T + tid;
         uint2 raw = make_uint2(0, 0);
         if (g < n_groups) raw = wrow[g];
-        uint32_t h[4] = {raw.x & 0xffffu, raw.x >> 16, raw.y & 0xffffu, raw.y >> 16};
-        uint32_t ky[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            finite &= (h[e] & 0x7c00u) != 0x7c00u;
-            if (h[e] == 0x8000u) h[e] = 0;  // -0 reads as +0
-            ky[e] = key_of_half(h[e]);
-        }
-        keys[2 * k] = ky[0] | (ky[1] << 16);
-        keys[2 * k + 1] = ky[2] | (ky[3] << 16);
+        group_keys(raw, keys[2 * k], keys[2 * k + 1], finite);
     }
     if (tid == 0) {  // the slice of out_idx inside this channel
         sm.seg_lo = a.seg ? a.seg[i] : 0;
@@ -488,16 +571,15 @@ __global__ __launch_bounds__(T) __attribute__((amdgpu_waves_per_eu(T <= 256 ? CM
 
     KM_T(1);
     // ---- bucket tables: counts and sums of places of the kept weights
-    uint32_t kept[G];  // 4 bits per group: which of its weights are kept
+    //      (4 bits of the bitmap per group of 4 weights; no bitmap reads without removed entries)
 #pragma unroll
     for (int k = 0; k < G; ++k) {
         const int g = k * T + tid;
-        kept[k] = 0;
         if (g < n_groups) {
-            kept[k] = ~(removed[g >> 3] >> ((g & 7) * 4)) & 0xfu;
+            const uint32_t kept = n_ex > 0 ? ~(removed[g >> 3] >> ((g & 7) * 4)) & 0xfu : 0xfu;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                if ((kept[k] >> e) & 1u) {
+                if ((kept >> e) & 1u) {
                     const uint32_t key = elem_key<G>(keys, k, e);
                     atomicAdd(reinterpret_cast<unsigned long long *>(&sm.scum[key >> kLowBits]),
                               (1ull << 32) | (key & (kLows - 1)));
@@ -551,12 +633,16 @@ __global__ __launch_bounds__(T) __attribute__((amdgpu_waves_per_eu(T <= 256 ? CM
     // ---- scatter the kept keys, ordered by bucket
 #pragma unroll
     for (int k = 0; k < G; ++k) {
+        const int g = k * T + tid;
+        if (g < n_groups) {
+            const uint32_t kept = n_ex > 0 ? ~(removed[g >> 3] >> ((g & 7) * 4)) & 0xfu : 0xfu;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            if ((kept[k] >> e) & 1u) {
-                const uint32_t key = elem_key<G>(keys, k, e);
-                const uint32_t pos = atomicAdd(&cursor[key >> kLowBits], 1u);
-                arr[pos] = (unsigned char)(key & (kLows - 1));
+            for (int e = 0; e < 4; ++e) {
+                if ((kept >> e) & 1u) {
+                    const uint32_t key = elem_key<G>(keys, k, e);
+                    const uint32_t pos = atomicAdd(&cursor[key >> kLowBits], 1u);
+                    arr[pos] = (unsigned char)(key & (kLows - 1));
+                }
             }
         }
     }
@@ -564,10 +650,10 @@ __global__ __launch_bounds__(T) __attribute__((amdgpu_waves_per_eu(T <= 256 ? CM
     KM_T(4);
 
     switch (K) {
-        case 2: lloyd_bucket<G, 2, T, LB>(a, i, sm, arr, keys, n_groups, M); break;
-        case 4: lloyd_bucket<G, 4, T, LB>(a, i, sm, arr, keys, n_groups, M); break;
-        case 8: lloyd_bucket<G, 8, T, LB>(a, i, sm, arr, keys, n_groups, M); break;
-        default: lloyd_bucket<G, 16, T, LB>(a, i, sm, arr, keys, n_groups, M); break;
+        case 2: lloyd_bucket<G, 2, T, LB>(a, i, sm, arr, cursor, keys, n_groups, M); break;
+        case 4: lloyd_bucket<G, 4, T, LB>(a, i, sm, arr, cursor, keys, n_groups, M); break;
+        case 8: lloyd_bucket<G, 8, T, LB>(a, i, sm, arr, cursor, keys, n_groups, M); break;
+        default: lloyd_bucket<G, 16, T, LB>(a, i, sm, arr, cursor, keys, n_groups, M); break;
     }
     KM_T(5);
     if (tid < CMPQ_KMAX) crow[tid] = tid < K ? sm.cent[tid] : INFINITY;
