@@ -6,16 +6,18 @@
 // channel once so that each round reads these numbers instead of recounting them:
 //
 //   * every weight becomes its 16-bit order key (unsigned order = value order); the top
-//     10 bits name one of 1024 buckets, the low 6 bits the place inside it;
+//     bits name a bucket (1024 buckets of 64 places, or 512 of 128 for short channels),
+//     the low bits the place inside it;
 //   * one pass counts the buckets and sums the places, a scan turns this into exclusive
 //     prefixes of the count and of the exact integer sum of x*2^24 (inside a bucket
 //     x*2^24 is affine in the place: sign, exponent and top mantissa bits are shared);
-//   * a second pass scatters the keys into an LDS array ordered by bucket (any order
-//     inside a bucket);
+//   * a second pass scatters the places into an LDS byte array ordered by bucket (any
+//     order inside a bucket); a bucket's stretch starts on a 4-byte boundary and its
+//     unused tail holds a filler above every place, so a scan reads whole words;
 //   * a round then costs, per boundary, the prefix of its bucket plus a scan of that one
-//     bucket's keys (a wavefront per boundary), a cell is the difference of two
-//     boundaries, and the new level is the exact integer sum divided in fp64 and rounded
-//     once to fp32 - the value an fp64 reference computes;
+//     bucket (a group of lanes per boundary, four places per word compared at once), a
+//     cell is the difference of two boundaries, and the new level is the exact integer sum
+//     divided in fp64 and rounded once to fp32 - the value an fp64 reference computes;
 //   * when no boundary moved the iteration has reached its fixed point and the remaining
 //     rounds, which would repeat it, are skipped.
 //
@@ -26,38 +28,30 @@
 // index) whenever their order may have changed; they need not stay ascending because a
 // level without members keeps a stale value.
 //
-// The weights stay in registers as packed keys for the final coding (branch-free search
-// over K-1 key boundaries).  A channel with NaN or infinity is flagged and left to the
-// general kernel.
+// The kernel is bound by instruction issue, not by latency: the serial part of a round
+// runs on one wavefront while the others sleep at barriers, and several workgroups share
+// a compute unit.  A channel with NaN or infinity is flagged and left to the general kernel.
 #include "kmeans_args.h"
-
-#ifdef CMPQ_KM_PROFILE
-__device__ unsigned long long g_km_prof[16];
-extern "C" void cmpq_debug_read(unsigned long long *out) {
-    (void)hipMemcpyFromSymbol(out, HIP_SYMBOL(g_km_prof), sizeof(g_km_prof));
-    unsigned long long z[16] = {0};
-    (void)hipMemcpyToSymbol(HIP_SYMBOL(g_km_prof), z, sizeof(z));
-}
-#define KM_T(i) do { if (threadIdx.x == 0 && (blockIdx.x & 63) == 0) { unsigned long long t_ = wall_clock64(); atomicAdd(&g_km_prof[i], t_ - t_prof); t_prof = t_; } } while (0)
-#define KM_T0() unsigned long long t_prof = wall_clock64()
-#else
-#define KM_T(i) do { } while (0)
-#define KM_T0() do { } while (0)
-#endif
 
 namespace {
 
-// A key splits into bucket (top 16 - LB bits) and place (low LB bits).  LB = 6 (1024
-// buckets of 64 places) suits long channels; short ones take LB = 7 (512 buckets): the
-// tables shrink and more workgroups share a compute unit.
-constexpr uint32_t kKeyInf = 0xffffu;  // boundary above every key
+constexpr uint32_t kKeyInf = 0xffffu;     // boundary above every key
+constexpr uint32_t kFill4 = 0x80808080u;  // four filler bytes: above every place (<= 127)
+
+// Bytes of the place array: one per weight plus up to 3 of filler per non-empty bucket.
+__host__ __device__ inline size_t bucket_arr_bytes(int64_t d_out, int lb) {
+    const int64_t buckets = (int64_t)1 << (16 - lb);
+    const int64_t pad = 3 * (d_out < buckets ? d_out : buckets);
+    return ((size_t)(d_out + pad) + 15) & ~(size_t)15;
+}
 
 template <int LB>
 struct BucketShared {
     static constexpr int kBuckets = 1 << (16 - LB);
     long long scum[kBuckets + 1];   // count << 32 | sum of places; then the exclusive prefix
                                     // over buckets of sum(x * 2^24)
-    uint32_t ncum[kBuckets + 1];    // exclusive prefix over buckets of the counts
+    uint16_t ncum[kBuckets + 2];    // exclusive prefix over buckets of the counts
+    uint16_t start[kBuckets + 2];   // where a bucket's stretch of the byte array begins
     uint32_t part_n[2][CMPQ_KMAX];  // by round parity, per boundary: kept weights of its bucket
     uint32_t part_l[2][CMPQ_KMAX];  //   not above it, and the sum of their places
     float cent[CMPQ_KMAX];          // levels by level index
@@ -69,6 +63,9 @@ struct BucketShared {
     int seg_lo, n_excl;
 };
 
+// Order key of an fp16 bit pattern: unsigned key order = value order.  -0 comes out one
+// key below +0 (0x7fff, 0x8000); nothing else lies between, and boundary_key never
+// returns 0x7fff, so the two zeros always share a cell.
 __device__ __forceinline__ uint32_t key_of_half(uint32_t h) {
     return (h & 0x8000u) ? (~h & 0xffffu) : (h | 0x8000u);
 }
@@ -77,6 +74,16 @@ __device__ __forceinline__ uint32_t half_of_key(uint32_t k) {
 }
 __device__ __forceinline__ float value_of_key(uint32_t k) {
     return __half2float(__ushort_as_half((unsigned short)half_of_key(k)));
+}
+// Two fp16 patterns in one word -> their two keys: flip the sign bit of a non-negative
+// value, every bit of a negative one.
+__device__ __forceinline__ uint32_t keys_of_half2(uint32_t w) {
+    const uint32_t neg = (w >> 15) & 0x00010001u;
+    return w ^ (__umul24(neg, 0x7fffu) + 0x80008000u);
+}
+// Bits 15 and 31 of the result are set where the exponent field is all ones.
+__device__ __forceinline__ uint32_t nonfinite_of_half2(uint32_t w) {
+    return (w & 0x7c007c00u) + 0x04000400u;
 }
 
 // x*2^24 of the first key of bucket b, and the step per place inside the bucket.
@@ -190,6 +197,7 @@ __device__ __forceinline__ uint32_t cell_of(uint32_t q, const uint32_t (&t)[CMPQ
 
 // Key of the largest fp16 value that belongs to `lo` rather than `hi` (lo < hi): values
 // below the midpoint, and the midpoint itself when lo has the smaller level index.
+// Never the key of -0: a boundary there would part the two zeros.
 __device__ __forceinline__ uint32_t boundary_key(float lo, float hi, int owner_lo, int owner_hi) {
     const double mid = ((double)lo + (double)hi) * 0.5;
     float f = (float)mid;  // round down to fp32 ...
@@ -203,6 +211,7 @@ __device__ __forceinline__ uint32_t boundary_key(float lo, float hi, int owner_l
     uint32_t key = key_of_half(h);
     if (value_of_key(key) > f) key -= 1;
     if ((double)value_of_key(key) == mid && owner_hi < owner_lo) key -= 1;
+    if (key == 0x7fffu) key = 0x7ffeu;
     return key;
 }
 
@@ -252,46 +261,83 @@ __device__ __forceinline__ void rank_levels(float c, float &sorted, int &own, fl
     if (j >= K - 1) have_hi = false;
 }
 
-// Packed keys of a group of 4 weights (two per word); -0 reads as +0.  `finite` is cleared
-// when one of them is NaN or infinite.
-__device__ __forceinline__ void group_keys(uint2 raw, uint32_t &k01, uint32_t &k23, int &finite) {
-    uint32_t h[4] = {raw.x & 0xffffu, raw.x >> 16, raw.y & 0xffffu, raw.y >> 16};
-    uint32_t ky[4];
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-        finite &= (h[e] & 0x7c00u) != 0x7c00u;
-        if (h[e] == 0x8000u) h[e] = 0;
-        ky[e] = key_of_half(h[e]);
-    }
-    k01 = ky[0] | (ky[1] << 16);
-    k23 = ky[2] | (ky[3] << 16);
-}
-
 template <int G>
 __device__ __forceinline__ uint32_t elem_key(const uint32_t (&keys)[2 * G], int k, int e) {
     return (keys[2 * k + (e >> 1)] >> (16 * (e & 1))) & 0xffffu;
 }
 
-// A group of L lanes: among the places arr[begin, end) of one bucket, how many are <= pl,
-// and their sum.  Result valid in every lane of the group.
+// A group of L lanes: among the places of one bucket, arr[begin, end) with begin and end
+// multiples of 4 and filler in the unused tail, how many are <= pl, and their sum.  Four
+// places per word are compared at once: a byte plus (127 - pl) reaches bit 7 exactly when
+// it is above pl (places and pl are at most 127, the filler is 128: no carry leaves a
+// byte).  Result valid in every lane of the group.
 template <int L>
 __device__ __forceinline__ void scan_bucket(const unsigned char *arr, uint32_t begin, uint32_t end,
                                             uint32_t pl, uint32_t &n, uint32_t &l) {
     const int sub = threadIdx.x & (L - 1);
+    const uint32_t *words = reinterpret_cast<const uint32_t *>(arr);
+    const uint32_t w_end = end >> 2;
+    const uint32_t bias = 0x7f7f7f7fu - pl * 0x01010101u;
     uint32_t cn = 0, cl = 0;
-    for (uint32_t j = begin + sub; j < end; j += 4 * L) {  // four reads in flight
-        uint32_t place[4];
+    for (uint32_t j = (begin >> 2) + sub; j < w_end; j += 4 * L) {  // four reads in flight
+        uint32_t x[4];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) place[u] = j + u * L < end ? arr[j + u * L] : 0xffu;
+        for (int u = 0; u < 4; ++u) x[u] = j + u * L < w_end ? words[j + u * L] : kFill4;
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            const bool in = place[u] <= pl;
-            cn += in;
-            cl += in ? place[u] : 0u;
+            const uint32_t le = (~((x[u] + bias) >> 7)) & 0x01010101u;  // 1 per byte <= pl
+            cn = __builtin_amdgcn_sad_u8(le, 0u, cn);
+            cl = __builtin_amdgcn_sad_u8(x[u] & ((le << 8) - le), 0u, cl);  // le * 255: a full byte per flag
         }
     }
     n = group_sum<L>(cn);
     l = group_sum<L>(cl);
+}
+
+// Counts the buckets and sums the places of the kept weights (packed 64-bit LDS atomics).
+template <int G, int T, int LB, bool MASKED>
+__device__ __forceinline__ void count_buckets(const uint32_t (&keys)[2 * G], const uint32_t *removed,
+                                              long long *scum, int n_groups) {
+    const int tid = threadIdx.x;
+#pragma unroll
+    for (int k = 0; k < G; ++k) {
+        const int g = k * T + tid;
+        if (g < n_groups) {
+            uint32_t kept = 0xfu;  // 4 bits of the bitmap per group of 4 weights
+            if constexpr (MASKED) kept = ~(removed[g >> 3] >> ((g & 7) * 4)) & 0xfu;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                if (!MASKED || ((kept >> e) & 1u)) {
+                    const uint32_t key = elem_key<G>(keys, k, e);
+                    atomicAdd(reinterpret_cast<unsigned long long *>(&scum[key >> LB]),
+                              (1ull << 32) | (key & ((1u << LB) - 1)));
+                }
+            }
+        }
+    }
+}
+
+// Puts the place of every kept weight into its bucket's stretch of the byte array.
+template <int G, int T, int LB, bool MASKED>
+__device__ __forceinline__ void scatter_places(const uint32_t (&keys)[2 * G], const uint32_t *removed,
+                                               uint32_t *cursor, unsigned char *arr, int n_groups) {
+    const int tid = threadIdx.x;
+#pragma unroll
+    for (int k = 0; k < G; ++k) {
+        const int g = k * T + tid;
+        if (g < n_groups) {
+            uint32_t kept = 0xfu;
+            if constexpr (MASKED) kept = ~(removed[g >> 3] >> ((g & 7) * 4)) & 0xfu;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                if (!MASKED || ((kept >> e) & 1u)) {
+                    const uint32_t key = elem_key<G>(keys, k, e);
+                    const uint32_t pos = atomicAdd(&cursor[key >> LB], 1u);
+                    arr[pos] = (unsigned char)(key & ((1u << LB) - 1));
+                }
+            }
+        }
+    }
 }
 
 template <int G, int K, int T, int LB>
@@ -301,7 +347,6 @@ __device__ __forceinline__ void lloyd_bucket(const KmArgs &a, int64_t i, BucketS
     constexpr int L = T / 16;  // lanes that share one boundary in a round
     constexpr int kLowBits = LB, kLows = 1 << LB, kBuckets = 1 << (16 - LB);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    KM_T0();
 
     // ---- start-up: level j = order statistic floor((2j+1)M/(2K)) of the kept weights.
     //      L lanes per rank: locate the bucket by its prefix, then bisect on the place
@@ -318,7 +363,7 @@ __device__ __forceinline__ void lloyd_bucket(const KmArgs &a, int64_t i, BucketS
                     if (sm.ncum[mid] <= r) lo = mid; else hi_b = mid - 1;
                 }
                 const uint32_t b = (uint32_t)lo, r_in = r - sm.ncum[b];
-                const uint32_t begin = sm.ncum[b], end = sm.ncum[b + 1];
+                const uint32_t begin = sm.start[b], end = sm.start[b + 1];
                 int pl = 0, ph = kLows - 1;  // smallest place with more than r_in weights at or below it
                 while (pl < ph) {
                     const int mid = (pl + ph) >> 1;
@@ -327,12 +372,12 @@ __device__ __forceinline__ void lloyd_bucket(const KmArgs &a, int64_t i, BucketS
                     if (n > r_in) ph = mid; else pl = mid + 1;
                 }
                 c = value_of_key((b << kLowBits) | (uint32_t)pl);
+                if (c == 0.0f) c = 0.0f;  // a level never starts as -0
             }
             if (sub == 0) sm.cent[j] = c;
         }
     }
     __syncthreads();
-    KM_T(6);
 
     // ---- rounds.  Wavefront 0 alone carries the levels (lane p = sorted position p) and
     //      does the serial part of a round; the others only join in the per-boundary bucket
@@ -371,7 +416,7 @@ __device__ __forceinline__ void lloyd_bucket(const KmArgs &a, int64_t i, BucketS
             uint32_t n = 0, l = 0;
             if (t != kKeyInf) {
                 const uint32_t b = t >> kLowBits;
-                scan_bucket<L>(arr, sm.ncum[b], sm.ncum[b + 1], t & (kLows - 1), n, l);
+                scan_bucket<L>(arr, sm.start[b], sm.start[b + 1], t & (kLows - 1), n, l);
             }
             if ((tid & (L - 1)) == 0) {
                 sm.part_n[par][p_mine] = n;
@@ -423,7 +468,6 @@ __device__ __forceinline__ void lloyd_bucket(const KmArgs &a, int64_t i, BucketS
             rank_levels<K>(c_level, c_sorted, own, hi, owner_lo, owner_hi, have_hi);
         }
     }
-    KM_T(7);
 
     // ---- final coding: 4 codes per lane and store.  Every wavefront fetches the final
     //      boundaries and the position -> level map left by wavefront 0.
@@ -433,30 +477,31 @@ __device__ __forceinline__ void lloyd_bucket(const KmArgs &a, int64_t i, BucketS
 #pragma unroll
     for (int p = 0; p < K - 1; ++p) thr[p] = (uint32_t)__builtin_amdgcn_readlane((int)tk_fin, p);
     uint32_t *crow = reinterpret_cast<uint32_t *>(a.codes + i * a.d_out);
-    // Many weights per lane and many levels: a table over the buckets replaces the search.
-    // A bucket with no boundary inside has one code; with one boundary, a code on either
-    // side of the boundary's place; with more (rare) the entry sends the weight to the search.
-    constexpr bool kTable = K >= 8 && G * T >= 2 * kBuckets;
-    // The longest channels fetch their weights again here (from cache) instead of holding
+    // Workgroups of 512 lanes fetch their weights again here (from cache) instead of holding
     // them in registers through the rounds: a third workgroup then fits a compute unit.
-    constexpr bool kReload = G >= 16;
-    const uint2 *wrow = reinterpret_cast<const uint2 *>(static_cast<const __half *>(a.W) + i * a.ldw);
+    constexpr bool kReload = T >= 512;
     uint32_t again[2 * G];
     if constexpr (kReload) {
-        int unused = 1;
+        const uint2 *wrow = reinterpret_cast<const uint2 *>(static_cast<const __half *>(a.W) + i * a.ldw);
 #pragma unroll
         for (int k = 0; k < G; ++k) {
             const int g = k * T + tid;
             uint2 raw = make_uint2(0, 0);
             if (g < n_groups) raw = wrow[g];
-            group_keys(raw, again[2 * k], again[2 * k + 1], unused);
+            again[2 * k] = keys_of_half2(raw.x);
+            again[2 * k + 1] = keys_of_half2(raw.y);
         }
     }
     auto key_at = [&](int k, int e) -> uint32_t {
         if constexpr (kReload) return elem_key<G>(again, k, e);
         else return elem_key<G>(keys, k, e);
     };
+    // Many weights per lane and many levels: a table over the buckets replaces the search.
+    // A bucket with no boundary inside has one code; with one boundary, a code on either
+    // side of the boundary's place; with more (rare) the entry sends the weight to the search.
+    constexpr bool kTable = K >= 8 && G * T >= 2 * kBuckets;
     if constexpr (kTable) {
+        int multi = 0;
         for (int bk = tid; bk < kBuckets; bk += T) {
             const uint32_t first = (uint32_t)bk << kLowBits;
             const uint32_t p0 = cell_of<K>(first, thr), p1 = cell_of<K>(first + kLows - 1, thr);
@@ -465,24 +510,42 @@ __device__ __forceinline__ void lloyd_bucket(const KmArgs &a, int64_t i, BucketS
                 ent |= 0xff00u;  // no place lies above this one
             } else {
                 ent |= (sm.tk[par][p0] & (kLows - 1)) << 8;
-                if (p1 > p0 + 1) ent |= 0x10000u;
+                if (p1 > p0 + 1) {
+                    ent |= 0x10000u;
+                    multi = 1;
+                }
             }
             tbl[bk] = ent;
         }
-        __syncthreads();
+        if (!__syncthreads_or(multi)) {
 #pragma unroll
-        for (int k = 0; k < G; ++k) {
-            const int g = k * T + tid;
-            uint32_t word = 0;
+            for (int k = 0; k < G; ++k) {
+                const int g = k * T + tid;
+                uint32_t word = 0;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const uint32_t key = key_at(k, e);
-                const uint32_t ent = tbl[key >> kLowBits];
-                uint32_t code = (key & (kLows - 1)) > ((ent >> 8) & 0xffu) ? (ent >> 4) & 15u : ent & 15u;
-                if (ent & 0x10000u) code = sm.code_of[cell_of<K>(key, thr)];
-                word |= code << (8 * e);
+                for (int e = 0; e < 4; ++e) {
+                    const uint32_t key = key_at(k, e);
+                    const uint32_t ent = tbl[key >> kLowBits];
+                    const uint32_t code = (key & (kLows - 1)) > ((ent >> 8) & 0xffu) ? (ent >> 4) & 15u : ent & 15u;
+                    word |= code << (8 * e);
+                }
+                if (g < n_groups) crow[g] = word;
             }
-            if (g < n_groups) crow[g] = word;
+        } else {
+#pragma unroll
+            for (int k = 0; k < G; ++k) {
+                const int g = k * T + tid;
+                uint32_t word = 0;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const uint32_t key = key_at(k, e);
+                    const uint32_t ent = tbl[key >> kLowBits];
+                    uint32_t code = (key & (kLows - 1)) > ((ent >> 8) & 0xffu) ? (ent >> 4) & 15u : ent & 15u;
+                    if (ent & 0x10000u) code = sm.code_of[cell_of<K>(key, thr)];
+                    word |= code << (8 * e);
+                }
+                if (g < n_groups) crow[g] = word;
+            }
         }
     } else {
         const bool ident = __ballot(lane < K && own_fin != lane) == 0ull;
@@ -500,21 +563,16 @@ __device__ __forceinline__ void lloyd_bucket(const KmArgs &a, int64_t i, BucketS
         }
     }
     __syncthreads();
-    KM_T(8);
 }
 
-#ifndef CMPQ_KM_WAVES
-#define CMPQ_KM_WAVES 6
-#endif
-#ifndef CMPQ_KM_WAVES_BIG
-#define CMPQ_KM_WAVES_BIG 6
-#endif
+// Occupancy: 6 wavefronts per SIMD (80 registers) - 6 workgroups of 256 lanes or 3 of 512
+// per compute unit, LDS permitting.
 template <int G, int T, int LB>
-__global__ __launch_bounds__(T) __attribute__((amdgpu_waves_per_eu(T <= 256 ? CMPQ_KM_WAVES : CMPQ_KM_WAVES_BIG, 8))) void kmeans_bucket_kernel(KmArgs a) {
-    constexpr int kLowBits = LB, kLows = 1 << LB, kBuckets = 1 << (16 - LB);
+__global__ __launch_bounds__(T) __attribute__((amdgpu_waves_per_eu(6, 8))) void kmeans_bucket_kernel(KmArgs a) {
+    constexpr int kBuckets = 1 << (16 - LB);
     // dynamic LDS: places of the kept weights, ordered by bucket (a byte each; the bucket
     // follows from the position) | removed-entry bitmap (one bit per weight) | the scatter
-    // cursors
+    // cursors, later the coding table
     extern __shared__ __align__(16) unsigned char dyn[];
     __shared__ BucketShared<LB> sm;
     const int64_t i = blockIdx.x;
@@ -530,22 +588,24 @@ __global__ __launch_bounds__(T) __attribute__((amdgpu_waves_per_eu(T <= 256 ? CM
         return;
     }
     const int K = 1 << b;
-    KM_T0();
     unsigned char *arr = dyn;
-    uint32_t *removed = reinterpret_cast<uint32_t *>(dyn + (((size_t)d_out + 15) & ~(size_t)15));
+    const size_t arr_bytes = bucket_arr_bytes(d_out, LB);
+    uint32_t *removed = reinterpret_cast<uint32_t *>(dyn + arr_bytes);
     const int n_words = (d_out + 31) >> 5;
     uint32_t *cursor = removed + ((n_words + 3) & ~3);
 
     // ---- load: lane owns groups g = k*T + tid of 4 weights, kept as packed 16-bit keys
     const uint2 *wrow = reinterpret_cast<const uint2 *>(static_cast<const __half *>(a.W) + i * a.ldw);
     uint32_t keys[2 * G];
-    int finite = 1;
+    uint32_t nonfinite = 0;
 #pragma unroll
     for (int k = 0; k < G; ++k) {
         const int g = k * T + tid;
         uint2 raw = make_uint2(0, 0);
         if (g < n_groups) raw = wrow[g];
-        group_keys(raw, keys[2 * k], keys[2 * k + 1], finite);
+        nonfinite |= nonfinite_of_half2(raw.x) | nonfinite_of_half2(raw.y);
+        keys[2 * k] = keys_of_half2(raw.x);
+        keys[2 * k + 1] = keys_of_half2(raw.y);
     }
     if (tid == 0) {  // the slice of out_idx inside this channel
         sm.seg_lo = a.seg ? a.seg[i] : 0;
@@ -554,54 +614,45 @@ __global__ __launch_bounds__(T) __attribute__((amdgpu_waves_per_eu(T <= 256 ? CM
     }
     for (int s = tid; s < kBuckets; s += T) sm.scum[s] = 0;  // first: count << 32 | sum of places
     for (int s = tid; s < n_words; s += T) removed[s] = 0;
-    KM_T(0);
-    if (!__syncthreads_and(finite)) {  // leave the channel to the general kernel
+    {
+        uint4 *a4 = reinterpret_cast<uint4 *>(arr);
+        for (int s = tid; s < (int)(arr_bytes >> 4); s += T) a4[s] = make_uint4(kFill4, kFill4, kFill4, kFill4);
+    }
+    if (!__syncthreads_and((nonfinite & 0x80008000u) == 0u)) {  // leave the channel to the general kernel
         if (tid == 0) a.deferred[i] = 1;
         return;
     }
     if (tid == 0) a.deferred[i] = 0;
     const int n_ex = sm.n_excl;
-    const int32_t *ex_idx = a.out_idx + sm.seg_lo;
-    const int32_t chan_base = (int32_t)(i * a.d_out);
-    for (int e = tid; e < n_ex; e += T) {  // entries of O_q do not take part in the clustering
-        const int o = ex_idx[e] - chan_base;
-        atomicOr(&removed[o >> 5], 1u << (o & 31));
-    }
-    __syncthreads();
-
-    KM_T(1);
-    // ---- bucket tables: counts and sums of places of the kept weights
-    //      (4 bits of the bitmap per group of 4 weights; no bitmap reads without removed entries)
-#pragma unroll
-    for (int k = 0; k < G; ++k) {
-        const int g = k * T + tid;
-        if (g < n_groups) {
-            const uint32_t kept = n_ex > 0 ? ~(removed[g >> 3] >> ((g & 7) * 4)) & 0xfu : 0xfu;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                if ((kept >> e) & 1u) {
-                    const uint32_t key = elem_key<G>(keys, k, e);
-                    atomicAdd(reinterpret_cast<unsigned long long *>(&sm.scum[key >> kLowBits]),
-                              (1ull << 32) | (key & (kLows - 1)));
-                }
-            }
+    if (n_ex > 0) {  // entries of O_q do not take part in the clustering
+        const int32_t *ex_idx = a.out_idx + sm.seg_lo;
+        const int32_t chan_base = (int32_t)(i * a.d_out);
+        for (int e = tid; e < n_ex; e += T) {
+            const int o = ex_idx[e] - chan_base;
+            atomicOr(&removed[o >> 5], 1u << (o & 31));
         }
+        __syncthreads();
     }
+
+    // ---- bucket tables: counts and sums of places of the kept weights
+    if (n_ex > 0) count_buckets<G, T, LB, true>(keys, removed, sm.scum, n_groups);
+    else count_buckets<G, T, LB, false>(keys, removed, sm.scum, n_groups);
     __syncthreads();
-    KM_T(2);
-    // ---- exclusive prefixes over buckets of count and exact sum; scatter cursors
+    // ---- exclusive prefixes over buckets of count and exact sum; where each bucket's
+    //      stretch of the byte array begins (counts rounded up to whole words)
     {
-        const int per = kBuckets / T > 0 ? kBuckets / T : 1;  // T is a power of two <= 1024
+        const int per = kBuckets / T > 0 ? kBuckets / T : 1;  // T is a power of two
         const int b0 = tid * per;
-        uint32_t n_loc = 0;
+        uint32_t n_loc = 0;  // count | padded count << 16: both stay below 2^16
         long long s_loc = 0;
         if (b0 < kBuckets) {
             for (int r = 0; r < per; ++r) {
                 const unsigned long long packed = (unsigned long long)sm.scum[b0 + r];
+                const uint32_t n = (uint32_t)(packed >> 32);
                 long long q0, step;
                 bucket_affine<LB>((uint32_t)(b0 + r), q0, step);
-                n_loc += (uint32_t)(packed >> 32);
-                s_loc += (long long)(packed >> 32) * q0 + step * (long long)(packed & 0xffffffffu);
+                n_loc += n | (((n + 3) & ~3u) << 16);
+                s_loc += (long long)n * q0 + step * (long long)(packed & 0xffffffffu);
             }
         }
         uint32_t n_run, n_tot;
@@ -615,39 +666,26 @@ __global__ __launch_bounds__(T) __attribute__((amdgpu_waves_per_eu(T <= 256 ? CM
                 long long q0, step;
                 bucket_affine<LB>((uint32_t)(b0 + r), q0, step);
                 const long long sb = (long long)n * q0 + step * (long long)(packed & 0xffffffffu);
-                sm.ncum[b0 + r] = n_run;
-                cursor[b0 + r] = n_run;  // where the next place of the bucket goes
+                sm.ncum[b0 + r] = (uint16_t)(n_run & 0xffffu);
+                sm.start[b0 + r] = (uint16_t)(n_run >> 16);
+                cursor[b0 + r] = n_run >> 16;  // where the next place of the bucket goes
                 sm.scum[b0 + r] = s_run;
-                n_run += n;
+                n_run += n | (((n + 3) & ~3u) << 16);
                 s_run += sb;
             }
         }
         if (tid == 0) {
-            sm.ncum[kBuckets] = n_tot;
+            sm.ncum[kBuckets] = (uint16_t)(n_tot & 0xffffu);
+            sm.start[kBuckets] = (uint16_t)(n_tot >> 16);
             sm.scum[kBuckets] = (long long)s_tot;
         }
     }
     __syncthreads();
     const uint32_t M = sm.ncum[kBuckets];
-    KM_T(3);
-    // ---- scatter the kept keys, ordered by bucket
-#pragma unroll
-    for (int k = 0; k < G; ++k) {
-        const int g = k * T + tid;
-        if (g < n_groups) {
-            const uint32_t kept = n_ex > 0 ? ~(removed[g >> 3] >> ((g & 7) * 4)) & 0xfu : 0xfu;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                if ((kept >> e) & 1u) {
-                    const uint32_t key = elem_key<G>(keys, k, e);
-                    const uint32_t pos = atomicAdd(&cursor[key >> kLowBits], 1u);
-                    arr[pos] = (unsigned char)(key & (kLows - 1));
-                }
-            }
-        }
-    }
+    // ---- scatter the places of the kept weights, ordered by bucket
+    if (n_ex > 0) scatter_places<G, T, LB, true>(keys, removed, cursor, arr, n_groups);
+    else scatter_places<G, T, LB, false>(keys, removed, cursor, arr, n_groups);
     __syncthreads();
-    KM_T(4);
 
     switch (K) {
         case 2: lloyd_bucket<G, 2, T, LB>(a, i, sm, arr, cursor, keys, n_groups, M); break;
@@ -655,12 +693,11 @@ __global__ __launch_bounds__(T) __attribute__((amdgpu_waves_per_eu(T <= 256 ? CM
         case 8: lloyd_bucket<G, 8, T, LB>(a, i, sm, arr, cursor, keys, n_groups, M); break;
         default: lloyd_bucket<G, 16, T, LB>(a, i, sm, arr, cursor, keys, n_groups, M); break;
     }
-    KM_T(5);
     if (tid < CMPQ_KMAX) crow[tid] = tid < K ? sm.cent[tid] : INFINITY;
 }
 
 size_t bucket_dyn_lds(int64_t d_out, int lb) {
-    size_t b = ((size_t)d_out + 15) & ~(size_t)15;
+    size_t b = bucket_arr_bytes(d_out, lb);
     b += (size_t)((((d_out + 31) >> 5) + 3) & ~3) * 4;
     b += ((size_t)1 << (16 - lb)) * 4;
     return b;
