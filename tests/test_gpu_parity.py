@@ -203,6 +203,26 @@ def test_kmeans_parity_degenerate_channels(env):
             _check_kmeans(cent, codes, ocent, ocodes, exact=True)
 
 
+@pytest.mark.parametrize("d_out", [512, 2048, 8192, 28672])
+def test_kmeans_parity_signed_zeros_and_boundaries_at_zero(env, d_out):
+    # +0 and -0 are one value: they share a cell whatever boundary lands on or next to zero
+    rng = np.random.default_rng(d_out + 11)
+    d_in = 12
+    W = rng.normal(0, 0.02, (d_in, d_out)).astype(np.float16)
+    z = rng.random(W.shape)
+    W[z < 0.15] = np.float16(0.0)
+    W[z < 0.075] = np.float16(-0.0)
+    W[0] = rng.choice(np.array([-1.0, -0.0, 0.0, 1.0], np.float16), d_out)        # symmetric: midpoint exactly 0
+    W[1] = rng.choice(np.array([-2.0 ** -24, -0.0, 0.0], np.float16), d_out)      # midpoint just below zero
+    W[2] = rng.choice(np.array([-0.0, 0.0, 2.0 ** -24], np.float16), d_out)
+    W[3] = rng.choice(np.array([-3.0, -0.0, 0.0, 1.0], np.float16), d_out)
+    for nb in (1, 2, 3, 4):
+        bits = np.full(d_in, nb, np.uint8)
+        cent, codes = _kmeans_gpu(env, W, bits, iters=20)
+        ocent, ocodes = env["orc"].kmeans(W, bits, iters=20)
+        _check_kmeans(cent, codes, ocent, ocodes, exact=True)
+
+
 def test_kmeans_parity_with_removed_entries_and_weights(env):
     rng = np.random.default_rng(2)
     d_in, d_out = 32, 777
