@@ -6,7 +6,7 @@
 size_t cmpq_ws_act_stats(int64_t d_in, int64_t n);
 size_t cmpq_ws_allocate_bits(int64_t d_in);
 size_t cmpq_ws_outlier_channels(int64_t d_in);
-size_t cmpq_ws_outlier_weights(int64_t d_in, int64_t d_out);
+size_t cmpq_ws_outlier_weights(int64_t d_in, int64_t d_out, int64_t k);
 size_t cmpq_ws_kmeans(int64_t d_in, int64_t d_out);
 size_t cmpq_ws_pack(int64_t d_in);
 size_t cmpq_ws_dequant_error(int64_t d_in);
@@ -17,7 +17,7 @@ extern "C" size_t cmpq_workspace_bytes(int op, int64_t d_in, int64_t d_out, int6
         case CMPQ_OP_ACT_STATS: return cmpq_ws_act_stats(d_in, n);
         case CMPQ_OP_ALLOCATE_BITS: return cmpq_ws_allocate_bits(d_in);
         case CMPQ_OP_OUTLIER_CHANNELS: return cmpq_ws_outlier_channels(d_in);
-        case CMPQ_OP_OUTLIER_WEIGHTS: return cmpq_ws_outlier_weights(d_in, d_out);
+        case CMPQ_OP_OUTLIER_WEIGHTS: return cmpq_ws_outlier_weights(d_in, d_out, n);
         case CMPQ_OP_KMEANS: return cmpq_ws_kmeans(d_in, d_out);
         case CMPQ_OP_PACK: return cmpq_ws_pack(d_in);
         case CMPQ_OP_DEQUANT_ERROR: return cmpq_ws_dequant_error(d_in);

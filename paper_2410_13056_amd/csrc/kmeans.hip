@@ -324,6 +324,11 @@ __global__ __launch_bounds__(kT) void kmeans_kernel(KmArgs a) {
         kmeans_channel<TW, WEIGHTED>(a, blockIdx.x, lds, sm);
         return;
     }
+    // usually nothing was left over: look at all flags of this workgroup's channels at once
+    int any = 0;
+    for (int64_t i = blockIdx.x + (int64_t)threadIdx.x * gridDim.x; i < a.d_in; i += (int64_t)kT * gridDim.x)
+        any |= a.deferred[i];
+    if (!__syncthreads_or(any)) return;
     for (int64_t i = blockIdx.x; i < a.d_in; i += gridDim.x) {
         if (!a.deferred[i]) continue;
         __syncthreads();  // LDS of the previous channel is no longer in use

@@ -719,6 +719,12 @@ int launch_variant(const KmArgs &a, hipStream_t s) {
 
 }  // namespace
 
+#ifndef CMPQ_LB512
+#define CMPQ_LB512 6
+#endif
+#ifndef CMPQ_LB256
+#define CMPQ_LB256 7
+#endif
 int launch_kmeans_hist(const KmArgs &a, hipStream_t s) {
     // A power-of-two workgroup of at most 512 lanes: up to 32 weights per lane, 64 for the
     // longest channels (two workgroups of 512 share a compute unit where one of 1024
@@ -728,12 +734,12 @@ int launch_kmeans_hist(const KmArgs &a, hipStream_t s) {
     while (T < 512 && T * 8 < groups) T <<= 1;
     const int64_t per_lane = cdiv(groups, T);
     if (per_lane > 16) return CMPQ_ESHAPE;
-    if (per_lane > 8) return launch_variant<16, 512, 6>(a, s);
+    if (per_lane > 8) return launch_variant<16, 512, CMPQ_LB512>(a, s);
     if (per_lane > 4) {
         switch (T) {
-            case 512: return launch_variant<8, 512, 6>(a, s);
-            case 256: return launch_variant<8, 256, 6>(a, s);
-            case 128: return launch_variant<8, 128, 6>(a, s);
+            case 512: return launch_variant<8, 512, CMPQ_LB512>(a, s);
+            case 256: return launch_variant<8, 256, CMPQ_LB256>(a, s);
+            case 128: return launch_variant<8, 128, 7>(a, s);
             default: return launch_variant<8, 64, 7>(a, s);
         }
     }

@@ -136,11 +136,25 @@ __global__ __launch_bounds__(kSelThreads) void allocate_bits_kernel(
 }
 
 // ------------------------------------------------------------------ whole layer, d_in*d_out keys
+//
+// Top-k of the scores of a whole layer, written in ascending linear index.  Three
+// histogram passes over the data fix the threshold key digit by digit (11 + 11 + 10
+// bits).  The data is shared out in wave-chunks (512 consecutive entries of one channel,
+// 8 per lane); a unit is one wavefront with a contiguous run of wave-chunks, four
+// consecutive units make a workgroup.  The last histogram pass also sets aside, unit by
+// unit and in index order, every entry whose top 22 bits reach the prefix known by then
+// - a superset of the answer that is a little over k entries long - so the result is
+// written from this staging list without a fourth pass over the data.  When a unit's
+// share of the list does not fit (many equal scores, or an unusual concentration), a
+// flag sends the call down the full path: per-workgroup tables from the last pass and
+// one more pass over the data.
 
 constexpr int kWThreads = 256;
-constexpr int kWPerThread = 8;
-constexpr int kChunk = kWThreads * kWPerThread;  // elements of one channel handled per step
+constexpr int kWaves = kWThreads / CMPQ_WAVE;
+constexpr int kWPerLane = 8;
+constexpr int kWaveChunk = CMPQ_WAVE * kWPerLane;
 constexpr int kMaxBlocks = 2048;
+constexpr int kMaxUnits = kMaxBlocks * kWaves;
 constexpr int kBins = 2048;
 
 struct WselState {
@@ -149,6 +163,7 @@ struct WselState {
     uint64_t rem;       // rank still to resolve inside the current prefix
     uint64_t need;      // ties (key == T) to take, in index order
     uint64_t total;     // number of candidate keys
+    uint32_t overflow;  // a unit's staging share was too small: take the full path
 };
 
 struct WselArgs {
@@ -157,64 +172,133 @@ struct WselArgs {
     const uint8_t *codes;
     const uint8_t *bits;
     int64_t d_in, d_out, ldw;
-    int64_t chunks_per_channel, total_chunks, chunks_per_block;
+    int64_t wc_per_channel, total_wc, wc_per_unit;
     int score;
     int vec_ok;  // 16-byte loads of W and 8-byte loads of codes are aligned
+    unsigned long long *stage_ik;  // per unit `cap` entries: linear index << 32 | key
+    uint16_t *stage_val;           //   and the entry's value as fp16 bits
+    uint32_t *stage_cnt;           // entries staged per unit
+    uint32_t cap;
 };
 
-// Keys of 8 consecutive entries of channel i starting at output o0 (o0 % 8 == 0).
-// valid bit j set when o0+j < d_out.
+struct WselPlan {
+    int64_t wc_per_channel, total_wc, wc_per_unit;
+    int nunits, nblocks;
+    uint32_t cap;
+};
+
+WselPlan wsel_plan(int64_t d_in, int64_t d_out, int64_t k) {
+    WselPlan p;
+    p.wc_per_channel = cdiv(d_out, kWaveChunk);
+    p.total_wc = p.wc_per_channel * d_in;
+    int64_t nu = p.total_wc < kMaxUnits ? p.total_wc : kMaxUnits;
+    if (nu < 1) nu = 1;
+    p.wc_per_unit = cdiv(p.total_wc, nu);
+    if (p.wc_per_unit < 1) p.wc_per_unit = 1;
+    nu = cdiv(p.total_wc, p.wc_per_unit);
+    if (nu < 1) nu = 1;
+    p.nblocks = (int)cdiv(nu, kWaves);
+    p.nunits = p.nblocks * kWaves;
+    // four times a unit's even share of k, plus room for small inputs
+    int64_t cap = 4 * cdiv(k, nu) + 256;
+    if (cap > p.wc_per_unit * kWaveChunk) cap = p.wc_per_unit * kWaveChunk;
+    p.cap = (uint32_t)cap;
+    return p;
+}
+
+// Eight consecutive entries of a channel as loaded: weights and codes still packed.
 template <typename TW>
-__device__ __forceinline__ uint32_t load_keys8(const WselArgs &a, int64_t i, int64_t o0,
-                                               const float *__restrict__ lut, uint32_t (&key)[8],
-                                               float (&wv)[8]) {
-    uint32_t valid = 0;
-    const TW *wrow = static_cast<const TW *>(a.W) + i * a.ldw;
-    const uint8_t *crow = a.codes ? a.codes + i * a.d_out : nullptr;
-    uint8_t c[8];
-    if (a.vec_ok && o0 + 8 <= a.d_out) {
-        valid = 0xffu;
-        if constexpr (sizeof(TW) == 2) {
-            const uint4 raw = *reinterpret_cast<const uint4 *>(wrow + o0);
-            const __half2 *h = reinterpret_cast<const __half2 *>(&raw);
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                float2 t = __half22float2(h[j]);
-                wv[2 * j] = t.x;
-                wv[2 * j + 1] = t.y;
-            }
-        } else {
-            const float4 r0 = *reinterpret_cast<const float4 *>(wrow + o0);
-            const float4 r1 = *reinterpret_cast<const float4 *>(wrow + o0 + 4);
-            wv[0] = r0.x, wv[1] = r0.y, wv[2] = r0.z, wv[3] = r0.w;
-            wv[4] = r1.x, wv[5] = r1.y, wv[6] = r1.z, wv[7] = r1.w;
-        }
-        if (crow) {
-            const uint2 cr = *reinterpret_cast<const uint2 *>(crow + o0);
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                c[j] = (cr.x >> (8 * j)) & 0xff;
-                c[4 + j] = (cr.y >> (8 * j)) & 0xff;
-            }
-        }
-    } else {
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            wv[j] = 0.f;
-            c[j] = 0;
-            if (o0 + j < a.d_out) {
-                valid |= 1u << j;
-                wv[j] = load_as_f32<TW>(wrow, o0 + j);
-                if (crow) c[j] = crow[o0 + j];
-            }
-        }
-    }
+struct Raw8;
+template <>
+struct Raw8<__half> {
+    uint4 w;
+    uint2 c;
+};
+template <>
+struct Raw8<float> {
+    float4 w0, w1;
+    uint2 c;
+};
+
+__device__ __forceinline__ uint2 fetch_codes8(const WselArgs &a, int64_t i, int64_t o0, bool vec) {
+    uint2 c = make_uint2(0, 0);
+    if (!a.codes) return c;
+    const uint8_t *crow = a.codes + i * a.d_out;
+    if (vec) return *reinterpret_cast<const uint2 *>(crow + o0);
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-        const float s = a.score == CMPQ_SCORE_RESIDUAL ? fabsf(wv[j] - lut[c[j] & 15]) : fabsf(wv[j]);
+        if (o0 + j < a.d_out) {
+            const uint32_t b = crow[o0 + j];
+            if (j < 4) c.x |= b << (8 * j); else c.y |= b << (8 * (j - 4));
+        }
+    }
+    return c;
+}
+
+__device__ __forceinline__ void fetch8(const WselArgs &a, int64_t i, int64_t o0, Raw8<__half> &r) {
+    const uint16_t *wrow = static_cast<const uint16_t *>(a.W) + i * a.ldw;
+    const bool vec = a.vec_ok && o0 + 8 <= a.d_out;
+    if (vec) {
+        r.w = *reinterpret_cast<const uint4 *>(wrow + o0);
+    } else {
+        uint32_t h[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) h[j] = o0 + j < a.d_out ? wrow[o0 + j] : 0u;
+        r.w = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
+    }
+    r.c = fetch_codes8(a, i, o0, vec);
+}
+
+__device__ __forceinline__ void fetch8(const WselArgs &a, int64_t i, int64_t o0, Raw8<float> &r) {
+    const float *wrow = static_cast<const float *>(a.W) + i * a.ldw;
+    const bool vec = a.vec_ok && o0 + 8 <= a.d_out;
+    if (vec) {
+        r.w0 = *reinterpret_cast<const float4 *>(wrow + o0);
+        r.w1 = *reinterpret_cast<const float4 *>(wrow + o0 + 4);
+    } else {
+        float f[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) f[j] = o0 + j < a.d_out ? wrow[o0 + j] : 0.f;
+        r.w0 = make_float4(f[0], f[1], f[2], f[3]);
+        r.w1 = make_float4(f[4], f[5], f[6], f[7]);
+    }
+    r.c = fetch_codes8(a, i, o0, vec);
+}
+
+__device__ __forceinline__ void unpack8(const Raw8<__half> &r, float (&wv)[8]) {
+    const __half2 *h = reinterpret_cast<const __half2 *>(&r.w);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const float2 t = __half22float2(h[j]);
+        wv[2 * j] = t.x;
+        wv[2 * j + 1] = t.y;
+    }
+}
+__device__ __forceinline__ void unpack8(const Raw8<float> &r, float (&wv)[8]) {
+    wv[0] = r.w0.x, wv[1] = r.w0.y, wv[2] = r.w0.z, wv[3] = r.w0.w;
+    wv[4] = r.w1.x, wv[5] = r.w1.y, wv[6] = r.w1.z, wv[7] = r.w1.w;
+}
+
+// Score keys of the 8 entries.  `cent` holds level (lane & 15) of the channel: the level
+// of a code comes from the lane of that number (all lanes of the wavefront take part).
+template <typename TW>
+__device__ __forceinline__ void score_keys8(const WselArgs &a, const Raw8<TW> &r, float cent,
+                                            uint32_t (&key)[8], float (&wv)[8]) {
+    unpack8(r, wv);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        float s = fabsf(wv[j]);
+        if (a.score == CMPQ_SCORE_RESIDUAL) {
+            const int code = (int)(((j < 4 ? r.c.x : r.c.y) >> (8 * (j & 3))) & 15u);
+            s = fabsf(wv[j] - __shfl(cent, code, CMPQ_WAVE));
+        }
         key[j] = __float_as_uint(s);
     }
-    return valid;
+}
+
+__device__ __forceinline__ uint32_t valid8(int64_t o0, int64_t d_out) {
+    if (o0 + 8 <= d_out) return 0xffu;
+    return o0 < d_out ? (1u << (int)(d_out - o0)) - 1u : 0u;
 }
 
 __device__ __forceinline__ bool channel_live(const WselArgs &a, int64_t i) {
@@ -222,11 +306,46 @@ __device__ __forceinline__ bool channel_live(const WselArgs &a, int64_t i) {
     return b >= 1 && b <= 4;
 }
 
-__device__ __forceinline__ void stage_lut(const WselArgs &a, int64_t i, float *lut) {
-    __syncthreads();
-    if (threadIdx.x < CMPQ_KMAX)
-        lut[threadIdx.x] = a.centroids ? a.centroids[i * CMPQ_KMAX + threadIdx.x] : 0.f;
-    __syncthreads();
+// Calls body(i, o0, key, wv, valid) for every wave-chunk in [q0, q1) of a live channel,
+// in order; o0 is this lane's first output.  The loads of the next wave-chunk are issued
+// before the current one is worked on.
+template <typename TW, typename F>
+__device__ __forceinline__ void for_each_wave_chunk(const WselArgs &a, int64_t q0, int64_t q1, F &&body) {
+    if (q0 >= q1) return;
+    const int lane = threadIdx.x & (CMPQ_WAVE - 1);
+    int64_t i = q0 / a.wc_per_channel, c = q0 % a.wc_per_channel;
+    bool live = channel_live(a, i);
+    float cent = live && a.centroids ? a.centroids[i * CMPQ_KMAX + (lane & 15)] : 0.f;
+    Raw8<TW> cur = {}, nxt = {};
+    if (live) fetch8(a, i, c * kWaveChunk + lane * kWPerLane, cur);
+    for (int64_t q = q0; q < q1; ++q) {
+        int64_t ni = i, nc = c + 1;
+        bool live_n = live;
+        float cent_n = cent;
+        if (nc == a.wc_per_channel) {
+            nc = 0;
+            ++ni;
+        }
+        if (q + 1 < q1) {
+            if (ni != i) {
+                live_n = channel_live(a, ni);
+                cent_n = live_n && a.centroids ? a.centroids[ni * CMPQ_KMAX + (lane & 15)] : 0.f;
+            }
+            if (live_n) fetch8(a, ni, nc * kWaveChunk + lane * kWPerLane, nxt);
+        }
+        if (live) {
+            const int64_t o0 = c * kWaveChunk + lane * kWPerLane;
+            uint32_t key[8];
+            float wv[8];
+            score_keys8<TW>(a, cur, cent, key, wv);
+            body(i, o0, key, wv, valid8(o0, a.d_out));
+        }
+        cur = nxt;
+        i = ni;
+        c = nc;
+        live = live_n;
+        cent = cent_n;
+    }
 }
 
 __global__ void wsel_init_kernel(WselState *st, uint32_t *hist, uint64_t k, int32_t *idx_out,
@@ -239,38 +358,35 @@ __global__ void wsel_init_kernel(WselState *st, uint32_t *hist, uint64_t k, int3
         st->rem = k;
         st->need = 0;
         st->total = 0;
+        st->overflow = 0;
     }
     for (int64_t j = t; j < k_fill; j += (int64_t)gridDim.x * blockDim.x) idx_out[j] = -1;
 }
 
 // PASS 0: digit = key >> 21 (11 bits), PASS 1: (key >> 10) & 2047, PASS 2: key & 1023.
-// The last pass also leaves, per workgroup, how many of its keys lie above the 22-bit
-// prefix and its own histogram of the last digit: once the threshold is known, the
-// counts that ordered compaction needs follow from these without another pass.
+// The last pass also stages the entries whose top 22 bits reach the prefix and leaves,
+// per workgroup, how many of its keys lie above the 22-bit prefix and its own histogram
+// of the last digit (what the full path needs to place its output without counting again).
 template <typename TW, int PASS>
-__global__ __launch_bounds__(kWThreads) void wsel_hist_kernel(WselArgs a, const WselState *st,
+__global__ __launch_bounds__(kWThreads) void wsel_hist_kernel(WselArgs a, WselState *st,
                                                                uint32_t *__restrict__ hist,
                                                                uint32_t *__restrict__ above,
                                                                uint32_t *__restrict__ local_last) {
     __shared__ uint32_t lh[kBins];
-    __shared__ float lut[CMPQ_KMAX];
-    __shared__ uint32_t red[kWThreads / CMPQ_WAVE];
+    __shared__ uint32_t red[kWaves];
     for (int b = threadIdx.x; b < kBins; b += kWThreads) lh[b] = 0;
+    __syncthreads();
     const uint32_t prefix = PASS == 0 ? 0u : st->prefix;
-    const int64_t q0 = (int64_t)blockIdx.x * a.chunks_per_block;
-    const int64_t q1 = min(a.total_chunks, q0 + a.chunks_per_block);
-    int64_t cur = -1;
-    uint32_t n_above = 0;
-    for (int64_t q = q0; q < q1; ++q) {
-        const int64_t i = q / a.chunks_per_channel, c = q % a.chunks_per_channel;
-        if (!channel_live(a, i)) continue;
-        if (i != cur) {
-            stage_lut(a, i, lut);
-            cur = i;
-        }
-        uint32_t key[8];
-        float wv[8];
-        const uint32_t valid = load_keys8<TW>(a, i, c * kChunk + threadIdx.x * kWPerThread, lut, key, wv);
+    const int lane = threadIdx.x & (CMPQ_WAVE - 1), wave = threadIdx.x / CMPQ_WAVE;
+    const int64_t unit = (int64_t)blockIdx.x * kWaves + wave;
+    const int64_t q0 = unit * a.wc_per_unit;
+    const int64_t q1 = min(a.total_wc, q0 + a.wc_per_unit);
+    uint32_t n_above = 0, n_staged = 0;
+    bool over = false;
+    unsigned long long *stage_ik = a.stage_ik + unit * a.cap;
+    uint16_t *stage_val = a.stage_val + unit * a.cap;
+    for_each_wave_chunk<TW>(a, q0, q1, [&](int64_t i, int64_t o0, const uint32_t (&key)[8], const float (&wv)[8], uint32_t valid) {
+        uint32_t n_cand = 0;
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             if (!((valid >> j) & 1u)) continue;
@@ -281,20 +397,43 @@ __global__ __launch_bounds__(kWThreads) void wsel_hist_kernel(WselArgs a, const 
             } else {
                 if ((key[j] >> 10) == (prefix >> 10)) atomicAdd(&lh[key[j] & 1023u], 1u);
                 n_above += (key[j] >> 10) > (prefix >> 10);
+                n_cand += (key[j] >> 10) >= (prefix >> 10);
             }
         }
-    }
+        if (PASS == 2 && __ballot(n_cand != 0) != 0ull) {
+            const uint32_t incl = wave_scan_incl_u32(n_cand);
+            const uint32_t tot = __shfl(incl, CMPQ_WAVE - 1, CMPQ_WAVE);
+            if (n_staged + tot <= a.cap) {
+                uint32_t pos = n_staged + incl - n_cand;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    if (((valid >> j) & 1u) && (key[j] >> 10) >= (prefix >> 10)) {
+                        stage_ik[pos] = ((unsigned long long)(uint32_t)(i * a.d_out + o0 + j) << 32) | key[j];
+                        stage_val[pos] = __half_as_ushort(__float2half_rn(wv[j]));
+                        ++pos;
+                    }
+                }
+            } else {
+                over = true;
+            }
+            n_staged += tot;
+        }
+    });
     __syncthreads();
     for (int b = threadIdx.x; b < kBins; b += kWThreads)
         if (lh[b]) atomicAdd(&hist[PASS * kBins + b], lh[b]);
     if (PASS == 2) {
+        if (lane == 0) {
+            a.stage_cnt[unit] = over ? 0u : n_staged;
+            if (over) st->overflow = 1u;
+        }
         for (int b = threadIdx.x; b < 1024; b += kWThreads) local_last[(int64_t)blockIdx.x * 1024 + b] = lh[b];
         n_above = wave_sum_u32(n_above);
-        if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = n_above;
+        if (lane == 0) red[wave] = n_above;
         __syncthreads();
         if (threadIdx.x == 0) {
             uint32_t t = 0;
-            for (int w = 0; w < kWThreads / CMPQ_WAVE; ++w) t += red[w];
+            for (int w = 0; w < kWaves; ++w) t += red[w];
             above[blockIdx.x] = t;
         }
     }
@@ -343,50 +482,72 @@ __global__ __launch_bounds__(1024) void wsel_pick_kernel(WselState *st, const ui
     }
 }
 
-// Per workgroup of the passes: keys above the threshold and keys equal to it, from the
-// tables the last histogram pass left.
-__global__ __launch_bounds__(kWThreads) void wsel_count_kernel(const WselState *st,
+// Keys above the threshold and keys equal to it: per unit from the staging list, or, on
+// the full path, per workgroup from the tables the last histogram pass left.
+__global__ __launch_bounds__(kWThreads) void wsel_count_kernel(const WselState *st, WselArgs a,
                                                                 const uint32_t *__restrict__ above,
                                                                 const uint32_t *__restrict__ local_last,
                                                                 uint32_t *__restrict__ cnt_gt,
                                                                 uint32_t *__restrict__ cnt_eq) {
-    __shared__ uint32_t red[kWThreads / CMPQ_WAVE];
-    const uint32_t digit = st->T & 1023u;
+    __shared__ uint32_t red[kWaves];
+    const int lane = threadIdx.x & (CMPQ_WAVE - 1), wave = threadIdx.x / CMPQ_WAVE;
+    const uint32_t T = st->T;
+    if (!st->overflow) {
+        const int64_t unit = (int64_t)blockIdx.x * kWaves + wave;
+        const unsigned long long *ik = a.stage_ik + unit * a.cap;
+        const uint32_t n = a.stage_cnt[unit];
+        uint32_t gt = 0, eq = 0;
+        for (uint32_t e = lane; e < n; e += CMPQ_WAVE) {
+            const uint32_t key = (uint32_t)ik[e];
+            gt += key > T;
+            eq += key == T;
+        }
+        gt = wave_sum_u32(gt);
+        eq = wave_sum_u32(eq);
+        if (lane == 0) {
+            cnt_gt[unit] = gt;
+            cnt_eq[unit] = eq;
+        }
+        return;
+    }
+    const uint32_t digit = T & 1023u;
     const bool everything = st->need == ~0ull;  // more asked than there is: every candidate counts
     const uint32_t *h = local_last + (int64_t)blockIdx.x * 1024;
     uint32_t gt = 0;
     for (int b = threadIdx.x; b < 1024; b += kWThreads)
         if (everything ? b > 0 : (uint32_t)b > digit) gt += h[b];
     gt = wave_sum_u32(gt);
-    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = gt;
+    if (lane == 0) red[wave] = gt;
     __syncthreads();
     if (threadIdx.x == 0) {
         uint32_t g = above[blockIdx.x];
-        for (int w = 0; w < kWThreads / CMPQ_WAVE; ++w) g += red[w];
+        for (int w = 0; w < kWaves; ++w) g += red[w];
         cnt_gt[blockIdx.x] = g;
         cnt_eq[blockIdx.x] = h[everything ? 0 : digit];
     }
 }
 
-// Exclusive prefix over workgroups of (ties seen) and (entries written).
-__global__ __launch_bounds__(1024) void wsel_offsets_kernel(const WselState *st, int nblocks,
+// Exclusive prefix over units (or workgroups, on the full path) of (ties seen) and
+// (entries written).
+__global__ __launch_bounds__(1024) void wsel_offsets_kernel(const WselState *st, int nunits, int nblocks,
                                                             const uint32_t *__restrict__ cnt_gt,
                                                             const uint32_t *__restrict__ cnt_eq,
                                                             uint64_t *__restrict__ tie_base,
                                                             uint64_t *__restrict__ out_base) {
     __shared__ uint32_t scan[17];
     const uint64_t need = st->need;
+    const int n = st->overflow ? nblocks : nunits;
     uint64_t tie_run = 0, out_run = 0;
-    for (int base = 0; base < nblocks; base += 1024) {
+    for (int base = 0; base < n; base += 1024) {
         const int b = base + threadIdx.x;
-        const uint32_t e = b < nblocks ? cnt_eq[b] : 0, g = b < nblocks ? cnt_gt[b] : 0;
+        const uint32_t e = b < n ? cnt_eq[b] : 0, g = b < n ? cnt_gt[b] : 0;
         uint32_t e_total, w_total;
         const uint64_t tb = tie_run + block_scan_excl_u32(e, scan, &e_total);
-        // ties of this workgroup that are still within the first `need`
+        // ties of this unit that are still within the first `need`
         uint64_t take = 0;
         if (tb < need) take = (need - tb) < e ? (need - tb) : e;
         const uint64_t ob = out_run + block_scan_excl_u32(g + (uint32_t)take, scan, &w_total);
-        if (b < nblocks) {
+        if (b < n) {
             tie_base[b] = tb;
             out_base[b] = ob;
         }
@@ -395,30 +556,72 @@ __global__ __launch_bounds__(1024) void wsel_offsets_kernel(const WselState *st,
     }
 }
 
+__device__ __forceinline__ uint32_t lanes_below(unsigned long long mask) {
+    return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+}
+
+// Writes the answer from the staging list: a wavefront per unit, 64 staged entries a step.
+__global__ __launch_bounds__(kWThreads) void wsel_emit_kernel(WselArgs a, const WselState *st,
+                                                               const uint64_t *__restrict__ tie_base,
+                                                               const uint64_t *__restrict__ out_base,
+                                                               int64_t k, int32_t *__restrict__ idx_out,
+                                                               uint16_t *__restrict__ val_out) {
+    if (st->overflow) return;
+    const int lane = threadIdx.x & (CMPQ_WAVE - 1), wave = threadIdx.x / CMPQ_WAVE;
+    const int64_t unit = (int64_t)blockIdx.x * kWaves + wave;
+    const uint32_t T = st->T;
+    const uint64_t need = st->need;
+    const unsigned long long *ik = a.stage_ik + unit * a.cap;
+    const uint16_t *sv = a.stage_val + unit * a.cap;
+    const uint32_t n = a.stage_cnt[unit];
+    uint64_t ties = tie_base[unit], outp = out_base[unit];
+    for (uint32_t e0 = 0; e0 < n; e0 += CMPQ_WAVE) {
+        const uint32_t e = e0 + lane;
+        const unsigned long long v = e < n ? ik[e] : 0ull;
+        const uint32_t key = (uint32_t)v;
+        const bool is_eq = e < n && key == T, is_gt = e < n && key > T;
+        const unsigned long long eq_mask = __ballot(is_eq);
+        const bool sel = is_gt || (is_eq && ties + lanes_below(eq_mask) < need);
+        const unsigned long long sel_mask = __ballot(sel);
+        const uint64_t pos = outp + lanes_below(sel_mask);
+        if (sel && (int64_t)pos < k) {
+            idx_out[pos] = (int32_t)(v >> 32);
+            if (val_out) val_out[pos] = sv[e];
+        }
+        ties += __popcll(eq_mask);
+        outp += __popcll(sel_mask);
+    }
+}
+
+// Full path: one more pass over the data, a workgroup per run of 4 units, 4 wave-chunks
+// (2048 consecutive entries) a step.
 template <typename TW>
 __global__ __launch_bounds__(kWThreads) void wsel_write_kernel(
     WselArgs a, const WselState *st, const uint64_t *__restrict__ tie_base,
     const uint64_t *__restrict__ out_base, int64_t k, int32_t *__restrict__ idx_out,
     uint16_t *__restrict__ val_out) {
-    __shared__ float lut[CMPQ_KMAX];
     __shared__ uint32_t scan[34];
+    if (!st->overflow) return;
+    const int lane = threadIdx.x & (CMPQ_WAVE - 1), wave = threadIdx.x / CMPQ_WAVE;
     const uint32_t T = st->T;
     const uint64_t need = st->need;
     uint64_t ties = tie_base[blockIdx.x], outp = out_base[blockIdx.x];
-    const int64_t q0 = (int64_t)blockIdx.x * a.chunks_per_block;
-    const int64_t q1 = min(a.total_chunks, q0 + a.chunks_per_block);
-    int64_t cur = -1;
-    for (int64_t q = q0; q < q1; ++q) {
-        const int64_t i = q / a.chunks_per_channel, c = q % a.chunks_per_channel;
-        if (!channel_live(a, i)) continue;
-        if (i != cur) {
-            stage_lut(a, i, lut);
-            cur = i;
+    const int64_t q0 = (int64_t)blockIdx.x * kWaves * a.wc_per_unit;
+    const int64_t q1 = min(a.total_wc, q0 + kWaves * a.wc_per_unit);
+    for (int64_t qb = q0; qb < q1; qb += kWaves) {
+        const int64_t q = qb + wave;
+        const int64_t i = q / a.wc_per_channel, c = q % a.wc_per_channel;
+        const int64_t o0 = c * kWaveChunk + lane * kWPerLane;
+        uint32_t key[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+        float wv[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        uint32_t valid = 0;
+        if (q < q1 && channel_live(a, i)) {  // uniform over the wavefront
+            Raw8<TW> raw;
+            fetch8(a, i, o0, raw);
+            const float cent = a.centroids ? a.centroids[i * CMPQ_KMAX + (lane & 15)] : 0.f;
+            score_keys8<TW>(a, raw, cent, key, wv);
+            valid = valid8(o0, a.d_out);
         }
-        uint32_t key[8];
-        float wv[8];
-        const int64_t o0 = c * kChunk + threadIdx.x * kWPerThread;
-        const uint32_t valid = load_keys8<TW>(a, i, o0, lut, key, wv);
         uint32_t n_eq = 0, n_gt = 0;
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
@@ -457,46 +660,52 @@ __global__ __launch_bounds__(kWThreads) void wsel_write_kernel(
     }
 }
 
-struct WselPlan {
-    int64_t chunks_per_channel, total_chunks, chunks_per_block;
-    int nblocks;
+struct WselWs {
+    WselState *st;
+    uint32_t *hist, *cnt_gt, *cnt_eq, *above, *local_last, *stage_cnt;
+    uint64_t *tie_base, *out_base;
+    unsigned long long *stage_ik;
+    uint16_t *stage_val;
+    size_t bytes;
 };
 
-WselPlan wsel_plan(int64_t d_in, int64_t d_out) {
-    WselPlan p;
-    p.chunks_per_channel = cdiv(d_out, kChunk);
-    p.total_chunks = p.chunks_per_channel * d_in;
-    int64_t nb = p.total_chunks < kMaxBlocks ? p.total_chunks : kMaxBlocks;
-    if (nb < 1) nb = 1;
-    p.chunks_per_block = cdiv(p.total_chunks, nb);
-    if (p.chunks_per_block < 1) p.chunks_per_block = 1;
-    p.nblocks = (int)cdiv(p.total_chunks, p.chunks_per_block);
-    if (p.nblocks < 1) p.nblocks = 1;
-    return p;
+WselWs wsel_carve(void *ws, const WselPlan &p) {
+    WsCarver carve(ws);
+    WselWs w;
+    w.st = carve.take<WselState>(1);
+    w.hist = carve.take<uint32_t>(3 * kBins);
+    w.cnt_gt = carve.take<uint32_t>(kMaxUnits);
+    w.cnt_eq = carve.take<uint32_t>(kMaxUnits);
+    w.tie_base = carve.take<uint64_t>(kMaxUnits);
+    w.out_base = carve.take<uint64_t>(kMaxUnits);
+    w.above = carve.take<uint32_t>(kMaxBlocks);
+    w.local_last = carve.take<uint32_t>((size_t)kMaxBlocks * 1024);
+    w.stage_cnt = carve.take<uint32_t>(kMaxUnits);
+    w.stage_ik = carve.take<unsigned long long>((size_t)p.nunits * p.cap);
+    w.stage_val = carve.take<uint16_t>((size_t)p.nunits * p.cap);
+    w.bytes = carve.need();
+    return w;
 }
 
 template <typename TW>
-int launch_weight_select(const WselArgs &a, const WselPlan &p, int64_t k, int32_t *idx_out,
+int launch_weight_select(WselArgs a, const WselPlan &p, int64_t k, int32_t *idx_out,
                          uint16_t *val_out, void *ws, hipStream_t s) {
-    WsCarver carve(ws);
-    WselState *st = carve.take<WselState>(1);
-    uint32_t *hist = carve.take<uint32_t>(3 * kBins);
-    uint32_t *cnt_gt = carve.take<uint32_t>(kMaxBlocks);
-    uint32_t *cnt_eq = carve.take<uint32_t>(kMaxBlocks);
-    uint64_t *tie_base = carve.take<uint64_t>(kMaxBlocks);
-    uint64_t *out_base = carve.take<uint64_t>(kMaxBlocks);
-    uint32_t *above = carve.take<uint32_t>(kMaxBlocks);
-    uint32_t *local_last = carve.take<uint32_t>((size_t)kMaxBlocks * 1024);
-    wsel_init_kernel<<<64, 256, 0, s>>>(st, hist, (uint64_t)k, idx_out, k);
-    wsel_hist_kernel<TW, 0><<<p.nblocks, kWThreads, 0, s>>>(a, st, hist, above, local_last);
-    wsel_pick_kernel<0><<<1, 1024, 0, s>>>(st, hist);
-    wsel_hist_kernel<TW, 1><<<p.nblocks, kWThreads, 0, s>>>(a, st, hist, above, local_last);
-    wsel_pick_kernel<1><<<1, 1024, 0, s>>>(st, hist);
-    wsel_hist_kernel<TW, 2><<<p.nblocks, kWThreads, 0, s>>>(a, st, hist, above, local_last);
-    wsel_pick_kernel<2><<<1, 1024, 0, s>>>(st, hist);
-    wsel_count_kernel<<<p.nblocks, kWThreads, 0, s>>>(st, above, local_last, cnt_gt, cnt_eq);
-    wsel_offsets_kernel<<<1, 1024, 0, s>>>(st, p.nblocks, cnt_gt, cnt_eq, tie_base, out_base);
-    wsel_write_kernel<TW><<<p.nblocks, kWThreads, 0, s>>>(a, st, tie_base, out_base, k, idx_out, val_out);
+    const WselWs w = wsel_carve(ws, p);
+    a.stage_ik = w.stage_ik;
+    a.stage_val = w.stage_val;
+    a.stage_cnt = w.stage_cnt;
+    a.cap = p.cap;
+    wsel_init_kernel<<<64, 256, 0, s>>>(w.st, w.hist, (uint64_t)k, idx_out, k);
+    wsel_hist_kernel<TW, 0><<<p.nblocks, kWThreads, 0, s>>>(a, w.st, w.hist, w.above, w.local_last);
+    wsel_pick_kernel<0><<<1, 1024, 0, s>>>(w.st, w.hist);
+    wsel_hist_kernel<TW, 1><<<p.nblocks, kWThreads, 0, s>>>(a, w.st, w.hist, w.above, w.local_last);
+    wsel_pick_kernel<1><<<1, 1024, 0, s>>>(w.st, w.hist);
+    wsel_hist_kernel<TW, 2><<<p.nblocks, kWThreads, 0, s>>>(a, w.st, w.hist, w.above, w.local_last);
+    wsel_pick_kernel<2><<<1, 1024, 0, s>>>(w.st, w.hist);
+    wsel_count_kernel<<<p.nblocks, kWThreads, 0, s>>>(w.st, a, w.above, w.local_last, w.cnt_gt, w.cnt_eq);
+    wsel_offsets_kernel<<<1, 1024, 0, s>>>(w.st, p.nunits, p.nblocks, w.cnt_gt, w.cnt_eq, w.tie_base, w.out_base);
+    wsel_emit_kernel<<<p.nblocks, kWThreads, 0, s>>>(a, w.st, w.tie_base, w.out_base, k, idx_out, val_out);
+    wsel_write_kernel<TW><<<p.nblocks, kWThreads, 0, s>>>(a, w.st, w.tie_base, w.out_base, k, idx_out, val_out);
     CMPQ_LAUNCH_CHECK();
     return CMPQ_OK;
 }
@@ -505,17 +714,9 @@ int launch_weight_select(const WselArgs &a, const WselPlan &p, int64_t k, int32_
 
 size_t cmpq_ws_allocate_bits(int64_t) { return 256; }
 size_t cmpq_ws_outlier_channels(int64_t) { return 256; }
-size_t cmpq_ws_outlier_weights(int64_t, int64_t) {
-    WsCarver carve(nullptr);
-    carve.take<WselState>(1);
-    carve.take<uint32_t>(3 * kBins);
-    carve.take<uint32_t>(kMaxBlocks);
-    carve.take<uint32_t>(kMaxBlocks);
-    carve.take<uint64_t>(kMaxBlocks);
-    carve.take<uint64_t>(kMaxBlocks);
-    carve.take<uint32_t>(kMaxBlocks);
-    carve.take<uint32_t>((size_t)kMaxBlocks * 1024);
-    return carve.need();
+size_t cmpq_ws_outlier_weights(int64_t d_in, int64_t d_out, int64_t k) {
+    if (k < 0) k = 0;
+    return wsel_carve(nullptr, wsel_plan(d_in, d_out, k)).bytes;
 }
 
 extern "C" int cmpq_allocate_bits(const float *sumsq, int64_t d_in, const uint8_t *chan_mask,
@@ -607,9 +808,9 @@ extern "C" int cmpq_extract_outliers(int mode, int score, const float *sumsq, co
     if (d_in > 0 && d_out > ((int64_t)1 << 31) / d_in) return CMPQ_ESHAPE;  // linear index in int32
     if (k > d_in * d_out) return CMPQ_ECOUNT;
     if (k == 0 || d_in == 0 || d_out == 0) return CMPQ_OK;
-    if (!ws || reinterpret_cast<uintptr_t>(ws) % 256 != 0 || ws_bytes < cmpq_ws_outlier_weights(d_in, d_out))
+    if (!ws || reinterpret_cast<uintptr_t>(ws) % 256 != 0 || ws_bytes < cmpq_ws_outlier_weights(d_in, d_out, k))
         return CMPQ_EWORKSPACE;
-    const WselPlan p = wsel_plan(d_in, d_out);
+    const WselPlan p = wsel_plan(d_in, d_out, k);
     WselArgs a;
     a.W = W;
     a.centroids = centroids;
@@ -618,9 +819,9 @@ extern "C" int cmpq_extract_outliers(int mode, int score, const float *sumsq, co
     a.d_in = d_in;
     a.d_out = d_out;
     a.ldw = ldw;
-    a.chunks_per_channel = p.chunks_per_channel;
-    a.total_chunks = p.total_chunks;
-    a.chunks_per_block = p.chunks_per_block;
+    a.wc_per_channel = p.wc_per_channel;
+    a.total_wc = p.total_wc;
+    a.wc_per_unit = p.wc_per_unit;
     a.score = score;
     const int esz = dtype == CMPQ_F16 ? 2 : 4;
     a.vec_ok = reinterpret_cast<uintptr_t>(W) % 16 == 0 && (ldw * esz) % 16 == 0 &&

@@ -290,6 +290,34 @@ def test_weight_outliers_parity(env, dtype, d_in, d_out):
     assert (got[live:] == -1).all() and len(np.unique(got[:live])) == live and (got[:live] >= 0).all()
 
 
+@pytest.mark.parametrize("case", ["spread", "ties", "concentrated", "ragged"])
+def test_weight_outliers_staging_and_full_path(env, case):
+    # large enough that a unit's share of the staging list is smaller than the unit: "spread"
+    # is answered from the list, "ties" and "concentrated" overflow it and take the full path
+    B, ws, orc = env["B"], env["ws"], env["orc"]
+    rng = np.random.default_rng(len(case))
+    d_in, d_out = (300, 16384) if case != "ragged" else (523, 9000 + 4)
+    W = rng.normal(0, 0.02, (d_in, d_out))
+    if case == "ties":
+        W = np.round(W * 64) / 64
+    if case == "concentrated":
+        W[7] *= 50
+    W = W.astype(np.float16)
+    bits = rng.integers(2, 5, d_in).astype(np.uint8)
+    bits[5] = 16
+    ocent, ocodes = orc.kmeans(W, bits, iters=2)
+    live = int((bits <= 4).sum()) * d_out
+    Wd, cd, kd, bd = _dev(W), _dev(ocent), _dev(ocodes), _dev(bits)
+    for score in (B.SCORE_RESIDUAL, B.SCORE_MAGNITUDE):
+        for k in (live // 100, 17):
+            idx = torch.full((k,), -7, dtype=torch.int32, device=DEV)
+            val = torch.zeros(k, dtype=torch.float16, device=DEV)
+            B.extract_weight_outliers(Wd, cd, kd, bd, k, idx, val, ws, score)
+            oidx, oval = orc.weight_outliers(W, ocent, ocodes, bits, k, score)
+            assert np.array_equal(_np(idx).astype(np.int64), oidx), (case, score, k)
+            assert np.array_equal(_np(val).view(np.uint16), oval)
+
+
 # ------------------------------------------------------------------ storage and error
 
 @pytest.mark.parametrize("d_out", [1, 31, 32, 33, 100, 512, 4096 + 16])
