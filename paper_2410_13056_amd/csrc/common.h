@@ -51,14 +51,16 @@ __device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v) {
     return v;
 }
 
-// Inclusive scan over the lanes of a wave.
+// Inclusive scan over the lanes of a wave, on the DPP data path: shifts by 1, 2, 4, 8
+// inside each row of 16 lanes (lanes shifted in from outside a row read 0), then the last
+// lane of row 0 / 2 into rows 1 / 3 and the last lane of the lower half into the upper.
 __device__ __forceinline__ uint32_t wave_scan_incl_u32(uint32_t v) {
-    const int lane = threadIdx.x & (CMPQ_WAVE - 1);
-#pragma unroll
-    for (int s = 1; s < CMPQ_WAVE; s <<= 1) {
-        uint32_t t = __shfl_up(v, s, CMPQ_WAVE);
-        if (lane >= s) v += t;
-    }
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x111, 0xF, 0xF, true);   // row_shr:1
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x112, 0xF, 0xF, true);   // row_shr:2
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xF, 0xF, true);   // row_shr:4
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x118, 0xF, 0xF, true);   // row_shr:8
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x142, 0xA, 0xF, false);  // row_bcast:15 -> rows 1, 3
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x143, 0xC, 0xF, false);  // row_bcast:31 -> rows 2, 3
     return v;
 }
 

@@ -372,12 +372,16 @@ __global__ __launch_bounds__(kWThreads) void wsel_hist_kernel(WselArgs a, WselSt
                                                                uint32_t *__restrict__ hist,
                                                                uint32_t *__restrict__ above,
                                                                uint32_t *__restrict__ local_last) {
-    __shared__ uint32_t lh[kBins];
+    // the first digit is the same for most keys: its histogram is kept in 4 copies, chosen
+    // by lane, so that fewer lanes collide on one counter
+    constexpr int kCopies = PASS == 0 ? 4 : 1;
+    __shared__ uint32_t lh[kCopies * kBins];
     __shared__ uint32_t red[kWaves];
-    for (int b = threadIdx.x; b < kBins; b += kWThreads) lh[b] = 0;
+    for (int b = threadIdx.x; b < kCopies * kBins; b += kWThreads) lh[b] = 0;
     __syncthreads();
     const uint32_t prefix = PASS == 0 ? 0u : st->prefix;
     const int lane = threadIdx.x & (CMPQ_WAVE - 1), wave = threadIdx.x / CMPQ_WAVE;
+    uint32_t *lh0 = lh + (lane & (kCopies - 1)) * kBins;
     const int64_t unit = (int64_t)blockIdx.x * kWaves + wave;
     const int64_t q0 = unit * a.wc_per_unit;
     const int64_t q1 = min(a.total_wc, q0 + a.wc_per_unit);
@@ -391,7 +395,7 @@ __global__ __launch_bounds__(kWThreads) void wsel_hist_kernel(WselArgs a, WselSt
         for (int j = 0; j < 8; ++j) {
             if (!((valid >> j) & 1u)) continue;
             if (PASS == 0) {
-                atomicAdd(&lh[key[j] >> 21], 1u);
+                atomicAdd(&lh0[key[j] >> 21], 1u);
             } else if (PASS == 1) {
                 if ((key[j] >> 21) == (prefix >> 21)) atomicAdd(&lh[(key[j] >> 10) & 2047u], 1u);
             } else {
@@ -420,8 +424,12 @@ __global__ __launch_bounds__(kWThreads) void wsel_hist_kernel(WselArgs a, WselSt
         }
     });
     __syncthreads();
-    for (int b = threadIdx.x; b < kBins; b += kWThreads)
-        if (lh[b]) atomicAdd(&hist[PASS * kBins + b], lh[b]);
+    for (int b = threadIdx.x; b < kBins; b += kWThreads) {
+        uint32_t n = lh[b];
+#pragma unroll
+        for (int r = 1; r < kCopies; ++r) n += lh[r * kBins + b];
+        if (n) atomicAdd(&hist[PASS * kBins + b], n);
+    }
     if (PASS == 2) {
         if (lane == 0) {
             a.stage_cnt[unit] = over ? 0u : n_staged;
@@ -528,31 +536,46 @@ __global__ __launch_bounds__(kWThreads) void wsel_count_kernel(const WselState *
 }
 
 // Exclusive prefix over units (or workgroups, on the full path) of (ties seen) and
-// (entries written).
+// (entries written).  A thread takes kMaxUnits / 1024 consecutive entries.
 __global__ __launch_bounds__(1024) void wsel_offsets_kernel(const WselState *st, int nunits, int nblocks,
                                                             const uint32_t *__restrict__ cnt_gt,
                                                             const uint32_t *__restrict__ cnt_eq,
                                                             uint64_t *__restrict__ tie_base,
                                                             uint64_t *__restrict__ out_base) {
+    constexpr int kPer = kMaxUnits / 1024;
     __shared__ uint32_t scan[17];
     const uint64_t need = st->need;
     const int n = st->overflow ? nblocks : nunits;
-    uint64_t tie_run = 0, out_run = 0;
-    for (int base = 0; base < n; base += 1024) {
-        const int b = base + threadIdx.x;
-        const uint32_t e = b < n ? cnt_eq[b] : 0, g = b < n ? cnt_gt[b] : 0;
-        uint32_t e_total, w_total;
-        const uint64_t tb = tie_run + block_scan_excl_u32(e, scan, &e_total);
-        // ties of this unit that are still within the first `need`
+    const int b0 = threadIdx.x * kPer;
+    uint32_t e[kPer], g[kPer], e_sum = 0;
+#pragma unroll
+    for (int r = 0; r < kPer; ++r) {
+        e[r] = b0 + r < n ? cnt_eq[b0 + r] : 0;
+        g[r] = b0 + r < n ? cnt_gt[b0 + r] : 0;
+        e_sum += e[r];
+    }
+    uint32_t e_total, w_total;
+    uint64_t tb = block_scan_excl_u32(e_sum, scan, &e_total);
+    // ties of an entry that are still within the first `need`
+    uint32_t w[kPer], w_sum = 0;
+    uint64_t tbs[kPer];
+#pragma unroll
+    for (int r = 0; r < kPer; ++r) {
+        tbs[r] = tb;
         uint64_t take = 0;
-        if (tb < need) take = (need - tb) < e ? (need - tb) : e;
-        const uint64_t ob = out_run + block_scan_excl_u32(g + (uint32_t)take, scan, &w_total);
-        if (b < n) {
-            tie_base[b] = tb;
-            out_base[b] = ob;
+        if (tb < need) take = (need - tb) < e[r] ? (need - tb) : e[r];
+        w[r] = g[r] + (uint32_t)take;
+        w_sum += w[r];
+        tb += e[r];
+    }
+    uint64_t ob = block_scan_excl_u32(w_sum, scan, &w_total);
+#pragma unroll
+    for (int r = 0; r < kPer; ++r) {
+        if (b0 + r < n) {
+            tie_base[b0 + r] = tbs[r];
+            out_base[b0 + r] = ob;
         }
-        tie_run += e_total;
-        out_run += w_total;
+        ob += w[r];
     }
 }
 
