@@ -390,7 +390,7 @@ __global__ __launch_bounds__(kWThreads) void wsel_hist_kernel(WselArgs a, WselSt
     unsigned long long *stage_ik = a.stage_ik + unit * a.cap;
     uint16_t *stage_val = a.stage_val + unit * a.cap;
     for_each_wave_chunk<TW>(a, q0, q1, [&](int64_t i, int64_t o0, const uint32_t (&key)[8], const float (&wv)[8], uint32_t valid) {
-        uint32_t n_cand = 0;
+        uint32_t cand = 0;  // bit j: entry j reaches the 22-bit prefix
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             if (!((valid >> j) & 1u)) continue;
@@ -401,19 +401,33 @@ __global__ __launch_bounds__(kWThreads) void wsel_hist_kernel(WselArgs a, WselSt
             } else {
                 if ((key[j] >> 10) == (prefix >> 10)) atomicAdd(&lh[key[j] & 1023u], 1u);
                 n_above += (key[j] >> 10) > (prefix >> 10);
-                n_cand += (key[j] >> 10) >= (prefix >> 10);
+                cand |= (uint32_t)((key[j] >> 10) >= (prefix >> 10)) << j;
             }
         }
-        if (PASS == 2 && __ballot(n_cand != 0) != 0ull) {
+        if (PASS == 2 && __ballot(cand != 0) != 0ull) {
+            const uint32_t n_cand = __popc(cand);
             const uint32_t incl = wave_scan_incl_u32(n_cand);
             const uint32_t tot = __shfl(incl, CMPQ_WAVE - 1, CMPQ_WAVE);
             if (n_staged + tot <= a.cap) {
+                // staged in index order: a lane's entries follow those of the lanes below it.
+                // Few lanes hold any and hardly one holds two: every lane with entries left
+                // stores its next one, until none is left.
                 uint32_t pos = n_staged + incl - n_cand;
+                while (__ballot(cand != 0) != 0ull) {
+                    if (cand) {
+                        const int j = __ffs(cand) - 1;
+                        cand &= cand - 1;
+                        uint32_t kj = key[0];
+                        float wj = wv[0];
 #pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    if (((valid >> j) & 1u) && (key[j] >> 10) >= (prefix >> 10)) {
-                        stage_ik[pos] = ((unsigned long long)(uint32_t)(i * a.d_out + o0 + j) << 32) | key[j];
-                        stage_val[pos] = __half_as_ushort(__float2half_rn(wv[j]));
+                        for (int t = 1; t < 8; ++t) {
+                            if (j == t) {
+                                kj = key[t];
+                                wj = wv[t];
+                            }
+                        }
+                        stage_ik[pos] = ((unsigned long long)(uint32_t)(i * a.d_out + o0 + j) << 32) | kj;
+                        stage_val[pos] = __half_as_ushort(__float2half_rn(wj));
                         ++pos;
                     }
                 }
