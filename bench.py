@@ -25,6 +25,10 @@ sys.path.insert(0, ROOT)
 # packed pair as two more; a compare is neither.
 ALU_PEAK_TFLOPS = 256 * 64 * 2.4e9 / 1e12
 HBM_PEAK_GBS = 8000.0
+# HBM bytes per k-means launch (mean over the launches of a step), from rocprofv3 --pmc
+# FETCH_SIZE / WRITE_SIZE runs scaled by a plain copy of known size; bench.py cannot collect
+# counters itself.  The summary of those runs is kept with the other profiles.
+KMEANS_TRAFFIC_BYTES = {"block70b": 504.1e6}
 
 
 def credited_kmeans_flops(result, iters):
@@ -67,6 +71,9 @@ def main():
     ap.add_argument("--workload", default="block70b",
                     help="block70b (default, the headline target), block13b, block7b, q7b, tiny")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (outside the timed region): under "
+                         "rocprofv3 --pmc it gives the HBM counters a kernel of known traffic to scale by")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU; every box here has one, and the path needs no "
@@ -91,6 +98,12 @@ def main():
         return P.quantize_block(weights, acts, layers, wl.bit_set, wl.avg_bits, wl.rho_act_ppm,
                                 wl.rho_q_ppm, wl.iters, ws, with_error=True, status=status, timer=timer)
 
+    if args.calibration_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)                            # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         out = step()
         del out
@@ -126,7 +139,7 @@ def main():
                    "tokens": {k: v[0] for k, v in wl.x_shapes.items()}},
         "roofline": {"kernel": "kmeans_bucket_kernel", "bound": "alu", "achieved": achieved,
                      "peak": ALU_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": achieved / ALU_PEAK_TFLOPS,
-                     "traffic": None, "launches_per_step": launches_per_step,
+                     "traffic": KMEANS_TRAFFIC_BYTES.get(wl.name), "launches_per_step": launches_per_step,
                      "avg_launch_ms": avg_launch_s * 1e3, "credited_flop_per_launch": flops / launches_per_step},
         "stages_ms_per_step": {k: round(v[1] / args.steps, 4) for k, v in sorted(stages.items())},
         "act_stats_hbm": {"achieved_GBs": x_bytes * args.steps / (ms_st / 1e3) / 1e9, "peak_GBs": HBM_PEAK_GBS,
