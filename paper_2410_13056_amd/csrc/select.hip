@@ -137,17 +137,27 @@ __global__ __launch_bounds__(kSelThreads) void allocate_bits_kernel(
 
 // ------------------------------------------------------------------ whole layer, d_in*d_out keys
 //
-// Top-k of the scores of a whole layer, written in ascending linear index.  Three
-// histogram passes over the data fix the threshold key digit by digit (11 + 11 + 10
-// bits).  The data is shared out in wave-chunks (512 consecutive entries of one channel,
-// 8 per lane); a unit is one wavefront with a contiguous run of wave-chunks, four
-// consecutive units make a workgroup.  The last histogram pass also sets aside, unit by
-// unit and in index order, every entry whose top 22 bits reach the prefix known by then
-// - a superset of the answer that is a little over k entries long - so the result is
-// written from this staging list without a fourth pass over the data.  When a unit's
-// share of the list does not fit (many equal scores, or an unusual concentration), a
-// flag sends the call down the full path: per-workgroup tables from the last pass and
-// one more pass over the data.
+// Top-k of the scores of a whole layer, written in ascending linear index.  The data is
+// shared out in wave-chunks (512 consecutive entries of one channel, 8 per lane); a unit
+// is one wavefront with a contiguous run of wave-chunks, four consecutive units make a
+// workgroup.
+//
+// Exact chain: three histogram passes over the data fix the threshold key digit by digit
+// (11 + 11 + 10 bits).  The last pass also sets aside, unit by unit and in index order,
+// every entry whose top 22 bits reach the prefix known by then - a superset of the answer
+// a little over k entries long - and the result is written from this staging list.  When
+// a unit's share of the list does not fit (many equal scores, or an unusual
+// concentration), a flag sends the call down the full path: per-workgroup tables from the
+// last pass and one more pass over the data.
+//
+// Fast chain, tried first: two histogram passes over a sample (every s-th wave-chunk)
+// give a 22-bit prefix that, by the sample, a few percent more than k entries reach.  One
+// pass over the data stages every entry that reaches it; the exact k-th key is then
+// found inside the list (two digits: the 22-bit bin relative to the guess, the low 10
+// bits) and the answer written from the list.  The sample only guides the guess: if the
+// list turns out to hold fewer than k entries, overflows, or the k-th key lies far above
+// the guess, a flag is raised and the exact chain, whose kernels otherwise return at
+// once, does the work.  Either way the result is the same set.
 
 constexpr int kWThreads = 256;
 constexpr int kWaves = kWThreads / CMPQ_WAVE;
@@ -156,6 +166,8 @@ constexpr int kWaveChunk = CMPQ_WAVE * kWPerLane;
 constexpr int kMaxBlocks = 2048;
 constexpr int kMaxUnits = kMaxBlocks * kWaves;
 constexpr int kBins = 2048;
+// histograms: 0-2 the digits of the exact chain, 3-4 the sample's, 5-6 the list's
+constexpr int kHists = 7;
 
 struct WselState {
     uint32_t prefix;    // digits fixed so far (high bits of the threshold key)
@@ -163,7 +175,13 @@ struct WselState {
     uint64_t rem;       // rank still to resolve inside the current prefix
     uint64_t need;      // ties (key == T) to take, in index order
     uint64_t total;     // number of candidate keys
-    uint32_t overflow;  // a unit's staging share was too small: take the full path
+    uint32_t overflow;  // exact chain: a unit's staging share was too small: take the full path
+    // fast chain
+    uint32_t fast_overflow;  // a unit's staging share was too small
+    uint32_t fast_failed;    // the list does not settle the answer: the exact chain runs
+    uint32_t guess22;        // staged: top 22 bits >= guess22
+    uint32_t T22;            // top 22 bits of the threshold, found in the list
+    uint64_t rem_b;          // rank of the threshold inside that 22-bit bin
 };
 
 struct WselArgs {
@@ -179,12 +197,16 @@ struct WselArgs {
     uint16_t *stage_val;           //   and the entry's value as fp16 bits
     uint32_t *stage_cnt;           // entries staged per unit
     uint32_t cap;
+    int64_t sample_stride, n_sample;  // sampled wave-chunks: q = j * stride, j < n_sample
+    uint64_t sample_rank;             // rank in the sample that the guess aims at
 };
 
 struct WselPlan {
     int64_t wc_per_channel, total_wc, wc_per_unit;
     int nunits, nblocks;
     uint32_t cap;
+    int64_t sample_stride, n_sample;
+    uint64_t sample_rank;
 };
 
 WselPlan wsel_plan(int64_t d_in, int64_t d_out, int64_t k) {
@@ -203,6 +225,22 @@ WselPlan wsel_plan(int64_t d_in, int64_t d_out, int64_t k) {
     int64_t cap = 4 * cdiv(k, nu) + 256;
     if (cap > p.wc_per_unit * kWaveChunk) cap = p.wc_per_unit * kWaveChunk;
     p.cap = (uint32_t)cap;
+    // sample: about 16384 wave-chunks, a prime stride that does not divide the chunks of a
+    // channel (so that every part of a channel is met); aim a margin above the sample's share
+    // of k: 6 %, or 8 standard deviations of a count of that size if that is more
+    static const int primes[] = {61, 59, 53, 47, 43, 41, 37, 31, 29, 23, 19, 17, 13, 11, 7, 5, 3};
+    p.sample_stride = 1;
+    for (int pr : primes) {
+        if ((int64_t)pr * 16384 <= p.total_wc && p.wc_per_channel % pr != 0) {
+            p.sample_stride = pr;
+            break;
+        }
+    }
+    p.n_sample = cdiv(p.total_wc, p.sample_stride);
+    const double ks = (double)k * (double)p.n_sample / (double)(p.total_wc > 0 ? p.total_wc : 1);
+    double margin = 8.0 / __builtin_sqrt(ks > 1.0 ? ks : 1.0);
+    if (margin < 0.06) margin = 0.06;
+    p.sample_rank = (uint64_t)(ks * (1.0 + margin)) + 8;
     return p;
 }
 
@@ -348,10 +386,223 @@ __device__ __forceinline__ void for_each_wave_chunk(const WselArgs &a, int64_t q
     }
 }
 
+// Appends the entries of this wave-chunk flagged in `cand` (bit j: entry j of the lane) to
+// the unit's staging list, in index order: a lane's entries follow those of the lanes
+// below it.  Few lanes hold any and hardly one holds two: every lane with entries left
+// stores its next one, until none is left.  Called by all lanes of the wavefront.
+__device__ __forceinline__ void stage_chunk(uint32_t cand, int64_t i, int64_t o0, int64_t d_out,
+                                            const uint32_t (&key)[8], const float (&wv)[8],
+                                            unsigned long long *__restrict__ stage_ik,
+                                            uint16_t *__restrict__ stage_val, uint32_t cap,
+                                            uint32_t &n_staged, bool &over) {
+    if (__ballot(cand != 0) == 0ull) return;
+    const uint32_t n_cand = __popc(cand);
+    const uint32_t incl = wave_scan_incl_u32(n_cand);
+    const uint32_t tot = __shfl(incl, CMPQ_WAVE - 1, CMPQ_WAVE);
+    if (n_staged + tot <= cap) {
+        uint32_t pos = n_staged + incl - n_cand;
+        while (__ballot(cand != 0) != 0ull) {
+            if (cand) {
+                const int j = __ffs(cand) - 1;
+                cand &= cand - 1;
+                uint32_t kj = key[0];
+                float wj = wv[0];
+#pragma unroll
+                for (int t = 1; t < 8; ++t) {
+                    if (j == t) {
+                        kj = key[t];
+                        wj = wv[t];
+                    }
+                }
+                stage_ik[pos] = ((unsigned long long)(uint32_t)(i * d_out + o0 + j) << 32) | kj;
+                stage_val[pos] = __half_as_ushort(__float2half_rn(wj));
+                ++pos;
+            }
+        }
+    } else {
+        over = true;
+    }
+    n_staged += tot;
+}
+
+struct PickShared {
+    uint32_t scan[17];
+    uint32_t bin, total;
+    uint64_t rem_in;
+    int ok;
+};
+
+// The bin of the 2048-bin histogram h that holds rank `rem`, counted from the largest bin
+// down (1-based), and the rank inside that bin.  Called by all 256 threads of a workgroup
+// (contains barriers); false when rem is 0 or exceeds the total.
+__device__ __forceinline__ bool block_pick(const uint32_t *__restrict__ h, uint64_t rem, PickShared &ps,
+                                           uint32_t &bin, uint64_t &rem_in, uint32_t &total) {
+    constexpr int kPer = kBins / kWThreads;
+    const int r0 = threadIdx.x * kPer;  // position r <-> bin kBins - 1 - r
+    uint32_t v[kPer], sum = 0;
+#pragma unroll
+    for (int r = 0; r < kPer; ++r) {
+        v[r] = h[kBins - 1 - (r0 + r)];
+        sum += v[r];
+    }
+    uint32_t tot;
+    const uint32_t before = block_scan_excl_u32(sum, ps.scan, &tot);
+    if (threadIdx.x == 0) {
+        ps.ok = 0;
+        ps.total = tot;
+        ps.bin = 0;
+        ps.rem_in = 0;
+    }
+    __syncthreads();
+    if (rem != 0 && rem <= tot) {
+        uint64_t run = before;
+#pragma unroll
+        for (int r = 0; r < kPer; ++r) {
+            if (v[r] && run < rem && rem <= run + v[r]) {
+                ps.bin = (uint32_t)(kBins - 1 - (r0 + r));
+                ps.rem_in = rem - run;
+                ps.ok = 1;
+            }
+            run += v[r];
+        }
+    }
+    __syncthreads();
+    bin = ps.bin;
+    rem_in = ps.rem_in;
+    total = ps.total;
+    return ps.ok != 0;
+}
+
+// Fast chain, sample passes: histogram of the first (PASS 0) or, inside the first digit's
+// bin, the second (PASS 1) 11-bit digit over every sample_stride-th wave-chunk.
+template <typename TW, int PASS>
+__global__ __launch_bounds__(kWThreads) void wsel_sample_kernel(WselArgs a, uint32_t *__restrict__ hist) {
+    __shared__ uint32_t lh[kBins];
+    __shared__ PickShared ps;
+    for (int b = threadIdx.x; b < kBins; b += kWThreads) lh[b] = 0;
+    uint32_t bin0 = 0;
+    if (PASS == 1) {
+        uint64_t r;
+        uint32_t tot;
+        if (!block_pick(hist + 3 * kBins, a.sample_rank, ps, bin0, r, tot)) return;
+    }
+    __syncthreads();
+    const int lane = threadIdx.x & (CMPQ_WAVE - 1), wave = threadIdx.x / CMPQ_WAVE;
+    const int64_t n_waves = (int64_t)gridDim.x * kWaves;
+    for (int64_t j = (int64_t)blockIdx.x * kWaves + wave; j < a.n_sample; j += n_waves) {
+        const int64_t q = j * a.sample_stride;
+        const int64_t i = q / a.wc_per_channel, c = q % a.wc_per_channel;
+        if (!channel_live(a, i)) continue;  // uniform over the wavefront
+        const int64_t o0 = c * kWaveChunk + lane * kWPerLane;
+        Raw8<TW> raw;
+        fetch8(a, i, o0, raw);
+        const float cent = a.centroids ? a.centroids[i * CMPQ_KMAX + (lane & 15)] : 0.f;
+        uint32_t key[8];
+        float wv[8];
+        score_keys8<TW>(a, raw, cent, key, wv);
+        const uint32_t valid = valid8(o0, a.d_out);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            if (!((valid >> e) & 1u)) continue;
+            if (PASS == 0) {
+                atomicAdd(&lh[key[e] >> 21], 1u);
+            } else if ((key[e] >> 21) == bin0) {
+                atomicAdd(&lh[(key[e] >> 10) & 2047u], 1u);
+            }
+        }
+    }
+    __syncthreads();
+    for (int b = threadIdx.x; b < kBins; b += kWThreads)
+        if (lh[b]) atomicAdd(&hist[(3 + PASS) * kBins + b], lh[b]);
+}
+
+// Fast chain, the one pass over the data: stages every entry whose top 22 bits reach the
+// guess read off the sample's histograms.
+template <typename TW>
+__global__ __launch_bounds__(kWThreads) void wsel_stage_kernel(WselArgs a, WselState *st,
+                                                                const uint32_t *__restrict__ hist) {
+    __shared__ PickShared ps;
+    uint32_t guess22 = 0;  // no usable sample: everything reaches it, the list overflows, the exact chain runs
+    {
+        uint32_t bin0, bin1, tot;
+        uint64_t rem0, rem1;
+        if (block_pick(hist + 3 * kBins, a.sample_rank, ps, bin0, rem0, tot) &&
+            block_pick(hist + 4 * kBins, rem0, ps, bin1, rem1, tot))
+            guess22 = (bin0 << 11) | bin1;
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0) st->guess22 = guess22;
+    const int lane = threadIdx.x & (CMPQ_WAVE - 1), wave = threadIdx.x / CMPQ_WAVE;
+    const int64_t unit = (int64_t)blockIdx.x * kWaves + wave;
+    const int64_t q0 = unit * a.wc_per_unit;
+    const int64_t q1 = min(a.total_wc, q0 + a.wc_per_unit);
+    uint32_t n_staged = 0;
+    bool over = false;
+    unsigned long long *stage_ik = a.stage_ik + unit * a.cap;
+    uint16_t *stage_val = a.stage_val + unit * a.cap;
+    for_each_wave_chunk<TW>(a, q0, q1, [&](int64_t i, int64_t o0, const uint32_t (&key)[8], const float (&wv)[8], uint32_t valid) {
+        uint32_t cand = 0;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) cand |= (uint32_t)(((valid >> j) & 1u) && (key[j] >> 10) >= guess22) << j;
+        stage_chunk(cand, i, o0, a.d_out, key, wv, stage_ik, stage_val, a.cap, n_staged, over);
+    });
+    if (lane == 0) {
+        a.stage_cnt[unit] = over ? 0u : n_staged;
+        if (over) st->fast_overflow = 1u;
+    }
+}
+
+// Fast chain, passes over the list.  PASS 0: histogram of the 22-bit bin relative to the
+// guess (everything 2047 bins or more above it shares the last bin).  PASS 1: first picks
+// the bin of rank k from that histogram - the list settles the answer only if it holds at
+// least k entries, did not overflow and the bin is not the shared last one - then
+// histograms the low 10 bits inside that bin.
+template <int PASS>
+__global__ __launch_bounds__(kWThreads) void wsel_list_kernel(WselArgs a, WselState *st,
+                                                               uint32_t *__restrict__ hist, uint64_t k) {
+    __shared__ uint32_t lh[kBins];
+    __shared__ PickShared ps;
+    for (int b = threadIdx.x; b < kBins; b += kWThreads) lh[b] = 0;
+    const uint32_t guess22 = st->guess22;
+    const bool overflowed = st->fast_overflow != 0;
+    uint32_t T22 = 0;
+    if (PASS == 1) {
+        uint32_t bin, tot;
+        uint64_t rem_b;
+        const bool ok = block_pick(hist + 5 * kBins, k, ps, bin, rem_b, tot);
+        const bool failed = overflowed || !ok || bin == (uint32_t)(kBins - 1);
+        if (blockIdx.x == 0 && threadIdx.x == 0) {
+            st->fast_failed = failed ? 1u : 0u;
+            st->T22 = guess22 + bin;
+            st->rem_b = rem_b;
+        }
+        if (failed) return;
+        T22 = guess22 + bin;
+    } else if (overflowed) {
+        return;
+    }
+    __syncthreads();
+    const int lane = threadIdx.x & (CMPQ_WAVE - 1), wave = threadIdx.x / CMPQ_WAVE;
+    const int64_t unit = (int64_t)blockIdx.x * kWaves + wave;
+    const unsigned long long *ik = a.stage_ik + unit * a.cap;
+    const uint32_t n = a.stage_cnt[unit];
+    for (uint32_t e = lane; e < n; e += CMPQ_WAVE) {
+        const uint32_t key = (uint32_t)ik[e];
+        if (PASS == 0) {
+            const uint32_t rel = (key >> 10) - guess22;
+            atomicAdd(&lh[rel < (uint32_t)(kBins - 1) ? rel : (uint32_t)(kBins - 1)], 1u);
+        } else if ((key >> 10) == T22) {
+            atomicAdd(&lh[key & 1023u], 1u);
+        }
+    }
+    __syncthreads();
+    for (int b = threadIdx.x; b < kBins; b += kWThreads)
+        if (lh[b]) atomicAdd(&hist[(5 + PASS) * kBins + b], lh[b]);
+}
+
 __global__ void wsel_init_kernel(WselState *st, uint32_t *hist, uint64_t k, int32_t *idx_out,
                                  int64_t k_fill) {
     const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (t < 3 * kBins) hist[t] = 0;
+    if (t < kHists * kBins) hist[t] = 0;
     if (t == 0) {
         st->prefix = 0;
         st->T = 0;
@@ -359,6 +610,11 @@ __global__ void wsel_init_kernel(WselState *st, uint32_t *hist, uint64_t k, int3
         st->need = 0;
         st->total = 0;
         st->overflow = 0;
+        st->fast_overflow = 0;
+        st->fast_failed = 0;
+        st->guess22 = 0;
+        st->T22 = 0;
+        st->rem_b = 0;
     }
     for (int64_t j = t; j < k_fill; j += (int64_t)gridDim.x * blockDim.x) idx_out[j] = -1;
 }
@@ -377,6 +633,7 @@ __global__ __launch_bounds__(kWThreads) void wsel_hist_kernel(WselArgs a, WselSt
     constexpr int kCopies = PASS == 0 ? 4 : 1;
     __shared__ uint32_t lh[kCopies * kBins];
     __shared__ uint32_t red[kWaves];
+    if (!st->fast_failed) return;  // the fast chain settled the answer
     for (int b = threadIdx.x; b < kCopies * kBins; b += kWThreads) lh[b] = 0;
     __syncthreads();
     const uint32_t prefix = PASS == 0 ? 0u : st->prefix;
@@ -404,38 +661,7 @@ __global__ __launch_bounds__(kWThreads) void wsel_hist_kernel(WselArgs a, WselSt
                 cand |= (uint32_t)((key[j] >> 10) >= (prefix >> 10)) << j;
             }
         }
-        if (PASS == 2 && __ballot(cand != 0) != 0ull) {
-            const uint32_t n_cand = __popc(cand);
-            const uint32_t incl = wave_scan_incl_u32(n_cand);
-            const uint32_t tot = __shfl(incl, CMPQ_WAVE - 1, CMPQ_WAVE);
-            if (n_staged + tot <= a.cap) {
-                // staged in index order: a lane's entries follow those of the lanes below it.
-                // Few lanes hold any and hardly one holds two: every lane with entries left
-                // stores its next one, until none is left.
-                uint32_t pos = n_staged + incl - n_cand;
-                while (__ballot(cand != 0) != 0ull) {
-                    if (cand) {
-                        const int j = __ffs(cand) - 1;
-                        cand &= cand - 1;
-                        uint32_t kj = key[0];
-                        float wj = wv[0];
-#pragma unroll
-                        for (int t = 1; t < 8; ++t) {
-                            if (j == t) {
-                                kj = key[t];
-                                wj = wv[t];
-                            }
-                        }
-                        stage_ik[pos] = ((unsigned long long)(uint32_t)(i * a.d_out + o0 + j) << 32) | kj;
-                        stage_val[pos] = __half_as_ushort(__float2half_rn(wj));
-                        ++pos;
-                    }
-                }
-            } else {
-                over = true;
-            }
-            n_staged += tot;
-        }
+        if (PASS == 2) stage_chunk(cand, i, o0, a.d_out, key, wv, stage_ik, stage_val, a.cap, n_staged, over);
     });
     __syncthreads();
     for (int b = threadIdx.x; b < kBins; b += kWThreads) {
@@ -465,6 +691,7 @@ __global__ __launch_bounds__(kWThreads) void wsel_hist_kernel(WselArgs a, WselSt
 template <int PASS>
 __global__ __launch_bounds__(1024) void wsel_pick_kernel(WselState *st, const uint32_t *__restrict__ hist) {
     __shared__ uint32_t scan[17];
+    if (!st->fast_failed) return;
     const uint32_t *h = hist + PASS * kBins;
     // walk bins from the largest digit down: position r <-> bin 2047 - r
     const int r0 = 2 * threadIdx.x, r1 = r0 + 1;
@@ -506,15 +733,31 @@ __global__ __launch_bounds__(1024) void wsel_pick_kernel(WselState *st, const ui
 
 // Keys above the threshold and keys equal to it: per unit from the staging list, or, on
 // the full path, per workgroup from the tables the last histogram pass left.
-__global__ __launch_bounds__(kWThreads) void wsel_count_kernel(const WselState *st, WselArgs a,
+// EXACT names the chain a launch belongs to; the launch of the other chain returns.  The
+// fast chain's launch first reads the threshold off the list's second histogram.
+template <bool EXACT>
+__global__ __launch_bounds__(kWThreads) void wsel_count_kernel(WselState *st, WselArgs a,
+                                                                const uint32_t *__restrict__ hist,
                                                                 const uint32_t *__restrict__ above,
                                                                 const uint32_t *__restrict__ local_last,
                                                                 uint32_t *__restrict__ cnt_gt,
                                                                 uint32_t *__restrict__ cnt_eq) {
     __shared__ uint32_t red[kWaves];
+    __shared__ PickShared ps;
+    if ((st->fast_failed != 0) != EXACT) return;
     const int lane = threadIdx.x & (CMPQ_WAVE - 1), wave = threadIdx.x / CMPQ_WAVE;
-    const uint32_t T = st->T;
-    if (!st->overflow) {
+    uint32_t T = st->T;
+    if (!EXACT) {
+        uint32_t digit, tot;
+        uint64_t need;
+        block_pick(hist + 6 * kBins, st->rem_b, ps, digit, need, tot);  // rem_b lies inside the bin
+        T = (st->T22 << 10) | digit;
+        if (blockIdx.x == 0 && threadIdx.x == 0) {
+            st->T = T;
+            st->need = need;
+        }
+    }
+    if (!EXACT || !st->overflow) {
         const int64_t unit = (int64_t)blockIdx.x * kWaves + wave;
         const unsigned long long *ik = a.stage_ik + unit * a.cap;
         const uint32_t n = a.stage_cnt[unit];
@@ -551,6 +794,7 @@ __global__ __launch_bounds__(kWThreads) void wsel_count_kernel(const WselState *
 
 // Exclusive prefix over units (or workgroups, on the full path) of (ties seen) and
 // (entries written).  A thread takes kMaxUnits / 1024 consecutive entries.
+template <bool EXACT>
 __global__ __launch_bounds__(1024) void wsel_offsets_kernel(const WselState *st, int nunits, int nblocks,
                                                             const uint32_t *__restrict__ cnt_gt,
                                                             const uint32_t *__restrict__ cnt_eq,
@@ -558,8 +802,9 @@ __global__ __launch_bounds__(1024) void wsel_offsets_kernel(const WselState *st,
                                                             uint64_t *__restrict__ out_base) {
     constexpr int kPer = kMaxUnits / 1024;
     __shared__ uint32_t scan[17];
+    if ((st->fast_failed != 0) != EXACT) return;
     const uint64_t need = st->need;
-    const int n = st->overflow ? nblocks : nunits;
+    const int n = EXACT && st->overflow ? nblocks : nunits;
     const int b0 = threadIdx.x * kPer;
     uint32_t e[kPer], g[kPer], e_sum = 0;
 #pragma unroll
@@ -598,12 +843,13 @@ __device__ __forceinline__ uint32_t lanes_below(unsigned long long mask) {
 }
 
 // Writes the answer from the staging list: a wavefront per unit, 64 staged entries a step.
+template <bool EXACT>
 __global__ __launch_bounds__(kWThreads) void wsel_emit_kernel(WselArgs a, const WselState *st,
                                                                const uint64_t *__restrict__ tie_base,
                                                                const uint64_t *__restrict__ out_base,
                                                                int64_t k, int32_t *__restrict__ idx_out,
                                                                uint16_t *__restrict__ val_out) {
-    if (st->overflow) return;
+    if ((st->fast_failed != 0) != EXACT || (EXACT && st->overflow)) return;
     const int lane = threadIdx.x & (CMPQ_WAVE - 1), wave = threadIdx.x / CMPQ_WAVE;
     const int64_t unit = (int64_t)blockIdx.x * kWaves + wave;
     const uint32_t T = st->T;
@@ -638,7 +884,7 @@ __global__ __launch_bounds__(kWThreads) void wsel_write_kernel(
     const uint64_t *__restrict__ out_base, int64_t k, int32_t *__restrict__ idx_out,
     uint16_t *__restrict__ val_out) {
     __shared__ uint32_t scan[34];
-    if (!st->overflow) return;
+    if (!st->fast_failed || !st->overflow) return;
     const int lane = threadIdx.x & (CMPQ_WAVE - 1), wave = threadIdx.x / CMPQ_WAVE;
     const uint32_t T = st->T;
     const uint64_t need = st->need;
@@ -710,7 +956,7 @@ WselWs wsel_carve(void *ws, const WselPlan &p) {
     WsCarver carve(ws);
     WselWs w;
     w.st = carve.take<WselState>(1);
-    w.hist = carve.take<uint32_t>(3 * kBins);
+    w.hist = carve.take<uint32_t>(kHists * kBins);
     w.cnt_gt = carve.take<uint32_t>(kMaxUnits);
     w.cnt_eq = carve.take<uint32_t>(kMaxUnits);
     w.tie_base = carve.take<uint64_t>(kMaxUnits);
@@ -732,16 +978,32 @@ int launch_weight_select(WselArgs a, const WselPlan &p, int64_t k, int32_t *idx_
     a.stage_val = w.stage_val;
     a.stage_cnt = w.stage_cnt;
     a.cap = p.cap;
+    a.sample_stride = p.sample_stride;
+    a.n_sample = p.n_sample;
+    a.sample_rank = p.sample_rank;
+    int64_t sample_blocks = cdiv(p.n_sample, 2 * kWaves);
+    if (sample_blocks > 1024) sample_blocks = 1024;
+    if (sample_blocks < 1) sample_blocks = 1;
     wsel_init_kernel<<<64, 256, 0, s>>>(w.st, w.hist, (uint64_t)k, idx_out, k);
+    // fast chain
+    wsel_sample_kernel<TW, 0><<<(unsigned)sample_blocks, kWThreads, 0, s>>>(a, w.hist);
+    wsel_sample_kernel<TW, 1><<<(unsigned)sample_blocks, kWThreads, 0, s>>>(a, w.hist);
+    wsel_stage_kernel<TW><<<p.nblocks, kWThreads, 0, s>>>(a, w.st, w.hist);
+    wsel_list_kernel<0><<<p.nblocks, kWThreads, 0, s>>>(a, w.st, w.hist, (uint64_t)k);
+    wsel_list_kernel<1><<<p.nblocks, kWThreads, 0, s>>>(a, w.st, w.hist, (uint64_t)k);
+    wsel_count_kernel<false><<<p.nblocks, kWThreads, 0, s>>>(w.st, a, w.hist, w.above, w.local_last, w.cnt_gt, w.cnt_eq);
+    wsel_offsets_kernel<false><<<1, 1024, 0, s>>>(w.st, p.nunits, p.nblocks, w.cnt_gt, w.cnt_eq, w.tie_base, w.out_base);
+    wsel_emit_kernel<false><<<p.nblocks, kWThreads, 0, s>>>(a, w.st, w.tie_base, w.out_base, k, idx_out, val_out);
+    // exact chain: every kernel returns at once unless the fast chain raised its flag
     wsel_hist_kernel<TW, 0><<<p.nblocks, kWThreads, 0, s>>>(a, w.st, w.hist, w.above, w.local_last);
     wsel_pick_kernel<0><<<1, 1024, 0, s>>>(w.st, w.hist);
     wsel_hist_kernel<TW, 1><<<p.nblocks, kWThreads, 0, s>>>(a, w.st, w.hist, w.above, w.local_last);
     wsel_pick_kernel<1><<<1, 1024, 0, s>>>(w.st, w.hist);
     wsel_hist_kernel<TW, 2><<<p.nblocks, kWThreads, 0, s>>>(a, w.st, w.hist, w.above, w.local_last);
     wsel_pick_kernel<2><<<1, 1024, 0, s>>>(w.st, w.hist);
-    wsel_count_kernel<<<p.nblocks, kWThreads, 0, s>>>(w.st, a, w.above, w.local_last, w.cnt_gt, w.cnt_eq);
-    wsel_offsets_kernel<<<1, 1024, 0, s>>>(w.st, p.nunits, p.nblocks, w.cnt_gt, w.cnt_eq, w.tie_base, w.out_base);
-    wsel_emit_kernel<<<p.nblocks, kWThreads, 0, s>>>(a, w.st, w.tie_base, w.out_base, k, idx_out, val_out);
+    wsel_count_kernel<true><<<p.nblocks, kWThreads, 0, s>>>(w.st, a, w.hist, w.above, w.local_last, w.cnt_gt, w.cnt_eq);
+    wsel_offsets_kernel<true><<<1, 1024, 0, s>>>(w.st, p.nunits, p.nblocks, w.cnt_gt, w.cnt_eq, w.tie_base, w.out_base);
+    wsel_emit_kernel<true><<<p.nblocks, kWThreads, 0, s>>>(a, w.st, w.tie_base, w.out_base, k, idx_out, val_out);
     wsel_write_kernel<TW><<<p.nblocks, kWThreads, 0, s>>>(a, w.st, w.tie_base, w.out_base, k, idx_out, val_out);
     CMPQ_LAUNCH_CHECK();
     return CMPQ_OK;
