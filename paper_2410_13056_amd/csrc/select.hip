@@ -170,11 +170,8 @@ constexpr int kBins = 2048;
 constexpr int kHists = 7;
 
 struct WselState {
-    uint32_t prefix;    // digits fixed so far (high bits of the threshold key)
     uint32_t T;         // final threshold key
-    uint64_t rem;       // rank still to resolve inside the current prefix
     uint64_t need;      // ties (key == T) to take, in index order
-    uint64_t total;     // number of candidate keys
     uint32_t overflow;  // exact chain: a unit's staging share was too small: take the full path
     // fast chain
     uint32_t fast_overflow;  // a unit's staging share was too small
@@ -225,13 +222,13 @@ WselPlan wsel_plan(int64_t d_in, int64_t d_out, int64_t k) {
     int64_t cap = 4 * cdiv(k, nu) + 256;
     if (cap > p.wc_per_unit * kWaveChunk) cap = p.wc_per_unit * kWaveChunk;
     p.cap = (uint32_t)cap;
-    // sample: about 16384 wave-chunks, a prime stride that does not divide the chunks of a
+    // sample: 8192 wave-chunks or more, a prime stride that does not divide the chunks of a
     // channel (so that every part of a channel is met); aim a margin above the sample's share
     // of k: 6 %, or 8 standard deviations of a count of that size if that is more
     static const int primes[] = {61, 59, 53, 47, 43, 41, 37, 31, 29, 23, 19, 17, 13, 11, 7, 5, 3};
     p.sample_stride = 1;
     for (int pr : primes) {
-        if ((int64_t)pr * 16384 <= p.total_wc && p.wc_per_channel % pr != 0) {
+        if ((int64_t)pr * 8192 <= p.total_wc && p.wc_per_channel % pr != 0) {
             p.sample_stride = pr;
             break;
         }
@@ -473,6 +470,27 @@ __device__ __forceinline__ bool block_pick(const uint32_t *__restrict__ h, uint6
     return ps.ok != 0;
 }
 
+// Exact chain: the digits fixed by the first `passes` histograms (11, 11, 10 bits from
+// the top) for rank k, and the rank left inside them.  `all` when k exceeds the number of
+// candidates: every candidate is taken (prefix 0).  Called by all threads of a workgroup.
+__device__ __forceinline__ void exact_prefix(const uint32_t *__restrict__ hist, uint64_t k, int passes,
+                                             PickShared &ps, uint32_t &prefix, uint64_t &rem, bool &all) {
+    prefix = 0;
+    rem = k;
+    all = false;
+    for (int pass = 0; pass < passes; ++pass) {
+        uint32_t bin, tot;
+        uint64_t rem_in;
+        if (!block_pick(hist + pass * kBins, rem, ps, bin, rem_in, tot)) {
+            all = true;
+            prefix = 0;
+            return;
+        }
+        prefix |= bin << (pass == 0 ? 21 : (pass == 1 ? 10 : 0));
+        rem = rem_in;
+    }
+}
+
 // Fast chain, sample passes: histogram of the first (PASS 0) or, inside the first digit's
 // bin, the second (PASS 1) 11-bit digit over every sample_stride-th wave-chunk.
 template <typename TW, int PASS>
@@ -489,27 +507,44 @@ __global__ __launch_bounds__(kWThreads) void wsel_sample_kernel(WselArgs a, uint
     __syncthreads();
     const int lane = threadIdx.x & (CMPQ_WAVE - 1), wave = threadIdx.x / CMPQ_WAVE;
     const int64_t n_waves = (int64_t)gridDim.x * kWaves;
-    for (int64_t j = (int64_t)blockIdx.x * kWaves + wave; j < a.n_sample; j += n_waves) {
-        const int64_t q = j * a.sample_stride;
-        const int64_t i = q / a.wc_per_channel, c = q % a.wc_per_channel;
-        if (!channel_live(a, i)) continue;  // uniform over the wavefront
-        const int64_t o0 = c * kWaveChunk + lane * kWPerLane;
+    // few workgroups (every one ends with a flush into the same global counters), several
+    // wave-chunks per wavefront, the next one's loads issued before the current one is used
+    struct Item {
+        int64_t i, o0;
+        bool live;
+        float cent;
         Raw8<TW> raw;
-        fetch8(a, i, o0, raw);
-        const float cent = a.centroids ? a.centroids[i * CMPQ_KMAX + (lane & 15)] : 0.f;
-        uint32_t key[8];
-        float wv[8];
-        score_keys8<TW>(a, raw, cent, key, wv);
-        const uint32_t valid = valid8(o0, a.d_out);
+    };
+    auto load = [&](int64_t j, Item &it) {
+        const int64_t q = j * a.sample_stride;
+        it.i = q / a.wc_per_channel;
+        it.o0 = (q % a.wc_per_channel) * kWaveChunk + lane * kWPerLane;
+        // all loads at once: the few channels of O_act are fetched and then dropped
+        it.live = channel_live(a, it.i);  // uniform over the wavefront
+        fetch8(a, it.i, it.o0, it.raw);
+        it.cent = a.centroids ? a.centroids[it.i * CMPQ_KMAX + (lane & 15)] : 0.f;
+    };
+    int64_t j = (int64_t)blockIdx.x * kWaves + wave;
+    Item cur = {}, nxt = {};
+    if (j < a.n_sample) load(j, cur);
+    for (; j < a.n_sample; j += n_waves) {
+        if (j + n_waves < a.n_sample) load(j + n_waves, nxt);
+        if (cur.live) {
+            uint32_t key[8];
+            float wv[8];
+            score_keys8<TW>(a, cur.raw, cur.cent, key, wv);
+            const uint32_t valid = valid8(cur.o0, a.d_out);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            if (!((valid >> e) & 1u)) continue;
-            if (PASS == 0) {
-                atomicAdd(&lh[key[e] >> 21], 1u);
-            } else if ((key[e] >> 21) == bin0) {
-                atomicAdd(&lh[(key[e] >> 10) & 2047u], 1u);
+            for (int e = 0; e < 8; ++e) {
+                if (!((valid >> e) & 1u)) continue;
+                if (PASS == 0) {
+                    atomicAdd(&lh[key[e] >> 21], 1u);
+                } else if ((key[e] >> 21) == bin0) {
+                    atomicAdd(&lh[(key[e] >> 10) & 2047u], 1u);
+                }
             }
         }
+        cur = nxt;
     }
     __syncthreads();
     for (int b = threadIdx.x; b < kBins; b += kWThreads)
@@ -552,12 +587,16 @@ __global__ __launch_bounds__(kWThreads) void wsel_stage_kernel(WselArgs a, WselS
 }
 
 // Fast chain, passes over the list.  PASS 0: histogram of the 22-bit bin relative to the
-// guess (everything 2047 bins or more above it shares the last bin).  PASS 1: first picks
+// guess; the threshold is expected a few bins above the guess, so only the first
+// kNearBins bins are told apart and everything beyond shares the last bin (fewer counters
+// to flush).  PASS 1: first picks
 // the bin of rank k from that histogram - the list settles the answer only if it holds at
 // least k entries, did not overflow and the bin is not the shared last one - then
 // histograms the low 10 bits inside that bin.
+constexpr uint32_t kNearBins = 511;
+
 template <int PASS>
-__global__ __launch_bounds__(kWThreads) void wsel_list_kernel(WselArgs a, WselState *st,
+__global__ __launch_bounds__(kWThreads) void wsel_list_kernel(WselArgs a, WselState *st, int nunits,
                                                                uint32_t *__restrict__ hist, uint64_t k) {
     __shared__ uint32_t lh[kBins];
     __shared__ PickShared ps;
@@ -582,33 +621,38 @@ __global__ __launch_bounds__(kWThreads) void wsel_list_kernel(WselArgs a, WselSt
     }
     __syncthreads();
     const int lane = threadIdx.x & (CMPQ_WAVE - 1), wave = threadIdx.x / CMPQ_WAVE;
-    const int64_t unit = (int64_t)blockIdx.x * kWaves + wave;
-    const unsigned long long *ik = a.stage_ik + unit * a.cap;
-    const uint32_t n = a.stage_cnt[unit];
-    for (uint32_t e = lane; e < n; e += CMPQ_WAVE) {
-        const uint32_t key = (uint32_t)ik[e];
-        if (PASS == 0) {
-            const uint32_t rel = (key >> 10) - guess22;
-            atomicAdd(&lh[rel < (uint32_t)(kBins - 1) ? rel : (uint32_t)(kBins - 1)], 1u);
-        } else if ((key >> 10) == T22) {
-            atomicAdd(&lh[key & 1023u], 1u);
+    uint32_t n_far = 0;
+    for (int64_t unit = (int64_t)blockIdx.x * kWaves + wave; unit < nunits; unit += (int64_t)gridDim.x * kWaves) {
+        const unsigned long long *ik = a.stage_ik + unit * a.cap;
+        const uint32_t n = a.stage_cnt[unit];
+#pragma unroll 4
+        for (uint32_t e = lane; e < n; e += CMPQ_WAVE) {
+            const uint32_t key = (uint32_t)ik[e];
+            if (PASS == 0) {
+                const uint32_t rel = (key >> 10) - guess22;
+                if (rel < kNearBins) atomicAdd(&lh[rel], 1u);
+                else ++n_far;  // most of the list: counted in a register, added once
+            } else if ((key >> 10) == T22) {
+                atomicAdd(&lh[key & 1023u], 1u);
+            }
         }
+    }
+    if (PASS == 0) {
+        n_far = wave_sum_u32(n_far);
+        if (lane == 0 && n_far) atomicAdd(&lh[kBins - 1], n_far);
     }
     __syncthreads();
     for (int b = threadIdx.x; b < kBins; b += kWThreads)
         if (lh[b]) atomicAdd(&hist[(5 + PASS) * kBins + b], lh[b]);
 }
 
-__global__ void wsel_init_kernel(WselState *st, uint32_t *hist, uint64_t k, int32_t *idx_out,
+__global__ void wsel_init_kernel(WselState *st, uint32_t *hist, int32_t *idx_out,
                                  int64_t k_fill) {
     const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (t < kHists * kBins) hist[t] = 0;
     if (t == 0) {
-        st->prefix = 0;
         st->T = 0;
-        st->rem = k;
         st->need = 0;
-        st->total = 0;
         st->overflow = 0;
         st->fast_overflow = 0;
         st->fast_failed = 0;
@@ -624,7 +668,7 @@ __global__ void wsel_init_kernel(WselState *st, uint32_t *hist, uint64_t k, int3
 // per workgroup, how many of its keys lie above the 22-bit prefix and its own histogram
 // of the last digit (what the full path needs to place its output without counting again).
 template <typename TW, int PASS>
-__global__ __launch_bounds__(kWThreads) void wsel_hist_kernel(WselArgs a, WselState *st,
+__global__ __launch_bounds__(kWThreads) void wsel_hist_kernel(WselArgs a, WselState *st, uint64_t k,
                                                                uint32_t *__restrict__ hist,
                                                                uint32_t *__restrict__ above,
                                                                uint32_t *__restrict__ local_last) {
@@ -635,8 +679,14 @@ __global__ __launch_bounds__(kWThreads) void wsel_hist_kernel(WselArgs a, WselSt
     __shared__ uint32_t red[kWaves];
     if (!st->fast_failed) return;  // the fast chain settled the answer
     for (int b = threadIdx.x; b < kCopies * kBins; b += kWThreads) lh[b] = 0;
+    __shared__ PickShared ps;
+    uint32_t prefix = 0;
+    {
+        uint64_t rem;
+        bool all;
+        exact_prefix(hist, k, PASS, ps, prefix, rem, all);  // the digits the passes before this one fixed
+    }
     __syncthreads();
-    const uint32_t prefix = PASS == 0 ? 0u : st->prefix;
     const int lane = threadIdx.x & (CMPQ_WAVE - 1), wave = threadIdx.x / CMPQ_WAVE;
     uint32_t *lh0 = lh + (lane & (kCopies - 1)) * kBins;
     const int64_t unit = (int64_t)blockIdx.x * kWaves + wave;
@@ -687,56 +737,11 @@ __global__ __launch_bounds__(kWThreads) void wsel_hist_kernel(WselArgs a, WselSt
     }
 }
 
-// One workgroup of 1024 threads, two bins each: find the digit holding rank `rem`.
-template <int PASS>
-__global__ __launch_bounds__(1024) void wsel_pick_kernel(WselState *st, const uint32_t *__restrict__ hist) {
-    __shared__ uint32_t scan[17];
-    if (!st->fast_failed) return;
-    const uint32_t *h = hist + PASS * kBins;
-    // walk bins from the largest digit down: position r <-> bin 2047 - r
-    const int r0 = 2 * threadIdx.x, r1 = r0 + 1;
-    const uint32_t h0 = h[kBins - 1 - r0], h1 = h[kBins - 1 - r1];
-    uint32_t total;
-    const uint32_t before = block_scan_excl_u32(h0 + h1, scan, &total);
-    const uint64_t rem = st->rem;
-    __syncthreads();
-    if (PASS == 0 && threadIdx.x == 0) st->total = total;
-    if (rem == 0 || rem > total) {
-        // nothing to take, or more asked than there is: take every candidate
-        if (threadIdx.x == 0) {
-            st->prefix = rem == 0 ? 0xffffffffu : 0u;
-            st->rem = rem == 0 ? 0 : rem;  // stays out of range; later passes land here again
-            if (PASS == 2) {
-                st->T = rem == 0 ? 0xffffffffu : 0u;
-                st->need = rem == 0 ? 0 : ~0ull;
-            }
-        }
-        return;
-    }
-    const int shift = PASS == 0 ? 21 : (PASS == 1 ? 10 : 0);
-    if (h0 && before < rem && rem <= (uint64_t)before + h0) {
-        st->prefix |= (uint32_t)(kBins - 1 - r0) << shift;
-        st->rem = rem - before;
-        if (PASS == 2) {
-            st->T = st->prefix;
-            st->need = rem - before;
-        }
-    } else if (h1 && before + h0 < rem && rem <= (uint64_t)before + h0 + h1) {
-        st->prefix |= (uint32_t)(kBins - 1 - r1) << shift;
-        st->rem = rem - before - h0;
-        if (PASS == 2) {
-            st->T = st->prefix;
-            st->need = rem - before - h0;
-        }
-    }
-}
-
 // Keys above the threshold and keys equal to it: per unit from the staging list, or, on
 // the full path, per workgroup from the tables the last histogram pass left.
-// EXACT names the chain a launch belongs to; the launch of the other chain returns.  The
-// fast chain's launch first reads the threshold off the list's second histogram.
-template <bool EXACT>
-__global__ __launch_bounds__(kWThreads) void wsel_count_kernel(WselState *st, WselArgs a,
+// First settles the threshold: read off the list's second histogram when the fast chain
+// holds the answer, else off the three histograms of the exact chain.
+__global__ __launch_bounds__(kWThreads) void wsel_count_kernel(WselState *st, WselArgs a, uint64_t k,
                                                                 const uint32_t *__restrict__ hist,
                                                                 const uint32_t *__restrict__ above,
                                                                 const uint32_t *__restrict__ local_last,
@@ -744,20 +749,24 @@ __global__ __launch_bounds__(kWThreads) void wsel_count_kernel(WselState *st, Ws
                                                                 uint32_t *__restrict__ cnt_eq) {
     __shared__ uint32_t red[kWaves];
     __shared__ PickShared ps;
-    if ((st->fast_failed != 0) != EXACT) return;
     const int lane = threadIdx.x & (CMPQ_WAVE - 1), wave = threadIdx.x / CMPQ_WAVE;
-    uint32_t T = st->T;
-    if (!EXACT) {
+    const bool exact = st->fast_failed != 0;
+    uint32_t T;
+    uint64_t need;
+    if (!exact) {
         uint32_t digit, tot;
-        uint64_t need;
         block_pick(hist + 6 * kBins, st->rem_b, ps, digit, need, tot);  // rem_b lies inside the bin
         T = (st->T22 << 10) | digit;
-        if (blockIdx.x == 0 && threadIdx.x == 0) {
-            st->T = T;
-            st->need = need;
-        }
+    } else {
+        bool all;
+        exact_prefix(hist, k, 3, ps, T, need, all);
+        if (all) need = ~0ull;  // T = 0: every candidate counts
     }
-    if (!EXACT || !st->overflow) {
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        st->T = T;
+        st->need = need;
+    }
+    if (!exact || !st->overflow) {
         const int64_t unit = (int64_t)blockIdx.x * kWaves + wave;
         const unsigned long long *ik = a.stage_ik + unit * a.cap;
         const uint32_t n = a.stage_cnt[unit];
@@ -776,7 +785,7 @@ __global__ __launch_bounds__(kWThreads) void wsel_count_kernel(WselState *st, Ws
         return;
     }
     const uint32_t digit = T & 1023u;
-    const bool everything = st->need == ~0ull;  // more asked than there is: every candidate counts
+    const bool everything = need == ~0ull;  // more asked than there is: every candidate counts
     const uint32_t *h = local_last + (int64_t)blockIdx.x * 1024;
     uint32_t gt = 0;
     for (int b = threadIdx.x; b < 1024; b += kWThreads)
@@ -794,7 +803,6 @@ __global__ __launch_bounds__(kWThreads) void wsel_count_kernel(WselState *st, Ws
 
 // Exclusive prefix over units (or workgroups, on the full path) of (ties seen) and
 // (entries written).  A thread takes kMaxUnits / 1024 consecutive entries.
-template <bool EXACT>
 __global__ __launch_bounds__(1024) void wsel_offsets_kernel(const WselState *st, int nunits, int nblocks,
                                                             const uint32_t *__restrict__ cnt_gt,
                                                             const uint32_t *__restrict__ cnt_eq,
@@ -802,9 +810,8 @@ __global__ __launch_bounds__(1024) void wsel_offsets_kernel(const WselState *st,
                                                             uint64_t *__restrict__ out_base) {
     constexpr int kPer = kMaxUnits / 1024;
     __shared__ uint32_t scan[17];
-    if ((st->fast_failed != 0) != EXACT) return;
     const uint64_t need = st->need;
-    const int n = EXACT && st->overflow ? nblocks : nunits;
+    const int n = st->fast_failed && st->overflow ? nblocks : nunits;
     const int b0 = threadIdx.x * kPer;
     uint32_t e[kPer], g[kPer], e_sum = 0;
 #pragma unroll
@@ -843,13 +850,10 @@ __device__ __forceinline__ uint32_t lanes_below(unsigned long long mask) {
 }
 
 // Writes the answer from the staging list: a wavefront per unit, 64 staged entries a step.
-template <bool EXACT>
-__global__ __launch_bounds__(kWThreads) void wsel_emit_kernel(WselArgs a, const WselState *st,
-                                                               const uint64_t *__restrict__ tie_base,
-                                                               const uint64_t *__restrict__ out_base,
-                                                               int64_t k, int32_t *__restrict__ idx_out,
-                                                               uint16_t *__restrict__ val_out) {
-    if ((st->fast_failed != 0) != EXACT || (EXACT && st->overflow)) return;
+__device__ __forceinline__ void emit_from_list(const WselArgs &a, const WselState *st,
+                                               const uint64_t *__restrict__ tie_base,
+                                               const uint64_t *__restrict__ out_base, int64_t k,
+                                               int32_t *__restrict__ idx_out, uint16_t *__restrict__ val_out) {
     const int lane = threadIdx.x & (CMPQ_WAVE - 1), wave = threadIdx.x / CMPQ_WAVE;
     const int64_t unit = (int64_t)blockIdx.x * kWaves + wave;
     const uint32_t T = st->T;
@@ -879,12 +883,11 @@ __global__ __launch_bounds__(kWThreads) void wsel_emit_kernel(WselArgs a, const 
 // Full path: one more pass over the data, a workgroup per run of 4 units, 4 wave-chunks
 // (2048 consecutive entries) a step.
 template <typename TW>
-__global__ __launch_bounds__(kWThreads) void wsel_write_kernel(
-    WselArgs a, const WselState *st, const uint64_t *__restrict__ tie_base,
-    const uint64_t *__restrict__ out_base, int64_t k, int32_t *__restrict__ idx_out,
-    uint16_t *__restrict__ val_out) {
-    __shared__ uint32_t scan[34];
-    if (!st->fast_failed || !st->overflow) return;
+__device__ __forceinline__ void write_full(const WselArgs &a, const WselState *st,
+                                           const uint64_t *__restrict__ tie_base,
+                                           const uint64_t *__restrict__ out_base, int64_t k,
+                                           int32_t *__restrict__ idx_out, uint16_t *__restrict__ val_out,
+                                           uint32_t *scan) {
     const int lane = threadIdx.x & (CMPQ_WAVE - 1), wave = threadIdx.x / CMPQ_WAVE;
     const uint32_t T = st->T;
     const uint64_t need = st->need;
@@ -943,6 +946,21 @@ __global__ __launch_bounds__(kWThreads) void wsel_write_kernel(
     }
 }
 
+// The last kernel of a call: from the list, unless the exact chain ran and its list
+// overflowed.
+template <typename TW>
+__global__ __launch_bounds__(kWThreads) void wsel_emit_kernel(WselArgs a, const WselState *st,
+                                                               const uint64_t *__restrict__ tie_base,
+                                                               const uint64_t *__restrict__ out_base,
+                                                               int64_t k, int32_t *__restrict__ idx_out,
+                                                               uint16_t *__restrict__ val_out) {
+    __shared__ uint32_t scan[34];
+    if (st->fast_failed && st->overflow)
+        write_full<TW>(a, st, tie_base, out_base, k, idx_out, val_out, scan);
+    else
+        emit_from_list(a, st, tie_base, out_base, k, idx_out, val_out);
+}
+
 struct WselWs {
     WselState *st;
     uint32_t *hist, *cnt_gt, *cnt_eq, *above, *local_last, *stage_cnt;
@@ -981,30 +999,25 @@ int launch_weight_select(WselArgs a, const WselPlan &p, int64_t k, int32_t *idx_
     a.sample_stride = p.sample_stride;
     a.n_sample = p.n_sample;
     a.sample_rank = p.sample_rank;
-    int64_t sample_blocks = cdiv(p.n_sample, 2 * kWaves);
-    if (sample_blocks > 1024) sample_blocks = 1024;
+    int64_t sample_blocks = cdiv(p.n_sample, kWaves);
+    if (sample_blocks > 512) sample_blocks = 512;
     if (sample_blocks < 1) sample_blocks = 1;
-    wsel_init_kernel<<<64, 256, 0, s>>>(w.st, w.hist, (uint64_t)k, idx_out, k);
+    wsel_init_kernel<<<64, 256, 0, s>>>(w.st, w.hist, idx_out, k);
     // fast chain
     wsel_sample_kernel<TW, 0><<<(unsigned)sample_blocks, kWThreads, 0, s>>>(a, w.hist);
     wsel_sample_kernel<TW, 1><<<(unsigned)sample_blocks, kWThreads, 0, s>>>(a, w.hist);
     wsel_stage_kernel<TW><<<p.nblocks, kWThreads, 0, s>>>(a, w.st, w.hist);
-    wsel_list_kernel<0><<<p.nblocks, kWThreads, 0, s>>>(a, w.st, w.hist, (uint64_t)k);
-    wsel_list_kernel<1><<<p.nblocks, kWThreads, 0, s>>>(a, w.st, w.hist, (uint64_t)k);
-    wsel_count_kernel<false><<<p.nblocks, kWThreads, 0, s>>>(w.st, a, w.hist, w.above, w.local_last, w.cnt_gt, w.cnt_eq);
-    wsel_offsets_kernel<false><<<1, 1024, 0, s>>>(w.st, p.nunits, p.nblocks, w.cnt_gt, w.cnt_eq, w.tie_base, w.out_base);
-    wsel_emit_kernel<false><<<p.nblocks, kWThreads, 0, s>>>(a, w.st, w.tie_base, w.out_base, k, idx_out, val_out);
-    // exact chain: every kernel returns at once unless the fast chain raised its flag
-    wsel_hist_kernel<TW, 0><<<p.nblocks, kWThreads, 0, s>>>(a, w.st, w.hist, w.above, w.local_last);
-    wsel_pick_kernel<0><<<1, 1024, 0, s>>>(w.st, w.hist);
-    wsel_hist_kernel<TW, 1><<<p.nblocks, kWThreads, 0, s>>>(a, w.st, w.hist, w.above, w.local_last);
-    wsel_pick_kernel<1><<<1, 1024, 0, s>>>(w.st, w.hist);
-    wsel_hist_kernel<TW, 2><<<p.nblocks, kWThreads, 0, s>>>(a, w.st, w.hist, w.above, w.local_last);
-    wsel_pick_kernel<2><<<1, 1024, 0, s>>>(w.st, w.hist);
-    wsel_count_kernel<true><<<p.nblocks, kWThreads, 0, s>>>(w.st, a, w.hist, w.above, w.local_last, w.cnt_gt, w.cnt_eq);
-    wsel_offsets_kernel<true><<<1, 1024, 0, s>>>(w.st, p.nunits, p.nblocks, w.cnt_gt, w.cnt_eq, w.tie_base, w.out_base);
-    wsel_emit_kernel<true><<<p.nblocks, kWThreads, 0, s>>>(a, w.st, w.tie_base, w.out_base, k, idx_out, val_out);
-    wsel_write_kernel<TW><<<p.nblocks, kWThreads, 0, s>>>(a, w.st, w.tie_base, w.out_base, k, idx_out, val_out);
+    const int list_blocks = p.nblocks < 256 ? p.nblocks : 256;  // few: each ends with a flush into shared counters
+    wsel_list_kernel<0><<<list_blocks, kWThreads, 0, s>>>(a, w.st, p.nunits, w.hist, (uint64_t)k);
+    wsel_list_kernel<1><<<list_blocks, kWThreads, 0, s>>>(a, w.st, p.nunits, w.hist, (uint64_t)k);
+    // exact chain: these return at once unless the fast chain raised its flag
+    wsel_hist_kernel<TW, 0><<<p.nblocks, kWThreads, 0, s>>>(a, w.st, (uint64_t)k, w.hist, w.above, w.local_last);
+    wsel_hist_kernel<TW, 1><<<p.nblocks, kWThreads, 0, s>>>(a, w.st, (uint64_t)k, w.hist, w.above, w.local_last);
+    wsel_hist_kernel<TW, 2><<<p.nblocks, kWThreads, 0, s>>>(a, w.st, (uint64_t)k, w.hist, w.above, w.local_last);
+    // threshold, placement and output, from whichever chain holds the answer
+    wsel_count_kernel<<<p.nblocks, kWThreads, 0, s>>>(w.st, a, (uint64_t)k, w.hist, w.above, w.local_last, w.cnt_gt, w.cnt_eq);
+    wsel_offsets_kernel<<<1, 1024, 0, s>>>(w.st, p.nunits, p.nblocks, w.cnt_gt, w.cnt_eq, w.tie_base, w.out_base);
+    wsel_emit_kernel<TW><<<p.nblocks, kWThreads, 0, s>>>(a, w.st, w.tie_base, w.out_base, k, idx_out, val_out);
     CMPQ_LAUNCH_CHECK();
     return CMPQ_OK;
 }
