@@ -71,6 +71,11 @@ def main():
     ap.add_argument("--workload", default="block70b",
                     help="block70b (default, the headline target), block13b, block7b, q7b, tiny")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--streams", type=int, default=3,
+                    help="streams the independent layers of a block are shared out over (default 3)")
+    ap.add_argument("--serial-steps", type=int, default=2,
+                    help="extra untimed steps on one stream for the per-stage and per-kernel figures "
+                         "that overlap would blur (0: skip)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (outside the timed region): under "
                          "rocprofv3 --pmc it gives the HBM counters a kernel of known traffic to scale by")
@@ -91,12 +96,13 @@ def main():
     wl = synth.workload(args.workload)
     weights, acts = synth.materialize(wl, dev)
     layers = [(l.name, l.x_key) for l in wl.layers]
-    ws = B.Workspace(dev)
+    ws = B.Workspace(dev) if args.streams <= 1 else [B.Workspace(dev) for _ in range(args.streams)]
     status = torch.zeros(1, dtype=torch.int32, device=dev)
 
     def step(timer=None):
         return P.quantize_block(weights, acts, layers, wl.bit_set, wl.avg_bits, wl.rho_act_ppm,
-                                wl.rho_q_ppm, wl.iters, ws, with_error=True, status=status, timer=timer)
+                                wl.rho_q_ppm, wl.iters, ws, with_error=True, status=status, timer=timer,
+                                streams=args.streams)
 
     if args.calibration_copy:
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
@@ -117,13 +123,23 @@ def main():
     assert status.item() == 0, "non-finite input flagged"
 
     stages = timer.totals()
+    serial = None
+    if args.streams > 1 and args.serial_steps > 0:     # one stream: launches do not share the GPU
+        ws1 = ws[0]
+        t1 = P.StageTimer()
+        for _ in range(args.serial_steps):
+            o1 = P.quantize_block(weights, acts, layers, wl.bit_set, wl.avg_bits, wl.rho_act_ppm,
+                                  wl.rho_q_ppm, wl.iters, ws1, with_error=True, status=status, timer=t1)
+            del o1
+        serial = t1.totals()
     flops = sum(credited_kmeans_flops(r, wl.iters) for r in out.values()) * 2      # two passes per layer
     n_km, ms_km = stages["kmeans"]
     launches_per_step = n_km // args.steps
     avg_launch_s = ms_km / 1e3 / n_km
     achieved = flops / launches_per_step / avg_launch_s / 1e12
     x_bytes = sum(acts[k].numel() * acts[k].element_size() for k in acts)
-    n_st, ms_st = stages["act_stats"]
+    n_st, ms_st = (serial or stages)["act_stats"]
+    n_st_steps = args.serial_steps if serial is not None else args.steps
     line = {
         "metric": "Mparams/s quantized (whole CMPQ path, both k-means passes) at the target average bits",
         "value": wl.params * args.steps / dt / 1e6,
@@ -142,9 +158,21 @@ def main():
                      "traffic": KMEANS_TRAFFIC_BYTES.get(wl.name), "launches_per_step": launches_per_step,
                      "avg_launch_ms": avg_launch_s * 1e3, "credited_flop_per_launch": flops / launches_per_step},
         "stages_ms_per_step": {k: round(v[1] / args.steps, 4) for k, v in sorted(stages.items())},
-        "act_stats_hbm": {"achieved_GBs": x_bytes * args.steps / (ms_st / 1e3) / 1e9, "peak_GBs": HBM_PEAK_GBS,
-                          "frac": x_bytes * args.steps / (ms_st / 1e3) / 1e9 / HBM_PEAK_GBS},
+        "streams": args.streams,
+        "act_stats_hbm": {"achieved_GBs": x_bytes * n_st_steps / (ms_st / 1e3) / 1e9, "peak_GBs": HBM_PEAK_GBS,
+                          "frac": x_bytes * n_st_steps / (ms_st / 1e3) / 1e9 / HBM_PEAK_GBS,
+                          "from": "serial steps" if serial is not None else "timed steps"},
     }
+    if serial is not None:
+        n1, ms1 = serial["kmeans"]
+        line["serial"] = {
+            "note": "same step on one stream, run after the timed region: launches do not overlap",
+            "steps": args.serial_steps,
+            "ms_per_step": round(sum(v[1] for v in serial.values()) / args.serial_steps, 4),
+            "stages_ms_per_step": {k: round(v[1] / args.serial_steps, 4) for k, v in sorted(serial.items())},
+            "kmeans_avg_launch_ms": ms1 / n1,
+            "kmeans_frac_of_alu_peak": flops / launches_per_step / (ms1 / 1e3 / n1) / 1e12 / ALU_PEAK_TFLOPS,
+        }
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(wl, weights, acts)
     print(json.dumps(line))

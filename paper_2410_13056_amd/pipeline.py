@@ -143,21 +143,71 @@ def quantize_layer(W: torch.Tensor, sumsq: torch.Tensor, bit_set: Sequence[int],
     return res
 
 
+_side_streams: Dict[tuple, list] = {}
+
+
+def _streams_for(device: torch.device, n: int):
+    """`n` streams of default priority on `device`, created once and reused."""
+    key = (device.type, device.index)
+    have = _side_streams.setdefault(key, [])
+    while len(have) < n:
+        have.append(torch.cuda.Stream(device=device))
+    return have[:n]
+
+
 def quantize_block(weights: Dict[str, torch.Tensor], acts: Dict[str, torch.Tensor], layers, bit_set,
                    avg_bits: float, rho_act_ppm: int, rho_q_ppm: int, iters: int,
-                   ws: Optional[B.Workspace] = None, with_error: bool = False,
-                   status: Optional[torch.Tensor] = None,
-                   timer: Optional[StageTimer] = None) -> Dict[str, LayerResult]:
+                   ws=None, with_error: bool = False, status: Optional[torch.Tensor] = None,
+                   timer: Optional[StageTimer] = None, streams: int = 1) -> Dict[str, LayerResult]:
     """One pass of the whole path over a decoder block: statistics once per distinct
-    input, then every linear layer.  `layers` lists (name, x_key) pairs."""
+    input, then every linear layer.  `layers` lists (name, x_key) pairs.
+
+    Layers do not depend on each other.  With ``streams > 1`` they are shared out over that
+    many streams (largest first, to the stream with the least work so far) so that the
+    compute-bound k-means of one layer runs beside the memory-bound steps of another; `ws`
+    is then a list with one workspace per stream.  The call returns with everything
+    enqueued and the current stream waiting for the others."""
     some = next(iter(weights.values()))
-    ws = ws or B.Workspace(some.device)
-    stats = {}
-    out = {}
-    for name, x_key in layers:
-        if x_key not in stats:
-            stats[x_key] = activation_stats(acts[x_key], ws, status=status, timer=timer)[1]
-        out[name] = quantize_layer(weights[name], stats[x_key], bit_set, avg_bits, rho_act_ppm,
-                                   rho_q_ppm, iters, ws, with_error=with_error, status=status,
-                                   timer=timer)
-    return out
+    dev = some.device
+    if streams <= 1:
+        ws = ws or B.Workspace(dev)
+        stats = {}
+        out = {}
+        for name, x_key in layers:
+            if x_key not in stats:
+                stats[x_key] = activation_stats(acts[x_key], ws, status=status, timer=timer)[1]
+            out[name] = quantize_layer(weights[name], stats[x_key], bit_set, avg_bits, rho_act_ppm,
+                                       rho_q_ppm, iters, ws, with_error=with_error, status=status,
+                                       timer=timer)
+        return out
+    if ws is None:
+        ws = [B.Workspace(dev) for _ in range(streams)]
+    if len(ws) != streams:
+        raise ValueError("one workspace per stream")
+    main = torch.cuda.current_stream(dev)
+    side = _streams_for(dev, streams)
+    for st in side:
+        st.wait_stream(main)
+    # largest layer first, each to the stream with the least work so far
+    order = sorted(layers, key=lambda l: -weights[l[0]].numel())
+    load = [0] * streams
+    stats: Dict[str, tuple] = {}          # x_key -> (sumsq, event, stream index)
+    results: Dict[str, LayerResult] = {}
+    for name, x_key in order:
+        j = min(range(streams), key=lambda t: load[t])
+        load[j] += weights[name].numel()
+        with torch.cuda.stream(side[j]):
+            if x_key not in stats:
+                sumsq = activation_stats(acts[x_key], ws[j], status=status, timer=timer)[1]
+                ev = torch.cuda.Event()
+                ev.record()
+                stats[x_key] = (sumsq, ev, j)
+            sumsq, ev, owner = stats[x_key]
+            if owner != j:
+                side[j].wait_event(ev)
+            results[name] = quantize_layer(weights[name], sumsq, bit_set, avg_bits, rho_act_ppm,
+                                           rho_q_ppm, iters, ws[j], with_error=with_error,
+                                           status=status, timer=timer)
+    for st in side:
+        main.wait_stream(st)
+    return {name: results[name] for name, _ in layers}

@@ -435,3 +435,28 @@ def test_end_to_end_scaled_workloads(env, name, shrink, tokens):
                                wl.iters, sumsq=_np(stats[layer.x_key]))
         _compare_layer(env, r, o, wl.bit_set, exact_levels=True)
     assert status.item() == 0
+
+
+def test_block_over_several_streams_matches_one_stream(env):
+    """Layers of a block shared out over 3 streams: every output bit-identical to the
+    single-stream run (which the tests above check against the oracle)."""
+    P, B, synth = env["P"], env["B"], env["synth"]
+    wl = synth.scaled(synth.workload("block70b"), tokens=512, shrink=8)
+    wts, xs = synth.materialize(wl, DEV)
+    layers = [(l.name, l.x_key) for l in wl.layers]
+    status = torch.zeros(1, dtype=torch.int32, device=DEV)
+    args = (wts, xs, layers, wl.bit_set, wl.avg_bits, wl.rho_act_ppm, wl.rho_q_ppm, wl.iters)
+    one = P.quantize_block(*args, B.Workspace(DEV), with_error=True, status=status)
+    for _ in range(2):                                  # the second run reuses streams and workspaces
+        many = P.quantize_block(*args, [B.Workspace(DEV) for _ in range(3)], with_error=True,
+                                status=status, streams=3)
+        torch.cuda.synchronize()
+        assert list(many) == list(one)
+        for name in one:
+            a, b = one[name], many[name]
+            assert a.counts == b.counts
+            for f in ("sumsq", "act_idx", "bits", "centroids", "codes", "out_idx", "out_val", "err_ch", "err_total"):
+                assert torch.equal(getattr(a, f), getattr(b, f)), (name, f)
+            for x, y in zip(a.packed + a.chan_idx + a.lut, b.packed + b.chan_idx + b.lut):
+                assert (x is None) == (y is None) and (x is None or torch.equal(x, y)), name
+    assert status.item() == 0
