@@ -318,6 +318,31 @@ def test_weight_outliers_staging_and_full_path(env, case):
             assert np.array_equal(_np(val).view(np.uint16), oval)
 
 
+@pytest.mark.parametrize("dtype", [np.float16, np.float32])
+def test_weight_outliers_sampled_guess(env, dtype):
+    # enough wave-chunks (17 per channel x 1536) that the first guess comes from a sample
+    # (every 3rd chunk); ragged channel tail, both dtypes and both scores
+    B, ws, orc = env["B"], env["ws"], env["orc"]
+    rng = np.random.default_rng(5)
+    d_in, d_out = 1536, 8192 + 8
+    W = rng.normal(0, 0.02, (d_in, d_out))
+    W[rng.random(W.shape) < 0.005] *= 8
+    W = W.astype(dtype)
+    bits = rng.integers(3, 5, d_in).astype(np.uint8)
+    bits[[11, 700]] = 16
+    ocent, ocodes = orc.kmeans(W, bits, iters=2)
+    live = int((bits <= 4).sum()) * d_out
+    Wd, cd, kd, bd = _dev(W), _dev(ocent), _dev(ocodes), _dev(bits)
+    for score in (B.SCORE_RESIDUAL, B.SCORE_MAGNITUDE):
+        for k in (live // 100, live // 2000):
+            idx = torch.full((k,), -7, dtype=torch.int32, device=DEV)
+            val = torch.zeros(k, dtype=torch.float16, device=DEV)
+            B.extract_weight_outliers(Wd, cd, kd, bd, k, idx, val, ws, score)
+            oidx, oval = orc.weight_outliers(W, ocent, ocodes, bits, k, score)
+            assert np.array_equal(_np(idx).astype(np.int64), oidx), (score, k)
+            assert np.array_equal(_np(val).view(np.uint16), oval)
+
+
 # ------------------------------------------------------------------ storage and error
 
 @pytest.mark.parametrize("d_out", [1, 31, 32, 33, 100, 512, 4096 + 16])
