@@ -147,7 +147,8 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": dt / args.steps * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32 compares, f64 sums" if wl.dtype == "f16" else "f32 compares, f64 sums (f32 weights)",
+        "dtype": "int64 (exact sums over 16-bit keys, one f64 divide per level)" if wl.dtype == "f16"
+                 else "f32 compares, f64 sums (f32 weights)",
         "data": "synthetic",
         "config": {"workload": wl.name, "params": wl.params, "layers": len(wl.layers),
                    "weights": wl.dtype, "bit_set": list(wl.bit_set), "avg_bits": wl.avg_bits,
