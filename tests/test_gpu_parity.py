@@ -223,6 +223,29 @@ def test_kmeans_parity_signed_zeros_and_boundaries_at_zero(env, d_out):
         _check_kmeans(cent, codes, ocent, ocodes, exact=True)
 
 
+def test_kmeans_direct_kernel_agrees(env):
+    """The brute-force kernel (CMPQ_KMEANS_DIRECT) is a second implementation: same bits as
+    the bucket kernel and as the oracle, with and without removed entries."""
+    B, orc = env["B"], env["orc"]
+    rng = np.random.default_rng(21)
+    d_in, d_out = 48, 4096
+    W = rng.normal(0, 0.02, (d_in, d_out))
+    W[rng.random(W.shape) < 0.01] *= 12
+    W = W.astype(np.float16)
+    bits = rng.integers(1, 5, d_in).astype(np.uint8)
+    bits[7] = 16
+    excl = np.sort(rng.choice(d_in * d_out, 2000, replace=False)).astype(np.int64)
+    try:
+        for out_idx in (None, excl):
+            ocent, ocodes = orc.kmeans(W, bits, out_idx=out_idx, iters=11)
+            for algo in (B.KMEANS_DIRECT, B.KMEANS_HISTOGRAM):
+                B.set_kmeans_algorithm(algo)
+                cent, codes = _kmeans_gpu(env, W, bits, out_idx=out_idx, iters=11)
+                _check_kmeans(cent, codes, ocent, ocodes, exact=True)
+    finally:
+        B.set_kmeans_algorithm(B.KMEANS_HISTOGRAM)
+
+
 def test_kmeans_parity_with_removed_entries_and_weights(env):
     rng = np.random.default_rng(2)
     d_in, d_out = 32, 777
