@@ -195,6 +195,26 @@ def dequant_error(W: np.ndarray, centroids: np.ndarray, codes: np.ndarray, bits:
     return err, tot
 
 
+def lut_matvec(X: np.ndarray, W: np.ndarray, centroids: np.ndarray, codes: np.ndarray, bits: np.ndarray,
+               out_idx: Optional[np.ndarray] = None) -> np.ndarray:
+    """Fig. 4: ``Y float64[m, d_out] = X [m, d_in] @ W_hat`` with the deployed W_hat (FP16 LUT
+    levels, outliers as FP16 weights)."""
+    X = _c(X)
+    W = _c(W)
+    m, d_in = X.shape
+    d_in2, d_out = W.shape
+    assert d_in == d_in2
+    oi = None if out_idx is None else _c(out_idx, np.int64)
+    Y = np.zeros((m, d_out), np.float64)
+    rc = lib().orc_lut_matvec(_p(X), _dtype_code(X), ctypes.c_int64(m), ctypes.c_int64(d_in),
+                              ctypes.c_int64(d_in), _p(W), _dtype_code(W), ctypes.c_int64(d_out),
+                              ctypes.c_int64(d_out), _p(_c(centroids, np.float32)), _p(_c(codes, np.uint8)),
+                              _p(_c(bits, np.uint8)), _p(oi), ctypes.c_int64(0 if oi is None else oi.shape[0]),
+                              _p(Y))
+    assert rc == 0, rc
+    return Y
+
+
 def quantize_layer(W: np.ndarray, X: np.ndarray, bit_set: Sequence[int], avg_bits: float,
                    rho_act_ppm: int = 4500, rho_q_ppm: int = 500, iters: int = 20,
                    sumsq: Optional[np.ndarray] = None, score: int = SCORE_RESIDUAL) -> dict:

@@ -487,6 +487,44 @@ int orc_dequant_error(const void *W, int dtype, int64_t d_in, int64_t d_out, int
     return 0;
 }
 
+/* ---- Fig. 4 / Sec. 6: the product with the deployed weight ----------------------------------- */
+
+/*
+ * Y[t,o] = sum_i X[t,i] * W_hat[i,o]  (Fig. 4: the input times the quantized weight plus
+ * the outlier matrices), with W_hat as it is stored for deployment:
+ *   a quantized entry reads its level from the FP16 look-up table of Sec. 5.1
+ *   (the level rounded to FP16, as orc_pack writes it);
+ *   an entry of O = O_act + O_q (channels with bits outside 1..4, entries of out_idx)
+ *   is the FP16 weight itself - it overrides the level, as in orc_dequant_error.
+ * Products and sums in fp64, channels added in ascending order.  Y is m x d_out, dense.
+ */
+int orc_lut_matvec(const void *X, int xdtype, int64_t m, int64_t d_in, int64_t ldx, const void *W,
+                   int dtype, int64_t d_out, int64_t ldw, const float *centroids,
+                   const uint8_t *codes, const uint8_t *bits, const int64_t *out_idx,
+                   int64_t n_out, double *Y) {
+    if (!X || !W || !centroids || !codes || !bits || !Y) return -1;
+    uint8_t *excl = (uint8_t *)calloc((size_t)(d_in * d_out > 0 ? d_in * d_out : 1), 1);
+    for (int64_t j = 0; j < n_out; ++j) excl[out_idx[j]] = 1;
+#pragma omp parallel for schedule(static)
+    for (int64_t o = 0; o < d_out; ++o) {
+        for (int64_t t = 0; t < m; ++t) {
+            double y = 0.0;
+            for (int64_t i = 0; i < d_in; ++i) {
+                int prot = bits[i] < 1 || bits[i] > 4;
+                double what;
+                if (prot || excl[i * d_out + o])
+                    what = half_to_double(double_to_half(load_elem(W, dtype, i * ldw + o)));
+                else
+                    what = half_to_double(double_to_half((double)centroids[i * ORC_KMAX + codes[i * d_out + o]]));
+                y += load_elem(X, xdtype, t * ldx + i) * what;
+            }
+            Y[t * d_out + o] = y;
+        }
+    }
+    free(excl);
+    return 0;
+}
+
 /* Threads the "parallel for" loops above will use (reported beside oracle timings). */
 int orc_num_threads(void) {
 #ifdef _OPENMP

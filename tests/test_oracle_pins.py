@@ -539,3 +539,72 @@ def test_more_levels_never_hurt_and_outlier_removal_helps(orc):
     assert len(r1["out_idx"]) == orc.count_ppm(5000, d_in * d_out)
     assert r1["chan_mask"].sum() == orc.count_ppm(4500, d_in) == len(r1["act_idx"])
     assert not set(r1["out_idx"] // d_out) & set(r1["act_idx"])
+
+
+# ------------------------------------------------------------------ Fig. 4: product with the deployed weight
+
+def _deployed_weight(W, cent, codes, bits, out_idx):
+    """W_hat of Fig. 4 built with numpy only: FP16 table levels, outliers as FP16 weights."""
+    lut = cent.astype(np.float16).astype(np.float64)
+    what = np.take_along_axis(lut, codes.astype(np.int64), axis=1)
+    w16 = W.astype(np.float16).astype(np.float64)
+    keep = np.zeros(W.shape, bool)
+    keep[(bits < 1) | (bits > 4), :] = True
+    if out_idx is not None and len(out_idx):
+        keep.reshape(-1)[out_idx] = True
+    return np.where(keep, w16, what)
+
+
+def test_lut_matvec_hand_example(orc):
+    # 2 channels x 2 outputs: channel 0 has two levels {-1, 3}, channel 1 is protected
+    W = np.array([[0.3, 2.9], [0.5, -0.25]], np.float32)
+    cent = np.zeros((2, 16), np.float32)
+    cent[0, :2] = [-1.0, 3.0]
+    codes = np.array([[0, 1], [0, 0]], np.uint8)
+    bits = np.array([1, orc.PROTECTED], np.uint8)
+    X = np.array([[2.0, 4.0], [1.0, 0.0]], np.float32)
+    Y = orc.lut_matvec(X, W, cent, codes, bits)
+    # y = x0 * level + x1 * w1:  [2*(-1) + 4*0.5, 2*3 + 4*(-0.25)] and [-1, 3]
+    assert np.array_equal(Y, np.array([[0.0, 5.0], [-1.0, 3.0]]))
+    # entry (0, 0) as an outlier: the weight 0.3 (as FP16) replaces the level -1
+    Y = orc.lut_matvec(X, W, cent, codes, bits, out_idx=np.array([0]))
+    w = float(np.float16(0.3))
+    assert np.allclose(Y, [[2 * w + 2.0, 5.0], [w, 3.0]], rtol=0, atol=1e-15)
+
+
+def test_lut_matvec_equals_dense_product_with_rebuilt_weight(orc):
+    rng = np.random.default_rng(31)
+    d_in, d_out, m = 45, 70, 3
+    W = rng.normal(0, 0.05, (d_in, d_out)).astype(np.float16)
+    X = rng.normal(0, 1, (m, d_in)).astype(np.float16)
+    bits = rng.integers(1, 5, d_in).astype(np.uint8)
+    bits[[3, 30]] = orc.PROTECTED
+    cent, codes = orc.kmeans(W, bits, iters=4)
+    out_idx = np.sort(rng.choice(d_in * d_out, 60, replace=False))
+    out_idx = out_idx[~np.isin(out_idx // d_out, [3, 30])]
+    for oi in (None, out_idx):
+        Y = orc.lut_matvec(X, W, cent, codes, bits, oi)
+        ref = X.astype(np.float64) @ _deployed_weight(W, cent, codes, bits, oi)
+        assert np.allclose(Y, ref, rtol=1e-13, atol=1e-13)
+    # every entry restored: the product with the FP16 weight itself
+    all_prot = np.full(d_in, orc.PROTECTED, np.uint8)
+    Y = orc.lut_matvec(X, W, cent, codes, all_prot)
+    assert np.allclose(Y, X.astype(np.float64) @ W.astype(np.float64), rtol=1e-13, atol=1e-13)
+
+
+def test_lut_matvec_agrees_with_the_packed_format(orc):
+    """The product computed from the stored streams (unpacked here bit by bit, Sec. 5.1) equals the
+    product computed from codes and levels: packing loses nothing the kernel needs."""
+    rng = np.random.default_rng(32)
+    d_in, d_out = 29, 50
+    W = rng.normal(0, 0.05, (d_in, d_out)).astype(np.float32)
+    x = rng.normal(0, 1, (1, d_in)).astype(np.float32)
+    bits = rng.integers(2, 5, d_in).astype(np.uint8)
+    cent, codes = orc.kmeans(W, bits, iters=3)
+    y = np.zeros(d_out)
+    for b in (2, 3, 4):
+        packed, chan, lut = orc.pack(codes, bits, cent, b)
+        for r, i in enumerate(chan):
+            row_codes, _ = _unpack(packed[r], b, d_out)
+            y += float(x[0, i]) * lut[r].view(np.float16).astype(np.float64)[row_codes]
+    assert np.allclose(orc.lut_matvec(x, W, cent, codes, bits)[0], y, rtol=1e-13, atol=1e-13)
