@@ -63,6 +63,8 @@ extern "C" {
 #define CMPQ_OP_KMEANS 4           /* n ignored                                  */
 #define CMPQ_OP_PACK 5             /* n ignored                                  */
 #define CMPQ_OP_DEQUANT_ERROR 6    /* n ignored                                  */
+#define CMPQ_OP_OUTLIERS_BY_COLUMN 7 /* n = entries of O_q                        */
+#define CMPQ_OP_LUT_MATVEC 8       /* n = tokens in the call                     */
 
 /* `mode` / `score` of cmpq_extract_outliers */
 #define CMPQ_OUTLIER_CHANNELS 0
@@ -218,6 +220,66 @@ int cmpq_dequant_error(const void *W, int dtype, int64_t d_in, int64_t d_out, in
                        const float *centroids, const uint8_t *codes, const uint8_t *bits,
                        const int32_t *out_idx, int64_t n_out, const float *sumsq, double *err_ch,
                        double *err_total, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * ---- Sec. 6 / Fig. 4: the product with the deployed weight --------------------------------
+ *
+ * Fig. 4 splits a layer by precision: per width a table-driven product of the input with
+ * the packed codes, plus the outlier matrices multiplied in FP16 with the same input, all
+ * summed into one output.  The three calls below are that consumer of cmpq_pack's format.
+ * The deployed weight is
+ *   W_hat[i,o] = FP16 table level lut[row(i)][code(i,o)]   for a quantized entry,
+ *              = fp16(W[i,o])                               for channels of O_act and entries of O_q
+ * (an outlier overrides its level: a table cannot store the exact zero that "W_q + O" of
+ * Sec. 3.2.2 would need), and Y[t,o] = sum_i X[t,i] * W_hat[i,o].
+ */
+
+/*
+ * The rows of O_act as they are deployed: W_act[j, :] = fp16(W[act_idx[j], :]) for
+ * j < k_act (act_idx from cmpq_extract_outliers, CHANNELS mode).  W_act is FP16
+ * [k_act, d_out] with leading dimension ld_act >= d_out.  No workspace.
+ */
+int cmpq_gather_channels(const void *W, int dtype, int64_t d_in, int64_t d_out, int64_t ldw,
+                         const int32_t *act_idx, int64_t k_act, uint16_t *W_act, int64_t ld_act,
+                         void *stream);
+
+/*
+ * O_q in the form the product reads: a compressed sparse matrix (Sec. 6) whose rows are
+ * the outputs, so that every output is one sequential sum.
+ * Input: out_idx [n_out] ascending linear indices i*d_out+o with their FP16 values out_val
+ * (from cmpq_extract_outliers), and the final centroids / codes of the layer.  Output:
+ *   colptr  [d_out+1] int32: entries of column o are colptr[o] .. colptr[o+1]-1;
+ *   row_idx [n_out]   int32: input channel of each entry, ascending inside a column;
+ *   delta   [n_out]   fp32 : out_val - FP16 table level of the entry's code.  Adding
+ *                            X[t,i]*delta to the table product makes the outlier override
+ *                            its level.
+ * Workspace: CMPQ_OP_OUTLIERS_BY_COLUMN.  d_out < 2^20.
+ */
+int cmpq_outliers_by_column(const int32_t *out_idx, const uint16_t *out_val, int64_t n_out,
+                            int64_t d_in, int64_t d_out, const float *centroids,
+                            const uint8_t *codes, int32_t *colptr, int32_t *row_idx, float *delta,
+                            void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Y[t,o] = sum_i X[t,i] * W_hat[i,o] for t < m: X FP16 [m, d_in] (ldx), Y fp32 [m, d_out]
+ * (ldy).  The weight arrives as stored:
+ *   bit_set, n_set, counts_host, packed, chan_idx, lut   as written by cmpq_pack (host
+ *       arrays of device pointers; a width with no channels may have null pointers);
+ *   act_idx [k_act], W_act [k_act, d_out] (ld_act)       the channels of O_act, FP16;
+ *   colptr, row_idx, delta                               O_q from cmpq_outliers_by_column
+ *                                                        (colptr null: no such outliers).
+ * Products and sums are fp32: per output the table products are summed over slabs of 128
+ * rows of one width in a fixed order, then the O_act rows, then the column's O_q entries;
+ * the result is reproducible bit for bit.  Workspace: CMPQ_OP_LUT_MATVEC with n = m.
+ * Limits: m <= 65535, d_out < 2^20.
+ */
+int cmpq_lut_matvec(const void *X, int64_t m, int64_t d_in, int64_t ldx, int64_t d_out,
+                    const int32_t *bit_set, int n_set, const int64_t *counts_host,
+                    const uint32_t *const *packed, const int32_t *const *chan_idx,
+                    const uint16_t *const *lut, const int32_t *act_idx, const uint16_t *W_act,
+                    int64_t k_act, int64_t ld_act, const int32_t *colptr, const int32_t *row_idx,
+                    const float *delta, float *Y, int64_t ldy, void *ws, size_t ws_bytes,
+                    void *stream);
 
 #ifdef __cplusplus
 }

@@ -19,6 +19,7 @@ F16, F32 = 0, 1
 KMAX = 16
 PROTECTED = 16
 STATUS_NONFINITE = 1
+OP_OUTLIERS_BY_COLUMN, OP_LUT_MATVEC = 7, 8
 OP_ACT_STATS, OP_ALLOCATE_BITS, OP_OUTLIER_CHANNELS, OP_OUTLIER_WEIGHTS, OP_KMEANS, OP_PACK, \
     OP_DEQUANT_ERROR = range(7)
 OUTLIER_CHANNELS, OUTLIER_WEIGHTS = 0, 1
@@ -28,7 +29,8 @@ KMEANS_HISTOGRAM, KMEANS_DIRECT = 0, 1
 
 EXPORTS = ("cmpq_workspace_bytes", "cmpq_strerror", "cmpq_count_ppm", "cmpq_act_stats",
            "cmpq_transpose", "cmpq_allocate_bits", "cmpq_extract_outliers",
-           "cmpq_kmeans_quantize", "cmpq_pack", "cmpq_dequant_error", "cmpq_set_kmeans_algorithm")
+           "cmpq_kmeans_quantize", "cmpq_pack", "cmpq_dequant_error", "cmpq_set_kmeans_algorithm",
+           "cmpq_gather_channels", "cmpq_outliers_by_column", "cmpq_lut_matvec")
 
 _i64, _i32, _int, _vp, _dbl, _sz = (ctypes.c_int64, ctypes.c_int32, ctypes.c_int, ctypes.c_void_p,
                                     ctypes.c_double, ctypes.c_size_t)
@@ -66,6 +68,10 @@ def lib() -> ctypes.CDLL:
         L.cmpq_dequant_error.argtypes = [_vp, _int, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _i64, _vp,
                                          _vp, _vp, _vp, _sz, _vp]
         L.cmpq_set_kmeans_algorithm.argtypes = [_int]
+        L.cmpq_gather_channels.argtypes = [_vp, _int, _i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp]
+        L.cmpq_outliers_by_column.argtypes = [_vp, _vp, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+        L.cmpq_lut_matvec.argtypes = [_vp, _i64, _i64, _i64, _i64, _vp, _int, _vp, _vp, _vp, _vp, _vp, _vp,
+                                      _i64, _i64, _vp, _vp, _vp, _vp, _i64, _vp, _sz, _vp]
         for name in EXPORTS[3:]:
             getattr(L, name).restype = _int
         _lib = L
@@ -222,3 +228,57 @@ def dequant_error(W: torch.Tensor, centroids: torch.Tensor, codes: torch.Tensor,
                                     _ptr(bits), _ptr(out_idx), int(n_out), _ptr(sumsq), _ptr(err_ch),
                                     _ptr(err_total), _ptr(buf), buf.numel(), _stream()),
            "cmpq_dequant_error")
+
+
+def gather_channels(W: torch.Tensor, act_idx: torch.Tensor, W_act: torch.Tensor) -> None:
+    """Fig. 4: the rows of O_act as deployed, ``W_act[j] = fp16(W[act_idx[j]])``."""
+    d_in, d_out, ldw = _rows(W)
+    k_act = int(act_idx.numel())
+    if k_act:
+        ka, do, ld_act = _rows(W_act)
+        if (ka, do) != (k_act, d_out) or W_act.dtype != torch.float16:
+            raise ValueError("W_act must be fp16 [k_act, d_out]")
+    else:
+        ld_act = d_out
+    _check(lib().cmpq_gather_channels(_ptr(W), _dtype(W), d_in, d_out, ldw, _ptr(act_idx), k_act,
+                                      _ptr(W_act), ld_act, _stream()),
+           "cmpq_gather_channels")
+
+
+def outliers_by_column(out_idx: Optional[torch.Tensor], out_val: Optional[torch.Tensor], n_out: int,
+                       d_in: int, d_out: int, centroids: torch.Tensor, codes: torch.Tensor,
+                       colptr: torch.Tensor, row_idx: torch.Tensor, delta: torch.Tensor, ws: Workspace) -> None:
+    buf = ws.get(workspace_bytes(OP_OUTLIERS_BY_COLUMN, d_in, d_out, n_out))
+    _check(lib().cmpq_outliers_by_column(_ptr(out_idx), _ptr(out_val), int(n_out), d_in, d_out, _ptr(centroids),
+                                         _ptr(codes), _ptr(colptr), _ptr(row_idx), _ptr(delta), _ptr(buf),
+                                         buf.numel(), _stream()),
+           "cmpq_outliers_by_column")
+
+
+def lut_matvec(X: torch.Tensor, d_out: int, bit_set: Sequence[int], counts: Sequence[int],
+               packed: Sequence[Optional[torch.Tensor]], chan_idx: Sequence[Optional[torch.Tensor]],
+               lut: Sequence[Optional[torch.Tensor]], act_idx: Optional[torch.Tensor],
+               W_act: Optional[torch.Tensor], colptr: Optional[torch.Tensor], row_idx: Optional[torch.Tensor],
+               delta: Optional[torch.Tensor], Y: torch.Tensor, ws: Workspace) -> None:
+    """Fig. 4: ``Y [m, d_out] fp32 = X [m, d_in] fp16 @ W_hat`` from the stored format."""
+    if X.dtype != torch.float16 or Y.dtype != torch.float32:
+        raise ValueError("X must be fp16 and Y fp32")
+    m, d_in, ldx = _rows(X)
+    m2, do, ldy = _rows(Y)
+    if (m2, do) != (m, d_out):
+        raise ValueError("Y must be [m, d_out]")
+    n = len(bit_set)
+    bs = (_i32 * n)(*bit_set)
+    cn = (_i64 * n)(*counts)
+    pk = (_vp * n)(*[_ptr(t) for t in packed])
+    ci = (_vp * n)(*[_ptr(t) for t in chan_idx])
+    lt = (_vp * n)(*[_ptr(t) for t in lut])
+    if row_idx is None or row_idx.numel() == 0:      # no entries of O_q: the library takes a null colptr
+        colptr = row_idx = delta = None
+    k_act = 0 if act_idx is None else int(act_idx.numel())
+    ld_act = d_out if W_act is None or k_act == 0 else _rows(W_act)[2]
+    buf = ws.get(workspace_bytes(OP_LUT_MATVEC, d_in, d_out, m))
+    _check(lib().cmpq_lut_matvec(_ptr(X), m, d_in, ldx, d_out, bs, n, cn, pk, ci, lt, _ptr(act_idx), _ptr(W_act),
+                                 k_act, ld_act, _ptr(colptr), _ptr(row_idx), _ptr(delta), _ptr(Y), ldy,
+                                 _ptr(buf), buf.numel(), _stream()),
+           "cmpq_lut_matvec")

@@ -1,0 +1,389 @@
+// The product with the deployed weight (Sec. 6 / Fig. 4 of arXiv 2410.13056): per width a
+// table-driven product of the input with the packed codes of cmpq_pack, plus the rows of
+// O_act and the entries of O_q.
+//
+//   Y[t,o] = sum_i X[t,i] * W_hat[i,o]
+//
+// The packed rows are input channels, so a row contributes X[t,i] * lut_i[code] to every
+// output: the 2^b products X[t,i] * lut_i[c] are formed once per row and the rest is table
+// look-ups and additions.  HBM bound: b/8 bytes per weight are read once per token.
+//
+//   * lut_matvec_kernel<B>: a workgroup takes 2048 outputs (a lane 32 consecutive ones:
+//     exactly B words of a row) and a slab of 128 rows of one width, 32 rows per
+//     wavefront.  The per-row tables of 4 rows at a time sit in LDS (one entry per lane
+//     to fill); a code becomes the address of its table entry with two instructions.
+//     The 16 entries of a table lie in 16 banks, so the look-ups of a wavefront never
+//     collide.  The four wavefronts' sums are added in order and written as one partial
+//     row per slab.
+//   * lut_matvec_finish_kernel: per output, the partial rows in slab order, then the O_act
+//     rows, then the column's O_q entries - every sum sequential, so the result is
+//     reproducible bit for bit.
+//   * cmpq_outliers_by_column / cmpq_gather_channels prepare O_q and O_act for this once,
+//     at quantization time.
+#include "common.h"
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kWaves = kThreads / CMPQ_WAVE;
+constexpr int kOutPerLane = 32;                        // 32 codes = B whole words
+constexpr int kTileOut = CMPQ_WAVE * kOutPerLane;      // outputs per workgroup
+constexpr int kRowsPerWave = 32;
+constexpr int kSlabRows = kWaves * kRowsPerWave;       // rows per workgroup
+constexpr int kGroup = 4;                              // rows whose tables are in LDS at once
+
+struct LmWidth {
+    const uint32_t *packed;
+    const int32_t *chan_idx;
+    const uint16_t *lut;
+    int64_t rows, words_per_row;
+    int slab0;  // index of this width's first slab among all slabs
+};
+
+// Code k of a lane's 32 codes held in w[0..B-1] (one bit-field extract, two instructions
+// where the code straddles two words).
+template <int B>
+__device__ __forceinline__ uint32_t code_at(const uint32_t (&w)[B], int k) {
+    const int bit = k * B, idx = bit >> 5, sh = bit & 31;
+    if (sh + B <= 32) return __builtin_amdgcn_ubfe(w[idx], sh, B);
+    return __builtin_amdgcn_alignbit(w[idx + 1 < B ? idx + 1 : idx], w[idx], sh) & ((1u << B) - 1u);
+}
+
+// (code << 2) + base in one instruction.  Written out because the compiler otherwise turns
+// the extract-then-shift into shift-mask-add, one instruction more per weight.
+__device__ __forceinline__ uint32_t entry_offset(uint32_t code, uint32_t base) {
+    uint32_t r;
+    asm("v_lshl_add_u32 %0, %1, 2, %2" : "=v"(r) : "v"(code), "v"(base));
+    return r;
+}
+
+template <int B>
+__global__ __launch_bounds__(kThreads) void lut_matvec_kernel(const __half *__restrict__ X, int64_t ldx,
+                                                               int64_t d_out, LmWidth wd, int n_slabs_total,
+                                                               float *__restrict__ partial) {
+    constexpr int K = 1 << B;
+    // per wavefront: two buffers of kGroup row tables (K floats each); then the four
+    // wavefronts' sums for the final addition
+    __shared__ float tbl[kWaves][2][kGroup * K];
+    __shared__ float red[kWaves][kTileOut];
+    const int lane = threadIdx.x & (CMPQ_WAVE - 1), wave = threadIdx.x / CMPQ_WAVE;
+    const int64_t token = blockIdx.z;
+    const __half *x = X + token * ldx;
+    const int64_t o0 = (int64_t)blockIdx.x * kTileOut + (int64_t)lane * kOutPerLane;
+    const int64_t word0 = (int64_t)blockIdx.x * (kTileOut / 32) * B + (int64_t)lane * B;
+    const int64_t r0 = (int64_t)blockIdx.y * kSlabRows + (int64_t)wave * kRowsPerWave;
+    const int64_t r1 = min(wd.rows, r0 + kRowsPerWave);
+    float acc[kOutPerLane];
+#pragma unroll
+    for (int k = 0; k < kOutPerLane; ++k) acc[k] = 0.f;
+
+    // entry (row g, level c) of a group's tables is filled by lane g*K + c
+    const int fill_g = lane / K, fill_c = lane % K;
+    auto table_entry = [&](int64_t r) -> float {
+        if (fill_g >= kGroup || r + fill_g >= r1) return 0.f;
+        const int64_t row = r + fill_g;
+        const float xi = __half2float(x[wd.chan_idx[row]]);
+        return xi * __half2float(__ushort_as_half(wd.lut[row * K + fill_c]));
+    };
+    // a lane's B words of a row: one vector load when they all exist
+    const bool full = word0 + B <= wd.words_per_row;
+    auto load_words = [&](int64_t r, uint32_t (&w)[kGroup][B]) {
+#pragma unroll
+        for (int g = 0; g < kGroup; ++g) {
+            const uint32_t *p = wd.packed + (r + g) * wd.words_per_row + word0;
+            if (r + g < r1 && full) {
+                typedef uint32_t WordsB __attribute__((ext_vector_type(B), aligned(4)));
+                const WordsB v = *reinterpret_cast<const WordsB *>(p);  // dword-aligned vector load
+#pragma unroll
+                for (int j = 0; j < B; ++j) w[g][j] = v[j];
+            } else {
+#pragma unroll
+                for (int j = 0; j < B; ++j) w[g][j] = (r + g < r1 && word0 + j < wd.words_per_row) ? p[j] : 0u;
+            }
+        }
+    };
+
+    if (r0 < r1) {
+        uint32_t w[kGroup][B], wn[kGroup][B];
+        float e = table_entry(r0), en = 0.f;
+        load_words(r0, w);
+        int buf = 0;
+        for (int64_t r = r0; r < r1; r += kGroup) {
+            // publish this group's tables, fetch the next group's words and table entry
+            if (kGroup * K >= CMPQ_WAVE || lane < kGroup * K) tbl[wave][buf][lane % (kGroup * K)] = e;
+            if (r + kGroup < r1) {
+                en = table_entry(r + kGroup);
+                load_words(r + kGroup, wn);
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            // byte offset of this wavefront's current buffer; code * 4 is added to it with one
+            // shift-and-add
+            const char *base = reinterpret_cast<const char *>(&tbl[0][0][0]);
+            const uint32_t wb = (uint32_t)((wave * 2 + buf) * (kGroup * K * 4));
+#pragma unroll
+            for (int g = 0; g < kGroup; ++g) {
+                // rows past the end have all-zero tables: their look-ups add 0
+#pragma unroll
+                for (int k = 0; k < kOutPerLane; ++k)
+                    acc[k] += *reinterpret_cast<const float *>(base + g * K * 4 + entry_offset(code_at<B>(w[g], k), wb));
+            }
+            __builtin_amdgcn_wave_barrier();
+            buf ^= 1;
+            e = en;
+#pragma unroll
+            for (int g = 0; g < kGroup; ++g)
+#pragma unroll
+                for (int j = 0; j < B; ++j) w[g][j] = wn[g][j];
+        }
+    }
+    // the four wavefronts' sums, added in wavefront order
+#pragma unroll
+    for (int k = 0; k < kOutPerLane; ++k) red[wave][lane * kOutPerLane + k] = acc[k];
+    __syncthreads();
+    float *prow = partial + (token * n_slabs_total + wd.slab0 + blockIdx.y) * d_out;
+    for (int c = threadIdx.x; c < kTileOut; c += kThreads) {
+        const int64_t o = (int64_t)blockIdx.x * kTileOut + c;
+        if (o < d_out) {
+            float t = red[0][c];
+#pragma unroll
+            for (int wv = 1; wv < kWaves; ++wv) t += red[wv][c];
+            prow[o] = t;
+        }
+    }
+    (void)o0;
+}
+
+__global__ __launch_bounds__(kThreads) void lut_matvec_finish_kernel(
+    const __half *__restrict__ X, int64_t ldx, int64_t d_out, const float *__restrict__ partial,
+    int n_slabs_total, const int32_t *__restrict__ act_idx, const __half *__restrict__ W_act,
+    int64_t k_act, int64_t ld_act, const int32_t *__restrict__ colptr,
+    const int32_t *__restrict__ row_idx, const float *__restrict__ delta, float *__restrict__ Y,
+    int64_t ldy) {
+    const int64_t o = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    const int64_t token = blockIdx.y;
+    if (o >= d_out) return;
+    const __half *x = X + token * ldx;
+    float y = 0.f;
+    const float *p = partial + token * n_slabs_total * d_out + o;
+    for (int sl = 0; sl < n_slabs_total; ++sl) y += p[(int64_t)sl * d_out];
+    for (int64_t j = 0; j < k_act; ++j)
+        y += __half2float(x[act_idx[j]]) * __half2float(W_act[j * ld_act + o]);
+    if (colptr) {
+        const int e1 = colptr[o + 1];
+        for (int e = colptr[o]; e < e1; ++e) y += __half2float(x[row_idx[e]]) * delta[e];
+    }
+    Y[token * ldy + o] = y;
+}
+
+template <typename TW>
+__global__ __launch_bounds__(kThreads) void gather_channels_kernel(const TW *__restrict__ W, int64_t d_out,
+                                                                    int64_t ldw,
+                                                                    const int32_t *__restrict__ act_idx,
+                                                                    uint16_t *__restrict__ W_act,
+                                                                    int64_t ld_act) {
+    const int64_t j = blockIdx.y;
+    const int64_t i = act_idx[j];
+    for (int64_t o = (int64_t)blockIdx.x * kThreads + threadIdx.x; o < d_out; o += (int64_t)gridDim.x * kThreads)
+        W_act[j * ld_act + o] = __half_as_ushort(__float2half_rn(load_as_f32<TW>(W, i * ldw + o)));
+}
+
+// ---- O_q by output column
+
+__global__ void obc_zero_kernel(int32_t *cnt, int64_t n) {
+    for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < n; t += (int64_t)gridDim.x * blockDim.x)
+        cnt[t] = 0;
+}
+
+__global__ void obc_count_kernel(const int32_t *__restrict__ out_idx, int64_t n_out, int64_t d_out,
+                                 int32_t *__restrict__ cnt) {
+    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < n_out; e += (int64_t)gridDim.x * blockDim.x)
+        atomicAdd(&cnt[out_idx[e] % d_out], 1);
+}
+
+// One workgroup: exclusive prefix of the column counts -> colptr and the scatter cursors.
+__global__ __launch_bounds__(1024) void obc_scan_kernel(const int32_t *__restrict__ cnt, int64_t d_out,
+                                                        int32_t *__restrict__ colptr,
+                                                        int32_t *__restrict__ cursor) {
+    __shared__ uint32_t scan[17];
+    uint32_t run = 0;
+    for (int64_t base = 0; base < d_out; base += 1024) {
+        const int64_t o = base + threadIdx.x;
+        const uint32_t c = o < d_out ? (uint32_t)cnt[o] : 0u;
+        uint32_t total;
+        const uint32_t before = run + block_scan_excl_u32(c, scan, &total);
+        if (o < d_out) {
+            colptr[o] = (int32_t)before;
+            cursor[o] = (int32_t)before;
+        }
+        run += total;
+    }
+    if (threadIdx.x == 0) colptr[d_out] = (int32_t)run;
+}
+
+__global__ void obc_scatter_kernel(const int32_t *__restrict__ out_idx, const uint16_t *__restrict__ out_val,
+                                   int64_t n_out, int64_t d_out, const float *__restrict__ centroids,
+                                   const uint8_t *__restrict__ codes, int32_t *__restrict__ cursor,
+                                   int32_t *__restrict__ row_idx, float *__restrict__ delta) {
+    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < n_out; e += (int64_t)gridDim.x * blockDim.x) {
+        const int32_t lin = out_idx[e];
+        const int32_t i = lin / (int32_t)d_out, o = lin % (int32_t)d_out;
+        const float level = __half2float(__float2half_rn(centroids[(int64_t)i * CMPQ_KMAX + (codes[lin] & 15)]));
+        const int32_t pos = atomicAdd(&cursor[o], 1);
+        row_idx[pos] = i;
+        delta[pos] = __half2float(__ushort_as_half(out_val[e])) - level;
+    }
+}
+
+// A thread per column: its entries arrive in any order; channels are distinct, so sorting by
+// channel (shell sort, in place) gives one well-defined order.
+__global__ void obc_sort_kernel(const int32_t *__restrict__ colptr, int64_t d_out,
+                                int32_t *__restrict__ row_idx, float *__restrict__ delta) {
+    const int64_t o = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (o >= d_out) return;
+    const int b = colptr[o], n = colptr[o + 1] - b;
+    int32_t *r = row_idx + b;
+    float *d = delta + b;
+    const int gaps[] = {1750, 701, 301, 132, 57, 23, 10, 4, 1};
+    for (int gi = 0; gi < 9; ++gi) {
+        const int gap = gaps[gi];
+        for (int i = gap; i < n; ++i) {
+            const int32_t kr = r[i];
+            const float kd = d[i];
+            int j = i;
+            while (j >= gap && r[j - gap] > kr) {
+                r[j] = r[j - gap];
+                d[j] = d[j - gap];
+                j -= gap;
+            }
+            r[j] = kr;
+            d[j] = kd;
+        }
+    }
+}
+
+int total_slabs(const int64_t *counts, int n_set) {
+    int64_t s = 0;
+    for (int j = 0; j < n_set; ++j) s += cdiv(counts[j] > 0 ? counts[j] : 0, kSlabRows);
+    return (int)s;
+}
+
+}  // namespace
+
+size_t cmpq_ws_outliers_by_column(int64_t d_out) {
+    return align_up((size_t)(d_out + 1) * sizeof(int32_t), 256) * 2;  // counts | cursors
+}
+
+// Upper bound without the per-width counts: every width may end with a partly filled slab.
+size_t cmpq_ws_lut_matvec(int64_t d_in, int64_t d_out, int64_t m) {
+    const int64_t slabs = cdiv(d_in, kSlabRows) + 4;
+    return align_up((size_t)m * (size_t)slabs * (size_t)d_out * sizeof(float), 256);
+}
+
+extern "C" int cmpq_gather_channels(const void *W, int dtype, int64_t d_in, int64_t d_out, int64_t ldw,
+                                    const int32_t *act_idx, int64_t k_act, uint16_t *W_act,
+                                    int64_t ld_act, void *stream) {
+    if (d_in < 0 || d_out < 0 || k_act < 0 || k_act > d_in) return CMPQ_EINVAL;
+    if (dtype != CMPQ_F16 && dtype != CMPQ_F32) return CMPQ_EINVAL;
+    if (k_act == 0 || d_out == 0) return CMPQ_OK;
+    if (!W || !act_idx || !W_act) return CMPQ_EINVAL;
+    if (ldw < d_out || ld_act < d_out || k_act > 65535) return CMPQ_ESHAPE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    int64_t gx = cdiv(d_out, kThreads);
+    if (gx > 64) gx = 64;
+    const dim3 grid((unsigned)gx, (unsigned)k_act);
+    if (dtype == CMPQ_F16)
+        gather_channels_kernel<__half><<<grid, kThreads, 0, s>>>(static_cast<const __half *>(W), d_out, ldw, act_idx, W_act, ld_act);
+    else
+        gather_channels_kernel<float><<<grid, kThreads, 0, s>>>(static_cast<const float *>(W), d_out, ldw, act_idx, W_act, ld_act);
+    CMPQ_LAUNCH_CHECK();
+    return CMPQ_OK;
+}
+
+extern "C" int cmpq_outliers_by_column(const int32_t *out_idx, const uint16_t *out_val, int64_t n_out,
+                                       int64_t d_in, int64_t d_out, const float *centroids,
+                                       const uint8_t *codes, int32_t *colptr, int32_t *row_idx,
+                                       float *delta, void *ws, size_t ws_bytes, void *stream) {
+    if (n_out < 0 || d_in < 0 || d_out < 0 || !colptr) return CMPQ_EINVAL;
+    if (n_out > 0 && (!out_idx || !out_val || !centroids || !codes || !row_idx || !delta)) return CMPQ_EINVAL;
+    if (d_out >= (1 << 20)) return CMPQ_ESHAPE;
+    if (d_in > 0 && d_out > ((int64_t)1 << 31) / d_in) return CMPQ_ESHAPE;
+    if (n_out > d_in * d_out) return CMPQ_ECOUNT;
+    if (!ws || reinterpret_cast<uintptr_t>(ws) % 256 != 0 || ws_bytes < cmpq_ws_outliers_by_column(d_out))
+        return CMPQ_EWORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    int32_t *cnt = static_cast<int32_t *>(ws);
+    int32_t *cursor = reinterpret_cast<int32_t *>(static_cast<char *>(ws) + cmpq_ws_outliers_by_column(d_out) / 2);
+    obc_zero_kernel<<<64, 256, 0, s>>>(cnt, d_out + 1);
+    if (n_out > 0) {
+        int64_t g = cdiv(n_out, 256);
+        if (g > 2048) g = 2048;
+        obc_count_kernel<<<(unsigned)g, 256, 0, s>>>(out_idx, n_out, d_out, cnt);
+    }
+    obc_scan_kernel<<<1, 1024, 0, s>>>(cnt, d_out, colptr, cursor);
+    if (n_out > 0 && d_out > 0) {
+        int64_t g = cdiv(n_out, 256);
+        if (g > 2048) g = 2048;
+        obc_scatter_kernel<<<(unsigned)g, 256, 0, s>>>(out_idx, out_val, n_out, d_out, centroids, codes, cursor, row_idx, delta);
+        obc_sort_kernel<<<(unsigned)cdiv(d_out, 64), 64, 0, s>>>(colptr, d_out, row_idx, delta);
+    }
+    CMPQ_LAUNCH_CHECK();
+    return CMPQ_OK;
+}
+
+extern "C" int cmpq_lut_matvec(const void *X, int64_t m, int64_t d_in, int64_t ldx, int64_t d_out,
+                               const int32_t *bit_set, int n_set, const int64_t *counts_host,
+                               const uint32_t *const *packed, const int32_t *const *chan_idx,
+                               const uint16_t *const *lut, const int32_t *act_idx,
+                               const uint16_t *W_act, int64_t k_act, int64_t ld_act,
+                               const int32_t *colptr, const int32_t *row_idx, const float *delta,
+                               float *Y, int64_t ldy, void *ws, size_t ws_bytes, void *stream) {
+    if (m < 0 || d_in < 0 || d_out < 0 || k_act < 0 || n_set < 0 || n_set > 4) return CMPQ_EINVAL;
+    if (n_set > 0 && (!bit_set || !counts_host || !packed || !chan_idx || !lut)) return CMPQ_EINVAL;
+    int64_t rows_total = k_act;
+    for (int j = 0; j < n_set; ++j) {
+        if (bit_set[j] < 1 || bit_set[j] > 4 || counts_host[j] < 0) return CMPQ_EINVAL;
+        if (counts_host[j] > 0 && (!packed[j] || !chan_idx[j] || !lut[j])) return CMPQ_EINVAL;
+        rows_total += counts_host[j];
+    }
+    if (rows_total > d_in) return CMPQ_EINVAL;
+    if (m == 0 || d_out == 0) return CMPQ_OK;
+    if (!Y || (d_in > 0 && !X)) return CMPQ_EINVAL;
+    if (k_act > 0 && (!act_idx || !W_act)) return CMPQ_EINVAL;
+    if (colptr && (!row_idx || !delta)) return CMPQ_EINVAL;
+    if (ldx < d_in || ldy < d_out || (k_act > 0 && ld_act < d_out)) return CMPQ_ESHAPE;
+    if (m > 65535 || d_out >= (1 << 20)) return CMPQ_ESHAPE;
+    const int n_slabs = total_slabs(counts_host, n_set);
+    if (!ws || reinterpret_cast<uintptr_t>(ws) % 256 != 0 || ws_bytes < cmpq_ws_lut_matvec(d_in, d_out, m))
+        return CMPQ_EWORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    float *partial = static_cast<float *>(ws);
+    const __half *Xh = static_cast<const __half *>(X);
+    int slab0 = 0;
+    for (int j = 0; j < n_set; ++j) {
+        if (counts_host[j] == 0) continue;
+        LmWidth wd;
+        wd.packed = packed[j];
+        wd.chan_idx = chan_idx[j];
+        wd.lut = lut[j];
+        wd.rows = counts_host[j];
+        wd.words_per_row = cdiv(d_out * bit_set[j], 32);
+        wd.slab0 = slab0;
+        const int slabs = (int)cdiv(wd.rows, kSlabRows);
+        if (slabs > 65535) return CMPQ_ESHAPE;
+        const dim3 grid((unsigned)cdiv(d_out, kTileOut), (unsigned)slabs, (unsigned)m);
+        switch (bit_set[j]) {
+            case 1: lut_matvec_kernel<1><<<grid, kThreads, 0, s>>>(Xh, ldx, d_out, wd, n_slabs, partial); break;
+            case 2: lut_matvec_kernel<2><<<grid, kThreads, 0, s>>>(Xh, ldx, d_out, wd, n_slabs, partial); break;
+            case 3: lut_matvec_kernel<3><<<grid, kThreads, 0, s>>>(Xh, ldx, d_out, wd, n_slabs, partial); break;
+            default: lut_matvec_kernel<4><<<grid, kThreads, 0, s>>>(Xh, ldx, d_out, wd, n_slabs, partial); break;
+        }
+        slab0 += slabs;
+    }
+    const dim3 fgrid((unsigned)cdiv(d_out, kThreads), (unsigned)m);
+    lut_matvec_finish_kernel<<<fgrid, kThreads, 0, s>>>(Xh, ldx, d_out, partial, n_slabs, act_idx,
+                                                       reinterpret_cast<const __half *>(W_act), k_act, ld_act,
+                                                       colptr, row_idx, delta, Y, ldy);
+    CMPQ_LAUNCH_CHECK();
+    return CMPQ_OK;
+}

@@ -143,6 +143,53 @@ def quantize_layer(W: torch.Tensor, sumsq: torch.Tensor, bit_set: Sequence[int],
     return res
 
 
+@dataclasses.dataclass
+class Deployed:
+    """A layer as the product kernel of Fig. 4 reads it (device tensors)."""
+    d_in: int
+    d_out: int
+    bit_set: Sequence[int]
+    counts: List[int]
+    packed: List[Optional[torch.Tensor]]
+    chan_idx: List[Optional[torch.Tensor]]
+    lut: List[Optional[torch.Tensor]]
+    act_idx: torch.Tensor             # [k_act] int32
+    W_act: torch.Tensor               # [k_act, d_out] fp16 rows of O_act
+    colptr: torch.Tensor              # [d_out+1] int32: O_q grouped by output column
+    row_idx: torch.Tensor             # [k_q] int32
+    delta: torch.Tensor               # [k_q] fp32: outlier value minus the table level it overrides
+
+
+def prepare_deployment(r: LayerResult, ws: Optional[B.Workspace] = None,
+                       timer: Optional[StageTimer] = None) -> Deployed:
+    """Sec. 6: what deployment keeps of a quantized layer - the packed streams of
+    `quantize_layer`, the FP16 rows of O_act and O_q regrouped by output column."""
+    ws = ws or B.Workspace(r.codes.device)
+    dev = r.codes.device
+    k_act, k_q = int(r.act_idx.numel()), int(r.out_idx.numel())
+    W_act = torch.empty((k_act, r.d_out), dtype=torch.float16, device=dev)
+    colptr = torch.empty(r.d_out + 1, dtype=torch.int32, device=dev)
+    row_idx = torch.empty(k_q, dtype=torch.int32, device=dev)
+    delta = torch.empty(k_q, dtype=torch.float32, device=dev)
+    with _stage(timer, "prepare_deployment"):
+        B.gather_channels(r.W_t, r.act_idx, W_act)
+        B.outliers_by_column(r.out_idx, r.out_val.view(torch.int16), k_q, r.d_in, r.d_out, r.centroids, r.codes,
+                             colptr, row_idx, delta, ws)
+    return Deployed(r.d_in, r.d_out, tuple(r.bit_set), list(r.counts), r.packed, r.chan_idx, r.lut,
+                    r.act_idx, W_act, colptr, row_idx, delta)
+
+
+def lut_matvec(dep: Deployed, X: torch.Tensor, ws: Optional[B.Workspace] = None,
+               timer: Optional[StageTimer] = None) -> torch.Tensor:
+    """Fig. 4: Y [m, d_out] fp32 = X [m, d_in] fp16 times the deployed weight."""
+    ws = ws or B.Workspace(X.device)
+    Y = torch.empty((X.shape[0], dep.d_out), dtype=torch.float32, device=X.device)
+    with _stage(timer, "lut_matvec"):
+        B.lut_matvec(X, dep.d_out, dep.bit_set, dep.counts, dep.packed, dep.chan_idx, dep.lut, dep.act_idx,
+                     dep.W_act, dep.colptr, dep.row_idx, dep.delta, Y, ws)
+    return Y
+
+
 _side_streams: Dict[tuple, list] = {}
 
 

@@ -1,0 +1,169 @@
+"""GPU-vs-oracle parity of the product with the deployed weight (Sec. 6 / Fig. 4), through
+the C ABI: cmpq_gather_channels, cmpq_outliers_by_column, cmpq_lut_matvec.
+
+Bars: the regrouped outlier structure is bit-exact (integers; deltas are differences of two
+FP16 values formed in fp32 on both sides).  The product is summed in fp32 on the GPU and in
+fp64 by the oracle: |Y - Y_ref| <= 2e-6 * sum_i |X[t,i] * W_hat[i,o]| + 1e-30 per output
+(the fp32 rounding of d_in products and additions stays far below it; one wrong, missing or
+doubled term of typical size exceeds it), and the GPU result is bit-reproducible.
+"""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda"
+
+
+@pytest.fixture(scope="module")
+def env(orc):
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2410_13056_amd import binding as B, pipeline as P, synth
+    B.lib()
+    return dict(B=B, P=P, synth=synth, ws=B.Workspace(DEV), orc=orc)
+
+
+def _np(t):
+    return t.detach().cpu().numpy()
+
+
+def _dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+def _what(W, cent, codes, bits, out_idx):
+    lut = cent.astype(np.float16).astype(np.float64)
+    what = np.take_along_axis(lut, codes.astype(np.int64), axis=1)
+    w16 = W.astype(np.float16).astype(np.float64)
+    keep = np.zeros(W.shape, bool)
+    keep[(bits < 1) | (bits > 4), :] = True
+    if out_idx is not None and len(out_idx):
+        keep.reshape(-1)[out_idx] = True
+    return np.where(keep, w16, what)
+
+
+def _check_product(Y, Yref, X, What):
+    bound = 2e-6 * (np.abs(X.astype(np.float64)) @ np.abs(What)) + 1e-30
+    err = np.abs(Y.astype(np.float64) - Yref)
+    assert (err <= bound).all(), float((err / bound).max())
+
+
+def test_gather_channels(env):
+    B = env["B"]
+    rng = np.random.default_rng(0)
+    for dtype in (np.float16, np.float32):
+        W = rng.normal(0, 1, (40, 333)).astype(dtype)
+        idx = np.array([3, 17, 39, 0], np.int32)
+        out = torch.empty((4, 333), dtype=torch.float16, device=DEV)
+        B.gather_channels(_dev(W), _dev(idx), out)
+        assert np.array_equal(_np(out), W[idx].astype(np.float16))
+    B.gather_channels(_dev(W), torch.empty(0, dtype=torch.int32, device=DEV),
+                      torch.empty((0, 333), dtype=torch.float16, device=DEV))      # nothing to do
+
+
+@pytest.mark.parametrize("d_in,d_out,n", [(7, 5, 0), (7, 5, 9), (64, 1000, 3000), (300, 4096, 20000)])
+def test_outliers_by_column(env, d_in, d_out, n):
+    B, ws = env["B"], env["ws"]
+    rng = np.random.default_rng(n)
+    cent = rng.normal(0, 0.1, (d_in, 16)).astype(np.float32)
+    codes = rng.integers(0, 16, (d_in, d_out)).astype(np.uint8)
+    idx = np.sort(rng.choice(d_in * d_out, n, replace=False)).astype(np.int32)
+    if n > 20:                                   # one crowded column: a long stretch to order
+        crowd = (np.arange(min(d_in, 40)) * d_out + 3).astype(np.int32)
+        idx = np.unique(np.concatenate([idx, crowd]))
+        n = len(idx)
+    val = rng.normal(0, 0.1, n).astype(np.float16)
+    colptr = torch.full((d_out + 1,), -1, dtype=torch.int32, device=DEV)
+    row = torch.full((max(n, 1),), -1, dtype=torch.int32, device=DEV)
+    delta = torch.zeros(max(n, 1), dtype=torch.float32, device=DEV)
+    B.outliers_by_column(_dev(idx) if n else None, _dev(val) if n else None, n, d_in, d_out, _dev(cent), _dev(codes),
+                         colptr, row, delta, ws)
+    i, o = idx // d_out, idx % d_out
+    order = np.lexsort((i, o))                   # by column, then channel
+    want_ptr = np.concatenate([[0], np.cumsum(np.bincount(o, minlength=d_out))]).astype(np.int32)
+    level = cent.astype(np.float16)[i, codes[i, o]].astype(np.float32)
+    want_delta = (val.astype(np.float32) - level)[order]
+    assert np.array_equal(_np(colptr), want_ptr)
+    assert np.array_equal(_np(row)[:n], i[order].astype(np.int32))
+    assert np.array_equal(_np(delta)[:n], want_delta)
+
+
+@pytest.mark.parametrize("bit_set,avg,d_in,d_out", [((1, 2), 1.5, 96, 50), ((2, 3, 4), 3.0, 300, 2048 + 40),
+                                                    ((3, 4), 3.5, 520, 4096 + 8), ((1, 2, 3, 4), 2.5, 260, 33),
+                                                    ((2, 3, 4), 3.3, 1100, 2000)])
+def test_lut_matvec_parity_end_to_end(env, bit_set, avg, d_in, d_out):
+    """Quantize with the library (checked against the oracle elsewhere), deploy, multiply;
+    the oracle multiplies with the weight rebuilt from W, levels, codes and outlier indices."""
+    B, P, ws, orc = env["B"], env["P"], env["ws"], env["orc"]
+    rng = np.random.default_rng(d_in + d_out)
+    W = rng.normal(0, 0.02, (d_in, d_out))
+    W[rng.random(W.shape) < 0.01] *= 10
+    W = W.astype(np.float16)
+    Xcal = (rng.normal(0, 1, (256, d_in)) * np.exp(rng.normal(0, 0.5, d_in))).astype(np.float16)
+    _, sumsq = P.activation_stats(_dev(Xcal), ws)
+    r = P.quantize_layer(_dev(W), sumsq, bit_set, avg, rho_act_ppm=20000, rho_q_ppm=10000, iters=5, ws=ws,
+                         transposed=True)
+    dep = P.prepare_deployment(r, ws)
+    bits, cent, codes, out_idx = _np(r.bits), _np(r.centroids), _np(r.codes), _np(r.out_idx).astype(np.int64)
+    What = _what(W, cent, codes, bits, out_idx)
+    for m in (1, 3):
+        X = rng.normal(0, 1, (m, d_in)).astype(np.float16)
+        Y = _np(P.lut_matvec(dep, _dev(X), ws))
+        Yref = orc.lut_matvec(X, W, cent, codes, bits, out_idx)
+        assert np.allclose(Yref, X.astype(np.float64) @ What, rtol=1e-12, atol=1e-12)
+        _check_product(Y, Yref, X, What)
+        assert np.array_equal(Y, _np(P.lut_matvec(dep, _dev(X), ws)))          # reproducible
+    # a strided input and output
+    Xw = torch.zeros((2, d_in + 8), dtype=torch.float16, device=DEV)
+    Xw[:, :d_in] = _dev(X[:2] if m >= 2 else np.repeat(X, 2, 0))
+    Yw = torch.full((2, d_out + 5), 7.0, dtype=torch.float32, device=DEV)
+    B.lut_matvec(Xw[:, :d_in], d_out, dep.bit_set, dep.counts, dep.packed, dep.chan_idx, dep.lut, dep.act_idx,
+                 dep.W_act, dep.colptr, dep.row_idx, dep.delta, Yw[:, :d_out], ws)
+    assert np.array_equal(_np(Yw[:, :d_out]), Y[:2]) and (_np(Yw[:, d_out:]) == 7.0).all()
+
+
+def test_lut_matvec_without_outliers_and_all_protected(env):
+    B, P, ws, orc = env["B"], env["P"], env["ws"], env["orc"]
+    rng = np.random.default_rng(3)
+    d_in, d_out = 150, 700
+    W = rng.normal(0, 0.05, (d_in, d_out)).astype(np.float16)
+    X = rng.normal(0, 1, (2, d_in)).astype(np.float16)
+    sumsq = _dev(rng.random(d_in).astype(np.float32) + 0.1)
+    # no outliers of either kind
+    r = P.quantize_layer(_dev(W), sumsq, (2, 3), 2.5, rho_act_ppm=0, rho_q_ppm=0, iters=3, ws=ws, transposed=True)
+    dep = P.prepare_deployment(r, ws)
+    assert dep.act_idx.numel() == 0 and dep.row_idx.numel() == 0
+    What = _what(W, _np(r.centroids), _np(r.codes), _np(r.bits), None)
+    Y = _np(P.lut_matvec(dep, _dev(X), ws))
+    _check_product(Y, X.astype(np.float64) @ What, X, What)
+    # every channel protected: the plain FP16 product
+    idx = torch.arange(d_in, dtype=torch.int32, device=DEV)
+    W_act = torch.empty((d_in, d_out), dtype=torch.float16, device=DEV)
+    B.gather_channels(_dev(W), idx, W_act)
+    Y = torch.empty((2, d_out), dtype=torch.float32, device=DEV)
+    B.lut_matvec(_dev(X), d_out, (2, 3), (0, 0), [None, None], [None, None], [None, None], idx, W_act,
+                 None, None, None, Y, ws)
+    Wd = W.astype(np.float64)
+    _check_product(_np(Y), X.astype(np.float64) @ Wd, X, Wd)
+
+
+def test_lut_matvec_full_size_layer(env):
+    """down_proj of the 70B-shaped block at full size, one token: every output against the oracle."""
+    P, synth, ws, orc = env["P"], env["synth"], env["ws"], env["orc"]
+    wl = synth.workload("block70b")
+    layer = next(l for l in wl.layers if l.name == "down_proj")
+    W = synth.make_weight(layer.d_out, layer.d_in, "f16", 11, DEV)          # [d_out, d_in] as a framework keeps it
+    g = torch.Generator(device="cpu")
+    g.manual_seed(5)
+    sumsq = (torch.rand(layer.d_in, generator=g) + 0.05).to(DEV)
+    r = P.quantize_layer(W, sumsq, wl.bit_set, wl.avg_bits, wl.rho_act_ppm, wl.rho_q_ppm, 3, ws)
+    dep = P.prepare_deployment(r, ws)
+    X = torch.randn((1, layer.d_in), generator=g).to(torch.float16).to(DEV)
+    Y = _np(P.lut_matvec(dep, X, ws))
+    Wt, cent, codes, bits = _np(r.W_t), _np(r.centroids), _np(r.codes), _np(r.bits)
+    out_idx = _np(r.out_idx).astype(np.int64)
+    Yref = orc.lut_matvec(_np(X), Wt, cent, codes, bits, out_idx)
+    What = _what(Wt, cent, codes, bits, out_idx)
+    _check_product(Y, Yref, _np(X), What)
