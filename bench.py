@@ -63,6 +63,34 @@ def cpu_baseline(wl, weights, acts):
                       f"whole path incl. both k-means passes"}
 
 
+def deployed_matvec(P, B, torch, out, layers, wl, acts, reps):
+    """The consumer of the stored format: one token through the 7 products of the block just
+    quantized (Sec. 6 / Fig. 4).  HBM bound: the packed codes are read once per token."""
+    dev = next(iter(out.values())).codes.device
+    ws = B.Workspace(dev)
+    deps = {name: P.prepare_deployment(out[name], ws) for name, _ in layers}
+    xs = {name: acts[x_key][:1].contiguous() for name, x_key in layers}
+    algo_bytes = 0
+    for name, _ in layers:
+        d = deps[name]
+        algo_bytes += sum(t.numel() * t.element_size() for t in d.packed + d.lut + d.chan_idx if t is not None)
+        algo_bytes += d.W_act.numel() * 2 + d.row_idx.numel() * 8 + d.colptr.numel() * 4 + d.d_in * 2 + d.d_out * 4
+    for name, _ in layers:
+        P.lut_matvec(deps[name], xs[name], ws)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        for name, _ in layers:
+            P.lut_matvec(deps[name], xs[name], ws)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / reps
+    return {"what": "Y = x W_hat for one token through all layers of the block, from the stored format",
+            "ms_per_token": dt * 1e3, "Gweights_per_s": wl.params / dt / 1e9,
+            "roofline": {"bound": "hbm", "achieved": algo_bytes / dt / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                         "frac": algo_bytes / dt / 1e9 / HBM_PEAK_GBS,
+                         "algorithmic_bytes_per_token": algo_bytes}}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -76,6 +104,9 @@ def main():
     ap.add_argument("--serial-steps", type=int, default=2,
                     help="extra untimed steps on one stream for the per-stage and per-kernel figures "
                          "that overlap would blur (0: skip)")
+    ap.add_argument("--deploy-reps", type=int, default=20,
+                    help="repetitions of the one-token product with the deployed block (Fig. 4), reported "
+                         "beside the headline figure; 0: skip")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (outside the timed region): under "
                          "rocprofv3 --pmc it gives the HBM counters a kernel of known traffic to scale by")
@@ -174,6 +205,8 @@ def main():
             "kmeans_avg_launch_ms": ms1 / n1,
             "kmeans_frac_of_alu_peak": flops / launches_per_step / (ms1 / 1e3 / n1) / 1e12 / ALU_PEAK_TFLOPS,
         }
+    if args.deploy_reps > 0:
+        line["deployed_matvec"] = deployed_matvec(P, B, torch, out, layers, wl, acts, args.deploy_reps)
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(wl, weights, acts)
     print(json.dumps(line))

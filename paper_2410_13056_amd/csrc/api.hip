@@ -10,7 +10,7 @@ size_t cmpq_ws_outlier_weights(int64_t d_in, int64_t d_out, int64_t k);
 size_t cmpq_ws_kmeans(int64_t d_in, int64_t d_out);
 size_t cmpq_ws_pack(int64_t d_in);
 size_t cmpq_ws_dequant_error(int64_t d_in);
-size_t cmpq_ws_outliers_by_column(int64_t d_out);
+size_t cmpq_ws_outliers_by_column(int64_t d_out, int64_t n_out);
 size_t cmpq_ws_lut_matvec(int64_t d_in, int64_t d_out, int64_t m);
 
 extern "C" size_t cmpq_workspace_bytes(int op, int64_t d_in, int64_t d_out, int64_t n) {
@@ -23,7 +23,7 @@ extern "C" size_t cmpq_workspace_bytes(int op, int64_t d_in, int64_t d_out, int6
         case CMPQ_OP_KMEANS: return cmpq_ws_kmeans(d_in, d_out);
         case CMPQ_OP_PACK: return cmpq_ws_pack(d_in);
         case CMPQ_OP_DEQUANT_ERROR: return cmpq_ws_dequant_error(d_in);
-        case CMPQ_OP_OUTLIERS_BY_COLUMN: return cmpq_ws_outliers_by_column(d_out);
+        case CMPQ_OP_OUTLIERS_BY_COLUMN: return cmpq_ws_outliers_by_column(d_out, n);
         case CMPQ_OP_LUT_MATVEC: return cmpq_ws_lut_matvec(d_in, d_out, n);
         default: return 0;
     }

@@ -28,9 +28,9 @@ constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / CMPQ_WAVE;
 constexpr int kOutPerLane = 32;                        // 32 codes = B whole words
 constexpr int kTileOut = CMPQ_WAVE * kOutPerLane;      // outputs per workgroup
-constexpr int kRowsPerWave = 32;
-constexpr int kSlabRows = kWaves * kRowsPerWave;       // rows per workgroup
+constexpr int kMaxRowsPerWave = 32;                    // a workgroup's slab: 4 wavefronts x 8, 16 or 32 rows
 constexpr int kGroup = 4;                              // rows whose tables are in LDS at once
+constexpr int kMaxWidths = 4;
 
 struct LmWidth {
     const uint32_t *packed;
@@ -38,6 +38,12 @@ struct LmWidth {
     const uint16_t *lut;
     int64_t rows, words_per_row;
     int slab0;  // index of this width's first slab among all slabs
+    int bits;
+};
+
+struct LmArgs {
+    LmWidth w[kMaxWidths];
+    int n_widths, rows_per_wave, n_slabs_total;
 };
 
 // Code k of a lane's 32 codes held in w[0..B-1] (one bit-field extract, two instructions
@@ -58,21 +64,20 @@ __device__ __forceinline__ uint32_t entry_offset(uint32_t code, uint32_t base) {
 }
 
 template <int B>
-__global__ __launch_bounds__(kThreads) void lut_matvec_kernel(const __half *__restrict__ X, int64_t ldx,
-                                                               int64_t d_out, LmWidth wd, int n_slabs_total,
-                                                               float *__restrict__ partial) {
+__device__ __forceinline__ void lut_slab(const __half *__restrict__ X, int64_t ldx, int64_t d_out,
+                                         const LmWidth &wd, int slab, int rows_per_wave, int n_slabs_total,
+                                         float *__restrict__ partial, float (*tbl_all)[2][kGroup * 16],
+                                         float (*red)[kTileOut]) {
     constexpr int K = 1 << B;
-    // per wavefront: two buffers of kGroup row tables (K floats each); then the four
-    // wavefronts' sums for the final addition
-    __shared__ float tbl[kWaves][2][kGroup * K];
-    __shared__ float red[kWaves][kTileOut];
+    // per wavefront: two buffers of kGroup row tables (K floats each)
+    float(*tbl)[2][kGroup * 16] = tbl_all;
     const int lane = threadIdx.x & (CMPQ_WAVE - 1), wave = threadIdx.x / CMPQ_WAVE;
     const int64_t token = blockIdx.z;
     const __half *x = X + token * ldx;
     const int64_t o0 = (int64_t)blockIdx.x * kTileOut + (int64_t)lane * kOutPerLane;
     const int64_t word0 = (int64_t)blockIdx.x * (kTileOut / 32) * B + (int64_t)lane * B;
-    const int64_t r0 = (int64_t)blockIdx.y * kSlabRows + (int64_t)wave * kRowsPerWave;
-    const int64_t r1 = min(wd.rows, r0 + kRowsPerWave);
+    const int64_t r0 = ((int64_t)slab * kWaves + wave) * rows_per_wave;
+    const int64_t r1 = min(wd.rows, r0 + rows_per_wave);
     float acc[kOutPerLane];
 #pragma unroll
     for (int k = 0; k < kOutPerLane; ++k) acc[k] = 0.f;
@@ -120,7 +125,7 @@ __global__ __launch_bounds__(kThreads) void lut_matvec_kernel(const __half *__re
             // byte offset of this wavefront's current buffer; code * 4 is added to it with one
             // shift-and-add
             const char *base = reinterpret_cast<const char *>(&tbl[0][0][0]);
-            const uint32_t wb = (uint32_t)((wave * 2 + buf) * (kGroup * K * 4));
+            const uint32_t wb = (uint32_t)((wave * 2 + buf) * (kGroup * 16 * 4));
 #pragma unroll
             for (int g = 0; g < kGroup; ++g) {
                 // rows past the end have all-zero tables: their look-ups add 0
@@ -141,7 +146,7 @@ __global__ __launch_bounds__(kThreads) void lut_matvec_kernel(const __half *__re
 #pragma unroll
     for (int k = 0; k < kOutPerLane; ++k) red[wave][lane * kOutPerLane + k] = acc[k];
     __syncthreads();
-    float *prow = partial + (token * n_slabs_total + wd.slab0 + blockIdx.y) * d_out;
+    float *prow = partial + (token * n_slabs_total + wd.slab0 + slab) * d_out;
     for (int c = threadIdx.x; c < kTileOut; c += kThreads) {
         const int64_t o = (int64_t)blockIdx.x * kTileOut + c;
         if (o < d_out) {
@@ -154,26 +159,71 @@ __global__ __launch_bounds__(kThreads) void lut_matvec_kernel(const __half *__re
     (void)o0;
 }
 
-__global__ __launch_bounds__(kThreads) void lut_matvec_finish_kernel(
+// grid: (tiles of 2048 outputs, slabs of all widths one after the other, tokens)
+__global__ __launch_bounds__(kThreads) void lut_matvec_kernel(const __half *__restrict__ X, int64_t ldx,
+                                                               int64_t d_out, LmArgs a,
+                                                               float *__restrict__ partial) {
+    __shared__ float tbl[kWaves][2][kGroup * 16];
+    __shared__ float red[kWaves][kTileOut];
+    int j = 0;
+    while (j + 1 < a.n_widths && (int)blockIdx.y >= a.w[j + 1].slab0) ++j;
+    const LmWidth &wd = a.w[j];
+    const int slab = (int)blockIdx.y - wd.slab0;
+    switch (wd.bits) {
+        case 1: lut_slab<1>(X, ldx, d_out, wd, slab, a.rows_per_wave, a.n_slabs_total, partial, tbl, red); break;
+        case 2: lut_slab<2>(X, ldx, d_out, wd, slab, a.rows_per_wave, a.n_slabs_total, partial, tbl, red); break;
+        case 3: lut_slab<3>(X, ldx, d_out, wd, slab, a.rows_per_wave, a.n_slabs_total, partial, tbl, red); break;
+        default: lut_slab<4>(X, ldx, d_out, wd, slab, a.rows_per_wave, a.n_slabs_total, partial, tbl, red); break;
+    }
+}
+
+constexpr int kFinWaves = 16;  // parts a column's sum is shared out over
+constexpr int kFinThreads = kFinWaves * CMPQ_WAVE;
+
+// 64 consecutive outputs per workgroup.  Wavefront w adds the slabs and O_act rows whose
+// index is w modulo 16 (a lane per output: whole cache lines), and takes 4 of the 64
+// columns of O_q, 16 lanes per column (lane l the entries l, l+16, ...).  All partial sums
+// meet in LDS and are added in a fixed order.
+__global__ __launch_bounds__(kFinThreads) void lut_matvec_finish_kernel(
     const __half *__restrict__ X, int64_t ldx, int64_t d_out, const float *__restrict__ partial,
     int n_slabs_total, const int32_t *__restrict__ act_idx, const __half *__restrict__ W_act,
     int64_t k_act, int64_t ld_act, const int32_t *__restrict__ colptr,
     const int32_t *__restrict__ row_idx, const float *__restrict__ delta, float *__restrict__ Y,
     int64_t ldy) {
-    const int64_t o = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    __shared__ float dense[kFinWaves][CMPQ_WAVE];
+    __shared__ float sparse[CMPQ_WAVE][17];
+    const int lane = threadIdx.x & (CMPQ_WAVE - 1), wave = threadIdx.x / CMPQ_WAVE;
     const int64_t token = blockIdx.y;
-    if (o >= d_out) return;
+    const int64_t o = (int64_t)blockIdx.x * CMPQ_WAVE + lane;
     const __half *x = X + token * ldx;
     float y = 0.f;
-    const float *p = partial + token * n_slabs_total * d_out + o;
-    for (int sl = 0; sl < n_slabs_total; ++sl) y += p[(int64_t)sl * d_out];
-    for (int64_t j = 0; j < k_act; ++j)
-        y += __half2float(x[act_idx[j]]) * __half2float(W_act[j * ld_act + o]);
-    if (colptr) {
-        const int e1 = colptr[o + 1];
-        for (int e = colptr[o]; e < e1; ++e) y += __half2float(x[row_idx[e]]) * delta[e];
+    if (o < d_out) {
+        const float *p = partial + token * n_slabs_total * d_out + o;
+        for (int sl = wave; sl < n_slabs_total; sl += kFinWaves) y += p[(int64_t)sl * d_out];
+        for (int64_t j = wave; j < k_act; j += kFinWaves)
+            y += __half2float(x[act_idx[j]]) * __half2float(W_act[j * ld_act + o]);
     }
-    Y[token * ldy + o] = y;
+    dense[wave][lane] = y;
+    {
+        const int col = wave * 4 + (lane >> 4), slot = lane & 15;
+        const int64_t oc = (int64_t)blockIdx.x * CMPQ_WAVE + col;
+        float t = 0.f;
+        if (colptr && oc < d_out) {
+            const int e1 = colptr[oc + 1];
+            for (int e = colptr[oc] + slot; e < e1; e += 16) t += __half2float(x[row_idx[e]]) * delta[e];
+        }
+        sparse[col][slot] = t;
+    }
+    __syncthreads();
+    if (wave == 0 && o < d_out) {
+        float t = 0.f;
+#pragma unroll
+        for (int w = 0; w < kFinWaves; ++w) t += dense[w][lane];
+        float u = 0.f;
+#pragma unroll
+        for (int sidx = 0; sidx < 16; ++sidx) u += sparse[lane][sidx];
+        Y[token * ldy + o] = t + u;
+    }
 }
 
 template <typename TW>
@@ -235,18 +285,44 @@ __global__ void obc_scatter_kernel(const int32_t *__restrict__ out_idx, const ui
     }
 }
 
-// A thread per column: its entries arrive in any order; channels are distinct, so sorting by
-// channel (shell sort, in place) gives one well-defined order.
-__global__ void obc_sort_kernel(const int32_t *__restrict__ colptr, int64_t d_out,
-                                int32_t *__restrict__ row_idx, float *__restrict__ delta) {
-    const int64_t o = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+// The scatter leaves a column's entries in any order.  Channels are distinct inside a
+// column, so ordering by channel gives one well-defined result.  A wavefront per column:
+// an entry's final place is the number of entries of the column with a smaller channel
+// (every lane walks the whole column; columns hold a few hundred entries).  A column longer
+// than kRankLimit is ordered by one lane with a shell sort instead.
+constexpr int kRankLimit = 2048;
+
+__global__ __launch_bounds__(kThreads) void obc_order_kernel(const int32_t *__restrict__ colptr, int64_t d_out,
+                                                              const int32_t *__restrict__ tmp_row,
+                                                              const float *__restrict__ tmp_delta,
+                                                              int32_t *__restrict__ row_idx,
+                                                              float *__restrict__ delta) {
+    const int lane = threadIdx.x & (CMPQ_WAVE - 1), wave = threadIdx.x / CMPQ_WAVE;
+    const int64_t o = (int64_t)blockIdx.x * kWaves + wave;
     if (o >= d_out) return;
     const int b = colptr[o], n = colptr[o + 1] - b;
+    if (n <= kRankLimit) {
+        for (int e = lane; e < n; e += CMPQ_WAVE) {
+            const int32_t mine = tmp_row[b + e];
+            int rank = 0;
+            for (int f = 0; f < n; ++f) rank += tmp_row[b + f] < mine;
+            row_idx[b + rank] = mine;
+            delta[b + rank] = tmp_delta[b + e];
+        }
+        return;
+    }
+    for (int e = lane; e < n; e += CMPQ_WAVE) {
+        row_idx[b + e] = tmp_row[b + e];
+        delta[b + e] = tmp_delta[b + e];
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    if (lane != 0) return;
     int32_t *r = row_idx + b;
     float *d = delta + b;
-    const int gaps[] = {1750, 701, 301, 132, 57, 23, 10, 4, 1};
-    for (int gi = 0; gi < 9; ++gi) {
-        const int gap = gaps[gi];
+    int gap = 1;
+    while (gap < n / 3) gap = 3 * gap + 1;
+    for (; gap >= 1; gap /= 3) {
         for (int i = gap; i < n; ++i) {
             const int32_t kr = r[i];
             const float kd = d[i];
@@ -262,21 +338,22 @@ __global__ void obc_sort_kernel(const int32_t *__restrict__ colptr, int64_t d_ou
     }
 }
 
-int total_slabs(const int64_t *counts, int n_set) {
+int64_t total_slabs(const int64_t *counts, int n_set, int rows_per_wave) {
     int64_t s = 0;
-    for (int j = 0; j < n_set; ++j) s += cdiv(counts[j] > 0 ? counts[j] : 0, kSlabRows);
-    return (int)s;
+    for (int j = 0; j < n_set; ++j) s += cdiv(counts[j] > 0 ? counts[j] : 0, (int64_t)kWaves * rows_per_wave);
+    return s;
 }
 
 }  // namespace
 
-size_t cmpq_ws_outliers_by_column(int64_t d_out) {
-    return align_up((size_t)(d_out + 1) * sizeof(int32_t), 256) * 2;  // counts | cursors
+// counts | cursors | channel and delta of every entry in scatter order
+size_t cmpq_ws_outliers_by_column(int64_t d_out, int64_t n_out) {
+    return align_up((size_t)(d_out + 1) * sizeof(int32_t), 256) * 2 + align_up((size_t)n_out * 4, 256) * 2;
 }
 
 // Upper bound without the per-width counts: every width may end with a partly filled slab.
 size_t cmpq_ws_lut_matvec(int64_t d_in, int64_t d_out, int64_t m) {
-    const int64_t slabs = cdiv(d_in, kSlabRows) + 4;
+    const int64_t slabs = cdiv(d_in, (int64_t)kWaves * 8) + kMaxWidths;  // the smallest slabs, one partly filled per width
     return align_up((size_t)m * (size_t)slabs * (size_t)d_out * sizeof(float), 256);
 }
 
@@ -309,11 +386,14 @@ extern "C" int cmpq_outliers_by_column(const int32_t *out_idx, const uint16_t *o
     if (d_out >= (1 << 20)) return CMPQ_ESHAPE;
     if (d_in > 0 && d_out > ((int64_t)1 << 31) / d_in) return CMPQ_ESHAPE;
     if (n_out > d_in * d_out) return CMPQ_ECOUNT;
-    if (!ws || reinterpret_cast<uintptr_t>(ws) % 256 != 0 || ws_bytes < cmpq_ws_outliers_by_column(d_out))
+    if (!ws || reinterpret_cast<uintptr_t>(ws) % 256 != 0 || ws_bytes < cmpq_ws_outliers_by_column(d_out, n_out))
         return CMPQ_EWORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
     int32_t *cnt = static_cast<int32_t *>(ws);
-    int32_t *cursor = reinterpret_cast<int32_t *>(static_cast<char *>(ws) + cmpq_ws_outliers_by_column(d_out) / 2);
+    const size_t col_bytes = align_up((size_t)(d_out + 1) * sizeof(int32_t), 256);
+    int32_t *cursor = reinterpret_cast<int32_t *>(static_cast<char *>(ws) + col_bytes);
+    int32_t *tmp_row = reinterpret_cast<int32_t *>(static_cast<char *>(ws) + 2 * col_bytes);
+    float *tmp_delta = reinterpret_cast<float *>(static_cast<char *>(ws) + 2 * col_bytes + align_up((size_t)n_out * 4, 256));
     obc_zero_kernel<<<64, 256, 0, s>>>(cnt, d_out + 1);
     if (n_out > 0) {
         int64_t g = cdiv(n_out, 256);
@@ -324,8 +404,8 @@ extern "C" int cmpq_outliers_by_column(const int32_t *out_idx, const uint16_t *o
     if (n_out > 0 && d_out > 0) {
         int64_t g = cdiv(n_out, 256);
         if (g > 2048) g = 2048;
-        obc_scatter_kernel<<<(unsigned)g, 256, 0, s>>>(out_idx, out_val, n_out, d_out, centroids, codes, cursor, row_idx, delta);
-        obc_sort_kernel<<<(unsigned)cdiv(d_out, 64), 64, 0, s>>>(colptr, d_out, row_idx, delta);
+        obc_scatter_kernel<<<(unsigned)g, 256, 0, s>>>(out_idx, out_val, n_out, d_out, centroids, codes, cursor, tmp_row, tmp_delta);
+        obc_order_kernel<<<(unsigned)cdiv(d_out, kWaves), kThreads, 0, s>>>(colptr, d_out, tmp_row, tmp_delta, row_idx, delta);
     }
     CMPQ_LAUNCH_CHECK();
     return CMPQ_OK;
@@ -353,35 +433,41 @@ extern "C" int cmpq_lut_matvec(const void *X, int64_t m, int64_t d_in, int64_t l
     if (colptr && (!row_idx || !delta)) return CMPQ_EINVAL;
     if (ldx < d_in || ldy < d_out || (k_act > 0 && ld_act < d_out)) return CMPQ_ESHAPE;
     if (m > 65535 || d_out >= (1 << 20)) return CMPQ_ESHAPE;
-    const int n_slabs = total_slabs(counts_host, n_set);
+    // rows per wavefront: the largest of 32, 16, 8 that still gives about a thousand workgroups
+    const int64_t tiles = cdiv(d_out, kTileOut);
+    int rpw = kMaxRowsPerWave;
+    while (rpw > 8 && tiles * total_slabs(counts_host, n_set, rpw) * m < 1024) rpw /= 2;
+    const int64_t n_slabs64 = total_slabs(counts_host, n_set, rpw);
+    if (n_slabs64 > 65535) return CMPQ_ESHAPE;
+    const int n_slabs = (int)n_slabs64;
     if (!ws || reinterpret_cast<uintptr_t>(ws) % 256 != 0 || ws_bytes < cmpq_ws_lut_matvec(d_in, d_out, m))
         return CMPQ_EWORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
     float *partial = static_cast<float *>(ws);
     const __half *Xh = static_cast<const __half *>(X);
+    LmArgs a;
+    a.n_widths = 0;
+    a.rows_per_wave = rpw;
+    a.n_slabs_total = n_slabs;
     int slab0 = 0;
     for (int j = 0; j < n_set; ++j) {
         if (counts_host[j] == 0) continue;
-        LmWidth wd;
+        LmWidth &wd = a.w[a.n_widths++];
         wd.packed = packed[j];
         wd.chan_idx = chan_idx[j];
         wd.lut = lut[j];
         wd.rows = counts_host[j];
         wd.words_per_row = cdiv(d_out * bit_set[j], 32);
         wd.slab0 = slab0;
-        const int slabs = (int)cdiv(wd.rows, kSlabRows);
-        if (slabs > 65535) return CMPQ_ESHAPE;
-        const dim3 grid((unsigned)cdiv(d_out, kTileOut), (unsigned)slabs, (unsigned)m);
-        switch (bit_set[j]) {
-            case 1: lut_matvec_kernel<1><<<grid, kThreads, 0, s>>>(Xh, ldx, d_out, wd, n_slabs, partial); break;
-            case 2: lut_matvec_kernel<2><<<grid, kThreads, 0, s>>>(Xh, ldx, d_out, wd, n_slabs, partial); break;
-            case 3: lut_matvec_kernel<3><<<grid, kThreads, 0, s>>>(Xh, ldx, d_out, wd, n_slabs, partial); break;
-            default: lut_matvec_kernel<4><<<grid, kThreads, 0, s>>>(Xh, ldx, d_out, wd, n_slabs, partial); break;
-        }
-        slab0 += slabs;
+        wd.bits = bit_set[j];
+        slab0 += (int)cdiv(wd.rows, (int64_t)kWaves * rpw);
     }
-    const dim3 fgrid((unsigned)cdiv(d_out, kThreads), (unsigned)m);
-    lut_matvec_finish_kernel<<<fgrid, kThreads, 0, s>>>(Xh, ldx, d_out, partial, n_slabs, act_idx,
+    if (a.n_widths > 0) {
+        const dim3 grid((unsigned)tiles, (unsigned)n_slabs, (unsigned)m);
+        lut_matvec_kernel<<<grid, kThreads, 0, s>>>(Xh, ldx, d_out, a, partial);
+    }
+    const dim3 fgrid((unsigned)cdiv(d_out, CMPQ_WAVE), (unsigned)m);
+    lut_matvec_finish_kernel<<<fgrid, kFinThreads, 0, s>>>(Xh, ldx, d_out, partial, n_slabs, act_idx,
                                                        reinterpret_cast<const __half *>(W_act), k_act, ld_act,
                                                        colptr, row_idx, delta, Y, ldy);
     CMPQ_LAUNCH_CHECK();
