@@ -100,6 +100,29 @@ def test_host_side_argument_errors(L):
     assert L.cmpq_pack(fake, 4, 64, fake, fake, bs, 3, cnt2, ptrs, ptrs, ptrs, None, 0, None) == -5
     assert L.cmpq_dequant_error(fake, 0, 4, 64, 64, fake, fake, fake, None, 0, None, None, fake, fake, 256, None) == -1
     assert L.cmpq_dequant_error(fake, 0, 4, 64, 8, fake, fake, fake, None, 0, None, fake, fake, fake, 256, None) == -2
+    # the deployed product
+    assert L.cmpq_gather_channels(fake, 0, 8, 64, 64, None, 2, fake, 64, None) == -1
+    assert L.cmpq_gather_channels(fake, 0, 8, 64, 64, fake, 9, fake, 64, None) == -1            # more rows than channels
+    assert L.cmpq_gather_channels(fake, 0, 8, 64, 32, fake, 2, fake, 64, None) == -2
+    assert L.cmpq_outliers_by_column(fake, fake, 4, 8, 64, fake, fake, None, fake, fake, fake, 1 << 20, None) == -1
+    assert L.cmpq_outliers_by_column(fake, fake, 4, 8, 64, fake, fake, fake, fake, fake, None, 0, None) == -5
+    assert L.cmpq_outliers_by_column(fake, fake, 4, 8, 1 << 20, fake, fake, fake, fake, fake, fake, 1 << 30, None) == -2
+    assert L.cmpq_outliers_by_column(fake, fake, 600, 8, 64, fake, fake, fake, fake, fake, fake, 1 << 20, None) == -4
+    one = (i64 * 3)(1, 1, 2)
+    assert L.cmpq_lut_matvec(fake, 1, 8, 8, 64, bs, 3, one, ptrs, ptrs, ptrs, None, None, 0, 64, None, None, None,
+                             None, 64, fake, 1 << 20, None) == -1                              # no output
+    assert L.cmpq_lut_matvec(fake, 1, 8, 4, 64, bs, 3, one, ptrs, ptrs, ptrs, None, None, 0, 64, None, None, None,
+                             fake, 64, fake, 1 << 20, None) == -2                              # ldx < d_in
+    assert L.cmpq_lut_matvec(fake, 1, 8, 8, 64, bs, 3, (i64 * 3)(4, 4, 4), ptrs, ptrs, ptrs, None, None, 0, 64, None,
+                             None, None, fake, 64, fake, 1 << 20, None) == -1                  # more rows than channels
+    assert L.cmpq_lut_matvec(fake, 1, 8, 8, 64, (i32 * 1)(5), 1, (i64 * 1)(1), ptrs, ptrs, ptrs, None, None, 0, 64, None,
+                             None, None, fake, 64, fake, 1 << 20, None) == -1                  # width outside 1..4
+    assert L.cmpq_lut_matvec(fake, 1, 8, 8, 64, bs, 3, one, ptrs, ptrs, ptrs, None, None, 0, 64, fake, None, None,
+                             fake, 64, fake, 1 << 20, None) == -1                              # colptr without entries
+    assert L.cmpq_lut_matvec(fake, 1, 8, 8, 64, bs, 3, one, ptrs, ptrs, ptrs, None, None, 0, 64, None, None, None,
+                             fake, 64, None, 0, None) == -5
+    assert L.cmpq_lut_matvec(fake, 70000, 8, 8, 64, bs, 3, one, ptrs, ptrs, ptrs, None, None, 0, 64, None, None, None,
+                             fake, 64, fake, 1 << 40, None) == -2                              # too many tokens
 
 
 def test_product_package_does_not_reach_the_oracle():
