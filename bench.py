@@ -69,7 +69,7 @@ def deployed_matvec(P, B, torch, out, layers, wl, acts, reps):
     dev = next(iter(out.values())).codes.device
     ws = B.Workspace(dev)
     deps = {name: P.prepare_deployment(out[name], ws) for name, _ in layers}
-    xs = {name: acts[x_key][:1].contiguous() for name, x_key in layers}
+    xs = {name: acts[x_key][:1].to(torch.float16).contiguous() for name, x_key in layers}
     algo_bytes = 0
     for name, _ in layers:
         d = deps[name]
