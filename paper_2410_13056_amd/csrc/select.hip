@@ -153,11 +153,10 @@ __global__ __launch_bounds__(kSelThreads) void allocate_bits_kernel(
 // Fast chain, tried first: two histogram passes over a sample (every s-th wave-chunk)
 // give a 22-bit prefix that, by the sample, a few percent more than k entries reach.  One
 // pass over the data stages every entry that reaches it; the exact k-th key is then
-// found inside the list (two digits: the 22-bit bin relative to the guess, the low 10
-// bits) and the answer written from the list.  The sample only guides the guess: if the
-// list turns out to hold fewer than k entries, overflows, or the k-th key lies far above
-// the guess, a flag is raised and the exact chain, whose kernels otherwise return at
-// once, does the work.  Either way the result is the same set.
+// found inside the list (the same three digits, over the list only) and the answer
+// written from the list.  The sample only guides the guess: if the list turns out to
+// hold fewer than k entries or overflows, a flag is raised and the exact chain, whose
+// kernels otherwise return at once, does the work.  Either way the result is the same set.
 
 constexpr int kWThreads = 256;
 constexpr int kWaves = kWThreads / CMPQ_WAVE;
@@ -166,8 +165,8 @@ constexpr int kWaveChunk = CMPQ_WAVE * kWPerLane;
 constexpr int kMaxBlocks = 2048;
 constexpr int kMaxUnits = kMaxBlocks * kWaves;
 constexpr int kBins = 2048;
-// histograms: 0-2 the digits of the exact chain, 3-4 the sample's, 5-6 the list's
-constexpr int kHists = 7;
+// histograms: 0-2 the digits of the exact chain, 3-4 the sample's, 5-7 the list's
+constexpr int kHists = 8;
 
 struct WselState {
     uint32_t T;         // final threshold key
@@ -177,8 +176,6 @@ struct WselState {
     uint32_t fast_overflow;  // a unit's staging share was too small
     uint32_t fast_failed;    // the list does not settle the answer: the exact chain runs
     uint32_t guess22;        // staged: top 22 bits >= guess22
-    uint32_t T22;            // top 22 bits of the threshold, found in the list
-    uint64_t rem_b;          // rank of the threshold inside that 22-bit bin
 };
 
 struct WselArgs {
@@ -586,42 +583,30 @@ __global__ __launch_bounds__(kWThreads) void wsel_stage_kernel(WselArgs a, WselS
     }
 }
 
-// Fast chain, passes over the list.  PASS 0: histogram of the 22-bit bin relative to the
-// guess; the threshold is expected a few bins above the guess, so only the first
-// kNearBins bins are told apart and everything beyond shares the last bin (fewer counters
-// to flush).  PASS 1: first picks
-// the bin of rank k from that histogram - the list settles the answer only if it holds at
-// least k entries, did not overflow and the bin is not the shared last one - then
-// histograms the low 10 bits inside that bin.
-constexpr uint32_t kNearBins = 511;
-
+// Fast chain, passes over the list: the exact k-th key of the list by the same three
+// digits as the exact chain (11 + 11 + 10 bits), each pass reading the digits the earlier
+// ones fixed off their histograms.  The second pass also settles whether the list holds
+// the answer at all: it does unless it overflowed or is shorter than k.
 template <int PASS>
 __global__ __launch_bounds__(kWThreads) void wsel_list_kernel(WselArgs a, WselState *st, int nunits,
                                                                uint32_t *__restrict__ hist, uint64_t k) {
     __shared__ uint32_t lh[kBins];
     __shared__ PickShared ps;
     for (int b = threadIdx.x; b < kBins; b += kWThreads) lh[b] = 0;
-    const uint32_t guess22 = st->guess22;
     const bool overflowed = st->fast_overflow != 0;
-    uint32_t T22 = 0;
-    if (PASS == 1) {
-        uint32_t bin, tot;
-        uint64_t rem_b;
-        const bool ok = block_pick(hist + 5 * kBins, k, ps, bin, rem_b, tot);
-        const bool failed = overflowed || !ok || bin == (uint32_t)(kBins - 1);
-        if (blockIdx.x == 0 && threadIdx.x == 0) {
-            st->fast_failed = failed ? 1u : 0u;
-            st->T22 = guess22 + bin;
-            st->rem_b = rem_b;
-        }
+    uint32_t prefix = 0;
+    if (PASS > 0) {
+        uint64_t rem;
+        bool all;
+        exact_prefix(hist + 5 * kBins, k, PASS, ps, prefix, rem, all);
+        const bool failed = overflowed || all;
+        if (PASS == 1 && blockIdx.x == 0 && threadIdx.x == 0) st->fast_failed = failed ? 1u : 0u;
         if (failed) return;
-        T22 = guess22 + bin;
     } else if (overflowed) {
         return;
     }
     __syncthreads();
     const int lane = threadIdx.x & (CMPQ_WAVE - 1), wave = threadIdx.x / CMPQ_WAVE;
-    uint32_t n_far = 0;
     for (int64_t unit = (int64_t)blockIdx.x * kWaves + wave; unit < nunits; unit += (int64_t)gridDim.x * kWaves) {
         const unsigned long long *ik = a.stage_ik + unit * a.cap;
         const uint32_t n = a.stage_cnt[unit];
@@ -629,17 +614,13 @@ __global__ __launch_bounds__(kWThreads) void wsel_list_kernel(WselArgs a, WselSt
         for (uint32_t e = lane; e < n; e += CMPQ_WAVE) {
             const uint32_t key = (uint32_t)ik[e];
             if (PASS == 0) {
-                const uint32_t rel = (key >> 10) - guess22;
-                if (rel < kNearBins) atomicAdd(&lh[rel], 1u);
-                else ++n_far;  // most of the list: counted in a register, added once
-            } else if ((key >> 10) == T22) {
-                atomicAdd(&lh[key & 1023u], 1u);
+                atomicAdd(&lh[key >> 21], 1u);
+            } else if (PASS == 1) {
+                if ((key >> 21) == (prefix >> 21)) atomicAdd(&lh[(key >> 10) & 2047u], 1u);
+            } else {
+                if ((key >> 10) == (prefix >> 10)) atomicAdd(&lh[key & 1023u], 1u);
             }
         }
-    }
-    if (PASS == 0) {
-        n_far = wave_sum_u32(n_far);
-        if (lane == 0 && n_far) atomicAdd(&lh[kBins - 1], n_far);
     }
     __syncthreads();
     for (int b = threadIdx.x; b < kBins; b += kWThreads)
@@ -657,8 +638,6 @@ __global__ void wsel_init_kernel(WselState *st, uint32_t *hist, int32_t *idx_out
         st->fast_overflow = 0;
         st->fast_failed = 0;
         st->guess22 = 0;
-        st->T22 = 0;
-        st->rem_b = 0;
     }
     for (int64_t j = t; j < k_fill; j += (int64_t)gridDim.x * blockDim.x) idx_out[j] = -1;
 }
@@ -753,13 +732,9 @@ __global__ __launch_bounds__(kWThreads) void wsel_count_kernel(WselState *st, Ws
     const bool exact = st->fast_failed != 0;
     uint32_t T;
     uint64_t need;
-    if (!exact) {
-        uint32_t digit, tot;
-        block_pick(hist + 6 * kBins, st->rem_b, ps, digit, need, tot);  // rem_b lies inside the bin
-        T = (st->T22 << 10) | digit;
-    } else {
-        bool all;
-        exact_prefix(hist, k, 3, ps, T, need, all);
+    {
+        bool all;  // the three digits of the list's histograms, or of the exact chain's
+        exact_prefix(exact ? hist : hist + 5 * kBins, k, 3, ps, T, need, all);
         if (all) need = ~0ull;  // T = 0: every candidate counts
     }
     if (blockIdx.x == 0 && threadIdx.x == 0) {
@@ -1010,6 +985,7 @@ int launch_weight_select(WselArgs a, const WselPlan &p, int64_t k, int32_t *idx_
     const int list_blocks = p.nblocks < 256 ? p.nblocks : 256;  // few: each ends with a flush into shared counters
     wsel_list_kernel<0><<<list_blocks, kWThreads, 0, s>>>(a, w.st, p.nunits, w.hist, (uint64_t)k);
     wsel_list_kernel<1><<<list_blocks, kWThreads, 0, s>>>(a, w.st, p.nunits, w.hist, (uint64_t)k);
+    wsel_list_kernel<2><<<list_blocks, kWThreads, 0, s>>>(a, w.st, p.nunits, w.hist, (uint64_t)k);
     // exact chain: these return at once unless the fast chain raised its flag
     wsel_hist_kernel<TW, 0><<<p.nblocks, kWThreads, 0, s>>>(a, w.st, (uint64_t)k, w.hist, w.above, w.local_last);
     wsel_hist_kernel<TW, 1><<<p.nblocks, kWThreads, 0, s>>>(a, w.st, (uint64_t)k, w.hist, w.above, w.local_last);
