@@ -151,3 +151,26 @@ def test_block70b_layers_full_size(env, layer):
     tot = _np(r.err_total)
     ref_w = float((r.err_ch * sumsq.double()).sum())
     assert abs(tot[0] - ref_w) <= 1e-9 * ref_w
+
+
+def test_block70b_three_streams_equals_one_stream_full_size(env):
+    """The whole 70B-shaped block exactly as bench.py runs it by default (layers shared out over
+    three streams): every output bit-identical to the one-stream run of the same call chain,
+    whose layers the tests above check against the oracle."""
+    P, B, synth = env["P"], env["B"], env["synth"]
+    wl = synth.workload("block70b")
+    wts, xs = synth.materialize(wl, DEV)
+    layers = [(l.name, l.x_key) for l in wl.layers]
+    status = torch.zeros(1, dtype=torch.int32, device=DEV)
+    args = (wts, xs, layers, wl.bit_set, wl.avg_bits, wl.rho_act_ppm, wl.rho_q_ppm, wl.iters)
+    one = P.quantize_block(*args, env["ws"], with_error=True, status=status)
+    many = P.quantize_block(*args, [B.Workspace(DEV) for _ in range(3)], with_error=True, status=status, streams=3)
+    torch.cuda.synchronize()
+    assert status.item() == 0
+    for name in one:
+        a, b = one[name], many[name]
+        assert a.counts == b.counts
+        for f in ("sumsq", "act_idx", "bits", "centroids", "codes", "out_idx", "out_val", "err_ch", "err_total"):
+            assert torch.equal(getattr(a, f), getattr(b, f)), (name, f)
+        for x, y in zip(a.packed + a.chan_idx + a.lut, b.packed + b.chan_idx + b.lut):
+            assert (x is None) == (y is None) and (x is None or torch.equal(x, y)), name
