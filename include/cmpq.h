@@ -87,7 +87,7 @@ const char *cmpq_strerror(int code);
 int64_t cmpq_count_ppm(int64_t ppm, int64_t n);
 
 /*
- * Sec. 3.2.1, "per-channel L2-norm of X": acc[i] (+)= sum_t X[t,i]^2 in fp64 and
+ * Sec. 3.2.1, the L2 norm of each channel of X: acc[i] (+)= sum_t X[t,i]^2 in fp64 and
  * sumsq[i] = (float)acc[i].  The square of the paper's a_i is kept: it ranks
  * channels identically and is the channel weight of the output error (App. B.3).
  *   X      [n, d_in], dtype CMPQ_F16 or CMPQ_F32, leading dimension ldx >= d_in.

@@ -12,7 +12,7 @@
  * Tensors are row-major with an explicit leading dimension.
  *
  * Steps, in the order of Sec. 3.2.1 / 3.2.2:
- *   orc_act_stats        a_i^2 = sum_t X[t,i]^2           (Sec. 3.2.1, "per-channel L2-norm of X")
+ *   orc_act_stats        a_i^2 = sum_t X[t,i]^2           (Sec. 3.2.1: L2 norm of each channel of X)
  *   orc_top_channels     O_act: channels with the largest a (Sec. 3.2.2)
  *   orc_allocate_bits    Algorithm 1, integer-budget reading
  *   orc_kmeans           per-channel K-means, K = 2^c_i      (Sec. 3.2.1; Sec. 3 eq. Q(x))
@@ -410,8 +410,8 @@ int orc_weight_outliers(const void *W, int dtype, int64_t d_in, int64_t d_out, i
  * each.  A row is a little-endian bit stream: the code of output o sits in
  * stream bits [o*b, (o+1)*b); stream bit s is bit (s mod 32) of word (s / 32);
  * rows are padded with zero bits to words_per_row = ceil(d_out*b/32) words.
- * lut[row*2^b + j] = level j in FP16 (round to nearest even): the "cluster
- * centers (look-up-table)" of Sec. 5.1.  Called once per width; returns the
+ * lut[row*2^b + j] = level j in FP16 (round to nearest even): the table of
+ * cluster centres that Sec. 5.1 counts per channel.  Called once per width; returns the
  * number of rows, or < 0.
  */
 int64_t orc_pack(const uint8_t *codes, int64_t d_in, int64_t d_out, const uint8_t *bits,

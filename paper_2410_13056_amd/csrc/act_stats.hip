@@ -1,5 +1,5 @@
 // cmpq_act_stats: per-channel sum of squares of the calibration activations
-// (Sec. 3.2.1 of arXiv 2410.13056, the "per-channel L2-norm of X", kept squared).
+// (Sec. 3.2.1 of arXiv 2410.13056: the L2 norm of each channel of X, kept squared).
 //
 // HBM bound: every element of X is read once.  Each lane streams 16-byte
 // pieces of a row (8 halves or 4 floats), a wave covers 1 KiB of one row, the
