@@ -98,6 +98,18 @@ def act_stats(X: np.ndarray, acc: Optional[np.ndarray] = None) -> Tuple[np.ndarr
     return acc, sumsq
 
 
+def act_stats_norm(X: np.ndarray, norm: int, acc: Optional[np.ndarray] = None) -> Tuple[np.ndarray, np.ndarray]:
+    """Tab. 13: ``(acc float64[d_in], stat float32[d_in])`` for norm 0 (l2, squared), 1 (l1), 2 (l-infinity)."""
+    X = _c(X)
+    n, d_in = X.shape
+    acc = np.zeros(d_in, np.float64) if acc is None else _c(acc, np.float64).copy()
+    stat = np.zeros(d_in, np.float32)
+    rc = lib().orc_act_stats_norm(_p(X), _dtype_code(X), ctypes.c_int64(n), ctypes.c_int64(d_in),
+                                  ctypes.c_int64(d_in), int(norm), _p(acc), _p(stat))
+    assert rc == 0, rc
+    return acc, stat
+
+
 def top_channels(sumsq: np.ndarray, k: int) -> Tuple[np.ndarray, np.ndarray]:
     sumsq = _c(sumsq, np.float32)
     d_in = sumsq.shape[0]

@@ -109,6 +109,30 @@ int orc_act_stats(const void *X, int dtype, int64_t n, int64_t d_in, int64_t ldx
     return 0;
 }
 
+/*
+ * App. (norm ablation, Tab. 13): the same statistic with the l1 or the l-infinity norm of
+ * each channel in place of the l2 norm.  norm 0: acc += sum x^2 (orc_act_stats); 1:
+ * acc += sum |x|; 2: acc = max(acc, max |x|).  stat[i] = (float)acc[i] ranks the channels
+ * (for the l2 norm the square, which has the same order).
+ */
+int orc_act_stats_norm(const void *X, int dtype, int64_t n, int64_t d_in, int64_t ldx, int norm,
+                       double *acc, float *stat) {
+    if (!X || !acc || n < 0 || d_in < 0 || ldx < d_in || norm < 0 || norm > 2) return -1;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < d_in; ++i) {
+        double s = acc[i];
+        for (int64_t t = 0; t < n; ++t) {
+            double x = load_elem(X, dtype, t * ldx + i);
+            if (norm == 0) s += x * x;
+            else if (norm == 1) s += fabs(x);
+            else if (fabs(x) > s) s = fabs(x);
+        }
+        acc[i] = s;
+        if (stat) stat[i] = (float)s;
+    }
+    return 0;
+}
+
 /* ---- ranking with a total order ----------------------------------------------------------- */
 
 typedef struct {

@@ -608,3 +608,26 @@ def test_lut_matvec_agrees_with_the_packed_format(orc):
             row_codes, _ = _unpack(packed[r], b, d_out)
             y += float(x[0, i]) * lut[r].view(np.float16).astype(np.float64)[row_codes]
     assert np.allclose(orc.lut_matvec(x, W, cent, codes, bits)[0], y, rtol=1e-13, atol=1e-13)
+
+
+# ------------------------------------------------------------------ Tab. 13: other norms as the statistic
+
+def test_act_stats_other_norms_match_numpy_and_chunking(orc):
+    rng = np.random.default_rng(41)
+    X = (rng.normal(0, 1, (300, 37)) * np.exp(rng.normal(0, 1, 37))).astype(np.float16)
+    X64 = X.astype(np.float64)
+    want = {0: (X64 ** 2).sum(0), 1: np.abs(X64).sum(0), 2: np.abs(X64).max(0)}
+    for norm, ref in want.items():
+        acc, stat = orc.act_stats_norm(X, norm)
+        assert np.allclose(acc, ref, rtol=1e-14, atol=0)
+        assert np.array_equal(stat, acc.astype(np.float32))
+        a1, _ = orc.act_stats_norm(X[:111], norm)                 # tokens arriving in two chunks
+        a2, _ = orc.act_stats_norm(X[111:], norm, acc=a1)
+        assert np.allclose(a2, ref, rtol=1e-14, atol=0)
+    assert np.array_equal(orc.act_stats_norm(X, 0)[0], orc.act_stats(X)[0])
+    # the norms are different criteria: one spike outranks a steady channel only under l-infinity
+    Y = np.zeros((100, 2), np.float32)
+    Y[:, 0] = 1.0
+    Y[7, 1] = 5.0
+    s2, s1, si = (orc.act_stats_norm(Y, k)[1] for k in (0, 1, 2))
+    assert s2[0] > s2[1] and s1[0] > s1[1] and si[1] > si[0]
