@@ -72,6 +72,11 @@ extern "C" {
 #define CMPQ_SCORE_RESIDUAL 0  /* |W' - W'_q|: the criterion of Sec. 3.2.2           */
 #define CMPQ_SCORE_MAGNITUDE 1 /* |W'|: the magnitude rule Sec. 3.2.2 contrasts with */
 
+/* `norm` of cmpq_act_stats_norm */
+#define CMPQ_NORM_L2 0   /* sum of squares: the criterion of Sec. 3.2.1 */
+#define CMPQ_NORM_L1 1   /* sum of magnitudes  (norm ablation, App. Tab. 13) */
+#define CMPQ_NORM_LINF 2 /* largest magnitude  (norm ablation, App. Tab. 13) */
+
 /* `init` of cmpq_kmeans_quantize */
 #define CMPQ_INIT_QUANTILE 0
 
@@ -99,6 +104,18 @@ int64_t cmpq_count_ppm(int64_t ppm, int64_t n);
 int cmpq_act_stats(const void *X, int dtype, int64_t n, int64_t d_in, int64_t ldx, double *acc,
                    float *sumsq, int accumulate, void *ws, size_t ws_bytes, int32_t *status,
                    void *stream);
+
+/*
+ * The same statistic under another norm (the appendix compares the l1 and l-infinity norms
+ * with the l2 norm as allocation criterion, Tab. 13): norm = CMPQ_NORM_L2 is cmpq_act_stats;
+ * CMPQ_NORM_L1: acc[i] (+)= sum_t |X[t,i]|; CMPQ_NORM_LINF: acc[i] = max(acc[i], max_t |X[t,i]|)
+ * (accumulate = 0 starts from 0).  stat[i] = (float)acc[i] is what cmpq_extract_outliers and
+ * cmpq_allocate_bits rank; the error weight of cmpq_dequant_error stays the l2 statistic.
+ * Arguments, workspace and status as cmpq_act_stats.
+ */
+int cmpq_act_stats_norm(const void *X, int dtype, int64_t n, int64_t d_in, int64_t ldx, int norm,
+                        double *acc, float *stat, int accumulate, void *ws, size_t ws_bytes,
+                        int32_t *status, void *stream);
 
 /*
  * Orientation helper for Sec. 3.2.1's W in R^{d_in x d_out}: dst[c, r] = src[r, c].

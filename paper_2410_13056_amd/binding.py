@@ -26,11 +26,12 @@ OUTLIER_CHANNELS, OUTLIER_WEIGHTS = 0, 1
 SCORE_RESIDUAL, SCORE_MAGNITUDE = 0, 1
 INIT_QUANTILE = 0
 KMEANS_HISTOGRAM, KMEANS_DIRECT = 0, 1
+NORM_L2, NORM_L1, NORM_LINF = 0, 1, 2
 
 EXPORTS = ("cmpq_workspace_bytes", "cmpq_strerror", "cmpq_count_ppm", "cmpq_act_stats",
            "cmpq_transpose", "cmpq_allocate_bits", "cmpq_extract_outliers",
            "cmpq_kmeans_quantize", "cmpq_pack", "cmpq_dequant_error", "cmpq_set_kmeans_algorithm",
-           "cmpq_gather_channels", "cmpq_outliers_by_column", "cmpq_lut_matvec")
+           "cmpq_gather_channels", "cmpq_outliers_by_column", "cmpq_lut_matvec", "cmpq_act_stats_norm")
 
 _i64, _i32, _int, _vp, _dbl, _sz = (ctypes.c_int64, ctypes.c_int32, ctypes.c_int, ctypes.c_void_p,
                                     ctypes.c_double, ctypes.c_size_t)
@@ -68,6 +69,7 @@ def lib() -> ctypes.CDLL:
         L.cmpq_dequant_error.argtypes = [_vp, _int, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _i64, _vp,
                                          _vp, _vp, _vp, _sz, _vp]
         L.cmpq_set_kmeans_algorithm.argtypes = [_int]
+        L.cmpq_act_stats_norm.argtypes = [_vp, _int, _i64, _i64, _i64, _int, _vp, _vp, _int, _vp, _sz, _vp, _vp]
         L.cmpq_gather_channels.argtypes = [_vp, _int, _i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp]
         L.cmpq_outliers_by_column.argtypes = [_vp, _vp, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
         L.cmpq_lut_matvec.argtypes = [_vp, _i64, _i64, _i64, _i64, _vp, _int, _vp, _vp, _vp, _vp, _vp, _vp,
@@ -282,3 +284,13 @@ def lut_matvec(X: torch.Tensor, d_out: int, bit_set: Sequence[int], counts: Sequ
                                  k_act, ld_act, _ptr(colptr), _ptr(row_idx), _ptr(delta), _ptr(Y), ldy,
                                  _ptr(buf), buf.numel(), _stream()),
            "cmpq_lut_matvec")
+
+
+def act_stats_norm(X: torch.Tensor, norm: int, acc: torch.Tensor, stat: Optional[torch.Tensor], accumulate: bool,
+                   ws: Workspace, status: Optional[torch.Tensor] = None) -> None:
+    """Tab. 13: the activation statistic under the l2 (squared), l1 or l-infinity norm."""
+    n, d_in, ldx = _rows(X)
+    buf = ws.get(workspace_bytes(OP_ACT_STATS, d_in, 0, n))
+    _check(lib().cmpq_act_stats_norm(_ptr(X), _dtype(X), n, d_in, ldx, int(norm), _ptr(acc), _ptr(stat),
+                                     int(bool(accumulate)), _ptr(buf), buf.numel(), _ptr(status), _stream()),
+           "cmpq_act_stats_norm")

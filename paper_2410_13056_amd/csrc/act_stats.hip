@@ -44,8 +44,22 @@ struct Vec<float> {
     }
 };
 
-// partial[split * d_in + col] = sum over the rows of this split of X[row, col]^2
-template <typename T>
+// One element into the running value of its column: x^2 (l2, App. Tab. 13's default), |x|
+// (l1) or the largest |x| (l-infinity).
+template <int NORM>
+__device__ __forceinline__ double fold(double s, float x) {
+    const double d = (double)x;
+    if (NORM == CMPQ_NORM_L2) return fma(d, d, s);
+    if (NORM == CMPQ_NORM_L1) return s + fabs(d);
+    return fmax(s, fabs(d));
+}
+template <int NORM>
+__device__ __forceinline__ double combine(double a, double b) {
+    return NORM == CMPQ_NORM_LINF ? fmax(a, b) : a + b;
+}
+
+// partial[split * d_in + col] = the statistic over the rows of this split of column col
+template <typename T, int NORM>
 __global__ __launch_bounds__(kThreads) void act_stats_vec_kernel(const T *__restrict__ X, int64_t n,
                                                                   int64_t d_in, int64_t ldx,
                                                                   int64_t rows_per_split,
@@ -71,19 +85,13 @@ __global__ __launch_bounds__(kThreads) void act_stats_vec_kernel(const T *__rest
 #pragma unroll
             for (int u = 0; u < 8; ++u)
 #pragma unroll
-                for (int v = 0; v < V; ++v) {
-                    double d = (double)f[u][v];
-                    s[v] = fma(d, d, s[v]);
-                }
+                for (int v = 0; v < V; ++v) s[v] = fold<NORM>(s[v], f[u][v]);
         }
         for (; r < r_end; r += kWaves) {
             float f[V];
             Vec<T>::load(p + r * ldx, f);
 #pragma unroll
-            for (int v = 0; v < V; ++v) {
-                double d = (double)f[v];
-                s[v] = fma(d, d, s[v]);
-            }
+            for (int v = 0; v < V; ++v) s[v] = fold<NORM>(s[v], f[v]);
         }
     }
 #pragma unroll
@@ -94,14 +102,14 @@ __global__ __launch_bounds__(kThreads) void act_stats_vec_kernel(const T *__rest
         if (col < d_in) {
             double t = red[0][c];
 #pragma unroll
-            for (int w = 1; w < kWaves; ++w) t += red[w][c];
+            for (int w = 1; w < kWaves; ++w) t = combine<NORM>(t, red[w][c]);
             partial[(int64_t)blockIdx.y * d_in + col] = t;
         }
     }
 }
 
 // Any alignment: one thread per column, threads of a wave read neighbouring columns.
-template <typename T>
+template <typename T, int NORM>
 __global__ __launch_bounds__(kThreads) void act_stats_any_kernel(const T *__restrict__ X, int64_t n,
                                                                   int64_t d_in, int64_t ldx,
                                                                   int64_t rows_per_split,
@@ -111,15 +119,13 @@ __global__ __launch_bounds__(kThreads) void act_stats_any_kernel(const T *__rest
     const int64_t r_begin = (int64_t)blockIdx.y * rows_per_split;
     const int64_t r_end = min(n, r_begin + rows_per_split);
     double s = 0.0;
-    for (int64_t r = r_begin; r < r_end; ++r) {
-        double d = (double)load_as_f32<T>(X, r * ldx + col);
-        s = fma(d, d, s);
-    }
+    for (int64_t r = r_begin; r < r_end; ++r) s = fold<NORM>(s, load_as_f32<T>(X, r * ldx + col));
     partial[(int64_t)blockIdx.y * d_in + col] = s;
 }
 
 // 64 columns per workgroup; the four wavefronts each add a quarter of the row splits
 // (in split order), then the quarters are added in order: a fixed summation tree.
+template <int NORM>
 __global__ __launch_bounds__(kThreads) void act_stats_finish_kernel(
     const double *__restrict__ partial, int splits, int64_t d_in, double *__restrict__ acc,
     float *__restrict__ sumsq, int accumulate, int32_t *__restrict__ status) {
@@ -130,13 +136,13 @@ __global__ __launch_bounds__(kThreads) void act_stats_finish_kernel(
     const int s0 = wave * per, s1 = min(splits, s0 + per);
     double t = 0.0;
     if (col < d_in)
-        for (int sidx = s0; sidx < s1; ++sidx) t += partial[(int64_t)sidx * d_in + col];
+        for (int sidx = s0; sidx < s1; ++sidx) t = combine<NORM>(t, partial[(int64_t)sidx * d_in + col]);
     red[wave][lane] = t;
     __syncthreads();
     if (wave == 0 && col < d_in) {
         double r = accumulate ? acc[col] : 0.0;
 #pragma unroll
-        for (int w = 0; w < kWaves; ++w) r += red[w][lane];
+        for (int w = 0; w < kWaves; ++w) r = combine<NORM>(r, red[w][lane]);
         acc[col] = r;
         if (sumsq) sumsq[col] = (float)r;
         if (status && !isfinite(r)) atomicOr(status, CMPQ_STATUS_NONFINITE);
@@ -151,23 +157,17 @@ int64_t pick_splits(int64_t n, int64_t col_blocks) {
     return s < 1 ? 1 : s;
 }
 
-}  // namespace
-
-size_t cmpq_ws_act_stats(int64_t d_in, int64_t n) {
+size_t ws_act_stats_impl(int64_t d_in, int64_t n) {
     // the widest column block gives the fewest column blocks, hence the most row splits
     int64_t col_blocks = cdiv(d_in, 512) > 0 ? cdiv(d_in, 512) : 1;
     int64_t s = pick_splits(n, col_blocks);
     return align_up((size_t)(s > 0 ? s : 1) * (size_t)(d_in > 0 ? d_in : 1) * sizeof(double), 256);
 }
 
-extern "C" int cmpq_act_stats(const void *X, int dtype, int64_t n, int64_t d_in, int64_t ldx,
-                              double *acc, float *sumsq, int accumulate, void *ws, size_t ws_bytes,
-                              int32_t *status, void *stream) {
-    if (!acc || n < 0 || d_in < 0 || (dtype != CMPQ_F16 && dtype != CMPQ_F32)) return CMPQ_EINVAL;
-    if (n > 0 && !X) return CMPQ_EINVAL;
-    if (ldx < d_in) return CMPQ_ESHAPE;
-    if (d_in == 0) return CMPQ_OK;
-    hipStream_t st = static_cast<hipStream_t>(stream);
+template <int NORM>
+int launch_act_stats(const void *X, int dtype, int64_t n, int64_t d_in, int64_t ldx, double *acc,
+                     float *stat, int accumulate, void *ws, size_t ws_bytes, int32_t *status,
+                     hipStream_t st) {
     const int vec = dtype == CMPQ_F16 ? 8 : 4;
     const bool aligned = n > 0 && d_in % vec == 0 && ldx % vec == 0 &&
                          reinterpret_cast<uintptr_t>(X) % 16 == 0;
@@ -183,23 +183,50 @@ extern "C" int cmpq_act_stats(const void *X, int dtype, int64_t n, int64_t d_in,
         dim3 grid((unsigned)col_blocks, (unsigned)splits);
         if (aligned) {
             if (dtype == CMPQ_F16)
-                act_stats_vec_kernel<__half><<<grid, kThreads, 0, st>>>(
+                act_stats_vec_kernel<__half, NORM><<<grid, kThreads, 0, st>>>(
                     static_cast<const __half *>(X), n, d_in, ldx, rps, partial);
             else
-                act_stats_vec_kernel<float><<<grid, kThreads, 0, st>>>(
+                act_stats_vec_kernel<float, NORM><<<grid, kThreads, 0, st>>>(
                     static_cast<const float *>(X), n, d_in, ldx, rps, partial);
         } else {
             if (dtype == CMPQ_F16)
-                act_stats_any_kernel<__half><<<grid, kThreads, 0, st>>>(
+                act_stats_any_kernel<__half, NORM><<<grid, kThreads, 0, st>>>(
                     static_cast<const __half *>(X), n, d_in, ldx, rps, partial);
             else
-                act_stats_any_kernel<float><<<grid, kThreads, 0, st>>>(
+                act_stats_any_kernel<float, NORM><<<grid, kThreads, 0, st>>>(
                     static_cast<const float *>(X), n, d_in, ldx, rps, partial);
         }
         CMPQ_LAUNCH_CHECK();
     }
-    act_stats_finish_kernel<<<(unsigned)cdiv(d_in, CMPQ_WAVE), kThreads, 0, st>>>(
-        partial, (int)splits, d_in, acc, sumsq, accumulate, status);
+    act_stats_finish_kernel<NORM><<<(unsigned)cdiv(d_in, CMPQ_WAVE), kThreads, 0, st>>>(
+        partial, (int)splits, d_in, acc, stat, accumulate, status);
     CMPQ_LAUNCH_CHECK();
     return CMPQ_OK;
+}
+
+}  // namespace
+
+size_t cmpq_ws_act_stats(int64_t d_in, int64_t n) { return ws_act_stats_impl(d_in, n); }
+
+extern "C" int cmpq_act_stats_norm(const void *X, int dtype, int64_t n, int64_t d_in, int64_t ldx,
+                                   int norm, double *acc, float *stat, int accumulate, void *ws,
+                                   size_t ws_bytes, int32_t *status, void *stream) {
+    if (!acc || n < 0 || d_in < 0 || (dtype != CMPQ_F16 && dtype != CMPQ_F32)) return CMPQ_EINVAL;
+    if (norm != CMPQ_NORM_L2 && norm != CMPQ_NORM_L1 && norm != CMPQ_NORM_LINF) return CMPQ_EINVAL;
+    if (n > 0 && !X) return CMPQ_EINVAL;
+    if (ldx < d_in) return CMPQ_ESHAPE;
+    if (d_in == 0) return CMPQ_OK;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    switch (norm) {
+        case CMPQ_NORM_L1: return launch_act_stats<CMPQ_NORM_L1>(X, dtype, n, d_in, ldx, acc, stat, accumulate, ws, ws_bytes, status, st);
+        case CMPQ_NORM_LINF: return launch_act_stats<CMPQ_NORM_LINF>(X, dtype, n, d_in, ldx, acc, stat, accumulate, ws, ws_bytes, status, st);
+        default: return launch_act_stats<CMPQ_NORM_L2>(X, dtype, n, d_in, ldx, acc, stat, accumulate, ws, ws_bytes, status, st);
+    }
+}
+
+extern "C" int cmpq_act_stats(const void *X, int dtype, int64_t n, int64_t d_in, int64_t ldx,
+                              double *acc, float *sumsq, int accumulate, void *ws, size_t ws_bytes,
+                              int32_t *status, void *stream) {
+    return cmpq_act_stats_norm(X, dtype, n, d_in, ldx, CMPQ_NORM_L2, acc, sumsq, accumulate, ws, ws_bytes,
+                               status, stream);
 }

@@ -91,6 +91,34 @@ def test_act_stats_strided_chunked_empty_and_status(env):
     assert st.item() == 0
 
 
+@pytest.mark.parametrize("dtype", [np.float16, np.float32])
+@pytest.mark.parametrize("norm", [0, 1, 2])
+def test_act_stats_other_norms_parity(env, dtype, norm):
+    """Tab. 13: l2 (squared), l1 and l-infinity statistics, in two chunks of tokens.  Sums of
+    magnitudes and maxima of fp16 inputs are exact in fp64: compared bit for bit.  Squares, and
+    fp32 inputs, within 1e-12 relative (the order of the fp64 additions differs)."""
+    B, ws, orc = env["B"], env["ws"], env["orc"]
+    rng = np.random.default_rng(17 + norm)
+    n, d_in = 777, 1000 + 8
+    X = (rng.normal(0, 1, (n, d_in)) * np.exp(rng.normal(0, 1, d_in))).astype(dtype)
+    Xd = _dev(X)
+    acc = torch.empty(d_in, dtype=torch.float64, device=DEV)
+    stat = torch.empty(d_in, dtype=torch.float32, device=DEV)
+    B.act_stats_norm(Xd[:300], norm, acc, stat, False, ws)
+    B.act_stats_norm(Xd[300:], norm, acc, stat, True, ws)
+    oacc, ostat = orc.act_stats_norm(X, norm)
+    if dtype == np.float16 and norm != 0:
+        assert np.array_equal(_np(acc), oacc) and np.array_equal(_np(stat), ostat)
+    else:
+        assert _rel(_np(acc), oacc) <= 1e-12 and _rel(_np(stat), ostat) <= 1e-6
+    # the statistic drives the same ranking calls
+    k = 9
+    idx = torch.empty(k, dtype=torch.int32, device=DEV)
+    mask = torch.empty(d_in, dtype=torch.uint8, device=DEV)
+    B.extract_channel_outliers(stat, k, idx, mask, ws)
+    assert np.array_equal(_np(idx), orc.top_channels(_np(stat), k)[0])        # same input on both sides
+
+
 def test_act_stats_is_reproducible(env):
     X = env["synth"].make_activations(20000, 2048, "f16", 5, DEV)
     a1, _ = env["P"].activation_stats(X, env["ws"])
