@@ -251,6 +251,23 @@ def test_kmeans_parity_signed_zeros_and_boundaries_at_zero(env, d_out):
         _check_kmeans(cent, codes, ocent, ocodes, exact=True)
 
 
+@pytest.mark.parametrize("dtype,d_out", [(np.float16, 32768), (np.float32, 16384)])
+def test_kmeans_parity_at_the_largest_channel_length(env, dtype, d_out):
+    """The documented limits of cmpq_kmeans_quantize: 32768 outputs per channel for fp16
+    weights, 16384 for fp32; with removed entries and every width."""
+    rng = np.random.default_rng(d_out)
+    d_in = 6
+    W = rng.normal(0, 0.02, (d_in, d_out))
+    W[rng.random(W.shape) < 0.005] *= 20
+    W = W.astype(dtype)
+    bits = np.array([1, 2, 3, 4, 16, 4], np.uint8)
+    excl = np.sort(rng.choice(d_in * d_out, 1500, replace=False)).astype(np.int64)
+    for out_idx in (None, excl):
+        cent, codes = _kmeans_gpu(env, W, bits, out_idx=out_idx, iters=6)
+        ocent, ocodes = env["orc"].kmeans(W, bits, out_idx=out_idx, iters=6)
+        _check_kmeans(cent, codes, ocent, ocodes, exact=dtype == np.float16)
+
+
 def test_kmeans_direct_kernel_agrees(env):
     """The brute-force kernel (CMPQ_KMEANS_DIRECT) is a second implementation: same bits as
     the bucket kernel and as the oracle, with and without removed entries."""
