@@ -433,10 +433,10 @@ extern "C" int cmpq_lut_matvec(const void *X, int64_t m, int64_t d_in, int64_t l
     if (colptr && (!row_idx || !delta)) return CMPQ_EINVAL;
     if (ldx < d_in || ldy < d_out || (k_act > 0 && ld_act < d_out)) return CMPQ_ESHAPE;
     if (m > 65535 || d_out >= (1 << 20)) return CMPQ_ESHAPE;
-    // rows per wavefront: the largest of 32, 16, 8 that still gives about a thousand workgroups
+    // rows per wavefront: the largest of 32, 16, 8 that still gives two workgroups per compute unit
     const int64_t tiles = cdiv(d_out, kTileOut);
     int rpw = kMaxRowsPerWave;
-    while (rpw > 8 && tiles * total_slabs(counts_host, n_set, rpw) * m < 1024) rpw /= 2;
+    while (rpw > 8 && tiles * total_slabs(counts_host, n_set, rpw) * m < 512) rpw /= 2;
     const int64_t n_slabs64 = total_slabs(counts_host, n_set, rpw);
     if (n_slabs64 > 65535) return CMPQ_ESHAPE;
     const int n_slabs = (int)n_slabs64;
