@@ -108,7 +108,7 @@ def test_lut_matvec_parity_end_to_end(env, bit_set, avg, d_in, d_out):
     dep = P.prepare_deployment(r, ws)
     bits, cent, codes, out_idx = _np(r.bits), _np(r.centroids), _np(r.codes), _np(r.out_idx).astype(np.int64)
     What = _what(W, cent, codes, bits, out_idx)
-    for m in (1, 3):
+    for m in (1, 3, 5, 8):                        # groups of 1, 2 and 4 tokens, with ragged last groups
         X = rng.normal(0, 1, (m, d_in)).astype(np.float16)
         Y = _np(P.lut_matvec(dep, _dev(X), ws))
         Yref = orc.lut_matvec(X, W, cent, codes, bits, out_idx)
