@@ -6,6 +6,8 @@ given identical levels, packed words - are bit-exact.  Levels agree within 1e-5 
 activation-weighted error within 1e-4 relative; the activation statistic within 1e-5
 relative of the fp64 oracle (observed: ~1e-15).
 """
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -553,3 +555,100 @@ def test_block_over_several_streams_matches_one_stream(env):
             for x, y in zip(a.packed + a.chan_idx + a.lut, b.packed + b.chan_idx + b.lut):
                 assert (x is None) == (y is None) and (x is None or torch.equal(x, y)), name
     assert status.item() == 0
+
+
+@pytest.mark.parametrize("seed", range(int(os.environ.get("CMPQ_RANDOM_CASES", "24"))))
+def test_randomized_layers_end_to_end(env, seed):
+    """Random shapes (any d_out, including odd ones), dtypes, bit sets, budgets, outlier fractions,
+    round counts and value patterns (heavy ties, constant stretches, signed zeros, spikes) through
+    the whole path, every output against the oracle."""
+    P, ws, orc = env["P"], env["ws"], env["orc"]
+    rng = np.random.default_rng(1000 + seed)
+    d_in = int(rng.integers(1, 90))
+    d_out = int(rng.choice([rng.integers(1, 40), rng.integers(40, 700), rng.integers(700, 6000)]))
+    dtype = np.float16 if rng.random() < 0.7 else np.float32
+    lo = int(rng.integers(1, 4))
+    hi = int(rng.integers(lo + 1, 5))
+    bit_set = tuple(range(lo, hi + 1))
+    avg = float(np.round(rng.uniform(lo, hi), 2)) if rng.random() < 0.8 else float(rng.integers(lo, hi + 1))
+    rho_act = int(rng.choice([0, 4500, 30000]))
+    rho_q = int(rng.choice([0, 500, 10000, 60000]))
+    iters = int(rng.integers(0, 9))
+    W = rng.normal(0, 0.02, (d_in, d_out))
+    style = int(rng.integers(0, 4))
+    if style == 1:
+        W = np.round(W * 128) / 128                                 # heavy ties
+    elif style == 2:
+        W[:, : d_out // 2] = 0.0                                    # constant stretch, zeros
+        W[rng.random(W.shape) < 0.05] = -0.0
+    elif style == 3:
+        W[rng.random(W.shape) < 0.01] *= 30                         # spikes
+    W = W.astype(dtype)
+    X = (rng.normal(0, 1, (64, d_in)) * np.exp(rng.normal(0, 1, d_in))).astype(dtype)
+    _, sumsq = P.activation_stats(_dev(X), ws)
+    r = P.quantize_layer(_dev(W), sumsq, bit_set, avg, rho_act, rho_q, iters, ws, with_error=True, keep_prelim=True,
+                         transposed=True)
+    o = orc.quantize_layer(W, X, bit_set, avg, rho_act, rho_q, iters)
+    assert np.array_equal(_np(r.sumsq), o["sumsq"]) or _rel(_np(r.sumsq), o["sumsq"]) <= 1e-5
+    if not np.array_equal(_np(r.sumsq), o["sumsq"]):                # rank on identical statistics
+        o = orc.quantize_layer(W, None, bit_set, avg, rho_act, rho_q, iters, sumsq=_np(r.sumsq))
+    _compare_layer(env, r, o, bit_set, exact_levels=dtype == np.float16)
+
+
+@pytest.mark.parametrize("seed", range(int(os.environ.get("CMPQ_RANDOM_CASES", "24"))))
+def test_randomized_long_channels_kmeans(env, seed):
+    """The workgroup shapes of long channels (256 and 512 lanes, table coding, re-fetched weights):
+    random lengths up to the limit, widths, removed entries, round counts and value patterns."""
+    rng = np.random.default_rng(5000 + seed)
+    d_in = int(rng.integers(2, 7))
+    d_out = int(rng.choice([4096, 8192, 8192 + 4 * int(rng.integers(1, 500)), 12288, 16384, 20000, 28672, 32768]))
+    W = rng.normal(0, float(rng.choice([0.02, 1.0, 30.0])), (d_in, d_out))
+    style = int(rng.integers(0, 4))
+    if style == 1:
+        W = np.round(W * 16) / 16
+    elif style == 2:
+        W[:, ::3] = 0.0
+        W[rng.random(W.shape) < 0.02] = -0.0
+    elif style == 3:
+        W[rng.random(W.shape) < 0.002] *= 100
+    W = np.clip(W, -60000, 60000).astype(np.float16)
+    bits = rng.integers(1, 5, d_in).astype(np.uint8)
+    if rng.random() < 0.3:
+        bits[int(rng.integers(0, d_in))] = 16
+    iters = int(rng.integers(0, 21))
+    out_idx = None
+    if rng.random() < 0.6:
+        n = int(rng.integers(1, d_in * d_out // 50))
+        out_idx = np.sort(rng.choice(d_in * d_out, n, replace=False)).astype(np.int64)
+    cent, codes = _kmeans_gpu(env, W, bits, out_idx=out_idx, iters=iters)
+    ocent, ocodes = env["orc"].kmeans(W, bits, out_idx=out_idx, iters=iters)
+    _check_kmeans(cent, codes, ocent, ocodes, exact=True)
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_randomized_large_selection(env, seed):
+    """O_q on layers large enough for a sampled first guess: random k, score, tie structure and
+    concentration; the selected set and values are exact."""
+    B, ws, orc = env["B"], env["ws"], env["orc"]
+    rng = np.random.default_rng(9000 + seed)
+    d_out = int(rng.choice([4096, 8192 + 8, 11008]))
+    d_in = int(13_000_000 // d_out + rng.integers(0, 200))
+    W = rng.normal(0, 0.02, (d_in, d_out)).astype(np.float32)
+    style = seed % 3
+    if style == 1:
+        W = np.round(W * 256) / 256                                 # many equal scores
+    elif style == 2:
+        W[int(rng.integers(0, d_in))] *= 40                         # one channel holds most of the answer
+    W = W.astype(np.float16)
+    bits = rng.integers(2, 5, d_in).astype(np.uint8)
+    bits[rng.choice(d_in, 5, replace=False)] = 16
+    ocent, ocodes = orc.kmeans(W, bits, iters=1)
+    live = int((bits <= 4).sum()) * d_out
+    k = int(live * float(rng.choice([0.0005, 0.005, 0.01, 0.03])))
+    score = B.SCORE_RESIDUAL if seed % 2 == 0 else B.SCORE_MAGNITUDE
+    idx = torch.full((k,), -7, dtype=torch.int32, device=DEV)
+    val = torch.zeros(k, dtype=torch.float16, device=DEV)
+    B.extract_weight_outliers(_dev(W), _dev(ocent), _dev(ocodes), _dev(bits), k, idx, val, ws, score)
+    oidx, oval = orc.weight_outliers(W, ocent, ocodes, bits, k, score)
+    assert np.array_equal(_np(idx).astype(np.int64), oidx)
+    assert np.array_equal(_np(val).view(np.uint16), oval)
