@@ -79,9 +79,7 @@ def deployed_matvec(P, B, torch, out, layers, wl, acts, reps):
 
     def token():
         for name, _ in layers:
-            d = deps[name]
-            B.lut_matvec(xs[name], d.d_out, d.bit_set, d.counts, d.packed, d.chan_idx, d.lut, d.act_idx,
-                         d.W_act, d.colptr, d.row_idx, d.delta, ys[name], ws)
+            deps[name].matvec_into(xs[name], ys[name], ws)
 
     token()
     torch.cuda.synchronize()

@@ -257,33 +257,54 @@ def outliers_by_column(out_idx: Optional[torch.Tensor], out_val: Optional[torch.
            "cmpq_outliers_by_column")
 
 
+class LutMatvecCall:
+    """``cmpq_lut_matvec`` for one deployed layer: everything that stays the same from token to
+    token (pointer tables, counts, sizes) is marshalled once, so a call costs little more than
+    the launch itself.  Holds the tensors it points into."""
+
+    def __init__(self, d_in: int, d_out: int, bit_set: Sequence[int], counts: Sequence[int],
+                 packed: Sequence[Optional[torch.Tensor]], chan_idx: Sequence[Optional[torch.Tensor]],
+                 lut: Sequence[Optional[torch.Tensor]], act_idx: Optional[torch.Tensor],
+                 W_act: Optional[torch.Tensor], colptr: Optional[torch.Tensor],
+                 row_idx: Optional[torch.Tensor], delta: Optional[torch.Tensor]):
+        n = len(bit_set)
+        if row_idx is None or row_idx.numel() == 0:      # no entries of O_q: the library takes a null colptr
+            colptr = row_idx = delta = None
+        k_act = 0 if act_idx is None else int(act_idx.numel())
+        ld_act = d_out if W_act is None or k_act == 0 else _rows(W_act)[2]
+        self._keep = (list(packed), list(chan_idx), list(lut), act_idx, W_act, colptr, row_idx, delta)
+        self.d_in, self.d_out = int(d_in), int(d_out)
+        self._head = (self.d_out, (_i32 * n)(*bit_set), n, (_i64 * n)(*counts),
+                      (_vp * n)(*[_ptr(t) for t in packed]), (_vp * n)(*[_ptr(t) for t in chan_idx]),
+                      (_vp * n)(*[_ptr(t) for t in lut]), _ptr(act_idx), _ptr(W_act), k_act, ld_act,
+                      _ptr(colptr), _ptr(row_idx), _ptr(delta))
+        self._ws_bytes = {}
+        self._fn = lib().cmpq_lut_matvec
+
+    def __call__(self, X: torch.Tensor, Y: torch.Tensor, ws: Workspace) -> None:
+        if X.dtype != torch.float16 or Y.dtype != torch.float32:
+            raise ValueError("X must be fp16 and Y fp32")
+        m, d_in, ldx = _rows(X)
+        m2, do, ldy = _rows(Y)
+        if (m2, do) != (m, self.d_out) or d_in != self.d_in:
+            raise ValueError("X must be [m, d_in] and Y [m, d_out]")
+        need = self._ws_bytes.get(m)
+        if need is None:
+            need = self._ws_bytes[m] = workspace_bytes(OP_LUT_MATVEC, d_in, do, m)
+        buf = ws.get(need)
+        rc = self._fn(_ptr(X), m, d_in, ldx, *self._head, _ptr(Y), ldy, buf.data_ptr(), buf.numel(), _stream())
+        if rc:
+            _check(rc, "cmpq_lut_matvec")
+
+
 def lut_matvec(X: torch.Tensor, d_out: int, bit_set: Sequence[int], counts: Sequence[int],
                packed: Sequence[Optional[torch.Tensor]], chan_idx: Sequence[Optional[torch.Tensor]],
                lut: Sequence[Optional[torch.Tensor]], act_idx: Optional[torch.Tensor],
                W_act: Optional[torch.Tensor], colptr: Optional[torch.Tensor], row_idx: Optional[torch.Tensor],
                delta: Optional[torch.Tensor], Y: torch.Tensor, ws: Workspace) -> None:
     """Fig. 4: ``Y [m, d_out] fp32 = X [m, d_in] fp16 @ W_hat`` from the stored format."""
-    if X.dtype != torch.float16 or Y.dtype != torch.float32:
-        raise ValueError("X must be fp16 and Y fp32")
-    m, d_in, ldx = _rows(X)
-    m2, do, ldy = _rows(Y)
-    if (m2, do) != (m, d_out):
-        raise ValueError("Y must be [m, d_out]")
-    n = len(bit_set)
-    bs = (_i32 * n)(*bit_set)
-    cn = (_i64 * n)(*counts)
-    pk = (_vp * n)(*[_ptr(t) for t in packed])
-    ci = (_vp * n)(*[_ptr(t) for t in chan_idx])
-    lt = (_vp * n)(*[_ptr(t) for t in lut])
-    if row_idx is None or row_idx.numel() == 0:      # no entries of O_q: the library takes a null colptr
-        colptr = row_idx = delta = None
-    k_act = 0 if act_idx is None else int(act_idx.numel())
-    ld_act = d_out if W_act is None or k_act == 0 else _rows(W_act)[2]
-    buf = ws.get(workspace_bytes(OP_LUT_MATVEC, d_in, d_out, m))
-    _check(lib().cmpq_lut_matvec(_ptr(X), m, d_in, ldx, d_out, bs, n, cn, pk, ci, lt, _ptr(act_idx), _ptr(W_act),
-                                 k_act, ld_act, _ptr(colptr), _ptr(row_idx), _ptr(delta), _ptr(Y), ldy,
-                                 _ptr(buf), buf.numel(), _stream()),
-           "cmpq_lut_matvec")
+    LutMatvecCall(_rows(X)[1], d_out, bit_set, counts, packed, chan_idx, lut, act_idx, W_act, colptr,
+                  row_idx, delta)(X, Y, ws)
 
 
 def act_stats_norm(X: torch.Tensor, norm: int, acc: torch.Tensor, stat: Optional[torch.Tensor], accumulate: bool,

@@ -8,15 +8,17 @@
 // output: the 2^b products X[t,i] * lut_i[c] are formed once per row and the rest is table
 // look-ups and additions.  HBM bound: b/8 bytes per weight are read once per token.
 //
-//   * lut_matvec_kernel<B>: a workgroup takes 2048 outputs (a lane 32 consecutive ones:
-//     exactly B words of a row) and a slab of 128 rows of one width, 32 rows per
-//     wavefront.  The per-row tables of 4 rows at a time sit in LDS (one entry per lane
-//     to fill); a code becomes the address of its table entry with two instructions.
-//     The 16 entries of a table lie in 16 banks, so the look-ups of a wavefront never
-//     collide.  The four wavefronts' sums are added in order and written as one partial
-//     row per slab.
-//   * lut_matvec_finish_kernel: per output, the partial rows in slab order, then the O_act
-//     rows, then the column's O_q entries - every sum sequential, so the result is
+//   * lut_matvec_kernel: one launch, two kinds of workgroup, each leaving one partial row
+//     per token:
+//       - a slab of 128 packed rows of one width times 2048 outputs (a lane 32 consecutive
+//         outputs: exactly B words of a row; 32 rows per wavefront).  The per-row tables of
+//         4 rows at a time sit in LDS (one entry per lane to fill); a code becomes the
+//         address of its table entry with two instructions.  The 16 entries of a table lie
+//         in 16 banks, so the look-ups of a wavefront never collide.
+//       - a slab of 128 rows of O_act (FP16 rows) times 2048 outputs.
+//     The four wavefronts' sums are added in order.
+//   * lut_matvec_finish_kernel: per output, the partial rows in order (packed slabs, O_act
+//     slabs), then the column's O_q entries - every sum in a fixed order, so the result is
 //     reproducible bit for bit.
 //   * cmpq_outliers_by_column / cmpq_gather_channels prepare O_q and O_act for this once,
 //     at quantization time.
@@ -43,8 +45,38 @@ struct LmWidth {
 
 struct LmArgs {
     LmWidth w[kMaxWidths];
-    int n_widths, rows_per_wave, n_slabs_total;
+    int n_widths, rows_per_wave;
+    int n_lut_slabs, n_act_slabs;  // blockIdx.y: O_act slabs first, then the packed slabs
+    int n_rows_total;              // partial rows per token: packed slabs, then O_act slabs
+    int act_vec_ok;                // W_act rows may be read 16 bytes at a time
+    const int32_t *act_idx;
+    const __half *W_act;
+    int64_t k_act, ld_act;
 };
+
+constexpr int kRedStride = CMPQ_WAVE + 1;  // sums of output k of all lanes: 64 floats, padded by one
+constexpr int kRedFloats = kOutPerLane * kRedStride;
+
+// The four wavefronts' sums of a 2048-output tile, added in wavefront order, into a partial
+// row.  Lanes write with stride 1 and read with stride 65: no bank is hit twice by a
+// half-wavefront either way.
+__device__ __forceinline__ void store_partial(const float (&acc)[kOutPerLane], float (*red)[kRedFloats],
+                                              float *__restrict__ prow, int64_t d_out) {
+    const int lane = threadIdx.x & (CMPQ_WAVE - 1), wave = threadIdx.x / CMPQ_WAVE;
+#pragma unroll
+    for (int k = 0; k < kOutPerLane; ++k) red[wave][k * kRedStride + lane] = acc[k];
+    __syncthreads();
+    for (int c = threadIdx.x; c < kTileOut; c += kThreads) {
+        const int64_t o = (int64_t)blockIdx.x * kTileOut + c;
+        if (o < d_out) {
+            const int at = (c & (kOutPerLane - 1)) * kRedStride + (c / kOutPerLane);
+            float t = red[0][at];
+#pragma unroll
+            for (int wv = 1; wv < kWaves; ++wv) t += red[wv][at];
+            prow[o] = t;
+        }
+    }
+}
 
 // Code k of a lane's 32 codes held in w[0..B-1] (one bit-field extract, two instructions
 // where the code straddles two words).
@@ -65,16 +97,15 @@ __device__ __forceinline__ uint32_t entry_offset(uint32_t code, uint32_t base) {
 
 template <int B>
 __device__ __forceinline__ void lut_slab(const __half *__restrict__ X, int64_t ldx, int64_t d_out,
-                                         const LmWidth &wd, int slab, int rows_per_wave, int n_slabs_total,
+                                         const LmWidth &wd, int slab, int rows_per_wave, int n_rows_total,
                                          float *__restrict__ partial, float (*tbl_all)[2][kGroup * 16],
-                                         float (*red)[kTileOut]) {
+                                         float (*red)[kRedFloats]) {
     constexpr int K = 1 << B;
     // per wavefront: two buffers of kGroup row tables (K floats each)
     float(*tbl)[2][kGroup * 16] = tbl_all;
     const int lane = threadIdx.x & (CMPQ_WAVE - 1), wave = threadIdx.x / CMPQ_WAVE;
     const int64_t token = blockIdx.z;
     const __half *x = X + token * ldx;
-    const int64_t o0 = (int64_t)blockIdx.x * kTileOut + (int64_t)lane * kOutPerLane;
     const int64_t word0 = (int64_t)blockIdx.x * (kTileOut / 32) * B + (int64_t)lane * B;
     const int64_t r0 = ((int64_t)slab * kWaves + wave) * rows_per_wave;
     const int64_t r1 = min(wd.rows, r0 + rows_per_wave);
@@ -142,87 +173,164 @@ __device__ __forceinline__ void lut_slab(const __half *__restrict__ X, int64_t l
                 for (int j = 0; j < B; ++j) w[g][j] = wn[g][j];
         }
     }
-    // the four wavefronts' sums, added in wavefront order
-#pragma unroll
-    for (int k = 0; k < kOutPerLane; ++k) red[wave][lane * kOutPerLane + k] = acc[k];
-    __syncthreads();
-    float *prow = partial + (token * n_slabs_total + wd.slab0 + slab) * d_out;
-    for (int c = threadIdx.x; c < kTileOut; c += kThreads) {
-        const int64_t o = (int64_t)blockIdx.x * kTileOut + c;
-        if (o < d_out) {
-            float t = red[0][c];
-#pragma unroll
-            for (int wv = 1; wv < kWaves; ++wv) t += red[wv][c];
-            prow[o] = t;
-        }
-    }
-    (void)o0;
+    store_partial(acc, red, partial + (token * n_rows_total + wd.slab0 + slab) * d_out, d_out);
 }
 
-// grid: (tiles of 2048 outputs, slabs of all widths one after the other, tokens)
+// A slab of O_act: 8 rows of FP16 weights per wavefront times their inputs (few rows, so
+// short slabs: the loop over rows is bound by latency).  A lane reads its 32 outputs of a
+// row as four 16-byte pieces, two rows in flight; the rows' inputs are fetched up front,
+// one per lane.
+constexpr int kActRowsPerWave = 8;
+
+__device__ __forceinline__ void act_slab(const __half *__restrict__ X, int64_t ldx, int64_t d_out,
+                                         const LmArgs &a, int slab, float *__restrict__ partial,
+                                         float (*red)[kRedFloats]) {
+    const int lane = threadIdx.x & (CMPQ_WAVE - 1), wave = threadIdx.x / CMPQ_WAVE;
+    const int64_t token = blockIdx.z;
+    const __half *x = X + token * ldx;
+    const int64_t o0 = (int64_t)blockIdx.x * kTileOut + (int64_t)lane * kOutPerLane;
+    const int64_t r0 = ((int64_t)slab * kWaves + wave) * kActRowsPerWave;
+    const int n = (int)max((int64_t)0, min(a.k_act - r0, (int64_t)kActRowsPerWave));
+    float acc[kOutPerLane];
+#pragma unroll
+    for (int k = 0; k < kOutPerLane; ++k) acc[k] = 0.f;
+    const float x_mine = lane < n ? __half2float(x[a.act_idx[r0 + lane]]) : 0.f;
+    // every row's input in a scalar register (rows past the count: 0), read before lanes part ways
+    float xs[kActRowsPerWave];
+#pragma unroll
+    for (int j = 0; j < kActRowsPerWave; ++j)
+        xs[j] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x_mine), j));
+    const bool vec = a.act_vec_ok && o0 + kOutPerLane <= d_out;
+    if (vec) {
+#pragma unroll
+        for (int j = 0; j < kActRowsPerWave; j += 2) {
+            if (j >= n) break;
+            uint4 raw[2][4];
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                // the second row of an odd count is read again from the first: its input is 0
+                const int64_t r = r0 + (j + u < n ? j + u : j);
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    raw[u][q] = reinterpret_cast<const uint4 *>(a.W_act + r * a.ld_act + o0)[q];
+            }
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const float xi = xs[j + u];
+                const __half2 *h = reinterpret_cast<const __half2 *>(raw[u]);
+#pragma unroll
+                for (int k = 0; k < kOutPerLane / 2; ++k) {
+                    const float2 wv = __half22float2(h[k]);
+                    acc[2 * k] = fmaf(xi, wv.x, acc[2 * k]);
+                    acc[2 * k + 1] = fmaf(xi, wv.y, acc[2 * k + 1]);
+                }
+            }
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < kActRowsPerWave; ++j) {
+            if (j >= n) break;
+            const float xi = xs[j];
+            const __half *wrow = a.W_act + (r0 + j) * a.ld_act + o0;
+#pragma unroll
+            for (int k = 0; k < kOutPerLane; ++k)
+                if (o0 + k < d_out) acc[k] = fmaf(xi, __half2float(wrow[k]), acc[k]);
+        }
+    }
+    store_partial(acc, red, partial + (token * a.n_rows_total + a.n_lut_slabs + slab) * d_out, d_out);
+}
+
+// grid: (tiles of 2048 outputs; O_act slabs, then packed slabs of all widths one after the
+// other; tokens)
 __global__ __launch_bounds__(kThreads) void lut_matvec_kernel(const __half *__restrict__ X, int64_t ldx,
                                                                int64_t d_out, LmArgs a,
                                                                float *__restrict__ partial) {
     __shared__ float tbl[kWaves][2][kGroup * 16];
-    __shared__ float red[kWaves][kTileOut];
+    __shared__ float red[kWaves][kRedFloats];
+    int y = (int)blockIdx.y;
+    if (y < a.n_act_slabs) {
+        act_slab(X, ldx, d_out, a, y, partial, red);
+        return;
+    }
+    y -= a.n_act_slabs;
     int j = 0;
-    while (j + 1 < a.n_widths && (int)blockIdx.y >= a.w[j + 1].slab0) ++j;
+    while (j + 1 < a.n_widths && y >= a.w[j + 1].slab0) ++j;
     const LmWidth &wd = a.w[j];
-    const int slab = (int)blockIdx.y - wd.slab0;
+    const int slab = y - wd.slab0;
     switch (wd.bits) {
-        case 1: lut_slab<1>(X, ldx, d_out, wd, slab, a.rows_per_wave, a.n_slabs_total, partial, tbl, red); break;
-        case 2: lut_slab<2>(X, ldx, d_out, wd, slab, a.rows_per_wave, a.n_slabs_total, partial, tbl, red); break;
-        case 3: lut_slab<3>(X, ldx, d_out, wd, slab, a.rows_per_wave, a.n_slabs_total, partial, tbl, red); break;
-        default: lut_slab<4>(X, ldx, d_out, wd, slab, a.rows_per_wave, a.n_slabs_total, partial, tbl, red); break;
+        case 1: lut_slab<1>(X, ldx, d_out, wd, slab, a.rows_per_wave, a.n_rows_total, partial, tbl, red); break;
+        case 2: lut_slab<2>(X, ldx, d_out, wd, slab, a.rows_per_wave, a.n_rows_total, partial, tbl, red); break;
+        case 3: lut_slab<3>(X, ldx, d_out, wd, slab, a.rows_per_wave, a.n_rows_total, partial, tbl, red); break;
+        default: lut_slab<4>(X, ldx, d_out, wd, slab, a.rows_per_wave, a.n_rows_total, partial, tbl, red); break;
     }
 }
 
-constexpr int kFinWaves = 16;  // parts a column's sum is shared out over
-constexpr int kFinThreads = kFinWaves * CMPQ_WAVE;
+constexpr int kFinCols = 16;  // outputs per workgroup
+constexpr int kFinRuns = kThreads / kFinCols;
 
-// 64 consecutive outputs per workgroup.  Wavefront w adds the slabs and O_act rows whose
-// index is w modulo 16 (a lane per output: whole cache lines), and takes 4 of the 64
-// columns of O_q, 16 lanes per column (lane l the entries l, l+16, ...).  All partial sums
-// meet in LDS and are added in a fixed order.
-__global__ __launch_bounds__(kFinThreads) void lut_matvec_finish_kernel(
+// 16 consecutive outputs per workgroup of 256 lanes.
+//   * O_q: 16 lanes per column; lane l takes the column's entries l, l+16, ... (8 in flight)
+//     and adds them in that order.
+//   * partial rows: cut into 16 runs of consecutive rows; lane (run, output) adds its run in
+//     row order (4 loads in flight).
+// Per output, the 16 run sums are added in run order, then the 16 O_q sums in lane order.
+__global__ __launch_bounds__(kThreads) void lut_matvec_finish_kernel(
     const __half *__restrict__ X, int64_t ldx, int64_t d_out, const float *__restrict__ partial,
-    int n_slabs_total, const int32_t *__restrict__ act_idx, const __half *__restrict__ W_act,
-    int64_t k_act, int64_t ld_act, const int32_t *__restrict__ colptr,
-    const int32_t *__restrict__ row_idx, const float *__restrict__ delta, float *__restrict__ Y,
-    int64_t ldy) {
-    __shared__ float dense[kFinWaves][CMPQ_WAVE];
-    __shared__ float sparse[CMPQ_WAVE][17];
-    const int lane = threadIdx.x & (CMPQ_WAVE - 1), wave = threadIdx.x / CMPQ_WAVE;
+    int n_rows_total, const int32_t *__restrict__ colptr, const int32_t *__restrict__ row_idx,
+    const float *__restrict__ delta, float *__restrict__ Y, int64_t ldy) {
+    constexpr int U = 8;
+    __shared__ float part[kFinRuns][kFinCols + 1];
+    __shared__ float sp[kFinCols][kFinRuns + 1];
+    const int hi = threadIdx.x / kFinCols, lo = threadIdx.x % kFinCols;
     const int64_t token = blockIdx.y;
-    const int64_t o = (int64_t)blockIdx.x * CMPQ_WAVE + lane;
+    const int64_t o0 = (int64_t)blockIdx.x * kFinCols;
     const __half *x = X + token * ldx;
-    float y = 0.f;
-    if (o < d_out) {
-        const float *p = partial + token * n_slabs_total * d_out + o;
-        for (int sl = wave; sl < n_slabs_total; sl += kFinWaves) y += p[(int64_t)sl * d_out];
-        for (int64_t j = wave; j < k_act; j += kFinWaves)
-            y += __half2float(x[act_idx[j]]) * __half2float(W_act[j * ld_act + o]);
-    }
-    dense[wave][lane] = y;
-    {
-        const int col = wave * 4 + (lane >> 4), slot = lane & 15;
-        const int64_t oc = (int64_t)blockIdx.x * CMPQ_WAVE + col;
-        float t = 0.f;
-        if (colptr && oc < d_out) {
-            const int e1 = colptr[oc + 1];
-            for (int e = colptr[oc] + slot; e < e1; e += 16) t += __half2float(x[row_idx[e]]) * delta[e];
+    // O_q of column o0 + hi, entries lo, lo + 16, ...
+    float t = 0.f;
+    if (colptr && o0 + hi < d_out) {
+        const int e1 = colptr[o0 + hi + 1];
+        for (int e = colptr[o0 + hi] + lo; e < e1; e += 16 * U) {
+            int32_t r[U];
+            float d[U], xv[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int ee = e + 16 * u;
+                const bool ok = ee < e1;
+                r[u] = ok ? row_idx[ee] : -1;
+                d[u] = ok ? delta[ee] : 0.f;
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) xv[u] = r[u] >= 0 ? __half2float(x[r[u]]) : 0.f;
+#pragma unroll
+            for (int u = 0; u < U; ++u) t = fmaf(xv[u], d[u], t);
         }
-        sparse[col][slot] = t;
     }
+    sp[hi][lo] = t;
+    // partial rows of output o0 + lo, run hi
+    float y = 0.f;
+    if (o0 + lo < d_out) {
+        const int per = (n_rows_total + kFinRuns - 1) / kFinRuns;
+        const int r0 = hi * per, r1 = min(n_rows_total, r0 + per);
+        const float *p = partial + token * n_rows_total * d_out + o0 + lo;
+        int r = r0;
+        for (; r + 4 <= r1; r += 4) {
+            float v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) v[u] = p[(int64_t)(r + u) * d_out];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) y += v[u];
+        }
+        for (; r < r1; ++r) y += p[(int64_t)r * d_out];
+    }
+    part[hi][lo] = y;
     __syncthreads();
-    if (wave == 0 && o < d_out) {
-        float t = 0.f;
+    if (threadIdx.x < kFinCols && o0 + threadIdx.x < d_out) {
+        float a = 0.f, b = 0.f;
 #pragma unroll
-        for (int w = 0; w < kFinWaves; ++w) t += dense[w][lane];
-        float u = 0.f;
+        for (int q = 0; q < kFinRuns; ++q) a += part[q][threadIdx.x];
 #pragma unroll
-        for (int sidx = 0; sidx < 16; ++sidx) u += sparse[lane][sidx];
-        Y[token * ldy + o] = t + u;
+        for (int q = 0; q < 16; ++q) b += sp[threadIdx.x][q];
+        Y[token * ldy + o0 + threadIdx.x] = a + b;
     }
 }
 
@@ -351,9 +459,10 @@ size_t cmpq_ws_outliers_by_column(int64_t d_out, int64_t n_out) {
     return align_up((size_t)(d_out + 1) * sizeof(int32_t), 256) * 2 + align_up((size_t)n_out * 4, 256) * 2;
 }
 
-// Upper bound without the per-width counts: every width may end with a partly filled slab.
+// Upper bound without the per-width counts: every width and O_act may end with a partly
+// filled slab.
 size_t cmpq_ws_lut_matvec(int64_t d_in, int64_t d_out, int64_t m) {
-    const int64_t slabs = cdiv(d_in, (int64_t)kWaves * 8) + kMaxWidths;  // the smallest slabs, one partly filled per width
+    const int64_t slabs = cdiv(d_in, (int64_t)kWaves * 8) + kMaxWidths + 2;  // the smallest slabs
     return align_up((size_t)m * (size_t)slabs * (size_t)d_out * sizeof(float), 256);
 }
 
@@ -437,9 +546,10 @@ extern "C" int cmpq_lut_matvec(const void *X, int64_t m, int64_t d_in, int64_t l
     const int64_t tiles = cdiv(d_out, kTileOut);
     int rpw = kMaxRowsPerWave;
     while (rpw > 8 && tiles * total_slabs(counts_host, n_set, rpw) * m < 512) rpw /= 2;
-    const int64_t n_slabs64 = total_slabs(counts_host, n_set, rpw);
-    if (n_slabs64 > 65535) return CMPQ_ESHAPE;
-    const int n_slabs = (int)n_slabs64;
+    const int64_t n_lut = total_slabs(counts_host, n_set, rpw);
+    const int64_t n_act = cdiv(k_act, (int64_t)kWaves * kActRowsPerWave);
+    const int64_t n_rows = n_lut + n_act;
+    if (n_rows > 65535) return CMPQ_ESHAPE;
     if (!ws || reinterpret_cast<uintptr_t>(ws) % 256 != 0 || ws_bytes < cmpq_ws_lut_matvec(d_in, d_out, m))
         return CMPQ_EWORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -448,7 +558,14 @@ extern "C" int cmpq_lut_matvec(const void *X, int64_t m, int64_t d_in, int64_t l
     LmArgs a;
     a.n_widths = 0;
     a.rows_per_wave = rpw;
-    a.n_slabs_total = n_slabs;
+    a.n_lut_slabs = (int)n_lut;
+    a.n_act_slabs = (int)n_act;
+    a.n_rows_total = (int)n_rows;
+    a.act_idx = act_idx;
+    a.W_act = reinterpret_cast<const __half *>(W_act);
+    a.k_act = k_act;
+    a.ld_act = ld_act;
+    a.act_vec_ok = reinterpret_cast<uintptr_t>(W_act) % 16 == 0 && ld_act % 8 == 0;
     int slab0 = 0;
     for (int j = 0; j < n_set; ++j) {
         if (counts_host[j] == 0) continue;
@@ -462,14 +579,14 @@ extern "C" int cmpq_lut_matvec(const void *X, int64_t m, int64_t d_in, int64_t l
         wd.bits = bit_set[j];
         slab0 += (int)cdiv(wd.rows, (int64_t)kWaves * rpw);
     }
-    if (a.n_widths > 0) {
-        const dim3 grid((unsigned)tiles, (unsigned)n_slabs, (unsigned)m);
+    for (int j = a.n_widths; j < kMaxWidths; ++j) a.w[j] = LmWidth{nullptr, nullptr, nullptr, 0, 0, 0, 0};
+    if (n_rows > 0) {
+        const dim3 grid((unsigned)tiles, (unsigned)n_rows, (unsigned)m);
         lut_matvec_kernel<<<grid, kThreads, 0, s>>>(Xh, ldx, d_out, a, partial);
     }
-    const dim3 fgrid((unsigned)cdiv(d_out, CMPQ_WAVE), (unsigned)m);
-    lut_matvec_finish_kernel<<<fgrid, kFinThreads, 0, s>>>(Xh, ldx, d_out, partial, n_slabs, act_idx,
-                                                       reinterpret_cast<const __half *>(W_act), k_act, ld_act,
-                                                       colptr, row_idx, delta, Y, ldy);
+    const dim3 fgrid((unsigned)cdiv(d_out, kFinCols), (unsigned)m);
+    lut_matvec_finish_kernel<<<fgrid, kThreads, 0, s>>>(Xh, ldx, d_out, partial, (int)n_rows, colptr, row_idx,
+                                                    delta, Y, ldy);
     CMPQ_LAUNCH_CHECK();
     return CMPQ_OK;
 }

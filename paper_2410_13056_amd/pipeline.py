@@ -158,6 +158,16 @@ class Deployed:
     colptr: torch.Tensor              # [d_out+1] int32: O_q grouped by output column
     row_idx: torch.Tensor             # [k_q] int32
     delta: torch.Tensor               # [k_q] fp32: outlier value minus the table level it overrides
+    _call: Optional[B.LutMatvecCall] = None
+
+    def matvec_into(self, X: torch.Tensor, Y: torch.Tensor, ws: B.Workspace) -> None:
+        """Y [m, d_out] fp32 = X [m, d_in] fp16 times this weight; the call's fixed arguments
+        are marshalled at the first use."""
+        if self._call is None:
+            self._call = B.LutMatvecCall(self.d_in, self.d_out, self.bit_set, self.counts, self.packed,
+                                         self.chan_idx, self.lut, self.act_idx, self.W_act, self.colptr,
+                                         self.row_idx, self.delta)
+        self._call(X, Y, ws)
 
 
 def prepare_deployment(r: LayerResult, ws: Optional[B.Workspace] = None,
@@ -185,8 +195,7 @@ def lut_matvec(dep: Deployed, X: torch.Tensor, ws: Optional[B.Workspace] = None,
     ws = ws or B.Workspace(X.device)
     Y = torch.empty((X.shape[0], dep.d_out), dtype=torch.float32, device=X.device)
     with _stage(timer, "lut_matvec"):
-        B.lut_matvec(X, dep.d_out, dep.bit_set, dep.counts, dep.packed, dep.chan_idx, dep.lut, dep.act_idx,
-                     dep.W_act, dep.colptr, dep.row_idx, dep.delta, Y, ws)
+        dep.matvec_into(X, Y, ws)
     return Y
 
 
