@@ -227,6 +227,24 @@ def lut_matvec(X: np.ndarray, W: np.ndarray, centroids: np.ndarray, codes: np.nd
     return Y
 
 
+def rtn_quantize(W: np.ndarray, bits: np.ndarray, group: int = 128):
+    """App. A.2: round-to-nearest with the uniform quantizer of Sec. 3, groups of `group`
+    consecutive outputs per input channel.  Returns ``(codes uint8[d_in, d_out],
+    scale float32[d_in, n_groups], zero float32[d_in, n_groups], err_ch float64[d_in])``."""
+    W = _c(W)
+    d_in, d_out = W.shape
+    ng = (d_out + group - 1) // group
+    codes = np.zeros((d_in, d_out), np.uint8)
+    scale = np.zeros((d_in, ng), np.float32)
+    zero = np.zeros((d_in, ng), np.float32)
+    err = np.zeros(d_in, np.float64)
+    rc = lib().orc_rtn_quantize(_p(W), _dtype_code(W), ctypes.c_int64(d_in), ctypes.c_int64(d_out),
+                                ctypes.c_int64(d_out), _p(_c(bits, np.uint8)), ctypes.c_int64(int(group)),
+                                _p(codes), _p(scale), _p(zero), _p(err))
+    assert rc == 0, rc
+    return codes, scale, zero, err
+
+
 def quantize_layer(W: np.ndarray, X: np.ndarray, bit_set: Sequence[int], avg_bits: float,
                    rho_act_ppm: int = 4500, rho_q_ppm: int = 500, iters: int = 20,
                    sumsq: Optional[np.ndarray] = None, score: int = SCORE_RESIDUAL) -> dict:

@@ -19,6 +19,8 @@
  *   orc_weight_outliers  O_q: largest |W' - W'_q|           (Sec. 3.2.2)
  *   orc_pack             per-width code matrices + FP16 look-up tables (Sec. 5.1, Fig. 4)
  *   orc_dequant_error    W_hat = W_q + O and ||X (W - W_hat)|| (Sec. 3.2.2; App. B.3 eq. Delta Y)
+ * Beside the path: orc_lut_matvec (Fig. 4), orc_act_stats_norm (App. Tab. 13) and
+ * orc_rtn_quantize (App. A.2: the uniform quantizer of Sec. 3 in place of K-means).
  *
  * Parity pins (tests/ -m "not gpu") cover every function here; none is
  * "parity unpinned" except the k-means trajectory on large inputs, which is
@@ -546,6 +548,75 @@ int orc_lut_matvec(const void *X, int xdtype, int64_t m, int64_t d_in, int64_t l
         }
     }
     free(excl);
+    return 0;
+}
+
+/* ---- App. A.2 (Tab. 10): CMPQ with the uniform quantizer ---------------------------------- */
+
+/*
+ * Round-to-nearest with the uniform quantizer of Sec. 3 in place of K-means: the widths still
+ * come from Algorithm 1 (bits[i] per input channel), the channels of O_act stay in FP16
+ * (bits[i] outside 1..4), and there is no O_q.  Channel i is cut into groups of `group`
+ * consecutive outputs (the last one may be shorter); per group, with N = bits[i]:
+ *
+ *     Delta = (max - min) / (2^N - 1),   code = Clamp(round((w - min) / Delta), 0, 2^N - 1)
+ *
+ * and the weight is rebuilt as min + code * Delta.
+ *
+ * Readings (the paper gives the formula in real numbers):
+ *   - the code is decided in fp32: Delta and the quotient are single IEEE operations on
+ *     floats, the rounding is to nearest with ties to even;
+ *   - a group whose weights are all equal has Delta = 0, code 0, and is rebuilt exactly;
+ *   - min and Delta are kept as fp32: zero[i, g] and scale[i, g], n_groups per channel;
+ *   - the error of a channel is sum_o (w - (min + code * Delta))^2 with the rebuilt value
+ *     taken exactly (fp64); a channel of O_act contributes the error of rounding to FP16.
+ */
+int orc_rtn_quantize(const void *W, int dtype, int64_t d_in, int64_t d_out, int64_t ldw,
+                     const uint8_t *bits, int64_t group, uint8_t *codes, float *scale, float *zero,
+                     double *err_ch) {
+    if (!W || !bits || !codes || !scale || !zero || group < 1) return -1;
+    const int64_t n_groups = (d_out + group - 1) / group;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < d_in; ++i) {
+        const int N = bits[i];
+        double e = 0.0;
+        if (N < 1 || N > 4) {
+            for (int64_t o = 0; o < d_out; ++o) {
+                const double w = load_elem(W, dtype, i * ldw + o);
+                const double d = w - half_to_double(double_to_half(w));
+                codes[i * d_out + o] = 0;
+                e += d * d;
+            }
+            for (int64_t g = 0; g < n_groups; ++g) scale[i * n_groups + g] = zero[i * n_groups + g] = 0.0f;
+        } else {
+            const float top = (float)((1 << N) - 1);
+            for (int64_t g = 0; g < n_groups; ++g) {
+                const int64_t o0 = g * group, o1 = o0 + group < d_out ? o0 + group : d_out;
+                float lo = (float)load_elem(W, dtype, i * ldw + o0), hi = lo;
+                for (int64_t o = o0 + 1; o < o1; ++o) {
+                    const float w = (float)load_elem(W, dtype, i * ldw + o);
+                    if (w < lo) lo = w;
+                    if (w > hi) hi = w;
+                }
+                const float delta = (hi - lo) / top;
+                scale[i * n_groups + g] = delta;
+                zero[i * n_groups + g] = lo;
+                for (int64_t o = o0; o < o1; ++o) {
+                    const float w = (float)load_elem(W, dtype, i * ldw + o);
+                    float q = 0.0f;
+                    if (delta != 0.0f) {
+                        q = rintf((w - lo) / delta);
+                        if (q < 0.0f) q = 0.0f;
+                        if (q > top) q = top;
+                    }
+                    codes[i * d_out + o] = (uint8_t)q;
+                    const double d = (double)w - ((double)lo + (double)q * (double)delta);
+                    e += d * d;
+                }
+            }
+        }
+        if (err_ch) err_ch[i] = e;
+    }
     return 0;
 }
 

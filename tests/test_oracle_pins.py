@@ -631,3 +631,111 @@ def test_act_stats_other_norms_match_numpy_and_chunking(orc):
     Y[7, 1] = 5.0
     s2, s1, si = (orc.act_stats_norm(Y, k)[1] for k in (0, 1, 2))
     assert s2[0] > s2[1] and s1[0] > s1[1] and si[1] > si[0]
+
+
+# ----------------------------------------------------------------------------- App. A.2: uniform quantizer
+
+def test_rtn_hand_examples(orc):
+    """Sec. 3, uniform quantizer: a ramp 0..7 at 3 bits has Delta = 1 and is its own code; the
+    same ramp shifted to 8..15 at 2 bits has Delta = 7/3 and the codes worked out by hand
+    (quotients 0, .43, .86, 1.29, 1.71, 2.14, 2.57, 3)."""
+    W = np.arange(16, dtype=np.float32).reshape(2, 8)
+    codes, scale, zero, err = orc.rtn_quantize(W, np.array([3, 2], np.uint8), group=8)
+    assert codes[0].tolist() == [0, 1, 2, 3, 4, 5, 6, 7]
+    assert codes[1].tolist() == [0, 0, 1, 1, 2, 2, 3, 3]
+    assert scale[:, 0].tolist() == [1.0, np.float32(7) / np.float32(3)] and zero[:, 0].tolist() == [0.0, 8.0]
+    assert err[0] == 0.0
+    # row 1: distances to the levels 8, 10.33, 12.67, 15 are 0, 1, 1/3, 2/3, 2/3, 1/3, 1, 0
+    assert abs(err[1] - (2 * 1.0 + 2 * (1 / 9) + 2 * (4 / 9))) < 1e-6
+
+
+def test_rtn_code_is_the_nearest_level_and_error_is_within_half_a_step(orc):
+    """Sec. 3: round-to-nearest on a uniform grid is the nearest of the 2^N levels
+    min + k Delta (checked by brute force over the levels in fp64), so no weight moves by
+    more than Delta / 2, and the ends of the range are kept exactly."""
+    rng = np.random.default_rng(3)
+    for N in (1, 2, 3, 4):
+        W = (rng.standard_t(4, size=(6, 300)) * 0.02).astype(np.float16)
+        bits = np.full(6, N, np.uint8)
+        codes, scale, zero, err = orc.rtn_quantize(W, bits, group=128)
+        assert scale.shape == (6, 3)
+        w = W.astype(np.float64)
+        for i in range(6):
+            for g in range(3):
+                sl = slice(128 * g, min(300, 128 * (g + 1)))
+                lo, d = float(zero[i, g]), float(scale[i, g])
+                assert lo == w[i, sl].min() and codes[i, sl].max() == 2 ** N - 1 and codes[i, sl].min() == 0
+                levels = lo + d * np.arange(2 ** N)
+                dist = np.abs(w[i, sl][:, None] - levels[None, :])
+                best = dist.min(axis=1)
+                mine = dist[np.arange(dist.shape[0]), codes[i, sl]]
+                assert np.all(mine <= best + 1e-6 * d)          # nearest, up to a rounding of the quotient
+                assert np.all(mine <= d / 2 * (1 + 1e-6))
+                assert abs(levels[-1] - w[i, sl].max()) <= 1e-6 * max(abs(levels[-1]), d)
+            rebuilt = np.concatenate([float(zero[i, g]) + float(scale[i, g]) * codes[i, 128 * g:128 * (g + 1)]
+                                      for g in range(3)])
+            assert abs(err[i] - np.sum((w[i] - rebuilt) ** 2)) <= 1e-12 * max(err[i], 1e-30)
+
+
+def test_rtn_groups_are_independent_and_ragged_tail_is_its_own_group(orc):
+    """App. A.2: group-wise ranges.  Two groups of very different spread must each use their
+    own step; a quantizer that ignored the group boundary would give the narrow group one
+    code only."""
+    rng = np.random.default_rng(5)
+    wide = rng.uniform(-8, 8, 128)
+    narrow = rng.uniform(-0.01, 0.01, 40)                     # a ragged last group of 40
+    W = np.concatenate([wide, narrow])[None, :].astype(np.float32)
+    codes, scale, zero, _ = orc.rtn_quantize(W, np.array([4], np.uint8), group=128)
+    assert scale.shape == (1, 2) and scale[0, 0] > 100 * scale[0, 1] > 0
+    assert len(set(codes[0, 128:].tolist())) > 8               # the narrow group uses its own 16 levels
+    alone = orc.rtn_quantize(W[:, 128:].copy(), np.array([4], np.uint8), group=128)
+    assert np.array_equal(alone[0][0], codes[0, 128:]) and alone[1][0, 0] == scale[0, 1]
+
+
+def test_rtn_invariances_and_degenerate_groups(orc):
+    """Facts any min/max uniform quantizer obeys: scaling by a power of two keeps the codes
+    and scales Delta (and the error by its square); quantizing the rebuilt weights again
+    changes nothing; codes are monotone in the weight; a constant group has Delta = 0 and is
+    exact; channels kept in FP16 get no codes and only the FP16 rounding error."""
+    rng = np.random.default_rng(7)
+    W = rng.normal(0, 0.05, size=(5, 256)).astype(np.float32)
+    W[3, :128] = 0.125                                          # a constant group
+    bits = np.array([2, 3, 4, 3, 16], np.uint8)
+    codes, scale, zero, err = orc.rtn_quantize(W, bits, group=128)
+    c4, s4, z4, e4 = orc.rtn_quantize(W * 4, bits, group=128)
+    assert np.array_equal(c4, codes) and np.array_equal(s4, scale * 4) and np.array_equal(z4, zero * 4)
+    assert np.allclose(e4[:4], err[:4] * 16, rtol=1e-12)
+    assert scale[3, 0] == 0 and zero[3, 0] == np.float32(0.125) and not codes[3, :128].any()
+    assert not codes[4].any() and not scale[4].any()
+    w16 = W[4].astype(np.float16).astype(np.float64)
+    assert abs(err[4] - np.sum((W[4].astype(np.float64) - w16) ** 2)) <= 1e-12 * err[4]
+    for i in range(4):
+        for g in range(2):
+            sl = slice(128 * g, 128 * (g + 1))
+            order = np.argsort(W[i, sl], kind="stable")
+            assert np.all(np.diff(codes[i, sl][order].astype(int)) >= 0)
+    rebuilt = np.zeros_like(W)
+    for g in range(2):
+        sl = slice(128 * g, 128 * (g + 1))
+        rebuilt[:, sl] = (zero[:, g:g + 1].astype(np.float64) + scale[:, g:g + 1].astype(np.float64) * codes[:, sl]).astype(np.float32)
+    again = orc.rtn_quantize(rebuilt, bits, group=128)
+    assert (again[0][:4] != codes[:4]).mean() < 1e-3           # fp32 rounding of a rebuilt level may flip a tie
+    assert np.all(again[3][:4] <= 1e-10 + 1e-3 * err[:4])
+
+
+def test_rtn_more_bits_never_hurt_and_kmeans_is_no_worse_on_heavy_tails(orc):
+    """App. A.2 / Tab. 10: the uniform grid wastes levels on heavy-tailed weights, so the
+    K-means levels of Sec. 3.2.1 give a smaller error at the same width; and for either
+    quantizer the error falls as the width grows."""
+    rng = np.random.default_rng(11)
+    W = (rng.standard_t(3, size=(4, 512)) * 0.02).astype(np.float16)
+    prev = None
+    for N in (2, 3, 4):
+        bits = np.full(4, N, np.uint8)
+        e_rtn = orc.rtn_quantize(W, bits, group=512)[3]
+        cent, codes = orc.kmeans(W, bits, iters=20)
+        e_km = orc.dequant_error(W, cent, codes, bits)[0]
+        assert np.all(e_km < e_rtn)
+        if prev is not None:
+            assert np.all(e_rtn < prev)
+        prev = e_rtn
