@@ -95,6 +95,35 @@ def deployed_matvec(P, B, torch, out, layers, wl, acts, reps):
                          "algorithmic_bytes_per_token": algo_bytes}}
 
 
+def rtn_variant(P, B, torch, out, layers, wl, reps):
+    """CMPQ with the uniform quantizer (App. A.2): O_act at 0.5 %, Algorithm 1 and round-to-nearest
+    in groups of 128 for every layer of the block, on the d_in x d_out copies already in HBM.
+    HBM bound: a weight is read once (2 bytes) and its code written once (1 byte)."""
+    dev = next(iter(out.values())).codes.device
+    ws = B.Workspace(dev)
+
+    def block():
+        for name, _ in layers:
+            r = out[name]
+            P.quantize_layer_rtn(r.W_t, r.sumsq, wl.bit_set, wl.avg_bits, 5000, 128, ws, with_error=True,
+                                 transposed=True)
+
+    block()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        block()
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / reps
+    algo = sum(out[n].d_in * out[n].d_out * (out[n].W_t.element_size() + 1)
+               + out[n].d_in * -(-out[n].d_out // 128) * 8 for n, _ in layers)
+    return {"what": "uniform round-to-nearest in groups of 128 with the widths of Algorithm 1, all layers, "
+                    "with the reconstruction error",
+            "ms_per_block": dt * 1e3, "Mparams_per_s": wl.params / dt / 1e6,
+            "roofline": {"bound": "hbm", "achieved": algo / dt / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                         "frac": algo / dt / 1e9 / HBM_PEAK_GBS, "algorithmic_bytes_per_block": algo}}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -110,6 +139,9 @@ def main():
                          "that overlap would blur (0: skip)")
     ap.add_argument("--deploy-reps", type=int, default=20,
                     help="repetitions of the one-token product with the deployed block (Fig. 4), reported "
+                         "beside the headline figure; 0: skip")
+    ap.add_argument("--rtn-reps", type=int, default=5,
+                    help="repetitions of the block through the uniform-quantizer variant (App. A.2), reported "
                          "beside the headline figure; 0: skip")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (outside the timed region): under "
@@ -211,6 +243,8 @@ def main():
         }
     if args.deploy_reps > 0:
         line["deployed_matvec"] = deployed_matvec(P, B, torch, out, layers, wl, acts, args.deploy_reps)
+    if args.rtn_reps > 0:
+        line["rtn_variant"] = rtn_variant(P, B, torch, out, layers, wl, args.rtn_reps)
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(wl, weights, acts)
     print(json.dumps(line))

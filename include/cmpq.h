@@ -224,6 +224,30 @@ int cmpq_pack(const uint8_t *codes, int64_t d_in, int64_t d_out, const uint8_t *
               uint16_t *const *lut, void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * App. A.2 (Tab. 10): CMPQ with the uniform quantizer of Sec. 3 in place of K-means.  Widths
+ * still come from cmpq_allocate_bits, channels of O_act (bits outside 1..4) stay FP16, there
+ * is no O_q.  Channel i is cut into groups of `group` consecutive outputs (a power of two in
+ * 8..512; the last group of a channel may be shorter) and per group, with N = bits[i],
+ *     Delta = (max - min) / (2^N - 1),  code = Clamp(round((w - min) / Delta), 0, 2^N - 1),
+ * decided in fp32 (one IEEE division each, ties to even); Delta = 0 gives code 0.  The weight
+ * is rebuilt as zero + code * scale.
+ *   W       [d_in, d_out], CMPQ_F16 or CMPQ_F32, leading dimension ldw >= d_out.
+ *   bits    [d_in] u8 from cmpq_allocate_bits.
+ *   codes   [d_in, d_out] u8 out, dense (0 on channels of O_act).
+ *   scale, zero  [d_in, ceil(d_out / group)] fp32 out: Delta and min of each group (0, 0 on
+ *           channels of O_act).
+ *   err_ch  [d_in] fp64 out, nullable: sum_o (w - (zero + code * scale))^2 with the rebuilt
+ *           value exact; on channels of O_act the error of rounding to FP16.
+ * All pointers are device pointers.  No workspace.  Status: CMPQ_STATUS_NONFINITE (the codes of
+ * a group that holds a non-finite weight are unspecified).  Errors: CMPQ_EINVAL for a null
+ * pointer, an unknown dtype or a group size that is not a power of two in 8..512; CMPQ_ESHAPE
+ * for ldw < d_out.
+ */
+int cmpq_rtn_quantize(const void *W, int dtype, int64_t d_in, int64_t d_out, int64_t ldw,
+                      const uint8_t *bits, int64_t group, uint8_t *codes, float *scale, float *zero,
+                      double *err_ch, int32_t *status, void *stream);
+
+/*
  * Reconstruction W_hat = W_q + O (Sec. 3.2.2) and the output error of App. B.3,
  * Delta Y = X (W - W_hat), with cross-channel products of X dropped:
  *   W_hat[i,o] = fp16(W[i,o]) for channels with bits outside 1..4 and for the entries of

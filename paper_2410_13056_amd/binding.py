@@ -31,7 +31,8 @@ NORM_L2, NORM_L1, NORM_LINF = 0, 1, 2
 EXPORTS = ("cmpq_workspace_bytes", "cmpq_strerror", "cmpq_count_ppm", "cmpq_act_stats",
            "cmpq_transpose", "cmpq_allocate_bits", "cmpq_extract_outliers",
            "cmpq_kmeans_quantize", "cmpq_pack", "cmpq_dequant_error", "cmpq_set_kmeans_algorithm",
-           "cmpq_gather_channels", "cmpq_outliers_by_column", "cmpq_lut_matvec", "cmpq_act_stats_norm")
+           "cmpq_gather_channels", "cmpq_outliers_by_column", "cmpq_lut_matvec", "cmpq_act_stats_norm",
+           "cmpq_rtn_quantize")
 
 _i64, _i32, _int, _vp, _dbl, _sz = (ctypes.c_int64, ctypes.c_int32, ctypes.c_int, ctypes.c_void_p,
                                     ctypes.c_double, ctypes.c_size_t)
@@ -74,6 +75,7 @@ def lib() -> ctypes.CDLL:
         L.cmpq_outliers_by_column.argtypes = [_vp, _vp, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
         L.cmpq_lut_matvec.argtypes = [_vp, _i64, _i64, _i64, _i64, _vp, _int, _vp, _vp, _vp, _vp, _vp, _vp,
                                       _i64, _i64, _vp, _vp, _vp, _vp, _i64, _vp, _sz, _vp]
+        L.cmpq_rtn_quantize.argtypes = [_vp, _int, _i64, _i64, _i64, _vp, _i64, _vp, _vp, _vp, _vp, _vp, _vp]
         for name in EXPORTS[3:]:
             getattr(L, name).restype = _int
         _lib = L
@@ -315,3 +317,21 @@ def act_stats_norm(X: torch.Tensor, norm: int, acc: torch.Tensor, stat: Optional
     _check(lib().cmpq_act_stats_norm(_ptr(X), _dtype(X), n, d_in, ldx, int(norm), _ptr(acc), _ptr(stat),
                                      int(bool(accumulate)), _ptr(buf), buf.numel(), _ptr(status), _stream()),
            "cmpq_act_stats_norm")
+
+
+def rtn_quantize(W: torch.Tensor, bits: torch.Tensor, group: int, codes: torch.Tensor, scale: torch.Tensor,
+                 zero: torch.Tensor, err_ch: Optional[torch.Tensor] = None,
+                 status: Optional[torch.Tensor] = None) -> None:
+    """App. A.2: round-to-nearest with the uniform quantizer, groups of `group` outputs per channel."""
+    d_in, d_out, ldw = _rows(W)
+    n_groups = -(-d_out // int(group)) if group > 0 else 0
+    if tuple(codes.shape) != (d_in, d_out) or not codes.is_contiguous() or codes.dtype != torch.uint8:
+        raise ValueError("codes must be a contiguous uint8 [d_in, d_out]")
+    for t in (scale, zero):
+        if tuple(t.shape) != (d_in, n_groups) or not t.is_contiguous() or t.dtype != torch.float32:
+            raise ValueError("scale and zero must be contiguous float32 [d_in, ceil(d_out / group)]")
+    if err_ch is not None and (err_ch.numel() != d_in or err_ch.dtype != torch.float64):
+        raise ValueError("err_ch must be float64 [d_in]")
+    _check(lib().cmpq_rtn_quantize(_ptr(W), _dtype(W), d_in, d_out, ldw, _ptr(bits), int(group), _ptr(codes),
+                                   _ptr(scale), _ptr(zero), _ptr(err_ch), _ptr(status), _stream()),
+           "cmpq_rtn_quantize")

@@ -144,6 +144,61 @@ def quantize_layer(W: torch.Tensor, sumsq: torch.Tensor, bit_set: Sequence[int],
 
 
 @dataclasses.dataclass
+class RtnResult:
+    """A layer quantized with the uniform quantizer (App. A.2; device tensors)."""
+    d_in: int
+    d_out: int
+    group: int
+    bit_set: Sequence[int]
+    counts: List[int]
+    sumsq: torch.Tensor
+    act_idx: torch.Tensor             # [k_act] int32: channels of O_act
+    chan_mask: torch.Tensor
+    bits: torch.Tensor                # [d_in] uint8 (16 = O_act channel)
+    codes: torch.Tensor               # [d_in, d_out] uint8
+    scale: torch.Tensor               # [d_in, ceil(d_out/group)] fp32 step of each group
+    zero: torch.Tensor                # [d_in, ceil(d_out/group)] fp32 minimum of each group
+    err_ch: Optional[torch.Tensor] = None
+    W_t: Optional[torch.Tensor] = None
+
+
+def quantize_layer_rtn(W: torch.Tensor, sumsq: torch.Tensor, bit_set: Sequence[int], avg_bits: float,
+                       rho_act_ppm: int = 5000, group: int = 128, ws: Optional[B.Workspace] = None,
+                       with_error: bool = False, status: Optional[torch.Tensor] = None,
+                       transposed: bool = False, timer: Optional[StageTimer] = None) -> RtnResult:
+    """App. A.2 (Tab. 10): the channel-wise widths of Algorithm 1 with round-to-nearest on a
+    uniform grid per group of `group` outputs instead of K-means; 0.5 % of the channels stay
+    FP16 by default and no single weights are taken out."""
+    ws = ws or B.Workspace(W.device)
+    dev = W.device
+    if transposed:
+        Wt = W
+        d_in, d_out = W.shape
+    else:
+        d_out, d_in = W.shape
+        Wt = torch.empty((d_in, d_out), dtype=W.dtype, device=dev)
+        with _stage(timer, "transpose"):
+            B.transpose(W, Wt)
+    k_act = B.count_ppm(rho_act_ppm, d_in)
+    act_idx = torch.empty(k_act, dtype=torch.int32, device=dev)
+    chan_mask = torch.empty(d_in, dtype=torch.uint8, device=dev)
+    with _stage(timer, "outlier_channels"):
+        B.extract_channel_outliers(sumsq, k_act, act_idx, chan_mask, ws)
+    bits = torch.empty(d_in, dtype=torch.uint8, device=dev)
+    with _stage(timer, "allocate_bits"):
+        counts = B.allocate_bits(sumsq, chan_mask, k_act, bit_set, avg_bits, bits, ws)
+    n_groups = -(-d_out // group)
+    codes = torch.empty((d_in, d_out), dtype=torch.uint8, device=dev)
+    scale = torch.empty((d_in, n_groups), dtype=torch.float32, device=dev)
+    zero = torch.empty((d_in, n_groups), dtype=torch.float32, device=dev)
+    err_ch = torch.empty(d_in, dtype=torch.float64, device=dev) if with_error else None
+    with _stage(timer, "rtn"):
+        B.rtn_quantize(Wt, bits, group, codes, scale, zero, err_ch, status)
+    return RtnResult(d_in, d_out, group, tuple(bit_set), counts, sumsq, act_idx, chan_mask, bits, codes,
+                     scale, zero, err_ch, Wt)
+
+
+@dataclasses.dataclass
 class Deployed:
     """A layer as the product kernel of Fig. 4 reads it (device tensors)."""
     d_in: int

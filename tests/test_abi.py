@@ -123,6 +123,14 @@ def test_host_side_argument_errors(L):
                              fake, 64, None, 0, None) == -5
     assert L.cmpq_lut_matvec(fake, 70000, 8, 8, 64, bs, 3, one, ptrs, ptrs, ptrs, None, None, 0, 64, None, None, None,
                              fake, 64, fake, 1 << 40, None) == -2                              # too many tokens
+    # the uniform quantizer
+    assert L.cmpq_rtn_quantize(fake, 0, 4, 64, 64, fake, 96, fake, fake, fake, None, None, None) == -1    # group no power of two
+    assert L.cmpq_rtn_quantize(fake, 0, 4, 64, 64, fake, 4, fake, fake, fake, None, None, None) == -1     # group below 8
+    assert L.cmpq_rtn_quantize(fake, 0, 4, 64, 64, fake, 1024, fake, fake, fake, None, None, None) == -1  # group above 512
+    assert L.cmpq_rtn_quantize(fake, 2, 4, 64, 64, fake, 128, fake, fake, fake, None, None, None) == -1   # dtype
+    assert L.cmpq_rtn_quantize(fake, 0, 4, 64, 64, fake, 128, None, fake, fake, None, None, None) == -1   # no codes
+    assert L.cmpq_rtn_quantize(fake, 0, 4, 64, 32, fake, 128, fake, fake, fake, None, None, None) == -2   # ldw < d_out
+    assert L.cmpq_rtn_quantize(None, 0, 0, 64, 64, None, 128, None, None, None, None, None, None) == 0    # nothing to do
 
 
 def test_product_package_does_not_reach_the_oracle():
