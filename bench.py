@@ -124,6 +124,38 @@ def rtn_variant(P, B, torch, out, layers, wl, reps):
                          "frac": algo / dt / 1e9 / HBM_PEAK_GBS, "algorithmic_bytes_per_block": algo}}
 
 
+def retarget(P, B, torch, out, layers, wl, reps):
+    """Other average widths for the block just quantized, from one kept K-means run per width
+    (the cost the paper's closing section names): the first pass becomes a row-wise choice."""
+    dev = next(iter(out.values())).codes.device
+    ws = B.Workspace(dev)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    caches = {n: P.build_width_cache(out[n].W_t, wl.bit_set, wl.iters, ws, transposed=True) for n, _ in layers}
+    torch.cuda.synchronize()
+    build_ms = (time.perf_counter() - t0) * 1e3
+    lo, hi = min(wl.bit_set), max(wl.bit_set)
+    budgets = [lo + (hi - lo) * f for f in (0.2, 0.5, 0.8)]
+
+    def block(avg):
+        for n, _ in layers:
+            P.quantize_layer_from_cache(caches[n], out[n].sumsq, avg, wl.rho_act_ppm, wl.rho_q_ppm, ws,
+                                        with_error=True)
+
+    block(budgets[0])
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        for avg in budgets:
+            block(avg)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / (reps * len(budgets))
+    return {"what": "the block at another average width from kept per-width runs (one stream; without "
+                    "statistics, orientation and the first K-means pass)",
+            "budgets": [round(b, 3) for b in budgets], "build_ms": build_ms,
+            "ms_per_budget": dt * 1e3, "Mparams_per_s": wl.params / dt / 1e6}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -140,6 +172,8 @@ def main():
     ap.add_argument("--deploy-reps", type=int, default=20,
                     help="repetitions of the one-token product with the deployed block (Fig. 4), reported "
                          "beside the headline figure; 0: skip")
+    ap.add_argument("--retarget-reps", type=int, default=2,
+                    help="repetitions of three other average widths from kept per-width runs; 0: skip")
     ap.add_argument("--rtn-reps", type=int, default=5,
                     help="repetitions of the block through the uniform-quantizer variant (App. A.2), reported "
                          "beside the headline figure; 0: skip")
@@ -243,6 +277,8 @@ def main():
         }
     if args.deploy_reps > 0:
         line["deployed_matvec"] = deployed_matvec(P, B, torch, out, layers, wl, acts, args.deploy_reps)
+    if args.retarget_reps > 0:
+        line["retarget"] = retarget(P, B, torch, out, layers, wl, args.retarget_reps)
     if args.rtn_reps > 0:
         line["rtn_variant"] = rtn_variant(P, B, torch, out, layers, wl, args.rtn_reps)
     if not args.no_cpu_baseline:

@@ -199,6 +199,27 @@ int cmpq_kmeans_quantize(const void *W, int dtype, int64_t d_in, int64_t d_out, 
                          void *stream);
 
 /*
+ * The preliminary quantization of Sec. 3.2.2 for a new budget, from runs kept per width.
+ * Levels and codes of a channel depend on its own weights and width only, so after one
+ * cmpq_kmeans_quantize per width b = bit_set[j] over ALL channels (bits[i] = b for every i, no
+ * out_idx), the first pass for any allocation `bits` is a row-wise choice:
+ *   centroids[i,:], codes[i,:] = those of run j with bit_set[j] == bits[i];
+ *   +infinity / 0 for a channel whose width is outside 1..4 (O_act) or not in bit_set -
+ * exactly what cmpq_kmeans_quantize(W, bits, no out_idx) writes.  This is what makes
+ * retargeting a quantized layer to another average width cheap (the cost the paper's closing
+ * section names): only the steps after the first pass run again.
+ *   bit_set             [n_set] host, distinct widths in 1..4, n_set <= 4.
+ *   centroids_by_width  host array of n_set device pointers to [d_in, 16] fp32.
+ *   codes_by_width      host array of n_set device pointers to [d_in, d_out] u8.
+ *   centroids [d_in, 16] fp32, codes [d_in, d_out] u8: out.
+ * No workspace.  Errors: CMPQ_EINVAL for null pointers, a width outside 1..4 or listed twice.
+ */
+int cmpq_select_by_width(const uint8_t *bits, int64_t d_in, int64_t d_out, const int32_t *bit_set,
+                         int n_set, const float *const *centroids_by_width,
+                         const uint8_t *const *codes_by_width, float *centroids, uint8_t *codes,
+                         void *stream);
+
+/*
  * Process-wide choice between the two implementations of the Lloyd rounds of Sec. 3.2.1
  * for fp16 weights with unit importance.  Both produce identical levels and codes; the
  * direct one exists for measurements against the plain ALU roofline.  Host only; takes

@@ -32,7 +32,7 @@ EXPORTS = ("cmpq_workspace_bytes", "cmpq_strerror", "cmpq_count_ppm", "cmpq_act_
            "cmpq_transpose", "cmpq_allocate_bits", "cmpq_extract_outliers",
            "cmpq_kmeans_quantize", "cmpq_pack", "cmpq_dequant_error", "cmpq_set_kmeans_algorithm",
            "cmpq_gather_channels", "cmpq_outliers_by_column", "cmpq_lut_matvec", "cmpq_act_stats_norm",
-           "cmpq_rtn_quantize")
+           "cmpq_rtn_quantize", "cmpq_select_by_width")
 
 _i64, _i32, _int, _vp, _dbl, _sz = (ctypes.c_int64, ctypes.c_int32, ctypes.c_int, ctypes.c_void_p,
                                     ctypes.c_double, ctypes.c_size_t)
@@ -76,6 +76,7 @@ def lib() -> ctypes.CDLL:
         L.cmpq_lut_matvec.argtypes = [_vp, _i64, _i64, _i64, _i64, _vp, _int, _vp, _vp, _vp, _vp, _vp, _vp,
                                       _i64, _i64, _vp, _vp, _vp, _vp, _i64, _vp, _sz, _vp]
         L.cmpq_rtn_quantize.argtypes = [_vp, _int, _i64, _i64, _i64, _vp, _i64, _vp, _vp, _vp, _vp, _vp, _vp]
+        L.cmpq_select_by_width.argtypes = [_vp, _i64, _i64, _vp, _int, _vp, _vp, _vp, _vp, _vp]
         for name in EXPORTS[3:]:
             getattr(L, name).restype = _int
         _lib = L
@@ -335,3 +336,21 @@ def rtn_quantize(W: torch.Tensor, bits: torch.Tensor, group: int, codes: torch.T
     _check(lib().cmpq_rtn_quantize(_ptr(W), _dtype(W), d_in, d_out, ldw, _ptr(bits), int(group), _ptr(codes),
                                    _ptr(scale), _ptr(zero), _ptr(err_ch), _ptr(status), _stream()),
            "cmpq_rtn_quantize")
+
+
+def select_by_width(bits: torch.Tensor, bit_set: Sequence[int], centroids_by_width: Sequence[torch.Tensor],
+                    codes_by_width: Sequence[torch.Tensor], centroids: torch.Tensor, codes: torch.Tensor) -> None:
+    """The first K-means pass for the allocation `bits`, chosen row by row from one kept run per width."""
+    d_in, d_out = codes.shape
+    n = len(bit_set)
+    for c, k in zip(centroids_by_width, codes_by_width):
+        if tuple(c.shape) != (d_in, KMAX) or tuple(k.shape) != (d_in, d_out) or not c.is_contiguous() \
+                or not k.is_contiguous() or c.dtype != torch.float32 or k.dtype != torch.uint8:
+            raise ValueError("kept runs must be contiguous [d_in,16] fp32 levels and [d_in,d_out] uint8 codes")
+    if not codes.is_contiguous() or not centroids.is_contiguous() or tuple(centroids.shape) != (d_in, KMAX):
+        raise ValueError("outputs must be contiguous [d_in,16] and [d_in,d_out]")
+    _check(lib().cmpq_select_by_width(_ptr(bits), d_in, d_out, (_i32 * n)(*bit_set), n,
+                                      (_vp * n)(*[_ptr(t) for t in centroids_by_width]),
+                                      (_vp * n)(*[_ptr(t) for t in codes_by_width]), _ptr(centroids), _ptr(codes),
+                                      _stream()),
+           "cmpq_select_by_width")

@@ -76,39 +76,36 @@ def activation_stats(X: torch.Tensor, ws: B.Workspace, acc: Optional[torch.Tenso
     return acc, sumsq
 
 
-def quantize_layer(W: torch.Tensor, sumsq: torch.Tensor, bit_set: Sequence[int], avg_bits: float,
-                   rho_act_ppm: int = 4500, rho_q_ppm: int = 500, iters: int = 20,
-                   ws: Optional[B.Workspace] = None, score: int = B.SCORE_RESIDUAL,
-                   with_error: bool = False, keep_prelim: bool = False,
-                   status: Optional[torch.Tensor] = None, transposed: bool = False,
-                   timer: Optional[StageTimer] = None) -> LayerResult:
-    """Quantizes one layer.  `W` is the framework's [d_out, d_in] weight (or already
-    d_in x d_out with ``transposed=True``); `sumsq` comes from `activation_stats`."""
-    ws = ws or B.Workspace(W.device)
-    dev = W.device
+def _oriented(W: torch.Tensor, transposed: bool, timer):
+    """The d_in x d_out copy the steps run on."""
     if transposed:
-        Wt = W
-        d_in, d_out = W.shape
-    else:
-        d_out, d_in = W.shape
-        Wt = torch.empty((d_in, d_out), dtype=W.dtype, device=dev)
-        with _stage(timer, "transpose"):
-            B.transpose(W, Wt)
-    # O_act (Sec. 3.2.2)
+        return W
+    d_out, d_in = W.shape
+    Wt = torch.empty((d_in, d_out), dtype=W.dtype, device=W.device)
+    with _stage(timer, "transpose"):
+        B.transpose(W, Wt)
+    return Wt
+
+
+def _channels_and_widths(sumsq, d_in, bit_set, avg_bits, rho_act_ppm, ws, timer):
+    """O_act (Sec. 3.2.2), then Algorithm 1 on W' = W - O_act."""
+    dev = sumsq.device
     k_act = B.count_ppm(rho_act_ppm, d_in)
     act_idx = torch.empty(k_act, dtype=torch.int32, device=dev)
     chan_mask = torch.empty(d_in, dtype=torch.uint8, device=dev)
     with _stage(timer, "outlier_channels"):
         B.extract_channel_outliers(sumsq, k_act, act_idx, chan_mask, ws)
-    # Algorithm 1 on W' = W - O_act
     bits = torch.empty(d_in, dtype=torch.uint8, device=dev)
     with _stage(timer, "allocate_bits"):
         counts = B.allocate_bits(sumsq, chan_mask, k_act, bit_set, avg_bits, bits, ws)
-    # preliminary quantization W'_q
-    cent1 = torch.empty((d_in, B.KMAX), dtype=torch.float32, device=dev)
-    codes1 = torch.empty((d_in, d_out), dtype=torch.uint8, device=dev)
-    with _stage(timer, "kmeans"):
-        B.kmeans_quantize(Wt, bits, None, 0, None, iters, cent1, codes1, ws, status)
+    return act_idx, chan_mask, bits, counts
+
+
+def _after_first_pass(Wt, sumsq, bit_set, counts, act_idx, chan_mask, bits, cent1, codes1, rho_q_ppm, iters,
+                      ws, score, with_error, keep_prelim, status, timer) -> LayerResult:
+    """O_q from the preliminary quantization, the final quantization, the stored format."""
+    dev = Wt.device
+    d_in, d_out = Wt.shape
     # O_q: largest |W' - W'_q|
     k_q = B.count_ppm(rho_q_ppm, d_in * d_out)
     out_idx = torch.empty(k_q, dtype=torch.int32, device=dev)
@@ -143,6 +140,82 @@ def quantize_layer(W: torch.Tensor, sumsq: torch.Tensor, bit_set: Sequence[int],
     return res
 
 
+def quantize_layer(W: torch.Tensor, sumsq: torch.Tensor, bit_set: Sequence[int], avg_bits: float,
+                   rho_act_ppm: int = 4500, rho_q_ppm: int = 500, iters: int = 20,
+                   ws: Optional[B.Workspace] = None, score: int = B.SCORE_RESIDUAL,
+                   with_error: bool = False, keep_prelim: bool = False,
+                   status: Optional[torch.Tensor] = None, transposed: bool = False,
+                   timer: Optional[StageTimer] = None) -> LayerResult:
+    """Quantizes one layer.  `W` is the framework's [d_out, d_in] weight (or already
+    d_in x d_out with ``transposed=True``); `sumsq` comes from `activation_stats`."""
+    ws = ws or B.Workspace(W.device)
+    dev = W.device
+    Wt = _oriented(W, transposed, timer)
+    d_in, d_out = Wt.shape
+    act_idx, chan_mask, bits, counts = _channels_and_widths(sumsq, d_in, bit_set, avg_bits, rho_act_ppm, ws, timer)
+    # preliminary quantization W'_q
+    cent1 = torch.empty((d_in, B.KMAX), dtype=torch.float32, device=dev)
+    codes1 = torch.empty((d_in, d_out), dtype=torch.uint8, device=dev)
+    with _stage(timer, "kmeans"):
+        B.kmeans_quantize(Wt, bits, None, 0, None, iters, cent1, codes1, ws, status)
+    return _after_first_pass(Wt, sumsq, bit_set, counts, act_idx, chan_mask, bits, cent1, codes1, rho_q_ppm,
+                             iters, ws, score, with_error, keep_prelim, status, timer)
+
+
+@dataclasses.dataclass
+class WidthCache:
+    """One preliminary K-means run per width over all channels of a layer (device tensors):
+    what `quantize_layer_from_cache` needs to retarget the layer to any average width."""
+    bit_set: Sequence[int]
+    iters: int
+    W_t: torch.Tensor                 # [d_in, d_out]
+    centroids: List[torch.Tensor]     # per width: [d_in, 16] fp32
+    codes: List[torch.Tensor]         # per width: [d_in, d_out] uint8
+
+
+def build_width_cache(W: torch.Tensor, bit_set: Sequence[int], iters: int = 20,
+                      ws: Optional[B.Workspace] = None, status: Optional[torch.Tensor] = None,
+                      transposed: bool = False, timer: Optional[StageTimer] = None) -> WidthCache:
+    """Runs the preliminary K-means of Sec. 3.2.2 once per width of `bit_set` over every
+    channel.  A channel's levels and codes do not depend on the other channels' widths, so
+    these runs hold the first pass of every possible allocation."""
+    ws = ws or B.Workspace(W.device)
+    dev = W.device
+    Wt = _oriented(W, transposed, timer)
+    d_in, d_out = Wt.shape
+    cents, codes = [], []
+    for b in bit_set:
+        bits_b = torch.full((d_in,), int(b), dtype=torch.uint8, device=dev)
+        c = torch.empty((d_in, B.KMAX), dtype=torch.float32, device=dev)
+        k = torch.empty((d_in, d_out), dtype=torch.uint8, device=dev)
+        with _stage(timer, "kmeans"):
+            B.kmeans_quantize(Wt, bits_b, None, 0, None, iters, c, k, ws, status)
+        cents.append(c), codes.append(k)
+    return WidthCache(tuple(bit_set), iters, Wt, cents, codes)
+
+
+def quantize_layer_from_cache(cache: WidthCache, sumsq: torch.Tensor, avg_bits: float,
+                              rho_act_ppm: int = 4500, rho_q_ppm: int = 500,
+                              ws: Optional[B.Workspace] = None, score: int = B.SCORE_RESIDUAL,
+                              with_error: bool = False, keep_prelim: bool = False,
+                              status: Optional[torch.Tensor] = None,
+                              timer: Optional[StageTimer] = None) -> LayerResult:
+    """`quantize_layer` for another average width (or other outlier fractions) of a layer
+    whose per-width runs are kept: the first K-means pass is a row-wise choice among them,
+    everything after it runs as usual.  Same results as `quantize_layer`, bit for bit."""
+    ws = ws or B.Workspace(cache.W_t.device)
+    dev = cache.W_t.device
+    d_in, d_out = cache.W_t.shape
+    act_idx, chan_mask, bits, counts = _channels_and_widths(sumsq, d_in, cache.bit_set, avg_bits, rho_act_ppm,
+                                                            ws, timer)
+    cent1 = torch.empty((d_in, B.KMAX), dtype=torch.float32, device=dev)
+    codes1 = torch.empty((d_in, d_out), dtype=torch.uint8, device=dev)
+    with _stage(timer, "select_by_width"):
+        B.select_by_width(bits, cache.bit_set, cache.centroids, cache.codes, cent1, codes1)
+    return _after_first_pass(cache.W_t, sumsq, cache.bit_set, counts, act_idx, chan_mask, bits, cent1, codes1,
+                             rho_q_ppm, cache.iters, ws, score, with_error, keep_prelim, status, timer)
+
+
 @dataclasses.dataclass
 class RtnResult:
     """A layer quantized with the uniform quantizer (App. A.2; device tensors)."""
@@ -171,22 +244,9 @@ def quantize_layer_rtn(W: torch.Tensor, sumsq: torch.Tensor, bit_set: Sequence[i
     FP16 by default and no single weights are taken out."""
     ws = ws or B.Workspace(W.device)
     dev = W.device
-    if transposed:
-        Wt = W
-        d_in, d_out = W.shape
-    else:
-        d_out, d_in = W.shape
-        Wt = torch.empty((d_in, d_out), dtype=W.dtype, device=dev)
-        with _stage(timer, "transpose"):
-            B.transpose(W, Wt)
-    k_act = B.count_ppm(rho_act_ppm, d_in)
-    act_idx = torch.empty(k_act, dtype=torch.int32, device=dev)
-    chan_mask = torch.empty(d_in, dtype=torch.uint8, device=dev)
-    with _stage(timer, "outlier_channels"):
-        B.extract_channel_outliers(sumsq, k_act, act_idx, chan_mask, ws)
-    bits = torch.empty(d_in, dtype=torch.uint8, device=dev)
-    with _stage(timer, "allocate_bits"):
-        counts = B.allocate_bits(sumsq, chan_mask, k_act, bit_set, avg_bits, bits, ws)
+    Wt = _oriented(W, transposed, timer)
+    d_in, d_out = Wt.shape
+    act_idx, chan_mask, bits, counts = _channels_and_widths(sumsq, d_in, bit_set, avg_bits, rho_act_ppm, ws, timer)
     n_groups = -(-d_out // group)
     codes = torch.empty((d_in, d_out), dtype=torch.uint8, device=dev)
     scale = torch.empty((d_in, n_groups), dtype=torch.float32, device=dev)

@@ -131,6 +131,14 @@ def test_host_side_argument_errors(L):
     assert L.cmpq_rtn_quantize(fake, 0, 4, 64, 64, fake, 128, None, fake, fake, None, None, None) == -1   # no codes
     assert L.cmpq_rtn_quantize(fake, 0, 4, 64, 32, fake, 128, fake, fake, fake, None, None, None) == -2   # ldw < d_out
     assert L.cmpq_rtn_quantize(None, 0, 0, 64, 64, None, 128, None, None, None, None, None, None) == 0    # nothing to do
+    # retargeting
+    two = (ctypes.c_void_p * 2)(256, 256)
+    assert L.cmpq_select_by_width(fake, 4, 64, (i32 * 2)(2, 2), 2, two, two, fake, fake, None) == -1      # width twice
+    assert L.cmpq_select_by_width(fake, 4, 64, (i32 * 2)(2, 7), 2, two, two, fake, fake, None) == -1      # width outside 1..4
+    assert L.cmpq_select_by_width(fake, 4, 64, (i32 * 2)(2, 3), 2, two, (ctypes.c_void_p * 2)(256, None), fake, fake,
+                                  None) == -1                                                             # a run missing
+    assert L.cmpq_select_by_width(fake, 4, 64, (i32 * 2)(2, 3), 2, two, two, None, fake, None) == -1      # no output
+    assert L.cmpq_select_by_width(None, 0, 64, (i32 * 2)(2, 3), 2, two, two, None, None, None) == 0       # nothing to do
 
 
 def test_product_package_does_not_reach_the_oracle():
