@@ -326,6 +326,20 @@ def _streams_for(device: torch.device, n: int):
     return have[:n]
 
 
+def assign_layers(sizes: Dict[str, int], streams: int) -> List[tuple]:
+    """Shares independent layers out over `streams` queues: largest first (equal sizes in the
+    order given), each to the queue with the least work so far, the lowest-numbered of equals.
+    Returns (name, queue) pairs in launch order."""
+    order = sorted(sizes, key=lambda n: -sizes[n])
+    load = [0] * streams
+    plan = []
+    for name in order:
+        j = min(range(streams), key=lambda t: load[t])
+        load[j] += sizes[name]
+        plan.append((name, j))
+    return plan
+
+
 def quantize_block(weights: Dict[str, torch.Tensor], acts: Dict[str, torch.Tensor], layers, bit_set,
                    avg_bits: float, rho_act_ppm: int, rho_q_ppm: int, iters: int,
                    ws=None, with_error: bool = False, status: Optional[torch.Tensor] = None,
@@ -359,14 +373,11 @@ def quantize_block(weights: Dict[str, torch.Tensor], acts: Dict[str, torch.Tenso
     side = _streams_for(dev, streams)
     for st in side:
         st.wait_stream(main)
-    # largest layer first, each to the stream with the least work so far
-    order = sorted(layers, key=lambda l: -weights[l[0]].numel())
-    load = [0] * streams
+    x_of = dict(layers)
     stats: Dict[str, tuple] = {}          # x_key -> (sumsq, event, stream index)
     results: Dict[str, LayerResult] = {}
-    for name, x_key in order:
-        j = min(range(streams), key=lambda t: load[t])
-        load[j] += weights[name].numel()
+    for name, j in assign_layers({n: weights[n].numel() for n, _ in layers}, streams):
+        x_key = x_of[name]
         with torch.cuda.stream(side[j]):
             if x_key not in stats:
                 sumsq = activation_stats(acts[x_key], ws[j], status=status, timer=timer)[1]
