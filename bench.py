@@ -77,19 +77,41 @@ def deployed_matvec(P, B, torch, out, layers, wl, acts, reps):
         algo_bytes += d.W_act.numel() * 2 + d.row_idx.numel() * 8 + d.colptr.numel() * 4 + d.d_in * 2 + d.d_out * 4
     ys = {name: torch.empty((1, deps[name].d_out), dtype=torch.float32, device=dev) for name, _ in layers}
 
-    def token():
+    def per_layer():
         for name, _ in layers:
             deps[name].matvec_into(xs[name], ys[name], ws)
 
-    token()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(reps):
-        token()
-    torch.cuda.synchronize()
-    dt = (time.perf_counter() - t0) / reps
-    return {"what": "Y = x W_hat for one token through all layers of the block, from the stored format",
+    # products that read the same input can run side by side (query/key/value; gate/up)
+    by_input = {}
+    for name, x_key in layers:
+        by_input.setdefault(x_key, []).append(name)
+    groups = [(P.group_products([deps[n] for n in names]), [xs[n] for n in names], [ys[n] for n in names])
+              for names in by_input.values()]
+    whole = (P.group_products([deps[n] for n, _ in layers]), [xs[n] for n, _ in layers], [ys[n] for n, _ in layers])
+
+    def grouped():
+        for call, gx, gy in groups:
+            call(gx, gy, ws)
+
+    def one_group():
+        whole[0](whole[1], whole[2], ws)
+
+    def timed(fn):
+        fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / reps
+
+    dt_layer, dt, dt_whole = timed(per_layer), timed(grouped), timed(one_group)
+    return {"what": "Y = x W_hat for one token through all layers of the block, from the stored format; "
+                    "products that read the same input are launched together",
+            "launch_groups": [names for names in by_input.values()],
             "ms_per_token": dt * 1e3, "Gweights_per_s": wl.params / dt / 1e9,
+            "ms_per_token_one_call_per_layer": dt_layer * 1e3,
+            "ms_per_token_all_products_in_one_group": dt_whole * 1e3,
             "roofline": {"bound": "hbm", "achieved": algo_bytes / dt / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                          "frac": algo_bytes / dt / 1e9 / HBM_PEAK_GBS,
                          "algorithmic_bytes_per_token": algo_bytes}}

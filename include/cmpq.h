@@ -343,6 +343,41 @@ int cmpq_lut_matvec(const void *X, int64_t m, int64_t d_in, int64_t ldx, int64_t
                     const float *delta, float *Y, int64_t ldy, void *ws, size_t ws_bytes,
                     void *stream);
 
+/*
+ * Several products in one pair of launches (Sec. 6 / Fig. 4 for the products that can run
+ * side by side: the query, key and value projections read the same input, so do the gate and
+ * up projections).  Single-token products are short, so a launch per layer is dominated by
+ * launch and first-load latency; grouped, the short layers run beside the long ones.
+ * Every field has the meaning of the argument of the same name of cmpq_lut_matvec; all
+ * products of a group share the number of tokens m.  Results are bit-identical to one
+ * cmpq_lut_matvec call per layer.
+ * Workspace: the sum over the layers of cmpq_workspace_bytes(CMPQ_OP_LUT_MATVEC, d_in, d_out, m)
+ * is always enough.  Limits: n_layers <= CMPQ_MAX_GROUP; those of cmpq_lut_matvec per layer; the
+ * partial rows of all layers together stay below 65536 (CMPQ_ESHAPE beyond).
+ * Errors are those of cmpq_lut_matvec; nothing is launched when one layer is rejected.
+ */
+#define CMPQ_MAX_GROUP 8
+typedef struct cmpq_deployed_layer {
+    const void *X; /* device, FP16 [m, d_in] */
+    int64_t d_in, ldx, d_out;
+    const int32_t *bit_set; /* host */
+    int n_set;
+    const int64_t *counts_host;          /* host */
+    const uint32_t *const *packed;       /* host array of device pointers */
+    const int32_t *const *chan_idx;      /* host array of device pointers */
+    const uint16_t *const *lut;          /* host array of device pointers */
+    const int32_t *act_idx;              /* device */
+    const uint16_t *W_act;               /* device */
+    int64_t k_act, ld_act;
+    const int32_t *colptr, *row_idx;     /* device, colptr nullable */
+    const float *delta;                  /* device */
+    float *Y;                            /* device, fp32 [m, d_out] */
+    int64_t ldy;
+} cmpq_deployed_layer;
+
+int cmpq_lut_matvec_group(const cmpq_deployed_layer *layers, int n_layers, int64_t m, void *ws,
+                          size_t ws_bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -32,11 +32,22 @@ EXPORTS = ("cmpq_workspace_bytes", "cmpq_strerror", "cmpq_count_ppm", "cmpq_act_
            "cmpq_transpose", "cmpq_allocate_bits", "cmpq_extract_outliers",
            "cmpq_kmeans_quantize", "cmpq_pack", "cmpq_dequant_error", "cmpq_set_kmeans_algorithm",
            "cmpq_gather_channels", "cmpq_outliers_by_column", "cmpq_lut_matvec", "cmpq_act_stats_norm",
-           "cmpq_rtn_quantize", "cmpq_select_by_width")
+           "cmpq_rtn_quantize", "cmpq_select_by_width", "cmpq_lut_matvec_group")
 
 _i64, _i32, _int, _vp, _dbl, _sz = (ctypes.c_int64, ctypes.c_int32, ctypes.c_int, ctypes.c_void_p,
                                     ctypes.c_double, ctypes.c_size_t)
 _lib = None
+
+
+MAX_GROUP = 8
+
+
+class DeployedLayer(ctypes.Structure):
+    """`cmpq_deployed_layer` of the header, field for field."""
+    _fields_ = [("X", _vp), ("d_in", _i64), ("ldx", _i64), ("d_out", _i64), ("bit_set", _vp), ("n_set", _int),
+                ("counts_host", _vp), ("packed", _vp), ("chan_idx", _vp), ("lut", _vp), ("act_idx", _vp),
+                ("W_act", _vp), ("k_act", _i64), ("ld_act", _i64), ("colptr", _vp), ("row_idx", _vp),
+                ("delta", _vp), ("Y", _vp), ("ldy", _i64)]
 
 
 class CmpqError(RuntimeError):
@@ -76,6 +87,7 @@ def lib() -> ctypes.CDLL:
         L.cmpq_lut_matvec.argtypes = [_vp, _i64, _i64, _i64, _i64, _vp, _int, _vp, _vp, _vp, _vp, _vp, _vp,
                                       _i64, _i64, _vp, _vp, _vp, _vp, _i64, _vp, _sz, _vp]
         L.cmpq_rtn_quantize.argtypes = [_vp, _int, _i64, _i64, _i64, _vp, _i64, _vp, _vp, _vp, _vp, _vp, _vp]
+        L.cmpq_lut_matvec_group.argtypes = [_vp, _int, _i64, _vp, _sz, _vp]
         L.cmpq_select_by_width.argtypes = [_vp, _i64, _i64, _vp, _int, _vp, _vp, _vp, _vp, _vp]
         for name in EXPORTS[3:]:
             getattr(L, name).restype = _int
@@ -298,6 +310,45 @@ class LutMatvecCall:
         rc = self._fn(_ptr(X), m, d_in, ldx, *self._head, _ptr(Y), ldy, buf.data_ptr(), buf.numel(), _stream())
         if rc:
             _check(rc, "cmpq_lut_matvec")
+
+
+class LutMatvecGroupCall:
+    """``cmpq_lut_matvec_group`` for a fixed set of deployed layers (`LutMatvecCall` objects):
+    the array of layer descriptions is built once; a call fills in inputs and outputs."""
+
+    def __init__(self, calls: Sequence[LutMatvecCall]):
+        if not 1 <= len(calls) <= MAX_GROUP:
+            raise ValueError(f"a group holds 1..{MAX_GROUP} layers")
+        self._calls = list(calls)
+        self._arr = (DeployedLayer * len(calls))()
+        for L, c in zip(self._arr, calls):
+            d_out, bs, n, cn, pk, ci, lt, act_idx, W_act, k_act, ld_act, colptr, row_idx, delta = c._head
+            L.d_in, L.d_out, L.n_set, L.k_act, L.ld_act = c.d_in, d_out, n, k_act, ld_act
+            L.bit_set, L.counts_host = ctypes.addressof(bs), ctypes.addressof(cn)
+            L.packed, L.chan_idx, L.lut = ctypes.addressof(pk), ctypes.addressof(ci), ctypes.addressof(lt)
+            L.act_idx, L.W_act, L.colptr, L.row_idx, L.delta = act_idx, W_act, colptr, row_idx, delta
+        self._ws_bytes = {}
+        self._fn = lib().cmpq_lut_matvec_group
+
+    def __call__(self, Xs: Sequence[torch.Tensor], Ys: Sequence[torch.Tensor], ws: Workspace) -> None:
+        if len(Xs) != len(self._calls) or len(Ys) != len(self._calls):
+            raise ValueError("one input and one output per layer")
+        m = Xs[0].shape[0]
+        for L, c, X, Y in zip(self._arr, self._calls, Xs, Ys):
+            if X.dtype != torch.float16 or Y.dtype != torch.float32:
+                raise ValueError("X must be fp16 and Y fp32")
+            mx, d_in, ldx = _rows(X)
+            my, do, ldy = _rows(Y)
+            if (mx, d_in) != (m, c.d_in) or (my, do) != (m, c.d_out):
+                raise ValueError("X must be [m, d_in] and Y [m, d_out], the same m for every layer")
+            L.X, L.ldx, L.Y, L.ldy = _ptr(X), ldx, _ptr(Y), ldy
+        need = self._ws_bytes.get(m)
+        if need is None:
+            need = self._ws_bytes[m] = sum(workspace_bytes(OP_LUT_MATVEC, c.d_in, c.d_out, m) for c in self._calls)
+        buf = ws.get(need)
+        rc = self._fn(self._arr, len(self._calls), m, buf.data_ptr(), buf.numel(), _stream())
+        if rc:
+            _check(rc, "cmpq_lut_matvec_group")
 
 
 def lut_matvec(X: torch.Tensor, d_out: int, bit_set: Sequence[int], counts: Sequence[int],

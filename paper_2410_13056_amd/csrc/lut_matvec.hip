@@ -43,15 +43,28 @@ struct LmWidth {
     int bits;
 };
 
+// One product of a launch, as the kernels see it.
 struct LmArgs {
     LmWidth w[kMaxWidths];
-    int n_widths, rows_per_wave;
-    int n_lut_slabs, n_act_slabs;  // blockIdx.y: O_act slabs first, then the packed slabs
-    int n_rows_total;              // partial rows per token: packed slabs, then O_act slabs
-    int act_vec_ok;                // W_act rows may be read 16 bytes at a time
+    const __half *X;
+    int64_t ldx, d_out;
+    float *partial;                // [tokens][n_rows_total][d_out]
     const int32_t *act_idx;
     const __half *W_act;
     int64_t k_act, ld_act;
+    int n_widths, rows_per_wave;
+    int n_lut_slabs, n_act_slabs;  // a layer's blockIdx.y range: O_act slabs first, then the packed slabs
+    int n_rows_total;              // partial rows per token: packed slabs, then O_act slabs
+    int act_vec_ok;                // W_act rows may be read 16 bytes at a time
+    int tiles;                     // tiles of 2048 outputs
+    int y0;                        // first blockIdx.y of this layer
+};
+
+constexpr int kMaxLayers = CMPQ_MAX_GROUP;
+
+struct LmGroup {
+    LmArgs l[kMaxLayers];
+    int n_layers;
 };
 
 constexpr int kRedStride = CMPQ_WAVE + 1;  // sums of output k of all lanes: 64 floats, padded by one
@@ -96,10 +109,12 @@ __device__ __forceinline__ uint32_t entry_offset(uint32_t code, uint32_t base) {
 }
 
 template <int B>
-__device__ __forceinline__ void lut_slab(const __half *__restrict__ X, int64_t ldx, int64_t d_out,
-                                         const LmWidth &wd, int slab, int rows_per_wave, int n_rows_total,
-                                         float *__restrict__ partial, float (*tbl_all)[2][kGroup * 16],
-                                         float (*red)[kRedFloats]) {
+__device__ __forceinline__ void lut_slab(const LmArgs &a, const LmWidth &wd, int slab,
+                                         float (*tbl_all)[2][kGroup * 16], float (*red)[kRedFloats]) {
+    const __half *__restrict__ X = a.X;
+    const int64_t ldx = a.ldx, d_out = a.d_out;
+    const int rows_per_wave = a.rows_per_wave, n_rows_total = a.n_rows_total;
+    float *__restrict__ partial = a.partial;
     constexpr int K = 1 << B;
     // per wavefront: two buffers of kGroup row tables (K floats each)
     float(*tbl)[2][kGroup * 16] = tbl_all;
@@ -182,9 +197,10 @@ __device__ __forceinline__ void lut_slab(const __half *__restrict__ X, int64_t l
 // one per lane.
 constexpr int kActRowsPerWave = 8;
 
-__device__ __forceinline__ void act_slab(const __half *__restrict__ X, int64_t ldx, int64_t d_out,
-                                         const LmArgs &a, int slab, float *__restrict__ partial,
-                                         float (*red)[kRedFloats]) {
+__device__ __forceinline__ void act_slab(const LmArgs &a, int slab, float (*red)[kRedFloats]) {
+    const __half *__restrict__ X = a.X;
+    const int64_t ldx = a.ldx, d_out = a.d_out;
+    float *__restrict__ partial = a.partial;
     const int lane = threadIdx.x & (CMPQ_WAVE - 1), wave = threadIdx.x / CMPQ_WAVE;
     const int64_t token = blockIdx.z;
     const __half *x = X + token * ldx;
@@ -240,16 +256,18 @@ __device__ __forceinline__ void act_slab(const __half *__restrict__ X, int64_t l
     store_partial(acc, red, partial + (token * a.n_rows_total + a.n_lut_slabs + slab) * d_out, d_out);
 }
 
-// grid: (tiles of 2048 outputs; O_act slabs, then packed slabs of all widths one after the
-// other; tokens)
-__global__ __launch_bounds__(kThreads) void lut_matvec_kernel(const __half *__restrict__ X, int64_t ldx,
-                                                               int64_t d_out, LmArgs a,
-                                                               float *__restrict__ partial) {
+// grid: (tiles of 2048 outputs of the widest layer; per layer its O_act slabs, then its packed
+// slabs of all widths one after the other; tokens)
+__global__ __launch_bounds__(kThreads) void lut_matvec_kernel(LmGroup g) {
     __shared__ float tbl[kWaves][2][kGroup * 16];
     __shared__ float red[kWaves][kRedFloats];
-    int y = (int)blockIdx.y;
+    int l = 0;
+    while (l + 1 < g.n_layers && (int)blockIdx.y >= g.l[l + 1].y0) ++l;
+    const LmArgs &a = g.l[l];
+    if ((int)blockIdx.x >= a.tiles) return;
+    int y = (int)blockIdx.y - a.y0;
     if (y < a.n_act_slabs) {
-        act_slab(X, ldx, d_out, a, y, partial, red);
+        act_slab(a, y, red);
         return;
     }
     y -= a.n_act_slabs;
@@ -258,10 +276,10 @@ __global__ __launch_bounds__(kThreads) void lut_matvec_kernel(const __half *__re
     const LmWidth &wd = a.w[j];
     const int slab = y - wd.slab0;
     switch (wd.bits) {
-        case 1: lut_slab<1>(X, ldx, d_out, wd, slab, a.rows_per_wave, a.n_rows_total, partial, tbl, red); break;
-        case 2: lut_slab<2>(X, ldx, d_out, wd, slab, a.rows_per_wave, a.n_rows_total, partial, tbl, red); break;
-        case 3: lut_slab<3>(X, ldx, d_out, wd, slab, a.rows_per_wave, a.n_rows_total, partial, tbl, red); break;
-        default: lut_slab<4>(X, ldx, d_out, wd, slab, a.rows_per_wave, a.n_rows_total, partial, tbl, red); break;
+        case 1: lut_slab<1>(a, wd, slab, tbl, red); break;
+        case 2: lut_slab<2>(a, wd, slab, tbl, red); break;
+        case 3: lut_slab<3>(a, wd, slab, tbl, red); break;
+        default: lut_slab<4>(a, wd, slab, tbl, red); break;
     }
 }
 
@@ -274,16 +292,41 @@ constexpr int kFinRuns = kThreads / kFinCols;
 //   * partial rows: cut into 16 runs of consecutive rows; lane (run, output) adds its run in
 //     row order (4 loads in flight).
 // Per output, the 16 run sums are added in run order, then the 16 O_q sums in lane order.
-__global__ __launch_bounds__(kThreads) void lut_matvec_finish_kernel(
-    const __half *__restrict__ X, int64_t ldx, int64_t d_out, const float *__restrict__ partial,
-    int n_rows_total, const int32_t *__restrict__ colptr, const int32_t *__restrict__ row_idx,
-    const float *__restrict__ delta, float *__restrict__ Y, int64_t ldy) {
+struct FinArgs {
+    const __half *X;
+    int64_t ldx, d_out;
+    const float *partial;
+    const int32_t *colptr, *row_idx;
+    const float *delta;
+    float *Y;
+    int64_t ldy;
+    int n_rows_total;
+    int x0;  // first blockIdx.x of this layer
+};
+
+struct FinGroup {
+    FinArgs l[kMaxLayers];
+    int n_layers;
+};
+
+__global__ __launch_bounds__(kThreads) void lut_matvec_finish_kernel(FinGroup g) {
+    int l = 0;
+    while (l + 1 < g.n_layers && (int)blockIdx.x >= g.l[l + 1].x0) ++l;
+    const FinArgs &a = g.l[l];
+    const __half *__restrict__ X = a.X;
+    const int64_t ldx = a.ldx, d_out = a.d_out, ldy = a.ldy;
+    const float *__restrict__ partial = a.partial;
+    const int n_rows_total = a.n_rows_total;
+    const int32_t *__restrict__ colptr = a.colptr;
+    const int32_t *__restrict__ row_idx = a.row_idx;
+    const float *__restrict__ delta = a.delta;
+    float *__restrict__ Y = a.Y;
     constexpr int U = 8;
     __shared__ float part[kFinRuns][kFinCols + 1];
     __shared__ float sp[kFinCols][kFinRuns + 1];
     const int hi = threadIdx.x / kFinCols, lo = threadIdx.x % kFinCols;
     const int64_t token = blockIdx.y;
-    const int64_t o0 = (int64_t)blockIdx.x * kFinCols;
+    const int64_t o0 = (int64_t)((int)blockIdx.x - a.x0) * kFinCols;
     const __half *x = X + token * ldx;
     // O_q of column o0 + hi, entries lo, lo + 16, ...
     float t = 0.f;
@@ -325,12 +368,12 @@ __global__ __launch_bounds__(kThreads) void lut_matvec_finish_kernel(
     part[hi][lo] = y;
     __syncthreads();
     if (threadIdx.x < kFinCols && o0 + threadIdx.x < d_out) {
-        float a = 0.f, b = 0.f;
+        float dense = 0.f, sparse = 0.f;
 #pragma unroll
-        for (int q = 0; q < kFinRuns; ++q) a += part[q][threadIdx.x];
+        for (int q = 0; q < kFinRuns; ++q) dense += part[q][threadIdx.x];
 #pragma unroll
-        for (int q = 0; q < 16; ++q) b += sp[threadIdx.x][q];
-        Y[token * ldy + o0 + threadIdx.x] = a + b;
+        for (int q = 0; q < 16; ++q) sparse += sp[threadIdx.x][q];
+        Y[token * ldy + o0 + threadIdx.x] = dense + sparse;
     }
 }
 
@@ -520,6 +563,137 @@ extern "C" int cmpq_outliers_by_column(const int32_t *out_idx, const uint16_t *o
     return CMPQ_OK;
 }
 
+namespace {
+
+// Host-side checks of one layer of a product (the rules of cmpq_lut_matvec).
+int check_layer(const cmpq_deployed_layer &L, int64_t m) {
+    if (L.d_in < 0 || L.d_out < 0 || L.k_act < 0 || L.n_set < 0 || L.n_set > kMaxWidths) return CMPQ_EINVAL;
+    if (L.n_set > 0 && (!L.bit_set || !L.counts_host || !L.packed || !L.chan_idx || !L.lut)) return CMPQ_EINVAL;
+    int64_t rows_total = L.k_act;
+    for (int j = 0; j < L.n_set; ++j) {
+        if (L.bit_set[j] < 1 || L.bit_set[j] > 4 || L.counts_host[j] < 0) return CMPQ_EINVAL;
+        if (L.counts_host[j] > 0 && (!L.packed[j] || !L.chan_idx[j] || !L.lut[j])) return CMPQ_EINVAL;
+        rows_total += L.counts_host[j];
+    }
+    if (rows_total > L.d_in) return CMPQ_EINVAL;
+    if (m == 0 || L.d_out == 0) return CMPQ_OK;
+    if (!L.Y || (L.d_in > 0 && !L.X)) return CMPQ_EINVAL;
+    if (L.k_act > 0 && (!L.act_idx || !L.W_act)) return CMPQ_EINVAL;
+    if (L.colptr && (!L.row_idx || !L.delta)) return CMPQ_EINVAL;
+    if (L.ldx < L.d_in || L.ldy < L.d_out || (L.k_act > 0 && L.ld_act < L.d_out)) return CMPQ_ESHAPE;
+    if (L.d_out >= (1 << 20)) return CMPQ_ESHAPE;
+    return CMPQ_OK;
+}
+
+int launch_group(const cmpq_deployed_layer *layers, int n_layers, int64_t m, void *ws, size_t ws_bytes,
+                 void *stream) {
+    if (n_layers < 0 || n_layers > kMaxLayers || m < 0 || (n_layers > 0 && !layers)) return CMPQ_EINVAL;
+    for (int i = 0; i < n_layers; ++i) {
+        const int rc = check_layer(layers[i], m);
+        if (rc != CMPQ_OK) return rc;
+    }
+    if (m > 65535) return CMPQ_ESHAPE;
+    if (m == 0) return CMPQ_OK;
+    // the longest products first: their workgroups are dispatched first
+    int order[kMaxLayers], n_live = 0;
+    for (int i = 0; i < n_layers; ++i)
+        if (layers[i].d_out > 0) order[n_live++] = i;
+    for (int i = 1; i < n_live; ++i)
+        for (int j = i; j > 0; --j) {
+            const cmpq_deployed_layer &p = layers[order[j - 1]], &q = layers[order[j]];
+            if (p.d_in * p.d_out >= q.d_in * q.d_out) break;
+            const int t = order[j];
+            order[j] = order[j - 1];
+            order[j - 1] = t;
+        }
+    if (n_live == 0) return CMPQ_OK;
+    LmGroup g;
+    FinGroup f;
+    g.n_layers = f.n_layers = n_live;
+    size_t ws_used = 0;
+    int64_t y_total = 0, x_total = 0, max_tiles = 0;
+    for (int s = 0; s < n_live; ++s) {
+        const cmpq_deployed_layer &L = layers[order[s]];
+        LmArgs &a = g.l[s];
+        // rows per wavefront: the largest of 32, 16, 8 that still gives two workgroups per compute unit
+        const int64_t tiles = cdiv(L.d_out, kTileOut);
+        int rpw = kMaxRowsPerWave;
+        while (rpw > 8 && tiles * total_slabs(L.counts_host, L.n_set, rpw) * m < 512) rpw /= 2;
+        const int64_t n_lut = total_slabs(L.counts_host, L.n_set, rpw);
+        const int64_t n_act = cdiv(L.k_act, (int64_t)kWaves * kActRowsPerWave);
+        const int64_t n_rows = n_lut + n_act;
+        a.n_widths = 0;
+        a.rows_per_wave = rpw;
+        a.n_lut_slabs = (int)n_lut;
+        a.n_act_slabs = (int)n_act;
+        a.n_rows_total = (int)n_rows;
+        a.tiles = (int)tiles;
+        a.y0 = (int)y_total;
+        a.X = static_cast<const __half *>(L.X);
+        a.ldx = L.ldx;
+        a.d_out = L.d_out;
+        a.partial = reinterpret_cast<float *>(static_cast<char *>(ws) + ws_used);
+        a.act_idx = L.act_idx;
+        a.W_act = reinterpret_cast<const __half *>(L.W_act);
+        a.k_act = L.k_act;
+        a.ld_act = L.ld_act;
+        a.act_vec_ok = reinterpret_cast<uintptr_t>(L.W_act) % 16 == 0 && L.ld_act % 8 == 0;
+        int slab0 = 0;
+        for (int j = 0; j < L.n_set; ++j) {
+            if (L.counts_host[j] == 0) continue;
+            LmWidth &wd = a.w[a.n_widths++];
+            wd.packed = L.packed[j];
+            wd.chan_idx = L.chan_idx[j];
+            wd.lut = L.lut[j];
+            wd.rows = L.counts_host[j];
+            wd.words_per_row = cdiv(L.d_out * L.bit_set[j], 32);
+            wd.slab0 = slab0;
+            wd.bits = L.bit_set[j];
+            slab0 += (int)cdiv(wd.rows, (int64_t)kWaves * rpw);
+        }
+        for (int j = a.n_widths; j < kMaxWidths; ++j) a.w[j] = LmWidth{nullptr, nullptr, nullptr, 0, 0, 0, 0};
+        FinArgs &fa = f.l[s];
+        fa.X = a.X;
+        fa.ldx = L.ldx;
+        fa.d_out = L.d_out;
+        fa.partial = a.partial;
+        fa.colptr = L.colptr;
+        fa.row_idx = L.row_idx;
+        fa.delta = L.delta;
+        fa.Y = L.Y;
+        fa.ldy = L.ldy;
+        fa.n_rows_total = (int)n_rows;
+        fa.x0 = (int)x_total;
+        ws_used += align_up((size_t)m * (size_t)n_rows * (size_t)L.d_out * sizeof(float), 256);
+        y_total += n_rows;
+        x_total += cdiv(L.d_out, kFinCols);
+        if (tiles > max_tiles) max_tiles = tiles;
+    }
+    for (int s = n_live; s < kMaxLayers; ++s) {
+        g.l[s] = g.l[0];
+        f.l[s] = f.l[0];
+    }
+    if (y_total > 65535 || x_total > 0x7fffffff) return CMPQ_ESHAPE;
+    if (ws_used > 0 && (!ws || reinterpret_cast<uintptr_t>(ws) % 256 != 0 || ws_bytes < ws_used))
+        return CMPQ_EWORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (y_total > 0) {
+        const dim3 grid((unsigned)max_tiles, (unsigned)y_total, (unsigned)m);
+        lut_matvec_kernel<<<grid, kThreads, 0, st>>>(g);
+    }
+    const dim3 fgrid((unsigned)x_total, (unsigned)m);
+    lut_matvec_finish_kernel<<<fgrid, kThreads, 0, st>>>(f);
+    CMPQ_LAUNCH_CHECK();
+    return CMPQ_OK;
+}
+
+}  // namespace
+
+extern "C" int cmpq_lut_matvec_group(const cmpq_deployed_layer *layers, int n_layers, int64_t m, void *ws,
+                                     size_t ws_bytes, void *stream) {
+    return launch_group(layers, n_layers, m, ws, ws_bytes, stream);
+}
+
 extern "C" int cmpq_lut_matvec(const void *X, int64_t m, int64_t d_in, int64_t ldx, int64_t d_out,
                                const int32_t *bit_set, int n_set, const int64_t *counts_host,
                                const uint32_t *const *packed, const int32_t *const *chan_idx,
@@ -527,66 +701,26 @@ extern "C" int cmpq_lut_matvec(const void *X, int64_t m, int64_t d_in, int64_t l
                                const uint16_t *W_act, int64_t k_act, int64_t ld_act,
                                const int32_t *colptr, const int32_t *row_idx, const float *delta,
                                float *Y, int64_t ldy, void *ws, size_t ws_bytes, void *stream) {
-    if (m < 0 || d_in < 0 || d_out < 0 || k_act < 0 || n_set < 0 || n_set > 4) return CMPQ_EINVAL;
-    if (n_set > 0 && (!bit_set || !counts_host || !packed || !chan_idx || !lut)) return CMPQ_EINVAL;
-    int64_t rows_total = k_act;
-    for (int j = 0; j < n_set; ++j) {
-        if (bit_set[j] < 1 || bit_set[j] > 4 || counts_host[j] < 0) return CMPQ_EINVAL;
-        if (counts_host[j] > 0 && (!packed[j] || !chan_idx[j] || !lut[j])) return CMPQ_EINVAL;
-        rows_total += counts_host[j];
-    }
-    if (rows_total > d_in) return CMPQ_EINVAL;
-    if (m == 0 || d_out == 0) return CMPQ_OK;
-    if (!Y || (d_in > 0 && !X)) return CMPQ_EINVAL;
-    if (k_act > 0 && (!act_idx || !W_act)) return CMPQ_EINVAL;
-    if (colptr && (!row_idx || !delta)) return CMPQ_EINVAL;
-    if (ldx < d_in || ldy < d_out || (k_act > 0 && ld_act < d_out)) return CMPQ_ESHAPE;
-    if (m > 65535 || d_out >= (1 << 20)) return CMPQ_ESHAPE;
-    // rows per wavefront: the largest of 32, 16, 8 that still gives two workgroups per compute unit
-    const int64_t tiles = cdiv(d_out, kTileOut);
-    int rpw = kMaxRowsPerWave;
-    while (rpw > 8 && tiles * total_slabs(counts_host, n_set, rpw) * m < 512) rpw /= 2;
-    const int64_t n_lut = total_slabs(counts_host, n_set, rpw);
-    const int64_t n_act = cdiv(k_act, (int64_t)kWaves * kActRowsPerWave);
-    const int64_t n_rows = n_lut + n_act;
-    if (n_rows > 65535) return CMPQ_ESHAPE;
-    if (!ws || reinterpret_cast<uintptr_t>(ws) % 256 != 0 || ws_bytes < cmpq_ws_lut_matvec(d_in, d_out, m))
-        return CMPQ_EWORKSPACE;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    float *partial = static_cast<float *>(ws);
-    const __half *Xh = static_cast<const __half *>(X);
-    LmArgs a;
-    a.n_widths = 0;
-    a.rows_per_wave = rpw;
-    a.n_lut_slabs = (int)n_lut;
-    a.n_act_slabs = (int)n_act;
-    a.n_rows_total = (int)n_rows;
-    a.act_idx = act_idx;
-    a.W_act = reinterpret_cast<const __half *>(W_act);
-    a.k_act = k_act;
-    a.ld_act = ld_act;
-    a.act_vec_ok = reinterpret_cast<uintptr_t>(W_act) % 16 == 0 && ld_act % 8 == 0;
-    int slab0 = 0;
-    for (int j = 0; j < n_set; ++j) {
-        if (counts_host[j] == 0) continue;
-        LmWidth &wd = a.w[a.n_widths++];
-        wd.packed = packed[j];
-        wd.chan_idx = chan_idx[j];
-        wd.lut = lut[j];
-        wd.rows = counts_host[j];
-        wd.words_per_row = cdiv(d_out * bit_set[j], 32);
-        wd.slab0 = slab0;
-        wd.bits = bit_set[j];
-        slab0 += (int)cdiv(wd.rows, (int64_t)kWaves * rpw);
-    }
-    for (int j = a.n_widths; j < kMaxWidths; ++j) a.w[j] = LmWidth{nullptr, nullptr, nullptr, 0, 0, 0, 0};
-    if (n_rows > 0) {
-        const dim3 grid((unsigned)tiles, (unsigned)n_rows, (unsigned)m);
-        lut_matvec_kernel<<<grid, kThreads, 0, s>>>(Xh, ldx, d_out, a, partial);
-    }
-    const dim3 fgrid((unsigned)cdiv(d_out, kFinCols), (unsigned)m);
-    lut_matvec_finish_kernel<<<fgrid, kThreads, 0, s>>>(Xh, ldx, d_out, partial, (int)n_rows, colptr, row_idx,
-                                                    delta, Y, ldy);
-    CMPQ_LAUNCH_CHECK();
-    return CMPQ_OK;
+    cmpq_deployed_layer L;
+    L.X = X;
+    L.d_in = d_in;
+    L.ldx = ldx;
+    L.d_out = d_out;
+    L.bit_set = bit_set;
+    L.n_set = n_set;
+    L.counts_host = counts_host;
+    L.packed = packed;
+    L.chan_idx = chan_idx;
+    L.lut = lut;
+    L.act_idx = act_idx;
+    L.W_act = W_act;
+    L.k_act = k_act;
+    L.ld_act = ld_act;
+    L.colptr = colptr;
+    L.row_idx = row_idx;
+    L.delta = delta;
+    L.Y = Y;
+    L.ldy = ldy;
+    if (m < 0) return CMPQ_EINVAL;
+    return launch_group(&L, 1, m, ws, ws_bytes, stream);
 }

@@ -275,14 +275,17 @@ class Deployed:
     delta: torch.Tensor               # [k_q] fp32: outlier value minus the table level it overrides
     _call: Optional[B.LutMatvecCall] = None
 
-    def matvec_into(self, X: torch.Tensor, Y: torch.Tensor, ws: B.Workspace) -> None:
-        """Y [m, d_out] fp32 = X [m, d_in] fp16 times this weight; the call's fixed arguments
-        are marshalled at the first use."""
+    def call(self) -> B.LutMatvecCall:
+        """The layer's fixed call arguments, marshalled at the first use."""
         if self._call is None:
             self._call = B.LutMatvecCall(self.d_in, self.d_out, self.bit_set, self.counts, self.packed,
                                          self.chan_idx, self.lut, self.act_idx, self.W_act, self.colptr,
                                          self.row_idx, self.delta)
-        self._call(X, Y, ws)
+        return self._call
+
+    def matvec_into(self, X: torch.Tensor, Y: torch.Tensor, ws: B.Workspace) -> None:
+        """Y [m, d_out] fp32 = X [m, d_in] fp16 times this weight."""
+        self.call()(X, Y, ws)
 
 
 def prepare_deployment(r: LayerResult, ws: Optional[B.Workspace] = None,
@@ -312,6 +315,13 @@ def lut_matvec(dep: Deployed, X: torch.Tensor, ws: Optional[B.Workspace] = None,
     with _stage(timer, "lut_matvec"):
         dep.matvec_into(X, Y, ws)
     return Y
+
+
+def group_products(deps: Sequence[Deployed]) -> B.LutMatvecGroupCall:
+    """Sec. 6: several deployed layers whose products may run side by side (the projections that
+    read the same input, or any independent ones) as one pair of launches:
+    ``group_products(deps)(Xs, Ys, ws)``.  Same results as one `lut_matvec` per layer."""
+    return B.LutMatvecGroupCall([d.call() for d in deps])
 
 
 _side_streams: Dict[tuple, list] = {}

@@ -123,6 +123,9 @@ def test_host_side_argument_errors(L):
                              fake, 64, None, 0, None) == -5
     assert L.cmpq_lut_matvec(fake, 70000, 8, 8, 64, bs, 3, one, ptrs, ptrs, ptrs, None, None, 0, 64, None, None, None,
                              fake, 64, fake, 1 << 40, None) == -2                              # too many tokens
+    assert L.cmpq_lut_matvec_group(None, 0, 1, None, 0, None) == 0                             # an empty group
+    assert L.cmpq_lut_matvec_group(None, 2, 1, None, 0, None) == -1                            # layers missing
+    assert L.cmpq_lut_matvec_group(fake, 9, 1, None, 0, None) == -1                            # more than CMPQ_MAX_GROUP
     # the uniform quantizer
     assert L.cmpq_rtn_quantize(fake, 0, 4, 64, 64, fake, 96, fake, fake, fake, None, None, None) == -1    # group no power of two
     assert L.cmpq_rtn_quantize(fake, 0, 4, 64, 64, fake, 4, fake, fake, fake, None, None, None) == -1     # group below 8

@@ -167,3 +167,78 @@ def test_lut_matvec_full_size_layer(env):
     Yref = orc.lut_matvec(_np(X), Wt, cent, codes, bits, out_idx)
     What = _what(Wt, cent, codes, bits, out_idx)
     _check_product(Y, Yref, _np(X), What)
+
+
+def _deploy_random_layer(env, rng, d_in, d_out, bit_set, avg, rho_act=20000, rho_q=10000):
+    P, ws = env["P"], env["ws"]
+    W = rng.normal(0, 0.02, (d_in, d_out))
+    W[rng.random(W.shape) < 0.01] *= 10
+    W = W.astype(np.float16)
+    sumsq = _dev((rng.random(d_in) ** 3 + 0.01).astype(np.float32))
+    r = P.quantize_layer(_dev(W), sumsq, bit_set, avg, rho_act_ppm=rho_act, rho_q_ppm=rho_q, iters=3, ws=ws,
+                         transposed=True)
+    return W, r, P.prepare_deployment(r, ws)
+
+
+def test_grouped_products_equal_single_calls_and_oracle(env):
+    """Products launched together (three that read one input, as query/key/value do, and two
+    with inputs of their own, one without outliers) give bit for bit what one call per layer
+    gives, and so match the oracle."""
+    P, ws, orc = env["P"], env["ws"], env["orc"]
+    rng = np.random.default_rng(21)
+    shapes = [(520, 2048 + 40, (2, 3, 4), 3.2, 20000, 10000), (520, 300, (3, 4), 3.5, 20000, 10000),
+              (520, 33, (1, 2), 1.5, 20000, 10000), (96, 4100, (2, 3), 2.5, 0, 0),
+              (1100, 2000, (2, 3, 4), 2.4, 4500, 500)]
+    layers = [_deploy_random_layer(env, rng, *s) for s in shapes]
+    deps = [d for _, _, d in layers]
+    group = P.group_products(deps)
+    for m in (1, 3):
+        shared = _dev(rng.normal(0, 1, (m, 520)).astype(np.float16))
+        Xs = [shared, shared, shared, _dev(rng.normal(0, 1, (m, 96)).astype(np.float16)),
+              _dev(rng.normal(0, 1, (m, 1100)).astype(np.float16))]
+        Ys = [torch.full((m, d.d_out), 3.0, dtype=torch.float32, device=DEV) for d in deps]
+        group(Xs, Ys, ws)
+        torch.cuda.synchronize()
+        for (W, r, dep), X, Y in zip(layers, Xs, Ys):
+            single = P.lut_matvec(dep, X, ws)
+            assert torch.equal(single, Y)
+            What = _what(W, _np(r.centroids), _np(r.codes), _np(r.bits), _np(r.out_idx).astype(np.int64))
+            Yref = orc.lut_matvec(_np(X), W, _np(r.centroids), _np(r.codes), _np(r.bits),
+                                  _np(r.out_idx).astype(np.int64))
+            _check_product(_np(Y), Yref, _np(X), What)
+    # a group of one, and the largest group
+    one = P.group_products(deps[:1])
+    Y1 = torch.empty((1, deps[0].d_out), dtype=torch.float32, device=DEV)
+    one([Xs[0][:1]], [Y1], ws)
+    assert torch.equal(Y1, P.lut_matvec(deps[0], Xs[0][:1], ws))
+    eight = P.group_products([deps[1]] * 8)
+    Y8 = [torch.empty((1, deps[1].d_out), dtype=torch.float32, device=DEV) for _ in range(8)]
+    eight([Xs[1][:1]] * 8, Y8, ws)
+    want = P.lut_matvec(deps[1], Xs[1][:1], ws)
+    assert all(torch.equal(y, want) for y in Y8)
+    with pytest.raises(ValueError):
+        P.group_products([deps[1]] * 9)
+
+
+def test_grouped_products_full_size_block(env):
+    """The products of the 70B-shaped block that read one input, grouped as the benchmark
+    groups them (query/key/value; gate/up), against one call per layer."""
+    P, synth, ws = env["P"], env["synth"], env["ws"]
+    wl = synth.workload("block70b")
+    g = torch.Generator(device="cpu")
+    g.manual_seed(5)
+    for names in (("q_proj", "k_proj", "v_proj"), ("gate_proj", "up_proj")):
+        deps = []
+        for name in names:
+            layer = [l for l in wl.layers if l.name == name][0]
+            W = synth.make_weight(layer.d_out, layer.d_in, "f16", 11 + len(deps), DEV)
+            sumsq = (torch.rand(layer.d_in, generator=g) + 0.05).to(DEV)
+            r = P.quantize_layer(W, sumsq, wl.bit_set, wl.avg_bits, wl.rho_act_ppm, wl.rho_q_ppm, 2, ws)
+            deps.append(P.prepare_deployment(r, ws))
+            del r, W
+        X = torch.randn((1, deps[0].d_in), generator=g).to(torch.float16).to(DEV)
+        Ys = [torch.empty((1, d.d_out), dtype=torch.float32, device=DEV) for d in deps]
+        P.group_products(deps)([X] * len(deps), Ys, ws)
+        for d, Y in zip(deps, Ys):
+            assert torch.equal(Y, P.lut_matvec(d, X, ws))
+        del deps
