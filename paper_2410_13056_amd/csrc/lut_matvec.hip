@@ -71,11 +71,12 @@ constexpr int kRedStride = CMPQ_WAVE + 1;  // sums of output k of all lanes: 64 
 constexpr int kRedFloats = kOutPerLane * kRedStride;
 
 // The four wavefronts' sums of a 2048-output tile, added in wavefront order, into a partial
-// row.  Lanes write with stride 1 and read with stride 65: no bank is hit twice by a
+// row.  Called once by every lane of the workgroup.  Lanes write with stride 1 and read with stride 65: no bank is hit twice by a
 // half-wavefront either way.
 __device__ __forceinline__ void store_partial(const float (&acc)[kOutPerLane], float (*red)[kRedFloats],
                                               float *__restrict__ prow, int64_t d_out) {
     const int lane = threadIdx.x & (CMPQ_WAVE - 1), wave = threadIdx.x / CMPQ_WAVE;
+    __syncthreads();  // the sums reuse the LDS of the tables: every wavefront is done with them
 #pragma unroll
     for (int k = 0; k < kOutPerLane; ++k) red[wave][k * kRedStride + lane] = acc[k];
     __syncthreads();
@@ -191,6 +192,124 @@ __device__ __forceinline__ void lut_slab(const LmArgs &a, const LmWidth &wd, int
     store_partial(acc, red, partial + (token * n_rows_total + wd.slab0 + slab) * d_out, d_out);
 }
 
+// Field p of `bits` bits of a lane's words (two instructions where it straddles two words).
+template <int B, int PB>
+__device__ __forceinline__ uint32_t field_at(const uint32_t (&w)[B], int p) {
+    const int bit = p * PB, idx = bit >> 5, sh = bit & 31;
+    if (sh + PB <= 32) return __builtin_amdgcn_ubfe(w[idx], sh, PB);
+    return __builtin_amdgcn_alignbit(w[idx + 1 < B ? idx + 1 : idx], w[idx], sh) & ((1u << PB) - 1u);
+}
+
+// Width 2: two neighbouring codes are looked up at once.  Per row two tables indexed by the
+// pair (c0 | c1 << B): A[pair] = x * lut[c0] for the even output, B[pair] = x * lut[c1] for the
+// odd one, read by one two-address LDS load.  One extract and one shift-and-add serve two
+// weights, so a weight costs 2 instead of 3 vector instructions; the sums are the same
+// products added in the same order.  A table of 16 entries lies in 16 banks: no conflicts.
+// (Written for any width whose pair table fits a wavefront; with width 3 the 64-entry tables
+// wrap around the LDS banks, the look-ups of a wavefront collide and the kernel is slower than
+// with single look-ups, so width 3 does not use it.)  Same slab shape, prefetch and double
+// buffering as lut_slab.
+template <int B>
+__device__ __forceinline__ void lut_slab_pairs(const LmArgs &a, const LmWidth &wd, int slab, float *smem,
+                                               float (*red)[kRedFloats]) {
+    constexpr int K = 1 << B, PB = 2 * B, KP = 1 << PB;   // levels, bits of a pair, entries of a pair table
+    constexpr int kRowsPerFill = CMPQ_WAVE / KP;           // rows whose tables one pass over the lanes fills
+    constexpr int kFills = kGroup / kRowsPerFill;
+    constexpr int kRowFloats = 2 * KP;                     // A then B
+    constexpr int kBufFloats = kGroup * kRowFloats;
+    static_assert(KP <= CMPQ_WAVE && kGroup % kRowsPerFill == 0, "pair tables are filled by whole wavefronts");
+    const __half *__restrict__ X = a.X;
+    const int64_t d_out = a.d_out;
+    const int lane = threadIdx.x & (CMPQ_WAVE - 1), wave = threadIdx.x / CMPQ_WAVE;
+    const int64_t token = blockIdx.z;
+    const __half *x = X + token * a.ldx;
+    const int64_t word0 = (int64_t)blockIdx.x * (kTileOut / 32) * B + (int64_t)lane * B;
+    const int64_t r0 = ((int64_t)slab * kWaves + wave) * a.rows_per_wave;
+    const int64_t r1 = min(wd.rows, r0 + a.rows_per_wave);
+    float acc[kOutPerLane];
+#pragma unroll
+    for (int k = 0; k < kOutPerLane; ++k) acc[k] = 0.f;
+
+    // pass f over the lanes fills the tables of row f * kRowsPerFill + lane / KP, entry lane % KP
+    const int fill_row = lane / KP, fill_e = lane % KP;
+    auto table_entries = [&](int64_t r, float (&ea)[kFills], float (&eb)[kFills]) {
+#pragma unroll
+        for (int f = 0; f < kFills; ++f) {
+            const int64_t row = r + f * kRowsPerFill + fill_row;
+            ea[f] = 0.f;
+            eb[f] = 0.f;
+            if (row < r1) {
+                const float xi = __half2float(x[wd.chan_idx[row]]);
+                ea[f] = xi * __half2float(__ushort_as_half(wd.lut[row * K + (fill_e & (K - 1))]));
+                eb[f] = xi * __half2float(__ushort_as_half(wd.lut[row * K + (fill_e >> B)]));
+            }
+        }
+    };
+    const bool full = word0 + B <= wd.words_per_row;
+    auto load_words = [&](int64_t r, uint32_t (&w)[kGroup][B]) {
+#pragma unroll
+        for (int g = 0; g < kGroup; ++g) {
+            const uint32_t *p = wd.packed + (r + g) * wd.words_per_row + word0;
+            if (r + g < r1 && full) {
+                typedef uint32_t WordsB __attribute__((ext_vector_type(B), aligned(4)));
+                const WordsB v = *reinterpret_cast<const WordsB *>(p);
+#pragma unroll
+                for (int j = 0; j < B; ++j) w[g][j] = v[j];
+            } else {
+#pragma unroll
+                for (int j = 0; j < B; ++j) w[g][j] = (r + g < r1 && word0 + j < wd.words_per_row) ? p[j] : 0u;
+            }
+        }
+    };
+
+    if (r0 < r1) {
+        uint32_t w[kGroup][B], wn[kGroup][B];
+        float ea[kFills], eb[kFills], ean[kFills], ebn[kFills];
+        table_entries(r0, ea, eb);
+        load_words(r0, w);
+        int buf = 0;
+        for (int64_t r = r0; r < r1; r += kGroup) {
+            float *mine = smem + (wave * 2 + buf) * kBufFloats;
+#pragma unroll
+            for (int f = 0; f < kFills; ++f) {
+                float *row_tbl = mine + (f * kRowsPerFill + fill_row) * kRowFloats;
+                row_tbl[fill_e] = ea[f];
+                row_tbl[KP + fill_e] = eb[f];
+            }
+            if (r + kGroup < r1) {
+                table_entries(r + kGroup, ean, ebn);
+                load_words(r + kGroup, wn);
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            const char *base = reinterpret_cast<const char *>(smem);
+            const uint32_t wb = (uint32_t)((wave * 2 + buf) * (kBufFloats * 4));
+#pragma unroll
+            for (int g = 0; g < kGroup; ++g) {
+                // rows past the end have all-zero tables: their look-ups add 0
+#pragma unroll
+                for (int p = 0; p < kOutPerLane / 2; ++p) {
+                    const char *at = base + g * (kRowFloats * 4) + entry_offset(field_at<B, PB>(w[g], p), wb);
+                    acc[2 * p] += *reinterpret_cast<const float *>(at);
+                    acc[2 * p + 1] += *reinterpret_cast<const float *>(at + KP * 4);
+                }
+            }
+            __builtin_amdgcn_wave_barrier();
+            buf ^= 1;
+#pragma unroll
+            for (int f = 0; f < kFills; ++f) {
+                ea[f] = ean[f];
+                eb[f] = ebn[f];
+            }
+#pragma unroll
+            for (int g = 0; g < kGroup; ++g)
+#pragma unroll
+                for (int j = 0; j < B; ++j) w[g][j] = wn[g][j];
+        }
+    }
+    store_partial(acc, red, a.partial + (token * a.n_rows_total + wd.slab0 + slab) * d_out, d_out);
+}
+
 // A slab of O_act: 8 rows of FP16 weights per wavefront times their inputs (few rows, so
 // short slabs: the loop over rows is bound by latency).  A lane reads its 32 outputs of a
 // row as four 16-byte pieces, two rows in flight; the rows' inputs are fetched up front,
@@ -259,8 +378,11 @@ __device__ __forceinline__ void act_slab(const LmArgs &a, int slab, float (*red)
 // grid: (tiles of 2048 outputs of the widest layer; per layer its O_act slabs, then its packed
 // slabs of all widths one after the other; tokens)
 __global__ __launch_bounds__(kThreads) void lut_matvec_kernel(LmGroup g) {
-    __shared__ float tbl[kWaves][2][kGroup * 16];
-    __shared__ float red[kWaves][kRedFloats];
+    // the tables of the look-ups and, after them, the wavefronts' sums share one piece of LDS
+    __shared__ float smem[kWaves * kRedFloats];
+    float(*tbl)[2][kGroup * 16] = reinterpret_cast<float(*)[2][kGroup * 16]>(smem);
+    float(*red)[kRedFloats] = reinterpret_cast<float(*)[kRedFloats]>(smem);
+    static_assert(kWaves * 2 * kGroup * 2 * 64 <= kWaves * kRedFloats, "pair tables fit the shared piece");
     int l = 0;
     while (l + 1 < g.n_layers && (int)blockIdx.y >= g.l[l + 1].y0) ++l;
     const LmArgs &a = g.l[l];
@@ -277,7 +399,7 @@ __global__ __launch_bounds__(kThreads) void lut_matvec_kernel(LmGroup g) {
     const int slab = y - wd.slab0;
     switch (wd.bits) {
         case 1: lut_slab<1>(a, wd, slab, tbl, red); break;
-        case 2: lut_slab<2>(a, wd, slab, tbl, red); break;
+        case 2: lut_slab_pairs<2>(a, wd, slab, smem, red); break;
         case 3: lut_slab<3>(a, wd, slab, tbl, red); break;
         default: lut_slab<4>(a, wd, slab, tbl, red); break;
     }
