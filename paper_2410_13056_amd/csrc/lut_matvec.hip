@@ -15,8 +15,10 @@
 //         4 rows at a time sit in LDS (one entry per lane to fill); a code becomes the
 //         address of its table entry with two instructions.  The 16 entries of a table lie
 //         in 16 banks, so the look-ups of a wavefront never collide.
-//       - a slab of 128 rows of O_act (FP16 rows) times 2048 outputs.
-//     The four wavefronts' sums are added in order.
+//         Width 2 looks two neighbouring codes up at once (pair tables).
+//       - a slab of 32 rows of O_act (FP16 rows) times 2048 outputs.
+//     The four wavefronts' sums are added in order.  A launch serves up to 8 products
+//     (cmpq_lut_matvec_group): every layer owns a range of blockIdx.y.
 //   * lut_matvec_finish_kernel: per output, the partial rows in order (packed slabs, O_act
 //     slabs), then the column's O_q entries - every sum in a fixed order, so the result is
 //     reproducible bit for bit.

@@ -51,7 +51,7 @@ def _compare(got, want):
 
 @pytest.mark.parametrize("dtype", ["f16", "f32"])
 @pytest.mark.parametrize("d_in,d_out,group", [(40, 2048, 128), (33, 4100, 128), (17, 1000, 32),
-                                               (9, 6152, 512), (64, 264, 8), (5, 7, 8), (12, 20480, 256)])
+                                               (9, 6152, 512), (64, 264, 8), (5, 7, 8), (12, 20480, 256), (3, 100, 512)])
 def test_rtn_parity(env, dtype, d_in, d_out, group):
     rng = np.random.default_rng(d_in * 131 + d_out)
     W = (rng.standard_t(4, size=(d_in, d_out)) * 0.02).astype(np.float16 if dtype == "f16" else np.float32)
