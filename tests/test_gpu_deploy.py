@@ -7,6 +7,8 @@ fp64 by the oracle: |Y - Y_ref| <= 2e-6 * sum_i |X[t,i] * W_hat[i,o]| + 1e-30 pe
 (the fp32 rounding of d_in products and additions stays far below it; one wrong, missing or
 doubled term of typical size exceeds it), and the GPU result is bit-reproducible.
 """
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -242,3 +244,35 @@ def test_grouped_products_full_size_block(env):
         for d, Y in zip(deps, Ys):
             assert torch.equal(Y, P.lut_matvec(d, X, ws))
         del deps
+
+
+@pytest.mark.parametrize("seed", range(int(os.environ.get("CMPQ_RANDOM_CASES", "12"))))
+def test_randomized_products_and_groups(env, seed):
+    """Random shapes (ragged tiles, odd d_out), bit sets down to one bit, budgets, outlier fractions
+    and token counts; 1 to 4 layers launched as a group, each product against the oracle and
+    against its own single call."""
+    P, ws, orc = env["P"], env["ws"], env["orc"]
+    rng = np.random.default_rng(7000 + seed)
+    n_layers = int(rng.integers(1, 5))
+    m = int(rng.integers(1, 4))
+    layers, Xs = [], []
+    for _ in range(n_layers):
+        d_in = int(rng.integers(8, 400))
+        d_out = int(rng.choice([rng.integers(1, 64), rng.integers(64, 2100), rng.integers(2100, 6500)]))
+        lo = int(rng.integers(1, 4))
+        hi = int(rng.integers(lo + 1, 5))
+        bit_set = tuple(range(lo, hi + 1))
+        avg = float(np.round(rng.uniform(lo, hi), 2))
+        layers.append(_deploy_random_layer(env, rng, d_in, d_out, bit_set, avg, int(rng.choice([0, 4500, 50000])),
+                                           int(rng.choice([0, 500, 20000]))))
+        Xs.append(_dev(rng.normal(0, 1, (m, d_in)).astype(np.float16)))
+    deps = [d for _, _, d in layers]
+    Ys = [torch.full((m, d.d_out), -5.0, dtype=torch.float32, device=DEV) for d in deps]
+    P.group_products(deps)(Xs, Ys, ws)
+    torch.cuda.synchronize()
+    for (W, r, dep), X, Y in zip(layers, Xs, Ys):
+        assert torch.equal(Y, P.lut_matvec(dep, X, ws))
+        out_idx = _np(r.out_idx).astype(np.int64)
+        What = _what(W, _np(r.centroids), _np(r.codes), _np(r.bits), out_idx)
+        Yref = orc.lut_matvec(_np(X), W, _np(r.centroids), _np(r.codes), _np(r.bits), out_idx)
+        _check_product(_np(Y), Yref, _np(X), What)
