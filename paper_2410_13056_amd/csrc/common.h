@@ -39,6 +39,13 @@ struct WsCarver {
     size_t need() const { return align_up(off, 256); }
 };
 
+// The wavefront's number inside its workgroup, as a value the compiler knows to be the same
+// in every lane: counters and addresses derived from it (row ranges, units, wave-chunks) then
+// live in scalar registers and the loop control costs no vector instructions.
+__device__ __forceinline__ int wave_index() {
+    return __builtin_amdgcn_readfirstlane((int)(threadIdx.x / CMPQ_WAVE));
+}
+
 __device__ __forceinline__ double wave_sum_f64(double v) {
 #pragma unroll
     for (int s = 32; s > 0; s >>= 1) v += __shfl_down(v, s, CMPQ_WAVE);

@@ -77,7 +77,7 @@ constexpr int kRedFloats = kOutPerLane * kRedStride;
 // half-wavefront either way.
 __device__ __forceinline__ void store_partial(const float (&acc)[kOutPerLane], float (*red)[kRedFloats],
                                               float *__restrict__ prow, int64_t d_out) {
-    const int lane = threadIdx.x & (CMPQ_WAVE - 1), wave = threadIdx.x / CMPQ_WAVE;
+    const int lane = threadIdx.x & (CMPQ_WAVE - 1), wave = wave_index();
     __syncthreads();  // the sums reuse the LDS of the tables: every wavefront is done with them
 #pragma unroll
     for (int k = 0; k < kOutPerLane; ++k) red[wave][k * kRedStride + lane] = acc[k];
@@ -121,7 +121,7 @@ __device__ __forceinline__ void lut_slab(const LmArgs &a, const LmWidth &wd, int
     constexpr int K = 1 << B;
     // per wavefront: two buffers of kGroup row tables (K floats each)
     float(*tbl)[2][kGroup * 16] = tbl_all;
-    const int lane = threadIdx.x & (CMPQ_WAVE - 1), wave = threadIdx.x / CMPQ_WAVE;
+    const int lane = threadIdx.x & (CMPQ_WAVE - 1), wave = wave_index();
     const int64_t token = blockIdx.z;
     const __half *x = X + token * ldx;
     const int64_t word0 = (int64_t)blockIdx.x * (kTileOut / 32) * B + (int64_t)lane * B;
@@ -222,7 +222,7 @@ __device__ __forceinline__ void lut_slab_pairs(const LmArgs &a, const LmWidth &w
     static_assert(KP <= CMPQ_WAVE && kGroup % kRowsPerFill == 0, "pair tables are filled by whole wavefronts");
     const __half *__restrict__ X = a.X;
     const int64_t d_out = a.d_out;
-    const int lane = threadIdx.x & (CMPQ_WAVE - 1), wave = threadIdx.x / CMPQ_WAVE;
+    const int lane = threadIdx.x & (CMPQ_WAVE - 1), wave = wave_index();
     const int64_t token = blockIdx.z;
     const __half *x = X + token * a.ldx;
     const int64_t word0 = (int64_t)blockIdx.x * (kTileOut / 32) * B + (int64_t)lane * B;
@@ -322,7 +322,7 @@ __device__ __forceinline__ void act_slab(const LmArgs &a, int slab, float (*red)
     const __half *__restrict__ X = a.X;
     const int64_t ldx = a.ldx, d_out = a.d_out;
     float *__restrict__ partial = a.partial;
-    const int lane = threadIdx.x & (CMPQ_WAVE - 1), wave = threadIdx.x / CMPQ_WAVE;
+    const int lane = threadIdx.x & (CMPQ_WAVE - 1), wave = wave_index();
     const int64_t token = blockIdx.z;
     const __half *x = X + token * ldx;
     const int64_t o0 = (int64_t)blockIdx.x * kTileOut + (int64_t)lane * kOutPerLane;
@@ -572,7 +572,7 @@ __global__ __launch_bounds__(kThreads) void obc_order_kernel(const int32_t *__re
                                                               const float *__restrict__ tmp_delta,
                                                               int32_t *__restrict__ row_idx,
                                                               float *__restrict__ delta) {
-    const int lane = threadIdx.x & (CMPQ_WAVE - 1), wave = threadIdx.x / CMPQ_WAVE;
+    const int lane = threadIdx.x & (CMPQ_WAVE - 1), wave = wave_index();
     const int64_t o = (int64_t)blockIdx.x * kWaves + wave;
     if (o >= d_out) return;
     const int b = colptr[o], n = colptr[o + 1] - b;

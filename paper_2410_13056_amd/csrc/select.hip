@@ -298,12 +298,14 @@ __device__ __forceinline__ void fetch8(const WselArgs &a, int64_t i, int64_t o0,
 }
 
 __device__ __forceinline__ void unpack8(const Raw8<__half> &r, float (&wv)[8]) {
-    const __half2 *h = reinterpret_cast<const __half2 *>(&r.w);
+    const uint32_t w4[4] = {r.w.x, r.w.y, r.w.z, r.w.w};
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-        const float2 t = __half22float2(h[j]);
-        wv[2 * j] = t.x;
-        wv[2 * j + 1] = t.y;
+        wv[2 * j] = __half2float(__ushort_as_half((uint16_t)w4[j]));
+        // the upper half converted in place (the compiler would shift it down first)
+        asm("v_cvt_f32_f16_sdwa %0, %1 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:WORD_1"
+            : "=v"(wv[2 * j + 1])
+            : "v"(w4[j]));
     }
 }
 __device__ __forceinline__ void unpack8(const Raw8<float> &r, float (&wv)[8]) {
@@ -317,15 +319,24 @@ template <typename TW>
 __device__ __forceinline__ void score_keys8(const WselArgs &a, const Raw8<TW> &r, float cent,
                                             uint32_t (&key)[8], float (&wv)[8]) {
     unpack8(r, wv);
+    if (a.score != CMPQ_SCORE_RESIDUAL) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) key[j] = __float_as_uint(fabsf(wv[j]));
+        return;
+    }
+    // One branch for the whole piece, so that the eight lane exchanges below are issued back to
+    // back.  Four codes per word, one per byte: the byte address of lane `code` (code * 4) is a
+    // bit-field extract of the word shifted up by two.
+    float level[8];
+    const uint32_t c4[2] = {(r.c.x & 0x0f0f0f0fu) << 2, (r.c.y & 0x0f0f0f0fu) << 2};
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-        float s = fabsf(wv[j]);
-        if (a.score == CMPQ_SCORE_RESIDUAL) {
-            const int code = (int)(((j < 4 ? r.c.x : r.c.y) >> (8 * (j & 3))) & 15u);
-            s = fabsf(wv[j] - __shfl(cent, code, CMPQ_WAVE));
-        }
-        key[j] = __float_as_uint(s);
+        uint32_t at;  // written out: the compiler turns the extract back into a shift and a mask
+        asm("v_bfe_u32 %0, %1, %2, 6" : "=v"(at) : "v"(c4[j >> 2]), "n"(8 * (j & 3)));
+        level[j] = __int_as_float(__builtin_amdgcn_ds_bpermute((int)at, __float_as_int(cent)));
     }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) key[j] = __float_as_uint(fabsf(wv[j] - level[j]));
 }
 
 __device__ __forceinline__ uint32_t valid8(int64_t o0, int64_t d_out) {
@@ -340,7 +351,7 @@ __device__ __forceinline__ bool channel_live(const WselArgs &a, int64_t i) {
 
 // Calls body(i, o0, key, wv, valid) for every wave-chunk in [q0, q1) of a live channel,
 // in order; o0 is this lane's first output.  The loads of the next wave-chunk are issued
-// before the current one is worked on.
+// before the current one is worked on (two ahead was measured and is slower).
 template <typename TW, typename F>
 __device__ __forceinline__ void for_each_wave_chunk(const WselArgs &a, int64_t q0, int64_t q1, F &&body) {
     if (q0 >= q1) return;
@@ -389,12 +400,21 @@ __device__ __forceinline__ void stage_chunk(uint32_t cand, int64_t i, int64_t o0
                                             unsigned long long *__restrict__ stage_ik,
                                             uint16_t *__restrict__ stage_val, uint32_t cap,
                                             uint32_t &n_staged, bool &over) {
-    if (__ballot(cand != 0) == 0ull) return;
-    const uint32_t n_cand = __popc(cand);
-    const uint32_t incl = wave_scan_incl_u32(n_cand);
-    const uint32_t tot = __shfl(incl, CMPQ_WAVE - 1, CMPQ_WAVE);
+    const unsigned long long has = __ballot(cand != 0);
+    if (has == 0ull) return;
+    // usual case: no lane holds two - places come from the lane mask alone
+    uint32_t excl, tot;
+    if (__ballot((cand & (cand - 1)) != 0) == 0ull) {
+        excl = __builtin_amdgcn_mbcnt_hi((uint32_t)(has >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)has, 0u));
+        tot = (uint32_t)__popcll(has);
+    } else {
+        const uint32_t n_cand = __popc(cand);
+        const uint32_t incl = wave_scan_incl_u32(n_cand);
+        tot = __shfl(incl, CMPQ_WAVE - 1, CMPQ_WAVE);
+        excl = incl - n_cand;
+    }
     if (n_staged + tot <= cap) {
-        uint32_t pos = n_staged + incl - n_cand;
+        uint32_t pos = n_staged + excl;
         while (__ballot(cand != 0) != 0ull) {
             if (cand) {
                 const int j = __ffs(cand) - 1;
@@ -502,7 +522,7 @@ __global__ __launch_bounds__(kWThreads) void wsel_sample_kernel(WselArgs a, uint
         if (!block_pick(hist + 3 * kBins, a.sample_rank, ps, bin0, r, tot)) return;
     }
     __syncthreads();
-    const int lane = threadIdx.x & (CMPQ_WAVE - 1), wave = threadIdx.x / CMPQ_WAVE;
+    const int lane = threadIdx.x & (CMPQ_WAVE - 1), wave = wave_index();
     const int64_t n_waves = (int64_t)gridDim.x * kWaves;
     // few workgroups (every one ends with a flush into the same global counters), several
     // wave-chunks per wavefront, the next one's loads issued before the current one is used
@@ -563,18 +583,21 @@ __global__ __launch_bounds__(kWThreads) void wsel_stage_kernel(WselArgs a, WselS
             guess22 = (bin0 << 11) | bin1;
     }
     if (blockIdx.x == 0 && threadIdx.x == 0) st->guess22 = guess22;
-    const int lane = threadIdx.x & (CMPQ_WAVE - 1), wave = threadIdx.x / CMPQ_WAVE;
+    const int lane = threadIdx.x & (CMPQ_WAVE - 1), wave = wave_index();
     const int64_t unit = (int64_t)blockIdx.x * kWaves + wave;
     const int64_t q0 = unit * a.wc_per_unit;
     const int64_t q1 = min(a.total_wc, q0 + a.wc_per_unit);
     uint32_t n_staged = 0;
     bool over = false;
+    const uint32_t reach = guess22 << 10;  // (key >> 10) >= guess22 as one compare
     unsigned long long *stage_ik = a.stage_ik + unit * a.cap;
     uint16_t *stage_val = a.stage_val + unit * a.cap;
     for_each_wave_chunk<TW>(a, q0, q1, [&](int64_t i, int64_t o0, const uint32_t (&key)[8], const float (&wv)[8], uint32_t valid) {
+        // bit j of cand: entry j exists and reaches the guess
         uint32_t cand = 0;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) cand |= (uint32_t)(((valid >> j) & 1u) && (key[j] >> 10) >= guess22) << j;
+        for (int j = 7; j >= 0; --j) cand = cand + cand + (key[j] >= reach ? 1u : 0u);
+        cand &= valid;
         stage_chunk(cand, i, o0, a.d_out, key, wv, stage_ik, stage_val, a.cap, n_staged, over);
     });
     if (lane == 0) {
@@ -606,7 +629,7 @@ __global__ __launch_bounds__(kWThreads) void wsel_list_kernel(WselArgs a, WselSt
         return;
     }
     __syncthreads();
-    const int lane = threadIdx.x & (CMPQ_WAVE - 1), wave = threadIdx.x / CMPQ_WAVE;
+    const int lane = threadIdx.x & (CMPQ_WAVE - 1), wave = wave_index();
     for (int64_t unit = (int64_t)blockIdx.x * kWaves + wave; unit < nunits; unit += (int64_t)gridDim.x * kWaves) {
         const unsigned long long *ik = a.stage_ik + unit * a.cap;
         const uint32_t n = a.stage_cnt[unit];
@@ -666,7 +689,7 @@ __global__ __launch_bounds__(kWThreads) void wsel_hist_kernel(WselArgs a, WselSt
         exact_prefix(hist, k, PASS, ps, prefix, rem, all);  // the digits the passes before this one fixed
     }
     __syncthreads();
-    const int lane = threadIdx.x & (CMPQ_WAVE - 1), wave = threadIdx.x / CMPQ_WAVE;
+    const int lane = threadIdx.x & (CMPQ_WAVE - 1), wave = wave_index();
     uint32_t *lh0 = lh + (lane & (kCopies - 1)) * kBins;
     const int64_t unit = (int64_t)blockIdx.x * kWaves + wave;
     const int64_t q0 = unit * a.wc_per_unit;
@@ -728,7 +751,7 @@ __global__ __launch_bounds__(kWThreads) void wsel_count_kernel(WselState *st, Ws
                                                                 uint32_t *__restrict__ cnt_eq) {
     __shared__ uint32_t red[kWaves];
     __shared__ PickShared ps;
-    const int lane = threadIdx.x & (CMPQ_WAVE - 1), wave = threadIdx.x / CMPQ_WAVE;
+    const int lane = threadIdx.x & (CMPQ_WAVE - 1), wave = wave_index();
     const bool exact = st->fast_failed != 0;
     uint32_t T;
     uint64_t need;
@@ -829,7 +852,7 @@ __device__ __forceinline__ void emit_from_list(const WselArgs &a, const WselStat
                                                const uint64_t *__restrict__ tie_base,
                                                const uint64_t *__restrict__ out_base, int64_t k,
                                                int32_t *__restrict__ idx_out, uint16_t *__restrict__ val_out) {
-    const int lane = threadIdx.x & (CMPQ_WAVE - 1), wave = threadIdx.x / CMPQ_WAVE;
+    const int lane = threadIdx.x & (CMPQ_WAVE - 1), wave = wave_index();
     const int64_t unit = (int64_t)blockIdx.x * kWaves + wave;
     const uint32_t T = st->T;
     const uint64_t need = st->need;
@@ -863,7 +886,7 @@ __device__ __forceinline__ void write_full(const WselArgs &a, const WselState *s
                                            const uint64_t *__restrict__ out_base, int64_t k,
                                            int32_t *__restrict__ idx_out, uint16_t *__restrict__ val_out,
                                            uint32_t *scan) {
-    const int lane = threadIdx.x & (CMPQ_WAVE - 1), wave = threadIdx.x / CMPQ_WAVE;
+    const int lane = threadIdx.x & (CMPQ_WAVE - 1), wave = wave_index();
     const uint32_t T = st->T;
     const uint64_t need = st->need;
     uint64_t ties = tie_base[blockIdx.x], outp = out_base[blockIdx.x];
