@@ -56,14 +56,16 @@ __device__ __forceinline__ uint32_t load8w(const TW *__restrict__ wrow, int64_t 
     return valid;
 }
 
-// lanes_per_group: a power of two in 1..64 (group / 8)
-template <typename TW, bool WITH_ERR>
+// lanes_per_group: a power of two in 1..64 (group / 8).  VEC: rows are read and written in
+// whole 8-weight pieces (aligned, d_out a multiple of 8), so a lane's piece exists entirely
+// or not at all and no entry needs a test of its own.
+template <typename TW, bool WITH_ERR, bool VEC>
 __global__ __launch_bounds__(kT) void rtn_kernel(const TW *__restrict__ W, int64_t d_out, int64_t ldw,
                                                   const uint8_t *__restrict__ bits, int lanes_per_group,
                                                   int64_t n_groups, uint8_t *__restrict__ codes,
                                                   float *__restrict__ scale, float *__restrict__ zero,
-                                                  double *__restrict__ err_ch, int32_t *__restrict__ status,
-                                                  int vec_ok) {
+                                                  double *__restrict__ err_ch, int32_t *__restrict__ status) {
+    constexpr int vec_ok = VEC ? 1 : 0;
     __shared__ double red[kT / CMPQ_WAVE];
     const int64_t i = blockIdx.x;
     const int tid = threadIdx.x;
@@ -78,10 +80,11 @@ __global__ __launch_bounds__(kT) void rtn_kernel(const TW *__restrict__ W, int64
         const int64_t o0 = base + (int64_t)tid * kPer;
         float w[kPer];
         const uint32_t valid = load8w<TW>(wrow, o0, d_out, vec_ok, w);
+        auto has = [&](int j) -> bool { return VEC ? valid != 0u : ((valid >> j) & 1u) != 0u; };
         float lo = INFINITY, hi = -INFINITY;
 #pragma unroll
         for (int j = 0; j < kPer; ++j)
-            if ((valid >> j) & 1u) {
+            if (has(j)) {
                 lo = fminf(lo, w[j]);
                 hi = fmaxf(hi, w[j]);
                 bad |= !isfinite(w[j]);
@@ -93,14 +96,16 @@ __global__ __launch_bounds__(kT) void rtn_kernel(const TW *__restrict__ W, int64
         }
         if (!valid) continue;
         float r[kPer];
-        if (kept) {
 #pragma unroll
-            for (int j = 0; j < kPer; ++j) {
-                r[j] = 0.f;
-                if (WITH_ERR && ((valid >> j) & 1u)) {
-                    const double d = (double)w[j] - (double)__half2float(__float2half_rn(w[j]));
-                    s = fma(d, d, s);
-                }
+        for (int j = 0; j < kPer; ++j) r[j] = 0.f;
+        if (kept) {
+            if (WITH_ERR) {
+#pragma unroll
+                for (int j = 0; j < kPer; ++j)
+                    if (has(j)) {
+                        const double d = (double)w[j] - (double)__half2float(__float2half_rn(w[j]));
+                        s = fma(d, d, s);
+                    }
             }
             lo = 0.f;
             hi = 0.f;
@@ -111,36 +116,39 @@ __global__ __launch_bounds__(kT) void rtn_kernel(const TW *__restrict__ W, int64
             scale[i * n_groups + g] = delta;
             zero[i * n_groups + g] = lo;
         }
-        if (!kept) {
+        if (!kept && delta != 0.f) {
             // The correctly rounded quotient (w - lo) / delta.  With delta well inside the
             // normal range this is the usual division sequence - reciprocal estimate, one
             // Newton step, then two residual corrections of the quotient - with the part that
             // only depends on delta done once per step instead of once per weight; no
             // intermediate can leave the normal range for a quotient that rounds to a code
             // above 0.  Other steps (tiny or huge delta) divide in the ordinary way.
-            const bool fast = delta >= 0x1p-60f && delta <= 0x1p60f;
-            float y = 0.f;
-            if (fast) {
+            float quo[kPer];
+            if (delta >= 0x1p-60f && delta <= 0x1p60f) {
                 const float y0 = __builtin_amdgcn_rcpf(delta);
-                y = fmaf(fmaf(-delta, y0, 1.f), y0, y0);
-            }
+                const float y = fmaf(fmaf(-delta, y0, 1.f), y0, y0);
 #pragma unroll
-            for (int j = 0; j < kPer; ++j) {
-                const float a = w[j] - lo;
-                float quo = 0.f;
-                if (fast) {
+                for (int j = 0; j < kPer; ++j) {
+                    const float a = w[j] - lo;
                     const float m = a * y;
                     const float q1 = fmaf(fmaf(-delta, m, a), y, m);
-                    quo = fmaf(fmaf(-delta, q1, a), y, q1);
-                } else if (delta != 0.f) {
-                    quo = a / delta;
+                    quo[j] = fmaf(fmaf(-delta, q1, a), y, q1);
                 }
-                r[j] = ((valid >> j) & 1u) ? fminf(fmaxf(rintf(quo), 0.f), top) : 0.f;
-                if (WITH_ERR && ((valid >> j) & 1u)) {
+            } else {
+#pragma unroll
+                for (int j = 0; j < kPer; ++j) quo[j] = (w[j] - lo) / delta;
+            }
+#pragma unroll
+            for (int j = 0; j < kPer; ++j)
+                if (has(j)) r[j] = fminf(fmaxf(rintf(quo[j]), 0.f), top);
+        }
+        if (WITH_ERR && !kept) {
+#pragma unroll
+            for (int j = 0; j < kPer; ++j)
+                if (has(j)) {
                     const double d = (double)w[j] - fma((double)r[j], (double)delta, (double)lo);
                     s = fma(d, d, s);
                 }
-            }
         }
         // r holds whole numbers in 0..15: the conversion packs them as bytes
         uint2 out = make_uint2(0u, 0u);
@@ -149,7 +157,7 @@ __global__ __launch_bounds__(kT) void rtn_kernel(const TW *__restrict__ W, int64
             out.x = __builtin_amdgcn_cvt_pk_u8_f32(r[j], j, out.x);
             out.y = __builtin_amdgcn_cvt_pk_u8_f32(r[4 + j], j, out.y);
         }
-        if (vec_ok && valid == 0xffu) {
+        if (VEC) {
             *reinterpret_cast<uint2 *>(crow + o0) = out;
         } else {
 #pragma unroll
@@ -188,16 +196,19 @@ extern "C" int cmpq_rtn_quantize(const void *W, int dtype, int64_t d_in, int64_t
     const int lpg = (int)(group / kPer);
     const int64_t n_groups = cdiv(d_out, group);
     const unsigned grid = (unsigned)d_in;
-#define CMPQ_RTN_LAUNCH(TW, ERR)                                                                          \
-    rtn_kernel<TW, ERR><<<grid, kT, 0, s>>>(static_cast<const TW *>(W), d_out, ldw, bits, lpg, n_groups, \
-                                            codes, scale, zero, err_ch, status, vec_ok)
-    if (dtype == CMPQ_F16) {
-        if (err_ch) CMPQ_RTN_LAUNCH(__half, true);
-        else CMPQ_RTN_LAUNCH(__half, false);
-    } else {
-        if (err_ch) CMPQ_RTN_LAUNCH(float, true);
-        else CMPQ_RTN_LAUNCH(float, false);
-    }
+#define CMPQ_RTN_LAUNCH(TW, ERR, VEC)                                                                          \
+    rtn_kernel<TW, ERR, VEC><<<grid, kT, 0, s>>>(static_cast<const TW *>(W), d_out, ldw, bits, lpg, n_groups, \
+                                                 codes, scale, zero, err_ch, status)
+#define CMPQ_RTN_PICK(TW)                                        \
+    do {                                                         \
+        if (err_ch && vec_ok) CMPQ_RTN_LAUNCH(TW, true, true);   \
+        else if (err_ch) CMPQ_RTN_LAUNCH(TW, true, false);       \
+        else if (vec_ok) CMPQ_RTN_LAUNCH(TW, false, true);       \
+        else CMPQ_RTN_LAUNCH(TW, false, false);                  \
+    } while (0)
+    if (dtype == CMPQ_F16) CMPQ_RTN_PICK(__half);
+    else CMPQ_RTN_PICK(float);
+#undef CMPQ_RTN_PICK
 #undef CMPQ_RTN_LAUNCH
     CMPQ_LAUNCH_CHECK();
     return CMPQ_OK;
