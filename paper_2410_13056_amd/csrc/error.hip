@@ -102,11 +102,18 @@ __global__ __launch_bounds__(kT) void dequant_error_kernel(
             if (!valid[u]) continue;
             // o is a multiple of 8: the 8 flags sit in one byte of the bitmap
             const uint32_t back = whole ? 0xffu : (restored[o >> 5] >> (o & 31)) & 0xffu;
+            // the eight levels first, without conditions, so that the look-ups go out together
+            float level[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) level[j] = lut[c[u][j] & 15u];
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
-                if (!((valid[u] >> j) & 1u)) continue;
-                const float what = ((back >> j) & 1u) ? __half2float(__float2half_rn(w[u][j]))
-                                                      : lut[c[u][j] & 15u];
+                // a restored entry is the weight rounded to FP16 (itself for FP16 input); an entry
+                // past the end of the channel counts as exact
+                float what = level[j];
+                if ((back >> j) & 1u)
+                    what = sizeof(TW) == 2 ? w[u][j] : __half2float(__float2half_rn(w[u][j]));
+                if (!((valid[u] >> j) & 1u)) what = w[u][j];
                 const double e = (double)w[u][j] - (double)what;
                 s = fma(e, e, s);
             }
