@@ -70,26 +70,33 @@ struct LmGroup {
 };
 
 constexpr int kRedStride = CMPQ_WAVE + 1;  // sums of output k of all lanes: 64 floats, padded by one
-constexpr int kRedFloats = kOutPerLane * kRedStride;
+constexpr int kRedHalf = kOutPerLane / 2;  // the sums meet in LDS in two halves of 16 outputs per lane
+constexpr int kRedFloats = kRedHalf * kRedStride;
 
 // The four wavefronts' sums of a 2048-output tile, added in wavefront order, into a partial
-// row.  Called once by every lane of the workgroup.  Lanes write with stride 1 and read with stride 65: no bank is hit twice by a
-// half-wavefront either way.
+// row.  Called once by every lane of the workgroup.  Lanes write with stride 1 and read with
+// stride 65: no bank is hit twice by a half-wavefront either way.  Two halves, so that the
+// LDS of a workgroup stays small enough for five workgroups per compute unit.
 __device__ __forceinline__ void store_partial(const float (&acc)[kOutPerLane], float (*red)[kRedFloats],
                                               float *__restrict__ prow, int64_t d_out) {
     const int lane = threadIdx.x & (CMPQ_WAVE - 1), wave = wave_index();
-    __syncthreads();  // the sums reuse the LDS of the tables: every wavefront is done with them
 #pragma unroll
-    for (int k = 0; k < kOutPerLane; ++k) red[wave][k * kRedStride + lane] = acc[k];
-    __syncthreads();
-    for (int c = threadIdx.x; c < kTileOut; c += kThreads) {
-        const int64_t o = (int64_t)blockIdx.x * kTileOut + c;
-        if (o < d_out) {
-            const int at = (c & (kOutPerLane - 1)) * kRedStride + (c / kOutPerLane);
-            float t = red[0][at];
+    for (int h = 0; h < 2; ++h) {
+        __syncthreads();  // the sums reuse the LDS of the tables (and of the first half)
 #pragma unroll
-            for (int wv = 1; wv < kWaves; ++wv) t += red[wv][at];
-            prow[o] = t;
+        for (int k = 0; k < kRedHalf; ++k) red[wave][k * kRedStride + lane] = acc[h * kRedHalf + k];
+        __syncthreads();
+        // lane l holds outputs 32 l .. 32 l + 31 of the tile; this half covers k = 16 h .. 16 h + 15
+        for (int c = threadIdx.x; c < kTileOut / 2; c += kThreads) {
+            const int l = c / kRedHalf, k = c % kRedHalf;
+            const int64_t o = (int64_t)blockIdx.x * kTileOut + l * kOutPerLane + h * kRedHalf + k;
+            if (o < d_out) {
+                const int at = k * kRedStride + l;
+                float t = red[0][at];
+#pragma unroll
+                for (int wv = 1; wv < kWaves; ++wv) t += red[wv][at];
+                prow[o] = t;
+            }
         }
     }
 }
@@ -215,7 +222,7 @@ template <int B>
 __device__ __forceinline__ void lut_slab_pairs(const LmArgs &a, const LmWidth &wd, int slab, float *smem,
                                                float (*red)[kRedFloats]) {
     constexpr int K = 1 << B, PB = 2 * B, KP = 1 << PB;   // levels, bits of a pair, entries of a pair table
-    constexpr int kRowsPerFill = CMPQ_WAVE / KP;           // rows whose tables one pass over the lanes fills
+    constexpr int kRowsPerFill = CMPQ_WAVE / KP < kGroup ? CMPQ_WAVE / KP : kGroup;  // rows one pass over the lanes fills
     constexpr int kFills = kGroup / kRowsPerFill;
     constexpr int kRowFloats = 2 * KP;                     // A then B
     constexpr int kBufFloats = kGroup * kRowFloats;
@@ -240,7 +247,7 @@ __device__ __forceinline__ void lut_slab_pairs(const LmArgs &a, const LmWidth &w
             const int64_t row = r + f * kRowsPerFill + fill_row;
             ea[f] = 0.f;
             eb[f] = 0.f;
-            if (row < r1) {
+            if (fill_row < kRowsPerFill && row < r1) {
                 const float xi = __half2float(x[wd.chan_idx[row]]);
                 ea[f] = xi * __half2float(__ushort_as_half(wd.lut[row * K + (fill_e & (K - 1))]));
                 eb[f] = xi * __half2float(__ushort_as_half(wd.lut[row * K + (fill_e >> B)]));
@@ -274,9 +281,11 @@ __device__ __forceinline__ void lut_slab_pairs(const LmArgs &a, const LmWidth &w
             float *mine = smem + (wave * 2 + buf) * kBufFloats;
 #pragma unroll
             for (int f = 0; f < kFills; ++f) {
-                float *row_tbl = mine + (f * kRowsPerFill + fill_row) * kRowFloats;
-                row_tbl[fill_e] = ea[f];
-                row_tbl[KP + fill_e] = eb[f];
+                if (fill_row < kRowsPerFill) {
+                    float *row_tbl = mine + (f * kRowsPerFill + fill_row) * kRowFloats;
+                    row_tbl[fill_e] = ea[f];
+                    row_tbl[KP + fill_e] = eb[f];
+                }
             }
             if (r + kGroup < r1) {
                 table_entries(r + kGroup, ean, ebn);
@@ -384,7 +393,7 @@ __global__ __launch_bounds__(kThreads) void lut_matvec_kernel(LmGroup g) {
     __shared__ float smem[kWaves * kRedFloats];
     float(*tbl)[2][kGroup * 16] = reinterpret_cast<float(*)[2][kGroup * 16]>(smem);
     float(*red)[kRedFloats] = reinterpret_cast<float(*)[kRedFloats]>(smem);
-    static_assert(kWaves * 2 * kGroup * 2 * 64 <= kWaves * kRedFloats, "pair tables fit the shared piece");
+    static_assert(kWaves * 2 * kGroup * 2 * 16 <= kWaves * kRedFloats, "pair tables fit the shared piece");
     int l = 0;
     while (l + 1 < g.n_layers && (int)blockIdx.y >= g.l[l + 1].y0) ++l;
     const LmArgs &a = g.l[l];
