@@ -245,6 +245,19 @@ def rtn_quantize(W: np.ndarray, bits: np.ndarray, group: int = 128):
     return codes, scale, zero, err
 
 
+def lut4(centroids: np.ndarray, bits: np.ndarray):
+    """Sec. 5.1 / Tab. 7: the look-up tables in 4 bits, one uniform grid per layer.  Returns
+    ``(codes4 uint8[d_in,16], range float32[2] = [min, step], centroids_q float32[d_in,16])``."""
+    cent = _c(centroids, np.float32)
+    d_in = cent.shape[0]
+    codes4 = np.zeros((d_in, KMAX), np.uint8)
+    rng = np.zeros(2, np.float32)
+    cq = np.zeros((d_in, KMAX), np.float32)
+    rc = lib().orc_lut4(_p(cent), _p(_c(bits, np.uint8)), ctypes.c_int64(d_in), _p(codes4), _p(rng), _p(cq))
+    assert rc == 0, rc
+    return codes4, rng, cq
+
+
 def quantize_layer(W: np.ndarray, X: np.ndarray, bit_set: Sequence[int], avg_bits: float,
                    rho_act_ppm: int = 4500, rho_q_ppm: int = 500, iters: int = 20,
                    sumsq: Optional[np.ndarray] = None, score: int = SCORE_RESIDUAL) -> dict:

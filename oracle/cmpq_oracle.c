@@ -20,7 +20,8 @@
  *   orc_pack             per-width code matrices + FP16 look-up tables (Sec. 5.1, Fig. 4)
  *   orc_dequant_error    W_hat = W_q + O and ||X (W - W_hat)|| (Sec. 3.2.2; App. B.3 eq. Delta Y)
  * Beside the path: orc_lut_matvec (Fig. 4), orc_act_stats_norm (App. Tab. 13) and
- * orc_rtn_quantize (App. A.2: the uniform quantizer of Sec. 3 in place of K-means).
+ * orc_rtn_quantize (App. A.2: the uniform quantizer of Sec. 3 in place of K-means),
+ * orc_lut4 (Sec. 5.1, Tab. 7: the look-up tables themselves held in 4 bits).
  *
  * Parity pins (tests/ -m "not gpu") cover every function here; none is
  * "parity unpinned" except the k-means trajectory on large inputs, which is
@@ -616,6 +617,58 @@ int orc_rtn_quantize(const void *W, int dtype, int64_t d_in, int64_t d_out, int6
             }
         }
         if (err_ch) err_ch[i] = e;
+    }
+    return 0;
+}
+
+/* ---- Sec. 5.1 (Tab. 7): look-up tables in 4 bits ---------------------------------------------- */
+
+/*
+ * The variant that stores every cluster centre in 4 bits instead of FP16.  The paper gives
+ * only the storage figure, (1*4 + 8*4)/4096 < 0.01 bit per weight for a 3-bit channel, which
+ * leaves no room for a scale per channel; it does not say how the centres are quantized.
+ * Reading: the uniform quantizer of Sec. 3 with N = 4 over all centres of the layer at once
+ * (one min and one Delta per layer, 8 bytes that do not show in the per-weight figure):
+ *     lo = min, hi = max over the levels of all channels with bits in 1..4,
+ *     Delta = (hi - lo) / 15,  code = Clamp(round((c - lo) / Delta), 0, 15),
+ *     c_q = lo + code * Delta  (exact sum, rounded once to fp32),
+ * code and Delta decided in fp32 as in orc_rtn_quantize; Delta = 0 gives code 0.
+ * Unused table slots and the channels of O_act keep +infinity and code 0.
+ * range[0] = lo, range[1] = Delta (0, 0 when no channel is quantized).
+ * This function is PARITY UNPINNED as far as the paper goes (no worked values); it is
+ * pinned to the textbook properties of a min/max uniform quantizer.
+ */
+int orc_lut4(const float *centroids, const uint8_t *bits, int64_t d_in, uint8_t *codes4,
+             float *range, float *centroids_q) {
+    if (!centroids || !bits || !codes4 || !range || !centroids_q) return -1;
+    float lo = INFINITY, hi = -INFINITY;
+    for (int64_t i = 0; i < d_in; ++i) {
+        if (bits[i] < 1 || bits[i] > 4) continue;
+        for (int j = 0; j < (1 << bits[i]); ++j) {
+            const float c = centroids[i * ORC_KMAX + j];
+            if (c < lo) lo = c;
+            if (c > hi) hi = c;
+        }
+    }
+    const int any = lo <= hi;
+    const float delta = any ? (hi - lo) / 15.0f : 0.0f;
+    range[0] = any ? lo : 0.0f;
+    range[1] = delta;
+    for (int64_t i = 0; i < d_in; ++i) {
+        const int K = (bits[i] >= 1 && bits[i] <= 4) ? (1 << bits[i]) : 0;
+        for (int j = 0; j < ORC_KMAX; ++j) {
+            float q = 0.0f;
+            codes4[i * ORC_KMAX + j] = 0;
+            centroids_q[i * ORC_KMAX + j] = INFINITY;
+            if (j >= K) continue;
+            if (delta != 0.0f) {
+                q = rintf((centroids[i * ORC_KMAX + j] - lo) / delta);
+                if (q < 0.0f) q = 0.0f;
+                if (q > 15.0f) q = 15.0f;
+            }
+            codes4[i * ORC_KMAX + j] = (uint8_t)q;
+            centroids_q[i * ORC_KMAX + j] = (float)((double)lo + (double)q * (double)delta);
+        }
     }
     return 0;
 }

@@ -739,3 +739,64 @@ def test_rtn_more_bits_never_hurt_and_kmeans_is_no_worse_on_heavy_tails(orc):
         if prev is not None:
             assert np.all(e_rtn < prev)
         prev = e_rtn
+
+
+# ----------------------------------------------------------------------------- Sec. 5.1 / Tab. 7: 4-bit tables
+
+def test_lut4_hand_example_and_textbook_properties(orc):
+    """One uniform 16-level grid per layer (Sec. 3's quantizer with N = 4 over all centres): a
+    table that already lies on such a grid is kept exactly; otherwise no centre moves by more
+    than half a step, the smallest and largest centre of the layer are kept, codes are
+    monotone in the centre, unused slots and FP16 channels stay +infinity, and doing it again
+    changes nothing."""
+    cent = np.full((3, 16), np.inf, np.float32)
+    cent[0, :4] = [-1.5, -0.5, 0.5, 1.5]                       # a 2-bit channel on the grid -1.5 + 0.2 k
+    cent[1, :8] = np.array([-1.5, -1.1, -0.7, -0.3, 0.1, 0.5, 0.9, 1.3], np.float32)
+    cent[2, :4] = [7, 8, 9, 10]                                # a channel kept in FP16: ignored
+    bits = np.array([2, 3, 16], np.uint8)
+    codes4, rng, cq = orc.lut4(cent, bits)
+    assert rng[0] == np.float32(-1.5) and abs(rng[1] - 0.2) < 1e-7
+    assert codes4[0, :4].tolist() == [0, 5, 10, 15] and codes4[1, :8].tolist() == [0, 2, 4, 6, 8, 10, 12, 14]
+    assert np.allclose(cq[0, :4], cent[0, :4], atol=1e-6) and np.allclose(cq[1, :8], cent[1, :8], atol=1e-6)
+    assert np.all(np.isposinf(cq[0, 4:])) and np.all(np.isposinf(cq[2])) and not codes4[2].any()
+
+    r = np.random.default_rng(3)
+    cent = np.full((40, 16), np.inf, np.float32)
+    bits = r.choice(np.array([1, 2, 3, 4, 16], np.uint8), 40)
+    for i, b in enumerate(bits):
+        if b <= 4:
+            cent[i, :1 << b] = np.sort(r.normal(0, 0.03, 1 << b)).astype(np.float32)
+    codes4, rng, cq = orc.lut4(cent, bits)
+    live = np.isfinite(cq)
+    assert np.array_equal(live, np.isfinite(cent) & (bits[:, None] <= 4))
+    step = float(rng[1])
+    assert np.all(np.abs(cq[live].astype(np.float64) - cent[live]) <= step / 2 * (1 + 1e-5))
+    assert cq[live].min() == cent[live].min() and abs(cq[live].max() - cent[live].max()) <= 1e-6 * step
+    assert codes4[live].min() == 0 and codes4[live].max() == 15
+    order = np.argsort(cent[live], kind="stable")
+    assert np.all(np.diff(codes4[live][order].astype(int)) >= 0)
+    again = orc.lut4(cq, bits)
+    assert np.array_equal(again[0], codes4) and np.allclose(again[2][live], cq[live], rtol=0, atol=1e-4 * step)
+    # a layer whose centres all coincide, and a layer without quantized channels
+    same = np.full((2, 16), np.inf, np.float32)
+    same[:, :4] = 0.25
+    c, g, q = orc.lut4(same, np.array([2, 2], np.uint8))
+    assert g.tolist() == [0.25, 0.0] and not c.any() and np.all(q[:, :4] == 0.25)
+    c, g, q = orc.lut4(same, np.array([16, 16], np.uint8))
+    assert g.tolist() == [0.0, 0.0] and np.all(np.isposinf(q))
+
+
+def test_lut4_costs_little_error_on_a_quantized_layer(orc):
+    """Tab. 7 reports a small loss from 4-bit tables.  On a layer whose channels share one
+    scale the 16-level grid moves every level by at most half a step of the layer's range / 15,
+    so the reconstruction error grows, but stays far below that of dropping one bit of width."""
+    r = np.random.default_rng(5)
+    W = (r.standard_t(5, size=(24, 512)) * 0.02).astype(np.float16)
+    bits3, bits2 = np.full(24, 3, np.uint8), np.full(24, 2, np.uint8)
+    cent, codes = orc.kmeans(W, bits3, iters=10)
+    e16 = orc.dequant_error(W, cent, codes, bits3)[1][1]
+    _, _, cq = orc.lut4(cent, bits3)
+    e4 = orc.dequant_error(W, cq, codes, bits3)[1][1]
+    cent2, codes2 = orc.kmeans(W, bits2, iters=10)
+    e_2bit = orc.dequant_error(W, cent2, codes2, bits2)[1][1]
+    assert e16 <= e4 < e_2bit
