@@ -178,6 +178,29 @@ def retarget(P, B, torch, out, layers, wl, reps):
             "ms_per_budget": dt * 1e3, "Mparams_per_s": wl.params / dt / 1e6}
 
 
+def lut4_variant(P, B, torch, out, layers, wl, reps):
+    """The tables of the block just quantized on one 16-level grid per layer (Sec. 5.1 / Tab. 7),
+    the stored format written again, and the reconstruction error with them."""
+    dev = next(iter(out.values())).codes.device
+    ws = B.Workspace(dev)
+
+    def block():
+        return [P.tables_in_4_bits(out[n], ws, with_error=True)[2] for n, _ in layers]
+
+    block()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        qs = block()
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / reps
+    e16 = sum(float(out[n].err_total[0]) for n, _ in layers)
+    e4 = sum(float(q.err_total[0]) for q in qs)
+    return {"what": "look-up tables in 4 bits (one uniform grid per layer): tables, stored format and error of "
+                    "all layers", "ms_per_block": dt * 1e3,
+            "weighted_error_vs_fp16_tables": e4 / e16 if e16 > 0 else None}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -196,6 +219,8 @@ def main():
                          "beside the headline figure; 0: skip")
     ap.add_argument("--retarget-reps", type=int, default=2,
                     help="repetitions of three other average widths from kept per-width runs; 0: skip")
+    ap.add_argument("--lut4-reps", type=int, default=3,
+                    help="repetitions of the block's tables put into 4 bits (Sec. 5.1, Tab. 7); 0: skip")
     ap.add_argument("--rtn-reps", type=int, default=5,
                     help="repetitions of the block through the uniform-quantizer variant (App. A.2), reported "
                          "beside the headline figure; 0: skip")
@@ -301,6 +326,8 @@ def main():
         line["deployed_matvec"] = deployed_matvec(P, B, torch, out, layers, wl, acts, args.deploy_reps)
     if args.retarget_reps > 0:
         line["retarget"] = retarget(P, B, torch, out, layers, wl, args.retarget_reps)
+    if args.lut4_reps > 0:
+        line["lut4_variant"] = lut4_variant(P, B, torch, out, layers, wl, args.lut4_reps)
     if args.rtn_reps > 0:
         line["rtn_variant"] = rtn_variant(P, B, torch, out, layers, wl, args.rtn_reps)
     if not args.no_cpu_baseline:

@@ -344,6 +344,25 @@ int cmpq_lut_matvec(const void *X, int64_t m, int64_t d_in, int64_t ldx, int64_t
                     void *stream);
 
 /*
+ * Sec. 5.1 / Tab. 7: the look-up tables held in 4 bits, (1*4 + 8*4)/4096 bits of overhead per
+ * weight for a 3-bit channel.  The paper does not say how the centres are quantized and the
+ * figure leaves no room for a scale per channel; the reading taken is one uniform 16-level
+ * grid per layer (the quantizer of Sec. 3 with N = 4 over all centres of the layer):
+ *     lo = min, hi = max over the first 2^bits[i] levels of every channel with bits in 1..4,
+ *     Delta = (hi - lo) / 15,  code = Clamp(round((c - lo) / Delta), 0, 15)   (fp32, ties to even),
+ *     c_q = lo + code * Delta, formed exactly and rounded once to fp32;  Delta = 0: code 0.
+ *   centroids   [d_in, 16] fp32 in (from cmpq_kmeans_quantize), bits [d_in] u8.
+ *   codes4      [d_in, 16] u8 out: the 4-bit code of every table entry (0 in unused slots).
+ *   range       [2] fp32 out, device: lo and Delta (0, 0 when no channel is quantized).
+ *   centroids_q [d_in, 16] fp32 out: the rebuilt tables (+infinity in unused slots and on
+ *               channels of O_act), to be handed to cmpq_pack, cmpq_dequant_error and the
+ *               deployed product in place of `centroids`.
+ * No workspace.  d_in <= 2^27.
+ */
+int cmpq_lut4_quantize(const float *centroids, const uint8_t *bits, int64_t d_in, uint8_t *codes4,
+                       float *range, float *centroids_q, void *stream);
+
+/*
  * Several products in one pair of launches (Sec. 6 / Fig. 4 for the products that can run
  * side by side: the query, key and value projections read the same input, so do the gate and
  * up projections).  Single-token products are short, so a launch per layer is dominated by

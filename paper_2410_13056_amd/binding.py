@@ -32,7 +32,7 @@ EXPORTS = ("cmpq_workspace_bytes", "cmpq_strerror", "cmpq_count_ppm", "cmpq_act_
            "cmpq_transpose", "cmpq_allocate_bits", "cmpq_extract_outliers",
            "cmpq_kmeans_quantize", "cmpq_pack", "cmpq_dequant_error", "cmpq_set_kmeans_algorithm",
            "cmpq_gather_channels", "cmpq_outliers_by_column", "cmpq_lut_matvec", "cmpq_act_stats_norm",
-           "cmpq_rtn_quantize", "cmpq_select_by_width", "cmpq_lut_matvec_group")
+           "cmpq_rtn_quantize", "cmpq_select_by_width", "cmpq_lut_matvec_group", "cmpq_lut4_quantize")
 
 _i64, _i32, _int, _vp, _dbl, _sz = (ctypes.c_int64, ctypes.c_int32, ctypes.c_int, ctypes.c_void_p,
                                     ctypes.c_double, ctypes.c_size_t)
@@ -87,6 +87,7 @@ def lib() -> ctypes.CDLL:
         L.cmpq_lut_matvec.argtypes = [_vp, _i64, _i64, _i64, _i64, _vp, _int, _vp, _vp, _vp, _vp, _vp, _vp,
                                       _i64, _i64, _vp, _vp, _vp, _vp, _i64, _vp, _sz, _vp]
         L.cmpq_rtn_quantize.argtypes = [_vp, _int, _i64, _i64, _i64, _vp, _i64, _vp, _vp, _vp, _vp, _vp, _vp]
+        L.cmpq_lut4_quantize.argtypes = [_vp, _vp, _i64, _vp, _vp, _vp, _vp]
         L.cmpq_lut_matvec_group.argtypes = [_vp, _int, _i64, _vp, _sz, _vp]
         L.cmpq_select_by_width.argtypes = [_vp, _i64, _i64, _vp, _int, _vp, _vp, _vp, _vp, _vp]
         for name in EXPORTS[3:]:
@@ -405,3 +406,17 @@ def select_by_width(bits: torch.Tensor, bit_set: Sequence[int], centroids_by_wid
                                       (_vp * n)(*[_ptr(t) for t in codes_by_width]), _ptr(centroids), _ptr(codes),
                                       _stream()),
            "cmpq_select_by_width")
+
+
+def lut4_quantize(centroids: torch.Tensor, bits: torch.Tensor, codes4: torch.Tensor, rng: torch.Tensor,
+                  centroids_q: torch.Tensor) -> None:
+    """Sec. 5.1 / Tab. 7: the tables of a layer on one uniform 16-level grid."""
+    d_in = centroids.shape[0]
+    for t, dt in ((centroids, torch.float32), (centroids_q, torch.float32), (codes4, torch.uint8)):
+        if tuple(t.shape) != (d_in, KMAX) or not t.is_contiguous() or t.dtype != dt:
+            raise ValueError("tables are contiguous [d_in, 16]: fp32 levels, uint8 codes")
+    if rng.numel() != 2 or rng.dtype != torch.float32:
+        raise ValueError("range is fp32 [2]")
+    _check(lib().cmpq_lut4_quantize(_ptr(centroids), _ptr(bits), d_in, _ptr(codes4), _ptr(rng), _ptr(centroids_q),
+                                    _stream()),
+           "cmpq_lut4_quantize")

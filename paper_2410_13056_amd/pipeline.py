@@ -216,6 +216,39 @@ def quantize_layer_from_cache(cache: WidthCache, sumsq: torch.Tensor, avg_bits: 
                              rho_q_ppm, cache.iters, ws, score, with_error, keep_prelim, status, timer)
 
 
+def tables_in_4_bits(r: LayerResult, ws: Optional[B.Workspace] = None, with_error: bool = False,
+                     timer: Optional[StageTimer] = None):
+    """Sec. 5.1 / Tab. 7: re-expresses the look-up tables of a quantized layer on one uniform
+    16-level grid and writes the stored format again with them.  Returns
+    ``(codes4 [d_in,16] uint8, range [2] fp32 = (min, step), LayerResult with the rebuilt tables)``."""
+    ws = ws or B.Workspace(r.codes.device)
+    dev = r.codes.device
+    codes4 = torch.empty((r.d_in, B.KMAX), dtype=torch.uint8, device=dev)
+    rng = torch.empty(2, dtype=torch.float32, device=dev)
+    cent_q = torch.empty((r.d_in, B.KMAX), dtype=torch.float32, device=dev)
+    with _stage(timer, "lut4"):
+        B.lut4_quantize(r.centroids, r.bits, codes4, rng, cent_q)
+    packed, chan_idx, lut = [], [], []
+    for b, c in zip(r.bit_set, r.counts):
+        if c == 0:
+            packed.append(None), chan_idx.append(None), lut.append(None)
+            continue
+        packed.append(torch.empty((c, (r.d_out * b + 31) // 32), dtype=torch.int32, device=dev))
+        chan_idx.append(torch.empty(c, dtype=torch.int32, device=dev))
+        lut.append(torch.empty((c, 1 << b), dtype=torch.float16, device=dev))
+    with _stage(timer, "pack"):
+        B.pack(r.codes, r.bits, cent_q, r.bit_set, r.counts, packed, chan_idx, lut, ws)
+    q = dataclasses.replace(r, centroids=cent_q, packed=packed, chan_idx=chan_idx, lut=lut, err_ch=None,
+                            err_total=None)
+    if with_error:
+        q.err_ch = torch.empty(r.d_in, dtype=torch.float64, device=dev)
+        q.err_total = torch.empty(2, dtype=torch.float64, device=dev)
+        with _stage(timer, "dequant_error"):
+            B.dequant_error(r.W_t, cent_q, r.codes, r.bits, r.out_idx, int(r.out_idx.numel()), r.sumsq, q.err_ch,
+                            q.err_total, ws)
+    return codes4, rng, q
+
+
 @dataclasses.dataclass
 class RtnResult:
     """A layer quantized with the uniform quantizer (App. A.2; device tensors)."""

@@ -126,6 +126,10 @@ def test_host_side_argument_errors(L):
     assert L.cmpq_lut_matvec_group(None, 0, 1, None, 0, None) == 0                             # an empty group
     assert L.cmpq_lut_matvec_group(None, 2, 1, None, 0, None) == -1                            # layers missing
     assert L.cmpq_lut_matvec_group(fake, 9, 1, None, 0, None) == -1                            # more than CMPQ_MAX_GROUP
+    # tables in 4 bits
+    assert L.cmpq_lut4_quantize(fake, fake, 4, fake, None, fake, None) == -1                    # no range
+    assert L.cmpq_lut4_quantize(None, fake, 4, fake, fake, fake, None) == -1                    # no tables
+    assert L.cmpq_lut4_quantize(fake, fake, -1, fake, fake, fake, None) == -1
     # the uniform quantizer
     assert L.cmpq_rtn_quantize(fake, 0, 4, 64, 64, fake, 96, fake, fake, fake, None, None, None) == -1    # group no power of two
     assert L.cmpq_rtn_quantize(fake, 0, 4, 64, 64, fake, 4, fake, fake, fake, None, None, None) == -1     # group below 8
