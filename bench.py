@@ -247,10 +247,10 @@ def main():
     ws = B.Workspace(dev) if args.streams <= 1 else [B.Workspace(dev) for _ in range(args.streams)]
     status = torch.zeros(1, dtype=torch.int32, device=dev)
 
-    def step(timer=None):
+    def step(timer=None, join=True):
         return P.quantize_block(weights, acts, layers, wl.bit_set, wl.avg_bits, wl.rho_act_ppm,
                                 wl.rho_q_ppm, wl.iters, ws, with_error=True, status=status, timer=timer,
-                                streams=args.streams)
+                                streams=args.streams, join=join)
 
     if args.calibration_copy:
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
@@ -268,6 +268,21 @@ def main():
         out = step(timer)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    back_to_back = None
+    if args.streams > 1:
+        # the same steps without joining the streams in between: the queues of one block run on
+        # into the next, as when a model is quantized block after block
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for _ in range(args.steps):
+            o2 = step(join=False)
+        P.join_streams(dev, args.streams)
+        torch.cuda.synchronize()
+        dt2 = time.perf_counter() - t1
+        del o2
+        back_to_back = {"note": "the same steps with the streams joined once at the end instead of after every step",
+                        "ms_per_step": dt2 / args.steps * 1e3,
+                        "Mparams_per_s": wl.params * args.steps / dt2 / 1e6}
     assert status.item() == 0, "non-finite input flagged"
 
     stages = timer.totals()
@@ -312,6 +327,8 @@ def main():
                           "frac": x_bytes * n_st_steps / (ms_st / 1e3) / 1e9 / HBM_PEAK_GBS,
                           "from": "serial steps" if serial is not None else "timed steps"},
     }
+    if back_to_back is not None:
+        line["steps_back_to_back"] = back_to_back
     if serial is not None:
         n1, ms1 = serial["kmeans"]
         line["serial"] = {

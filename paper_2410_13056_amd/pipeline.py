@@ -386,7 +386,8 @@ def assign_layers(sizes: Dict[str, int], streams: int) -> List[tuple]:
 def quantize_block(weights: Dict[str, torch.Tensor], acts: Dict[str, torch.Tensor], layers, bit_set,
                    avg_bits: float, rho_act_ppm: int, rho_q_ppm: int, iters: int,
                    ws=None, with_error: bool = False, status: Optional[torch.Tensor] = None,
-                   timer: Optional[StageTimer] = None, streams: int = 1) -> Dict[str, LayerResult]:
+                   timer: Optional[StageTimer] = None, streams: int = 1,
+                   join: bool = True) -> Dict[str, LayerResult]:
     """One pass of the whole path over a decoder block: statistics once per distinct
     input, then every linear layer.  `layers` lists (name, x_key) pairs.
 
@@ -394,7 +395,11 @@ def quantize_block(weights: Dict[str, torch.Tensor], acts: Dict[str, torch.Tenso
     many streams (largest first, to the stream with the least work so far) so that the
     compute-bound k-means of one layer runs beside the memory-bound steps of another; `ws`
     is then a list with one workspace per stream.  The call returns with everything
-    enqueued and the current stream waiting for the others."""
+    enqueued and the current stream waiting for the others.
+
+    With ``join=False`` the current stream does not wait: the streams run on into the next
+    call (a model is quantized block after block, and the queues of one block need not drain
+    before those of the next fill), and the caller joins once at the end with `join_streams`."""
     some = next(iter(weights.values()))
     dev = some.device
     if streams <= 1:
@@ -430,9 +435,18 @@ def quantize_block(weights: Dict[str, torch.Tensor], acts: Dict[str, torch.Tenso
             sumsq, ev, owner = stats[x_key]
             if owner != j:
                 side[j].wait_event(ev)
+                sumsq.record_stream(side[j])      # its memory is not reused before this stream is done with it
             results[name] = quantize_layer(weights[name], sumsq, bit_set, avg_bits, rho_act_ppm,
                                            rho_q_ppm, iters, ws[j], with_error=with_error,
                                            status=status, timer=timer)
-    for st in side:
-        main.wait_stream(st)
+    if join:
+        for st in side:
+            main.wait_stream(st)
     return {name: results[name] for name, _ in layers}
+
+
+def join_streams(device, streams: int) -> None:
+    """Makes the current stream wait for the streams `quantize_block(..., join=False)` used."""
+    main = torch.cuda.current_stream(device)
+    for st in _streams_for(torch.device(device), streams):
+        main.wait_stream(st)

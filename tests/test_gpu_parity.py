@@ -557,6 +557,33 @@ def test_block_over_several_streams_matches_one_stream(env):
     assert status.item() == 0
 
 
+def test_blocks_run_on_without_a_join_between_them(env):
+    """Three blocks enqueued one after the other without joining the streams in between (earlier
+    results dropped while later blocks are still being enqueued, as a model quantized block after
+    block would do), one join at the end: the last block equals a joined run bit for bit."""
+    P, B, synth = env["P"], env["B"], env["synth"]
+    wl = synth.scaled(synth.workload("block70b"), tokens=512, shrink=8)
+    wts, xs = synth.materialize(wl, DEV)
+    layers = [(l.name, l.x_key) for l in wl.layers]
+    status = torch.zeros(1, dtype=torch.int32, device=DEV)
+    args = (wts, xs, layers, wl.bit_set, wl.avg_bits, wl.rho_act_ppm, wl.rho_q_ppm, wl.iters)
+    wss = [B.Workspace(DEV) for _ in range(3)]
+    want = P.quantize_block(*args, wss, with_error=True, status=status, streams=3)
+    torch.cuda.synchronize()
+    got = None
+    for _ in range(3):
+        got = P.quantize_block(*args, wss, with_error=True, status=status, streams=3, join=False)
+    P.join_streams(DEV, 3)
+    torch.cuda.synchronize()
+    for name in want:
+        a, b = want[name], got[name]
+        for f in ("sumsq", "act_idx", "bits", "centroids", "codes", "out_idx", "out_val", "err_ch", "err_total"):
+            assert torch.equal(getattr(a, f), getattr(b, f)), (name, f)
+        for x, y in zip(a.packed + a.chan_idx + a.lut, b.packed + b.chan_idx + b.lut):
+            assert (x is None) == (y is None) and (x is None or torch.equal(x, y)), name
+    assert status.item() == 0
+
+
 @pytest.mark.parametrize("seed", range(int(os.environ.get("CMPQ_RANDOM_CASES", "24"))))
 def test_randomized_layers_end_to_end(env, seed):
     """Random shapes (any d_out, including odd ones), dtypes, bit sets, budgets, outlier fractions,
