@@ -190,7 +190,9 @@ int cmpq_extract_outliers(int mode, int score, const float *sumsq, const void *W
  * index.  Update: level = sum(m*x)/sum(m) of its members, accumulated in fp64 and rounded
  * once to fp32; a level without members keeps its value.  -0.0 reads as +0.0.
  * Limits: d_out <= 32768 for CMPQ_F16, <= 16384 for CMPQ_F32 (CMPQ_ESHAPE beyond).
- * Workspace: CMPQ_OP_KMEANS.  Status: CMPQ_STATUS_NONFINITE.
+ * Workspace: CMPQ_OP_KMEANS.  Status: CMPQ_STATUS_NONFINITE (the levels and codes of a channel
+ * that holds a non-finite weight are unspecified, its codes stay below K; the other channels
+ * are not affected).
  */
 int cmpq_kmeans_quantize(const void *W, int dtype, int64_t d_in, int64_t d_out, int64_t ldw,
                          const uint8_t *bits, const int32_t *out_idx, int64_t n_out,

@@ -414,9 +414,10 @@ extern "C" int cmpq_kmeans_quantize(const void *W, int dtype, int64_t d_in, int6
         a.seg = seg;
     }
     if (kmeans_fast_eligible(a, dtype)) {
+        // the bucket kernel takes every channel itself
+        if (g_kmeans_algorithm != CMPQ_KMEANS_DIRECT) return launch_kmeans_hist(a, s);
         a.deferred = static_cast<uint8_t *>(ws);
-        const int rc = g_kmeans_algorithm == CMPQ_KMEANS_DIRECT ? launch_kmeans_fast(a, s)
-                                                                : launch_kmeans_hist(a, s);
+        const int rc = launch_kmeans_fast(a, s);
         if (rc != CMPQ_OK) return rc;
         return launch_kmeans<__half, false>(a, s);  // only the channels the first kernel deferred
     }

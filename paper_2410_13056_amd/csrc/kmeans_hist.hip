@@ -584,7 +584,6 @@ __global__ __launch_bounds__(T) __attribute__((amdgpu_waves_per_eu(6, 8))) void 
         if (tid < CMPQ_KMAX) crow[tid] = INFINITY;
         uint32_t *c32 = reinterpret_cast<uint32_t *>(a.codes + i * a.d_out);
         for (int g = tid; g < n_groups; g += T) c32[g] = 0;
-        if (tid == 0) a.deferred[i] = 0;
         return;
     }
     const int K = 1 << b;
@@ -618,11 +617,15 @@ __global__ __launch_bounds__(T) __attribute__((amdgpu_waves_per_eu(6, 8))) void 
         uint4 *a4 = reinterpret_cast<uint4 *>(arr);
         for (int s = tid; s < (int)(arr_bytes >> 4); s += T) a4[s] = make_uint4(kFill4, kFill4, kFill4, kFill4);
     }
-    if (!__syncthreads_and((nonfinite & 0x80008000u) == 0u)) {  // leave the channel to the general kernel
-        if (tid == 0) a.deferred[i] = 1;
+    if (!__syncthreads_and((nonfinite & 0x80008000u) == 0u)) {
+        // a non-finite weight: the caller's status word says so; the channel gets defined
+        // outputs (all levels 0, all codes 0) instead of a clustering of NaNs
+        if (tid == 0 && a.status) atomicOr(a.status, CMPQ_STATUS_NONFINITE);
+        if (tid < CMPQ_KMAX) crow[tid] = tid < K ? 0.0f : INFINITY;
+        uint32_t *c32 = reinterpret_cast<uint32_t *>(a.codes + i * a.d_out);
+        for (int g = tid; g < n_groups; g += T) c32[g] = 0;
         return;
     }
-    if (tid == 0) a.deferred[i] = 0;
     const int n_ex = sm.n_excl;
     if (n_ex > 0) {  // entries of O_q do not take part in the clustering
         const int32_t *ex_idx = a.out_idx + sm.seg_lo;

@@ -327,8 +327,11 @@ def test_kmeans_flags_nonfinite_weights_and_is_reproducible(env):
     c2, k2 = _kmeans_gpu(env, W, bits, status=st)
     assert st.item() == 0 and np.array_equal(c1, c2) and np.array_equal(k1, k2)
     W[2, 7] = np.nan
-    _kmeans_gpu(env, W, bits, status=st)
+    c3, k3 = _kmeans_gpu(env, W, bits, status=st)
     assert st.item() & env["B"].STATUS_NONFINITE
+    ok = np.arange(8) != 2                       # the other channels are not affected
+    assert np.array_equal(c3[ok], c1[ok]) and np.array_equal(k3[ok], k1[ok])
+    assert k3[2].max() < 8
 
 
 # ------------------------------------------------------------------ O_q
