@@ -30,7 +30,8 @@
 //
 // The kernel is bound by instruction issue, not by latency: the serial part of a round
 // runs on one wavefront while the others sleep at barriers, and several workgroups share
-// a compute unit.  A channel with NaN or infinity is flagged and left to the general kernel.
+// a compute unit.  A channel with NaN or infinity raises the status flag and gets levels 0
+// and codes 0.
 #include "kmeans_args.h"
 
 namespace {
@@ -348,6 +349,10 @@ __device__ __forceinline__ void lloyd_bucket(const KmArgs &a, int64_t i, BucketS
     constexpr int kLowBits = LB, kLows = 1 << LB, kBuckets = 1 << (16 - LB);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
 
+    // Start-up and rounds are a chain of short dependent steps (half the lifetime of a
+    // workgroup): they go first at instruction issue, ahead of the wide, latency-tolerant
+    // passes of the other workgroups on the compute unit.
+    __builtin_amdgcn_s_setprio(3);
     // ---- start-up: level j = order statistic floor((2j+1)M/(2K)) of the kept weights.
     //      L lanes per rank: locate the bucket by its prefix, then bisect on the place
     //      with counting scans of that bucket.
@@ -469,6 +474,7 @@ __device__ __forceinline__ void lloyd_bucket(const KmArgs &a, int64_t i, BucketS
         }
     }
 
+    __builtin_amdgcn_s_setprio(0);
     // ---- final coding: 4 codes per lane and store.  Every wavefront fetches the final
     //      boundaries and the position -> level map left by wavefront 0.
     const uint32_t tk_fin = sm.tk[par][lane & (CMPQ_KMAX - 1)];
