@@ -65,6 +65,7 @@ extern "C" {
 #define CMPQ_OP_DEQUANT_ERROR 6    /* n ignored                                  */
 #define CMPQ_OP_OUTLIERS_BY_COLUMN 7 /* n = entries of O_q                        */
 #define CMPQ_OP_LUT_MATVEC 8       /* n = tokens in the call                     */
+#define CMPQ_OP_PACK_WITH_ERROR 9  /* n ignored                                  */
 
 /* `mode` / `score` of cmpq_extract_outliers */
 #define CMPQ_OUTLIER_CHANNELS 0
@@ -284,6 +285,21 @@ int cmpq_dequant_error(const void *W, int dtype, int64_t d_in, int64_t d_out, in
                        const float *centroids, const uint8_t *codes, const uint8_t *bits,
                        const int32_t *out_idx, int64_t n_out, const float *sumsq, double *err_ch,
                        double *err_total, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * cmpq_pack (Sec. 5.1) and cmpq_dequant_error (App. B.3) in one pass over the codes, for a
+ * caller that wants both: every argument means what it means in those two calls, the packed
+ * rows, channel lists and tables are bit-identical to cmpq_pack's, err_ch and err_total equal
+ * cmpq_dequant_error's up to the order of the fp64 additions.  HBM traffic per weight: the
+ * weight and one code byte in, bits/8 bytes out (the two calls read the code byte twice).
+ * Errors: those of the two calls.  Workspace: CMPQ_OP_PACK_WITH_ERROR.
+ */
+int cmpq_pack_with_error(const void *W, int dtype, int64_t d_in, int64_t d_out, int64_t ldw,
+                         const uint8_t *codes, const uint8_t *bits, const float *centroids,
+                         const int32_t *bit_set, int n_set, const int64_t *counts_host,
+                         uint32_t *const *packed, int32_t *const *chan_idx, uint16_t *const *lut,
+                         const int32_t *out_idx, int64_t n_out, const float *sumsq, double *err_ch,
+                         double *err_total, void *ws, size_t ws_bytes, void *stream);
 
 /*
  * ---- Sec. 6 / Fig. 4: the product with the deployed weight --------------------------------

@@ -19,7 +19,7 @@ F16, F32 = 0, 1
 KMAX = 16
 PROTECTED = 16
 STATUS_NONFINITE = 1
-OP_OUTLIERS_BY_COLUMN, OP_LUT_MATVEC = 7, 8
+OP_OUTLIERS_BY_COLUMN, OP_LUT_MATVEC, OP_PACK_WITH_ERROR = 7, 8, 9
 OP_ACT_STATS, OP_ALLOCATE_BITS, OP_OUTLIER_CHANNELS, OP_OUTLIER_WEIGHTS, OP_KMEANS, OP_PACK, \
     OP_DEQUANT_ERROR = range(7)
 OUTLIER_CHANNELS, OUTLIER_WEIGHTS = 0, 1
@@ -32,7 +32,8 @@ EXPORTS = ("cmpq_workspace_bytes", "cmpq_strerror", "cmpq_count_ppm", "cmpq_act_
            "cmpq_transpose", "cmpq_allocate_bits", "cmpq_extract_outliers",
            "cmpq_kmeans_quantize", "cmpq_pack", "cmpq_dequant_error", "cmpq_set_kmeans_algorithm",
            "cmpq_gather_channels", "cmpq_outliers_by_column", "cmpq_lut_matvec", "cmpq_act_stats_norm",
-           "cmpq_rtn_quantize", "cmpq_select_by_width", "cmpq_lut_matvec_group", "cmpq_lut4_quantize")
+           "cmpq_rtn_quantize", "cmpq_select_by_width", "cmpq_lut_matvec_group", "cmpq_lut4_quantize",
+           "cmpq_pack_with_error")
 
 _i64, _i32, _int, _vp, _dbl, _sz = (ctypes.c_int64, ctypes.c_int32, ctypes.c_int, ctypes.c_void_p,
                                     ctypes.c_double, ctypes.c_size_t)
@@ -80,6 +81,8 @@ def lib() -> ctypes.CDLL:
         L.cmpq_pack.argtypes = [_vp, _i64, _i64, _vp, _vp, _vp, _int, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
         L.cmpq_dequant_error.argtypes = [_vp, _int, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _i64, _vp,
                                          _vp, _vp, _vp, _sz, _vp]
+        L.cmpq_pack_with_error.argtypes = [_vp, _int, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _int, _vp, _vp, _vp, _vp,
+                                           _vp, _i64, _vp, _vp, _vp, _vp, _sz, _vp]
         L.cmpq_set_kmeans_algorithm.argtypes = [_int]
         L.cmpq_act_stats_norm.argtypes = [_vp, _int, _i64, _i64, _i64, _int, _vp, _vp, _int, _vp, _sz, _vp, _vp]
         L.cmpq_gather_channels.argtypes = [_vp, _int, _i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp]
@@ -246,6 +249,29 @@ def dequant_error(W: torch.Tensor, centroids: torch.Tensor, codes: torch.Tensor,
                                     _ptr(bits), _ptr(out_idx), int(n_out), _ptr(sumsq), _ptr(err_ch),
                                     _ptr(err_total), _ptr(buf), buf.numel(), _stream()),
            "cmpq_dequant_error")
+
+
+def pack_with_error(W: torch.Tensor, codes: torch.Tensor, bits: torch.Tensor, centroids: torch.Tensor,
+                    bit_set: Sequence[int], counts: Sequence[int], packed: Sequence[Optional[torch.Tensor]],
+                    chan_idx: Sequence[Optional[torch.Tensor]], lut: Sequence[Optional[torch.Tensor]],
+                    out_idx: Optional[torch.Tensor], n_out: int, sumsq: Optional[torch.Tensor],
+                    err_ch: torch.Tensor, err_total: torch.Tensor, ws: Workspace) -> None:
+    """`pack` and `dequant_error` in one pass over the codes."""
+    d_in, d_out, ldw = _rows(W)
+    if tuple(codes.shape) != (d_in, d_out):
+        raise ValueError("codes must have the shape of W")
+    n = len(bit_set)
+    bs = (_i32 * n)(*bit_set)
+    cn = (_i64 * n)(*counts)
+    pk = (_vp * n)(*[_ptr(t) for t in packed])
+    ci = (_vp * n)(*[_ptr(t) for t in chan_idx])
+    lt = (_vp * n)(*[_ptr(t) for t in lut])
+    buf = ws.get(workspace_bytes(OP_PACK_WITH_ERROR, d_in, d_out))
+    _check(lib().cmpq_pack_with_error(_ptr(W), _dtype(W), d_in, d_out, ldw, _ptr(codes), _ptr(bits),
+                                      _ptr(centroids), bs, n, cn, pk, ci, lt, _ptr(out_idx), int(n_out),
+                                      _ptr(sumsq), _ptr(err_ch), _ptr(err_total), _ptr(buf), buf.numel(),
+                                      _stream()),
+           "cmpq_pack_with_error")
 
 
 def gather_channels(W: torch.Tensor, act_idx: torch.Tensor, W_act: torch.Tensor) -> None:

@@ -24,6 +24,14 @@ __device__ __forceinline__ size_t align_up_dev(size_t x) { return (x + 15) & ~(s
 int launch_segment_offsets(const int32_t *idx, int64_t n, int64_t d_in, int64_t d_out, int32_t *seg,
                            hipStream_t s);
 
+// err_ch[i] = sum_o (W - W_hat)^2 of cmpq_dequant_error, one workgroup per channel; `slices`
+// (nullable) cuts out_idx by channel.
+int launch_dequant_error_rows(const void *W, int dtype, int64_t d_in, int64_t d_out, int64_t ldw,
+                              const float *centroids, const uint8_t *codes, const uint8_t *bits,
+                              const int32_t *out_idx, const int32_t *slices, double *err_ch, hipStream_t s);
+// totals[0] = sum_i sumsq[i] * err_ch[i] (sumsq null: weight 1), totals[1] = sum_i err_ch[i].
+int launch_error_totals(const double *err_ch, const float *sumsq, int64_t d_in, double *totals, hipStream_t s);
+
 // Carves aligned pieces out of the caller's workspace; `need` ends up as the total.
 struct WsCarver {
     char *base;

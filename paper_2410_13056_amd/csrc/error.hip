@@ -162,6 +162,30 @@ __global__ __launch_bounds__(1024) void error_totals_kernel(const double *__rest
 
 }  // namespace
 
+int launch_dequant_error_rows(const void *W, int dtype, int64_t d_in, int64_t d_out, int64_t ldw,
+                              const float *centroids, const uint8_t *codes, const uint8_t *bits,
+                              const int32_t *out_idx, const int32_t *slices, double *err_ch, hipStream_t s) {
+    if (d_in <= 0) return CMPQ_OK;
+    const size_t lds = (size_t)cdiv(d_out > 0 ? d_out : 1, 32) * 4;
+    const int esz = dtype == CMPQ_F16 ? 2 : 4;
+    const int vec_ok = reinterpret_cast<uintptr_t>(W) % 16 == 0 && (ldw * esz) % 16 == 0 &&
+                       reinterpret_cast<uintptr_t>(codes) % 8 == 0 && d_out % 8 == 0;
+    if (dtype == CMPQ_F16)
+        dequant_error_kernel<__half><<<(unsigned)d_in, kT, lds, s>>>(
+            static_cast<const __half *>(W), d_out, ldw, centroids, codes, bits, out_idx, slices, err_ch, vec_ok);
+    else
+        dequant_error_kernel<float><<<(unsigned)d_in, kT, lds, s>>>(
+            static_cast<const float *>(W), d_out, ldw, centroids, codes, bits, out_idx, slices, err_ch, vec_ok);
+    CMPQ_LAUNCH_CHECK();
+    return CMPQ_OK;
+}
+
+int launch_error_totals(const double *err_ch, const float *sumsq, int64_t d_in, double *totals, hipStream_t s) {
+    error_totals_kernel<<<1, 1024, 0, s>>>(err_ch, sumsq, d_in, totals);
+    CMPQ_LAUNCH_CHECK();
+    return CMPQ_OK;
+}
+
 size_t cmpq_ws_dequant_error(int64_t d_in) {
     return align_up((size_t)(d_in + 1) * sizeof(int32_t), 256);  // slice offsets of out_idx
 }
@@ -187,20 +211,8 @@ extern "C" int cmpq_dequant_error(const void *W, int dtype, int64_t d_in, int64_
         if (rc != CMPQ_OK) return rc;
         slices = static_cast<const int32_t *>(ws);
     }
-    if (d_in > 0) {
-        const size_t lds = (size_t)cdiv(d_out > 0 ? d_out : 1, 32) * 4;
-        const int esz = dtype == CMPQ_F16 ? 2 : 4;
-        const int vec_ok = reinterpret_cast<uintptr_t>(W) % 16 == 0 && (ldw * esz) % 16 == 0 &&
-                           reinterpret_cast<uintptr_t>(codes) % 8 == 0 && d_out % 8 == 0;
-        if (dtype == CMPQ_F16)
-            dequant_error_kernel<__half><<<(unsigned)d_in, kT, lds, s>>>(
-                static_cast<const __half *>(W), d_out, ldw, centroids, codes, bits, out_idx, slices, err_ch, vec_ok);
-        else
-            dequant_error_kernel<float><<<(unsigned)d_in, kT, lds, s>>>(
-                static_cast<const float *>(W), d_out, ldw, centroids, codes, bits, out_idx, slices, err_ch, vec_ok);
-        CMPQ_LAUNCH_CHECK();
-    }
-    error_totals_kernel<<<1, 1024, 0, s>>>(err_ch, sumsq, d_in, err_total);
-    CMPQ_LAUNCH_CHECK();
-    return CMPQ_OK;
+    if (const int rc = launch_dequant_error_rows(W, dtype, d_in, d_out, ldw, centroids, codes, bits, out_idx,
+                                                 slices, err_ch, s))
+        return rc;
+    return launch_error_totals(err_ch, sumsq, d_in, err_total, s);
 }

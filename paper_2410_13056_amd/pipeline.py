@@ -126,17 +126,19 @@ def _after_first_pass(Wt, sumsq, bit_set, counts, act_idx, chan_mask, bits, cent
         packed.append(torch.empty((c, (d_out * b + 31) // 32), dtype=torch.int32, device=dev))
         chan_idx.append(torch.empty(c, dtype=torch.int32, device=dev))
         lut.append(torch.empty((c, 1 << b), dtype=torch.float16, device=dev))
-    with _stage(timer, "pack"):
-        B.pack(codes, bits, cent, bit_set, counts, packed, chan_idx, lut, ws)
     res = LayerResult(d_in, d_out, tuple(bit_set), counts, sumsq, act_idx, chan_mask, bits, cent, codes,
                       out_idx, out_val, packed, chan_idx, lut, W_t=Wt)
     if keep_prelim:
         res.centroids_prelim, res.codes_prelim = cent1, codes1
-    if with_error:
+    if with_error:      # stored format and error in one pass over the codes
         res.err_ch = torch.empty(d_in, dtype=torch.float64, device=dev)
         res.err_total = torch.empty(2, dtype=torch.float64, device=dev)
-        with _stage(timer, "dequant_error"):
-            B.dequant_error(Wt, cent, codes, bits, out_idx, k_q, sumsq, res.err_ch, res.err_total, ws)
+        with _stage(timer, "pack_with_error"):
+            B.pack_with_error(Wt, codes, bits, cent, bit_set, counts, packed, chan_idx, lut, out_idx, k_q, sumsq,
+                              res.err_ch, res.err_total, ws)
+    else:
+        with _stage(timer, "pack"):
+            B.pack(codes, bits, cent, bit_set, counts, packed, chan_idx, lut, ws)
     return res
 
 

@@ -100,6 +100,15 @@ def test_host_side_argument_errors(L):
     assert L.cmpq_pack(fake, 4, 64, fake, fake, bs, 3, cnt2, ptrs, ptrs, ptrs, None, 0, None) == -5
     assert L.cmpq_dequant_error(fake, 0, 4, 64, 64, fake, fake, fake, None, 0, None, None, fake, fake, 256, None) == -1
     assert L.cmpq_dequant_error(fake, 0, 4, 64, 8, fake, fake, fake, None, 0, None, fake, fake, fake, 256, None) == -2
+    # both in one pass: the errors of either call
+    pe = L.cmpq_pack_with_error
+    assert pe(fake, 0, 4, 64, 64, fake, fake, fake, bs, 3, cnt2, ptrs, ptrs, ptrs, None, 0, None, None, fake, fake, 4096, None) == -1
+    assert pe(fake, 2, 4, 64, 64, fake, fake, fake, bs, 3, cnt2, ptrs, ptrs, ptrs, None, 0, None, fake, fake, fake, 4096, None) == -1
+    assert pe(fake, 0, 4, 64, 8, fake, fake, fake, bs, 3, cnt2, ptrs, ptrs, ptrs, None, 0, None, fake, fake, fake, 4096, None) == -2
+    assert pe(fake, 0, 4, 64, 64, fake, fake, fake, (i32 * 2)(3, 2), 2, cnt, ptrs, ptrs, ptrs, None, 0, None, fake, fake, fake, 4096, None) == -3
+    assert pe(fake, 0, 4, 64, 64, fake, fake, fake, bs, 3, cnt2, ptrs, ptrs, ptrs, None, 3, None, fake, fake, fake, 4096, None) == -1
+    assert pe(fake, 0, 4, 64, 64, fake, fake, fake, bs, 3, cnt2, ptrs, ptrs, ptrs, None, 0, None, fake, fake, None, 0, None) == -5
+    assert pe(fake, 0, 4, 64, 64, fake, fake, fake, bs, 3, cnt2, ptrs, ptrs, ptrs, None, 0, None, fake, fake, fake, 256, None) == -5
     # the deployed product
     assert L.cmpq_gather_channels(fake, 0, 8, 64, 64, None, 2, fake, 64, None) == -1
     assert L.cmpq_gather_channels(fake, 0, 8, 64, 64, fake, 9, fake, 64, None) == -1            # more rows than channels

@@ -474,6 +474,56 @@ def test_dequant_error_parity(env, dtype):
         assert (err == 0).all() and (tot == 0).all()
 
 
+@pytest.mark.parametrize("dtype", [np.float16, np.float32])
+@pytest.mark.parametrize("d_in,d_out", [(1, 1), (7, 31), (45, 1234), (19, 4096 + 48), (6, 8192 + 32 * 256 + 8)])
+def test_pack_with_error_parity(env, dtype, d_in, d_out):
+    """Stored format and error in one pass: against the oracle (packed rows, channel lists and
+    tables bit for bit, errors to 1e-12), and bit for bit against the two separate calls."""
+    B, ws, orc = env["B"], env["ws"], env["orc"]
+    rng = np.random.default_rng(d_in * 131 + d_out)
+    W = rng.normal(0, 0.05, (d_in, d_out)).astype(dtype)
+    bit_set = (2, 3, 4)
+    bits = rng.choice(np.array(bit_set + (16,), np.uint8), d_in, p=[0.3, 0.3, 0.3, 0.1])
+    cent, codes = orc.kmeans(W, bits, iters=3)
+    sumsq = rng.lognormal(3, 1, d_in).astype(np.float32)
+    n_q = min(d_in * d_out, 1 + d_in * d_out // 50)
+    out_idx = np.sort(rng.choice(d_in * d_out, n_q, replace=False)).astype(np.int64)
+    counts = [int((bits == b).sum()) for b in bit_set]
+
+    def outputs():
+        packed = [torch.full((c, (d_out * b + 31) // 32), -1, dtype=torch.int32, device=DEV) if c else None
+                  for b, c in zip(bit_set, counts)]
+        chan = [torch.full((c,), -1, dtype=torch.int32, device=DEV) if c else None for c in counts]
+        lut = [torch.full((c, 1 << b), -1, dtype=torch.float16, device=DEV) if c else None
+               for b, c in zip(bit_set, counts)]
+        return packed, chan, lut, torch.empty(d_in, dtype=torch.float64, device=DEV), \
+            torch.empty(2, dtype=torch.float64, device=DEV)
+
+    dW, dk, db, dc = _dev(W), _dev(codes), _dev(bits), _dev(cent)
+    for oi in (None, out_idx):
+        for ss in (None, sumsq):
+            d_oi = None if oi is None else _dev(oi.astype(np.int32))
+            n_oi = 0 if oi is None else len(oi)
+            d_ss = None if ss is None else _dev(ss)
+            packed, chan, lut, err, tot = outputs()
+            B.pack_with_error(dW, dk, db, dc, bit_set, counts, packed, chan, lut, d_oi, n_oi, d_ss, err, tot, ws)
+            p2, c2, l2, e2, t2 = outputs()
+            B.pack(dk, db, dc, bit_set, counts, p2, c2, l2, ws)
+            B.dequant_error(dW, dc, dk, db, d_oi, n_oi, d_ss, e2, t2, ws)
+            oerr, otot = orc.dequant_error(W, cent, codes, bits, oi, ss)
+            assert _rel(_np(err), oerr) < 1e-12 and _rel(_np(tot), otot) < 1e-12
+            assert _rel(_np(err), _np(e2)) < 1e-12 and _rel(_np(tot), _np(t2)) < 1e-12
+            for j, b in enumerate(bit_set):
+                if counts[j] == 0:
+                    continue
+                opk, och, olut = orc.pack(codes, bits, cent, b)
+                assert np.array_equal(_np(packed[j]).view(np.uint32), opk)
+                assert np.array_equal(_np(chan[j]), och)
+                assert np.array_equal(_np(lut[j]).view(np.uint16), olut)
+                assert torch.equal(packed[j], p2[j]) and torch.equal(chan[j], c2[j])
+                assert torch.equal(lut[j].view(torch.int16), l2[j].view(torch.int16))
+
+
 # ------------------------------------------------------------------ the whole path, free running
 
 def _compare_layer(env, r, o, bit_set, exact_levels):
