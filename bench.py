@@ -209,6 +209,8 @@ def main():
     ap.add_argument("--workload", default="block70b",
                     help="block70b (default, the headline target), block13b, block7b, q7b, tiny")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--joined-steps", type=int, default=None,
+                    help="steps of the extra run that joins the streams after every step (default: --steps; 0: none)")
     ap.add_argument("--streams", type=int, default=3,
                     help="streams the independent layers of a block are shared out over (default 3)")
     ap.add_argument("--serial-steps", type=int, default=2,
@@ -262,27 +264,31 @@ def main():
         out = step()
         del out
     torch.cuda.synchronize()
+    # The timed region: K steps enqueued one after the other, as when a model is quantized block
+    # after block; with several streams the queues of one step run on into the next and the
+    # streams are joined once, before the closing synchronisation.
     timer = P.StageTimer()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        out = step(timer)
+        out = step(timer, join=False)
+    if args.streams > 1:
+        P.join_streams(dev, args.streams)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
-    back_to_back = None
-    if args.streams > 1:
-        # the same steps without joining the streams in between: the queues of one block run on
-        # into the next, as when a model is quantized block after block
-        torch.cuda.synchronize()
+    joined = None
+    n_joined = args.steps if args.joined_steps is None else args.joined_steps
+    if args.streams > 1 and n_joined > 0:
+        # the same steps with every stream joined after every step: no step starts before the
+        # one before it has drained
         t1 = time.perf_counter()
-        for _ in range(args.steps):
-            o2 = step(join=False)
-        P.join_streams(dev, args.streams)
+        for _ in range(n_joined):
+            o2 = step(join=True)
         torch.cuda.synchronize()
         dt2 = time.perf_counter() - t1
         del o2
-        back_to_back = {"note": "the same steps with the streams joined once at the end instead of after every step",
-                        "ms_per_step": dt2 / args.steps * 1e3,
-                        "Mparams_per_s": wl.params * args.steps / dt2 / 1e6}
+        joined = {"note": "the same steps with the streams joined after every step instead of once at the end",
+                  "steps": n_joined, "ms_per_step": dt2 / n_joined * 1e3,
+                  "Mparams_per_s": wl.params * n_joined / dt2 / 1e6}
     assert status.item() == 0, "non-finite input flagged"
 
     stages = timer.totals()
@@ -327,8 +333,8 @@ def main():
                           "frac": x_bytes * n_st_steps / (ms_st / 1e3) / 1e9 / HBM_PEAK_GBS,
                           "from": "serial steps" if serial is not None else "timed steps"},
     }
-    if back_to_back is not None:
-        line["steps_back_to_back"] = back_to_back
+    if joined is not None:
+        line["steps_joined_one_by_one"] = joined
     if serial is not None:
         n1, ms1 = serial["kmeans"]
         line["serial"] = {

@@ -153,10 +153,12 @@ def test_block70b_layers_full_size(env, layer):
     assert abs(tot[0] - ref_w) <= 1e-9 * ref_w
 
 
-def test_block70b_three_streams_equals_one_stream_full_size(env):
+@pytest.mark.parametrize("join", [False, True])
+def test_block70b_three_streams_equals_one_stream_full_size(env, join):
     """The whole 70B-shaped block exactly as bench.py runs it by default (layers shared out over
-    three streams): every output bit-identical to the one-stream run of the same call chain,
-    whose layers the tests above check against the oracle."""
+    three streams; steps enqueued one after the other with one join at the end, or joined one by
+    one): every output of the last step bit-identical to the one-stream run of the same call
+    chain, whose layers the tests above check against the oracle."""
     P, B, synth = env["P"], env["B"], env["synth"]
     wl = synth.workload("block70b")
     wts, xs = synth.materialize(wl, DEV)
@@ -164,7 +166,12 @@ def test_block70b_three_streams_equals_one_stream_full_size(env):
     status = torch.zeros(1, dtype=torch.int32, device=DEV)
     args = (wts, xs, layers, wl.bit_set, wl.avg_bits, wl.rho_act_ppm, wl.rho_q_ppm, wl.iters)
     one = P.quantize_block(*args, env["ws"], with_error=True, status=status)
-    many = P.quantize_block(*args, [B.Workspace(DEV) for _ in range(3)], with_error=True, status=status, streams=3)
+    wss = [B.Workspace(DEV) for _ in range(3)]
+    many = None
+    for _ in range(2):
+        many = P.quantize_block(*args, wss, with_error=True, status=status, streams=3, join=join)
+    if not join:
+        P.join_streams(DEV, 3)
     torch.cuda.synchronize()
     assert status.item() == 0
     for name in one:
