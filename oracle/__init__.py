@@ -136,8 +136,10 @@ def allocate_bits(sumsq: np.ndarray, chan_mask: Optional[np.ndarray], bit_set: S
 
 
 def kmeans(W: np.ndarray, bits: np.ndarray, out_idx: Optional[np.ndarray] = None,
-           elem_weight: Optional[np.ndarray] = None, iters: int = 20, trace: bool = False):
-    """Returns ``(centroids float32[d_in,16], codes uint8[d_in,d_out][, sse float64[d_in,iters+1]])``."""
+           elem_weight: Optional[np.ndarray] = None, iters: int = 20, trace: bool = False,
+           start: Optional[np.ndarray] = None):
+    """Returns ``(centroids float32[d_in,16], codes uint8[d_in,d_out][, sse float64[d_in,iters+1]])``.
+    `start` [d_in,16] float32 replaces the quantile start of every channel by the given levels."""
     W = _c(W)
     d_in, d_out = W.shape
     bits = _c(bits, np.uint8)
@@ -146,10 +148,13 @@ def kmeans(W: np.ndarray, bits: np.ndarray, out_idx: Optional[np.ndarray] = None
     cent = np.zeros((d_in, KMAX), np.float32)
     codes = np.zeros((d_in, d_out), np.uint8)
     sse = np.zeros((d_in, iters + 1), np.float64) if trace else None
+    st = None if start is None else _c(start, np.float32)
+    if st is not None and st.shape != (d_in, KMAX):
+        raise ValueError("start must be [d_in, 16]")
     rc = lib().orc_kmeans(_p(W), _dtype_code(W), ctypes.c_int64(d_in), ctypes.c_int64(d_out),
                           ctypes.c_int64(d_out), _p(bits), _p(oi),
                           ctypes.c_int64(0 if oi is None else oi.shape[0]), _p(ew),
-                          int(iters), _p(cent), _p(codes), _p(sse))
+                          int(iters), _p(st), _p(cent), _p(codes), _p(sse))
     assert rc == 0, rc
     return (cent, codes, sse) if trace else (cent, codes)
 
@@ -260,10 +265,13 @@ def lut4(centroids: np.ndarray, bits: np.ndarray):
 
 def quantize_layer(W: np.ndarray, X: np.ndarray, bit_set: Sequence[int], avg_bits: float,
                    rho_act_ppm: int = 4500, rho_q_ppm: int = 500, iters: int = 20,
-                   sumsq: Optional[np.ndarray] = None, score: int = SCORE_RESIDUAL) -> dict:
+                   sumsq: Optional[np.ndarray] = None, score: int = SCORE_RESIDUAL,
+                   iters_final_from_prelim: Optional[int] = None) -> dict:
     """The whole path of Sec. 3.2, step by step, on one layer.
 
     ``W`` is ``[d_in, d_out]`` (paper orientation), ``X`` is ``[n, d_in]``.
+    ``iters_final_from_prelim`` (variant): the final K-means starts from the levels of the
+    preliminary one and runs that many rounds, instead of `iters` rounds from the quantile start.
     """
     d_in, d_out = W.shape
     if sumsq is None:
@@ -274,7 +282,10 @@ def quantize_layer(W: np.ndarray, X: np.ndarray, bit_set: Sequence[int], avg_bit
     cent1, codes1 = kmeans(W, bits, iters=iters)                          # W'_q
     k_q = count_ppm(rho_q_ppm, d_in * d_out)
     out_idx, out_val = weight_outliers(W, cent1, codes1, bits, k_q, score)  # O_q
-    cent, codes = kmeans(W, bits, out_idx=out_idx, iters=iters)           # W_q
+    if iters_final_from_prelim is None:
+        cent, codes = kmeans(W, bits, out_idx=out_idx, iters=iters)       # W_q
+    else:
+        cent, codes = kmeans(W, bits, out_idx=out_idx, iters=iters_final_from_prelim, start=cent1)
     packs = {b: pack(codes, bits, cent, b) for b in bit_set}
     err_ch, totals = dequant_error(W, cent, codes, bits, out_idx, sumsq)
     return dict(sumsq=sumsq, act_idx=act_idx, chan_mask=chan_mask, bits=bits, counts=counts,

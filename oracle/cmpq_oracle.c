@@ -315,8 +315,8 @@ static int nearest_level(double x, const float *c, int K) {
  */
 int orc_kmeans(const void *W, int dtype, int64_t d_in, int64_t d_out, int64_t ldw,
                const uint8_t *bits, const int64_t *out_idx, int64_t n_out,
-               const float *elem_weight, int iters, float *centroids, uint8_t *codes,
-               double *sse_trace) {
+               const float *elem_weight, int iters, const float *start, float *centroids,
+               uint8_t *codes, double *sse_trace) {
     if (!W || !bits || !centroids || !codes || iters < 0 || ldw < d_out) return -1;
     /* excluded entries as a dense 0/1 map */
     uint8_t *excl = (uint8_t *)calloc((size_t)(d_in * d_out > 0 ? d_in * d_out : 1), 1);
@@ -354,6 +354,14 @@ int orc_kmeans(const void *W, int dtype, int64_t d_in, int64_t d_out, int64_t ld
         qsort(srt, (size_t)M, sizeof(double), cmp_f64);
         for (int j = 0; j < K; ++j)
             c[j] = M ? (float)srt[((int64_t)(2 * j + 1) * M) / (2 * K)] : 0.0f;
+        /* Variant (not in the paper, which names no start for either pass of Sec. 3.2.2): the
+         * caller's levels instead of the quantile start, e.g. those of the preliminary
+         * quantization for the final one.  Level j keeps index j; -0 reads as +0. */
+        if (start)
+            for (int j = 0; j < K; ++j) {
+                float v = start[i * ORC_KMAX + j];
+                c[j] = v == 0.0f ? 0.0f : v;
+            }
 
         for (int r = 0; r <= iters; ++r) {
             double sum[ORC_KMAX], mass[ORC_KMAX], sse = 0.0;

@@ -800,3 +800,70 @@ def test_lut4_costs_little_error_on_a_quantized_layer(orc):
     cent2, codes2 = orc.kmeans(W, bits2, iters=10)
     e_2bit = orc.dequant_error(W, cent2, codes2, bits2)[1][1]
     assert e16 <= e4 < e_2bit
+
+
+# ------------------------------------------------------------------ K-means from given levels (variant)
+
+def test_kmeans_from_given_levels_continues_the_same_iteration(orc):
+    """r rounds from the quantile start, then s more from where they ended, are r + s rounds:
+    the given-start path is the cold path (pinned above) entered later.  0 rounds return the
+    start itself, so the quantile levels are available to start from."""
+    rng = np.random.default_rng(77)
+    W = rng.normal(0, 0.05, (9, 300)).astype(np.float16)
+    W[3, :40] = W[3, 0]                                   # ties and a short run of equal values
+    bits = np.array([1, 2, 3, 4, 2, 3, 4, 16, 4], np.uint8)
+    excl = np.sort(rng.choice(9 * 300, 60, replace=False)).astype(np.int64)
+    for oi in (None, excl):
+        c0, k0 = orc.kmeans(W, bits, out_idx=oi, iters=0)
+        c7, k7 = orc.kmeans(W, bits, out_idx=oi, iters=7)
+        g0, h0 = orc.kmeans(W, bits, out_idx=oi, iters=0, start=c0)
+        assert np.array_equal(g0, c0) and np.array_equal(h0, k0)
+        g7, h7 = orc.kmeans(W, bits, out_idx=oi, iters=7, start=c0)
+        assert np.array_equal(g7, c7) and np.array_equal(h7, k7)
+        c3, _ = orc.kmeans(W, bits, out_idx=oi, iters=3)
+        g4, h4 = orc.kmeans(W, bits, out_idx=oi, iters=4, start=c3)
+        assert np.array_equal(g4, c7) and np.array_equal(h4, k7)
+
+
+def test_kmeans_from_given_levels_keeps_level_indices_and_fixed_points(orc):
+    """Level j stays level j: a permuted start gives the permuted result.  A start that is a
+    fixed point (levels = means of their own cells) comes back unchanged after any number of
+    rounds.  The objective never rises from one round to the next."""
+    rng = np.random.default_rng(78)
+    x = np.concatenate([rng.normal(m, 0.01, 50) for m in (-0.3, -0.1, 0.2, 0.5)]).astype(np.float32)
+    W = x[None, :]
+    bits = np.array([2], np.uint8)
+    c, k = orc.kmeans(W, bits, iters=30)                  # well separated: converged long before
+    again, k2 = orc.kmeans(W, bits, iters=5, start=c)
+    assert np.array_equal(again, c) and np.array_equal(k2, k)
+    perm = np.array([2, 0, 3, 1])
+    start = c.copy()
+    start[0, :4] = c[0, perm]
+    cp, kp = orc.kmeans(W, bits, iters=5, start=start)
+    assert np.array_equal(cp[0, :4], c[0, perm])
+    assert np.array_equal(perm[kp[0]], k[0])              # code j of the permuted run is level perm[j]
+    rough = np.full((1, 16), np.inf, np.float32)
+    rough[0, :4] = [-1.0, 0.0, 0.01, 1.0]
+    _, _, sse = orc.kmeans(W, bits, iters=12, start=rough, trace=True)
+    assert (np.diff(sse[0]) <= 1e-12 * sse[0, 0]).all() and sse[0, -1] < sse[0, 0]
+    # a level that gets no member keeps the value it was given; -0 is taken as +0
+    lone = np.full((1, 16), np.inf, np.float32)
+    lone[0, :4] = [-0.0, 100.0, -0.3, 0.3]
+    cl, kl = orc.kmeans(W, bits, iters=3, start=lone)
+    assert cl[0, 1] == 100.0 and not (kl == 1).any()
+    z, _ = orc.kmeans(W, bits, iters=0, start=lone)
+    assert z[0, 0] == 0.0 and not np.signbit(z[0, 0])
+
+
+def test_whole_path_with_final_levels_started_from_the_preliminary_ones(orc):
+    """The variant of the whole path: same O_act, widths, preliminary quantization and O_q as the
+    default; the final levels are those of K-means started at the preliminary levels."""
+    rng = np.random.default_rng(79)
+    W = rng.normal(0, 0.02, (40, 256)).astype(np.float16)
+    X = rng.normal(0, 1, (64, 40)).astype(np.float16)
+    a = orc.quantize_layer(W, X, (2, 3, 4), 3.0, 45000, 10000, iters=6)
+    b = orc.quantize_layer(W, X, (2, 3, 4), 3.0, 45000, 10000, iters=6, iters_final_from_prelim=4)
+    for f in ("act_idx", "bits", "cent1", "codes1", "out_idx", "out_val"):
+        assert np.array_equal(a[f], b[f]), f
+    want, wk = orc.kmeans(W, a["bits"], out_idx=a["out_idx"], iters=4, start=a["cent1"])
+    assert np.array_equal(b["centroids"], want) and np.array_equal(b["codes"], wk)
