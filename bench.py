@@ -201,6 +201,31 @@ def lut4_variant(P, B, torch, out, layers, wl, reps):
             "weighted_error_vs_fp16_tables": e4 / e16 if e16 > 0 else None}
 
 
+def continued_final_pass(P, torch, step_variant, out, layers, wl, rounds, reps, n_streams, dev):
+    """The block with the final K-means of every layer continued from the preliminary levels for
+    `rounds` rounds instead of started again from the quantiles (a variant; the paper names no
+    start): time per block in the launch configuration of the headline figure, and the weighted
+    reconstruction error against that of the default."""
+    res = {}
+    e_default = sum(float(out[n].err_total[0]) for n, _ in layers)
+    for r in rounds:
+        o = step_variant(r)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            o = step_variant(r)
+        if n_streams > 1:
+            P.join_streams(dev, n_streams)
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / reps
+        e = sum(float(o[n].err_total[0]) for n, _ in layers)
+        res[str(r)] = {"ms_per_block": dt * 1e3, "Mparams_per_s": wl.params / dt / 1e6,
+                       "weighted_error_vs_default": e / e_default if e_default > 0 else None}
+        del o
+    return {"what": "final K-means continued from the preliminary levels for r rounds (not the default: both "
+                    "passes start from the quantiles); keyed by r", "rounds": res}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -211,6 +236,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--joined-steps", type=int, default=None,
                     help="steps of the extra run that joins the streams after every step (default: --steps; 0: none)")
+    ap.add_argument("--continued-reps", type=int, default=3,
+                    help="repetitions of the variant whose final K-means continues from the preliminary "
+                         "levels; 0: skip")
     ap.add_argument("--streams", type=int, default=3,
                     help="streams the independent layers of a block are shared out over (default 3)")
     ap.add_argument("--serial-steps", type=int, default=2,
@@ -351,6 +379,13 @@ def main():
         line["retarget"] = retarget(P, B, torch, out, layers, wl, args.retarget_reps)
     if args.lut4_reps > 0:
         line["lut4_variant"] = lut4_variant(P, B, torch, out, layers, wl, args.lut4_reps)
+    if args.continued_reps > 0:
+        def step_variant(r):
+            return P.quantize_block(weights, acts, layers, wl.bit_set, wl.avg_bits, wl.rho_act_ppm,
+                                    wl.rho_q_ppm, wl.iters, ws, with_error=True, status=status,
+                                    streams=args.streams, join=False, iters_final_from_prelim=r)
+        line["final_pass_continued_from_prelim"] = continued_final_pass(
+            P, torch, step_variant, out, layers, wl, (5, wl.iters), args.continued_reps, args.streams, dev)
     if args.rtn_reps > 0:
         line["rtn_variant"] = rtn_variant(P, B, torch, out, layers, wl, args.rtn_reps)
     if not args.no_cpu_baseline:

@@ -80,6 +80,7 @@ extern "C" {
 
 /* `init` of cmpq_kmeans_quantize */
 #define CMPQ_INIT_QUANTILE 0
+#define CMPQ_INIT_GIVEN 1
 
 /* argument of cmpq_set_kmeans_algorithm */
 #define CMPQ_KMEANS_HISTOGRAM 0 /* rounds read cumulative tables of the channel (default)   */
@@ -184,16 +185,20 @@ int cmpq_extract_outliers(int mode, int score, const float *sumsq, const void *W
  *   iters       rounds of (assign, update), run in full; then one more assignment.
  *   init        CMPQ_INIT_QUANTILE: level j starts at the order statistic
  *               floor((2j+1)*M/(2K)) of the M entries with positive weight; 0 when M = 0.
- *   centroids   [d_in, 16] fp32 out: K levels, then +infinity; all +infinity for a channel
- *               with bits outside 1..4.
+ *               CMPQ_INIT_GIVEN (a variant; the paper names no start): level j starts at
+ *               centroids[i][j] as found on entry, j < K, in any order and with repeats
+ *               allowed; -0.0 reads as +0.0; the levels must be finite.  Sec. 3.2.2's final
+ *               quantization can so continue from the preliminary one's levels.
+ *   centroids   [d_in, 16] fp32 out (in/out with CMPQ_INIT_GIVEN): K levels, then +infinity;
+ *               all +infinity for a channel with bits outside 1..4.
  *   codes       [d_in, d_out] uint8 out (0 for such a channel).
  * Assignment: the nearest level in exact arithmetic, equal distances to the smaller level
  * index.  Update: level = sum(m*x)/sum(m) of its members, accumulated in fp64 and rounded
  * once to fp32; a level without members keeps its value.  -0.0 reads as +0.0.
  * Limits: d_out <= 32768 for CMPQ_F16, <= 16384 for CMPQ_F32 (CMPQ_ESHAPE beyond).
  * Workspace: CMPQ_OP_KMEANS.  Status: CMPQ_STATUS_NONFINITE (the levels and codes of a channel
- * that holds a non-finite weight are unspecified, its codes stay below K; the other channels
- * are not affected).
+ * that holds a non-finite weight, or is given a non-finite starting level, are unspecified, its
+ * codes stay below K; the other channels are not affected).
  */
 int cmpq_kmeans_quantize(const void *W, int dtype, int64_t d_in, int64_t d_out, int64_t ldw,
                          const uint8_t *bits, const int32_t *out_idx, int64_t n_out,

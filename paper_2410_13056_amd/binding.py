@@ -25,6 +25,7 @@ OP_ACT_STATS, OP_ALLOCATE_BITS, OP_OUTLIER_CHANNELS, OP_OUTLIER_WEIGHTS, OP_KMEA
 OUTLIER_CHANNELS, OUTLIER_WEIGHTS = 0, 1
 SCORE_RESIDUAL, SCORE_MAGNITUDE = 0, 1
 INIT_QUANTILE = 0
+INIT_GIVEN = 1
 KMEANS_HISTOGRAM, KMEANS_DIRECT = 0, 1
 NORM_L2, NORM_L1, NORM_LINF = 0, 1, 2
 

@@ -303,7 +303,16 @@ __device__ void kmeans_channel(const KmArgs &a, int64_t i, unsigned char *lds, K
     if (tid == 0 && sm.nonfinite && a.status) atomicOr(a.status, CMPQ_STATUS_NONFINITE);
     __syncthreads();
 
-    quantile_start<TW>(sm, K, d_out, xs, incl, reinterpret_cast<uint32_t *>(sums));
+    if (a.start_given) {  // the caller's levels, in level order; -0 is taken as +0
+        if (tid < K) {
+            const float given = crow[tid];
+            if (!isfinite(given) && a.status) atomicOr(a.status, CMPQ_STATUS_NONFINITE);
+            sm.cent[tid] = given == 0.0f ? 0.0f : given;
+        }
+        __syncthreads();
+    } else {
+        quantile_start<TW>(sm, K, d_out, xs, incl, reinterpret_cast<uint32_t *>(sums));
+    }
 
     switch (K) {
         case 2: lloyd_rounds<TW, WEIGHTED, 2>(a, i, sm, xs, incl, sums, mass); break;
@@ -381,7 +390,7 @@ extern "C" int cmpq_kmeans_quantize(const void *W, int dtype, int64_t d_in, int6
                                     int32_t *status, void *stream) {
     if (d_in < 0 || d_out < 0 || n_out < 0 || iters < 0) return CMPQ_EINVAL;
     if (dtype != CMPQ_F16 && dtype != CMPQ_F32) return CMPQ_EINVAL;
-    if (init != CMPQ_INIT_QUANTILE) return CMPQ_EINVAL;
+    if (init != CMPQ_INIT_QUANTILE && init != CMPQ_INIT_GIVEN) return CMPQ_EINVAL;
     if (!bits || !centroids || (n_out > 0 && !out_idx)) return CMPQ_EINVAL;
     if (d_in > 0 && d_out > 0 && (!W || !codes)) return CMPQ_EINVAL;
     if (ldw < d_out) return CMPQ_ESHAPE;
@@ -399,6 +408,7 @@ extern "C" int cmpq_kmeans_quantize(const void *W, int dtype, int64_t d_in, int6
     a.n_out = n_out;
     a.ew = elem_weight;
     a.iters = iters;
+    a.start_given = init == CMPQ_INIT_GIVEN;
     a.centroids = centroids;
     a.codes = codes;
     a.status = status;
@@ -415,7 +425,8 @@ extern "C" int cmpq_kmeans_quantize(const void *W, int dtype, int64_t d_in, int6
     }
     if (kmeans_fast_eligible(a, dtype)) {
         // the bucket kernel takes every channel itself
-        if (g_kmeans_algorithm != CMPQ_KMEANS_DIRECT) return launch_kmeans_hist(a, s);
+        // (so does a run from given levels, whichever implementation is selected)
+        if (g_kmeans_algorithm != CMPQ_KMEANS_DIRECT || a.start_given) return launch_kmeans_hist(a, s);
         a.deferred = static_cast<uint8_t *>(ws);
         const int rc = launch_kmeans_fast(a, s);
         if (rc != CMPQ_OK) return rc;

@@ -10,6 +10,7 @@ struct KmArgs {
     int64_t n_out;
     const float *ew;
     int iters;
+    int start_given;  // the rounds start from the levels found in `centroids` (CMPQ_INIT_GIVEN)
     float *centroids;
     uint8_t *codes;
     int32_t *status;

@@ -355,8 +355,9 @@ __device__ __forceinline__ void lloyd_bucket(const KmArgs &a, int64_t i, BucketS
     __builtin_amdgcn_s_setprio(3);
     // ---- start-up: level j = order statistic floor((2j+1)M/(2K)) of the kept weights.
     //      L lanes per rank: locate the bucket by its prefix, then bisect on the place
-    //      with counting scans of that bucket.
-    {
+    //      with counting scans of that bucket.  Not when the caller gave the levels: they
+    //      are in place already.
+    if (!a.start_given) {
         const int j = tid / L, sub = tid & (L - 1);
         if (j < K) {
             float c = 0.0f;
@@ -623,9 +624,15 @@ __global__ __launch_bounds__(T) __attribute__((amdgpu_waves_per_eu(6, 8))) void 
         uint4 *a4 = reinterpret_cast<uint4 *>(arr);
         for (int s = tid; s < (int)(arr_bytes >> 4); s += T) a4[s] = make_uint4(kFill4, kFill4, kFill4, kFill4);
     }
-    if (!__syncthreads_and((nonfinite & 0x80008000u) == 0u)) {
-        // a non-finite weight: the caller's status word says so; the channel gets defined
-        // outputs (all levels 0, all codes 0) instead of a clustering of NaNs
+    bool bad_start = false;
+    if (a.start_given && tid < K) {  // the caller's levels, in level order; -0 is taken as +0
+        const float given = crow[tid];
+        bad_start = !isfinite(given);
+        sm.cent[tid] = given == 0.0f ? 0.0f : given;
+    }
+    if (!__syncthreads_and((nonfinite & 0x80008000u) == 0u && !bad_start)) {
+        // a non-finite weight or starting level: the caller's status word says so; the channel
+        // gets defined outputs (all levels 0, all codes 0) instead of a clustering of NaNs
         if (tid == 0 && a.status) atomicOr(a.status, CMPQ_STATUS_NONFINITE);
         if (tid < CMPQ_KMAX) crow[tid] = tid < K ? 0.0f : INFINITY;
         uint32_t *c32 = reinterpret_cast<uint32_t *>(a.codes + i * a.d_out);

@@ -102,7 +102,8 @@ def _channels_and_widths(sumsq, d_in, bit_set, avg_bits, rho_act_ppm, ws, timer)
 
 
 def _after_first_pass(Wt, sumsq, bit_set, counts, act_idx, chan_mask, bits, cent1, codes1, rho_q_ppm, iters,
-                      ws, score, with_error, keep_prelim, status, timer) -> LayerResult:
+                      ws, score, with_error, keep_prelim, status, timer,
+                      iters_final_from_prelim: Optional[int] = None) -> LayerResult:
     """O_q from the preliminary quantization, the final quantization, the stored format."""
     dev = Wt.device
     d_in, d_out = Wt.shape
@@ -113,10 +114,16 @@ def _after_first_pass(Wt, sumsq, bit_set, counts, act_idx, chan_mask, bits, cent
     with _stage(timer, "outlier_weights"):
         B.extract_weight_outliers(Wt, cent1, codes1, bits, k_q, out_idx, out_val, ws, score)
     # final quantization of W - O
-    cent = torch.empty((d_in, B.KMAX), dtype=torch.float32, device=dev)
     codes = torch.empty((d_in, d_out), dtype=torch.uint8, device=dev)
-    with _stage(timer, "kmeans"):
-        B.kmeans_quantize(Wt, bits, out_idx, k_q, None, iters, cent, codes, ws, status)
+    if iters_final_from_prelim is None:
+        cent = torch.empty((d_in, B.KMAX), dtype=torch.float32, device=dev)
+        with _stage(timer, "kmeans"):
+            B.kmeans_quantize(Wt, bits, out_idx, k_q, None, iters, cent, codes, ws, status)
+    else:  # variant: continue from the preliminary levels (a copy; the call updates it in place)
+        cent = cent1.clone()
+        with _stage(timer, "kmeans"):
+            B.kmeans_quantize(Wt, bits, out_idx, k_q, None, iters_final_from_prelim, cent, codes, ws, status,
+                              init=B.INIT_GIVEN)
     # stored format
     packed, chan_idx, lut = [], [], []
     for b, c in zip(bit_set, counts):
@@ -147,9 +154,14 @@ def quantize_layer(W: torch.Tensor, sumsq: torch.Tensor, bit_set: Sequence[int],
                    ws: Optional[B.Workspace] = None, score: int = B.SCORE_RESIDUAL,
                    with_error: bool = False, keep_prelim: bool = False,
                    status: Optional[torch.Tensor] = None, transposed: bool = False,
-                   timer: Optional[StageTimer] = None) -> LayerResult:
+                   timer: Optional[StageTimer] = None,
+                   iters_final_from_prelim: Optional[int] = None) -> LayerResult:
     """Quantizes one layer.  `W` is the framework's [d_out, d_in] weight (or already
-    d_in x d_out with ``transposed=True``); `sumsq` comes from `activation_stats`."""
+    d_in x d_out with ``transposed=True``); `sumsq` comes from `activation_stats`.
+
+    ``iters_final_from_prelim`` (a variant; the paper names no start for either K-means of
+    Sec. 3.2.2): the final quantization starts from the levels of the preliminary one and runs
+    that many rounds, instead of `iters` rounds from the quantile start."""
     ws = ws or B.Workspace(W.device)
     dev = W.device
     Wt = _oriented(W, transposed, timer)
@@ -161,7 +173,7 @@ def quantize_layer(W: torch.Tensor, sumsq: torch.Tensor, bit_set: Sequence[int],
     with _stage(timer, "kmeans"):
         B.kmeans_quantize(Wt, bits, None, 0, None, iters, cent1, codes1, ws, status)
     return _after_first_pass(Wt, sumsq, bit_set, counts, act_idx, chan_mask, bits, cent1, codes1, rho_q_ppm,
-                             iters, ws, score, with_error, keep_prelim, status, timer)
+                             iters, ws, score, with_error, keep_prelim, status, timer, iters_final_from_prelim)
 
 
 @dataclasses.dataclass
@@ -389,7 +401,7 @@ def quantize_block(weights: Dict[str, torch.Tensor], acts: Dict[str, torch.Tenso
                    avg_bits: float, rho_act_ppm: int, rho_q_ppm: int, iters: int,
                    ws=None, with_error: bool = False, status: Optional[torch.Tensor] = None,
                    timer: Optional[StageTimer] = None, streams: int = 1,
-                   join: bool = True) -> Dict[str, LayerResult]:
+                   join: bool = True, iters_final_from_prelim: Optional[int] = None) -> Dict[str, LayerResult]:
     """One pass of the whole path over a decoder block: statistics once per distinct
     input, then every linear layer.  `layers` lists (name, x_key) pairs.
 
@@ -398,6 +410,8 @@ def quantize_block(weights: Dict[str, torch.Tensor], acts: Dict[str, torch.Tenso
     compute-bound k-means of one layer runs beside the memory-bound steps of another; `ws`
     is then a list with one workspace per stream.  The call returns with everything
     enqueued and the current stream waiting for the others.
+
+    ``iters_final_from_prelim``: see `quantize_layer` (a variant, off by default).
 
     With ``join=False`` the current stream does not wait: the streams run on into the next
     call (a model is quantized block after block, and the queues of one block need not drain
@@ -413,7 +427,7 @@ def quantize_block(weights: Dict[str, torch.Tensor], acts: Dict[str, torch.Tenso
                 stats[x_key] = activation_stats(acts[x_key], ws, status=status, timer=timer)[1]
             out[name] = quantize_layer(weights[name], stats[x_key], bit_set, avg_bits, rho_act_ppm,
                                        rho_q_ppm, iters, ws, with_error=with_error, status=status,
-                                       timer=timer)
+                                       timer=timer, iters_final_from_prelim=iters_final_from_prelim)
         return out
     if ws is None:
         ws = [B.Workspace(dev) for _ in range(streams)]
@@ -440,7 +454,8 @@ def quantize_block(weights: Dict[str, torch.Tensor], acts: Dict[str, torch.Tenso
                 sumsq.record_stream(side[j])      # its memory is not reused before this stream is done with it
             results[name] = quantize_layer(weights[name], sumsq, bit_set, avg_bits, rho_act_ppm,
                                            rho_q_ppm, iters, ws[j], with_error=with_error,
-                                           status=status, timer=timer)
+                                           status=status, timer=timer,
+                                           iters_final_from_prelim=iters_final_from_prelim)
     if join:
         for st in side:
             main.wait_stream(st)

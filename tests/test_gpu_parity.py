@@ -173,15 +173,19 @@ def test_channel_outliers_and_allocation_parity(env, d_in):
 
 # ------------------------------------------------------------------ k-means
 
-def _kmeans_gpu(env, W, bits, out_idx=None, ew=None, iters=20, status=None):
+def _kmeans_gpu(env, W, bits, out_idx=None, ew=None, iters=20, status=None, start=None):
     B, ws = env["B"], env["ws"]
     Wd = _dev(W)
     d_in, d_out = W.shape
-    cent = torch.empty((d_in, 16), dtype=torch.float32, device=DEV)
+    if start is None:
+        cent = torch.empty((d_in, 16), dtype=torch.float32, device=DEV)
+    else:
+        cent = _dev(np.ascontiguousarray(start, np.float32))
     codes = torch.full((d_in, d_out), 255, dtype=torch.uint8, device=DEV)
     oi = None if out_idx is None else _dev(out_idx.astype(np.int32))
     B.kmeans_quantize(Wd, _dev(bits), oi, 0 if out_idx is None else len(out_idx),
-                      None if ew is None else _dev(ew), iters, cent, codes, ws, status)
+                      None if ew is None else _dev(ew), iters, cent, codes, ws, status,
+                      init=B.INIT_QUANTILE if start is None else B.INIT_GIVEN)
     return _np(cent), _np(codes)
 
 
@@ -332,6 +336,63 @@ def test_kmeans_flags_nonfinite_weights_and_is_reproducible(env):
     ok = np.arange(8) != 2                       # the other channels are not affected
     assert np.array_equal(c3[ok], c1[ok]) and np.array_equal(k3[ok], k1[ok])
     assert k3[2].max() < 8
+
+
+@pytest.mark.parametrize("dtype", [np.float16, np.float32])
+@pytest.mark.parametrize("d_in,d_out", [(6, 64), (9, 300), (11, 4096 + 24), (5, 8192), (4, 28672)])
+def test_kmeans_from_given_levels_parity(env, dtype, d_in, d_out):
+    """CMPQ_INIT_GIVEN: rounds started from the caller's levels (the preliminary ones, a shuffled
+    copy with a repeat, levels far outside the data), with and without removed entries."""
+    orc = env["orc"]
+    if dtype == np.float32:
+        d_out = min(d_out, 16384)                        # the limit of the entry point for fp32
+    rng = np.random.default_rng(d_in * 17 + d_out)
+    W = rng.normal(0, 0.03, (d_in, d_out)).astype(dtype)
+    W[0, : d_out // 3] = W[0, 0]
+    bits = rng.integers(1, 5, d_in).astype(np.uint8)
+    bits[d_in // 2] = 16
+    n_q = max(1, d_in * d_out // 80)
+    excl = np.sort(rng.choice(d_in * d_out, n_q, replace=False)).astype(np.int64)
+    prelim, _ = orc.kmeans(W, bits, iters=3)
+    odd = prelim.copy()
+    for i in range(d_in):
+        K = 1 << int(bits[i]) if bits[i] <= 4 else 0
+        if K >= 2:
+            odd[i, :K] = rng.permutation(odd[i, :K])
+            odd[i, K - 1] = odd[i, 0]                    # a repeated level
+        if K >= 4:
+            odd[i, 1] = 50.0                             # beyond every weight: stays without members
+            odd[i, 2] = -0.0
+    for start in (prelim, odd):
+        for oi in (None, excl):
+            for iters in (0, 4):
+                ocent, ocodes = orc.kmeans(W, bits, out_idx=oi, iters=iters, start=start)
+                cent, codes = _kmeans_gpu(env, W, bits, out_idx=oi, iters=iters, start=start)
+                _check_kmeans(cent, codes, ocent, ocodes, exact=dtype == np.float16)
+
+
+def test_kmeans_from_given_levels_weighted_and_flags(env):
+    """The general kernel (importance per entry) from given levels; a non-finite starting level
+    raises the status flag and leaves the other channels as they are."""
+    orc, B = env["orc"], env["B"]
+    rng = np.random.default_rng(5)
+    d_in, d_out = 7, 700
+    W = rng.normal(0, 0.03, (d_in, d_out)).astype(np.float16)
+    bits = np.array([2, 3, 4, 16, 1, 4, 3], np.uint8)
+    ew = rng.lognormal(0, 1, (d_in, d_out)).astype(np.float32)
+    start, _ = orc.kmeans(W, bits, iters=2)
+    ocent, ocodes = orc.kmeans(W, bits, elem_weight=ew, iters=5, start=start)
+    cent, codes = _kmeans_gpu(env, W, bits, ew=ew, iters=5, start=start)
+    _check_kmeans(cent, codes, ocent, ocodes, exact=False)
+    st = torch.zeros(1, dtype=torch.int32, device=DEV)
+    good, gk = _kmeans_gpu(env, W, bits, iters=5, start=start, status=st)
+    assert st.item() == 0
+    bad = start.copy()
+    bad[2, 3] = np.nan
+    c, k = _kmeans_gpu(env, W, bits, iters=5, start=bad, status=st)
+    assert st.item() & B.STATUS_NONFINITE
+    ok = np.arange(d_in) != 2
+    assert np.array_equal(c[ok], good[ok]) and np.array_equal(k[ok], gk[ok]) and k[2].max() < 16
 
 
 # ------------------------------------------------------------------ O_q
@@ -560,11 +621,13 @@ def test_end_to_end_tiny_config(env):
     _compare_layer(env, r, o, wl.bit_set, exact_levels=False)
 
 
+@pytest.mark.parametrize("from_prelim", [None, 5])
 @pytest.mark.parametrize("name,shrink,tokens", [("q7b", 8, 2048), ("block7b", 16, 1024),
                                                 ("block13b", 16, 1024), ("block70b", 32, 512)])
-def test_end_to_end_scaled_workloads(env, name, shrink, tokens):
+def test_end_to_end_scaled_workloads(env, name, shrink, tokens, from_prelim):
     """Every configuration's structure (layer mix, budget, outlier fractions, rounds) at a size the
-    oracle finishes in seconds; dimensions stay multiples of 8, several tiles and ragged tails."""
+    oracle finishes in seconds; dimensions stay multiples of 8, several tiles and ragged tails.
+    Also with the final K-means continued from the preliminary levels for 5 rounds (the variant)."""
     P, synth, ws, orc = env["P"], env["synth"], env["ws"], env["orc"]
     wl = synth.scaled(synth.workload(name), tokens=tokens, shrink=shrink)
     wts, xs = synth.materialize(wl, DEV)
@@ -577,10 +640,11 @@ def test_end_to_end_scaled_workloads(env, name, shrink, tokens):
             assert np.array_equal(_np(stats[layer.x_key]), osum)
         W = wts[layer.name]
         r = P.quantize_layer(W, stats[layer.x_key], wl.bit_set, wl.avg_bits, wl.rho_act_ppm, wl.rho_q_ppm,
-                             wl.iters, ws, with_error=True, keep_prelim=True, status=status)
+                             wl.iters, ws, with_error=True, keep_prelim=True, status=status,
+                             iters_final_from_prelim=from_prelim)
         assert torch.equal(r.W_t, W.t().contiguous())
         o = orc.quantize_layer(_np(W).T.copy(), None, wl.bit_set, wl.avg_bits, wl.rho_act_ppm, wl.rho_q_ppm,
-                               wl.iters, sumsq=_np(stats[layer.x_key]))
+                               wl.iters, sumsq=_np(stats[layer.x_key]), iters_final_from_prelim=from_prelim)
         _compare_layer(env, r, o, wl.bit_set, exact_levels=True)
     assert status.item() == 0
 
