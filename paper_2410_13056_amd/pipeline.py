@@ -213,7 +213,8 @@ def quantize_layer_from_cache(cache: WidthCache, sumsq: torch.Tensor, avg_bits: 
                               ws: Optional[B.Workspace] = None, score: int = B.SCORE_RESIDUAL,
                               with_error: bool = False, keep_prelim: bool = False,
                               status: Optional[torch.Tensor] = None,
-                              timer: Optional[StageTimer] = None) -> LayerResult:
+                              timer: Optional[StageTimer] = None,
+                              iters_final_from_prelim: Optional[int] = None) -> LayerResult:
     """`quantize_layer` for another average width (or other outlier fractions) of a layer
     whose per-width runs are kept: the first K-means pass is a row-wise choice among them,
     everything after it runs as usual.  Same results as `quantize_layer`, bit for bit."""
@@ -227,7 +228,8 @@ def quantize_layer_from_cache(cache: WidthCache, sumsq: torch.Tensor, avg_bits: 
     with _stage(timer, "select_by_width"):
         B.select_by_width(bits, cache.bit_set, cache.centroids, cache.codes, cent1, codes1)
     return _after_first_pass(cache.W_t, sumsq, cache.bit_set, counts, act_idx, chan_mask, bits, cent1, codes1,
-                             rho_q_ppm, cache.iters, ws, score, with_error, keep_prelim, status, timer)
+                             rho_q_ppm, cache.iters, ws, score, with_error, keep_prelim, status, timer,
+                             iters_final_from_prelim)
 
 
 def tables_in_4_bits(r: LayerResult, ws: Optional[B.Workspace] = None, with_error: bool = False,

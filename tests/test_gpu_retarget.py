@@ -60,6 +60,13 @@ def test_cache_route_equals_direct_route_and_oracle(env, dtype, d_in, d_out):
                              keep_prelim=True)
         torch.cuda.synchronize()
         _same(a, b)
+    # the variant with the final pass continued from the preliminary levels takes both routes alike
+    a = P.quantize_layer_from_cache(cache, sumsq, 3.0, 4500, 500, env["ws"], with_error=True, keep_prelim=True,
+                                    iters_final_from_prelim=3)
+    b = P.quantize_layer(Wd, sumsq, bit_set, 3.0, 4500, 500, iters, env["ws"], with_error=True, keep_prelim=True,
+                         iters_final_from_prelim=3)
+    torch.cuda.synchronize()
+    _same(a, b)
     # the last budgets against the oracle's direct route
     o = orc.quantize_layer(np.ascontiguousarray(W.T), X, bit_set, 3.63, 10000, 2000, iters)
     a = P.quantize_layer_from_cache(cache, sumsq, 3.63, 10000, 2000, env["ws"], with_error=True)
