@@ -201,19 +201,18 @@ __device__ __forceinline__ uint32_t cell_of(uint32_t q, const uint32_t (&t)[CMPQ
 // Never the key of -0: a boundary there would part the two zeros.
 __device__ __forceinline__ uint32_t boundary_key(float lo, float hi, int owner_lo, int owner_hi) {
     const double mid = ((double)lo + (double)hi) * 0.5;
-    float f = (float)mid;  // round down to fp32 ...
-    if ((double)f > mid) {
-        uint32_t u = __float_as_uint(f);
-        if (f > 0.0f) u -= 1; else if (f == 0.0f) u = 0x80000001u; else u += 1;
-        f = __uint_as_float(u);
+    float f = (float)mid;  // round down to fp32 ...: one step towards -infinity when the cast went up
+    {
+        const uint32_t u = __float_as_uint(f);
+        const uint32_t down = f > 0.0f ? u - 1u : (f == 0.0f ? 0x80000001u : u + 1u);
+        f = (double)f > mid ? __uint_as_float(down) : f;
     }
     uint32_t h = __half_as_ushort(__float2half_rn(f));  // ... then down to fp16
-    if (h == 0x8000u) h = 0;                            // -0 is +0 here; checked below against f
+    h = h == 0x8000u ? 0u : h;                          // -0 is +0 here; checked below against f
     uint32_t key = key_of_half(h);
-    if (value_of_key(key) > f) key -= 1;
-    if ((double)value_of_key(key) == mid && owner_hi < owner_lo) key -= 1;
-    if (key == 0x7fffu) key = 0x7ffeu;
-    return key;
+    key -= value_of_key(key) > f ? 1u : 0u;
+    key -= ((double)value_of_key(key) == mid && owner_hi < owner_lo) ? 1u : 0u;
+    return key == 0x7fffu ? 0x7ffeu : key;
 }
 
 // Wave 0: levels by level index (lane j holds c for j < K) -> per sorted position p
