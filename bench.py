@@ -106,10 +106,13 @@ def deployed_matvec(P, B, torch, out, layers, wl, acts, reps):
         return (time.perf_counter() - t0) / reps
 
     dt_layer, dt, dt_whole = timed(per_layer), timed(grouped), timed(one_group)
+    graph = P.capture_products(groups, ws)      # the same launches as `grouped`, submitted as one HIP graph
+    dt_graph = timed(graph.replay)
     return {"what": "Y = x W_hat for one token through all layers of the block, from the stored format; "
                     "products that read the same input are launched together",
             "launch_groups": [names for names in by_input.values()],
             "ms_per_token": dt * 1e3, "Gweights_per_s": wl.params / dt / 1e9,
+            "ms_per_token_launches_in_a_hip_graph": dt_graph * 1e3,
             "ms_per_token_one_call_per_layer": dt_layer * 1e3,
             "ms_per_token_all_products_in_one_group": dt_whole * 1e3,
             "roofline": {"bound": "hbm", "achieved": algo_bytes / dt / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",

@@ -373,6 +373,24 @@ def group_products(deps: Sequence[Deployed]) -> B.LutMatvecGroupCall:
     return B.LutMatvecGroupCall([d.call() for d in deps])
 
 
+def capture_products(steps: Sequence[tuple], ws: B.Workspace):
+    """Sec. 6: the product launches of one token recorded as a HIP graph.  `steps` is a sequence
+    of ``(call, Xs, Ys)`` with `call` from `group_products`; the launches go into the graph in
+    that order and ``graph.replay()`` submits them at once, which removes the host's share of a
+    chain of short launches.  The graph reads and writes the tensors given here: the caller
+    puts the next token into `Xs` and takes the result from `Ys` after the replay.  The steps
+    run once before recording, so that the workspace has its final size."""
+    for call, xs, ys in steps:
+        call(xs, ys, ws)
+    dev = steps[0][1][0].device
+    torch.cuda.synchronize(dev)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=_streams_for(dev, 1)[0]):
+        for call, xs, ys in steps:
+            call(xs, ys, ws)
+    return graph
+
+
 _side_streams: Dict[tuple, list] = {}
 
 

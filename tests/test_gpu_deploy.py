@@ -276,3 +276,32 @@ def test_randomized_products_and_groups(env, seed):
         What = _what(W, _np(r.centroids), _np(r.codes), _np(r.bits), out_idx)
         Yref = orc.lut_matvec(_np(X), W, _np(r.centroids), _np(r.codes), _np(r.bits), out_idx)
         _check_product(_np(Y), Yref, _np(X), What)
+
+
+def test_products_replayed_from_a_hip_graph_equal_eager_launches(env):
+    """The launches of a token recorded once (two groups, three layers) and replayed four times
+    with new inputs, eager work and synchronisations in between: every replay equals the eager
+    result of the same inputs bit for bit."""
+    P, B = env["P"], env["B"]
+    ws = B.Workspace(DEV)
+    rng = np.random.default_rng(31)
+    deps = [_deploy_random_layer(env, rng, d_in, d_out, (2, 3, 4), 3.0)[2] for d_in, d_out in
+            ((96, 512), (96, 160), (160, 96))]
+    xa = torch.zeros((1, 96), dtype=torch.float16, device=DEV)
+    xb = torch.zeros((1, 160), dtype=torch.float16, device=DEV)
+    ys = [torch.zeros((1, d.d_out), dtype=torch.float32, device=DEV) for d in deps]
+    steps = [(P.group_products(deps[:2]), [xa, xa], ys[:2]), (P.group_products(deps[2:]), [xb], ys[2:])]
+    graph = P.capture_products(steps, ws)
+    gen = torch.Generator(device=DEV).manual_seed(11)
+    for it in range(4):
+        xa.copy_(torch.randn((1, 96), generator=gen, device=DEV).to(torch.float16))
+        xb.copy_(torch.randn((1, 160), generator=gen, device=DEV).to(torch.float16))
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [y.clone() for y in ys]
+        for y in ys:
+            y.fill_(-1.0)
+        want = [P.lut_matvec(d, x, B.Workspace(DEV)) for d, x in zip(deps, (xa, xa, xb))]   # eager, own workspace
+        torch.cuda.synchronize()
+        for g, w in zip(got, want):
+            assert torch.equal(g, w), it
