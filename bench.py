@@ -232,8 +232,8 @@ def continued_final_pass(P, torch, step_variant, out, layers, wl, rounds, reps, 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=5)
-    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="block70b",
                     help="block70b (default, the headline target), block13b, block7b, q7b, tiny")
     ap.add_argument("--no-cpu-baseline", action="store_true")
