@@ -179,7 +179,7 @@ __device__ __forceinline__ void pack32_words(const uint32_t (&r)[8], uint32_t (&
     }
 }
 
-// One channel of d_out = 32 * groups entries: a lane takes 32 consecutive entries per step.
+// 32 codes packed and written as B words.
 template <int B>
 __device__ __forceinline__ void pack_store(const uint32_t (&r)[8], uint32_t *__restrict__ dst) {
     uint32_t pw[B];
@@ -188,6 +188,7 @@ __device__ __forceinline__ void pack_store(const uint32_t (&r)[8], uint32_t *__r
     for (int t = 0; t < B; ++t) dst[t] = pw[t];
 }
 
+// One channel of d_out = 32 * groups entries: a lane takes 32 consecutive entries per step.
 template <typename TW>
 __device__ __forceinline__ double pack_error_row(const TW *__restrict__ wrow, const uint8_t *__restrict__ crow,
                                                  int64_t groups, uint32_t *__restrict__ dst, int b,
