@@ -120,13 +120,12 @@ __device__ __forceinline__ uint32_t group_sum(uint32_t v) {
 }
 
 __device__ __forceinline__ unsigned long long wave_scan_incl_u64(unsigned long long v) {
-    const int lane = threadIdx.x & 63;
-#pragma unroll
-    for (int s = 1; s < 64; s <<= 1) {
-        const unsigned long long t = __shfl_up(v, s, CMPQ_WAVE);
-        if (lane >= s) v += t;
-    }
-    return v;
+    // Three limbs of 22, 22 and 20 bits: the 64 partial sums of a limb stay below 2^28, so
+    // each limb is scanned on the DPP path, and the limbs are joined modulo 2^64 (sums of
+    // two's complement values come out right).
+    const uint32_t l0 = (uint32_t)v & 0x3fffffu, l1 = (uint32_t)(v >> 22) & 0x3fffffu, l2 = (uint32_t)(v >> 44);
+    const uint32_t s0 = wave_scan_incl_u32(l0), s1 = wave_scan_incl_u32(l1), s2 = wave_scan_incl_u32(l2);
+    return (unsigned long long)s0 + ((unsigned long long)s1 << 22) + ((unsigned long long)s2 << 44);
 }
 
 // Exclusive scan of a (count, sum) pair per thread over the workgroup, one set of
