@@ -361,18 +361,47 @@ __device__ __forceinline__ void lloyd_bucket(const KmArgs &a, int64_t i, BucketS
             float c = 0.0f;
             if (M > 0) {
                 const uint32_t r = (uint32_t)(((uint64_t)(2 * j + 1) * M) / (uint64_t)(2 * K));
-                int lo = 0, hi_b = kBuckets - 1;  // largest b with ncum[b] <= r
+                const int g0 = lane & ~(L - 1);  // first lane of this group inside its wavefront
+                // largest b with ncum[b] <= r: the L lanes probe L evenly spaced buckets at a time
+                // (ncum does not decrease, so the probes that pass come first)
+                int lo = 0, hi_b = kBuckets - 1;
                 while (lo < hi_b) {
-                    const int mid = (lo + hi_b + 1) >> 1;
-                    if (sm.ncum[mid] <= r) lo = mid; else hi_b = mid - 1;
+                    const int step = (hi_b - lo + L - 1) / L;
+                    const int probe = min(lo + (sub + 1) * step, hi_b);
+                    const unsigned long long pass = __ballot(sm.ncum[probe] <= r) >> g0;
+                    const int c_pass = __popcll(L < 64 ? pass & ((1ull << L) - 1) : pass);
+                    const int nlo = c_pass > 0 ? min(lo + c_pass * step, hi_b) : lo;
+                    if (c_pass < L) hi_b = min(lo + (c_pass + 1) * step, hi_b) - 1;
+                    lo = nlo;
                 }
                 const uint32_t b = (uint32_t)lo, r_in = r - sm.ncum[b];
                 const uint32_t begin = sm.start[b], end = sm.start[b + 1];
-                int pl = 0, ph = kLows - 1;  // smallest place with more than r_in weights at or below it
+                // smallest place with more than r_in weights at or below it: bisection on the place.
+                // The bucket's words are fetched once (4 per lane) when they fit; the counting
+                // scans of the bisection then run on registers.
+                const uint32_t w_begin = begin >> 2, w_end = end >> 2;
+                const bool fits = w_end - w_begin <= 4u * L;
+                const uint32_t *words = reinterpret_cast<const uint32_t *>(arr);
+                uint32_t x[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const uint32_t at = w_begin + sub + u * L;
+                    x[u] = at < w_end ? words[at] : kFill4;
+                }
+                int pl = 0, ph = kLows - 1;
                 while (pl < ph) {
                     const int mid = (pl + ph) >> 1;
                     uint32_t n, l;
-                    scan_bucket<L>(arr, begin, end, (uint32_t)mid, n, l);
+                    if (fits) {
+                        const uint32_t bias = 0x7f7f7f7fu - (uint32_t)mid * 0x01010101u;
+                        uint32_t cn = 0;
+#pragma unroll
+                        for (int u = 0; u < 4; ++u)
+                            cn = __builtin_amdgcn_sad_u8((~((x[u] + bias) >> 7)) & 0x01010101u, 0u, cn);
+                        n = group_sum<L>(cn);
+                    } else {
+                        scan_bucket<L>(arr, begin, end, (uint32_t)mid, n, l);
+                    }
                     if (n > r_in) ph = mid; else pl = mid + 1;
                 }
                 c = value_of_key((b << kLowBits) | (uint32_t)pl);
@@ -570,10 +599,11 @@ __device__ __forceinline__ void lloyd_bucket(const KmArgs &a, int64_t i, BucketS
     __syncthreads();
 }
 
-// Occupancy: 6 wavefronts per SIMD (80 registers) - 6 workgroups of 256 lanes or 3 of 512
-// per compute unit, LDS permitting.
+// Occupancy: 6 wavefronts per SIMD for the 16-group variant (77 registers: 3 workgroups of
+// 512 lanes per compute unit, which is also what LDS allows at d_out = 28 672), 7 for the
+// shorter multi-wavefront variants (at most 72 registers: 7 workgroups of 256 lanes).
 template <int G, int T, int LB>
-__global__ __launch_bounds__(T) __attribute__((amdgpu_waves_per_eu(6, 8))) void kmeans_bucket_kernel(KmArgs a) {
+__global__ __launch_bounds__(T) __attribute__((amdgpu_waves_per_eu(6, 7))) void kmeans_bucket_kernel(KmArgs a) {
     constexpr int kBuckets = 1 << (16 - LB);
     // dynamic LDS: places of the kept weights, ordered by bucket (a byte each; the bucket
     // follows from the position) | removed-entry bitmap (one bit per weight) | the scatter
