@@ -419,8 +419,21 @@ __device__ __forceinline__ void lloyd_bucket(const KmArgs &a, int64_t i, BucketS
     float c_sorted = 0.0f, hi = 0.0f;
     int own = lane, owner_lo = 0, owner_hi = 0;
     bool have_hi = false;
-    if (wave == 0)
-        rank_levels<K>(lane < K ? sm.cent[lane] : INFINITY, c_sorted, own, hi, owner_lo, owner_hi, have_hi);
+    if (wave == 0) {
+        // starting levels that ascend strictly (the usual outcome of the quantile start) are
+        // in sorted order already: each level's upper neighbour sits one lane up
+        const float c0 = lane < K ? sm.cent[lane] : INFINITY;
+        const float c0_up = __uint_as_float(row_from_above(__float_as_uint(c0)));
+        if (__ballot(lane < K - 1 && !(c0 < c0_up)) == 0ull) {
+            c_sorted = c0;
+            hi = c0_up;
+            owner_lo = lane;
+            owner_hi = lane + 1;
+            have_hi = lane < K - 1;
+        } else {
+            rank_levels<K>(c0, c_sorted, own, hi, owner_lo, owner_hi, have_hi);
+        }
+    }
     uint32_t tk_prev = 0xffffffffu;
     const int p_mine = tid / L;  // the boundary this lane helps with
     int par = 0;
