@@ -46,6 +46,7 @@ def lib():
         _lib.orc_count_ppm.restype = ctypes.c_int64
         _lib.orc_count_ppm.argtypes = [ctypes.c_int64, ctypes.c_int64]
         _lib.orc_pack.restype = ctypes.c_int64
+        _lib.orc_weight_outliers_per_channel.restype = ctypes.c_int64
         _lib.orc_f32_to_f16.restype = ctypes.c_uint16
         _lib.orc_f32_to_f16.argtypes = [ctypes.c_float]
         _lib.orc_f16_to_f64.restype = ctypes.c_double
@@ -177,6 +178,27 @@ def weight_outliers(W: np.ndarray, centroids: Optional[np.ndarray], codes: Optio
     return idx[:k], val[:k]
 
 
+def weight_outliers_per_channel(W: np.ndarray, centroids: Optional[np.ndarray], codes: Optional[np.ndarray],
+                                bits: np.ndarray, k: int, score: int = SCORE_RESIDUAL):
+    """The variant of O_q with `k` entries in every channel whose width is in 1..4.  Returns
+    ``(idx int64[k * n_live] ascending, val uint16[k * n_live] = FP16 bit patterns)``."""
+    W = _c(W)
+    d_in, d_out = W.shape
+    bits = _c(bits, np.uint8)
+    cent = None if centroids is None else _c(centroids, np.float32)
+    cd = None if codes is None else _c(codes, np.uint8)
+    n_live = int(((bits >= 1) & (bits <= 4)).sum())
+    idx = np.zeros(max(k * n_live, 1), np.int64)
+    val = np.zeros(max(k * n_live, 1), np.uint16)
+    n = lib().orc_weight_outliers_per_channel(_p(W), _dtype_code(W), ctypes.c_int64(d_in), ctypes.c_int64(d_out),
+                                              ctypes.c_int64(d_out), _p(cent), _p(cd), _p(bits), int(score),
+                                              ctypes.c_int64(k), _p(idx), _p(val))
+    if n < 0:
+        raise ValueError(f"orc_weight_outliers_per_channel rc={n}")
+    assert n == k * n_live, (n, k, n_live)
+    return idx[:n], val[:n]
+
+
 def pack(codes: np.ndarray, bits: np.ndarray, centroids: np.ndarray, b: int):
     """Returns ``(packed uint32[rows, ceil(d_out*b/32)], chan_idx int32[rows], lut uint16[rows, 2^b])``."""
     codes = _c(codes, np.uint8)
@@ -263,15 +285,32 @@ def lut4(centroids: np.ndarray, bits: np.ndarray):
     return codes4, rng, cq
 
 
+def lut4_codebook(centroids: np.ndarray, bits: np.ndarray, iters: int = 20):
+    """Sec. 5.1 / Tab. 7: the look-up tables in 4 bits, as codes into one 16-entry table per layer
+    found by K-means over all the layer's FP16 centres.  Returns ``(codes4 uint8[d_in,16],
+    table float32[16], centroids_q float32[d_in,16])``."""
+    cent = _c(centroids, np.float32)
+    d_in = cent.shape[0]
+    codes4 = np.zeros((d_in, KMAX), np.uint8)
+    table = np.zeros(KMAX, np.float32)
+    cq = np.zeros((d_in, KMAX), np.float32)
+    rc = lib().orc_lut4_codebook(_p(cent), _p(_c(bits, np.uint8)), ctypes.c_int64(d_in), int(iters), _p(codes4),
+                                 _p(table), _p(cq))
+    assert rc == 0, rc
+    return codes4, table, cq
+
+
 def quantize_layer(W: np.ndarray, X: np.ndarray, bit_set: Sequence[int], avg_bits: float,
                    rho_act_ppm: int = 4500, rho_q_ppm: int = 500, iters: int = 20,
                    sumsq: Optional[np.ndarray] = None, score: int = SCORE_RESIDUAL,
-                   iters_final_from_prelim: Optional[int] = None) -> dict:
+                   iters_final_from_prelim: Optional[int] = None, per_channel: bool = False) -> dict:
     """The whole path of Sec. 3.2, step by step, on one layer.
 
     ``W`` is ``[d_in, d_out]`` (paper orientation), ``X`` is ``[n, d_in]``.
     ``iters_final_from_prelim`` (variant): the final K-means starts from the levels of the
     preliminary one and runs that many rounds, instead of `iters` rounds from the quantile start.
+    ``per_channel`` (variant): O_q takes ``round_half_up(rho_q * d_out)`` entries in every channel
+    outside O_act instead of ``round_half_up(rho_q * d_in * d_out)`` over the layer.
     """
     d_in, d_out = W.shape
     if sumsq is None:
@@ -280,8 +319,11 @@ def quantize_layer(W: np.ndarray, X: np.ndarray, bit_set: Sequence[int], avg_bit
     act_idx, chan_mask = top_channels(sumsq, k_act)                      # O_act
     bits, counts = allocate_bits(sumsq, chan_mask, bit_set, avg_bits)     # Algorithm 1 on W'
     cent1, codes1 = kmeans(W, bits, iters=iters)                          # W'_q
-    k_q = count_ppm(rho_q_ppm, d_in * d_out)
-    out_idx, out_val = weight_outliers(W, cent1, codes1, bits, k_q, score)  # O_q
+    if per_channel:
+        out_idx, out_val = weight_outliers_per_channel(W, cent1, codes1, bits, count_ppm(rho_q_ppm, d_out), score)
+    else:
+        k_q = count_ppm(rho_q_ppm, d_in * d_out)
+        out_idx, out_val = weight_outliers(W, cent1, codes1, bits, k_q, score)  # O_q
     if iters_final_from_prelim is None:
         cent, codes = kmeans(W, bits, out_idx=out_idx, iters=iters)       # W_q
     else:

@@ -17,11 +17,13 @@
  *   orc_allocate_bits    Algorithm 1, integer-budget reading
  *   orc_kmeans           per-channel K-means, K = 2^c_i      (Sec. 3.2.1; Sec. 3 eq. Q(x))
  *   orc_weight_outliers  O_q: largest |W' - W'_q|           (Sec. 3.2.2)
+ *   orc_weight_outliers_per_channel  the same with a fixed count per channel (a variant)
  *   orc_pack             per-width code matrices + FP16 look-up tables (Sec. 5.1, Fig. 4)
  *   orc_dequant_error    W_hat = W_q + O and ||X (W - W_hat)|| (Sec. 3.2.2; App. B.3 eq. Delta Y)
  * Beside the path: orc_lut_matvec (Fig. 4), orc_act_stats_norm (App. Tab. 13) and
  * orc_rtn_quantize (App. A.2: the uniform quantizer of Sec. 3 in place of K-means),
- * orc_lut4 (Sec. 5.1, Tab. 7: the look-up tables themselves held in 4 bits).
+ * orc_lut4_codebook (Sec. 5.1, Tab. 7: the look-up tables themselves held in 4 bits, as codes
+ * into one 16-entry table per layer) and orc_lut4 (the same on a uniform grid, an alternative).
  *
  * Parity pins (tests/ -m "not gpu") cover every function here; none is
  * "parity unpinned" except the k-means trajectory on large inputs, which is
@@ -128,6 +130,7 @@ int orc_act_stats_norm(const void *X, int dtype, int64_t n, int64_t d_in, int64_
             double x = load_elem(X, dtype, t * ldx + i);
             if (norm == 0) s += x * x;
             else if (norm == 1) s += fabs(x);
+            else if (x != x) s = x; /* a NaN stays, as it does in the two sums */
             else if (fabs(x) > s) s = fabs(x);
         }
         acc[i] = s;
@@ -437,6 +440,47 @@ int orc_weight_outliers(const void *W, int dtype, int64_t d_in, int64_t d_out, i
     return 0;
 }
 
+/*
+ * The same selection with the count fixed per channel instead of per layer (a variant; the
+ * rule of Sec. 3.2.2 is the layer-wide one above): in every channel with bits in 1..4 the k
+ * entries with the largest score, larger first, equal scores by smaller output index.  The
+ * channels follow each other in ascending order and the entries of a channel are ascending,
+ * so idx_out[k * n_live] is ascending as a whole; val_out as above.  Returns the number of
+ * entries written (k times the number of such channels), or < 0 (k > d_out: -3).
+ */
+int64_t orc_weight_outliers_per_channel(const void *W, int dtype, int64_t d_in, int64_t d_out,
+                                        int64_t ldw, const float *centroids, const uint8_t *codes,
+                                        const uint8_t *bits, int score, int64_t k,
+                                        int64_t *idx_out, uint16_t *val_out) {
+    if (!W || !bits || k < 0) return -1;
+    if (score == ORC_SCORE_RESIDUAL && (!centroids || !codes)) return -1;
+    if (k > d_out) return -3;
+    keyidx_t *r = (keyidx_t *)malloc(sizeof(keyidx_t) * (size_t)(d_out ? d_out : 1));
+    int64_t *sel = (int64_t *)malloc(sizeof(int64_t) * (size_t)(k ? k : 1));
+    int64_t n = 0;
+    for (int64_t i = 0; i < d_in; ++i) {
+        if (bits[i] < 1 || bits[i] > 4) continue;
+        for (int64_t o = 0; o < d_out; ++o) {
+            double w = load_elem(W, dtype, i * ldw + o);
+            double s = score == ORC_SCORE_RESIDUAL
+                           ? fabs(w - (double)centroids[i * ORC_KMAX + codes[i * d_out + o]])
+                           : fabs(w);
+            r[o].key = float_bits((float)s);
+            r[o].idx = o;
+        }
+        qsort(r, (size_t)d_out, sizeof(keyidx_t), cmp_keyidx);
+        for (int64_t j = 0; j < k; ++j) sel[j] = r[j].idx;
+        qsort(sel, (size_t)k, sizeof(int64_t), cmp_i64);
+        for (int64_t j = 0; j < k; ++j, ++n) {
+            if (idx_out) idx_out[n] = i * d_out + sel[j];
+            if (val_out) val_out[n] = double_to_half(load_elem(W, dtype, i * ldw + sel[j]));
+        }
+    }
+    free(sel);
+    free(r);
+    return n;
+}
+
 /* ---- Sec. 5.1 / Fig. 4: stored format ------------------------------------------------------ */
 
 /*
@@ -679,6 +723,59 @@ int orc_lut4(const float *centroids, const uint8_t *bits, int64_t d_in, uint8_t 
         }
     }
     return 0;
+}
+
+/*
+ * Sec. 5.1 / Tab. 7 again, the reading taken as the default: the storage figure
+ * (1*4 + 8*4)/4096 leaves 4 bits per table entry and nothing per channel, and Tab. 7 reports a
+ * loss of at most 1.5 % - which a uniform grid over a heavy-tailed range of centres cannot
+ * give.  So the 4 bits index one 16-entry table per layer, found by the paper's own
+ * non-uniform quantizer (Sec. 3 eq. Q(x); Sec. 3.2.1's K-means with K = 16) over all the
+ * centres of the layer as the stored format holds them:
+ *   values     v = FP16(centroids[i][j]), j < 2^bits[i], channels with bits in 1..4, in
+ *              (i, j) order: one "channel" of M values;
+ *   clustering orc_kmeans on it with 4 bits: quantile start, `iters` rounds, exact nearest
+ *              level, fp64 means rounded to fp32 (the readings stated there);
+ *   codes4     the code of each value from that run's closing assignment (0 in unused slots);
+ *   table[16]  the 16 levels as fp32;
+ *   centroids_q[i][j] = FP16(table[codes4[i][j]]) as fp32: what a stored FP16 table of the
+ *              layer gives back (+infinity in unused slots and on channels of O_act).
+ * With no quantized channel the table is all zero.  "parity unpinned" against the paper (it
+ * prints no values); pinned to the clustering's properties and to Tab. 7's order of magnitude.
+ */
+int orc_lut4_codebook(const float *centroids, const uint8_t *bits, int64_t d_in, int iters,
+                      uint8_t *codes4, float *table, float *centroids_q) {
+    if (!centroids || !bits || !codes4 || !table || !centroids_q || iters < 0) return -1;
+    int64_t M = 0;
+    for (int64_t i = 0; i < d_in; ++i)
+        if (bits[i] >= 1 && bits[i] <= 4) M += 1 << bits[i];
+    uint16_t *v = (uint16_t *)malloc(sizeof(uint16_t) * (size_t)(M ? M : 1));
+    uint8_t *code = (uint8_t *)malloc((size_t)(M ? M : 1));
+    int64_t n = 0;
+    for (int64_t i = 0; i < d_in; ++i)
+        if (bits[i] >= 1 && bits[i] <= 4)
+            for (int j = 0; j < (1 << bits[i]); ++j) v[n++] = double_to_half((double)centroids[i * ORC_KMAX + j]);
+    const uint8_t four = 4;
+    float levels[ORC_KMAX];
+    int rc = orc_kmeans(v, ORC_F16, 1, M, M, &four, NULL, 0, NULL, iters, NULL, levels, code, NULL);
+    if (rc == 0) {
+        for (int j = 0; j < ORC_KMAX; ++j) table[j] = levels[j];
+        n = 0;
+        for (int64_t i = 0; i < d_in; ++i) {
+            const int K = (bits[i] >= 1 && bits[i] <= 4) ? (1 << bits[i]) : 0;
+            for (int j = 0; j < ORC_KMAX; ++j) {
+                codes4[i * ORC_KMAX + j] = 0;
+                centroids_q[i * ORC_KMAX + j] = INFINITY;
+                if (j >= K) continue;
+                const uint8_t c = code[n++];
+                codes4[i * ORC_KMAX + j] = c;
+                centroids_q[i * ORC_KMAX + j] = (float)half_to_double(double_to_half((double)levels[c]));
+            }
+        }
+    }
+    free(v);
+    free(code);
+    return rc;
 }
 
 /* Threads the "parallel for" loops above will use (reported beside oracle timings). */

@@ -429,6 +429,71 @@ def test_residual_score_finds_planted_distorters_not_just_big_weights(orc):
     assert all(i // d_out == 7 for i in idxm)
 
 
+def test_weight_outliers_per_channel_equal_row_sorts(orc):
+    """The per-channel variant of O_q: in every channel outside O_act, the k first entries of
+    that row's full (score descending, output index ascending) sort - with a coarse grid so that
+    tied scores decide membership; count per channel as the fraction of d_out, half rounded up."""
+    rng = np.random.default_rng(113)
+    d_in, d_out = 12, 200
+    W = (rng.integers(-30, 30, (d_in, d_out)) / 64.0).astype(np.float16)
+    bits = rng.integers(1, 5, d_in).astype(np.uint8)
+    bits[[0, 7]] = orc.PROTECTED
+    live = [i for i in range(d_in) if bits[i] <= 4]
+    cent, codes = orc.kmeans(W, bits, iters=4)
+    resid = np.abs(W.astype(np.float64) - np.take_along_axis(cent.astype(np.float64), codes.astype(np.int64),
+                                                            axis=1)).astype(np.float32)
+    for score, key in ((orc.SCORE_RESIDUAL, resid), (orc.SCORE_MAGNITUDE, np.abs(W).astype(np.float32))):
+        for k in (0, 1, 7, d_out):
+            idx, val = orc.weight_outliers_per_channel(W, cent, codes, bits, k, score)
+            want = []
+            for i in live:
+                order = sorted(range(d_out), key=lambda o: (-float(key[i, o]), o))
+                want += [i * d_out + o for o in sorted(order[:k])]
+            assert list(idx) == want                                   # ascending as a whole, too
+            assert np.array_equal(val, W.reshape(-1)[idx].view(np.uint16))
+    with pytest.raises(ValueError):
+        orc.weight_outliers_per_channel(W, cent, codes, bits, d_out + 1)
+    # the count: 0.5 % of 200 outputs is exactly 1, 0.74 % rounds to 1, 0.75 % to 2
+    assert [orc.count_ppm(p, d_out) for p in (5000, 7400, 7500)] == [1, 1, 2]
+    # a single channel: the two scopes are the same selection
+    one = np.full(1, 3, np.uint8)
+    c1, k1 = orc.kmeans(W[:1], one, iters=4)
+    a, _ = orc.weight_outliers_per_channel(W[:1], c1, k1, one, 9)
+    b, _ = orc.weight_outliers(W[:1], c1, k1, one, 9)
+    assert np.array_equal(a, b)
+
+
+def test_per_channel_and_layer_scope_agree_when_outliers_are_spread_evenly(orc):
+    """With exactly k far entries planted in every channel (all larger than anything else in
+    the layer; magnitude score, so that the clustering plays no part), the layer-wide top
+    (k * d_in) of Sec. 3.2.2 and the per-channel top k are the same set; moving one planted
+    entry to another channel makes them differ in exactly the way the definitions say."""
+    rng = np.random.default_rng(114)
+    d_in, d_out, k = 6, 128, 3
+    W = rng.normal(0, 0.01, (d_in, d_out)).astype(np.float32)
+    spots = {i: sorted(rng.choice(d_out, k, replace=False)) for i in range(d_in)}
+    for i, os_ in spots.items():
+        for t, o in enumerate(os_):
+            W[i, o] = (1.0 + 0.01 * (i * k + t)) * (-1) ** t
+    bits = np.full(d_in, 2, np.uint8)
+    planted = sorted(i * d_out + o for i, os_ in spots.items() for o in os_)
+    a, _ = orc.weight_outliers_per_channel(W, None, None, bits, k, orc.SCORE_MAGNITUDE)
+    b, _ = orc.weight_outliers(W, None, None, bits, k * d_in, orc.SCORE_MAGNITUDE)
+    assert list(a) == planted and list(b) == planted
+    # channel 0 loses one far entry, channel 1 gains one
+    o_from = spots[0][0]
+    o_to = next(o for o in range(d_out) if o not in spots[1])
+    W2 = W.copy()
+    W2[0, o_from] = 0.0
+    W2[1, o_to] = 2.0
+    a2, _ = orc.weight_outliers_per_channel(W2, None, None, bits, k, orc.SCORE_MAGNITUDE)
+    b2, _ = orc.weight_outliers(W2, None, None, bits, k * d_in, orc.SCORE_MAGNITUDE)
+    per = lambda idx, i: sum(1 for x in idx if x // d_out == i)
+    assert [per(a2, i) for i in range(d_in)] == [k] * d_in            # the count per channel is fixed
+    assert per(b2, 1) == k + 1 and 1 * d_out + o_to in b2             # the layer-wide rule follows the values
+    assert 1 * d_out + o_to in a2 and per(b2, 0) + per(b2, 1) >= 2 * k - 1
+
+
 # ----------------------------------------------------------------------------- storage (Sec. 5.1, Fig. 4)
 
 def _unpack(row_words, b, d_out):
@@ -631,6 +696,16 @@ def test_act_stats_other_norms_match_numpy_and_chunking(orc):
     Y[7, 1] = 5.0
     s2, s1, si = (orc.act_stats_norm(Y, k)[1] for k in (0, 1, 2))
     assert s2[0] > s2[1] and s1[0] > s1[1] and si[1] > si[0]
+    # a channel that holds a NaN (or an infinity) comes out non-finite under every norm, also
+    # when the bad token arrives in an earlier chunk; the other channels are untouched
+    for bad in (np.nan, np.inf):
+        Z = Y.copy()
+        Z[3, 1] = bad
+        for norm in (0, 1, 2):
+            acc = orc.act_stats_norm(Z, norm)[0]
+            assert not np.isfinite(acc[1]) and acc[0] == orc.act_stats_norm(Y, norm)[0][0]
+            a1 = orc.act_stats_norm(Z[:50], norm)[0]
+            assert not np.isfinite(orc.act_stats_norm(Z[50:], norm, acc=a1)[0][1])
 
 
 # ----------------------------------------------------------------------------- App. A.2: uniform quantizer
@@ -800,6 +875,97 @@ def test_lut4_costs_little_error_on_a_quantized_layer(orc):
     cent2, codes2 = orc.kmeans(W, bits2, iters=10)
     e_2bit = orc.dequant_error(W, cent2, codes2, bits2)[1][1]
     assert e16 <= e4 < e_2bit
+
+
+def _heavy_tailed_quantized_layer(orc, d_in=48, d_out=1024, seed=6):
+    """A layer in the image of the synthetic workloads (narrow Gaussian bulk, 0.5 % of the entries
+    from a heavy tail), widths 2..4, quantized by the oracle."""
+    r = np.random.default_rng(seed)
+    W = r.normal(0, 0.02, (d_in, d_out))
+    tail = r.random(W.shape) < 0.005
+    W[tail] = 0.1 * r.standard_t(3, size=int(tail.sum()))
+    W = W.astype(np.float16)
+    bits = r.choice(np.array([2, 3, 4], np.uint8), d_in)
+    cent, codes = orc.kmeans(W, bits, iters=20)
+    return W, bits, cent, codes
+
+
+def test_lut4_codebook_is_a_16_level_table_per_layer(orc):
+    """Sec. 5.1 / Tab. 7, the storage side: after the call every table entry of the layer is one
+    of at most 16 FP16 values (4 bits per entry, nothing per channel: the printed (1*4 + 8*4)/4096
+    for a 3-bit channel of 4096 outputs, below 0.01 bit per weight), codes4 names it, unused
+    slots and FP16 channels stay +infinity."""
+    W, bits, cent, codes = _heavy_tailed_quantized_layer(orc)
+    bits[5] = orc.PROTECTED
+    cent[5] = np.inf
+    codes4, table, cq = orc.lut4_codebook(cent, bits)
+    K = np.where(bits <= 4, 1 << np.minimum(bits, 4).astype(int), 0)
+    used = np.arange(16)[None, :] < K[:, None]
+    assert np.array_equal(np.isfinite(cq), used) and not codes4[~used].any()
+    table16 = table.astype(np.float16).astype(np.float32)                 # the stored FP16 table
+    assert np.array_equal(cq[used], table16[codes4[used]])
+    assert len(np.unique(cq[used])) <= 16
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "sec5_1_storage_overhead.txt")) if not l.startswith("#")]
+    d, b, entry_bits, kind, printed = next(r for r in rows if r[2] == "4")
+    per_weight = (1 * 4 + (1 << int(b)) * int(entry_bits)) / int(d)
+    assert kind == "below" and per_weight < float(printed)
+    layer_table_bits = 16 * 16                                            # one FP16 table per layer
+    assert layer_table_bits / (int(d) * int(d)) < 1e-4                    # does not change the figure
+
+
+def test_lut4_codebook_is_lloyds_algorithm_on_the_fp16_centres(orc):
+    """The clustering side, against numpy: every code is the nearest table level in exact
+    arithmetic (ties to the smaller index); run to convergence, every level with members is
+    the mean of its members (Lloyd's fixed point); the squared error over the centres is at
+    least the optimum of the exact 1-D dynamic programme and reaches it on planted groups."""
+    r = np.random.default_rng(9)
+    cent = np.full((30, 16), np.inf, np.float32)
+    bits = r.choice(np.array([1, 2, 3, 16], np.uint8), 30)
+    for i, b in enumerate(bits):
+        if b <= 4:
+            cent[i, :1 << b] = np.sort(r.standard_t(3, 1 << b) * 0.03).astype(np.float32)
+    codes4, table, cq = orc.lut4_codebook(cent, bits, iters=200)
+    used = np.isfinite(cq)
+    v = cent[used].astype(np.float16).astype(np.float64)
+    c = codes4[used]
+    d = np.abs(v[:, None] - table.astype(np.float64)[None, :])
+    assert np.array_equal(c, d.argmin(1))                                 # argmin takes the first of equals
+    for j in range(16):
+        if (c == j).any():
+            assert table[j] == np.float32(v[c == j].mean())
+    sse = float(((v - table.astype(np.float64)[c]) ** 2).sum())
+    assert sse >= _optimal_sse(v, 16) * (1 - 1e-9) - 1e-18
+    # 16 well separated groups of equal size: the optimum, whatever the channel they sit in
+    centres = np.arange(16) * 1.0 - 7.5
+    vals = (centres[:, None] + r.normal(0, 1e-3, (16, 8))).astype(np.float16).astype(np.float32)
+    flat = r.permutation(vals.reshape(-1))
+    cent = flat.reshape(8, 16)
+    _, table, cq = orc.lut4_codebook(cent, np.full(8, 4, np.uint8), iters=10)
+    assert np.allclose(np.sort(table), vals.astype(np.float64).mean(1), rtol=0, atol=1e-6)
+    # a layer whose channels share one 16-level table keeps it exactly; no quantized channel: zeros
+    one = np.sort(r.normal(0, 0.05, 16)).astype(np.float16).astype(np.float32)
+    same = np.tile(one, (11, 1))
+    c4, table, cq = orc.lut4_codebook(same, np.full(11, 4, np.uint8))
+    assert np.array_equal(cq, same) and np.array_equal(table, one) and np.array_equal(c4, np.tile(np.arange(16), (11, 1)))
+    c4, table, cq = orc.lut4_codebook(same, np.full(11, 16, np.uint8))
+    assert not table.any() and not c4.any() and np.all(np.isposinf(cq))
+
+
+def test_lut4_codebook_costs_what_tab7_says_where_the_uniform_grid_does_not(orc):
+    """Tab. 7: 4-bit centres cost at most 1.5 % (perplexity).  On a heavy-tailed layer the
+    per-layer table keeps the reconstruction error within a factor 1.5 of the FP16 tables' and
+    far below that of one bit less per weight, while the uniform 16-level grid - whose step is
+    set by the few far centres - multiplies it many times over."""
+    W, bits, cent, codes = _heavy_tailed_quantized_layer(orc)
+    e16 = orc.dequant_error(W, cent, codes, bits)[1][1]
+    e4 = orc.dequant_error(W, orc.lut4_codebook(cent, bits)[2], codes, bits)[1][1]
+    e4_uniform = orc.dequant_error(W, orc.lut4(cent, bits)[2], codes, bits)[1][1]
+    less = np.maximum(bits - 1, 1).astype(np.uint8)
+    cl, kl = orc.kmeans(W, less, iters=20)
+    e_less = orc.dequant_error(W, cl, kl, less)[1][1]
+    assert e16 * (1 - 1e-3) <= e4 <= 1.5 * e16
+    assert e4 < e_less
+    assert e4_uniform > 10 * e16 and e4_uniform > 10 * e4
 
 
 # ------------------------------------------------------------------ K-means from given levels (variant)
