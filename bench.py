@@ -7,9 +7,11 @@ A step is one pass of the whole path over one decoder block (or layer) of synthe
 input already resident in HBM: activation statistics for every distinct input, then for
 each linear layer the orientation copy, O_act, Algorithm 1, preliminary k-means, O_q,
 final k-means, packing and the reconstruction error.  Prints ONE JSON line:
-Mparams/s, the roofline figures of the dominant kernel (k-means, measured with events
-on the launch stream inside the timed steps) and the CPU oracle timed on a bounded
-sample of the same workload.
+Mparams/s, the roofline figures of the dominant kernel (k-means) and of the
+memory-bound kernels - each kernel bracketed by events right around its launch, on its
+launch stream, in steps that run on one stream so that no other launch shares the GPU,
+and again inside the timed steps - and the CPU oracle timed on a bounded sample of the
+same workload.
 """
 import argparse
 import json
@@ -20,15 +22,20 @@ import time
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-# MI355X: 256 compute units x 64 lanes x 2.4 GHz, one plain fp32 result (compare, add,
-# select) per lane and clock.  The datasheet's 157.3 TFLOP/s counts an FMA as two and a
-# packed pair as two more; a compare is neither.
-ALU_PEAK_TFLOPS = 256 * 64 * 2.4e9 / 1e12
+# MI355X's published fp32 vector peak: 256 compute units x 4 SIMDs x 16 lanes x 2.4 GHz x 2 (a
+# fused multiply-add counts as two) x 2 (two packed pairs per lane) = 157.3 TFLOP/s.  The
+# k-means figure is quoted against it.  Compares, adds and selects are neither fused nor packed:
+# one result per lane and clock, 256 x 64 x 2.4e9 = 39.3 T results/s, is the rate at which vector
+# instructions can issue at all (the clock is the data sheet's, not measured).
+FP32_PEAK_TFLOPS = 157.3
+ISSUE_PEAK_TOPS = 256 * 64 * 2.4e9 / 1e12
 HBM_PEAK_GBS = 8000.0
-# HBM bytes per k-means launch (mean over the launches of a step), from rocprofv3 --pmc
-# FETCH_SIZE / WRITE_SIZE runs scaled by a plain copy of known size; bench.py cannot collect
-# counters itself.  The summary of those runs is kept with the other profiles.
+# Constants taken from the kept rocprofv3 --pmc summaries (bench.py cannot collect counters):
+# mean HBM bytes per k-means launch (FETCH_SIZE + WRITE_SIZE scaled by a plain copy of known
+# size) and mean vector-ALU instructions per k-means launch (SQ_INSTS_VALU, per wavefront).
 KMEANS_TRAFFIC_BYTES = {"block70b": 504.1e6}
+KMEANS_VALU_WAVE_INSTS_PER_STEP = {"block70b": 2.45e9}     # 14 launches
+KMEANS_COUNTERS_FILE = "profiles/kmeans_bucket_block70b_counters.txt"
 
 
 def credited_kmeans_flops(result, iters):
@@ -42,25 +49,32 @@ def credited_kmeans_flops(result, iters):
 
 
 def cpu_baseline(wl, weights, acts):
-    """The oracle, as it stands, on a bounded sample: the first layer cut to as many input
-    channels as keep the run to roughly 10-30 s, and 2048 calibration tokens."""
-    import numpy as np
+    """The oracle, as it stands, on a bounded sample of the workload: the first layer cut to a
+    few thousand input channels, and for a block also a slice of its widest layer (the longest
+    channels, which hold most of the block's weights), 2048 calibration tokens each; sized to
+    keep the run to roughly 10-30 s."""
     import oracle
     oracle.build()
-    layer = wl.layers[0]
-    target_params = 67_200_000 if len(wl.layers) > 1 else 16_800_000
-    ch = max(8, min(layer.d_in, target_params // layer.d_out))
-    tok = min(2048, wl.x_shapes[layer.x_key][0])
-    W = weights[layer.name][:, :ch].t().contiguous().cpu().numpy()          # [ch, d_out]
-    X = acts[layer.x_key][:tok, :ch].contiguous().cpu().numpy()
-    t0 = time.perf_counter()
-    oracle.quantize_layer(W, X, wl.bit_set, wl.avg_bits, wl.rho_act_ppm, wl.rho_q_ppm, wl.iters)
-    dt = time.perf_counter() - t0
-    return {"value": ch * layer.d_out / dt / 1e6, "unit": "Mparams/s", "cores": oracle.num_threads(),
+    picks = [(wl.layers[0], 16_800_000)]
+    if len(wl.layers) > 1:
+        widest = max(wl.layers, key=lambda l: l.d_out)
+        if widest is not wl.layers[0]:
+            picks.append((widest, 34_000_000))
+    total, dt, what = 0, 0.0, []
+    for layer, target in picks:
+        ch = max(8, min(layer.d_in, target // layer.d_out))
+        tok = min(2048, wl.x_shapes[layer.x_key][0])
+        W = weights[layer.name][:, :ch].t().contiguous().cpu().numpy()          # [ch, d_out]
+        X = acts[layer.x_key][:tok, :ch].contiguous().cpu().numpy()
+        t0 = time.perf_counter()
+        oracle.quantize_layer(W, X, wl.bit_set, wl.avg_bits, wl.rho_act_ppm, wl.rho_q_ppm, wl.iters)
+        dt += time.perf_counter() - t0
+        total += ch * layer.d_out
+        what.append(f"{layer.name} cut to its first {ch} of {layer.d_in} input channels ({ch}x{layer.d_out} "
+                    f"weights, {tok} of {wl.x_shapes[layer.x_key][0]} tokens)")
+    return {"value": total / dt / 1e6, "unit": "Mparams/s", "cores": oracle.num_threads(),
             "kind": "oracle", "seconds": round(dt, 2),
-            "sample": f"{layer.name} cut to its first {ch} of {layer.d_in} input channels "
-                      f"({ch}x{layer.d_out} weights), {tok} of {wl.x_shapes[layer.x_key][0]} tokens, "
-                      f"whole path incl. both k-means passes"}
+            "sample": "; ".join(what) + "; whole path incl. both k-means passes"}
 
 
 def deployed_matvec(P, B, torch, out, layers, wl, acts, reps):
@@ -182,26 +196,29 @@ def retarget(P, B, torch, out, layers, wl, reps):
 
 
 def lut4_variant(P, B, torch, out, layers, wl, reps):
-    """The tables of the block just quantized on one 16-level grid per layer (Sec. 5.1 / Tab. 7),
-    the stored format written again, and the reconstruction error with them."""
+    """The tables of the block just quantized held in 4 bits per entry (Sec. 5.1 / Tab. 7): codes
+    into one 16-level table per layer found by K-means over the layer's centres, the stored format
+    written again, and the reconstruction error with them; the uniform 16-level grid beside it."""
     dev = next(iter(out.values())).codes.device
     ws = B.Workspace(dev)
 
-    def block():
-        return [P.tables_in_4_bits(out[n], ws, with_error=True)[2] for n, _ in layers]
+    def block(mode):
+        return [P.tables_in_4_bits(out[n], ws, with_error=True, mode=mode, iters=wl.iters)[2] for n, _ in layers]
 
-    block()
+    block(B.LUT4_CODEBOOK)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(reps):
-        qs = block()
+        qs = block(B.LUT4_CODEBOOK)
     torch.cuda.synchronize()
     dt = (time.perf_counter() - t0) / reps
     e16 = sum(float(out[n].err_total[0]) for n, _ in layers)
     e4 = sum(float(q.err_total[0]) for q in qs)
-    return {"what": "look-up tables in 4 bits (one uniform grid per layer): tables, stored format and error of "
-                    "all layers", "ms_per_block": dt * 1e3,
-            "weighted_error_vs_fp16_tables": e4 / e16 if e16 > 0 else None}
+    e4u = sum(float(q.err_total[0]) for q in block(B.LUT4_UNIFORM))
+    return {"what": "look-up tables in 4 bits (codes into one 16-level table per layer, K-means over the layer's "
+                    "centres): tables, stored format and error of all layers", "ms_per_block": dt * 1e3,
+            "weighted_error_vs_fp16_tables": e4 / e16 if e16 > 0 else None,
+            "weighted_error_vs_fp16_tables_uniform_grid": e4u / e16 if e16 > 0 else None}
 
 
 def continued_final_pass(P, torch, step_variant, out, layers, wl, rounds, reps, n_streams, dev):
@@ -246,7 +263,7 @@ def main():
                     help="streams the independent layers of a block are shared out over (default 3)")
     ap.add_argument("--serial-steps", type=int, default=2,
                     help="extra untimed steps on one stream for the per-stage and per-kernel figures "
-                         "that overlap would blur (0: skip)")
+                         "that overlap would blur (at least 1)")
     ap.add_argument("--deploy-reps", type=int, default=20,
                     help="repetitions of the one-token product with the deployed block (Fig. 4), reported "
                          "beside the headline figure; 0: skip")
@@ -298,7 +315,7 @@ def main():
     # The timed region: K steps enqueued one after the other, as when a model is quantized block
     # after block; with several streams the queues of one step run on into the next and the
     # streams are joined once, before the closing synchronisation.
-    timer = P.StageTimer()
+    timer = P.StageTimer(kernels=True)
     t0 = time.perf_counter()
     for _ in range(args.steps):
         out = step(timer, join=False)
@@ -323,23 +340,72 @@ def main():
     assert status.item() == 0, "non-finite input flagged"
 
     stages = timer.totals()
-    serial = None
-    if args.streams > 1 and args.serial_steps > 0:     # one stream: launches do not share the GPU
-        ws1 = ws[0]
-        t1 = P.StageTimer()
-        for _ in range(args.serial_steps):
-            o1 = P.quantize_block(weights, acts, layers, wl.bit_set, wl.avg_bits, wl.rho_act_ppm,
-                                  wl.rho_q_ppm, wl.iters, ws1, with_error=True, status=status, timer=t1)
-            del o1
-        serial = t1.totals()
+    kern_timed = timer.kernel_totals()
+    # One stream: no other launch shares the GPU.  These steps give the per-kernel durations the
+    # roofline figures are quoted on (they are what a one-stream kernel trace shows).
+    ws1 = ws[0] if args.streams > 1 else ws
+    t1 = P.StageTimer(kernels=True)
+    n_serial = max(1, args.serial_steps)
+    for _ in range(n_serial):
+        o1 = P.quantize_block(weights, acts, layers, wl.bit_set, wl.avg_bits, wl.rho_act_ppm,
+                              wl.rho_q_ppm, wl.iters, ws1, with_error=True, status=status, timer=t1)
+        del o1
+    serial = t1.totals()
+    kern = t1.kernel_totals()
+
+    def per_step(table, name, steps):
+        n, ms = table.get(name, (0, 0.0))
+        return n // steps, ms / steps
+
+    # ---- k-means: the dominant kernel
     flops = sum(credited_kmeans_flops(r, wl.iters) for r in out.values()) * 2      # two passes per layer
-    n_km, ms_km = stages["kmeans"]
-    launches_per_step = n_km // args.steps
-    avg_launch_s = ms_km / 1e3 / n_km
-    achieved = flops / launches_per_step / avg_launch_s / 1e12
+    n_km = per_step(kern, "kmeans_prelim", n_serial)[0] + per_step(kern, "kmeans_final", n_serial)[0]
+    ms_km = per_step(kern, "kmeans_prelim", n_serial)[1] + per_step(kern, "kmeans_final", n_serial)[1]
+    avg_launch_s = ms_km / 1e3 / max(n_km, 1)
+    achieved = flops / max(n_km, 1) / avg_launch_s / 1e12
+    ms_km_timed = per_step(kern_timed, "kmeans_prelim", args.steps)[1] + per_step(kern_timed, "kmeans_final", args.steps)[1]
+    roofline = {"kernel": "kmeans_bucket_kernel", "bound": "alu", "achieved": achieved, "peak": FP32_PEAK_TFLOPS,
+                "unit": "TFLOP/s", "frac": achieved / FP32_PEAK_TFLOPS,
+                "traffic": KMEANS_TRAFFIC_BYTES.get(wl.name),
+                "what": "credited work (per weight and round K-1 compares + 2 accumulations, K-1 for the final "
+                        "coding: what a brute-force Lloyd executes) / mean duration of the kernel on one stream, "
+                        "against the published fp32 vector peak; the kernel reaches the same bits with fewer "
+                        "operations, see `executed`",
+                "launches_per_step": n_km, "avg_launch_ms": avg_launch_s * 1e3,
+                "credited_flop_per_launch": flops / max(n_km, 1),
+                "traffic_from": "constant: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE summary under profiles/",
+                "avg_launch_ms_in_timed_region": ms_km_timed / max(n_km, 1)}
+    valu = KMEANS_VALU_WAVE_INSTS_PER_STEP.get(wl.name)
+    if valu is not None:
+        lane_ops = valu * 64
+        roofline["executed"] = {
+            "what": "vector-ALU instructions the kernel issues (SQ_INSTS_VALU x 64 lanes, a constant from the "
+                    "kept counter summary) / the same duration, against one instruction per lane and clock",
+            "lane_ops_per_step": lane_ops, "achieved_Tops": lane_ops / (ms_km / 1e3) / 1e12,
+            "issue_peak_Tops": ISSUE_PEAK_TOPS, "frac_of_issue_peak": lane_ops / (ms_km / 1e3) / 1e12 / ISSUE_PEAK_TOPS,
+            "clock_assumed_GHz": 2.4, "from": KMEANS_COUNTERS_FILE,
+            "executed_over_credited": lane_ops / flops}
+
+    # ---- the memory-bound kernels: algorithmic bytes / kernel duration on one stream
     x_bytes = sum(acts[k].numel() * acts[k].element_size() for k in acts)
-    n_st, ms_st = (serial or stages)["act_stats"]
-    n_st_steps = args.serial_steps if serial is not None else args.steps
+    esz = 2 if wl.dtype == "f16" else 4
+    live = sum(sum(r.counts) * r.d_out for r in out.values())                       # weights outside O_act
+    pe_bytes = sum(r.d_in * r.d_out * (esz + 1) + sum(c * ((r.d_out * b + 31) // 32) * 4 for b, c in zip(r.bit_set, r.counts))
+                   for r in out.values())
+    hbm = {}
+    for kernel, stage, nbytes, what in (
+            ("act_stats_vec_kernel", "act_stats", x_bytes, "X read once"),
+            ("transpose16_vec_kernel", "transpose", 2 * esz * wl.params, "W read and written once"),
+            ("wsel_stage_kernel", "outlier_weights", live * (esz + 1), "weight and code of every candidate read once"),
+            ("pack_error_kernel", "pack_with_error", pe_bytes, "weight and code read once, packed words written")):
+        n_k, ms_k = per_step(kern, stage, n_serial)
+        if n_k == 0 or ms_k <= 0:
+            continue
+        gbs = nbytes / (ms_k / 1e3) / 1e9
+        hbm[kernel] = {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS,
+                       "algorithmic_bytes_per_step": nbytes, "what": what, "launches_per_step": n_k,
+                       "ms_per_step": ms_k, "ms_per_step_in_timed_region": per_step(kern_timed, stage, args.steps)[1],
+                       "entry_point_ms_per_step": per_step(serial, stage, n_serial)[1]}
     line = {
         "metric": "Mparams/s quantized (whole CMPQ path, both k-means passes) at the target average bits",
         "value": wl.params * args.steps / dt / 1e6,
@@ -354,28 +420,20 @@ def main():
                    "weights": wl.dtype, "bit_set": list(wl.bit_set), "avg_bits": wl.avg_bits,
                    "rho_act_ppm": wl.rho_act_ppm, "rho_q_ppm": wl.rho_q_ppm, "iters": wl.iters,
                    "tokens": {k: v[0] for k, v in wl.x_shapes.items()}},
-        "roofline": {"kernel": "kmeans_bucket_kernel", "bound": "alu", "achieved": achieved,
-                     "peak": ALU_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": achieved / ALU_PEAK_TFLOPS,
-                     "traffic": KMEANS_TRAFFIC_BYTES.get(wl.name), "launches_per_step": launches_per_step,
-                     "avg_launch_ms": avg_launch_s * 1e3, "credited_flop_per_launch": flops / launches_per_step},
+        "roofline": roofline,
+        "hbm_kernels": hbm,
         "stages_ms_per_step": {k: round(v[1] / args.steps, 4) for k, v in sorted(stages.items())},
         "streams": args.streams,
-        "act_stats_hbm": {"achieved_GBs": x_bytes * n_st_steps / (ms_st / 1e3) / 1e9, "peak_GBs": HBM_PEAK_GBS,
-                          "frac": x_bytes * n_st_steps / (ms_st / 1e3) / 1e9 / HBM_PEAK_GBS,
-                          "from": "serial steps" if serial is not None else "timed steps"},
+        "serial": {
+            "note": "same step on one stream, run after the timed region: launches do not overlap; the "
+                    "per-kernel figures above come from these steps",
+            "steps": n_serial,
+            "ms_per_step": round(sum(v[1] for v in serial.values()) / n_serial, 4),
+            "stages_ms_per_step": {k: round(v[1] / n_serial, 4) for k, v in sorted(serial.items())},
+            "kernels_ms_per_step": {k: round(v[1] / n_serial, 4) for k, v in sorted(kern.items())}},
     }
     if joined is not None:
         line["steps_joined_one_by_one"] = joined
-    if serial is not None:
-        n1, ms1 = serial["kmeans"]
-        line["serial"] = {
-            "note": "same step on one stream, run after the timed region: launches do not overlap",
-            "steps": args.serial_steps,
-            "ms_per_step": round(sum(v[1] for v in serial.values()) / args.serial_steps, 4),
-            "stages_ms_per_step": {k: round(v[1] / args.serial_steps, 4) for k, v in sorted(serial.items())},
-            "kmeans_avg_launch_ms": ms1 / n1,
-            "kmeans_frac_of_alu_peak": flops / launches_per_step / (ms1 / 1e3 / n1) / 1e12 / ALU_PEAK_TFLOPS,
-        }
     if args.deploy_reps > 0:
         line["deployed_matvec"] = deployed_matvec(P, B, torch, out, layers, wl, acts, args.deploy_reps)
     if args.retarget_reps > 0:

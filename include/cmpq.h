@@ -18,7 +18,8 @@
  *   - returns CMPQ_OK (0) or a negative CMPQ_E* code; cmpq_strerror names it.
  *     Argument errors are detected on the host before anything is enqueued.
  *   - every data pointer is a DEVICE pointer owned by the caller unless the
- *     comment says "host".  The library keeps nothing between calls and
+ *     comment says "host".  The library keeps nothing between calls (the one
+ *     exception says so: cmpq_time_kernel) and
  *     allocates no device memory: scratch comes from the caller's workspace
  *     `ws` of `ws_bytes` bytes (256-byte aligned), at least
  *     cmpq_workspace_bytes(op, d_in, d_out, n) large, else CMPQ_EWORKSPACE.
@@ -66,12 +67,16 @@ extern "C" {
 #define CMPQ_OP_OUTLIERS_BY_COLUMN 7 /* n = entries of O_q                        */
 #define CMPQ_OP_LUT_MATVEC 8       /* n = tokens in the call                     */
 #define CMPQ_OP_PACK_WITH_ERROR 9  /* n ignored                                  */
+#define CMPQ_OP_LUT4 10            /* sizes ignored                              */
 
 /* `mode` / `score` of cmpq_extract_outliers */
 #define CMPQ_OUTLIER_CHANNELS 0
 #define CMPQ_OUTLIER_WEIGHTS 1
 #define CMPQ_SCORE_RESIDUAL 0  /* |W' - W'_q|: the criterion of Sec. 3.2.2           */
 #define CMPQ_SCORE_MAGNITUDE 1 /* |W'|: the magnitude rule Sec. 3.2.2 contrasts with */
+/* `scope` of cmpq_extract_outliers, weights mode */
+#define CMPQ_SCOPE_LAYER 0   /* the k largest scores of the whole layer: Sec. 3.2.2 */
+#define CMPQ_SCOPE_CHANNEL 1 /* the k largest scores of every channel (a variant)  */
 
 /* `norm` of cmpq_act_stats_norm */
 #define CMPQ_NORM_L2 0   /* sum of squares: the criterion of Sec. 3.2.1 */
@@ -82,7 +87,7 @@ extern "C" {
 #define CMPQ_INIT_QUANTILE 0
 #define CMPQ_INIT_GIVEN 1
 
-/* argument of cmpq_set_kmeans_algorithm */
+/* `algorithm` of cmpq_kmeans_job */
 #define CMPQ_KMEANS_HISTOGRAM 0 /* rounds read cumulative tables of the channel (default)   */
 #define CMPQ_KMEANS_DIRECT 1    /* rounds revisit every weight: K-1 compares, 2 accumulations */
 
@@ -157,22 +162,32 @@ int cmpq_allocate_bits(const float *sumsq, int64_t d_in, const uint8_t *chan_mas
  *
  * mode CMPQ_OUTLIER_CHANNELS (O_act): keys are sumsq[d_in].
  *   idx_out [k] int32 channel indices; chan_mask_out [d_in] (nullable) 1 = selected.
- *   W, centroids, codes, bits, val_out are ignored.  k <= d_in.
+ *   scope, W, centroids, codes, bits, val_out are ignored.  k > d_in: CMPQ_ECOUNT.
  *
  * mode CMPQ_OUTLIER_WEIGHTS (O_q): candidates are the entries of channels with bits in
  *   1..4 (W' = W - O_act).  Key = fp32 |w - centroids[i][codes[i,o]]| for
  *   CMPQ_SCORE_RESIDUAL (needs centroids [d_in,16] and codes [d_in,d_out] from a first
- *   cmpq_kmeans_quantize), or fp32 |w| for CMPQ_SCORE_MAGNITUDE.  The selection is over
- *   the whole layer.  idx_out [k] int32 linear indices i*d_out+o; val_out [k] (nullable)
- *   the weights as FP16 bit patterns.  k above the number of candidates: CMPQ_ECOUNT.
+ *   cmpq_kmeans_quantize), or fp32 |w| for CMPQ_SCORE_MAGNITUDE.
+ *   scope CMPQ_SCOPE_LAYER (the paper's rule): the k largest keys of the whole layer.
+ *     idx_out [k] int32 linear indices i*d_out+o, ascending; val_out [k] (nullable) the
+ *     weights as FP16 bit patterns.  k > d_in*d_out: CMPQ_ECOUNT.  The number of candidates
+ *     depends on `bits`, which is device data: when k exceeds it, every candidate is
+ *     returned and the rest of idx_out holds -1 (val_out there is left as it was).
+ *   scope CMPQ_SCOPE_CHANNEL (a variant: the same count in every channel, so that no
+ *     channel's slice of the sparse list is longer than another's): the k largest keys of
+ *     EACH channel with bits in 1..4, same order and tie rule inside the channel (equal keys
+ *     by smaller output index).  idx_out / val_out hold k entries per such channel, the
+ *     channels in ascending order, i.e. [k * n_live] ascending linear indices with n_live =
+ *     number of channels with bits in 1..4 (the sum of cmpq_allocate_bits' counts).
+ *     k > d_out: CMPQ_ECOUNT.
  *   sumsq and chan_mask_out are ignored.
- * Workspace: CMPQ_OP_OUTLIER_CHANNELS / CMPQ_OP_OUTLIER_WEIGHTS.
+ * Workspace: CMPQ_OP_OUTLIER_CHANNELS / CMPQ_OP_OUTLIER_WEIGHTS (n = k).
  */
-int cmpq_extract_outliers(int mode, int score, const float *sumsq, const void *W, int dtype,
-                          int64_t d_in, int64_t d_out, int64_t ldw, const float *centroids,
-                          const uint8_t *codes, const uint8_t *bits, int64_t k, int32_t *idx_out,
-                          uint16_t *val_out, uint8_t *chan_mask_out, void *ws, size_t ws_bytes,
-                          void *stream);
+int cmpq_extract_outliers(int mode, int score, int scope, const float *sumsq, const void *W,
+                          int dtype, int64_t d_in, int64_t d_out, int64_t ldw,
+                          const float *centroids, const uint8_t *codes, const uint8_t *bits,
+                          int64_t k, int32_t *idx_out, uint16_t *val_out, uint8_t *chan_mask_out,
+                          void *ws, size_t ws_bytes, void *stream);
 
 /*
  * Sec. 3.2.1, channel-wise non-uniform quantization: for every channel with bits[i] in
@@ -228,12 +243,35 @@ int cmpq_select_by_width(const uint8_t *bits, int64_t d_in, int64_t d_out, const
                          void *stream);
 
 /*
- * Process-wide choice between the two implementations of the Lloyd rounds of Sec. 3.2.1
- * for fp16 weights with unit importance.  Both produce identical levels and codes; the
- * direct one exists for measurements against the plain ALU roofline.  Host only; takes
- * effect at the next cmpq_kmeans_quantize call.  Returns CMPQ_EINVAL for another value.
+ * cmpq_kmeans_quantize with every choice spelled out per call: a plain C structure of
+ * pointers and sizes.  The fields up to `status` mean what the arguments of the same name
+ * of cmpq_kmeans_quantize mean; that call is this one with algorithm = CMPQ_KMEANS_HISTOGRAM.
+ *   algorithm   which implementation runs the Lloyd rounds of Sec. 3.2.1 for fp16 weights with
+ *               unit importance.  Both give identical levels and codes: CMPQ_KMEANS_HISTOGRAM
+ *               reads cumulative tables of the channel, CMPQ_KMEANS_DIRECT revisits every
+ *               weight (K-1 compares, 2 accumulations; kept as the independent second
+ *               implementation).  Other inputs (fp32, elem_weight, rows that are not a whole
+ *               number of 4 entries) run on the general kernel whatever is named here, and so
+ *               does init = CMPQ_INIT_GIVEN with CMPQ_KMEANS_DIRECT (on the histogram kernel).
+ * The library reads the structure during the call only.  Errors and workspace as
+ * cmpq_kmeans_quantize; CMPQ_EINVAL for a null job or an unknown algorithm.
  */
-int cmpq_set_kmeans_algorithm(int algorithm);
+typedef struct cmpq_kmeans_job {
+    const void *W; /* device, [d_in, d_out] */
+    int dtype;
+    int64_t d_in, d_out, ldw;
+    const uint8_t *bits;     /* device, [d_in] */
+    const int32_t *out_idx;  /* device, [n_out], nullable */
+    int64_t n_out;
+    const float *elem_weight; /* device, nullable */
+    int iters, init;
+    float *centroids; /* device, [d_in, 16] */
+    uint8_t *codes;   /* device, [d_in, d_out] */
+    int32_t *status;  /* device, nullable */
+    int algorithm;
+} cmpq_kmeans_job;
+
+int cmpq_kmeans_quantize_job(const cmpq_kmeans_job *job, void *ws, size_t ws_bytes, void *stream);
 
 /*
  * Sec. 5.1 / Fig. 4, the stored format: one code matrix per width.  For j < n_set and
@@ -368,22 +406,34 @@ int cmpq_lut_matvec(const void *X, int64_t m, int64_t d_in, int64_t ldx, int64_t
 
 /*
  * Sec. 5.1 / Tab. 7: the look-up tables held in 4 bits, (1*4 + 8*4)/4096 bits of overhead per
- * weight for a 3-bit channel.  The paper does not say how the centres are quantized and the
- * figure leaves no room for a scale per channel; the reading taken is one uniform 16-level
- * grid per layer (the quantizer of Sec. 3 with N = 4 over all centres of the layer):
- *     lo = min, hi = max over the first 2^bits[i] levels of every channel with bits in 1..4,
- *     Delta = (hi - lo) / 15,  code = Clamp(round((c - lo) / Delta), 0, 15)   (fp32, ties to even),
- *     c_q = lo + code * Delta, formed exactly and rounded once to fp32;  Delta = 0: code 0.
- *   centroids   [d_in, 16] fp32 in (from cmpq_kmeans_quantize), bits [d_in] u8.
- *   codes4      [d_in, 16] u8 out: the 4-bit code of every table entry (0 in unused slots).
- *   range       [2] fp32 out, device: lo and Delta (0, 0 when no channel is quantized).
- *   centroids_q [d_in, 16] fp32 out: the rebuilt tables (+infinity in unused slots and on
- *               channels of O_act), to be handed to cmpq_pack, cmpq_dequant_error and the
- *               deployed product in place of `centroids`.
- * No workspace.  d_in <= 2^27.
+ * weight for a 3-bit channel.  The paper does not say how the centres are quantized; the
+ * figure leaves 4 bits per table entry and nothing per channel.
+ *   mode CMPQ_LUT4_CODEBOOK (the reading taken): the 4 bits index one 16-entry table per
+ *     layer, found by the non-uniform quantizer of Sec. 3 (K-means with K = 16, as
+ *     cmpq_kmeans_quantize runs it: quantile start, `iters` rounds, nearest level in exact
+ *     arithmetic with ties to the smaller index, fp64 means rounded once to fp32) over all
+ *     centres of the layer as the stored format holds them, v = FP16(centroids[i][j]) for
+ *     j < 2^bits[i] and bits[i] in 1..4 (-0 as +0; a non-finite centre takes no part).
+ *       table       [16] fp32 out, device: the levels (all 0 when no channel is quantized);
+ *       codes4      [d_in, 16] u8 out: the level of every table entry (0 in unused slots);
+ *       centroids_q [d_in, 16] fp32 out: FP16(table[codes4]) - what a stored FP16 table of
+ *                   the layer gives back; +infinity in unused slots and on channels of O_act.
+ *     Workspace: CMPQ_OP_LUT4.
+ *   mode CMPQ_LUT4_UNIFORM (an alternative): one uniform 16-level grid per layer, the uniform
+ *     quantizer of Sec. 3 with N = 4 over all centres (fp32 values, not rounded to FP16):
+ *       lo = min, hi = max, Delta = (hi - lo) / 15, code = Clamp(round((c - lo) / Delta), 0, 15)
+ *       in fp32 with ties to even, c_q = lo + code * Delta formed exactly and rounded once to
+ *       fp32; Delta = 0: code 0.  table[0] = lo, table[1] = Delta (0, 0 when no channel is
+ *       quantized), the other entries are left alone.  `iters` is ignored; no workspace.
+ * centroids [d_in, 16] fp32 in (from cmpq_kmeans_quantize), bits [d_in] u8.  centroids_q goes
+ * to cmpq_pack, cmpq_dequant_error and the deployed product in place of `centroids`.
+ * d_in <= 2^27.
  */
-int cmpq_lut4_quantize(const float *centroids, const uint8_t *bits, int64_t d_in, uint8_t *codes4,
-                       float *range, float *centroids_q, void *stream);
+#define CMPQ_LUT4_CODEBOOK 0
+#define CMPQ_LUT4_UNIFORM 1
+int cmpq_lut4_quantize(int mode, const float *centroids, const uint8_t *bits, int64_t d_in, int iters,
+                       uint8_t *codes4, float *table, float *centroids_q, void *ws, size_t ws_bytes,
+                       void *stream);
 
 /*
  * Several products in one pair of launches (Sec. 6 / Fig. 4 for the products that can run
@@ -419,6 +469,24 @@ typedef struct cmpq_deployed_layer {
 
 int cmpq_lut_matvec_group(const cmpq_deployed_layer *layers, int n_layers, int64_t m, void *ws,
                           size_t ws_bytes, void *stream);
+
+/*
+ * Measurement hook (for a benchmark that wants the duration of one kernel rather than of an
+ * entry point, which may launch several).  Arms the CALLING THREAD: the next launch of the
+ * named kernel from this thread records event_begin (a hipEvent_t passed as void*) on the
+ * launch stream right before the kernel and event_end right after it, and the hook is
+ * disarmed again.  Null events disarm.  The elapsed time between the two events, once both
+ * have completed, is the kernel's duration on that stream (plus what else shares the GPU
+ * with it when other streams are busy).  This is the one piece of state the library keeps,
+ * and it is per thread; it changes no result.  CMPQ_EINVAL for an unknown kernel.
+ */
+#define CMPQ_KERNEL_ACT_STATS 0     /* the streaming pass of cmpq_act_stats over X (aligned input)     */
+#define CMPQ_KERNEL_TRANSPOSE 1     /* cmpq_transpose, fp16 with aligned rows                           */
+#define CMPQ_KERNEL_KMEANS 2        /* the k-means kernel of cmpq_kmeans_quantize (histogram algorithm) */
+#define CMPQ_KERNEL_OUTLIER_STAGE 3 /* the one pass over the layer of the layer-wide O_q selection      */
+#define CMPQ_KERNEL_PACK_ERROR 4    /* the one-pass kernel of cmpq_pack_with_error                      */
+#define CMPQ_KERNEL_COUNT 5
+int cmpq_time_kernel(int kernel, void *event_begin, void *event_end);
 
 #ifdef __cplusplus
 }

@@ -19,11 +19,14 @@ F16, F32 = 0, 1
 KMAX = 16
 PROTECTED = 16
 STATUS_NONFINITE = 1
-OP_OUTLIERS_BY_COLUMN, OP_LUT_MATVEC, OP_PACK_WITH_ERROR = 7, 8, 9
+OP_OUTLIERS_BY_COLUMN, OP_LUT_MATVEC, OP_PACK_WITH_ERROR, OP_LUT4 = 7, 8, 9, 10
 OP_ACT_STATS, OP_ALLOCATE_BITS, OP_OUTLIER_CHANNELS, OP_OUTLIER_WEIGHTS, OP_KMEANS, OP_PACK, \
     OP_DEQUANT_ERROR = range(7)
 OUTLIER_CHANNELS, OUTLIER_WEIGHTS = 0, 1
 SCORE_RESIDUAL, SCORE_MAGNITUDE = 0, 1
+SCOPE_LAYER, SCOPE_CHANNEL = 0, 1
+LUT4_CODEBOOK, LUT4_UNIFORM = 0, 1
+KERNEL_ACT_STATS, KERNEL_TRANSPOSE, KERNEL_KMEANS, KERNEL_OUTLIER_STAGE, KERNEL_PACK_ERROR = range(5)
 INIT_QUANTILE = 0
 INIT_GIVEN = 1
 KMEANS_HISTOGRAM, KMEANS_DIRECT = 0, 1
@@ -31,10 +34,10 @@ NORM_L2, NORM_L1, NORM_LINF = 0, 1, 2
 
 EXPORTS = ("cmpq_workspace_bytes", "cmpq_strerror", "cmpq_count_ppm", "cmpq_act_stats",
            "cmpq_transpose", "cmpq_allocate_bits", "cmpq_extract_outliers",
-           "cmpq_kmeans_quantize", "cmpq_pack", "cmpq_dequant_error", "cmpq_set_kmeans_algorithm",
+           "cmpq_kmeans_quantize", "cmpq_pack", "cmpq_dequant_error", "cmpq_kmeans_quantize_job",
            "cmpq_gather_channels", "cmpq_outliers_by_column", "cmpq_lut_matvec", "cmpq_act_stats_norm",
            "cmpq_rtn_quantize", "cmpq_select_by_width", "cmpq_lut_matvec_group", "cmpq_lut4_quantize",
-           "cmpq_pack_with_error")
+           "cmpq_pack_with_error", "cmpq_time_kernel")
 
 _i64, _i32, _int, _vp, _dbl, _sz = (ctypes.c_int64, ctypes.c_int32, ctypes.c_int, ctypes.c_void_p,
                                     ctypes.c_double, ctypes.c_size_t)
@@ -50,6 +53,13 @@ class DeployedLayer(ctypes.Structure):
                 ("counts_host", _vp), ("packed", _vp), ("chan_idx", _vp), ("lut", _vp), ("act_idx", _vp),
                 ("W_act", _vp), ("k_act", _i64), ("ld_act", _i64), ("colptr", _vp), ("row_idx", _vp),
                 ("delta", _vp), ("Y", _vp), ("ldy", _i64)]
+
+
+class KmeansJob(ctypes.Structure):
+    """`cmpq_kmeans_job` of the header, field for field."""
+    _fields_ = [("W", _vp), ("dtype", _int), ("d_in", _i64), ("d_out", _i64), ("ldw", _i64), ("bits", _vp),
+                ("out_idx", _vp), ("n_out", _i64), ("elem_weight", _vp), ("iters", _int), ("init", _int),
+                ("centroids", _vp), ("codes", _vp), ("status", _vp), ("algorithm", _int)]
 
 
 class CmpqError(RuntimeError):
@@ -75,7 +85,7 @@ def lib() -> ctypes.CDLL:
         L.cmpq_act_stats.argtypes = [_vp, _int, _i64, _i64, _i64, _vp, _vp, _int, _vp, _sz, _vp, _vp]
         L.cmpq_transpose.argtypes = [_vp, _int, _i64, _i64, _i64, _vp, _i64, _vp]
         L.cmpq_allocate_bits.argtypes = [_vp, _i64, _vp, _i64, _vp, _int, _dbl, _vp, _vp, _vp, _sz, _vp]
-        L.cmpq_extract_outliers.argtypes = [_int, _int, _vp, _vp, _int, _i64, _i64, _i64, _vp, _vp,
+        L.cmpq_extract_outliers.argtypes = [_int, _int, _int, _vp, _vp, _int, _i64, _i64, _i64, _vp, _vp,
                                             _vp, _i64, _vp, _vp, _vp, _vp, _sz, _vp]
         L.cmpq_kmeans_quantize.argtypes = [_vp, _int, _i64, _i64, _i64, _vp, _vp, _i64, _vp, _int,
                                            _int, _vp, _vp, _vp, _sz, _vp, _vp]
@@ -84,14 +94,15 @@ def lib() -> ctypes.CDLL:
                                          _vp, _vp, _vp, _sz, _vp]
         L.cmpq_pack_with_error.argtypes = [_vp, _int, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _int, _vp, _vp, _vp, _vp,
                                            _vp, _i64, _vp, _vp, _vp, _vp, _sz, _vp]
-        L.cmpq_set_kmeans_algorithm.argtypes = [_int]
+        L.cmpq_kmeans_quantize_job.argtypes = [ctypes.POINTER(KmeansJob), _vp, _sz, _vp]
+        L.cmpq_time_kernel.argtypes = [_int, _vp, _vp]
         L.cmpq_act_stats_norm.argtypes = [_vp, _int, _i64, _i64, _i64, _int, _vp, _vp, _int, _vp, _sz, _vp, _vp]
         L.cmpq_gather_channels.argtypes = [_vp, _int, _i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp]
         L.cmpq_outliers_by_column.argtypes = [_vp, _vp, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
         L.cmpq_lut_matvec.argtypes = [_vp, _i64, _i64, _i64, _i64, _vp, _int, _vp, _vp, _vp, _vp, _vp, _vp,
                                       _i64, _i64, _vp, _vp, _vp, _vp, _i64, _vp, _sz, _vp]
         L.cmpq_rtn_quantize.argtypes = [_vp, _int, _i64, _i64, _i64, _vp, _i64, _vp, _vp, _vp, _vp, _vp, _vp]
-        L.cmpq_lut4_quantize.argtypes = [_vp, _vp, _i64, _vp, _vp, _vp, _vp]
+        L.cmpq_lut4_quantize.argtypes = [_int, _vp, _vp, _i64, _int, _vp, _vp, _vp, _vp, _sz, _vp]
         L.cmpq_lut_matvec_group.argtypes = [_vp, _int, _i64, _vp, _sz, _vp]
         L.cmpq_select_by_width.argtypes = [_vp, _i64, _i64, _vp, _int, _vp, _vp, _vp, _vp, _vp]
         for name in EXPORTS[3:]:
@@ -108,8 +119,10 @@ def count_ppm(ppm: int, n: int) -> int:
     return int(lib().cmpq_count_ppm(int(ppm), int(n)))
 
 
-def set_kmeans_algorithm(algorithm: int) -> None:
-    _check(lib().cmpq_set_kmeans_algorithm(int(algorithm)), "cmpq_set_kmeans_algorithm")
+def time_kernel(kernel: int, event_begin: Optional[int], event_end: Optional[int]) -> None:
+    """Arms the calling thread: the next launch of `kernel` is bracketed by the two events
+    (raw hipEvent_t handles as integers); None disarms."""
+    _check(lib().cmpq_time_kernel(int(kernel), event_begin, event_end), "cmpq_time_kernel")
 
 
 def workspace_bytes(op: int, d_in: int, d_out: int = 0, n: int = 0) -> int:
@@ -196,7 +209,7 @@ def extract_channel_outliers(sumsq: torch.Tensor, k: int, idx_out: torch.Tensor,
                              chan_mask_out: Optional[torch.Tensor], ws: Workspace) -> None:
     d_in = sumsq.numel()
     buf = ws.get(workspace_bytes(OP_OUTLIER_CHANNELS, d_in, 0, k))
-    _check(lib().cmpq_extract_outliers(OUTLIER_CHANNELS, SCORE_RESIDUAL, _ptr(sumsq), None, F16, d_in, 0, 0,
+    _check(lib().cmpq_extract_outliers(OUTLIER_CHANNELS, SCORE_RESIDUAL, SCOPE_LAYER, _ptr(sumsq), None, F16, d_in, 0, 0,
                                        None, None, None, int(k), _ptr(idx_out), None, _ptr(chan_mask_out),
                                        _ptr(buf), buf.numel(), _stream()),
            "cmpq_extract_outliers(channels)")
@@ -204,10 +217,13 @@ def extract_channel_outliers(sumsq: torch.Tensor, k: int, idx_out: torch.Tensor,
 
 def extract_weight_outliers(W: torch.Tensor, centroids: Optional[torch.Tensor], codes: Optional[torch.Tensor],
                             bits: torch.Tensor, k: int, idx_out: torch.Tensor, val_out: Optional[torch.Tensor],
-                            ws: Workspace, score: int = SCORE_RESIDUAL) -> None:
+                            ws: Workspace, score: int = SCORE_RESIDUAL, scope: int = SCOPE_LAYER) -> None:
+    """O_q: the `k` largest scores of the layer (SCOPE_LAYER, Sec. 3.2.2) or of every channel
+    (SCOPE_CHANNEL: `idx_out` / `val_out` then hold k entries per quantized channel)."""
     d_in, d_out, ldw = _rows(W)
     buf = ws.get(workspace_bytes(OP_OUTLIER_WEIGHTS, d_in, d_out, k))
-    _check(lib().cmpq_extract_outliers(OUTLIER_WEIGHTS, int(score), None, _ptr(W), _dtype(W), d_in, d_out, ldw,
+    _check(lib().cmpq_extract_outliers(OUTLIER_WEIGHTS, int(score), int(scope), None, _ptr(W), _dtype(W), d_in,
+                                       d_out, ldw,
                                        _ptr(centroids), _ptr(codes), _ptr(bits), int(k), _ptr(idx_out),
                                        _ptr(val_out), None, _ptr(buf), buf.numel(), _stream()),
            "cmpq_extract_outliers(weights)")
@@ -216,13 +232,21 @@ def extract_weight_outliers(W: torch.Tensor, centroids: Optional[torch.Tensor], 
 def kmeans_quantize(W: torch.Tensor, bits: torch.Tensor, out_idx: Optional[torch.Tensor], n_out: int,
                     elem_weight: Optional[torch.Tensor], iters: int, centroids: torch.Tensor,
                     codes: torch.Tensor, ws: Workspace, status: Optional[torch.Tensor] = None,
-                    init: int = INIT_QUANTILE) -> None:
+                    init: int = INIT_QUANTILE, algorithm: Optional[int] = None) -> None:
+    """`cmpq_kmeans_quantize`; with `algorithm` given, `cmpq_kmeans_quantize_job` naming it."""
     d_in, d_out, ldw = _rows(W)
     buf = ws.get(workspace_bytes(OP_KMEANS, d_in, d_out))
-    _check(lib().cmpq_kmeans_quantize(_ptr(W), _dtype(W), d_in, d_out, ldw, _ptr(bits), _ptr(out_idx), int(n_out),
-                                      _ptr(elem_weight), int(iters), int(init), _ptr(centroids), _ptr(codes),
-                                      _ptr(buf), buf.numel(), _ptr(status), _stream()),
-           "cmpq_kmeans_quantize")
+    if algorithm is None:
+        _check(lib().cmpq_kmeans_quantize(_ptr(W), _dtype(W), d_in, d_out, ldw, _ptr(bits), _ptr(out_idx),
+                                          int(n_out), _ptr(elem_weight), int(iters), int(init), _ptr(centroids),
+                                          _ptr(codes), _ptr(buf), buf.numel(), _ptr(status), _stream()),
+               "cmpq_kmeans_quantize")
+        return
+    job = KmeansJob(_ptr(W), _dtype(W), d_in, d_out, ldw, _ptr(bits), _ptr(out_idx), int(n_out),
+                    _ptr(elem_weight), int(iters), int(init), _ptr(centroids), _ptr(codes), _ptr(status),
+                    int(algorithm))
+    _check(lib().cmpq_kmeans_quantize_job(ctypes.byref(job), _ptr(buf), buf.numel(), _stream()),
+           "cmpq_kmeans_quantize_job")
 
 
 def pack(codes: torch.Tensor, bits: torch.Tensor, centroids: torch.Tensor, bit_set: Sequence[int],
@@ -435,15 +459,18 @@ def select_by_width(bits: torch.Tensor, bit_set: Sequence[int], centroids_by_wid
            "cmpq_select_by_width")
 
 
-def lut4_quantize(centroids: torch.Tensor, bits: torch.Tensor, codes4: torch.Tensor, rng: torch.Tensor,
-                  centroids_q: torch.Tensor) -> None:
-    """Sec. 5.1 / Tab. 7: the tables of a layer on one uniform 16-level grid."""
+def lut4_quantize(centroids: torch.Tensor, bits: torch.Tensor, codes4: torch.Tensor, table: torch.Tensor,
+                  centroids_q: torch.Tensor, ws: Workspace, mode: int = LUT4_CODEBOOK, iters: int = 20) -> None:
+    """Sec. 5.1 / Tab. 7: the tables of a layer in 4 bits - codes into one 16-level table per layer
+    (LUT4_CODEBOOK; `table` receives the levels) or on one uniform grid (LUT4_UNIFORM; `table[0:2]`
+    receives minimum and step)."""
     d_in = centroids.shape[0]
     for t, dt in ((centroids, torch.float32), (centroids_q, torch.float32), (codes4, torch.uint8)):
         if tuple(t.shape) != (d_in, KMAX) or not t.is_contiguous() or t.dtype != dt:
             raise ValueError("tables are contiguous [d_in, 16]: fp32 levels, uint8 codes")
-    if rng.numel() != 2 or rng.dtype != torch.float32:
-        raise ValueError("range is fp32 [2]")
-    _check(lib().cmpq_lut4_quantize(_ptr(centroids), _ptr(bits), d_in, _ptr(codes4), _ptr(rng), _ptr(centroids_q),
-                                    _stream()),
+    if table.numel() != KMAX or table.dtype != torch.float32 or not table.is_contiguous():
+        raise ValueError("table is fp32 [16]")
+    buf = ws.get(workspace_bytes(OP_LUT4, d_in))
+    _check(lib().cmpq_lut4_quantize(int(mode), _ptr(centroids), _ptr(bits), d_in, int(iters), _ptr(codes4),
+                                    _ptr(table), _ptr(centroids_q), _ptr(buf), buf.numel(), _stream()),
            "cmpq_lut4_quantize")

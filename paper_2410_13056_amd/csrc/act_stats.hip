@@ -51,11 +51,14 @@ __device__ __forceinline__ double fold(double s, float x) {
     const double d = (double)x;
     if (NORM == CMPQ_NORM_L2) return fma(d, d, s);
     if (NORM == CMPQ_NORM_L1) return s + fabs(d);
-    return fmax(s, fabs(d));
+    // fmax drops a NaN operand; a channel that holds one must come out non-finite like under
+    // the other norms, so that the status flag is raised for it
+    return (d != d || s != s) ? s + d : fmax(s, fabs(d));
 }
 template <int NORM>
 __device__ __forceinline__ double combine(double a, double b) {
-    return NORM == CMPQ_NORM_LINF ? fmax(a, b) : a + b;
+    if (NORM != CMPQ_NORM_LINF) return a + b;
+    return (a != a || b != b) ? a + b : fmax(a, b);  // a NaN partial stays
 }
 
 // partial[split * d_in + col] = the statistic over the rows of this split of column col
@@ -182,12 +185,14 @@ int launch_act_stats(const void *X, int dtype, int64_t n, int64_t d_in, int64_t 
         const int64_t rps = cdiv(n, splits);
         dim3 grid((unsigned)col_blocks, (unsigned)splits);
         if (aligned) {
+            cmpq_timing_before(CMPQ_KERNEL_ACT_STATS, st);
             if (dtype == CMPQ_F16)
                 act_stats_vec_kernel<__half, NORM><<<grid, kThreads, 0, st>>>(
                     static_cast<const __half *>(X), n, d_in, ldx, rps, partial);
             else
                 act_stats_vec_kernel<float, NORM><<<grid, kThreads, 0, st>>>(
                     static_cast<const float *>(X), n, d_in, ldx, rps, partial);
+            cmpq_timing_after(CMPQ_KERNEL_ACT_STATS, st);
         } else {
             if (dtype == CMPQ_F16)
                 act_stats_any_kernel<__half, NORM><<<grid, kThreads, 0, st>>>(

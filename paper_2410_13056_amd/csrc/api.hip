@@ -13,6 +13,7 @@ size_t cmpq_ws_dequant_error(int64_t d_in);
 size_t cmpq_ws_outliers_by_column(int64_t d_out, int64_t n_out);
 size_t cmpq_ws_lut_matvec(int64_t d_in, int64_t d_out, int64_t m);
 size_t cmpq_ws_pack_with_error(int64_t d_in);
+size_t cmpq_ws_lut4();
 
 extern "C" size_t cmpq_workspace_bytes(int op, int64_t d_in, int64_t d_out, int64_t n) {
     if (d_in < 0 || d_out < 0 || n < 0) return 0;
@@ -27,6 +28,7 @@ extern "C" size_t cmpq_workspace_bytes(int op, int64_t d_in, int64_t d_out, int6
         case CMPQ_OP_OUTLIERS_BY_COLUMN: return cmpq_ws_outliers_by_column(d_out, n);
         case CMPQ_OP_LUT_MATVEC: return cmpq_ws_lut_matvec(d_in, d_out, n);
         case CMPQ_OP_PACK_WITH_ERROR: return cmpq_ws_pack_with_error(d_in);
+        case CMPQ_OP_LUT4: return cmpq_ws_lut4();
         default: return 0;
     }
 }
@@ -46,6 +48,39 @@ extern "C" const char *cmpq_strerror(int code) {
 
 extern "C" int64_t cmpq_count_ppm(int64_t ppm, int64_t n) {
     return (int64_t)(((unsigned __int128)ppm * (unsigned __int128)n + 500000u) / 1000000u);
+}
+
+namespace {
+
+struct ArmedTimer {
+    int kernel = -1;
+    hipEvent_t begin = nullptr, end = nullptr;
+};
+thread_local ArmedTimer g_timer;
+
+}  // namespace
+
+extern "C" int cmpq_time_kernel(int kernel, void *event_begin, void *event_end) {
+    if (kernel < 0 || kernel >= CMPQ_KERNEL_COUNT) return CMPQ_EINVAL;
+    if (!event_begin || !event_end) {
+        g_timer = ArmedTimer();
+        return CMPQ_OK;
+    }
+    g_timer.kernel = kernel;
+    g_timer.begin = static_cast<hipEvent_t>(event_begin);
+    g_timer.end = static_cast<hipEvent_t>(event_end);
+    return CMPQ_OK;
+}
+
+void cmpq_timing_before(int kernel, hipStream_t s) {
+    if (g_timer.kernel == kernel) (void)hipEventRecord(g_timer.begin, s);
+}
+
+void cmpq_timing_after(int kernel, hipStream_t s) {
+    if (g_timer.kernel == kernel) {
+        (void)hipEventRecord(g_timer.end, s);
+        g_timer = ArmedTimer();
+    }
 }
 
 namespace {
@@ -125,10 +160,12 @@ extern "C" int cmpq_transpose(const void *src, int dtype, int64_t rows, int64_t 
     const bool vec = dtype == CMPQ_F16 && rows % 4 == 0 && cols % 4 == 0 && ld_src % 4 == 0 &&
                      ld_dst % 4 == 0 && reinterpret_cast<uintptr_t>(src) % 8 == 0 &&
                      reinterpret_cast<uintptr_t>(dst) % 8 == 0;
-    if (vec)
+    if (vec) {
+        cmpq_timing_before(CMPQ_KERNEL_TRANSPOSE, st);
         transpose16_vec_kernel<<<grid, 256, 0, st>>>(static_cast<const uint16_t *>(src), rows, cols,
                                                      ld_src, static_cast<uint16_t *>(dst), ld_dst);
-    else if (dtype == CMPQ_F16)
+        cmpq_timing_after(CMPQ_KERNEL_TRANSPOSE, st);
+    } else if (dtype == CMPQ_F16)
         transpose_kernel<uint16_t><<<grid, 256, 0, st>>>(static_cast<const uint16_t *>(src), rows,
                                                          cols, ld_src, static_cast<uint16_t *>(dst),
                                                          ld_dst);

@@ -16,6 +16,11 @@
         if (hipGetLastError() != hipSuccess) return CMPQ_EHIP; \
     } while (0)
 
+// Measurement hook of cmpq_time_kernel: brackets a launch of `kernel` with the events the
+// calling thread armed, if any.
+void cmpq_timing_before(int kernel, hipStream_t s);
+void cmpq_timing_after(int kernel, hipStream_t s);
+
 static inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 __device__ __forceinline__ size_t align_up_dev(size_t x) { return (x + 15) & ~(size_t)15; }

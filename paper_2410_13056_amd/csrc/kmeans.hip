@@ -370,17 +370,63 @@ int launch_kmeans(const KmArgs &a, hipStream_t s) {
 
 }  // namespace
 
-static int g_kmeans_algorithm = CMPQ_KMEANS_HISTOGRAM;
-
-extern "C" int cmpq_set_kmeans_algorithm(int algorithm) {
-    if (algorithm != CMPQ_KMEANS_HISTOGRAM && algorithm != CMPQ_KMEANS_DIRECT) return CMPQ_EINVAL;
-    g_kmeans_algorithm = algorithm;
-    return CMPQ_OK;
-}
-
 size_t cmpq_ws_kmeans(int64_t d_in, int64_t) {
     // one byte per channel (deferred flags) | d_in + 1 slice offsets of out_idx
     return align_up((size_t)(d_in > 0 ? d_in : 1), 256) + align_up((size_t)(d_in + 1) * sizeof(int32_t), 256);
+}
+
+extern "C" int cmpq_kmeans_quantize_job(const cmpq_kmeans_job *job, void *ws, size_t ws_bytes, void *stream) {
+    if (!job) return CMPQ_EINVAL;
+    const cmpq_kmeans_job &j = *job;
+    const int64_t d_in = j.d_in, d_out = j.d_out;
+    if (d_in < 0 || d_out < 0 || j.n_out < 0 || j.iters < 0) return CMPQ_EINVAL;
+    if (j.dtype != CMPQ_F16 && j.dtype != CMPQ_F32) return CMPQ_EINVAL;
+    if (j.init != CMPQ_INIT_QUANTILE && j.init != CMPQ_INIT_GIVEN) return CMPQ_EINVAL;
+    if (j.algorithm != CMPQ_KMEANS_HISTOGRAM && j.algorithm != CMPQ_KMEANS_DIRECT) return CMPQ_EINVAL;
+    if (!j.bits || !j.centroids || (j.n_out > 0 && !j.out_idx)) return CMPQ_EINVAL;
+    if (d_in > 0 && d_out > 0 && (!j.W || !j.codes)) return CMPQ_EINVAL;
+    if (j.ldw < d_out) return CMPQ_ESHAPE;
+    if (d_out > (j.dtype == CMPQ_F16 ? 32768 : 16384)) return CMPQ_ESHAPE;
+    if (d_in > 0 && d_out > ((int64_t)1 << 31) / d_in) return CMPQ_ESHAPE;
+    if (d_in >= ((int64_t)1 << 31)) return CMPQ_ESHAPE;
+    if (d_in == 0) return CMPQ_OK;
+    KmArgs a;
+    a.W = j.W;
+    a.d_in = d_in;
+    a.d_out = d_out;
+    a.ldw = j.ldw;
+    a.bits = j.bits;
+    a.out_idx = j.out_idx;
+    a.n_out = j.n_out;
+    a.ew = j.elem_weight;
+    a.iters = j.iters;
+    a.start_given = j.init == CMPQ_INIT_GIVEN;
+    a.centroids = j.centroids;
+    a.codes = j.codes;
+    a.status = j.status;
+    a.deferred = nullptr;
+    a.seg = nullptr;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (!ws || reinterpret_cast<uintptr_t>(ws) % 256 != 0 || ws_bytes < cmpq_ws_kmeans(d_in, d_out))
+        return CMPQ_EWORKSPACE;
+    if (j.n_out > 0) {
+        int32_t *seg = reinterpret_cast<int32_t *>(static_cast<char *>(ws) + align_up((size_t)d_in, 256));
+        const int rc = launch_segment_offsets(j.out_idx, j.n_out, d_in, d_out, seg, s);
+        if (rc != CMPQ_OK) return rc;
+        a.seg = seg;
+    }
+    if (kmeans_fast_eligible(a, j.dtype)) {
+        // the bucket kernel takes every channel itself
+        // (so does a run from given levels, whichever implementation is named)
+        if (j.algorithm != CMPQ_KMEANS_DIRECT || a.start_given) return launch_kmeans_hist(a, s);
+        a.deferred = static_cast<uint8_t *>(ws);
+        const int rc = launch_kmeans_fast(a, s);
+        if (rc != CMPQ_OK) return rc;
+        return launch_kmeans<__half, false>(a, s);  // only the channels the first kernel deferred
+    }
+    if (j.dtype == CMPQ_F16)
+        return j.elem_weight ? launch_kmeans<__half, true>(a, s) : launch_kmeans<__half, false>(a, s);
+    return j.elem_weight ? launch_kmeans<float, true>(a, s) : launch_kmeans<float, false>(a, s);
 }
 
 extern "C" int cmpq_kmeans_quantize(const void *W, int dtype, int64_t d_in, int64_t d_out,
@@ -388,51 +434,21 @@ extern "C" int cmpq_kmeans_quantize(const void *W, int dtype, int64_t d_in, int6
                                     int64_t n_out, const float *elem_weight, int iters, int init,
                                     float *centroids, uint8_t *codes, void *ws, size_t ws_bytes,
                                     int32_t *status, void *stream) {
-    if (d_in < 0 || d_out < 0 || n_out < 0 || iters < 0) return CMPQ_EINVAL;
-    if (dtype != CMPQ_F16 && dtype != CMPQ_F32) return CMPQ_EINVAL;
-    if (init != CMPQ_INIT_QUANTILE && init != CMPQ_INIT_GIVEN) return CMPQ_EINVAL;
-    if (!bits || !centroids || (n_out > 0 && !out_idx)) return CMPQ_EINVAL;
-    if (d_in > 0 && d_out > 0 && (!W || !codes)) return CMPQ_EINVAL;
-    if (ldw < d_out) return CMPQ_ESHAPE;
-    if (d_out > (dtype == CMPQ_F16 ? 32768 : 16384)) return CMPQ_ESHAPE;
-    if (d_in > 0 && d_out > ((int64_t)1 << 31) / d_in) return CMPQ_ESHAPE;
-    if (d_in >= ((int64_t)1 << 31)) return CMPQ_ESHAPE;
-    if (d_in == 0) return CMPQ_OK;
-    KmArgs a;
-    a.W = W;
-    a.d_in = d_in;
-    a.d_out = d_out;
-    a.ldw = ldw;
-    a.bits = bits;
-    a.out_idx = out_idx;
-    a.n_out = n_out;
-    a.ew = elem_weight;
-    a.iters = iters;
-    a.start_given = init == CMPQ_INIT_GIVEN;
-    a.centroids = centroids;
-    a.codes = codes;
-    a.status = status;
-    a.deferred = nullptr;
-    a.seg = nullptr;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    if (!ws || reinterpret_cast<uintptr_t>(ws) % 256 != 0 || ws_bytes < cmpq_ws_kmeans(d_in, d_out))
-        return CMPQ_EWORKSPACE;
-    if (n_out > 0) {
-        int32_t *seg = reinterpret_cast<int32_t *>(static_cast<char *>(ws) + align_up((size_t)d_in, 256));
-        const int rc = launch_segment_offsets(out_idx, n_out, d_in, d_out, seg, s);
-        if (rc != CMPQ_OK) return rc;
-        a.seg = seg;
-    }
-    if (kmeans_fast_eligible(a, dtype)) {
-        // the bucket kernel takes every channel itself
-        // (so does a run from given levels, whichever implementation is selected)
-        if (g_kmeans_algorithm != CMPQ_KMEANS_DIRECT || a.start_given) return launch_kmeans_hist(a, s);
-        a.deferred = static_cast<uint8_t *>(ws);
-        const int rc = launch_kmeans_fast(a, s);
-        if (rc != CMPQ_OK) return rc;
-        return launch_kmeans<__half, false>(a, s);  // only the channels the first kernel deferred
-    }
-    if (dtype == CMPQ_F16)
-        return elem_weight ? launch_kmeans<__half, true>(a, s) : launch_kmeans<__half, false>(a, s);
-    return elem_weight ? launch_kmeans<float, true>(a, s) : launch_kmeans<float, false>(a, s);
+    cmpq_kmeans_job j = {};
+    j.W = W;
+    j.dtype = dtype;
+    j.d_in = d_in;
+    j.d_out = d_out;
+    j.ldw = ldw;
+    j.bits = bits;
+    j.out_idx = out_idx;
+    j.n_out = n_out;
+    j.elem_weight = elem_weight;
+    j.iters = iters;
+    j.init = init;
+    j.centroids = centroids;
+    j.codes = codes;
+    j.status = status;
+    j.algorithm = CMPQ_KMEANS_HISTOGRAM;
+    return cmpq_kmeans_quantize_job(&j, ws, ws_bytes, stream);
 }

@@ -379,6 +379,7 @@ extern "C" int cmpq_pack_with_error(const void *W, int dtype, int64_t d_in, int6
                               (ldw * esz) % 16 == 0 && reinterpret_cast<uintptr_t>(codes) % 16 == 0;
         if (one_pass) {
             const size_t lds = (size_t)(d_out / 32) * 4;
+            cmpq_timing_before(CMPQ_KERNEL_PACK_ERROR, s);
             if (dtype == CMPQ_F16)
                 pack_error_kernel<__half><<<(unsigned)d_in, kPeT, lds, s>>>(
                     static_cast<const __half *>(W), d_out, ldw, codes, bits, centroids, row_of, p, out_idx, slices,
@@ -387,6 +388,7 @@ extern "C" int cmpq_pack_with_error(const void *W, int dtype, int64_t d_in, int6
                 pack_error_kernel<float><<<(unsigned)d_in, kPeT, lds, s>>>(
                     static_cast<const float *>(W), d_out, ldw, codes, bits, centroids, row_of, p, out_idx, slices,
                     err_ch);
+            cmpq_timing_after(CMPQ_KERNEL_PACK_ERROR, s);
             CMPQ_LAUNCH_CHECK();
         } else {  // ragged or unaligned rows: the kernels of the two separate calls
             const int vec_ok = reinterpret_cast<uintptr_t>(codes) % 16 == 0 && d_out % 16 == 0;

@@ -878,20 +878,16 @@ __device__ __forceinline__ void emit_from_list(const WselArgs &a, const WselStat
     }
 }
 
-// Full path: one more pass over the data, a workgroup per run of 4 units, 4 wave-chunks
-// (2048 consecutive entries) a step.
+// Writes, in index order, the selected entries of the wave-chunks [q0, q1): keys above T, and
+// of the keys equal to T those whose running tie count is still below `need`.  The whole
+// workgroup takes 4 wave-chunks (2048 consecutive entries) a step; `ties` and `outp` are the
+// tie count and the output position before q0, positions at or beyond out_end are dropped.
 template <typename TW>
-__device__ __forceinline__ void write_full(const WselArgs &a, const WselState *st,
-                                           const uint64_t *__restrict__ tie_base,
-                                           const uint64_t *__restrict__ out_base, int64_t k,
-                                           int32_t *__restrict__ idx_out, uint16_t *__restrict__ val_out,
-                                           uint32_t *scan) {
+__device__ __forceinline__ void write_chunks(const WselArgs &a, uint32_t T, uint64_t need, uint64_t ties,
+                                             uint64_t outp, int64_t q0, int64_t q1, int64_t out_end,
+                                             int32_t *__restrict__ idx_out, uint16_t *__restrict__ val_out,
+                                             uint32_t *scan) {
     const int lane = threadIdx.x & (CMPQ_WAVE - 1), wave = wave_index();
-    const uint32_t T = st->T;
-    const uint64_t need = st->need;
-    uint64_t ties = tie_base[blockIdx.x], outp = out_base[blockIdx.x];
-    const int64_t q0 = (int64_t)blockIdx.x * kWaves * a.wc_per_unit;
-    const int64_t q1 = min(a.total_wc, q0 + kWaves * a.wc_per_unit);
     for (int64_t qb = q0; qb < q1; qb += kWaves) {
         const int64_t q = qb + wave;
         const int64_t i = q / a.wc_per_channel, c = q % a.wc_per_channel;
@@ -929,7 +925,7 @@ __device__ __forceinline__ void write_full(const WselArgs &a, const WselState *s
                 ++my_tie;
             }
             if (sel) {
-                if ((int64_t)pos < k) {
+                if ((int64_t)pos < out_end) {
                     idx_out[pos] = (int32_t)(i * a.d_out + o0 + j);
                     if (val_out) val_out[pos] = __half_as_ushort(__float2half_rn(wv[j]));
                 }
@@ -942,6 +938,19 @@ __device__ __forceinline__ void write_full(const WselArgs &a, const WselState *s
         ties += eq_total;
         outp += sel_total;
     }
+}
+
+// Full path: one more pass over the data, a workgroup per run of 4 units.
+template <typename TW>
+__device__ __forceinline__ void write_full(const WselArgs &a, const WselState *st,
+                                           const uint64_t *__restrict__ tie_base,
+                                           const uint64_t *__restrict__ out_base, int64_t k,
+                                           int32_t *__restrict__ idx_out, uint16_t *__restrict__ val_out,
+                                           uint32_t *scan) {
+    const int64_t q0 = (int64_t)blockIdx.x * kWaves * a.wc_per_unit;
+    const int64_t q1 = min(a.total_wc, q0 + kWaves * a.wc_per_unit);
+    write_chunks<TW>(a, st->T, st->need, tie_base[blockIdx.x], out_base[blockIdx.x], q0, q1, k, idx_out, val_out,
+                     scan);
 }
 
 // The last kernel of a call: from the list, unless the exact chain ran and its list
@@ -957,6 +966,77 @@ __global__ __launch_bounds__(kWThreads) void wsel_emit_kernel(WselArgs a, const 
         write_full<TW>(a, st, tie_base, out_base, k, idx_out, val_out, scan);
     else
         emit_from_list(a, st, tie_base, out_base, k, idx_out, val_out);
+}
+
+// ------------------------------------------------------------------ one channel at a time
+//
+// The variant of O_q with the same count in every channel: a workgroup per channel finds the
+// channel's k-th largest key by the same three digits (11 + 11 + 10 bits, the keys formed
+// again from the weights in every pass: a channel's row stays in cache) and writes the
+// channel's k entries in index order at the place its rank among the quantized channels gives.
+
+// rank[i] = number of channels before i with bits in 1..4.
+__global__ __launch_bounds__(1024) void wsel_live_rank_kernel(const uint8_t *__restrict__ bits, int64_t d_in,
+                                                              int32_t *__restrict__ rank) {
+    __shared__ uint32_t scan[17];
+    uint32_t run = 0;
+    for (int64_t base = 0; base < d_in; base += blockDim.x) {
+        const int64_t i = base + threadIdx.x;
+        const uint32_t f = i < d_in && bits[i] >= 1 && bits[i] <= 4;
+        uint32_t total;
+        const uint32_t before = run + block_scan_excl_u32(f, scan, &total);
+        if (i < d_in) rank[i] = (int32_t)before;
+        run += total;
+    }
+}
+
+template <typename TW>
+__global__ __launch_bounds__(kWThreads) void wsel_channel_kernel(WselArgs a, const int32_t *__restrict__ live_rank,
+                                                                  int64_t k, int32_t *__restrict__ idx_out,
+                                                                  uint16_t *__restrict__ val_out) {
+    __shared__ uint32_t lh[kBins];
+    __shared__ PickShared ps;
+    __shared__ uint32_t scan[34];
+    const int64_t i = blockIdx.x;
+    if (!channel_live(a, i)) return;  // uniform over the workgroup
+    const int lane = threadIdx.x & (CMPQ_WAVE - 1), wave = wave_index();
+    const float cent = a.centroids ? a.centroids[i * CMPQ_KMAX + (lane & 15)] : 0.f;
+    uint32_t prefix = 0;
+    uint64_t rem = (uint64_t)k;  // 1 <= k <= d_out: every pass finds its digit
+    for (int pass = 0; pass < 3; ++pass) {
+        for (int b = threadIdx.x; b < kBins; b += kWThreads) lh[b] = 0;
+        __syncthreads();
+        for (int64_t c = wave; c < a.wc_per_channel; c += kWaves) {
+            const int64_t o0 = c * kWaveChunk + lane * kWPerLane;
+            Raw8<TW> raw;
+            fetch8(a, i, o0, raw);
+            uint32_t key[8];
+            float wv[8];
+            score_keys8<TW>(a, raw, cent, key, wv);
+            const uint32_t valid = valid8(o0, a.d_out);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                if (!((valid >> j) & 1u)) continue;
+                if (pass == 0) {
+                    atomicAdd(&lh[key[j] >> 21], 1u);
+                } else if (pass == 1) {
+                    if ((key[j] >> 21) == (prefix >> 21)) atomicAdd(&lh[(key[j] >> 10) & 2047u], 1u);
+                } else {
+                    if ((key[j] >> 10) == (prefix >> 10)) atomicAdd(&lh[key[j] & 1023u], 1u);
+                }
+            }
+        }
+        __syncthreads();
+        uint32_t bin, tot;
+        uint64_t rem_in;
+        block_pick(lh, rem, ps, bin, rem_in, tot);
+        prefix |= bin << (pass == 0 ? 21 : (pass == 1 ? 10 : 0));
+        rem = rem_in;
+        __syncthreads();
+    }
+    const int64_t out0 = (int64_t)live_rank[i] * k;
+    write_chunks<TW>(a, prefix, rem, 0, (uint64_t)out0, i * a.wc_per_channel, (i + 1) * a.wc_per_channel, out0 + k,
+                     idx_out, val_out, scan);
 }
 
 struct WselWs {
@@ -1004,7 +1084,9 @@ int launch_weight_select(WselArgs a, const WselPlan &p, int64_t k, int32_t *idx_
     // fast chain
     wsel_sample_kernel<TW, 0><<<(unsigned)sample_blocks, kWThreads, 0, s>>>(a, w.hist);
     wsel_sample_kernel<TW, 1><<<(unsigned)sample_blocks, kWThreads, 0, s>>>(a, w.hist);
+    cmpq_timing_before(CMPQ_KERNEL_OUTLIER_STAGE, s);
     wsel_stage_kernel<TW><<<p.nblocks, kWThreads, 0, s>>>(a, w.st, w.hist);
+    cmpq_timing_after(CMPQ_KERNEL_OUTLIER_STAGE, s);
     const int list_blocks = p.nblocks < 256 ? p.nblocks : 256;  // few: each ends with a flush into shared counters
     wsel_list_kernel<0><<<list_blocks, kWThreads, 0, s>>>(a, w.st, p.nunits, w.hist, (uint64_t)k);
     wsel_list_kernel<1><<<list_blocks, kWThreads, 0, s>>>(a, w.st, p.nunits, w.hist, (uint64_t)k);
@@ -1027,7 +1109,10 @@ size_t cmpq_ws_allocate_bits(int64_t) { return 256; }
 size_t cmpq_ws_outlier_channels(int64_t) { return 256; }
 size_t cmpq_ws_outlier_weights(int64_t d_in, int64_t d_out, int64_t k) {
     if (k < 0) k = 0;
-    return wsel_carve(nullptr, wsel_plan(d_in, d_out, k)).bytes;
+    // the layer-wide selection's tables and lists; the per-channel one needs d_in ranks
+    const size_t layer = wsel_carve(nullptr, wsel_plan(d_in, d_out, k)).bytes;
+    const size_t channel = align_up((size_t)(d_in > 0 ? d_in : 1) * sizeof(int32_t), 256);
+    return layer > channel ? layer : channel;
 }
 
 extern "C" int cmpq_allocate_bits(const float *sumsq, int64_t d_in, const uint8_t *chan_mask,
@@ -1092,7 +1177,7 @@ extern "C" int cmpq_allocate_bits(const float *sumsq, int64_t d_in, const uint8_
     return CMPQ_OK;
 }
 
-extern "C" int cmpq_extract_outliers(int mode, int score, const float *sumsq, const void *W,
+extern "C" int cmpq_extract_outliers(int mode, int score, int scope, const float *sumsq, const void *W,
                                      int dtype, int64_t d_in, int64_t d_out, int64_t ldw,
                                      const float *centroids, const uint8_t *codes,
                                      const uint8_t *bits, int64_t k, int32_t *idx_out,
@@ -1111,13 +1196,15 @@ extern "C" int cmpq_extract_outliers(int mode, int score, const float *sumsq, co
     }
     if (mode != CMPQ_OUTLIER_WEIGHTS) return CMPQ_EINVAL;
     if (score != CMPQ_SCORE_RESIDUAL && score != CMPQ_SCORE_MAGNITUDE) return CMPQ_EINVAL;
+    if (scope != CMPQ_SCOPE_LAYER && scope != CMPQ_SCOPE_CHANNEL) return CMPQ_EINVAL;
     if (dtype != CMPQ_F16 && dtype != CMPQ_F32) return CMPQ_EINVAL;
     if (d_out < 0 || !bits || (k > 0 && !idx_out)) return CMPQ_EINVAL;
     if (d_in > 0 && d_out > 0 && !W) return CMPQ_EINVAL;
     if (score == CMPQ_SCORE_RESIDUAL && d_in > 0 && d_out > 0 && (!centroids || !codes)) return CMPQ_EINVAL;
     if (ldw < d_out) return CMPQ_ESHAPE;
     if (d_in > 0 && d_out > ((int64_t)1 << 31) / d_in) return CMPQ_ESHAPE;  // linear index in int32
-    if (k > d_in * d_out) return CMPQ_ECOUNT;
+    if (scope == CMPQ_SCOPE_CHANNEL ? k > d_out : k > d_in * d_out) return CMPQ_ECOUNT;
+    if (scope == CMPQ_SCOPE_CHANNEL && d_in > 0 && k > ((int64_t)1 << 31) / d_in) return CMPQ_ESHAPE;
     if (k == 0 || d_in == 0 || d_out == 0) return CMPQ_OK;
     if (!ws || reinterpret_cast<uintptr_t>(ws) % 256 != 0 || ws_bytes < cmpq_ws_outlier_weights(d_in, d_out, k))
         return CMPQ_EWORKSPACE;
@@ -1137,6 +1224,16 @@ extern "C" int cmpq_extract_outliers(int mode, int score, const float *sumsq, co
     const int esz = dtype == CMPQ_F16 ? 2 : 4;
     a.vec_ok = reinterpret_cast<uintptr_t>(W) % 16 == 0 && (ldw * esz) % 16 == 0 &&
                (a.codes == nullptr || (reinterpret_cast<uintptr_t>(codes) % 8 == 0 && d_out % 8 == 0));
+    if (scope == CMPQ_SCOPE_CHANNEL) {
+        int32_t *live_rank = static_cast<int32_t *>(ws);
+        wsel_live_rank_kernel<<<1, 1024, 0, s>>>(bits, d_in, live_rank);
+        if (dtype == CMPQ_F16)
+            wsel_channel_kernel<__half><<<(unsigned)d_in, kWThreads, 0, s>>>(a, live_rank, k, idx_out, val_out);
+        else
+            wsel_channel_kernel<float><<<(unsigned)d_in, kWThreads, 0, s>>>(a, live_rank, k, idx_out, val_out);
+        CMPQ_LAUNCH_CHECK();
+        return CMPQ_OK;
+    }
     return dtype == CMPQ_F16 ? launch_weight_select<__half>(a, p, k, idx_out, val_out, ws, s)
                              : launch_weight_select<float>(a, p, k, idx_out, val_out, ws, s);
 }

@@ -14,24 +14,48 @@ import torch
 from . import binding as B
 
 
+# the kernel that dominates each stage: `StageTimer(kernels=True)` times it by itself
+_KERNEL_OF_STAGE = {"act_stats": B.KERNEL_ACT_STATS, "transpose": B.KERNEL_TRANSPOSE,
+                    "kmeans_prelim": B.KERNEL_KMEANS, "kmeans_final": B.KERNEL_KMEANS,
+                    "outlier_weights": B.KERNEL_OUTLIER_STAGE, "pack_with_error": B.KERNEL_PACK_ERROR}
+
+
 class StageTimer:
     """Brackets each C-ABI call with a pair of events on the stream the call is
-    enqueued on; `totals()` returns {stage: (calls, milliseconds)} once they ran."""
+    enqueued on; `totals()` returns {stage: (calls, milliseconds)} once they ran.
 
-    def __init__(self):
+    With ``kernels=True`` the library's measurement hook also brackets the one kernel that
+    dominates the stage (`cmpq_time_kernel`: events recorded right before and after that launch,
+    on its stream); `kernel_totals()` returns the same shape for those."""
+
+    def __init__(self, kernels: bool = False):
         self.pairs: Dict[str, list] = {}
+        self.kpairs: Dict[str, list] = {}
+        self.kernels = kernels
 
     @contextlib.contextmanager
     def stage(self, name: str):
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        kid = _KERNEL_OF_STAGE.get(name) if self.kernels else None
+        if kid is not None:
+            k0, k1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            k0.record(), k1.record()          # creates the handles; the library records them again
+            B.time_kernel(kid, k0.cuda_event, k1.cuda_event)
         a.record()
         yield
         b.record()
         self.pairs.setdefault(name, []).append((a, b))
+        if kid is not None:
+            B.time_kernel(kid, None, None)    # in case the call took a path without that kernel
+            self.kpairs.setdefault(name, []).append((k0, k1))
 
     def totals(self) -> Dict[str, tuple]:
         torch.cuda.synchronize()
         return {k: (len(v), sum(a.elapsed_time(b) for a, b in v)) for k, v in self.pairs.items()}
+
+    def kernel_totals(self) -> Dict[str, tuple]:
+        torch.cuda.synchronize()
+        return {k: (len(v), sum(a.elapsed_time(b) for a, b in v)) for k, v in self.kpairs.items()}
 
 
 def _stage(timer: Optional[StageTimer], name: str):
@@ -103,25 +127,30 @@ def _channels_and_widths(sumsq, d_in, bit_set, avg_bits, rho_act_ppm, ws, timer)
 
 def _after_first_pass(Wt, sumsq, bit_set, counts, act_idx, chan_mask, bits, cent1, codes1, rho_q_ppm, iters,
                       ws, score, with_error, keep_prelim, status, timer,
-                      iters_final_from_prelim: Optional[int] = None) -> LayerResult:
+                      iters_final_from_prelim: Optional[int] = None, oq_per_channel: bool = False) -> LayerResult:
     """O_q from the preliminary quantization, the final quantization, the stored format."""
     dev = Wt.device
     d_in, d_out = Wt.shape
-    # O_q: largest |W' - W'_q|
-    k_q = B.count_ppm(rho_q_ppm, d_in * d_out)
+    # O_q: largest |W' - W'_q|, over the layer (Sec. 3.2.2) or, as a variant, per channel
+    if oq_per_channel:
+        k_each = B.count_ppm(rho_q_ppm, d_out)
+        k_q = k_each * sum(counts)
+    else:
+        k_each = k_q = B.count_ppm(rho_q_ppm, d_in * d_out)
     out_idx = torch.empty(k_q, dtype=torch.int32, device=dev)
     out_val = torch.empty(k_q, dtype=torch.float16, device=dev)
     with _stage(timer, "outlier_weights"):
-        B.extract_weight_outliers(Wt, cent1, codes1, bits, k_q, out_idx, out_val, ws, score)
+        B.extract_weight_outliers(Wt, cent1, codes1, bits, k_each, out_idx, out_val, ws, score,
+                                  B.SCOPE_CHANNEL if oq_per_channel else B.SCOPE_LAYER)
     # final quantization of W - O
     codes = torch.empty((d_in, d_out), dtype=torch.uint8, device=dev)
     if iters_final_from_prelim is None:
         cent = torch.empty((d_in, B.KMAX), dtype=torch.float32, device=dev)
-        with _stage(timer, "kmeans"):
+        with _stage(timer, "kmeans_final"):
             B.kmeans_quantize(Wt, bits, out_idx, k_q, None, iters, cent, codes, ws, status)
     else:  # variant: continue from the preliminary levels (a copy; the call updates it in place)
         cent = cent1.clone()
-        with _stage(timer, "kmeans"):
+        with _stage(timer, "kmeans_final"):
             B.kmeans_quantize(Wt, bits, out_idx, k_q, None, iters_final_from_prelim, cent, codes, ws, status,
                               init=B.INIT_GIVEN)
     # stored format
@@ -155,9 +184,12 @@ def quantize_layer(W: torch.Tensor, sumsq: torch.Tensor, bit_set: Sequence[int],
                    with_error: bool = False, keep_prelim: bool = False,
                    status: Optional[torch.Tensor] = None, transposed: bool = False,
                    timer: Optional[StageTimer] = None,
-                   iters_final_from_prelim: Optional[int] = None) -> LayerResult:
+                   iters_final_from_prelim: Optional[int] = None, oq_per_channel: bool = False) -> LayerResult:
     """Quantizes one layer.  `W` is the framework's [d_out, d_in] weight (or already
     d_in x d_out with ``transposed=True``); `sumsq` comes from `activation_stats`.
+
+    ``oq_per_channel`` (a variant; Sec. 3.2.2 selects over the layer): O_q takes
+    ``round_half_up(rho_q * d_out)`` entries in every channel outside O_act.
 
     ``iters_final_from_prelim`` (a variant; the paper names no start for either K-means of
     Sec. 3.2.2): the final quantization starts from the levels of the preliminary one and runs
@@ -170,10 +202,11 @@ def quantize_layer(W: torch.Tensor, sumsq: torch.Tensor, bit_set: Sequence[int],
     # preliminary quantization W'_q
     cent1 = torch.empty((d_in, B.KMAX), dtype=torch.float32, device=dev)
     codes1 = torch.empty((d_in, d_out), dtype=torch.uint8, device=dev)
-    with _stage(timer, "kmeans"):
+    with _stage(timer, "kmeans_prelim"):
         B.kmeans_quantize(Wt, bits, None, 0, None, iters, cent1, codes1, ws, status)
     return _after_first_pass(Wt, sumsq, bit_set, counts, act_idx, chan_mask, bits, cent1, codes1, rho_q_ppm,
-                             iters, ws, score, with_error, keep_prelim, status, timer, iters_final_from_prelim)
+                             iters, ws, score, with_error, keep_prelim, status, timer, iters_final_from_prelim,
+                             oq_per_channel)
 
 
 @dataclasses.dataclass
@@ -202,7 +235,7 @@ def build_width_cache(W: torch.Tensor, bit_set: Sequence[int], iters: int = 20,
         bits_b = torch.full((d_in,), int(b), dtype=torch.uint8, device=dev)
         c = torch.empty((d_in, B.KMAX), dtype=torch.float32, device=dev)
         k = torch.empty((d_in, d_out), dtype=torch.uint8, device=dev)
-        with _stage(timer, "kmeans"):
+        with _stage(timer, "kmeans_prelim"):
             B.kmeans_quantize(Wt, bits_b, None, 0, None, iters, c, k, ws, status)
         cents.append(c), codes.append(k)
     return WidthCache(tuple(bit_set), iters, Wt, cents, codes)
@@ -233,17 +266,19 @@ def quantize_layer_from_cache(cache: WidthCache, sumsq: torch.Tensor, avg_bits: 
 
 
 def tables_in_4_bits(r: LayerResult, ws: Optional[B.Workspace] = None, with_error: bool = False,
-                     timer: Optional[StageTimer] = None):
-    """Sec. 5.1 / Tab. 7: re-expresses the look-up tables of a quantized layer on one uniform
-    16-level grid and writes the stored format again with them.  Returns
-    ``(codes4 [d_in,16] uint8, range [2] fp32 = (min, step), LayerResult with the rebuilt tables)``."""
+                     timer: Optional[StageTimer] = None, mode: int = B.LUT4_CODEBOOK, iters: int = 20):
+    """Sec. 5.1 / Tab. 7: re-expresses the look-up tables of a quantized layer in 4 bits per entry -
+    codes into one 16-level table per layer (default) or on one uniform grid (``mode =
+    B.LUT4_UNIFORM``) - and writes the stored format again with them.  Returns ``(codes4 [d_in,16]
+    uint8, table [16] fp32 (the levels; minimum and step in the first two entries for the uniform
+    grid), LayerResult with the rebuilt tables)``."""
     ws = ws or B.Workspace(r.codes.device)
     dev = r.codes.device
     codes4 = torch.empty((r.d_in, B.KMAX), dtype=torch.uint8, device=dev)
-    rng = torch.empty(2, dtype=torch.float32, device=dev)
+    rng = torch.zeros(B.KMAX, dtype=torch.float32, device=dev)
     cent_q = torch.empty((r.d_in, B.KMAX), dtype=torch.float32, device=dev)
     with _stage(timer, "lut4"):
-        B.lut4_quantize(r.centroids, r.bits, codes4, rng, cent_q)
+        B.lut4_quantize(r.centroids, r.bits, codes4, rng, cent_q, ws, mode, iters)
     packed, chan_idx, lut = [], [], []
     for b, c in zip(r.bit_set, r.counts):
         if c == 0:

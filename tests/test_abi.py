@@ -52,7 +52,7 @@ def test_counts_and_messages(L):
     for code in range(0, -7, -1):
         assert B.strerror(code) and "unknown cmpq" not in B.strerror(code)
     assert "unknown cmpq" in B.strerror(-99)
-    for op in range(7):
+    for op in range(11):
         assert B.workspace_bytes(op, 4096, 4096, 1000) % 256 == 0
         assert B.workspace_bytes(op, 4096, 4096, 1000) >= 256
     assert B.workspace_bytes(99, 1, 1, 1) == 0
@@ -79,12 +79,15 @@ def test_host_side_argument_errors(L):
     assert L.cmpq_allocate_bits(fake, 16, None, 0, (i32 * 2)(4, 5), 2, ctypes.c_double(4.0), fake, cnt, fake, 256, None) == -3
     assert L.cmpq_allocate_bits(fake, 16, None, 3, bs, 3, ctypes.c_double(3.0), fake, cnt, fake, 256, None) == -1
     # outliers
-    assert L.cmpq_extract_outliers(0, 0, fake, None, 0, 16, 0, 0, None, None, None, 17, fake, None, None, fake, 256, None) == -4
-    assert L.cmpq_extract_outliers(1, 0, None, fake, 0, 4, 4, 4, fake, fake, fake, 17, fake, None, None, fake, 1 << 20, None) == -4
-    assert L.cmpq_extract_outliers(1, 0, None, fake, 0, 4, 4, 4, None, fake, fake, 1, fake, None, None, fake, 1 << 20, None) == -1
-    assert L.cmpq_extract_outliers(1, 0, None, fake, 0, 4, 4, 4, fake, fake, fake, 1, fake, None, None, fake, 16, None) == -5
-    assert L.cmpq_extract_outliers(5, 0, None, fake, 0, 4, 4, 4, fake, fake, fake, 1, fake, None, None, fake, 1 << 20, None) == -1
-    assert L.cmpq_extract_outliers(1, 0, None, fake, 0, 1 << 20, 1 << 20, 1 << 20, fake, fake, fake, 1, fake, None, None, fake, 1 << 20, None) == -2
+    assert L.cmpq_extract_outliers(0, 0, 0, fake, None, 0, 16, 0, 0, None, None, None, 17, fake, None, None, fake, 256, None) == -4
+    assert L.cmpq_extract_outliers(1, 0, 0, None, fake, 0, 4, 4, 4, fake, fake, fake, 17, fake, None, None, fake, 1 << 20, None) == -4
+    assert L.cmpq_extract_outliers(1, 0, 0, None, fake, 0, 4, 4, 4, None, fake, fake, 1, fake, None, None, fake, 1 << 20, None) == -1
+    assert L.cmpq_extract_outliers(1, 0, 0, None, fake, 0, 4, 4, 4, fake, fake, fake, 1, fake, None, None, fake, 16, None) == -5
+    assert L.cmpq_extract_outliers(5, 0, 0, None, fake, 0, 4, 4, 4, fake, fake, fake, 1, fake, None, None, fake, 1 << 20, None) == -1
+    assert L.cmpq_extract_outliers(1, 0, 0, None, fake, 0, 1 << 20, 1 << 20, 1 << 20, fake, fake, fake, 1, fake, None, None, fake, 1 << 20, None) == -2
+    assert L.cmpq_extract_outliers(1, 0, 2, None, fake, 0, 4, 4, 4, fake, fake, fake, 1, fake, None, None, fake, 1 << 20, None) == -1   # scope
+    assert L.cmpq_extract_outliers(1, 0, 1, None, fake, 0, 4, 4, 4, fake, fake, fake, 5, fake, None, None, fake, 1 << 20, None) == -4   # per channel: k > d_out
+    assert L.cmpq_extract_outliers(1, 0, 1, None, fake, 0, 4, 4, 4, fake, fake, fake, 0, None, None, None, None, 0, None) == 0          # nothing asked
     # k-means
     assert L.cmpq_kmeans_quantize(fake, 0, 4, 40000, 40000, fake, None, 0, None, 5, 0, fake, fake, fake, 256, None, None) == -2
     assert L.cmpq_kmeans_quantize(fake, 1, 4, 20000, 20000, fake, None, 0, None, 5, 0, fake, fake, fake, 256, None, None) == -2
@@ -136,9 +139,30 @@ def test_host_side_argument_errors(L):
     assert L.cmpq_lut_matvec_group(None, 2, 1, None, 0, None) == -1                            # layers missing
     assert L.cmpq_lut_matvec_group(fake, 9, 1, None, 0, None) == -1                            # more than CMPQ_MAX_GROUP
     # tables in 4 bits
-    assert L.cmpq_lut4_quantize(fake, fake, 4, fake, None, fake, None) == -1                    # no range
-    assert L.cmpq_lut4_quantize(None, fake, 4, fake, fake, fake, None) == -1                    # no tables
-    assert L.cmpq_lut4_quantize(fake, fake, -1, fake, fake, fake, None) == -1
+    for mode in (0, 1):
+        assert L.cmpq_lut4_quantize(mode, fake, fake, 4, 20, fake, None, fake, fake, 1 << 21, None) == -1   # no table
+        assert L.cmpq_lut4_quantize(mode, None, fake, 4, 20, fake, fake, fake, fake, 1 << 21, None) == -1   # no centres
+        assert L.cmpq_lut4_quantize(mode, fake, fake, -1, 20, fake, fake, fake, fake, 1 << 21, None) == -1
+        assert L.cmpq_lut4_quantize(mode, fake, fake, 4, -1, fake, fake, fake, fake, 1 << 21, None) == -1   # rounds
+    assert L.cmpq_lut4_quantize(2, fake, fake, 4, 20, fake, fake, fake, fake, 1 << 21, None) == -1          # mode
+    assert L.cmpq_lut4_quantize(0, fake, fake, 4, 20, fake, fake, fake, fake, 4096, None) == -5             # workspace
+    assert L.cmpq_lut4_quantize(0, fake, fake, 4, 20, fake, fake, fake, None, 0, None) == -5
+    # the job form of the K-means call
+    from paper_2410_13056_amd.binding import KmeansJob
+    def job(**kw):
+        j = KmeansJob(256, 0, 4, 64, 64, 256, None, 0, None, 5, 0, 256, 256, None, 0)
+        for k, v in kw.items():
+            setattr(j, k, v)
+        return ctypes.byref(j)
+    assert L.cmpq_kmeans_quantize_job(None, fake, 1 << 20, None) == -1
+    assert L.cmpq_kmeans_quantize_job(job(algorithm=2), fake, 1 << 20, None) == -1
+    assert L.cmpq_kmeans_quantize_job(job(algorithm=1, iters=-1), fake, 1 << 20, None) == -1
+    assert L.cmpq_kmeans_quantize_job(job(d_out=40000, ldw=40000), fake, 1 << 20, None) == -2
+    assert L.cmpq_kmeans_quantize_job(job(), fake, 16, None) == -5
+    assert L.cmpq_kmeans_quantize_job(job(d_in=0), None, 0, None) == 0
+    # measurement hook: unknown kernel; arming and disarming touch no GPU state
+    assert L.cmpq_time_kernel(-1, fake, fake) == -1 and L.cmpq_time_kernel(5, fake, fake) == -1
+    assert L.cmpq_time_kernel(2, fake, fake) == 0 and L.cmpq_time_kernel(2, None, None) == 0
     # the uniform quantizer
     assert L.cmpq_rtn_quantize(fake, 0, 4, 64, 64, fake, 96, fake, fake, fake, None, None, None) == -1    # group no power of two
     assert L.cmpq_rtn_quantize(fake, 0, 4, 64, 64, fake, 4, fake, fake, fake, None, None, None) == -1     # group below 8

@@ -87,12 +87,19 @@ def _selection_properties(Wt, cent1, codes1, bits, out_idx, out_val, k):
         assert int(tie_in.max()) < int(tie_out.min())            # equal scores: smaller index first
 
 
-@pytest.mark.parametrize("layer", ["gate_proj", "down_proj", "k_proj"])
-def test_block70b_layers_full_size(env, layer):
-    """70B-shaped layers at full size (8192->28672, 28672->8192, 8192->1024), bits {2,3,4} avg 3.5,
-    1 % weight outliers, 20 rounds."""
+@pytest.mark.parametrize("workload,layer", [
+    ("block70b", "gate_proj"), ("block70b", "down_proj"), ("block70b", "k_proj"), ("block70b", "q_proj"),
+    ("block7b", "gate_proj"), ("block7b", "down_proj"), ("block13b", "gate_proj"), ("block13b", "down_proj"),
+    ("block13b", "q_proj")])
+def test_block_layers_full_size(env, workload, layer):
+    """Layers of the three decoder-block configurations at full size, with each configuration's
+    own widths, outlier fractions and round count: 70B-shaped 8192->28672, 28672->8192,
+    8192->1024, 8192->8192 (bits {2,3,4} avg 3.5, 1 % weight outliers); 7B-shaped 4096->11008,
+    11008->4096 ({2,3} avg 2.2, the paper's 0.45 % / 0.05 %); 13B-shaped 5120->13824,
+    13824->5120, 5120->5120 ({2,3,4} avg 2.5, 0.5 %).  Channel lengths 1024 ... 28672 reach every
+    launch variant of the K-means kernel."""
     P, synth, ws, orc, B = env["P"], env["synth"], env["ws"], env["orc"], env["B"]
-    wl = synth.workload("block70b")
+    wl = synth.workload(workload)
     spec = next(l for l in wl.layers if l.name == layer)
     j = wl.layers.index(spec)
     W = synth.make_weight(spec.d_out, spec.d_in, wl.dtype, seed=wl.seed * 1000 + j, device=DEV)

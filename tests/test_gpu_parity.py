@@ -121,6 +121,35 @@ def test_act_stats_other_norms_parity(env, dtype, norm):
     assert np.array_equal(_np(idx), orc.top_channels(_np(stat), k)[0])        # same input on both sides
 
 
+@pytest.mark.parametrize("norm", [0, 1, 2])
+@pytest.mark.parametrize("bad", [np.nan, np.inf])
+def test_act_stats_norms_flag_nonfinite_input(env, norm, bad):
+    """A NaN or an infinity in X raises the status flag under every norm (a maximum must not
+    drop the NaN), in the first chunk of tokens or a later one, on the aligned and the unaligned
+    kernel; the flag stays clear on finite input."""
+    B, ws, orc = env["B"], env["ws"], env["orc"]
+    rng = np.random.default_rng(5)
+    X = rng.normal(0, 1, (200, 256)).astype(np.float16)
+    for cols in (slice(0, 256), slice(3, 103)):
+        Z = X.copy()
+        Z[150, 40] = bad
+        Zd = _dev(Z)[:, cols]
+        d_in = Zd.shape[1]
+        for split in (0, 100, 180):
+            acc = torch.empty(d_in, dtype=torch.float64, device=DEV)
+            st = torch.zeros(1, dtype=torch.int32, device=DEV)
+            if split:
+                B.act_stats_norm(Zd[:split], norm, acc, None, False, ws, st)
+            B.act_stats_norm(Zd[split:], norm, acc, None, bool(split), ws, st)
+            assert st.item() & B.STATUS_NONFINITE
+            oacc = orc.act_stats_norm(Z[:, cols], norm)[0]
+            assert np.array_equal(np.isfinite(_np(acc)), np.isfinite(oacc))
+        st = torch.zeros(1, dtype=torch.int32, device=DEV)
+        acc = torch.empty(d_in, dtype=torch.float64, device=DEV)
+        B.act_stats_norm(_dev(X)[:, cols], norm, acc, None, False, ws, st)
+        assert st.item() == 0
+
+
 def test_act_stats_is_reproducible(env):
     X = env["synth"].make_activations(20000, 2048, "f16", 5, DEV)
     a1, _ = env["P"].activation_stats(X, env["ws"])
@@ -173,7 +202,7 @@ def test_channel_outliers_and_allocation_parity(env, d_in):
 
 # ------------------------------------------------------------------ k-means
 
-def _kmeans_gpu(env, W, bits, out_idx=None, ew=None, iters=20, status=None, start=None):
+def _kmeans_gpu(env, W, bits, out_idx=None, ew=None, iters=20, status=None, start=None, algorithm=None):
     B, ws = env["B"], env["ws"]
     Wd = _dev(W)
     d_in, d_out = W.shape
@@ -185,7 +214,7 @@ def _kmeans_gpu(env, W, bits, out_idx=None, ew=None, iters=20, status=None, star
     oi = None if out_idx is None else _dev(out_idx.astype(np.int32))
     B.kmeans_quantize(Wd, _dev(bits), oi, 0 if out_idx is None else len(out_idx),
                       None if ew is None else _dev(ew), iters, cent, codes, ws, status,
-                      init=B.INIT_QUANTILE if start is None else B.INIT_GIVEN)
+                      init=B.INIT_QUANTILE if start is None else B.INIT_GIVEN, algorithm=algorithm)
     return _np(cent), _np(codes)
 
 
@@ -286,15 +315,11 @@ def test_kmeans_direct_kernel_agrees(env):
     bits = rng.integers(1, 5, d_in).astype(np.uint8)
     bits[7] = 16
     excl = np.sort(rng.choice(d_in * d_out, 2000, replace=False)).astype(np.int64)
-    try:
-        for out_idx in (None, excl):
-            ocent, ocodes = orc.kmeans(W, bits, out_idx=out_idx, iters=11)
-            for algo in (B.KMEANS_DIRECT, B.KMEANS_HISTOGRAM):
-                B.set_kmeans_algorithm(algo)
-                cent, codes = _kmeans_gpu(env, W, bits, out_idx=out_idx, iters=11)
-                _check_kmeans(cent, codes, ocent, ocodes, exact=True)
-    finally:
-        B.set_kmeans_algorithm(B.KMEANS_HISTOGRAM)
+    for out_idx in (None, excl):
+        ocent, ocodes = orc.kmeans(W, bits, out_idx=out_idx, iters=11)
+        for algo in (B.KMEANS_DIRECT, B.KMEANS_HISTOGRAM):       # named per call (the job form of the call)
+            cent, codes = _kmeans_gpu(env, W, bits, out_idx=out_idx, iters=11, algorithm=algo)
+            _check_kmeans(cent, codes, ocent, ocodes, exact=True)
 
 
 def test_kmeans_parity_with_removed_entries_and_weights(env):
@@ -475,6 +500,51 @@ def test_weight_outliers_sampled_guess(env, dtype):
             oidx, oval = orc.weight_outliers(W, ocent, ocodes, bits, k, score)
             assert np.array_equal(_np(idx).astype(np.int64), oidx), (score, k)
             assert np.array_equal(_np(val).view(np.uint16), oval)
+
+
+@pytest.mark.parametrize("dtype", [np.float16, np.float32])
+@pytest.mark.parametrize("d_in,d_out", [(3, 5), (20, 96), (16, 2048 + 40), (70, 333), (40, 8192)])
+def test_weight_outliers_per_channel_parity(env, dtype, d_in, d_out):
+    """The per-channel scope of O_q: k entries in every quantized channel, bit-exact against the
+    oracle's per-row sorts - tied scores (coarse grid), channels of O_act in between, ragged
+    channel lengths, every k from none to the whole channel, both scores."""
+    B, ws, orc = env["B"], env["ws"], env["orc"]
+    rng = np.random.default_rng(d_in * 11 + d_out)
+    W = (rng.integers(-40, 40, (d_in, d_out)) / 64.0).astype(dtype)
+    bits = rng.integers(1, 5, d_in).astype(np.uint8)
+    bits[rng.integers(0, d_in, 2)] = 16
+    ocent, ocodes = orc.kmeans(W, bits, iters=3)
+    n_live = int((bits <= 4).sum())
+    Wd, cd, kd, bd = _dev(W), _dev(ocent), _dev(ocodes), _dev(bits)
+    for score in (B.SCORE_RESIDUAL, B.SCORE_MAGNITUDE):
+        for k in sorted({0, 1, 3, d_out // 100 + 1, d_out // 2, d_out}):
+            idx = torch.full((max(k * n_live, 1),), -7, dtype=torch.int32, device=DEV)
+            val = torch.zeros(max(k * n_live, 1), dtype=torch.float16, device=DEV)
+            B.extract_weight_outliers(Wd, cd, kd, bd, k, idx, val, ws, score, B.SCOPE_CHANNEL)
+            oidx, oval = orc.weight_outliers_per_channel(W, ocent, ocodes, bits, k, score)
+            assert np.array_equal(_np(idx)[:k * n_live].astype(np.int64), oidx), (score, k)
+            assert np.array_equal(_np(val)[:k * n_live].view(np.uint16), oval)
+
+
+def test_layer_with_per_channel_outliers_end_to_end(env):
+    """The whole path with O_q taken per channel (count = the fraction of d_out, half rounded
+    up), free running against the oracle's same chain: every integer output identical."""
+    P, ws, orc = env["P"], env["ws"], env["orc"]
+    rng = np.random.default_rng(31)
+    d_in, d_out = 96, 1200
+    W = rng.normal(0, 0.02, (d_in, d_out))
+    W[rng.random(W.shape) < 0.01] *= 9
+    W = W.astype(np.float16)
+    X = (rng.normal(0, 1, (64, d_in)) * np.exp(rng.normal(0, 0.7, d_in))).astype(np.float16)
+    _, sumsq = P.activation_stats(_dev(X), ws)
+    r = P.quantize_layer(_dev(W), sumsq, (2, 3, 4), 3.2, 20000, 7500, 8, ws, with_error=True, transposed=True,
+                         oq_per_channel=True)
+    o = orc.quantize_layer(W, X, (2, 3, 4), 3.2, 20000, 7500, 8, per_channel=True)
+    assert len(o["out_idx"]) == 9 * int((o["bits"] <= 4).sum())           # 0.75 % of 1200
+    assert np.array_equal(_np(r.bits), o["bits"]) and np.array_equal(_np(r.out_idx).astype(np.int64), o["out_idx"])
+    assert np.array_equal(_np(r.out_val).view(np.uint16), o["out_val"])
+    assert np.array_equal(_np(r.centroids), o["centroids"]) and np.array_equal(_np(r.codes), o["codes"])
+    assert abs(_np(r.err_total)[0] - o["totals"][0]) <= 1e-9 * o["totals"][0]
 
 
 # ------------------------------------------------------------------ storage and error
