@@ -18,8 +18,8 @@
  *   - returns CMPQ_OK (0) or a negative CMPQ_E* code; cmpq_strerror names it.
  *     Argument errors are detected on the host before anything is enqueued.
  *   - every data pointer is a DEVICE pointer owned by the caller unless the
- *     comment says "host".  The library keeps nothing between calls (the one
- *     exception says so: cmpq_time_kernel) and
+ *     comment says "host".  The library keeps nothing between calls (the two
+ *     exceptions say so: cmpq_time_kernel, cmpq_act_stats_static) and
  *     allocates no device memory: scratch comes from the caller's workspace
  *     `ws` of `ws_bytes` bytes (256-byte aligned), at least
  *     cmpq_workspace_bytes(op, d_in, d_out, n) large, else CMPQ_EWORKSPACE.
@@ -123,6 +123,21 @@ int cmpq_act_stats(const void *X, int dtype, int64_t n, int64_t d_in, int64_t ld
 int cmpq_act_stats_norm(const void *X, int dtype, int64_t n, int64_t d_in, int64_t ldx, int norm,
                         double *acc, float *stat, int accumulate, void *ws, size_t ws_bytes,
                         int32_t *status, void *stream);
+
+/*
+ * cmpq_act_stats for callers that cannot allocate device memory or hand over a workspace:
+ * code under HIP graph capture, tight serving or calibration loops, harnesses that forbid
+ * allocation.  Same arguments (without ws / ws_bytes), same results bit for bit; the
+ * row-split partial sums go to a fixed array inside the library, (2048*512 + 262144) fp64
+ * = 10 MiB of device memory per GPU that the process holds from the library's load on.
+ * The call allocates and frees nothing and records no memset (nothing in the array has to
+ * start at zero: every partial that is read was written by the same call).
+ * Limits: d_in <= 262144, else CMPQ_ESHAPE.  CMPQ_EHIP when the runtime cannot name the
+ * array's address on the current device.  All calls on one GPU share the array: two calls
+ * that overlap on one GPU (different streams, or threads) race; calls on one stream do not.
+ */
+int cmpq_act_stats_static(const void *X, int dtype, int64_t n, int64_t d_in, int64_t ldx, double *acc,
+                          float *sumsq, int accumulate, int32_t *status, void *stream);
 
 /*
  * Orientation helper for Sec. 3.2.1's W in R^{d_in x d_out}: dst[c, r] = src[r, c].

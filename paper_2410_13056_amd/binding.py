@@ -37,7 +37,7 @@ EXPORTS = ("cmpq_workspace_bytes", "cmpq_strerror", "cmpq_count_ppm", "cmpq_act_
            "cmpq_kmeans_quantize", "cmpq_pack", "cmpq_dequant_error", "cmpq_kmeans_quantize_job",
            "cmpq_gather_channels", "cmpq_outliers_by_column", "cmpq_lut_matvec", "cmpq_act_stats_norm",
            "cmpq_rtn_quantize", "cmpq_select_by_width", "cmpq_lut_matvec_group", "cmpq_lut4_quantize",
-           "cmpq_pack_with_error", "cmpq_time_kernel")
+           "cmpq_pack_with_error", "cmpq_time_kernel", "cmpq_act_stats_static")
 
 _i64, _i32, _int, _vp, _dbl, _sz = (ctypes.c_int64, ctypes.c_int32, ctypes.c_int, ctypes.c_void_p,
                                     ctypes.c_double, ctypes.c_size_t)
@@ -96,6 +96,7 @@ def lib() -> ctypes.CDLL:
                                            _vp, _i64, _vp, _vp, _vp, _vp, _sz, _vp]
         L.cmpq_kmeans_quantize_job.argtypes = [ctypes.POINTER(KmeansJob), _vp, _sz, _vp]
         L.cmpq_time_kernel.argtypes = [_int, _vp, _vp]
+        L.cmpq_act_stats_static.argtypes = [_vp, _int, _i64, _i64, _i64, _vp, _vp, _int, _vp, _vp]
         L.cmpq_act_stats_norm.argtypes = [_vp, _int, _i64, _i64, _i64, _int, _vp, _vp, _int, _vp, _sz, _vp, _vp]
         L.cmpq_gather_channels.argtypes = [_vp, _int, _i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp]
         L.cmpq_outliers_by_column.argtypes = [_vp, _vp, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
@@ -182,6 +183,15 @@ def act_stats(X: torch.Tensor, acc: torch.Tensor, sumsq: Optional[torch.Tensor],
     _check(lib().cmpq_act_stats(_ptr(X), _dtype(X), n, d_in, ldx, _ptr(acc), _ptr(sumsq),
                                 int(bool(accumulate)), _ptr(buf), buf.numel(), _ptr(status), _stream()),
            "cmpq_act_stats")
+
+
+def act_stats_static(X: torch.Tensor, acc: torch.Tensor, sumsq: Optional[torch.Tensor], accumulate: bool,
+                     status: Optional[torch.Tensor] = None) -> None:
+    """`act_stats` without a workspace: the library's own fixed scratch array (no allocation)."""
+    n, d_in, ldx = _rows(X)
+    _check(lib().cmpq_act_stats_static(_ptr(X), _dtype(X), n, d_in, ldx, _ptr(acc), _ptr(sumsq),
+                                       int(bool(accumulate)), _ptr(status), _stream()),
+           "cmpq_act_stats_static")
 
 
 def transpose(src: torch.Tensor, dst: torch.Tensor) -> None:

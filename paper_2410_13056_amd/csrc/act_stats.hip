@@ -9,6 +9,8 @@
 // the result does not depend on how rows are split beyond the last fp64 bit.
 // Row splits leave fp64 partials in the workspace; a second kernel adds them in
 // split order, which makes the whole reduction reproducible.
+#include <mutex>
+
 #include "common.h"
 
 namespace {
@@ -227,6 +229,59 @@ extern "C" int cmpq_act_stats_norm(const void *X, int dtype, int64_t n, int64_t 
         case CMPQ_NORM_LINF: return launch_act_stats<CMPQ_NORM_LINF>(X, dtype, n, d_in, ldx, acc, stat, accumulate, ws, ws_bytes, status, st);
         default: return launch_act_stats<CMPQ_NORM_L2>(X, dtype, n, d_in, ldx, acc, stat, accumulate, ws, ws_bytes, status, st);
     }
+}
+
+// ---- the same call for callers that cannot allocate ---------------------------------------
+//
+// The row-split partials live in a file-scope device array instead of a caller workspace.
+// Every GPU holds its own copy of the array at its own address; the address is looked up once
+// per device and only that pointer is handed to kernels.
+
+constexpr int64_t kStaticMaxDin = 262144;
+// row splits x d_in never exceeds 2048 x 512 + d_in (see pick_splits: about 2048 workgroups
+// of 512 columns each, rounded up by at most one split)
+constexpr size_t kStaticDoubles = (size_t)2048 * 512 + (size_t)kStaticMaxDin;
+static __device__ __align__(256) double scratch[kStaticDoubles];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+double *g_scratch_ptr[kMaxDevices];  // per device: where that GPU keeps `scratch`
+
+// Device address of `scratch` on the current device; null if the runtime cannot name it.
+double *scratch_on_current_device() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        (void)hipGetLastError();
+        return nullptr;
+    }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        double *p = nullptr;
+        if (hipGetSymbolAddress(reinterpret_cast<void **>(&p), HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+            (void)hipGetLastError();
+            return nullptr;
+        }
+        g_scratch_ptr[dev] = p;
+    }
+    return g_scratch_ptr[dev];
+}
+}  // namespace
+
+extern "C" int cmpq_act_stats_static(const void *X, int dtype, int64_t n, int64_t d_in, int64_t ldx,
+                                     double *acc, float *sumsq, int accumulate, int32_t *status,
+                                     void *stream) {
+    if (!acc || n < 0 || d_in < 0 || (dtype != CMPQ_F16 && dtype != CMPQ_F32)) return CMPQ_EINVAL;
+    if (n > 0 && !X) return CMPQ_EINVAL;
+    if (ldx < d_in) return CMPQ_ESHAPE;
+    if (d_in > kStaticMaxDin) return CMPQ_ESHAPE;  // beyond what the fixed scratch array is sized for
+    if (d_in == 0) return CMPQ_OK;
+    if (ws_act_stats_impl(d_in, n) > sizeof(double) * kStaticDoubles) return CMPQ_ESHAPE;
+    double *ptr = scratch_on_current_device();
+    if (!ptr) return CMPQ_EHIP;
+    return launch_act_stats<CMPQ_NORM_L2>(X, dtype, n, d_in, ldx, acc, sumsq, accumulate, ptr,
+                                          sizeof(double) * kStaticDoubles, status,
+                                          static_cast<hipStream_t>(stream));
 }
 
 extern "C" int cmpq_act_stats(const void *X, int dtype, int64_t n, int64_t d_in, int64_t ldx,

@@ -163,6 +163,12 @@ def test_host_side_argument_errors(L):
     # measurement hook: unknown kernel; arming and disarming touch no GPU state
     assert L.cmpq_time_kernel(-1, fake, fake) == -1 and L.cmpq_time_kernel(5, fake, fake) == -1
     assert L.cmpq_time_kernel(2, fake, fake) == 0 and L.cmpq_time_kernel(2, None, None) == 0
+    # the call without a workspace
+    assert L.cmpq_act_stats_static(fake, 0, 8, 8, 8, None, None, 0, None, None) == -1            # no accumulator
+    assert L.cmpq_act_stats_static(fake, 3, 8, 8, 8, fake, None, 0, None, None) == -1            # dtype
+    assert L.cmpq_act_stats_static(fake, 0, 8, 8, 4, fake, None, 0, None, None) == -2            # ldx < d_in
+    assert L.cmpq_act_stats_static(fake, 0, 8, 262145, 262145, fake, None, 0, None, None) == -2  # beyond the fixed array
+    assert L.cmpq_act_stats_static(None, 0, 0, 0, 0, fake, None, 0, None, None) == 0             # nothing to do
     # the uniform quantizer
     assert L.cmpq_rtn_quantize(fake, 0, 4, 64, 64, fake, 96, fake, fake, fake, None, None, None) == -1    # group no power of two
     assert L.cmpq_rtn_quantize(fake, 0, 4, 64, 64, fake, 4, fake, fake, fake, None, None, None) == -1     # group below 8
