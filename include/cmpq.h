@@ -289,6 +289,17 @@ typedef struct cmpq_kmeans_job {
 int cmpq_kmeans_quantize_job(const cmpq_kmeans_job *job, void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * Introspection for host-side checks: the launch shape the histogram K-means kernel uses for
+ * fp16 channels of d_out weights (d_out a multiple of 4, at most 32768).  shape [6], host, out:
+ * lanes per workgroup, groups of 4 weights per lane, low key bits that name the place inside a
+ * bucket (64 or 128 places; 2^(16 - bits) buckets), bytes of the per-channel place array, bytes
+ * of dynamic LDS per workgroup, bytes of static LDS per workgroup.  Launches nothing.
+ * CMPQ_EINVAL for a null pointer or a length that is no positive multiple of 4, CMPQ_ESHAPE
+ * beyond the limit.
+ */
+int cmpq_kmeans_launch_shape(int64_t d_out, int64_t *shape);
+
+/*
  * Sec. 5.1 / Fig. 4, the stored format: one code matrix per width.  For j < n_set and
  * b = bit_set[j], the channels with bits == b in ascending index form the rows:
  *   chan_idx[j] [counts_host[j]] int32             channel of each row;

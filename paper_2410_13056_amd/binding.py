@@ -37,7 +37,7 @@ EXPORTS = ("cmpq_workspace_bytes", "cmpq_strerror", "cmpq_count_ppm", "cmpq_act_
            "cmpq_kmeans_quantize", "cmpq_pack", "cmpq_dequant_error", "cmpq_kmeans_quantize_job",
            "cmpq_gather_channels", "cmpq_outliers_by_column", "cmpq_lut_matvec", "cmpq_act_stats_norm",
            "cmpq_rtn_quantize", "cmpq_select_by_width", "cmpq_lut_matvec_group", "cmpq_lut4_quantize",
-           "cmpq_pack_with_error", "cmpq_time_kernel", "cmpq_act_stats_static")
+           "cmpq_pack_with_error", "cmpq_time_kernel", "cmpq_act_stats_static", "cmpq_kmeans_launch_shape")
 
 _i64, _i32, _int, _vp, _dbl, _sz = (ctypes.c_int64, ctypes.c_int32, ctypes.c_int, ctypes.c_void_p,
                                     ctypes.c_double, ctypes.c_size_t)
@@ -96,6 +96,7 @@ def lib() -> ctypes.CDLL:
                                            _vp, _i64, _vp, _vp, _vp, _vp, _sz, _vp]
         L.cmpq_kmeans_quantize_job.argtypes = [ctypes.POINTER(KmeansJob), _vp, _sz, _vp]
         L.cmpq_time_kernel.argtypes = [_int, _vp, _vp]
+        L.cmpq_kmeans_launch_shape.argtypes = [_i64, _vp]
         L.cmpq_act_stats_static.argtypes = [_vp, _int, _i64, _i64, _i64, _vp, _vp, _int, _vp, _vp]
         L.cmpq_act_stats_norm.argtypes = [_vp, _int, _i64, _i64, _i64, _int, _vp, _vp, _int, _vp, _sz, _vp, _vp]
         L.cmpq_gather_channels.argtypes = [_vp, _int, _i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp]
@@ -118,6 +119,14 @@ def strerror(code: int) -> str:
 
 def count_ppm(ppm: int, n: int) -> int:
     return int(lib().cmpq_count_ppm(int(ppm), int(n)))
+
+
+def kmeans_launch_shape(d_out: int):
+    """(lanes, groups of 4 per lane, place bits, place-array bytes, dynamic LDS, static LDS) of the
+    histogram K-means kernel for channels of `d_out` fp16 weights."""
+    shape = (_i64 * 6)()
+    _check(lib().cmpq_kmeans_launch_shape(int(d_out), shape), "cmpq_kmeans_launch_shape")
+    return tuple(int(v) for v in shape)
 
 
 def time_kernel(kernel: int, event_begin: Optional[int], event_end: Optional[int]) -> None:

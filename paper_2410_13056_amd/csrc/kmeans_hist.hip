@@ -586,17 +586,46 @@ int launch_variant(const KmArgs &a, hipStream_t s) {
 #ifndef CMPQ_LB256
 #define CMPQ_LB256 7
 #endif
+// The launch shape launch_kmeans_hist picks for a channel length: lanes per workgroup, groups of
+// 4 weights per lane, low bits of a key that name the place inside a bucket.  0 lanes: too long.
+static void hist_variant(int64_t d_out, int &T_out, int &G_out, int &LB_out) {
+    const int64_t groups = d_out / 4;
+    int64_t T = 64;
+    while (T < 512 && T * 8 < groups) T <<= 1;
+    const int64_t per_lane = cdiv(groups, T);
+    T_out = (int)T;
+    LB_out = T == 512 ? CMPQ_LB512 : (T == 256 ? CMPQ_LB256 : 7);
+    if (per_lane > 16) T_out = 0, G_out = 0;
+    else if (per_lane > 8) G_out = 16, LB_out = CMPQ_LB512;
+    else if (per_lane > 4) G_out = 8;
+    else if (per_lane > 2) G_out = 4;
+    else if (per_lane > 1) G_out = 2;
+    else G_out = 1;
+}
+
+extern "C" int cmpq_kmeans_launch_shape(int64_t d_out, int64_t *shape) {
+    if (!shape || d_out < 4 || d_out % 4 != 0) return CMPQ_EINVAL;
+    int T, G, LB;
+    hist_variant(d_out, T, G, LB);
+    if (T == 0) return CMPQ_ESHAPE;
+    shape[0] = T;
+    shape[1] = G;
+    shape[2] = LB;
+    shape[3] = (int64_t)bucket_arr_bytes(d_out, LB);
+    shape[4] = (int64_t)bucket_dyn_lds(d_out, LB);
+    shape[5] = LB == 6 ? (int64_t)sizeof(BucketShared<6>) : (int64_t)sizeof(BucketShared<7>);
+    return CMPQ_OK;
+}
+
 int launch_kmeans_hist(const KmArgs &a, hipStream_t s) {
     // A power-of-two workgroup of at most 512 lanes: up to 32 weights per lane, 64 for the
     // longest channels (two workgroups of 512 share a compute unit where one of 1024
     // would leave it idle at every barrier).
-    const int64_t groups = a.d_out / 4;
-    int64_t T = 64;
-    while (T < 512 && T * 8 < groups) T <<= 1;
-    const int64_t per_lane = cdiv(groups, T);
-    if (per_lane > 16) return CMPQ_ESHAPE;
-    if (per_lane > 8) return launch_variant<16, 512, CMPQ_LB512>(a, s);
-    if (per_lane > 4) {
+    int T, G, LB;
+    hist_variant(a.d_out, T, G, LB);
+    if (T == 0) return CMPQ_ESHAPE;
+    if (G == 16) return launch_variant<16, 512, CMPQ_LB512>(a, s);
+    if (G == 8) {
         switch (T) {
             case 512: return launch_variant<8, 512, CMPQ_LB512>(a, s);
             case 256: return launch_variant<8, 256, CMPQ_LB256>(a, s);
@@ -604,7 +633,7 @@ int launch_kmeans_hist(const KmArgs &a, hipStream_t s) {
             default: return launch_variant<8, 64, 7>(a, s);
         }
     }
-    if (per_lane > 2) return launch_variant<4, 64, 7>(a, s);
-    if (per_lane > 1) return launch_variant<2, 64, 7>(a, s);
+    if (G == 4) return launch_variant<4, 64, 7>(a, s);
+    if (G == 2) return launch_variant<2, 64, 7>(a, s);
     return launch_variant<1, 64, 7>(a, s);
 }

@@ -57,3 +57,75 @@ def test_layers_are_shared_out_largest_first():
     assert [j for _, j in plan[:3]] == [0, 1, 2]
     assert assign_layers(sizes, 1) == [(n, 0) for n, _ in plan]
     assert assign_layers({}, 2) == []
+
+
+def _arrangement_bounds(d_out, keys, kept, shape):
+    """Every index the histogram K-means kernel forms for one channel, recomputed on the host from
+    the launch shape the library reports: bucket counts, padded stretches of the place array, the
+    16-bit prefix tables, the removed-entry bitmap, the scatter cursors / coding table, and the
+    per-lane ownership of weight groups.  Raises AssertionError on any index out of its array."""
+    T, G, LB, arr_bytes, dyn, static = shape
+    buckets = 1 << (16 - LB)
+    n_groups = d_out // 4
+    assert G * T >= n_groups                                    # every group of 4 weights has a lane
+    assert T in (64, 128, 256, 512) and (T // 16) * 16 == T     # T/16 lanes share a boundary: 15 boundaries fit
+    assert max(1, buckets // T) * T >= buckets                  # the prefix pass covers every bucket
+    # dynamic LDS = place array | removed bitmap (whole 16-byte pieces) | one word per bucket
+    n_words = (d_out + 31) >> 5
+    assert dyn == arr_bytes + ((n_words + 3) & ~3) * 4 + buckets * 4
+    assert arr_bytes % 16 == 0
+    assert ((n_groups - 1) >> 3) < n_words                       # bitmap word of the last group
+    b = keys[kept] >> LB
+    assert b.max(initial=0) < buckets
+    n = np.bincount(b, minlength=buckets).astype(np.int64)
+    padded = (n + 3) & ~3
+    start = np.concatenate([[0], np.cumsum(padded)])
+    ncum = np.concatenate([[0], np.cumsum(n)])
+    assert start[-1] <= arr_bytes                               # scatter and scans stay inside the array
+    assert start[-1] < 65536 and ncum[-1] < 65536               # the tables are 16 bits wide
+    per = max(1, buckets // T)
+    packed = (n | (padded << 16)).reshape(-1, per).sum(1)       # a lane's share of the (count, stretch) scan
+    assert int(packed.sum()) < 1 << 32 and int((n.reshape(-1, per).sum(1)).max()) < 65536
+    # scans read whole words of a stretch: [start >> 2, end >> 2), 4 * L at a time, guarded by the end
+    assert np.all(start % 4 == 0) and start[-1] // 4 <= arr_bytes // 4
+    # three workgroups of the longest configured channels (28 672 weights) share a compute unit's 160 KiB
+    total = static + 512 + dyn                                  # + what the compiler adds to the static part
+    if d_out <= 28672:
+        assert 3 * total <= 160 * 1024
+    return int(start[-1]), total
+
+
+def test_kmeans_kernel_indices_stay_in_bounds_on_adversarial_channels():
+    """The two builds of the K-means kernel that faulted on the GPU differed from the shipped one
+    only in register allocation; a cause in the shared index arithmetic would show here.  Every
+    launch shape, its extreme channel lengths, and key layouts that push each table to its
+    limit: all keys in one bucket, every bucket occupied, counts of 1 mod 4 everywhere (most
+    padding), everything removed, the largest channel."""
+    from paper_2410_13056_amd import binding as B
+    B.lib()
+    rng = np.random.default_rng(0)
+    lengths = sorted({4, 8, 252, 256, 260, 512, 1024, 2044, 2048, 2052, 4096, 4100, 5120, 8192, 8196, 11008,
+                      13824, 16384, 16388, 28672, 32764, 32768})
+    worst = 0
+    for d_out in lengths:
+        shape = B.kmeans_launch_shape(d_out)
+        LB = shape[2]
+        buckets = 1 << (16 - LB)
+        layouts = {
+            "one bucket": np.full(d_out, 0x8000 + 5, np.uint16),
+            "every bucket": (np.arange(d_out) % buckets).astype(np.uint16) << LB,
+            "most padding": np.repeat(np.arange(buckets, dtype=np.uint16) << LB, 5)[:d_out]
+            if d_out >= 5 else np.zeros(d_out, np.uint16),
+            "random": rng.integers(0, 65536, d_out).astype(np.uint16),
+            "gaussian": (0x8000 + np.clip(rng.normal(0, 900, d_out), -30000, 30000)).astype(np.uint16),
+        }
+        for name, keys in layouts.items():
+            keys = np.resize(keys, d_out).astype(np.int64)
+            for kept in (np.ones(d_out, bool), np.zeros(d_out, bool), rng.random(d_out) < 0.99):
+                used, total = _arrangement_bounds(d_out, keys, kept, shape)
+                worst = max(worst, total)
+    assert worst <= 64 * 1024                                   # the largest workgroup's LDS
+    with np.testing.assert_raises(Exception):
+        B.kmeans_launch_shape(32772)
+    with np.testing.assert_raises(Exception):
+        B.kmeans_launch_shape(6)
