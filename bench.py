@@ -274,6 +274,9 @@ def main():
     ap.add_argument("--rtn-reps", type=int, default=5,
                     help="repetitions of the block through the uniform-quantizer variant (App. A.2), reported "
                          "beside the headline figure; 0: skip")
+    ap.add_argument("--two-calls", action="store_true",
+                    help="final K-means and stored format + error as two calls (cmpq_kmeans_quantize, then "
+                         "cmpq_pack_with_error) instead of the one call whose coding pass writes them")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (outside the timed region): under "
                          "rocprofv3 --pmc it gives the HBM counters a kernel of known traffic to scale by")
@@ -300,7 +303,7 @@ def main():
     def step(timer=None, join=True):
         return P.quantize_block(weights, acts, layers, wl.bit_set, wl.avg_bits, wl.rho_act_ppm,
                                 wl.rho_q_ppm, wl.iters, ws, with_error=True, status=status, timer=timer,
-                                streams=args.streams, join=join)
+                                streams=args.streams, join=join, fused=not args.two_calls)
 
     if args.calibration_copy:
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
@@ -347,7 +350,8 @@ def main():
     n_serial = max(1, args.serial_steps)
     for _ in range(n_serial):
         o1 = P.quantize_block(weights, acts, layers, wl.bit_set, wl.avg_bits, wl.rho_act_ppm,
-                              wl.rho_q_ppm, wl.iters, ws1, with_error=True, status=status, timer=t1)
+                              wl.rho_q_ppm, wl.iters, ws1, with_error=True, status=status, timer=t1,
+                              fused=not args.two_calls)
         del o1
     serial = t1.totals()
     kern = t1.kernel_totals()
@@ -425,6 +429,8 @@ def main():
         "hbm_kernels": hbm,
         "stages_ms_per_step": {k: round(v[1] / args.steps, 4) for k, v in sorted(stages.items())},
         "streams": args.streams,
+        "final_pass": "two calls: cmpq_kmeans_quantize, cmpq_pack_with_error" if args.two_calls else
+                      "one call: cmpq_kmeans_quantize_job writes the stored format and the error from its coding pass",
         "serial": {
             "note": "same step on one stream, run after the timed region: launches do not overlap; the "
                     "per-kernel figures above come from these steps",
@@ -445,7 +451,8 @@ def main():
         def step_variant(r):
             return P.quantize_block(weights, acts, layers, wl.bit_set, wl.avg_bits, wl.rho_act_ppm,
                                     wl.rho_q_ppm, wl.iters, ws, with_error=True, status=status,
-                                    streams=args.streams, join=False, iters_final_from_prelim=r)
+                                    streams=args.streams, join=False, iters_final_from_prelim=r,
+                                    fused=not args.two_calls)
         line["final_pass_continued_from_prelim"] = continued_final_pass(
             P, torch, step_variant, out, layers, wl, (5, wl.iters), args.continued_reps, args.streams, dev)
     if args.rtn_reps > 0:

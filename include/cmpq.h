@@ -260,7 +260,8 @@ int cmpq_select_by_width(const uint8_t *bits, int64_t d_in, int64_t d_out, const
 /*
  * cmpq_kmeans_quantize with every choice spelled out per call: a plain C structure of
  * pointers and sizes.  The fields up to `status` mean what the arguments of the same name
- * of cmpq_kmeans_quantize mean; that call is this one with algorithm = CMPQ_KMEANS_HISTOGRAM.
+ * of cmpq_kmeans_quantize mean; that call is this one with algorithm = CMPQ_KMEANS_HISTOGRAM
+ * and nothing of the stored format asked for.
  *   algorithm   which implementation runs the Lloyd rounds of Sec. 3.2.1 for fp16 weights with
  *               unit importance.  Both give identical levels and codes: CMPQ_KMEANS_HISTOGRAM
  *               reads cumulative tables of the channel, CMPQ_KMEANS_DIRECT revisits every
@@ -268,8 +269,22 @@ int cmpq_select_by_width(const uint8_t *bits, int64_t d_in, int64_t d_out, const
  *               implementation).  Other inputs (fp32, elem_weight, rows that are not a whole
  *               number of 4 entries) run on the general kernel whatever is named here, and so
  *               does init = CMPQ_INIT_GIVEN with CMPQ_KMEANS_DIRECT (on the histogram kernel).
- * The library reads the structure during the call only.  Errors and workspace as
- * cmpq_kmeans_quantize; CMPQ_EINVAL for a null job or an unknown algorithm.
+ *   bit_set ... err_total   (all null / 0: not asked for.)  Sec. 3.2.2's final quantization is
+ *               followed by the stored format (Sec. 5.1) and the error (App. B.3) of the very
+ *               codes it produces; with these fields set, the call leaves what
+ *               cmpq_pack_with_error(W, ..., codes, bits, centroids, bit_set, n_set,
+ *               counts_host, packed, chan_idx, lut, out_idx, n_out, sumsq, err_ch, err_total)
+ *               would leave after it - packed rows, channel lists and tables bit-identical,
+ *               err_ch / err_total equal up to the order of the fp64 additions - and, where the
+ *               histogram kernel runs, writes them from its coding pass instead of reading
+ *               weights and codes again.  Every one of the fields must then be given as for
+ *               that call (sumsq nullable).  `codes` may be null only in this case and only
+ *               for inputs the histogram kernel takes (fp16, unit importance, rows of whole
+ *               groups of 4 entries, 8-byte aligned; CMPQ_KMEANS_HISTOGRAM): the dense codes
+ *               are then not written at all.
+ * The library reads the structure during the call only.  Errors as cmpq_kmeans_quantize and
+ * cmpq_pack_with_error; CMPQ_EINVAL for a null job, an unknown algorithm, or a stored format
+ * asked for in part.  Workspace: CMPQ_OP_KMEANS.
  */
 typedef struct cmpq_kmeans_job {
     const void *W; /* device, [d_in, d_out] */
@@ -284,6 +299,16 @@ typedef struct cmpq_kmeans_job {
     uint8_t *codes;   /* device, [d_in, d_out] */
     int32_t *status;  /* device, nullable */
     int algorithm;
+    /* the stored format and the error, as in cmpq_pack_with_error */
+    const int32_t *bit_set;     /* host */
+    int n_set;
+    const int64_t *counts_host; /* host */
+    uint32_t *const *packed;    /* host array of device pointers */
+    int32_t *const *chan_idx;   /* host array of device pointers */
+    uint16_t *const *lut;       /* host array of device pointers */
+    const float *sumsq;         /* device, nullable */
+    double *err_ch;             /* device, [d_in] */
+    double *err_total;          /* device, [2] */
 } cmpq_kmeans_job;
 
 int cmpq_kmeans_quantize_job(const cmpq_kmeans_job *job, void *ws, size_t ws_bytes, void *stream);

@@ -59,7 +59,9 @@ class KmeansJob(ctypes.Structure):
     """`cmpq_kmeans_job` of the header, field for field."""
     _fields_ = [("W", _vp), ("dtype", _int), ("d_in", _i64), ("d_out", _i64), ("ldw", _i64), ("bits", _vp),
                 ("out_idx", _vp), ("n_out", _i64), ("elem_weight", _vp), ("iters", _int), ("init", _int),
-                ("centroids", _vp), ("codes", _vp), ("status", _vp), ("algorithm", _int)]
+                ("centroids", _vp), ("codes", _vp), ("status", _vp), ("algorithm", _int),
+                ("bit_set", _vp), ("n_set", _int), ("counts_host", _vp), ("packed", _vp), ("chan_idx", _vp),
+                ("lut", _vp), ("sumsq", _vp), ("err_ch", _vp), ("err_total", _vp)]
 
 
 class CmpqError(RuntimeError):
@@ -264,6 +266,33 @@ def kmeans_quantize(W: torch.Tensor, bits: torch.Tensor, out_idx: Optional[torch
     job = KmeansJob(_ptr(W), _dtype(W), d_in, d_out, ldw, _ptr(bits), _ptr(out_idx), int(n_out),
                     _ptr(elem_weight), int(iters), int(init), _ptr(centroids), _ptr(codes), _ptr(status),
                     int(algorithm))
+    _check(lib().cmpq_kmeans_quantize_job(ctypes.byref(job), _ptr(buf), buf.numel(), _stream()),
+           "cmpq_kmeans_quantize_job")
+
+
+def kmeans_quantize_pack(W: torch.Tensor, bits: torch.Tensor, out_idx: Optional[torch.Tensor], n_out: int,
+                         iters: int, centroids: torch.Tensor, codes: Optional[torch.Tensor],
+                         bit_set: Sequence[int], counts: Sequence[int], packed: Sequence[Optional[torch.Tensor]],
+                         chan_idx: Sequence[Optional[torch.Tensor]], lut: Sequence[Optional[torch.Tensor]],
+                         sumsq: Optional[torch.Tensor], err_ch: torch.Tensor, err_total: torch.Tensor,
+                         ws: Workspace, status: Optional[torch.Tensor] = None, init: int = INIT_QUANTILE,
+                         algorithm: int = KMEANS_HISTOGRAM, elem_weight: Optional[torch.Tensor] = None) -> None:
+    """`cmpq_kmeans_quantize_job` with the stored format and the error asked for: the K-means
+    call followed by what `pack_with_error` leaves, written from the coding pass where the
+    histogram kernel runs.  `codes` may be None there (the dense codes are then not written)."""
+    d_in, d_out, ldw = _rows(W)
+    n = len(bit_set)
+    bs = (_i32 * n)(*bit_set)
+    cn = (_i64 * n)(*counts)
+    pk = (_vp * n)(*[_ptr(t) for t in packed])
+    ci = (_vp * n)(*[_ptr(t) for t in chan_idx])
+    lt = (_vp * n)(*[_ptr(t) for t in lut])
+    buf = ws.get(workspace_bytes(OP_KMEANS, d_in, d_out))
+    c = ctypes.cast
+    job = KmeansJob(_ptr(W), _dtype(W), d_in, d_out, ldw, _ptr(bits), _ptr(out_idx), int(n_out),
+                    _ptr(elem_weight), int(iters), int(init), _ptr(centroids), _ptr(codes), _ptr(status),
+                    int(algorithm), c(bs, _vp), n, c(cn, _vp), c(pk, _vp), c(ci, _vp), c(lt, _vp), _ptr(sumsq),
+                    _ptr(err_ch), _ptr(err_total))
     _check(lib().cmpq_kmeans_quantize_job(ctypes.byref(job), _ptr(buf), buf.numel(), _stream()),
            "cmpq_kmeans_quantize_job")
 

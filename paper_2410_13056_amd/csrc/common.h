@@ -37,6 +37,21 @@ int launch_dequant_error_rows(const void *W, int dtype, int64_t d_in, int64_t d_
 // totals[0] = sum_i sumsq[i] * err_ch[i] (sumsq null: weight 1), totals[1] = sum_i err_ch[i].
 int launch_error_totals(const double *err_ch, const float *sumsq, int64_t d_in, double *totals, hipStream_t s);
 
+// Where the stored format of cmpq_pack goes: per width of the bit set the packed rows, the
+// channel list and the FP16 tables (device pointers; null for a width without channels).
+struct PackPtrs {
+    uint32_t *packed[4];
+    int32_t *chan_idx[4];
+    uint16_t *lut[4];
+    int width[4];
+    int n_set;
+};
+// Checks the host arrays of cmpq_pack and gathers the device pointers.
+int gather_pack_ptrs(int64_t d_in, int64_t d_out, const int32_t *bit_set, int n_set, const int64_t *counts_host,
+                     uint32_t *const *packed, int32_t *const *chan_idx, uint16_t *const *lut, PackPtrs &p);
+// row_of[i] = row of channel i inside its width group (-1: it stores no row); fills the channel lists.
+int launch_pack_index(const uint8_t *bits, int64_t d_in, const PackPtrs &p, int32_t *row_of, hipStream_t s);
+
 // Carves aligned pieces out of the caller's workspace; `need` ends up as the total.
 struct WsCarver {
     char *base;
@@ -137,6 +152,15 @@ __device__ __forceinline__ void block_scan_excl_2xu32(uint32_t a, uint32_t b, ui
     b_total = scratch[33];
     a_excl = scratch[wave] + ai - a;
     b_excl = scratch[17 + wave] + bi - b;
+}
+
+// Four B-bit codes, one per byte of `r`, moved together into the low 4*B bits.
+template <int B>
+__device__ __forceinline__ uint32_t squeeze4(uint32_t r) {
+    constexpr uint32_t m = (1u << B) - 1u, m2 = (1u << (2 * B)) - 1u;
+    uint32_t x = r & (m * 0x01010101u);
+    x = (x | (x >> (8 - B))) & (m2 * 0x00010001u);
+    return (x | (x >> (16 - 2 * B))) & ((1u << (4 * B)) - 1u);
 }
 
 // fp32 bit pattern -> unsigned key with the same order as the value.

@@ -370,9 +370,18 @@ int launch_kmeans(const KmArgs &a, hipStream_t s) {
 
 }  // namespace
 
-size_t cmpq_ws_kmeans(int64_t d_in, int64_t) {
+size_t cmpq_ws_pack_with_error(int64_t d_in);
+
+static size_t ws_kmeans_base(int64_t d_in) {
     // one byte per channel (deferred flags) | d_in + 1 slice offsets of out_idx
     return align_up((size_t)(d_in > 0 ? d_in : 1), 256) + align_up((size_t)(d_in + 1) * sizeof(int32_t), 256);
+}
+
+size_t cmpq_ws_kmeans(int64_t d_in, int64_t) {
+    // ... | each channel's row in its width group | what cmpq_pack_with_error needs when the
+    // stored format is asked for and the histogram kernel does not take the input
+    return ws_kmeans_base(d_in) + align_up((size_t)(d_in > 0 ? d_in : 1) * sizeof(int32_t), 256) +
+           cmpq_ws_pack_with_error(d_in);
 }
 
 extern "C" int cmpq_kmeans_quantize_job(const cmpq_kmeans_job *job, void *ws, size_t ws_bytes, void *stream) {
@@ -384,12 +393,16 @@ extern "C" int cmpq_kmeans_quantize_job(const cmpq_kmeans_job *job, void *ws, si
     if (j.init != CMPQ_INIT_QUANTILE && j.init != CMPQ_INIT_GIVEN) return CMPQ_EINVAL;
     if (j.algorithm != CMPQ_KMEANS_HISTOGRAM && j.algorithm != CMPQ_KMEANS_DIRECT) return CMPQ_EINVAL;
     if (!j.bits || !j.centroids || (j.n_out > 0 && !j.out_idx)) return CMPQ_EINVAL;
-    if (d_in > 0 && d_out > 0 && (!j.W || !j.codes)) return CMPQ_EINVAL;
+    const bool want_format = j.bit_set || j.n_set || j.counts_host || j.packed || j.chan_idx || j.lut || j.err_ch ||
+                             j.err_total || j.sumsq;
+    if (want_format && (!j.bit_set || !j.counts_host || !j.err_ch || !j.err_total)) return CMPQ_EINVAL;
+    if (d_in > 0 && d_out > 0 && (!j.W || (!j.codes && !want_format))) return CMPQ_EINVAL;
     if (j.ldw < d_out) return CMPQ_ESHAPE;
     if (d_out > (j.dtype == CMPQ_F16 ? 32768 : 16384)) return CMPQ_ESHAPE;
     if (d_in > 0 && d_out > ((int64_t)1 << 31) / d_in) return CMPQ_ESHAPE;
     if (d_in >= ((int64_t)1 << 31)) return CMPQ_ESHAPE;
-    if (d_in == 0) return CMPQ_OK;
+    if (d_in == 0)
+        return want_format ? launch_error_totals(j.err_ch, j.sumsq, 0, j.err_total, static_cast<hipStream_t>(stream)) : CMPQ_OK;
     KmArgs a;
     a.W = j.W;
     a.d_in = d_in;
@@ -406,9 +419,37 @@ extern "C" int cmpq_kmeans_quantize_job(const cmpq_kmeans_job *job, void *ws, si
     a.status = j.status;
     a.deferred = nullptr;
     a.seg = nullptr;
+    a.fused = 0;
+    a.row_of = nullptr;
+    a.err_ch = nullptr;
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (!ws || reinterpret_cast<uintptr_t>(ws) % 256 != 0 || ws_bytes < cmpq_ws_kmeans(d_in, d_out))
         return CMPQ_EWORKSPACE;
+    char *ws_row_of = static_cast<char *>(ws) + ws_kmeans_base(d_in);
+    char *ws_tail = ws_row_of + align_up((size_t)d_in * sizeof(int32_t), 256);
+    const bool hist_takes_it = kmeans_fast_eligible(a, j.dtype) && (j.algorithm != CMPQ_KMEANS_DIRECT || a.start_given);
+    if (want_format) {
+        if (d_out > 1 << 20) return CMPQ_ESHAPE;
+        if (const int rc = gather_pack_ptrs(d_in, d_out, j.bit_set, j.n_set, j.counts_host, j.packed, j.chan_idx, j.lut, a.pack))
+            return rc;
+        if (!hist_takes_it) {
+            // the general kernels write dense codes; the stored format follows in a pass of its own
+            if (d_out > 0 && !j.codes) return CMPQ_EINVAL;
+            cmpq_kmeans_job plain = j;
+            plain.bit_set = nullptr, plain.n_set = 0, plain.counts_host = nullptr, plain.packed = nullptr;
+            plain.chan_idx = nullptr, plain.lut = nullptr, plain.sumsq = nullptr, plain.err_ch = nullptr;
+            plain.err_total = nullptr;
+            if (const int rc = cmpq_kmeans_quantize_job(&plain, ws, ws_bytes, stream)) return rc;
+            return cmpq_pack_with_error(j.W, j.dtype, d_in, d_out, j.ldw, j.codes, j.bits, j.centroids, j.bit_set,
+                                        j.n_set, j.counts_host, j.packed, j.chan_idx, j.lut, j.out_idx, j.n_out,
+                                        j.sumsq, j.err_ch, j.err_total, ws_tail, cmpq_ws_pack_with_error(d_in), stream);
+        }
+        int32_t *row_of = reinterpret_cast<int32_t *>(ws_row_of);
+        if (const int rc = launch_pack_index(j.bits, d_in, a.pack, row_of, s)) return rc;
+        a.fused = 1;
+        a.row_of = row_of;
+        a.err_ch = j.err_ch;
+    }
     if (j.n_out > 0) {
         int32_t *seg = reinterpret_cast<int32_t *>(static_cast<char *>(ws) + align_up((size_t)d_in, 256));
         const int rc = launch_segment_offsets(j.out_idx, j.n_out, d_in, d_out, seg, s);
@@ -418,7 +459,10 @@ extern "C" int cmpq_kmeans_quantize_job(const cmpq_kmeans_job *job, void *ws, si
     if (kmeans_fast_eligible(a, j.dtype)) {
         // the bucket kernel takes every channel itself
         // (so does a run from given levels, whichever implementation is named)
-        if (j.algorithm != CMPQ_KMEANS_DIRECT || a.start_given) return launch_kmeans_hist(a, s);
+        if (hist_takes_it) {
+            if (const int rc = launch_kmeans_hist(a, s)) return rc;
+            return a.fused ? launch_error_totals(j.err_ch, j.sumsq, d_in, j.err_total, s) : CMPQ_OK;
+        }
         a.deferred = static_cast<uint8_t *>(ws);
         const int rc = launch_kmeans_fast(a, s);
         if (rc != CMPQ_OK) return rc;

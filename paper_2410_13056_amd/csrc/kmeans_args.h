@@ -20,10 +20,17 @@ struct KmArgs {
     uint8_t *deferred;
     // seg[i]..seg[i+1]: the slice of out_idx inside channel i (null when n_out is 0).
     const int32_t *seg;
+    // Stored format and error written by the coding pass of the bucket kernel (Sec. 5.1;
+    // App. B.3) instead of by a pass of their own: where the rows go, the row of each channel
+    // inside its width group, and the per-channel squared error.  Unused unless `fused`.
+    int fused;
+    PackPtrs pack;
+    const int32_t *row_of;
+    double *err_ch;
 };
 
 // Histogram k-means (kmeans_hist.hip) and fixed-point brute-force k-means
 // (kmeans_fast.hip), both for fp16 weights with unit importance.
-int launch_kmeans_hist(const KmArgs &a, hipStream_t s);
+int launch_kmeans_hist(const KmArgs &a, hipStream_t s);  // honours a.fused
 int launch_kmeans_fast(const KmArgs &a, hipStream_t s);
 bool kmeans_fast_eligible(const KmArgs &a, int dtype);

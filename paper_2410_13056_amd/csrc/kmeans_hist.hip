@@ -60,7 +60,14 @@ struct BucketShared {
     uint32_t scan32[17];
     unsigned long long scan64[17];
     int seg_lo, n_excl;
+    double cent64[CMPQ_KMAX];       // final levels by level index, as the error sum reads them
 };
+
+// Two order keys in one word -> the two fp16 patterns they stand for (inverse of keys_of_half2).
+__device__ __forceinline__ uint32_t halves_of_keys2(uint32_t kk) {
+    const uint32_t pos = (kk >> 15) & 0x00010001u;  // key of a non-negative value: only the sign bit was flipped
+    return kk ^ (0xffffffffu ^ __umul24(pos, 0x7fffu));
+}
 
 template <int G>
 __device__ __forceinline__ uint32_t elem_key(const uint32_t (&keys)[2 * G], int k, int e) {
@@ -141,10 +148,116 @@ __device__ __forceinline__ void scatter_places(const uint32_t (&keys)[2 * G], co
     }
 }
 
+// The coding pass with the stored format and the error folded in (Sec. 5.1; App. B.3): every
+// lane takes groups g = tid, tid + T, ... of 4 weights (fetched again: the place array cannot
+// give a weight's position back), finds their codes, adds (w - level)^2 in fp64 - nothing for an
+// entry of O_q, whose FP16 weight is restored - and puts the group's 4 * B code bits into the
+// channel's row of the bit stream, which is built in the place array the rounds no longer need.
+// A rolled loop: its fp64 temporaries would not fit the register budget of the unrolled one.
+// Returns the lane's share of the error.  Contains a barrier: called by all threads.
 template <int G, int K, int T, int LB>
+__device__ __forceinline__ double coding_pass_fused(const KmArgs &a, int64_t i, BucketShared<LB> &sm,
+                                                    unsigned char *arr, uint32_t *tbl, const uint32_t *removed,
+                                                    int n_ex, int n_groups, int par) {
+    constexpr int kLowBits = LB, kLows = 1 << LB, kBuckets = 1 << (16 - LB);
+    constexpr int B = K == 2 ? 1 : (K == 4 ? 2 : (K == 8 ? 3 : 4));
+    const int tid = threadIdx.x, lane = tid & 63;
+    const uint32_t tk_fin = sm.tk[par][lane & (CMPQ_KMAX - 1)];
+    uint32_t thr[CMPQ_KMAX];
+#pragma unroll
+    for (int p = 0; p < K - 1; ++p) thr[p] = (uint32_t)__builtin_amdgcn_readlane((int)tk_fin, p);
+    if (tid < CMPQ_KMAX) sm.cent64[tid] = (double)sm.cent[tid];
+    // bytes of the row that the groups below do not write: zero, up to whole words
+    const int row_bytes = (int)(((int64_t)a.d_out * B + 31) / 32) * 4;
+    const int coded = B == 4 ? 2 * n_groups : (B == 2 ? n_groups : (B == 3 ? 3 * ((n_groups + 1) >> 1) : (n_groups + 1) >> 1));
+    for (int x = coded + tid; x < row_bytes; x += T) arr[x] = 0;
+    // a table over the buckets replaces the search where there are many levels: a bucket with no
+    // boundary inside has one code; with one boundary, a code on either side of the boundary's
+    // place; with more (rare) the entry sends the weight to the search
+    constexpr bool kTable = K >= 8 && G * T >= 2 * kBuckets;  // worth it for long channels only
+    if constexpr (kTable) {
+        for (int bk = tid; bk < kBuckets; bk += T) {
+            const uint32_t first = (uint32_t)bk << kLowBits;
+            const uint32_t p0 = cell_of<K>(first, thr), p1 = cell_of<K>(first + kLows - 1, thr);
+            uint32_t ent = sm.code_of[p0] | (sm.code_of[p1] << 4);
+            if (p1 == p0) {
+                ent |= 0xff00u;  // no place lies above this one
+            } else {
+                ent |= (sm.tk[par][p0] & (kLows - 1)) << 8;
+                if (p1 > p0 + 1) ent |= 0x10000u;
+            }
+            tbl[bk] = ent;
+        }
+    }
+    __syncthreads();
+    const uint2 *wrow = reinterpret_cast<const uint2 *>(static_cast<const __half *>(a.W) + i * a.ldw);
+    uint32_t *crow = a.codes ? reinterpret_cast<uint32_t *>(a.codes + i * a.d_out) : nullptr;
+    double err = 0.0;
+    const int n_steps = (n_groups + T - 1) / T;  // the same for every lane: the neighbour exchange below needs all of them
+    uint2 raw = make_uint2(0, 0);
+    if (tid < n_groups) raw = wrow[tid];
+#pragma unroll 1
+    for (int step = 0; step < n_steps; ++step) {
+        const int g = step * T + tid;
+        const bool in = g < n_groups;
+        const uint2 cur = raw;
+        if (g + T < n_groups) raw = wrow[g + T];  // the next group's weights, ahead of time
+        const uint32_t kk[2] = {keys_of_half2(cur.x), keys_of_half2(cur.y)};
+        uint32_t word = 0;  // the 4 codes, one per byte
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const uint32_t key = (kk[e >> 1] >> (16 * (e & 1))) & 0xffffu;
+            uint32_t code;
+            if constexpr (kTable) {
+                const uint32_t ent = tbl[key >> kLowBits];
+                code = (key & (kLows - 1)) > ((ent >> 8) & 0xffu) ? (ent >> 4) & 15u : ent & 15u;
+                if (ent & 0x10000u) code = sm.code_of[cell_of<K>(key, thr)];
+            } else {
+                code = sm.code_of[cell_of<K>(key, thr)];
+            }
+            word |= code << (8 * e);
+        }
+        if (in && crow) crow[g] = word;
+        uint32_t kept = in ? 0xfu : 0u;
+        if (n_ex > 0 && in) kept = ~(removed[g >> 3] >> ((g & 7) * 4)) & 0xfu;
+        const uint32_t hw[2] = {cur.x, cur.y};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float w = __half2float(__ushort_as_half((unsigned short)(hw[e >> 1] >> (16 * (e & 1)))));
+            double d = (double)w - sm.cent64[(word >> (8 * e)) & 15u];
+            d = ((kept >> e) & 1u) ? d : 0.0;
+            err = fma(d, d, err);
+        }
+        const uint32_t f = in ? squeeze4<B>(word) : 0u;
+        if constexpr (B == 4) {
+            if (in) reinterpret_cast<uint16_t *>(arr)[g] = (uint16_t)f;
+        } else if constexpr (B == 2) {
+            if (in) arr[g] = (unsigned char)f;
+        } else {
+            // 12 (4) bits: an even lane joins its own with those of the lane above it (the next
+            // group: T is even, so a lane's groups keep its parity) into 3 (1) whole bytes
+            const uint32_t v = f | (row_from_above(f) << (4 * B));
+            if (in && (tid & 1) == 0) {
+                if constexpr (B == 3) {
+                    unsigned char *dst = arr + 3 * (g >> 1);
+                    dst[0] = (unsigned char)v;
+                    dst[1] = (unsigned char)(v >> 8);
+                    dst[2] = (unsigned char)(v >> 16);
+                } else {
+                    arr[g >> 1] = (unsigned char)v;
+                }
+            }
+        }
+    }
+    __syncthreads();
+    return err;
+}
+
+template <int G, int K, int T, int LB, bool FUSED>
 __device__ __forceinline__ void lloyd_bucket(const KmArgs &a, int64_t i, BucketShared<LB> &sm,
-                                             const unsigned char *arr, uint32_t *tbl,
-                                             const uint32_t (&keys)[2 * G], int n_groups, uint32_t M) {
+                                             unsigned char *arr, uint32_t *tbl, const uint32_t *removed, int n_ex,
+                                             const uint32_t (&keys)[2 * G], int n_groups, uint32_t M,
+                                             double &err_out) {
     constexpr int L = T / 16;  // lanes that share one boundary in a round
     constexpr int kLowBits = LB, kLows = 1 << LB, kBuckets = 1 << (16 - LB);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -318,6 +431,10 @@ __device__ __forceinline__ void lloyd_bucket(const KmArgs &a, int64_t i, BucketS
     }
 
     __builtin_amdgcn_s_setprio(0);
+    if constexpr (FUSED) {
+        err_out = coding_pass_fused<G, K, T, LB>(a, i, sm, arr, tbl, removed, n_ex, n_groups, par);
+        return;
+    }
     // ---- final coding: 4 codes per lane and store.  Every wavefront fetches the final
     //      boundaries and the position -> level map left by wavefront 0.
     const uint32_t tk_fin = sm.tk[par][lane & (CMPQ_KMAX - 1)];
@@ -417,7 +534,8 @@ __device__ __forceinline__ void lloyd_bucket(const KmArgs &a, int64_t i, BucketS
 // Occupancy: 6 wavefronts per SIMD for the 16-group variant (77 registers: 3 workgroups of
 // 512 lanes per compute unit, which is also what LDS allows at d_out = 28 672), 7 for the
 // shorter multi-wavefront variants (at most 72 registers: 7 workgroups of 256 lanes).
-template <int G, int T, int LB>
+// FUSED: the coding pass also writes the channel's row of the stored format and its squared error.
+template <int G, int T, int LB, bool FUSED>
 __global__ __launch_bounds__(T) __attribute__((amdgpu_waves_per_eu(6, 7))) void kmeans_bucket_kernel(KmArgs a) {
     constexpr int kBuckets = 1 << (16 - LB);
     // dynamic LDS: places of the kept weights, ordered by bucket (a byte each; the bucket
@@ -430,11 +548,27 @@ __global__ __launch_bounds__(T) __attribute__((amdgpu_waves_per_eu(6, 7))) void 
     const int d_out = (int)a.d_out, n_groups = d_out >> 2;
     const int b = a.bits[i];
     float *crow = a.centroids + i * CMPQ_KMAX;
-    if (b < 1 || b > 4) {  // a channel of O_act: no levels, no codes
+    if (b < 1 || b > 4) {  // a channel of O_act: no levels, no codes, no row; kept whole in FP16: no error
         if (tid < CMPQ_KMAX) crow[tid] = INFINITY;
-        uint32_t *c32 = reinterpret_cast<uint32_t *>(a.codes + i * a.d_out);
-        for (int g = tid; g < n_groups; g += T) c32[g] = 0;
+        if (a.codes) {
+            uint32_t *c32 = reinterpret_cast<uint32_t *>(a.codes + i * a.d_out);
+            for (int g = tid; g < n_groups; g += T) c32[g] = 0;
+        }
+        if (FUSED && tid == 0) a.err_ch[i] = 0.0;
         return;
+    }
+    // where the channel's row of the stored format goes
+    uint32_t *row_dst = nullptr;
+    uint16_t *lut_dst = nullptr;
+    const int row_words = (int)(((int64_t)d_out * b + 31) / 32);
+    if constexpr (FUSED) {
+        const int32_t row = a.row_of[i];
+        int j = 0;
+        while (j < a.pack.n_set && a.pack.width[j] != b) ++j;
+        if (row >= 0 && j < a.pack.n_set) {
+            if (a.pack.packed[j]) row_dst = a.pack.packed[j] + (int64_t)row * row_words;
+            if (a.pack.lut[j]) lut_dst = a.pack.lut[j] + ((int64_t)row << b);
+        }
     }
     const int K = 1 << b;
     unsigned char *arr = dyn;
@@ -478,8 +612,15 @@ __global__ __launch_bounds__(T) __attribute__((amdgpu_waves_per_eu(6, 7))) void 
         // gets defined outputs (all levels 0, all codes 0) instead of a clustering of NaNs
         if (tid == 0 && a.status) atomicOr(a.status, CMPQ_STATUS_NONFINITE);
         if (tid < CMPQ_KMAX) crow[tid] = tid < K ? 0.0f : INFINITY;
-        uint32_t *c32 = reinterpret_cast<uint32_t *>(a.codes + i * a.d_out);
-        for (int g = tid; g < n_groups; g += T) c32[g] = 0;
+        if (a.codes) {
+            uint32_t *c32 = reinterpret_cast<uint32_t *>(a.codes + i * a.d_out);
+            for (int g = tid; g < n_groups; g += T) c32[g] = 0;
+        }
+        if constexpr (FUSED) {  // the row of all-zero codes, the table of zero levels, no number for the error
+            if (row_dst) for (int w = tid; w < row_words; w += T) row_dst[w] = 0;
+            if (lut_dst && tid < K) lut_dst[tid] = 0;
+            if (tid == 0) a.err_ch[i] = __longlong_as_double(0x7ff8000000000000ll);
+        }
         return;
     }
     const int n_ex = sm.n_excl;
@@ -546,13 +687,32 @@ __global__ __launch_bounds__(T) __attribute__((amdgpu_waves_per_eu(6, 7))) void 
     else scatter_places<G, T, LB, false>(keys, removed, cursor, arr, n_groups);
     __syncthreads();
 
+    double err = 0.0;
     switch (K) {
-        case 2: lloyd_bucket<G, 2, T, LB>(a, i, sm, arr, cursor, keys, n_groups, M); break;
-        case 4: lloyd_bucket<G, 4, T, LB>(a, i, sm, arr, cursor, keys, n_groups, M); break;
-        case 8: lloyd_bucket<G, 8, T, LB>(a, i, sm, arr, cursor, keys, n_groups, M); break;
-        default: lloyd_bucket<G, 16, T, LB>(a, i, sm, arr, cursor, keys, n_groups, M); break;
+        case 2: lloyd_bucket<G, 2, T, LB, FUSED>(a, i, sm, arr, cursor, removed, n_ex, keys, n_groups, M, err); break;
+        case 4: lloyd_bucket<G, 4, T, LB, FUSED>(a, i, sm, arr, cursor, removed, n_ex, keys, n_groups, M, err); break;
+        case 8: lloyd_bucket<G, 8, T, LB, FUSED>(a, i, sm, arr, cursor, removed, n_ex, keys, n_groups, M, err); break;
+        default: lloyd_bucket<G, 16, T, LB, FUSED>(a, i, sm, arr, cursor, removed, n_ex, keys, n_groups, M, err); break;
     }
     if (tid < CMPQ_KMAX) crow[tid] = tid < K ? sm.cent[tid] : INFINITY;
+    if constexpr (FUSED) {
+        // the row is complete in the place array (the coding pass ends with a barrier): copy it
+        // out, the table in FP16 beside it, and add the lanes' error sums in a fixed order
+        if (row_dst) {
+            const uint32_t *stage = reinterpret_cast<const uint32_t *>(arr);
+            for (int w = tid; w < row_words; w += T) row_dst[w] = stage[w];
+        }
+        if (lut_dst && tid < K) lut_dst[tid] = __half_as_ushort(__float2half_rn(sm.cent[tid]));
+        err = wave_sum_f64(err);
+        double *red = reinterpret_cast<double *>(sm.scan64);
+        if ((tid & 63) == 0) red[tid >> 6] = err;
+        __syncthreads();
+        if (tid == 0) {
+            double t = 0.0;
+            for (int w = 0; w < T / CMPQ_WAVE; ++w) t += red[w];
+            a.err_ch[i] = t;
+        }
+    }
 }
 
 size_t bucket_dyn_lds(int64_t d_out, int lb) {
@@ -564,7 +724,7 @@ size_t bucket_dyn_lds(int64_t d_out, int lb) {
 
 template <int G, int T, int LB>
 int launch_variant(const KmArgs &a, hipStream_t s) {
-    auto kern = kmeans_bucket_kernel<G, T, LB>;
+    auto kern = a.fused ? kmeans_bucket_kernel<G, T, LB, true> : kmeans_bucket_kernel<G, T, LB, false>;
     const size_t lds = bucket_dyn_lds(a.d_out, LB);
     if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {

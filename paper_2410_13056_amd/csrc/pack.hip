@@ -9,14 +9,6 @@
 
 namespace {
 
-struct PackPtrs {
-    uint32_t *packed[4];
-    int32_t *chan_idx[4];
-    uint16_t *lut[4];
-    int width[4];
-    int n_set;
-};
-
 // row_of[i] = row of channel i inside its width group, -1 when it stores no row.
 __global__ __launch_bounds__(1024) void pack_index_kernel(const uint8_t *__restrict__ bits,
                                                           int64_t d_in, PackPtrs p,
@@ -156,15 +148,6 @@ __device__ __forceinline__ void pe_fetch(PeStep<TW> &st, const TW *__restrict__ 
         st.raw[q] = *reinterpret_cast<const uint4 *>(wrow + o0 + PeStep<TW>::kPer * q);
 }
 
-// Four B-bit codes, one per byte of `r`, moved together into the low 4*B bits.
-template <int B>
-__device__ __forceinline__ uint32_t squeeze4(uint32_t r) {
-    constexpr uint32_t m = (1u << B) - 1u, m2 = (1u << (2 * B)) - 1u;
-    uint32_t x = r & (m * 0x01010101u);
-    x = (x | (x >> (8 - B))) & (m2 * 0x00010001u);
-    return (x | (x >> (16 - 2 * B))) & ((1u << (4 * B)) - 1u);
-}
-
 // The 32 codes of r[0..8), four to a word, as B whole words of the bit stream.
 template <int B>
 __device__ __forceinline__ void pack32_words(const uint32_t (&r)[8], uint32_t (&w)[B]) {
@@ -282,7 +265,8 @@ __global__ __launch_bounds__(kPeT) void pack_error_kernel(
     }
 }
 
-// Checks the host arrays of cmpq_pack and gathers the device pointers.
+}  // namespace
+
 int gather_pack_ptrs(int64_t d_in, int64_t d_out, const int32_t *bit_set, int n_set, const int64_t *counts_host,
                      uint32_t *const *packed, int32_t *const *chan_idx, uint16_t *const *lut, PackPtrs &p) {
     if (n_set < 1 || n_set > 4) return CMPQ_EBUDGET;
@@ -308,7 +292,11 @@ int gather_pack_ptrs(int64_t d_in, int64_t d_out, const int32_t *bit_set, int n_
     return CMPQ_OK;
 }
 
-}  // namespace
+int launch_pack_index(const uint8_t *bits, int64_t d_in, const PackPtrs &p, int32_t *row_of, hipStream_t s) {
+    pack_index_kernel<<<1, 1024, 0, s>>>(bits, d_in, p, row_of);
+    CMPQ_LAUNCH_CHECK();
+    return CMPQ_OK;
+}
 
 size_t cmpq_ws_pack(int64_t d_in) { return align_up((size_t)(d_in > 0 ? d_in : 1) * sizeof(int32_t), 256); }
 

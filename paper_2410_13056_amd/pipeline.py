@@ -127,7 +127,8 @@ def _channels_and_widths(sumsq, d_in, bit_set, avg_bits, rho_act_ppm, ws, timer)
 
 def _after_first_pass(Wt, sumsq, bit_set, counts, act_idx, chan_mask, bits, cent1, codes1, rho_q_ppm, iters,
                       ws, score, with_error, keep_prelim, status, timer,
-                      iters_final_from_prelim: Optional[int] = None, oq_per_channel: bool = False) -> LayerResult:
+                      iters_final_from_prelim: Optional[int] = None, oq_per_channel: bool = False,
+                      fused: bool = True) -> LayerResult:
     """O_q from the preliminary quantization, the final quantization, the stored format."""
     dev = Wt.device
     d_in, d_out = Wt.shape
@@ -142,18 +143,7 @@ def _after_first_pass(Wt, sumsq, bit_set, counts, act_idx, chan_mask, bits, cent
     with _stage(timer, "outlier_weights"):
         B.extract_weight_outliers(Wt, cent1, codes1, bits, k_each, out_idx, out_val, ws, score,
                                   B.SCOPE_CHANNEL if oq_per_channel else B.SCOPE_LAYER)
-    # final quantization of W - O
-    codes = torch.empty((d_in, d_out), dtype=torch.uint8, device=dev)
-    if iters_final_from_prelim is None:
-        cent = torch.empty((d_in, B.KMAX), dtype=torch.float32, device=dev)
-        with _stage(timer, "kmeans_final"):
-            B.kmeans_quantize(Wt, bits, out_idx, k_q, None, iters, cent, codes, ws, status)
-    else:  # variant: continue from the preliminary levels (a copy; the call updates it in place)
-        cent = cent1.clone()
-        with _stage(timer, "kmeans_final"):
-            B.kmeans_quantize(Wt, bits, out_idx, k_q, None, iters_final_from_prelim, cent, codes, ws, status,
-                              init=B.INIT_GIVEN)
-    # stored format
+    # stored format: one block of packed rows, channel list and FP16 tables per width
     packed, chan_idx, lut = [], [], []
     for b, c in zip(bit_set, counts):
         if c == 0:
@@ -162,13 +152,28 @@ def _after_first_pass(Wt, sumsq, bit_set, counts, act_idx, chan_mask, bits, cent
         packed.append(torch.empty((c, (d_out * b + 31) // 32), dtype=torch.int32, device=dev))
         chan_idx.append(torch.empty(c, dtype=torch.int32, device=dev))
         lut.append(torch.empty((c, 1 << b), dtype=torch.float16, device=dev))
+    # final quantization of W - O
+    codes = torch.empty((d_in, d_out), dtype=torch.uint8, device=dev)
+    given = iters_final_from_prelim is not None
+    # variant: continue from the preliminary levels (a copy; the call updates it in place)
+    cent = cent1.clone() if given else torch.empty((d_in, B.KMAX), dtype=torch.float32, device=dev)
+    rounds, init = (iters_final_from_prelim, B.INIT_GIVEN) if given else (iters, B.INIT_QUANTILE)
     res = LayerResult(d_in, d_out, tuple(bit_set), counts, sumsq, act_idx, chan_mask, bits, cent, codes,
                       out_idx, out_val, packed, chan_idx, lut, W_t=Wt)
     if keep_prelim:
         res.centroids_prelim, res.codes_prelim = cent1, codes1
-    if with_error:      # stored format and error in one pass over the codes
+    if with_error:
         res.err_ch = torch.empty(d_in, dtype=torch.float64, device=dev)
         res.err_total = torch.empty(2, dtype=torch.float64, device=dev)
+    if with_error and fused:
+        # one call: the coding pass of the final K-means writes the stored format and the error
+        with _stage(timer, "kmeans_final"):
+            B.kmeans_quantize_pack(Wt, bits, out_idx, k_q, rounds, cent, codes, bit_set, counts, packed, chan_idx,
+                                   lut, sumsq, res.err_ch, res.err_total, ws, status, init=init)
+        return res
+    with _stage(timer, "kmeans_final"):
+        B.kmeans_quantize(Wt, bits, out_idx, k_q, None, rounds, cent, codes, ws, status, init=init)
+    if with_error:      # stored format and error in one pass over the codes
         with _stage(timer, "pack_with_error"):
             B.pack_with_error(Wt, codes, bits, cent, bit_set, counts, packed, chan_idx, lut, out_idx, k_q, sumsq,
                               res.err_ch, res.err_total, ws)
@@ -184,12 +189,17 @@ def quantize_layer(W: torch.Tensor, sumsq: torch.Tensor, bit_set: Sequence[int],
                    with_error: bool = False, keep_prelim: bool = False,
                    status: Optional[torch.Tensor] = None, transposed: bool = False,
                    timer: Optional[StageTimer] = None,
-                   iters_final_from_prelim: Optional[int] = None, oq_per_channel: bool = False) -> LayerResult:
+                   iters_final_from_prelim: Optional[int] = None, oq_per_channel: bool = False,
+                   fused: bool = True) -> LayerResult:
     """Quantizes one layer.  `W` is the framework's [d_out, d_in] weight (or already
     d_in x d_out with ``transposed=True``); `sumsq` comes from `activation_stats`.
 
     ``oq_per_channel`` (a variant; Sec. 3.2.2 selects over the layer): O_q takes
     ``round_half_up(rho_q * d_out)`` entries in every channel outside O_act.
+
+    ``fused`` (with ``with_error``): the final K-means writes the stored format and the error
+    from its coding pass (`cmpq_kmeans_quantize_job`); ``fused=False`` runs `cmpq_kmeans_quantize`
+    and `cmpq_pack_with_error` one after the other.  Same results.
 
     ``iters_final_from_prelim`` (a variant; the paper names no start for either K-means of
     Sec. 3.2.2): the final quantization starts from the levels of the preliminary one and runs
@@ -206,7 +216,7 @@ def quantize_layer(W: torch.Tensor, sumsq: torch.Tensor, bit_set: Sequence[int],
         B.kmeans_quantize(Wt, bits, None, 0, None, iters, cent1, codes1, ws, status)
     return _after_first_pass(Wt, sumsq, bit_set, counts, act_idx, chan_mask, bits, cent1, codes1, rho_q_ppm,
                              iters, ws, score, with_error, keep_prelim, status, timer, iters_final_from_prelim,
-                             oq_per_channel)
+                             oq_per_channel, fused)
 
 
 @dataclasses.dataclass
@@ -247,7 +257,7 @@ def quantize_layer_from_cache(cache: WidthCache, sumsq: torch.Tensor, avg_bits: 
                               with_error: bool = False, keep_prelim: bool = False,
                               status: Optional[torch.Tensor] = None,
                               timer: Optional[StageTimer] = None,
-                              iters_final_from_prelim: Optional[int] = None) -> LayerResult:
+                              iters_final_from_prelim: Optional[int] = None, fused: bool = True) -> LayerResult:
     """`quantize_layer` for another average width (or other outlier fractions) of a layer
     whose per-width runs are kept: the first K-means pass is a row-wise choice among them,
     everything after it runs as usual.  Same results as `quantize_layer`, bit for bit."""
@@ -262,7 +272,7 @@ def quantize_layer_from_cache(cache: WidthCache, sumsq: torch.Tensor, avg_bits: 
         B.select_by_width(bits, cache.bit_set, cache.centroids, cache.codes, cent1, codes1)
     return _after_first_pass(cache.W_t, sumsq, cache.bit_set, counts, act_idx, chan_mask, bits, cent1, codes1,
                              rho_q_ppm, cache.iters, ws, score, with_error, keep_prelim, status, timer,
-                             iters_final_from_prelim)
+                             iters_final_from_prelim, False, fused)
 
 
 def tables_in_4_bits(r: LayerResult, ws: Optional[B.Workspace] = None, with_error: bool = False,
@@ -456,7 +466,8 @@ def quantize_block(weights: Dict[str, torch.Tensor], acts: Dict[str, torch.Tenso
                    avg_bits: float, rho_act_ppm: int, rho_q_ppm: int, iters: int,
                    ws=None, with_error: bool = False, status: Optional[torch.Tensor] = None,
                    timer: Optional[StageTimer] = None, streams: int = 1,
-                   join: bool = True, iters_final_from_prelim: Optional[int] = None) -> Dict[str, LayerResult]:
+                   join: bool = True, iters_final_from_prelim: Optional[int] = None,
+                   fused: bool = True) -> Dict[str, LayerResult]:
     """One pass of the whole path over a decoder block: statistics once per distinct
     input, then every linear layer.  `layers` lists (name, x_key) pairs.
 
@@ -482,7 +493,7 @@ def quantize_block(weights: Dict[str, torch.Tensor], acts: Dict[str, torch.Tenso
                 stats[x_key] = activation_stats(acts[x_key], ws, status=status, timer=timer)[1]
             out[name] = quantize_layer(weights[name], stats[x_key], bit_set, avg_bits, rho_act_ppm,
                                        rho_q_ppm, iters, ws, with_error=with_error, status=status,
-                                       timer=timer, iters_final_from_prelim=iters_final_from_prelim)
+                                       timer=timer, iters_final_from_prelim=iters_final_from_prelim, fused=fused)
         return out
     if ws is None:
         ws = [B.Workspace(dev) for _ in range(streams)]
@@ -510,7 +521,7 @@ def quantize_block(weights: Dict[str, torch.Tensor], acts: Dict[str, torch.Tenso
             results[name] = quantize_layer(weights[name], sumsq, bit_set, avg_bits, rho_act_ppm,
                                            rho_q_ppm, iters, ws[j], with_error=with_error,
                                            status=status, timer=timer,
-                                           iters_final_from_prelim=iters_final_from_prelim)
+                                           iters_final_from_prelim=iters_final_from_prelim, fused=fused)
     if join:
         for st in side:
             main.wait_stream(st)

@@ -150,7 +150,7 @@ def test_host_side_argument_errors(L):
     # the job form of the K-means call
     from paper_2410_13056_amd.binding import KmeansJob
     def job(**kw):
-        j = KmeansJob(256, 0, 4, 64, 64, 256, None, 0, None, 5, 0, 256, 256, None, 0)
+        j = KmeansJob(256, 0, 4, 64, 64, 256, None, 0, None, 5, 0, 256, 256, None, 0)   # no stored format asked for
         for k, v in kw.items():
             setattr(j, k, v)
         return ctypes.byref(j)
@@ -160,6 +160,14 @@ def test_host_side_argument_errors(L):
     assert L.cmpq_kmeans_quantize_job(job(d_out=40000, ldw=40000), fake, 1 << 20, None) == -2
     assert L.cmpq_kmeans_quantize_job(job(), fake, 16, None) == -5
     assert L.cmpq_kmeans_quantize_job(job(d_in=0), None, 0, None) == 0
+    assert L.cmpq_kmeans_quantize_job(job(codes=None), fake, 1 << 20, None) == -1               # codes only optional with the stored format
+    assert L.cmpq_kmeans_quantize_job(job(err_ch=256), fake, 1 << 20, None) == -1               # the stored format asked for in part
+    bs3, one3 = (i32 * 3)(2, 3, 4), (i64 * 3)(1, 1, 1)
+    nul3 = (ctypes.c_void_p * 3)(None, None, None)
+    addr = lambda x: ctypes.cast(x, ctypes.c_void_p)
+    assert L.cmpq_kmeans_quantize_job(job(bit_set=addr(bs3), n_set=3, counts_host=addr(one3), packed=addr(nul3),
+                                          chan_idx=addr(nul3), lut=addr(nul3), err_ch=256, err_total=256),
+                                      fake, 1 << 20, None) == -1                                # counts without arrays
     # measurement hook: unknown kernel; arming and disarming touch no GPU state
     assert L.cmpq_time_kernel(-1, fake, fake) == -1 and L.cmpq_time_kernel(5, fake, fake) == -1
     assert L.cmpq_time_kernel(2, fake, fake) == 0 and L.cmpq_time_kernel(2, None, None) == 0

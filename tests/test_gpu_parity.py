@@ -605,6 +605,121 @@ def test_dequant_error_parity(env, dtype):
         assert (err == 0).all() and (tot == 0).all()
 
 
+@pytest.mark.parametrize("d_out", [4, 36, 252, 1000, 2052, 4100, 8192, 11008, 16388, 28672])
+@pytest.mark.parametrize("bit_set", [(1, 2, 3, 4), (2, 3)])
+def test_kmeans_with_stored_format_from_its_coding_pass(env, d_out, bit_set):
+    """The job form of the K-means call with the stored format and the error asked for (the
+    coding pass of the histogram kernel writes them): levels and codes identical to the plain
+    call and to the oracle, packed rows / channel lists / tables bit for bit those of
+    cmpq_pack_with_error and of the oracle, errors to 1e-12 - for every launch shape of the
+    kernel, every width, channels of O_act in between, with and without removed entries, with
+    the dense codes written or left out, and from given starting levels."""
+    B, ws, orc = env["B"], env["ws"], env["orc"]
+    rng = np.random.default_rng(d_out * 7 + len(bit_set))
+    d_in = 24 if d_out > 4096 else 40
+    W = rng.normal(0, 0.02, (d_in, d_out))
+    W[rng.random(W.shape) < 0.01] *= 10
+    W = W.astype(np.float16)
+    bits = rng.choice(np.array(bit_set + (16,), np.uint8), d_in)
+    bits[:len(bit_set)] = bit_set                                   # every width present
+    counts = [int((bits == b).sum()) for b in bit_set]
+    sumsq = rng.lognormal(3, 1, d_in).astype(np.float32)
+    n_q = max(1, d_in * d_out // 80)
+    excl = np.sort(rng.choice(d_in * d_out, n_q, replace=False)).astype(np.int64)
+    dW, db, dss = _dev(W), _dev(bits), _dev(sumsq)
+
+    def outputs():
+        packed = [torch.full((c, (d_out * b + 31) // 32), -1, dtype=torch.int32, device=DEV) if c else None
+                  for b, c in zip(bit_set, counts)]
+        chan = [torch.full((c,), -1, dtype=torch.int32, device=DEV) if c else None for c in counts]
+        lut = [torch.full((c, 1 << b), -1, dtype=torch.float16, device=DEV) if c else None
+               for b, c in zip(bit_set, counts)]
+        return packed, chan, lut, torch.full((d_in,), -1.0, dtype=torch.float64, device=DEV), \
+            torch.full((2,), -1.0, dtype=torch.float64, device=DEV)
+
+    for oi, start_iters in ((None, None), (excl, None), (excl, 3)):
+        iters = 5
+        ostart = None
+        if start_iters is not None:
+            ostart, _ = orc.kmeans(W, bits, iters=start_iters)
+        ocent, ocodes = orc.kmeans(W, bits, out_idx=oi, iters=iters, start=ostart)
+        oerr, otot = orc.dequant_error(W, ocent, ocodes, bits, oi, sumsq)
+        d_oi = None if oi is None else _dev(oi.astype(np.int32))
+        n_oi = 0 if oi is None else len(oi)
+        init = B.INIT_QUANTILE if ostart is None else B.INIT_GIVEN
+        for with_codes in (True, False):
+            cent = torch.empty((d_in, 16), dtype=torch.float32, device=DEV) if ostart is None else _dev(ostart)
+            codes = torch.full((d_in, d_out), 255, dtype=torch.uint8, device=DEV) if with_codes else None
+            packed, chan, lut, err, tot = outputs()
+            B.kmeans_quantize_pack(dW, db, d_oi, n_oi, iters, cent, codes, bit_set, counts, packed, chan, lut, dss,
+                                   err, tot, ws, init=init)
+            assert np.array_equal(_np(cent), ocent)
+            if with_codes:
+                assert np.array_equal(_np(codes), ocodes)
+            assert _rel(_np(err), oerr) < 1e-12 and _rel(_np(tot), otot) < 1e-12
+            # the two-call route on the same levels and codes
+            p2, c2, l2, e2, t2 = outputs()
+            B.pack_with_error(dW, _dev(ocodes), db, _dev(ocent), bit_set, counts, p2, c2, l2, d_oi, n_oi, dss, e2, t2, ws)
+            assert _rel(_np(err), _np(e2)) < 1e-12 and _rel(_np(tot), _np(t2)) < 1e-12
+            for j, b in enumerate(bit_set):
+                opk, och, olut = orc.pack(ocodes, bits, ocent, b)
+                assert np.array_equal(_np(packed[j]).view(np.uint32), opk), (b, with_codes)
+                assert np.array_equal(_np(chan[j]), och)
+                assert np.array_equal(_np(lut[j]).view(np.uint16), olut)
+                assert torch.equal(packed[j], p2[j]) and torch.equal(chan[j], c2[j])
+                assert torch.equal(lut[j].view(torch.int16), l2[j].view(torch.int16))
+
+
+def test_kmeans_with_stored_format_other_inputs_and_flags(env):
+    """The same job on inputs the histogram kernel does not take (fp32 weights, importance
+    weights, the brute-force rounds): the general kernels run and the stored format follows in
+    its own pass - same outputs as the two calls; a non-finite channel raises the flag, gets a
+    row of zero codes and no number for its error while the other channels are untouched."""
+    B, ws, orc = env["B"], env["ws"], env["orc"]
+    rng = np.random.default_rng(3)
+    d_in, d_out, bit_set = 12, 640, (2, 3, 4)
+    bits = rng.choice(np.array(bit_set, np.uint8), d_in)
+    counts = [int((bits == b).sum()) for b in bit_set]
+
+    def run(W, ew=None, algorithm=B.KMEANS_HISTOGRAM, status=None):
+        packed = [torch.full((c, (d_out * b + 31) // 32), -1, dtype=torch.int32, device=DEV) if c else None
+                  for b, c in zip(bit_set, counts)]
+        chan = [torch.full((c,), -1, dtype=torch.int32, device=DEV) if c else None for c in counts]
+        lut = [torch.full((c, 1 << b), -1, dtype=torch.float16, device=DEV) if c else None
+               for b, c in zip(bit_set, counts)]
+        err = torch.full((d_in,), -1.0, dtype=torch.float64, device=DEV)
+        tot = torch.full((2,), -1.0, dtype=torch.float64, device=DEV)
+        cent = torch.empty((d_in, 16), dtype=torch.float32, device=DEV)
+        codes = torch.empty((d_in, d_out), dtype=torch.uint8, device=DEV)
+        B.kmeans_quantize_pack(_dev(W), _dev(bits), None, 0, 4, cent, codes, bit_set, counts, packed, chan, lut, None,
+                               err, tot, ws, status, algorithm=algorithm, elem_weight=None if ew is None else _dev(ew))
+        return _np(cent), _np(codes), packed, lut, _np(err), _np(tot)
+
+    W32 = rng.normal(0, 0.05, (d_in, d_out)).astype(np.float32)
+    ew = rng.lognormal(0, 1, (d_in, d_out)).astype(np.float32)
+    for W, e, algo in ((W32, None, B.KMEANS_HISTOGRAM), (W32.astype(np.float16), ew, B.KMEANS_HISTOGRAM),
+                       (W32.astype(np.float16), None, B.KMEANS_DIRECT)):
+        cent, codes, packed, lut, err, tot = run(W, e, algo)
+        ocent, ocodes = orc.kmeans(W, bits, elem_weight=e, iters=4)
+        assert _rel(cent, ocent) <= 1e-5 and (codes != ocodes).mean() <= 1e-4
+        oerr, otot = orc.dequant_error(W, cent, codes, bits)          # the GPU's own levels and codes
+        assert _rel(err, oerr) < 1e-12 and _rel(tot, otot) < 1e-12
+        for j, b in enumerate(bit_set):
+            opk, _, olut = orc.pack(codes, bits, cent, b)
+            assert np.array_equal(_np(packed[j]).view(np.uint32), opk) and np.array_equal(_np(lut[j]).view(np.uint16), olut)
+    bad = W32.astype(np.float16)
+    bad[5, 77] = np.inf
+    st = torch.zeros(1, dtype=torch.int32, device=DEV)
+    cent, codes, packed, lut, err, tot = run(bad, status=st)
+    good = run(W32.astype(np.float16))
+    assert st.item() & B.STATUS_NONFINITE and np.isnan(err[5]) and not codes[5].any()
+    keep = np.arange(d_in) != 5
+    assert np.array_equal(err[keep], good[4][keep]) and np.array_equal(codes[keep], good[1][keep])
+    j5 = bit_set.index(int(bits[5]))
+    row5 = int((bits[:5] == bits[5]).sum())
+    assert not _np(packed[j5])[row5].any() and not _np(lut[j5]).view(np.uint16)[row5].any()
+
+
 @pytest.mark.parametrize("dtype", [np.float16, np.float32])
 @pytest.mark.parametrize("d_in,d_out", [(1, 1), (7, 31), (45, 1234), (19, 4096 + 48), (6, 8192 + 32 * 256 + 8)])
 def test_pack_with_error_parity(env, dtype, d_in, d_out):
