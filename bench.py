@@ -277,6 +277,9 @@ def main():
     ap.add_argument("--two-calls", action="store_true",
                     help="final K-means and stored format + error as two calls (cmpq_kmeans_quantize, then "
                          "cmpq_pack_with_error) instead of the one call whose coding pass writes them")
+    ap.add_argument("--shared-tables", action="store_true",
+                    help="the final K-means starts from the per-channel tables the preliminary one kept "
+                         "instead of building them again (same results; not the default)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (outside the timed region): under "
                          "rocprofv3 --pmc it gives the HBM counters a kernel of known traffic to scale by")
@@ -303,7 +306,8 @@ def main():
     def step(timer=None, join=True):
         return P.quantize_block(weights, acts, layers, wl.bit_set, wl.avg_bits, wl.rho_act_ppm,
                                 wl.rho_q_ppm, wl.iters, ws, with_error=True, status=status, timer=timer,
-                                streams=args.streams, join=join, fused=not args.two_calls)
+                                streams=args.streams, join=join, fused=not args.two_calls,
+                                share_tables=args.shared_tables)
 
     if args.calibration_copy:
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
@@ -351,7 +355,7 @@ def main():
     for _ in range(n_serial):
         o1 = P.quantize_block(weights, acts, layers, wl.bit_set, wl.avg_bits, wl.rho_act_ppm,
                               wl.rho_q_ppm, wl.iters, ws1, with_error=True, status=status, timer=t1,
-                              fused=not args.two_calls)
+                              fused=not args.two_calls, share_tables=args.shared_tables)
         del o1
     serial = t1.totals()
     kern = t1.kernel_totals()
@@ -452,7 +456,7 @@ def main():
             return P.quantize_block(weights, acts, layers, wl.bit_set, wl.avg_bits, wl.rho_act_ppm,
                                     wl.rho_q_ppm, wl.iters, ws, with_error=True, status=status,
                                     streams=args.streams, join=False, iters_final_from_prelim=r,
-                                    fused=not args.two_calls)
+                                    fused=not args.two_calls, share_tables=args.shared_tables)
         line["final_pass_continued_from_prelim"] = continued_final_pass(
             P, torch, step_variant, out, layers, wl, (5, wl.iters), args.continued_reps, args.streams, dev)
     if args.rtn_reps > 0:

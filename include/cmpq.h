@@ -55,6 +55,7 @@ extern "C" {
 #define CMPQ_PROTECTED 16 /* bits[i] of a channel of O_act: kept whole in FP16   */
 
 #define CMPQ_STATUS_NONFINITE 1
+#define CMPQ_STATUS_ARRANGEMENT 2 /* cmpq_kmeans_quantize_job was handed something that is no kept arrangement */
 
 /* `op` of cmpq_workspace_bytes */
 #define CMPQ_OP_ACT_STATS 0        /* n = tokens in the call                     */
@@ -68,6 +69,7 @@ extern "C" {
 #define CMPQ_OP_LUT_MATVEC 8       /* n = tokens in the call                     */
 #define CMPQ_OP_PACK_WITH_ERROR 9  /* n ignored                                  */
 #define CMPQ_OP_LUT4 10            /* sizes ignored                              */
+#define CMPQ_OP_KMEANS_ARRANGEMENT 11 /* bytes of cmpq_kmeans_job.arrangement; n ignored; 0: not available */
 
 /* `mode` / `score` of cmpq_extract_outliers */
 #define CMPQ_OUTLIER_CHANNELS 0
@@ -90,6 +92,10 @@ extern "C" {
 /* `algorithm` of cmpq_kmeans_job */
 #define CMPQ_KMEANS_HISTOGRAM 0 /* rounds read cumulative tables of the channel (default)   */
 #define CMPQ_KMEANS_DIRECT 1    /* rounds revisit every weight: K-1 compares, 2 accumulations */
+/* `arrangement_use` of cmpq_kmeans_job */
+#define CMPQ_ARRANGEMENT_NONE 0
+#define CMPQ_ARRANGEMENT_KEEP 1  /* leave this run's per-channel tables in `arrangement`       */
+#define CMPQ_ARRANGEMENT_REUSE 2 /* start from the tables an earlier run left in `arrangement` */
 
 size_t cmpq_workspace_bytes(int op, int64_t d_in, int64_t d_out, int64_t n);
 const char *cmpq_strerror(int code);
@@ -282,6 +288,21 @@ int cmpq_select_by_width(const uint8_t *bits, int64_t d_in, int64_t d_out, const
  *               for inputs the histogram kernel takes (fp16, unit importance, rows of whole
  *               groups of 4 entries, 8-byte aligned; CMPQ_KMEANS_HISTOGRAM): the dense codes
  *               are then not written at all.
+ *   arrangement, arrangement_use   (null / CMPQ_ARRANGEMENT_NONE: not used.)  Sec. 3.2.2 runs
+ *               the quantizer twice on the same channels: the final quantization differs from
+ *               the preliminary one only by the entries of O_q (0.05 % - 1 % of a layer).  The
+ *               histogram kernel's rounds read per-channel tables (weights counted and ordered
+ *               by 16-bit key) that do not depend on the width or on the levels, so the
+ *               preliminary run can leave them (CMPQ_ARRANGEMENT_KEEP: n_out must be 0) in a
+ *               caller buffer of cmpq_workspace_bytes(CMPQ_OP_KMEANS_ARRANGEMENT, d_in, d_out, 0)
+ *               bytes, 16-byte aligned, and the final run (CMPQ_ARRANGEMENT_REUSE, with its
+ *               out_idx) starts from them instead of fetching, keying, counting and ordering the
+ *               weights again: it takes the entries of out_idx out of the tables.  Levels, codes
+ *               and everything else come out bit for bit as without the buffer.  The later call
+ *               must name the same W, d_in, d_out, ldw and bits as the one that kept the buffer;
+ *               only inputs the histogram kernel takes (see `codes` above) can use it, otherwise
+ *               CMPQ_EINVAL.  A buffer that holds no kept arrangement for a channel raises
+ *               CMPQ_STATUS_ARRANGEMENT and leaves that channel's outputs as for a non-finite one.
  * The library reads the structure during the call only.  Errors as cmpq_kmeans_quantize and
  * cmpq_pack_with_error; CMPQ_EINVAL for a null job, an unknown algorithm, or a stored format
  * asked for in part.  Workspace: CMPQ_OP_KMEANS.
@@ -309,6 +330,9 @@ typedef struct cmpq_kmeans_job {
     const float *sumsq;         /* device, nullable */
     double *err_ch;             /* device, [d_in] */
     double *err_total;          /* device, [2] */
+    /* tables shared between the two quantizations of Sec. 3.2.2 */
+    void *arrangement;          /* device */
+    int arrangement_use;
 } cmpq_kmeans_job;
 
 int cmpq_kmeans_quantize_job(const cmpq_kmeans_job *job, void *ws, size_t ws_bytes, void *stream);

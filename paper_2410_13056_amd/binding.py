@@ -19,7 +19,9 @@ F16, F32 = 0, 1
 KMAX = 16
 PROTECTED = 16
 STATUS_NONFINITE = 1
-OP_OUTLIERS_BY_COLUMN, OP_LUT_MATVEC, OP_PACK_WITH_ERROR, OP_LUT4 = 7, 8, 9, 10
+OP_OUTLIERS_BY_COLUMN, OP_LUT_MATVEC, OP_PACK_WITH_ERROR, OP_LUT4, OP_KMEANS_ARRANGEMENT = 7, 8, 9, 10, 11
+ARRANGEMENT_NONE, ARRANGEMENT_KEEP, ARRANGEMENT_REUSE = 0, 1, 2
+STATUS_ARRANGEMENT = 2
 OP_ACT_STATS, OP_ALLOCATE_BITS, OP_OUTLIER_CHANNELS, OP_OUTLIER_WEIGHTS, OP_KMEANS, OP_PACK, \
     OP_DEQUANT_ERROR = range(7)
 OUTLIER_CHANNELS, OUTLIER_WEIGHTS = 0, 1
@@ -61,7 +63,8 @@ class KmeansJob(ctypes.Structure):
                 ("out_idx", _vp), ("n_out", _i64), ("elem_weight", _vp), ("iters", _int), ("init", _int),
                 ("centroids", _vp), ("codes", _vp), ("status", _vp), ("algorithm", _int),
                 ("bit_set", _vp), ("n_set", _int), ("counts_host", _vp), ("packed", _vp), ("chan_idx", _vp),
-                ("lut", _vp), ("sumsq", _vp), ("err_ch", _vp), ("err_total", _vp)]
+                ("lut", _vp), ("sumsq", _vp), ("err_ch", _vp), ("err_total", _vp),
+                ("arrangement", _vp), ("arrangement_use", _int)]
 
 
 class CmpqError(RuntimeError):
@@ -253,11 +256,12 @@ def extract_weight_outliers(W: torch.Tensor, centroids: Optional[torch.Tensor], 
 def kmeans_quantize(W: torch.Tensor, bits: torch.Tensor, out_idx: Optional[torch.Tensor], n_out: int,
                     elem_weight: Optional[torch.Tensor], iters: int, centroids: torch.Tensor,
                     codes: torch.Tensor, ws: Workspace, status: Optional[torch.Tensor] = None,
-                    init: int = INIT_QUANTILE, algorithm: Optional[int] = None) -> None:
-    """`cmpq_kmeans_quantize`; with `algorithm` given, `cmpq_kmeans_quantize_job` naming it."""
+                    init: int = INIT_QUANTILE, algorithm: Optional[int] = None,
+                    arrangement: Optional[torch.Tensor] = None, arrangement_use: int = ARRANGEMENT_NONE) -> None:
+    """`cmpq_kmeans_quantize`; with `algorithm` or `arrangement` given, `cmpq_kmeans_quantize_job`."""
     d_in, d_out, ldw = _rows(W)
     buf = ws.get(workspace_bytes(OP_KMEANS, d_in, d_out))
-    if algorithm is None:
+    if algorithm is None and arrangement is None:
         _check(lib().cmpq_kmeans_quantize(_ptr(W), _dtype(W), d_in, d_out, ldw, _ptr(bits), _ptr(out_idx),
                                           int(n_out), _ptr(elem_weight), int(iters), int(init), _ptr(centroids),
                                           _ptr(codes), _ptr(buf), buf.numel(), _ptr(status), _stream()),
@@ -265,9 +269,15 @@ def kmeans_quantize(W: torch.Tensor, bits: torch.Tensor, out_idx: Optional[torch
         return
     job = KmeansJob(_ptr(W), _dtype(W), d_in, d_out, ldw, _ptr(bits), _ptr(out_idx), int(n_out),
                     _ptr(elem_weight), int(iters), int(init), _ptr(centroids), _ptr(codes), _ptr(status),
-                    int(algorithm))
+                    int(KMEANS_HISTOGRAM if algorithm is None else algorithm))
+    job.arrangement, job.arrangement_use = _ptr(arrangement), int(arrangement_use)
     _check(lib().cmpq_kmeans_quantize_job(ctypes.byref(job), _ptr(buf), buf.numel(), _stream()),
            "cmpq_kmeans_quantize_job")
+
+
+def arrangement_bytes(d_in: int, d_out: int) -> int:
+    """Size of the buffer the two K-means runs of a layer can share (0: not available for this shape)."""
+    return workspace_bytes(OP_KMEANS_ARRANGEMENT, d_in, d_out)
 
 
 def kmeans_quantize_pack(W: torch.Tensor, bits: torch.Tensor, out_idx: Optional[torch.Tensor], n_out: int,
@@ -276,7 +286,8 @@ def kmeans_quantize_pack(W: torch.Tensor, bits: torch.Tensor, out_idx: Optional[
                          chan_idx: Sequence[Optional[torch.Tensor]], lut: Sequence[Optional[torch.Tensor]],
                          sumsq: Optional[torch.Tensor], err_ch: torch.Tensor, err_total: torch.Tensor,
                          ws: Workspace, status: Optional[torch.Tensor] = None, init: int = INIT_QUANTILE,
-                         algorithm: int = KMEANS_HISTOGRAM, elem_weight: Optional[torch.Tensor] = None) -> None:
+                         algorithm: int = KMEANS_HISTOGRAM, elem_weight: Optional[torch.Tensor] = None,
+                         arrangement: Optional[torch.Tensor] = None, arrangement_use: int = ARRANGEMENT_NONE) -> None:
     """`cmpq_kmeans_quantize_job` with the stored format and the error asked for: the K-means
     call followed by what `pack_with_error` leaves, written from the coding pass where the
     histogram kernel runs.  `codes` may be None there (the dense codes are then not written)."""
@@ -292,7 +303,7 @@ def kmeans_quantize_pack(W: torch.Tensor, bits: torch.Tensor, out_idx: Optional[
     job = KmeansJob(_ptr(W), _dtype(W), d_in, d_out, ldw, _ptr(bits), _ptr(out_idx), int(n_out),
                     _ptr(elem_weight), int(iters), int(init), _ptr(centroids), _ptr(codes), _ptr(status),
                     int(algorithm), c(bs, _vp), n, c(cn, _vp), c(pk, _vp), c(ci, _vp), c(lt, _vp), _ptr(sumsq),
-                    _ptr(err_ch), _ptr(err_total))
+                    _ptr(err_ch), _ptr(err_total), _ptr(arrangement), int(arrangement_use))
     _check(lib().cmpq_kmeans_quantize_job(ctypes.byref(job), _ptr(buf), buf.numel(), _stream()),
            "cmpq_kmeans_quantize_job")
 

@@ -14,6 +14,7 @@ size_t cmpq_ws_outliers_by_column(int64_t d_out, int64_t n_out);
 size_t cmpq_ws_lut_matvec(int64_t d_in, int64_t d_out, int64_t m);
 size_t cmpq_ws_pack_with_error(int64_t d_in);
 size_t cmpq_ws_lut4();
+size_t cmpq_ws_kmeans_arrangement(int64_t d_in, int64_t d_out);
 
 extern "C" size_t cmpq_workspace_bytes(int op, int64_t d_in, int64_t d_out, int64_t n) {
     if (d_in < 0 || d_out < 0 || n < 0) return 0;
@@ -29,6 +30,7 @@ extern "C" size_t cmpq_workspace_bytes(int op, int64_t d_in, int64_t d_out, int6
         case CMPQ_OP_LUT_MATVEC: return cmpq_ws_lut_matvec(d_in, d_out, n);
         case CMPQ_OP_PACK_WITH_ERROR: return cmpq_ws_pack_with_error(d_in);
         case CMPQ_OP_LUT4: return cmpq_ws_lut4();
+        case CMPQ_OP_KMEANS_ARRANGEMENT: return cmpq_ws_kmeans_arrangement(d_in, d_out);
         default: return 0;
     }
 }

@@ -377,6 +377,10 @@ static size_t ws_kmeans_base(int64_t d_in) {
     return align_up((size_t)(d_in > 0 ? d_in : 1), 256) + align_up((size_t)(d_in + 1) * sizeof(int32_t), 256);
 }
 
+size_t cmpq_ws_kmeans_arrangement(int64_t d_in, int64_t d_out) {
+    return align_up((size_t)(d_in > 0 ? d_in : 0) * kmeans_hist_arrangement_stride(d_out), 256);
+}
+
 size_t cmpq_ws_kmeans(int64_t d_in, int64_t) {
     // ... | each channel's row in its width group | what cmpq_pack_with_error needs when the
     // stored format is asked for and the histogram kernel does not take the input
@@ -392,6 +396,9 @@ extern "C" int cmpq_kmeans_quantize_job(const cmpq_kmeans_job *job, void *ws, si
     if (j.dtype != CMPQ_F16 && j.dtype != CMPQ_F32) return CMPQ_EINVAL;
     if (j.init != CMPQ_INIT_QUANTILE && j.init != CMPQ_INIT_GIVEN) return CMPQ_EINVAL;
     if (j.algorithm != CMPQ_KMEANS_HISTOGRAM && j.algorithm != CMPQ_KMEANS_DIRECT) return CMPQ_EINVAL;
+    if (j.arrangement_use != CMPQ_ARRANGEMENT_NONE && j.arrangement_use != CMPQ_ARRANGEMENT_KEEP &&
+        j.arrangement_use != CMPQ_ARRANGEMENT_REUSE)
+        return CMPQ_EINVAL;
     if (!j.bits || !j.centroids || (j.n_out > 0 && !j.out_idx)) return CMPQ_EINVAL;
     const bool want_format = j.bit_set || j.n_set || j.counts_host || j.packed || j.chan_idx || j.lut || j.err_ch ||
                              j.err_total || j.sumsq;
@@ -422,12 +429,23 @@ extern "C" int cmpq_kmeans_quantize_job(const cmpq_kmeans_job *job, void *ws, si
     a.fused = 0;
     a.row_of = nullptr;
     a.err_ch = nullptr;
+    a.arr_keep = nullptr;
+    a.arr_reuse = nullptr;
+    a.arr_stride = 0;
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (!ws || reinterpret_cast<uintptr_t>(ws) % 256 != 0 || ws_bytes < cmpq_ws_kmeans(d_in, d_out))
         return CMPQ_EWORKSPACE;
     char *ws_row_of = static_cast<char *>(ws) + ws_kmeans_base(d_in);
     char *ws_tail = ws_row_of + align_up((size_t)d_in * sizeof(int32_t), 256);
     const bool hist_takes_it = kmeans_fast_eligible(a, j.dtype) && (j.algorithm != CMPQ_KMEANS_DIRECT || a.start_given);
+    if (j.arrangement_use != CMPQ_ARRANGEMENT_NONE) {
+        // only the histogram kernel builds and reads arrangements; one is kept from all weights
+        if (!j.arrangement || !hist_takes_it || reinterpret_cast<uintptr_t>(j.arrangement) % 16 != 0) return CMPQ_EINVAL;
+        if (j.arrangement_use == CMPQ_ARRANGEMENT_KEEP && j.n_out > 0) return CMPQ_EINVAL;
+        a.arr_stride = (int64_t)kmeans_hist_arrangement_stride(d_out);
+        if (j.arrangement_use == CMPQ_ARRANGEMENT_KEEP) a.arr_keep = j.arrangement;
+        else a.arr_reuse = j.arrangement;
+    }
     if (want_format) {
         if (d_out > 1 << 20) return CMPQ_ESHAPE;
         if (const int rc = gather_pack_ptrs(d_in, d_out, j.bit_set, j.n_set, j.counts_host, j.packed, j.chan_idx, j.lut, a.pack))

@@ -27,10 +27,18 @@ struct KmArgs {
     PackPtrs pack;
     const int32_t *row_of;
     double *err_ch;
+    // The bucket kernel's per-channel arrangement (bucket table and place array built from all
+    // weights of a channel): written for a later run (arr_keep) or taken from an earlier one
+    // instead of building it again (arr_reuse).  arr_stride bytes per channel.
+    void *arr_keep;
+    const void *arr_reuse;
+    int64_t arr_stride;
 };
 
 // Histogram k-means (kmeans_hist.hip) and fixed-point brute-force k-means
 // (kmeans_fast.hip), both for fp16 weights with unit importance.
-int launch_kmeans_hist(const KmArgs &a, hipStream_t s);  // honours a.fused
+int launch_kmeans_hist(const KmArgs &a, hipStream_t s);  // honours a.fused, a.arr_keep, a.arr_reuse
+// Bytes per channel of the arrangement for channels of d_out weights (0: the kernel does not take them).
+size_t kmeans_hist_arrangement_stride(int64_t d_out);
 int launch_kmeans_fast(const KmArgs &a, hipStream_t s);
 bool kmeans_fast_eligible(const KmArgs &a, int dtype);

@@ -194,57 +194,74 @@ __device__ __forceinline__ double coding_pass_fused(const KmArgs &a, int64_t i, 
     uint32_t *crow = a.codes ? reinterpret_cast<uint32_t *>(a.codes + i * a.d_out) : nullptr;
     double err = 0.0;
     const int n_steps = (n_groups + T - 1) / T;  // the same for every lane: the neighbour exchange below needs all of them
-    uint2 raw = make_uint2(0, 0);
-    if (tid < n_groups) raw = wrow[tid];
+    // the weights of the next few groups are fetched while the current ones are worked on: this
+    // pass may be the first to touch the row (when the tables came from an earlier run)
+    constexpr int kAhead = 4;
+    uint2 nxt[kAhead];
+#pragma unroll
+    for (int u = 0; u < kAhead; ++u) {
+        const int g = u * T + tid;
+        nxt[u] = g < n_groups ? wrow[g] : make_uint2(0, 0);
+    }
 #pragma unroll 1
-    for (int step = 0; step < n_steps; ++step) {
-        const int g = step * T + tid;
-        const bool in = g < n_groups;
-        const uint2 cur = raw;
-        if (g + T < n_groups) raw = wrow[g + T];  // the next group's weights, ahead of time
-        const uint32_t kk[2] = {keys_of_half2(cur.x), keys_of_half2(cur.y)};
-        uint32_t word = 0;  // the 4 codes, one per byte
+    for (int step0 = 0; step0 < n_steps; step0 += kAhead) {
+        uint2 chunk[kAhead];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const uint32_t key = (kk[e >> 1] >> (16 * (e & 1))) & 0xffffu;
-            uint32_t code;
-            if constexpr (kTable) {
-                const uint32_t ent = tbl[key >> kLowBits];
-                code = (key & (kLows - 1)) > ((ent >> 8) & 0xffu) ? (ent >> 4) & 15u : ent & 15u;
-                if (ent & 0x10000u) code = sm.code_of[cell_of<K>(key, thr)];
-            } else {
-                code = sm.code_of[cell_of<K>(key, thr)];
-            }
-            word |= code << (8 * e);
+        for (int u = 0; u < kAhead; ++u) {
+            chunk[u] = nxt[u];
+            const int gn = (step0 + kAhead + u) * T + tid;
+            nxt[u] = gn < n_groups ? wrow[gn] : make_uint2(0, 0);
         }
-        if (in && crow) crow[g] = word;
-        uint32_t kept = in ? 0xfu : 0u;
-        if (n_ex > 0 && in) kept = ~(removed[g >> 3] >> ((g & 7) * 4)) & 0xfu;
-        const uint32_t hw[2] = {cur.x, cur.y};
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const float w = __half2float(__ushort_as_half((unsigned short)(hw[e >> 1] >> (16 * (e & 1)))));
-            double d = (double)w - sm.cent64[(word >> (8 * e)) & 15u];
-            d = ((kept >> e) & 1u) ? d : 0.0;
-            err = fma(d, d, err);
-        }
-        const uint32_t f = in ? squeeze4<B>(word) : 0u;
-        if constexpr (B == 4) {
-            if (in) reinterpret_cast<uint16_t *>(arr)[g] = (uint16_t)f;
-        } else if constexpr (B == 2) {
-            if (in) arr[g] = (unsigned char)f;
-        } else {
-            // 12 (4) bits: an even lane joins its own with those of the lane above it (the next
-            // group: T is even, so a lane's groups keep its parity) into 3 (1) whole bytes
-            const uint32_t v = f | (row_from_above(f) << (4 * B));
-            if (in && (tid & 1) == 0) {
-                if constexpr (B == 3) {
-                    unsigned char *dst = arr + 3 * (g >> 1);
-                    dst[0] = (unsigned char)v;
-                    dst[1] = (unsigned char)(v >> 8);
-                    dst[2] = (unsigned char)(v >> 16);
+        for (int u = 0; u < kAhead; ++u) {
+            if (step0 + u >= n_steps) break;  // uniform over the workgroup
+            const int g = (step0 + u) * T + tid;
+            const bool in = g < n_groups;
+            const uint2 cur = chunk[u];
+            const uint32_t kk[2] = {keys_of_half2(cur.x), keys_of_half2(cur.y)};
+            uint32_t word = 0;  // the 4 codes, one per byte
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const uint32_t key = (kk[e >> 1] >> (16 * (e & 1))) & 0xffffu;
+                uint32_t code;
+                if constexpr (kTable) {
+                    const uint32_t ent = tbl[key >> kLowBits];
+                    code = (key & (kLows - 1)) > ((ent >> 8) & 0xffu) ? (ent >> 4) & 15u : ent & 15u;
+                    if (ent & 0x10000u) code = sm.code_of[cell_of<K>(key, thr)];
                 } else {
-                    arr[g >> 1] = (unsigned char)v;
+                    code = sm.code_of[cell_of<K>(key, thr)];
+                }
+                word |= code << (8 * e);
+            }
+            if (in && crow) crow[g] = word;
+            uint32_t kept = in ? 0xfu : 0u;
+            if (n_ex > 0 && in) kept = ~(removed[g >> 3] >> ((g & 7) * 4)) & 0xfu;
+            const uint32_t hw[2] = {cur.x, cur.y};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float w = __half2float(__ushort_as_half((unsigned short)(hw[e >> 1] >> (16 * (e & 1)))));
+                double d = (double)w - sm.cent64[(word >> (8 * e)) & 15u];
+                d = ((kept >> e) & 1u) ? d : 0.0;
+                err = fma(d, d, err);
+            }
+            const uint32_t f = in ? squeeze4<B>(word) : 0u;
+            if constexpr (B == 4) {
+                if (in) reinterpret_cast<uint16_t *>(arr)[g] = (uint16_t)f;
+            } else if constexpr (B == 2) {
+                if (in) arr[g] = (unsigned char)f;
+            } else {
+                // 12 (4) bits: an even lane joins its own with those of the lane above it (the next
+                // group: T is even, so a lane's groups keep its parity) into 3 (1) whole bytes
+                const uint32_t v = f | (row_from_above(f) << (4 * B));
+                if (in && (tid & 1) == 0) {
+                    if constexpr (B == 3) {
+                        unsigned char *dst = arr + 3 * (g >> 1);
+                        dst[0] = (unsigned char)v;
+                        dst[1] = (unsigned char)(v >> 8);
+                        dst[2] = (unsigned char)(v >> 16);
+                    } else {
+                        arr[g >> 1] = (unsigned char)v;
+                    }
                 }
             }
         }
@@ -531,13 +548,47 @@ __device__ __forceinline__ void lloyd_bucket(const KmArgs &a, int64_t i, BucketS
     __syncthreads();
 }
 
+// What a run may leave behind for a later run on the same channel (the final quantization of
+// Sec. 3.2.2 differs from the preliminary one by the few entries of O_q): per channel a header
+// word, the per-bucket (count << 32 | sum of places) table and the place array, as built from
+// ALL weights of the channel.  The later run loads them instead of fetching, keying, counting
+// and scattering the weights again, takes the entries of O_q out of the table and blanks one
+// byte of the place array per such entry.
+constexpr uint32_t kArrMagic = 0xC3A77A00u;  // + 1: an arrangement follows; + 2: the channel held a non-finite weight
+__host__ __device__ inline size_t arrangement_stride(int64_t d_out, int lb) {
+    return 16 + ((size_t)8 << (16 - lb)) + bucket_arr_bytes(d_out, lb);
+}
+
+constexpr int kModePlain = 0;  // codes only
+constexpr int kModeFused = 1;  // the coding pass also writes the row of the stored format and the error
+constexpr int kModeReuse = 2;  // starts from a kept arrangement; codes like kModeFused (outputs optional)
+
+// One of the place bytes of bucket stretch [w0, w1) (words) that equals `place` becomes a filler.
+// Lanes that remove equal values race for the bytes: compare-and-swap, try the next on a loss.
+__device__ __forceinline__ void blank_one_place(uint32_t *words, uint32_t w0, uint32_t w1, uint32_t place) {
+    const uint32_t pat = place * 0x01010101u;
+    for (uint32_t j = w0; j < w1; ++j) {
+        uint32_t x = words[j];
+        for (;;) {
+            const uint32_t t = x ^ pat;
+            const uint32_t zero = (t - 0x01010101u) & ~t & 0x80808080u;  // lowest flag marks a byte that matches
+            if (!zero) break;
+            const uint32_t sh = (uint32_t)(__ffs(zero) - 8);             // bit offset of that byte
+            const uint32_t nw = (x & ~(0xffu << sh)) | (0x80u << sh);
+            const uint32_t old = atomicCAS(&words[j], x, nw);
+            if (old == x) return;
+            x = old;
+        }
+    }
+}
+
 // Occupancy: 6 wavefronts per SIMD for the 16-group variant (77 registers: 3 workgroups of
 // 512 lanes per compute unit, which is also what LDS allows at d_out = 28 672), 7 for the
 // shorter multi-wavefront variants (at most 72 registers: 7 workgroups of 256 lanes).
-// FUSED: the coding pass also writes the channel's row of the stored format and its squared error.
-template <int G, int T, int LB, bool FUSED>
+template <int G, int T, int LB, int MODE>
 __global__ __launch_bounds__(T) __attribute__((amdgpu_waves_per_eu(6, 7))) void kmeans_bucket_kernel(KmArgs a) {
     constexpr int kBuckets = 1 << (16 - LB);
+    constexpr bool kCodesFused = MODE != kModePlain;
     // dynamic LDS: places of the kept weights, ordered by bucket (a byte each; the bucket
     // follows from the position) | removed-entry bitmap (one bit per weight) | the scatter
     // cursors, later the coding table
@@ -554,14 +605,14 @@ __global__ __launch_bounds__(T) __attribute__((amdgpu_waves_per_eu(6, 7))) void 
             uint32_t *c32 = reinterpret_cast<uint32_t *>(a.codes + i * a.d_out);
             for (int g = tid; g < n_groups; g += T) c32[g] = 0;
         }
-        if (FUSED && tid == 0) a.err_ch[i] = 0.0;
+        if (kCodesFused && a.err_ch && tid == 0) a.err_ch[i] = 0.0;
         return;
     }
     // where the channel's row of the stored format goes
     uint32_t *row_dst = nullptr;
     uint16_t *lut_dst = nullptr;
     const int row_words = (int)(((int64_t)d_out * b + 31) / 32);
-    if constexpr (FUSED) {
+    if (kCodesFused && a.fused) {
         const int32_t row = a.row_of[i];
         int j = 0;
         while (j < a.pack.n_set && a.pack.width[j] != b) ++j;
@@ -576,28 +627,61 @@ __global__ __launch_bounds__(T) __attribute__((amdgpu_waves_per_eu(6, 7))) void 
     uint32_t *removed = reinterpret_cast<uint32_t *>(dyn + arr_bytes);
     const int n_words = (d_out + 31) >> 5;
     uint32_t *cursor = removed + ((n_words + 3) & ~3);
+    const __half *wrow_h = static_cast<const __half *>(a.W) + i * a.ldw;
+    const uint2 *wrow = reinterpret_cast<const uint2 *>(wrow_h);
+    // the arrangement this run leaves (any mode but reuse) or starts from (reuse)
+    unsigned char *keep = nullptr;
+    if (MODE != kModeReuse && a.arr_keep) keep = static_cast<unsigned char *>(a.arr_keep) + i * a.arr_stride;
+    const int per = kBuckets / T > 0 ? kBuckets / T : 1;  // buckets a lane owns in the prefix pass (T is a power of two)
+    const int b0 = tid * per;
 
-    // ---- load: lane owns groups g = k*T + tid of 4 weights, kept as packed 16-bit keys
-    const uint2 *wrow = reinterpret_cast<const uint2 *>(static_cast<const __half *>(a.W) + i * a.ldw);
     uint32_t keys[2 * G];
-    uint32_t nonfinite = 0;
-#pragma unroll
-    for (int k = 0; k < G; ++k) {
-        const int g = k * T + tid;
-        uint2 raw = make_uint2(0, 0);
-        if (g < n_groups) raw = wrow[g];
-        nonfinite |= nonfinite_of_half2(raw.x) | nonfinite_of_half2(raw.y);
-        keys[2 * k] = keys_of_half2(raw.x);
-        keys[2 * k + 1] = keys_of_half2(raw.y);
-    }
+    uint32_t n_orig[8];  // reuse: the kept arrangement's count of each bucket this lane owns (per <= 8)
+    bool input_ok = true;
+    uint32_t bad_status = CMPQ_STATUS_NONFINITE;
     if (tid == 0) {  // the slice of out_idx inside this channel
         sm.seg_lo = a.seg ? a.seg[i] : 0;
         const int64_t lo = a.seg ? a.seg[i + 1] : 0;
         sm.n_excl = (int)lo - sm.seg_lo;
     }
-    for (int s = tid; s < kBuckets; s += T) sm.scum[s] = 0;  // first: count << 32 | sum of places
     for (int s = tid; s < n_words; s += T) removed[s] = 0;
-    {
+    if constexpr (MODE == kModeReuse) {
+        // ---- the kept arrangement: header, bucket table, place array
+        const unsigned char *src = static_cast<const unsigned char *>(a.arr_reuse) + i * a.arr_stride;
+        const uint32_t head = *reinterpret_cast<const uint32_t *>(src);
+        if (head != kArrMagic + 1u) {
+            input_ok = false;  // the earlier run flagged the channel, or this is no arrangement at all
+            if (head != kArrMagic + 2u) bad_status = CMPQ_STATUS_ARRANGEMENT;
+        } else {
+            const unsigned long long *tsrc = reinterpret_cast<const unsigned long long *>(src + 16);
+            if (b0 < kBuckets) {
+#pragma unroll
+                for (int r = 0; r < 8; ++r) {
+                    if (r < per) {
+                        const unsigned long long packed = tsrc[b0 + r];
+                        n_orig[r] = (uint32_t)(packed >> 32);
+                        sm.scum[b0 + r] = (long long)packed;
+                    }
+                }
+            }
+            const uint4 *asrc = reinterpret_cast<const uint4 *>(src + 16 + (size_t)kBuckets * 8);
+            uint4 *a4 = reinterpret_cast<uint4 *>(arr);
+            for (int s = tid; s < (int)(arr_bytes >> 4); s += T) a4[s] = asrc[s];
+        }
+    } else {
+        // ---- load: lane owns groups g = k*T + tid of 4 weights, kept as packed 16-bit keys
+        uint32_t nonfinite = 0;
+#pragma unroll
+        for (int k = 0; k < G; ++k) {
+            const int g = k * T + tid;
+            uint2 raw = make_uint2(0, 0);
+            if (g < n_groups) raw = wrow[g];
+            nonfinite |= nonfinite_of_half2(raw.x) | nonfinite_of_half2(raw.y);
+            keys[2 * k] = keys_of_half2(raw.x);
+            keys[2 * k + 1] = keys_of_half2(raw.y);
+        }
+        input_ok = (nonfinite & 0x80008000u) == 0u;
+        for (int s = tid; s < kBuckets; s += T) sm.scum[s] = 0;  // first: count << 32 | sum of places
         uint4 *a4 = reinterpret_cast<uint4 *>(arr);
         for (int s = tid; s < (int)(arr_bytes >> 4); s += T) a4[s] = make_uint4(kFill4, kFill4, kFill4, kFill4);
     }
@@ -607,20 +691,22 @@ __global__ __launch_bounds__(T) __attribute__((amdgpu_waves_per_eu(6, 7))) void 
         bad_start = !isfinite(given);
         sm.cent[tid] = given == 0.0f ? 0.0f : given;
     }
-    if (!__syncthreads_and((nonfinite & 0x80008000u) == 0u && !bad_start)) {
-        // a non-finite weight or starting level: the caller's status word says so; the channel
-        // gets defined outputs (all levels 0, all codes 0) instead of a clustering of NaNs
-        if (tid == 0 && a.status) atomicOr(a.status, CMPQ_STATUS_NONFINITE);
+    if (!__syncthreads_and(input_ok && !bad_start)) {
+        // a non-finite weight or starting level (or no usable arrangement): the caller's status
+        // word says so; the channel gets defined outputs (all levels 0, all codes 0) instead of
+        // a clustering of NaNs
+        if (tid == 0 && a.status) atomicOr(a.status, (int)(input_ok ? CMPQ_STATUS_NONFINITE : bad_status));
         if (tid < CMPQ_KMAX) crow[tid] = tid < K ? 0.0f : INFINITY;
         if (a.codes) {
             uint32_t *c32 = reinterpret_cast<uint32_t *>(a.codes + i * a.d_out);
             for (int g = tid; g < n_groups; g += T) c32[g] = 0;
         }
-        if constexpr (FUSED) {  // the row of all-zero codes, the table of zero levels, no number for the error
+        if constexpr (kCodesFused) {  // the row of all-zero codes, the table of zero levels, no number for the error
             if (row_dst) for (int w = tid; w < row_words; w += T) row_dst[w] = 0;
             if (lut_dst && tid < K) lut_dst[tid] = 0;
-            if (tid == 0) a.err_ch[i] = __longlong_as_double(0x7ff8000000000000ll);
+            if (a.err_ch && tid == 0) a.err_ch[i] = __longlong_as_double(0x7ff8000000000000ll);
         }
+        if (keep && tid == 0) *reinterpret_cast<uint32_t *>(keep) = kArrMagic + 2u;
         return;
     }
     const int n_ex = sm.n_excl;
@@ -630,29 +716,41 @@ __global__ __launch_bounds__(T) __attribute__((amdgpu_waves_per_eu(6, 7))) void 
         for (int e = tid; e < n_ex; e += T) {
             const int o = ex_idx[e] - chan_base;
             atomicOr(&removed[o >> 5], 1u << (o & 31));
+            if constexpr (MODE == kModeReuse) {  // out of its bucket's count and sum of places
+                const uint32_t key = key_of_half(__half_as_ushort(wrow_h[o]));
+                atomicAdd(reinterpret_cast<unsigned long long *>(&sm.scum[key >> LB]),
+                          0ull - ((1ull << 32) | (key & ((1u << LB) - 1))));
+            }
         }
         __syncthreads();
     }
 
     // ---- bucket tables: counts and sums of places of the kept weights
-    if (n_ex > 0) count_buckets<G, T, LB, true>(keys, removed, sm.scum, n_groups);
-    else count_buckets<G, T, LB, false>(keys, removed, sm.scum, n_groups);
-    __syncthreads();
+    if constexpr (MODE != kModeReuse) {
+        if (n_ex > 0) count_buckets<G, T, LB, true>(keys, removed, sm.scum, n_groups);
+        else count_buckets<G, T, LB, false>(keys, removed, sm.scum, n_groups);
+        __syncthreads();
+    }
     // ---- exclusive prefixes over buckets of count and exact sum; where each bucket's
-    //      stretch of the byte array begins (counts rounded up to whole words)
+    //      stretch of the byte array begins (counts rounded up to whole words; with a kept
+    //      arrangement the stretches are those of its counts, the prefixes those of what is left)
     {
-        const int per = kBuckets / T > 0 ? kBuckets / T : 1;  // T is a power of two
-        const int b0 = tid * per;
+        unsigned long long *keep_tbl = keep ? reinterpret_cast<unsigned long long *>(keep + 16) : nullptr;
         uint32_t n_loc = 0;  // count | padded count << 16: both stay below 2^16
         long long s_loc = 0;
         if (b0 < kBuckets) {
-            for (int r = 0; r < per; ++r) {
-                const unsigned long long packed = (unsigned long long)sm.scum[b0 + r];
-                const uint32_t n = (uint32_t)(packed >> 32);
-                long long q0, step;
-                bucket_affine<LB>((uint32_t)(b0 + r), q0, step);
-                n_loc += n | (((n + 3) & ~3u) << 16);
-                s_loc += (long long)n * q0 + step * (long long)(packed & 0xffffffffu);
+#pragma unroll
+            for (int r = 0; r < 8; ++r) {
+                if (r < per) {
+                    const unsigned long long packed = (unsigned long long)sm.scum[b0 + r];
+                    const uint32_t n = (uint32_t)(packed >> 32);
+                    const uint32_t n_place = MODE == kModeReuse ? n_orig[r] : n;
+                    long long q0, step;
+                    bucket_affine<LB>((uint32_t)(b0 + r), q0, step);
+                    n_loc += n | (((n_place + 3) & ~3u) << 16);
+                    s_loc += (long long)n * q0 + step * (long long)(packed & 0xffffffffu);
+                    if (keep_tbl) keep_tbl[b0 + r] = packed;
+                }
             }
         }
         uint32_t n_run, n_tot;
@@ -660,18 +758,22 @@ __global__ __launch_bounds__(T) __attribute__((amdgpu_waves_per_eu(6, 7))) void 
         block_scan_excl_pair(n_loc, (unsigned long long)s_loc, sm.scan32, sm.scan64, n_run, s_run_u, n_tot, s_tot);
         long long s_run = (long long)s_run_u;
         if (b0 < kBuckets) {
-            for (int r = 0; r < per; ++r) {
-                const unsigned long long packed = (unsigned long long)sm.scum[b0 + r];
-                const uint32_t n = (uint32_t)(packed >> 32);
-                long long q0, step;
-                bucket_affine<LB>((uint32_t)(b0 + r), q0, step);
-                const long long sb = (long long)n * q0 + step * (long long)(packed & 0xffffffffu);
-                sm.ncum[b0 + r] = (uint16_t)(n_run & 0xffffu);
-                sm.start[b0 + r] = (uint16_t)(n_run >> 16);
-                cursor[b0 + r] = n_run >> 16;  // where the next place of the bucket goes
-                sm.scum[b0 + r] = s_run;
-                n_run += n | (((n + 3) & ~3u) << 16);
-                s_run += sb;
+#pragma unroll
+            for (int r = 0; r < 8; ++r) {
+                if (r < per) {
+                    const unsigned long long packed = (unsigned long long)sm.scum[b0 + r];
+                    const uint32_t n = (uint32_t)(packed >> 32);
+                    const uint32_t n_place = MODE == kModeReuse ? n_orig[r] : n;
+                    long long q0, step;
+                    bucket_affine<LB>((uint32_t)(b0 + r), q0, step);
+                    const long long sb = (long long)n * q0 + step * (long long)(packed & 0xffffffffu);
+                    sm.ncum[b0 + r] = (uint16_t)(n_run & 0xffffu);
+                    sm.start[b0 + r] = (uint16_t)(n_run >> 16);
+                    cursor[b0 + r] = n_run >> 16;  // where the next place of the bucket goes
+                    sm.scum[b0 + r] = s_run;
+                    n_run += n | (((n_place + 3) & ~3u) << 16);
+                    s_run += sb;
+                }
             }
         }
         if (tid == 0) {
@@ -682,20 +784,40 @@ __global__ __launch_bounds__(T) __attribute__((amdgpu_waves_per_eu(6, 7))) void 
     }
     __syncthreads();
     const uint32_t M = sm.ncum[kBuckets];
-    // ---- scatter the places of the kept weights, ordered by bucket
-    if (n_ex > 0) scatter_places<G, T, LB, true>(keys, removed, cursor, arr, n_groups);
-    else scatter_places<G, T, LB, false>(keys, removed, cursor, arr, n_groups);
+    if constexpr (MODE == kModeReuse) {
+        // ---- one place byte per entry of O_q becomes a filler
+        if (n_ex > 0) {
+            const int32_t *ex_idx = a.out_idx + sm.seg_lo;
+            const int32_t chan_base = (int32_t)(i * a.d_out);
+            for (int e = tid; e < n_ex; e += T) {
+                const uint32_t key = key_of_half(__half_as_ushort(wrow_h[ex_idx[e] - chan_base]));
+                const uint32_t bk = key >> LB;
+                blank_one_place(reinterpret_cast<uint32_t *>(arr), sm.start[bk] >> 2, sm.start[bk + 1] >> 2,
+                                key & ((1u << LB) - 1));
+            }
+        }
+    } else {
+        // ---- scatter the places of the kept weights, ordered by bucket
+        if (n_ex > 0) scatter_places<G, T, LB, true>(keys, removed, cursor, arr, n_groups);
+        else scatter_places<G, T, LB, false>(keys, removed, cursor, arr, n_groups);
+    }
     __syncthreads();
+    if (keep) {  // the arrangement as it stands, for a later run on this channel
+        const uint4 *a4 = reinterpret_cast<const uint4 *>(arr);
+        uint4 *adst = reinterpret_cast<uint4 *>(keep + 16 + (size_t)kBuckets * 8);
+        for (int s = tid; s < (int)(arr_bytes >> 4); s += T) adst[s] = a4[s];
+        if (tid == 0) *reinterpret_cast<uint32_t *>(keep) = kArrMagic + 1u;
+    }
 
     double err = 0.0;
     switch (K) {
-        case 2: lloyd_bucket<G, 2, T, LB, FUSED>(a, i, sm, arr, cursor, removed, n_ex, keys, n_groups, M, err); break;
-        case 4: lloyd_bucket<G, 4, T, LB, FUSED>(a, i, sm, arr, cursor, removed, n_ex, keys, n_groups, M, err); break;
-        case 8: lloyd_bucket<G, 8, T, LB, FUSED>(a, i, sm, arr, cursor, removed, n_ex, keys, n_groups, M, err); break;
-        default: lloyd_bucket<G, 16, T, LB, FUSED>(a, i, sm, arr, cursor, removed, n_ex, keys, n_groups, M, err); break;
+        case 2: lloyd_bucket<G, 2, T, LB, kCodesFused>(a, i, sm, arr, cursor, removed, n_ex, keys, n_groups, M, err); break;
+        case 4: lloyd_bucket<G, 4, T, LB, kCodesFused>(a, i, sm, arr, cursor, removed, n_ex, keys, n_groups, M, err); break;
+        case 8: lloyd_bucket<G, 8, T, LB, kCodesFused>(a, i, sm, arr, cursor, removed, n_ex, keys, n_groups, M, err); break;
+        default: lloyd_bucket<G, 16, T, LB, kCodesFused>(a, i, sm, arr, cursor, removed, n_ex, keys, n_groups, M, err); break;
     }
     if (tid < CMPQ_KMAX) crow[tid] = tid < K ? sm.cent[tid] : INFINITY;
-    if constexpr (FUSED) {
+    if constexpr (kCodesFused) {
         // the row is complete in the place array (the coding pass ends with a barrier): copy it
         // out, the table in FP16 beside it, and add the lanes' error sums in a fixed order
         if (row_dst) {
@@ -707,7 +829,7 @@ __global__ __launch_bounds__(T) __attribute__((amdgpu_waves_per_eu(6, 7))) void 
         double *red = reinterpret_cast<double *>(sm.scan64);
         if ((tid & 63) == 0) red[tid >> 6] = err;
         __syncthreads();
-        if (tid == 0) {
+        if (tid == 0 && a.err_ch) {
             double t = 0.0;
             for (int w = 0; w < T / CMPQ_WAVE; ++w) t += red[w];
             a.err_ch[i] = t;
@@ -724,7 +846,8 @@ size_t bucket_dyn_lds(int64_t d_out, int lb) {
 
 template <int G, int T, int LB>
 int launch_variant(const KmArgs &a, hipStream_t s) {
-    auto kern = a.fused ? kmeans_bucket_kernel<G, T, LB, true> : kmeans_bucket_kernel<G, T, LB, false>;
+    auto kern = a.arr_reuse ? kmeans_bucket_kernel<G, T, LB, kModeReuse>
+                            : (a.fused ? kmeans_bucket_kernel<G, T, LB, kModeFused> : kmeans_bucket_kernel<G, T, LB, kModePlain>);
     const size_t lds = bucket_dyn_lds(a.d_out, LB);
     if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
@@ -761,6 +884,13 @@ static void hist_variant(int64_t d_out, int &T_out, int &G_out, int &LB_out) {
     else if (per_lane > 2) G_out = 4;
     else if (per_lane > 1) G_out = 2;
     else G_out = 1;
+}
+
+size_t kmeans_hist_arrangement_stride(int64_t d_out) {
+    if (d_out < 4 || d_out % 4 != 0) return 0;
+    int T, G, LB;
+    hist_variant(d_out, T, G, LB);
+    return T == 0 ? 0 : arrangement_stride(d_out, LB);
 }
 
 extern "C" int cmpq_kmeans_launch_shape(int64_t d_out, int64_t *shape) {

@@ -125,10 +125,21 @@ def _channels_and_widths(sumsq, d_in, bit_set, avg_bits, rho_act_ppm, ws, timer)
     return act_idx, chan_mask, bits, counts
 
 
+def _shared_tables(Wt: torch.Tensor) -> Optional[torch.Tensor]:
+    """The buffer through which the preliminary K-means of a layer hands its per-channel tables
+    to the final one (`cmpq_kmeans_job.arrangement`), or None where the histogram kernel would
+    not take the input (other than fp16, rows not whole groups of 4 or not 8-byte aligned)."""
+    d_in, d_out = Wt.shape
+    if Wt.dtype != torch.float16 or d_out % 4 or Wt.data_ptr() % 8 or (d_in > 1 and Wt.stride(0) % 4):
+        return None
+    n = B.arrangement_bytes(d_in, d_out)
+    return torch.empty(n, dtype=torch.uint8, device=Wt.device) if n > 0 else None
+
+
 def _after_first_pass(Wt, sumsq, bit_set, counts, act_idx, chan_mask, bits, cent1, codes1, rho_q_ppm, iters,
                       ws, score, with_error, keep_prelim, status, timer,
                       iters_final_from_prelim: Optional[int] = None, oq_per_channel: bool = False,
-                      fused: bool = True) -> LayerResult:
+                      fused: bool = True, tables: Optional[torch.Tensor] = None) -> LayerResult:
     """O_q from the preliminary quantization, the final quantization, the stored format."""
     dev = Wt.device
     d_in, d_out = Wt.shape
@@ -158,6 +169,7 @@ def _after_first_pass(Wt, sumsq, bit_set, counts, act_idx, chan_mask, bits, cent
     # variant: continue from the preliminary levels (a copy; the call updates it in place)
     cent = cent1.clone() if given else torch.empty((d_in, B.KMAX), dtype=torch.float32, device=dev)
     rounds, init = (iters_final_from_prelim, B.INIT_GIVEN) if given else (iters, B.INIT_QUANTILE)
+    reuse = B.ARRANGEMENT_REUSE if tables is not None else B.ARRANGEMENT_NONE
     res = LayerResult(d_in, d_out, tuple(bit_set), counts, sumsq, act_idx, chan_mask, bits, cent, codes,
                       out_idx, out_val, packed, chan_idx, lut, W_t=Wt)
     if keep_prelim:
@@ -169,10 +181,12 @@ def _after_first_pass(Wt, sumsq, bit_set, counts, act_idx, chan_mask, bits, cent
         # one call: the coding pass of the final K-means writes the stored format and the error
         with _stage(timer, "kmeans_final"):
             B.kmeans_quantize_pack(Wt, bits, out_idx, k_q, rounds, cent, codes, bit_set, counts, packed, chan_idx,
-                                   lut, sumsq, res.err_ch, res.err_total, ws, status, init=init)
+                                   lut, sumsq, res.err_ch, res.err_total, ws, status, init=init,
+                                   arrangement=tables, arrangement_use=reuse)
         return res
     with _stage(timer, "kmeans_final"):
-        B.kmeans_quantize(Wt, bits, out_idx, k_q, None, rounds, cent, codes, ws, status, init=init)
+        B.kmeans_quantize(Wt, bits, out_idx, k_q, None, rounds, cent, codes, ws, status, init=init,
+                          arrangement=tables, arrangement_use=reuse)
     if with_error:      # stored format and error in one pass over the codes
         with _stage(timer, "pack_with_error"):
             B.pack_with_error(Wt, codes, bits, cent, bit_set, counts, packed, chan_idx, lut, out_idx, k_q, sumsq,
@@ -190,7 +204,7 @@ def quantize_layer(W: torch.Tensor, sumsq: torch.Tensor, bit_set: Sequence[int],
                    status: Optional[torch.Tensor] = None, transposed: bool = False,
                    timer: Optional[StageTimer] = None,
                    iters_final_from_prelim: Optional[int] = None, oq_per_channel: bool = False,
-                   fused: bool = True) -> LayerResult:
+                   fused: bool = True, share_tables: bool = False) -> LayerResult:
     """Quantizes one layer.  `W` is the framework's [d_out, d_in] weight (or already
     d_in x d_out with ``transposed=True``); `sumsq` comes from `activation_stats`.
 
@@ -200,6 +214,10 @@ def quantize_layer(W: torch.Tensor, sumsq: torch.Tensor, bit_set: Sequence[int],
     ``fused`` (with ``with_error``): the final K-means writes the stored format and the error
     from its coding pass (`cmpq_kmeans_quantize_job`); ``fused=False`` runs `cmpq_kmeans_quantize`
     and `cmpq_pack_with_error` one after the other.  Same results.
+
+    ``share_tables`` (off by default): the preliminary K-means leaves its per-channel tables for
+    the final one (`cmpq_kmeans_job.arrangement`), which then does not build them again.  Same
+    results; measured, the instructions it saves are paid for by the extra memory traffic.
 
     ``iters_final_from_prelim`` (a variant; the paper names no start for either K-means of
     Sec. 3.2.2): the final quantization starts from the levels of the preliminary one and runs
@@ -212,11 +230,13 @@ def quantize_layer(W: torch.Tensor, sumsq: torch.Tensor, bit_set: Sequence[int],
     # preliminary quantization W'_q
     cent1 = torch.empty((d_in, B.KMAX), dtype=torch.float32, device=dev)
     codes1 = torch.empty((d_in, d_out), dtype=torch.uint8, device=dev)
+    tables = _shared_tables(Wt) if share_tables else None
     with _stage(timer, "kmeans_prelim"):
-        B.kmeans_quantize(Wt, bits, None, 0, None, iters, cent1, codes1, ws, status)
+        B.kmeans_quantize(Wt, bits, None, 0, None, iters, cent1, codes1, ws, status, arrangement=tables,
+                          arrangement_use=B.ARRANGEMENT_KEEP if tables is not None else B.ARRANGEMENT_NONE)
     return _after_first_pass(Wt, sumsq, bit_set, counts, act_idx, chan_mask, bits, cent1, codes1, rho_q_ppm,
                              iters, ws, score, with_error, keep_prelim, status, timer, iters_final_from_prelim,
-                             oq_per_channel, fused)
+                             oq_per_channel, fused, tables)
 
 
 @dataclasses.dataclass
@@ -467,7 +487,7 @@ def quantize_block(weights: Dict[str, torch.Tensor], acts: Dict[str, torch.Tenso
                    ws=None, with_error: bool = False, status: Optional[torch.Tensor] = None,
                    timer: Optional[StageTimer] = None, streams: int = 1,
                    join: bool = True, iters_final_from_prelim: Optional[int] = None,
-                   fused: bool = True) -> Dict[str, LayerResult]:
+                   fused: bool = True, share_tables: bool = False) -> Dict[str, LayerResult]:
     """One pass of the whole path over a decoder block: statistics once per distinct
     input, then every linear layer.  `layers` lists (name, x_key) pairs.
 
@@ -493,7 +513,8 @@ def quantize_block(weights: Dict[str, torch.Tensor], acts: Dict[str, torch.Tenso
                 stats[x_key] = activation_stats(acts[x_key], ws, status=status, timer=timer)[1]
             out[name] = quantize_layer(weights[name], stats[x_key], bit_set, avg_bits, rho_act_ppm,
                                        rho_q_ppm, iters, ws, with_error=with_error, status=status,
-                                       timer=timer, iters_final_from_prelim=iters_final_from_prelim, fused=fused)
+                                       timer=timer, iters_final_from_prelim=iters_final_from_prelim, fused=fused,
+                                       share_tables=share_tables)
         return out
     if ws is None:
         ws = [B.Workspace(dev) for _ in range(streams)]
@@ -521,7 +542,8 @@ def quantize_block(weights: Dict[str, torch.Tensor], acts: Dict[str, torch.Tenso
             results[name] = quantize_layer(weights[name], sumsq, bit_set, avg_bits, rho_act_ppm,
                                            rho_q_ppm, iters, ws[j], with_error=with_error,
                                            status=status, timer=timer,
-                                           iters_final_from_prelim=iters_final_from_prelim, fused=fused)
+                                           iters_final_from_prelim=iters_final_from_prelim, fused=fused,
+                                           share_tables=share_tables)
     if join:
         for st in side:
             main.wait_stream(st)

@@ -670,6 +670,115 @@ def test_kmeans_with_stored_format_from_its_coding_pass(env, d_out, bit_set):
                 assert torch.equal(lut[j].view(torch.int16), l2[j].view(torch.int16))
 
 
+@pytest.mark.parametrize("d_out", [4, 36, 252, 1000, 2052, 4100, 8192, 11008, 16388, 28672, 32768])
+def test_final_kmeans_from_the_preliminary_runs_tables(env, d_out):
+    """Sec. 3.2.2 runs the quantizer twice on the same channels.  With the preliminary run's
+    per-channel tables kept (`arrangement`), the final run - which takes the entries of O_q out
+    of them instead of building them again - gives the oracle's levels and codes bit for bit,
+    with or without the stored format asked for: every launch shape, channels of O_act in
+    between, removed entries that repeat one value many times, a channel with everything
+    removed, another width in the second run, and given starting levels."""
+    B, ws, orc = env["B"], env["ws"], env["orc"]
+    rng = np.random.default_rng(d_out + 1)
+    d_in = 12 if d_out > 4096 else 24
+    W = rng.normal(0, 0.02, (d_in, d_out))
+    W[rng.random(W.shape) < 0.01] *= 10
+    W = W.astype(np.float16)
+    W[3, : max(1, d_out // 3)] = np.float16(0.0371)                 # one value many times ...
+    W[4, ::2] = np.float16(-0.0)                                    # ... and both zeros
+    W[4, 1::2] = np.float16(0.0) if d_out < 64 else W[4, 1::2]
+    bit_set = (2, 3, 4)
+    bits = rng.choice(np.array(bit_set + (16,), np.uint8), d_in)
+    bits[:3] = bit_set
+    bits[3], bits[4], bits[5] = 3, 2, 4
+    counts = [int((bits == b).sum()) for b in bit_set]
+    n_q = max(1, d_in * d_out // 60)
+    excl = set(rng.choice(d_in * d_out, n_q, replace=False).tolist())
+    excl |= {3 * d_out + o for o in range(0, max(1, d_out // 3), 2)}    # many removed entries of one value
+    excl |= {4 * d_out + o for o in range(0, d_out, 3)}
+    excl |= {5 * d_out + o for o in range(d_out)}                       # a whole channel
+    excl = np.array(sorted(excl), np.int64)
+    dW, db = _dev(W), _dev(bits)
+    tables = torch.zeros(B.arrangement_bytes(d_in, d_out), dtype=torch.uint8, device=DEV)
+    assert tables.numel() > 0
+    cent1 = torch.empty((d_in, 16), dtype=torch.float32, device=DEV)
+    codes1 = torch.empty((d_in, d_out), dtype=torch.uint8, device=DEV)
+    B.kmeans_quantize(dW, db, None, 0, None, 4, cent1, codes1, ws, arrangement=tables,
+                      arrangement_use=B.ARRANGEMENT_KEEP)
+    o1, k1 = orc.kmeans(W, bits, iters=4)
+    assert np.array_equal(_np(cent1), o1) and np.array_equal(_np(codes1), k1)     # keeping changes nothing
+    d_oi = _dev(excl.astype(np.int32))
+    bits2 = bits.copy()
+    bits2[bits2 == 2] = 3                                           # the tables do not depend on the width
+    for bb, start in ((bits, None), (bits, o1), (bits2, None)):
+        ocent, ocodes = orc.kmeans(W, bb, out_idx=excl, iters=5, start=start)
+        init = B.INIT_QUANTILE if start is None else B.INIT_GIVEN
+        # plain call from the kept tables
+        cent = torch.empty((d_in, 16), dtype=torch.float32, device=DEV) if start is None else _dev(start)
+        codes = torch.full((d_in, d_out), 255, dtype=torch.uint8, device=DEV)
+        B.kmeans_quantize(dW, _dev(bb), d_oi, len(excl), None, 5, cent, codes, ws, init=init, arrangement=tables,
+                          arrangement_use=B.ARRANGEMENT_REUSE)
+        assert np.array_equal(_np(cent), ocent) and np.array_equal(_np(codes), ocodes)
+        # and with the stored format from the coding pass
+        cnt = [int((bb == b).sum()) for b in bit_set]
+        packed = [torch.full((c, (d_out * b + 31) // 32), -1, dtype=torch.int32, device=DEV) if c else None
+                  for b, c in zip(bit_set, cnt)]
+        chan = [torch.full((c,), -1, dtype=torch.int32, device=DEV) if c else None for c in cnt]
+        lut = [torch.full((c, 1 << b), -1, dtype=torch.float16, device=DEV) if c else None for b, c in zip(bit_set, cnt)]
+        err = torch.full((d_in,), -1.0, dtype=torch.float64, device=DEV)
+        tot = torch.full((2,), -1.0, dtype=torch.float64, device=DEV)
+        cent = torch.empty((d_in, 16), dtype=torch.float32, device=DEV) if start is None else _dev(start)
+        codes = torch.full((d_in, d_out), 255, dtype=torch.uint8, device=DEV)
+        B.kmeans_quantize_pack(dW, _dev(bb), d_oi, len(excl), 5, cent, codes, bit_set, cnt, packed, chan, lut, None, err,
+                               tot, ws, init=init, arrangement=tables, arrangement_use=B.ARRANGEMENT_REUSE)
+        assert np.array_equal(_np(cent), ocent) and np.array_equal(_np(codes), ocodes)
+        oerr, otot = orc.dequant_error(W, ocent, ocodes, bb, excl, None)
+        assert _rel(_np(err), oerr) < 1e-12 and _rel(_np(tot), otot) < 1e-12
+        for j, b in enumerate(bit_set):
+            if cnt[j]:
+                opk, och, olut = orc.pack(ocodes, bb, ocent, b)
+                assert np.array_equal(_np(packed[j]).view(np.uint32), opk) and np.array_equal(_np(chan[j]), och)
+                assert np.array_equal(_np(lut[j]).view(np.uint16), olut)
+
+
+def test_kept_tables_flags(env):
+    """A channel that held a non-finite weight when the tables were kept is flagged again by the
+    run that starts from them; a buffer that holds no kept tables raises the arrangement flag;
+    either way the other channels and the caller's memory are left in order."""
+    B, ws, orc = env["B"], env["ws"], env["orc"]
+    rng = np.random.default_rng(8)
+    d_in, d_out = 6, 2048
+    W = rng.normal(0, 0.02, (d_in, d_out)).astype(np.float16)
+    W[2, 100] = np.nan
+    bits = np.full(d_in, 3, np.uint8)
+    dW, db = _dev(W), _dev(bits)
+    tables = torch.zeros(B.arrangement_bytes(d_in, d_out), dtype=torch.uint8, device=DEV)
+    cent = torch.empty((d_in, 16), dtype=torch.float32, device=DEV)
+    codes = torch.empty((d_in, d_out), dtype=torch.uint8, device=DEV)
+    st = torch.zeros(1, dtype=torch.int32, device=DEV)
+    B.kmeans_quantize(dW, db, None, 0, None, 3, cent, codes, ws, st, arrangement=tables, arrangement_use=B.ARRANGEMENT_KEEP)
+    assert st.item() == B.STATUS_NONFINITE
+    st.zero_()
+    c2, k2 = torch.empty_like(cent), torch.empty_like(codes)
+    B.kmeans_quantize(dW, db, None, 0, None, 3, c2, k2, ws, st, arrangement=tables, arrangement_use=B.ARRANGEMENT_REUSE)
+    assert st.item() == B.STATUS_NONFINITE
+    assert torch.equal(c2, cent) and torch.equal(k2, codes)        # flagged channel included: zeros both times
+    keep = np.arange(d_in) != 2
+    oc, ok = orc.kmeans(W[keep], bits[keep], iters=3)
+    assert np.array_equal(_np(c2)[keep], oc) and np.array_equal(_np(k2)[keep], ok)
+    st.zero_()
+    blank = torch.zeros_like(tables)
+    B.kmeans_quantize(dW, db, None, 0, None, 3, c2, k2, ws, st, arrangement=blank, arrangement_use=B.ARRANGEMENT_REUSE)
+    assert st.item() == B.STATUS_ARRANGEMENT and not _np(k2).any()
+    # the buffer is for the histogram kernel only, and is kept from all weights
+    with pytest.raises(B.CmpqError):
+        B.kmeans_quantize(_dev(W.astype(np.float32)), db, None, 0, None, 3, c2, k2, ws, arrangement=tables,
+                          arrangement_use=B.ARRANGEMENT_KEEP)
+    with pytest.raises(B.CmpqError):
+        B.kmeans_quantize(dW, db, _dev(np.array([5], np.int32)), 1, None, 3, c2, k2, ws, arrangement=tables,
+                          arrangement_use=B.ARRANGEMENT_KEEP)
+
+
 def test_kmeans_with_stored_format_other_inputs_and_flags(env):
     """The same job on inputs the histogram kernel does not take (fp32 weights, importance
     weights, the brute-force rounds): the general kernels run and the stored format follows in
