@@ -322,14 +322,25 @@ def main():
     # The timed region: K steps enqueued one after the other, as when a model is quantized block
     # after block; with several streams the queues of one step run on into the next and the
     # streams are joined once, before the closing synchronisation.
-    timer = P.StageTimer()      # entry points only: events around single kernels would break up the queues
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        out = step(timer, join=False)
+        out = step(join=False)
     if args.streams > 1:
         P.join_streams(dev, args.streams)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    # The same K steps once more with a pair of events around every entry point, on its stream:
+    # how long each stage takes while the other streams' launches share the GPU.  (Kept out of
+    # the timed steps: 70 event records a step on three streams cost a few per cent.)
+    timer = P.StageTimer()
+    t_ev = time.perf_counter()
+    for _ in range(args.steps):
+        o_ev = step(timer, join=False)
+    if args.streams > 1:
+        P.join_streams(dev, args.streams)
+    torch.cuda.synchronize()
+    dt_ev = time.perf_counter() - t_ev
+    del o_ev
     joined = None
     n_joined = args.steps if args.joined_steps is None else args.joined_steps
     if args.streams > 1 and n_joined > 0:
@@ -382,7 +393,7 @@ def main():
                 "credited_flop_per_launch": flops / max(n_km, 1),
                 "traffic_from": "constant: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE summary under profiles/",
                 "avg_entry_point_ms_in_timed_region": ms_km_timed / max(n_km, 1),
-                "timed_region_note": "events around the entry point on its stream inside the timed steps; with "
+                "timed_region_note": "events around the entry point on its stream in a repeat of the timed steps; with "
                                      "several streams the launches share the GPU, so this is longer than a launch alone"}
     valu = KMEANS_VALU_WAVE_INSTS_PER_STEP.get(wl.name)
     if valu is not None:
@@ -432,6 +443,8 @@ def main():
         "roofline": roofline,
         "hbm_kernels": hbm,
         "stages_ms_per_step": {k: round(v[1] / args.steps, 4) for k, v in sorted(stages.items())},
+        "stages_note": "entry-point durations from events on the launch streams, in a repeat of the timed steps "
+                       "(%.3f ms per step with the events in place)" % (dt_ev / args.steps * 1e3),
         "streams": args.streams,
         "final_pass": "two calls: cmpq_kmeans_quantize, cmpq_pack_with_error" if args.two_calls else
                       "one call: cmpq_kmeans_quantize_job writes the stored format and the error from its coding pass",

@@ -349,11 +349,12 @@ __device__ __forceinline__ bool channel_live(const WselArgs &a, int64_t i) {
     return b >= 1 && b <= 4;
 }
 
-// Calls body(i, o0, key, wv, valid) for every wave-chunk in [q0, q1) of a live channel,
-// in order; o0 is this lane's first output.  The loads of the next wave-chunk are issued
-// before the current one is worked on (two ahead was measured and is slower).
+// Calls body(i, o0, raw, cent) for every wave-chunk in [q0, q1) of a live channel, in order;
+// o0 is this lane's first output, raw its 8 entries as loaded, cent level (lane & 15) of the
+// channel.  The loads of the next wave-chunk are issued before the current one is worked on
+// (two ahead was measured and is slower).
 template <typename TW, typename F>
-__device__ __forceinline__ void for_each_wave_chunk(const WselArgs &a, int64_t q0, int64_t q1, F &&body) {
+__device__ __forceinline__ void for_each_raw_chunk(const WselArgs &a, int64_t q0, int64_t q1, F &&body) {
     if (q0 >= q1) return;
     const int lane = threadIdx.x & (CMPQ_WAVE - 1);
     int64_t i = q0 / a.wc_per_channel, c = q0 % a.wc_per_channel;
@@ -376,18 +377,61 @@ __device__ __forceinline__ void for_each_wave_chunk(const WselArgs &a, int64_t q
             }
             if (live_n) fetch8(a, ni, nc * kWaveChunk + lane * kWPerLane, nxt);
         }
-        if (live) {
-            const int64_t o0 = c * kWaveChunk + lane * kWPerLane;
-            uint32_t key[8];
-            float wv[8];
-            score_keys8<TW>(a, cur, cent, key, wv);
-            body(i, o0, key, wv, valid8(o0, a.d_out));
-        }
+        if (live) body(i, c * kWaveChunk + lane * kWPerLane, cur, cent);
         cur = nxt;
         i = ni;
         c = nc;
         live = live_n;
         cent = cent_n;
+    }
+}
+
+// The same with the score keys formed: body(i, o0, key, wv, valid).
+template <typename TW, typename F>
+__device__ __forceinline__ void for_each_wave_chunk(const WselArgs &a, int64_t q0, int64_t q1, F &&body) {
+    for_each_raw_chunk<TW>(a, q0, q1, [&](int64_t i, int64_t o0, const Raw8<TW> &raw, float cent) {
+        uint32_t key[8];
+        float wv[8];
+        score_keys8<TW>(a, raw, cent, key, wv);
+        body(i, o0, key, wv, valid8(o0, a.d_out));
+    });
+}
+
+// w - level in fp32 straight from a packed FP16 weight (the conversion is part of the
+// instruction: a fused multiply-add w * 1 - level with an FP16 first operand, rounded once,
+// which is the subtraction's own rounding).  HI picks the upper half of the word.
+template <int HI>
+__device__ __forceinline__ float half_minus(uint32_t packed, float level) {
+    float d;
+    if (HI)
+        asm("v_fma_mix_f32 %0, %1, 1.0, -%2 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "=v"(d) : "v"(packed), "v"(level));
+    else
+        asm("v_fma_mix_f32 %0, %1, 1.0, -%2 op_sel_hi:[1,0,0]" : "=v"(d) : "v"(packed), "v"(level));
+    return d;
+}
+
+// Signed scores of the 8 FP16 entries: w - level (residual score) or w (magnitude score); the
+// ranking key of an entry is the bit pattern of the magnitude of its score.
+__device__ __forceinline__ void signed_scores8(const WselArgs &a, const Raw8<__half> &r, float cent, float (&d)[8]) {
+    const uint32_t w4[4] = {r.w.x, r.w.y, r.w.z, r.w.w};
+    float level[8];
+    if (a.score == CMPQ_SCORE_RESIDUAL) {
+        // one branch for the whole piece, so that the eight lane exchanges are issued back to back
+        const uint32_t c4[2] = {(r.c.x & 0x0f0f0f0fu) << 2, (r.c.y & 0x0f0f0f0fu) << 2};
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            uint32_t at;
+            asm("v_bfe_u32 %0, %1, %2, 6" : "=v"(at) : "v"(c4[j >> 2]), "n"(8 * (j & 3)));
+            level[j] = __int_as_float(__builtin_amdgcn_ds_bpermute((int)at, __float_as_int(cent)));
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) level[j] = 0.f;
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        d[2 * j] = half_minus<0>(w4[j], level[2 * j]);
+        d[2 * j + 1] = half_minus<1>(w4[j], level[2 * j + 1]);
     }
 }
 
@@ -430,6 +474,50 @@ __device__ __forceinline__ void stage_chunk(uint32_t cand, int64_t i, int64_t o0
                 }
                 stage_ik[pos] = ((unsigned long long)(uint32_t)(i * d_out + o0 + j) << 32) | kj;
                 stage_val[pos] = __half_as_ushort(__float2half_rn(wj));
+                ++pos;
+            }
+        }
+    } else {
+        over = true;
+    }
+    n_staged += tot;
+}
+
+// stage_chunk for FP16 input: the key of a candidate is the magnitude of its signed score d,
+// its value the packed FP16 weight itself.
+__device__ __forceinline__ void stage_chunk_half(uint32_t cand, int64_t i, int64_t o0, int64_t d_out,
+                                                 const float (&d)[8], const uint4 &w,
+                                                 unsigned long long *__restrict__ stage_ik,
+                                                 uint16_t *__restrict__ stage_val, uint32_t cap,
+                                                 uint32_t &n_staged, bool &over) {
+    const unsigned long long has = __ballot(cand != 0);
+    if (has == 0ull) return;
+    uint32_t excl, tot;
+    if (__ballot((cand & (cand - 1)) != 0) == 0ull) {  // usual case: no lane holds two
+        excl = __builtin_amdgcn_mbcnt_hi((uint32_t)(has >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)has, 0u));
+        tot = (uint32_t)__popcll(has);
+    } else {
+        const uint32_t n_cand = __popc(cand);
+        const uint32_t incl = wave_scan_incl_u32(n_cand);
+        tot = __shfl(incl, CMPQ_WAVE - 1, CMPQ_WAVE);
+        excl = incl - n_cand;
+    }
+    if (n_staged + tot <= cap) {
+        uint32_t pos = n_staged + excl;
+        const uint32_t w4[4] = {w.x, w.y, w.z, w.w};
+        while (__ballot(cand != 0) != 0ull) {
+            if (cand) {
+                const int j = __ffs(cand) - 1;
+                cand &= cand - 1;
+                float dj = d[0];
+                uint32_t wj = w4[0];
+#pragma unroll
+                for (int t = 1; t < 8; ++t) {
+                    if (j == t) dj = d[t];
+                    if ((t & 1) == 0 && (j >> 1) == (t >> 1)) wj = w4[t >> 1];
+                }
+                stage_ik[pos] = ((unsigned long long)(uint32_t)(i * d_out + o0 + j) << 32) | __float_as_uint(fabsf(dj));
+                stage_val[pos] = (uint16_t)(wj >> (16 * (j & 1)));
                 ++pos;
             }
         }
@@ -592,14 +680,31 @@ __global__ __launch_bounds__(kWThreads) void wsel_stage_kernel(WselArgs a, WselS
     const uint32_t reach = guess22 << 10;  // (key >> 10) >= guess22 as one compare
     unsigned long long *stage_ik = a.stage_ik + unit * a.cap;
     uint16_t *stage_val = a.stage_val + unit * a.cap;
-    for_each_wave_chunk<TW>(a, q0, q1, [&](int64_t i, int64_t o0, const uint32_t (&key)[8], const float (&wv)[8], uint32_t valid) {
-        // bit j of cand: entry j exists and reaches the guess
-        uint32_t cand = 0;
+    if constexpr (std::is_same<TW, __half>::value) {
+        // FP16 weights: the scores stay signed floats and are compared by magnitude (the order of
+        // non-negative floats is that of their bit patterns, and "not below" keeps a NaN score a
+        // candidate, as its bit pattern would be), the conversion of a weight is folded into the
+        // subtraction, and only a candidate's key and value are formed
+        const float reach_f = __uint_as_float(reach);
+        for_each_raw_chunk<TW>(a, q0, q1, [&](int64_t i, int64_t o0, const Raw8<TW> &raw, float cent) {
+            float d[8];
+            signed_scores8(a, raw, cent, d);
+            uint32_t cand = 0;  // bit j: entry j reaches the guess
 #pragma unroll
-        for (int j = 7; j >= 0; --j) cand = cand + cand + (key[j] >= reach ? 1u : 0u);
-        cand &= valid;
-        stage_chunk(cand, i, o0, a.d_out, key, wv, stage_ik, stage_val, a.cap, n_staged, over);
-    });
+            for (int j = 7; j >= 0; --j) cand = cand + cand + (!(fabsf(d[j]) < reach_f) ? 1u : 0u);
+            cand &= valid8(o0, a.d_out);
+            stage_chunk_half(cand, i, o0, a.d_out, d, raw.w, stage_ik, stage_val, a.cap, n_staged, over);
+        });
+    } else {
+        for_each_wave_chunk<TW>(a, q0, q1, [&](int64_t i, int64_t o0, const uint32_t (&key)[8], const float (&wv)[8], uint32_t valid) {
+            // bit j of cand: entry j exists and reaches the guess
+            uint32_t cand = 0;
+#pragma unroll
+            for (int j = 7; j >= 0; --j) cand = cand + cand + (key[j] >= reach ? 1u : 0u);
+            cand &= valid;
+            stage_chunk(cand, i, o0, a.d_out, key, wv, stage_ik, stage_val, a.cap, n_staged, over);
+        });
+    }
     if (lane == 0) {
         a.stage_cnt[unit] = over ? 0u : n_staged;
         if (over) st->fast_overflow = 1u;
