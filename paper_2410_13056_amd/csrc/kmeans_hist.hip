@@ -175,6 +175,7 @@ __device__ __forceinline__ double coding_pass_fused(const KmArgs &a, int64_t i, 
     // boundary inside has one code; with one boundary, a code on either side of the boundary's
     // place; with more (rare) the entry sends the weight to the search
     constexpr bool kTable = K >= 8 && G * T >= 2 * kBuckets;  // worth it for long channels only
+    int multi = 0;
     if constexpr (kTable) {
         for (int bk = tid; bk < kBuckets; bk += T) {
             const uint32_t first = (uint32_t)bk << kLowBits;
@@ -184,12 +185,15 @@ __device__ __forceinline__ double coding_pass_fused(const KmArgs &a, int64_t i, 
                 ent |= 0xff00u;  // no place lies above this one
             } else {
                 ent |= (sm.tk[par][p0] & (kLows - 1)) << 8;
-                if (p1 > p0 + 1) ent |= 0x10000u;
+                if (p1 > p0 + 1) {
+                    ent |= 0x10000u;
+                    multi = 1;
+                }
             }
             tbl[bk] = ent;
         }
     }
-    __syncthreads();
+    const bool any_multi = __syncthreads_or(multi) != 0;  // also the barrier before the groups below
     const uint2 *wrow = reinterpret_cast<const uint2 *>(static_cast<const __half *>(a.W) + i * a.ldw);
     uint32_t *crow = a.codes ? reinterpret_cast<uint32_t *>(a.codes + i * a.d_out) : nullptr;
     double err = 0.0;
@@ -219,30 +223,34 @@ __device__ __forceinline__ double coding_pass_fused(const KmArgs &a, int64_t i, 
             const bool in = g < n_groups;
             const uint2 cur = chunk[u];
             const uint32_t kk[2] = {keys_of_half2(cur.x), keys_of_half2(cur.y)};
-            uint32_t word = 0;  // the 4 codes, one per byte
+            uint32_t code[4];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const uint32_t key = (kk[e >> 1] >> (16 * (e & 1))) & 0xffffu;
-                uint32_t code;
                 if constexpr (kTable) {
                     const uint32_t ent = tbl[key >> kLowBits];
-                    code = (key & (kLows - 1)) > ((ent >> 8) & 0xffu) ? (ent >> 4) & 15u : ent & 15u;
-                    if (ent & 0x10000u) code = sm.code_of[cell_of<K>(key, thr)];
+                    code[e] = (key & (kLows - 1)) > ((ent >> 8) & 0xffu) ? (ent >> 4) & 15u : ent & 15u;
+                    if (any_multi && (ent & 0x10000u)) code[e] = sm.code_of[cell_of<K>(key, thr)];
                 } else {
-                    code = sm.code_of[cell_of<K>(key, thr)];
+                    code[e] = sm.code_of[cell_of<K>(key, thr)];
                 }
-                word |= code << (8 * e);
             }
+            const uint32_t word = code[0] | (code[1] << 8) | (code[2] << 16) | (code[3] << 24);  // one code per byte
             if (in && crow) crow[g] = word;
+            // (w - level)^2 of the four entries; an entry of O_q (restored to its FP16 weight) and a
+            // lane past the end add an exact zero: their difference is masked bit by bit
             uint32_t kept = in ? 0xfu : 0u;
             if (n_ex > 0 && in) kept = ~(removed[g >> 3] >> ((g & 7) * 4)) & 0xfu;
             const uint32_t hw[2] = {cur.x, cur.y};
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const float w = __half2float(__ushort_as_half((unsigned short)(hw[e >> 1] >> (16 * (e & 1)))));
-                double d = (double)w - sm.cent64[(word >> (8 * e)) & 15u];
-                d = ((kept >> e) & 1u) ? d : 0.0;
-                err = fma(d, d, err);
+                const double d = (double)w - sm.cent64[code[e]];
+                const uint32_t m = (uint32_t)__builtin_amdgcn_sbfe((int)kept, e, 1);  // all ones or zero
+                const unsigned long long db = (unsigned long long)__double_as_longlong(d);
+                const double dm = __longlong_as_double((long long)(((unsigned long long)(m & (uint32_t)(db >> 32)) << 32) |
+                                                                   (m & (uint32_t)db)));
+                err = fma(dm, dm, err);
             }
             const uint32_t f = in ? squeeze4<B>(word) : 0u;
             if constexpr (B == 4) {
