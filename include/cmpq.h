@@ -563,6 +563,23 @@ int cmpq_lut_matvec_group(const cmpq_deployed_layer *layers, int n_layers, int64
 #define CMPQ_KERNEL_COUNT 5
 int cmpq_time_kernel(int kernel, void *event_begin, void *event_end);
 
+/*
+ * Measurement helper (for a benchmark that prices a kernel against a peak that depends on the
+ * clock): the shader clock under a vector-ALU load.  Enqueues one kernel on `stream`:
+ * n_workgroups workgroups of 256 lanes each run `iters` rounds of 64 dependent fused
+ * multiply-adds on four independent chains per lane and read two counters before and after,
+ * the shader-clock counter and the constant-rate wall counter.
+ *   ticks     [n_workgroups, 2] u64 out, device: per workgroup the two differences
+ *             (shader ticks, wall ticks);
+ *   wall_khz  host out: the rate of the wall counter in kHz.
+ * clock = shader ticks / wall ticks * wall rate, per workgroup; the caller reads `ticks`
+ * after synchronising.  With n_workgroups a multiple of the number of compute units the
+ * whole GPU is busy while the counters run.  It changes nothing else and keeps nothing.
+ * CMPQ_EINVAL: null pointer, iters < 1, n_workgroups outside 1..65536; CMPQ_EHIP when the
+ * runtime does not report the wall counter's rate.
+ */
+int cmpq_shader_clock_probe(int iters, int n_workgroups, uint64_t *ticks, int *wall_khz, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

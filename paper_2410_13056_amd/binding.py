@@ -39,7 +39,8 @@ EXPORTS = ("cmpq_workspace_bytes", "cmpq_strerror", "cmpq_count_ppm", "cmpq_act_
            "cmpq_kmeans_quantize", "cmpq_pack", "cmpq_dequant_error", "cmpq_kmeans_quantize_job",
            "cmpq_gather_channels", "cmpq_outliers_by_column", "cmpq_lut_matvec", "cmpq_act_stats_norm",
            "cmpq_rtn_quantize", "cmpq_select_by_width", "cmpq_lut_matvec_group", "cmpq_lut4_quantize",
-           "cmpq_pack_with_error", "cmpq_time_kernel", "cmpq_act_stats_static", "cmpq_kmeans_launch_shape")
+           "cmpq_pack_with_error", "cmpq_time_kernel", "cmpq_act_stats_static", "cmpq_kmeans_launch_shape",
+           "cmpq_shader_clock_probe")
 
 _i64, _i32, _int, _vp, _dbl, _sz = (ctypes.c_int64, ctypes.c_int32, ctypes.c_int, ctypes.c_void_p,
                                     ctypes.c_double, ctypes.c_size_t)
@@ -102,6 +103,7 @@ def lib() -> ctypes.CDLL:
         L.cmpq_kmeans_quantize_job.argtypes = [ctypes.POINTER(KmeansJob), _vp, _sz, _vp]
         L.cmpq_time_kernel.argtypes = [_int, _vp, _vp]
         L.cmpq_kmeans_launch_shape.argtypes = [_i64, _vp]
+        L.cmpq_shader_clock_probe.argtypes = [_int, _int, _vp, _vp, _vp]
         L.cmpq_act_stats_static.argtypes = [_vp, _int, _i64, _i64, _i64, _vp, _vp, _int, _vp, _vp]
         L.cmpq_act_stats_norm.argtypes = [_vp, _int, _i64, _i64, _i64, _int, _vp, _vp, _int, _vp, _sz, _vp, _vp]
         L.cmpq_gather_channels.argtypes = [_vp, _int, _i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp]
@@ -138,6 +140,16 @@ def time_kernel(kernel: int, event_begin: Optional[int], event_end: Optional[int
     """Arms the calling thread: the next launch of `kernel` is bracketed by the two events
     (raw hipEvent_t handles as integers); None disarms."""
     _check(lib().cmpq_time_kernel(int(kernel), event_begin, event_end), "cmpq_time_kernel")
+
+
+def shader_clock_probe(iters: int, ticks: torch.Tensor) -> int:
+    """Enqueues the clock probe with one workgroup per row of `ticks` ([n, 2] int64, device);
+    returns the wall counter's rate in kHz.  Read `ticks` after synchronising."""
+    assert ticks.dtype == torch.int64 and ticks.dim() == 2 and ticks.shape[1] == 2 and ticks.is_contiguous()
+    khz = ctypes.c_int(0)
+    _check(lib().cmpq_shader_clock_probe(int(iters), int(ticks.shape[0]), _ptr(ticks), ctypes.byref(khz),
+                                         _stream()), "cmpq_shader_clock_probe")
+    return int(khz.value)
 
 
 def workspace_bytes(op: int, d_in: int, d_out: int = 0, n: int = 0) -> int:

@@ -74,6 +74,44 @@ extern "C" int cmpq_time_kernel(int kernel, void *event_begin, void *event_end) 
     return CMPQ_OK;
 }
 
+namespace {
+
+// Four independent chains of dependent fused multiply-adds per lane between two readings of
+// the shader-clock counter and of the constant-rate wall counter.
+__global__ __launch_bounds__(256) void shader_clock_kernel(int iters, unsigned long long *ticks) {
+    float a0 = (float)threadIdx.x * 1e-3f, a1 = a0 + 1.f, a2 = a0 + 2.f, a3 = a0 + 3.f;
+    const float m = 0.999f, c = 1e-3f;
+    const unsigned long long t0 = clock64(), w0 = wall_clock64();
+    for (int i = 0; i < iters; ++i) {
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+            a0 = fmaf(a0, m, c);
+            a1 = fmaf(a1, m, c);
+            a2 = fmaf(a2, m, c);
+            a3 = fmaf(a3, m, c);
+        }
+    }
+    const unsigned long long t1 = clock64(), w1 = wall_clock64();
+    if (threadIdx.x == 0) {
+        ticks[2 * blockIdx.x] = t1 - t0;
+        ticks[2 * blockIdx.x + 1] = w1 - w0;
+    }
+    if (a0 + a1 + a2 + a3 == 12345.678f) ticks[0] = 0;  // keeps the chains alive
+}
+
+}  // namespace
+
+extern "C" int cmpq_shader_clock_probe(int iters, int n_workgroups, uint64_t *ticks, int *wall_khz, void *stream) {
+    if (!ticks || !wall_khz || iters < 1 || n_workgroups < 1 || n_workgroups > 65536) return CMPQ_EINVAL;
+    int dev = 0, khz = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return CMPQ_EHIP;
+    if (hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev) != hipSuccess || khz <= 0) return CMPQ_EHIP;
+    *wall_khz = khz;
+    shader_clock_kernel<<<dim3((unsigned)n_workgroups), dim3(256), 0, static_cast<hipStream_t>(stream)>>>(
+        iters, reinterpret_cast<unsigned long long *>(ticks));
+    return hipGetLastError() == hipSuccess ? CMPQ_OK : CMPQ_EHIP;
+}
+
 void cmpq_timing_before(int kernel, hipStream_t s) {
     if (g_timer.kernel == kernel) (void)hipEventRecord(g_timer.begin, s);
 }

@@ -193,6 +193,13 @@ def test_host_side_argument_errors(L):
                                   None) == -1                                                             # a run missing
     assert L.cmpq_select_by_width(fake, 4, 64, (i32 * 2)(2, 3), 2, two, two, None, fake, None) == -1      # no output
     assert L.cmpq_select_by_width(None, 0, 64, (i32 * 2)(2, 3), 2, two, two, None, None, None) == 0       # nothing to do
+    # the clock probe
+    khz = ctypes.c_int(0)
+    L.cmpq_shader_clock_probe.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+    assert L.cmpq_shader_clock_probe(100, 4, None, ctypes.byref(khz), None) == -1                         # no output
+    assert L.cmpq_shader_clock_probe(0, 4, fake, ctypes.byref(khz), None) == -1                           # no rounds
+    assert L.cmpq_shader_clock_probe(100, 0, fake, ctypes.byref(khz), None) == -1                         # no workgroups
+    assert L.cmpq_shader_clock_probe(100, 70000, fake, ctypes.byref(khz), None) == -1                     # too many
 
 
 def test_product_package_does_not_reach_the_oracle():

@@ -915,6 +915,39 @@ def test_end_to_end_tiny_config(env):
     _compare_layer(env, r, o, wl.bit_set, exact_levels=False)
 
 
+def test_shader_clock_probe_reads_a_plausible_clock(env):
+    """The measurement helper: both counters advance in every workgroup and their ratio is a
+    clock between 0.5 and 3.5 GHz (the part's shader clock is 2.4 GHz at most)."""
+    B = env["B"]
+    ticks = torch.zeros((64, 2), dtype=torch.int64, device=DEV)
+    khz = B.shader_clock_probe(500, ticks)
+    torch.cuda.synchronize()
+    t = _np(ticks).astype(np.float64)
+    assert khz > 0 and (t > 0).all()
+    ghz = t[:, 0] / t[:, 1] * khz * 1e3 / 1e9
+    assert 0.5 < ghz.min() and ghz.max() < 3.5, (ghz.min(), ghz.max())
+
+
+@pytest.mark.parametrize("rho_act_ppm,rho_q_ppm", [(0, 0), (5000, 0), (0, 5000), (4500, 500), (2500, 2500),
+                                                    (500, 4500), (4500, 10000), (4500, 20000)])
+def test_outlier_ratio_sweep(env, rho_act_ppm, rho_q_ppm):
+    """The appendix's sweep over the share of outliers and its split between the two kinds (none,
+    one kind only, 0.5 % split three ways, 1 % and 2 % of weight outliers): every setting
+    against the oracle on one layer with a ragged channel length."""
+    P, synth, ws, orc = env["P"], env["synth"], env["ws"], env["orc"]
+    d_in, d_out, n = 320, 1336, 512
+    W = synth.make_weight(d_out, d_in, "f16", 11, DEV)
+    X = synth.make_activations(n, d_in, "f16", 12, DEV, hot_frac=0.02, hot_scale=20.0)
+    _, sumsq = P.activation_stats(X, ws)
+    bit_set, avg, iters = (2, 3, 4), 3.25, 6
+    r = P.quantize_layer(W, sumsq, bit_set, avg, rho_act_ppm, rho_q_ppm, iters, ws, with_error=True,
+                         keep_prelim=True)
+    o = orc.quantize_layer(_np(W).T.copy(), None, bit_set, avg, rho_act_ppm, rho_q_ppm, iters, sumsq=_np(sumsq))
+    assert len(o["act_idx"]) == env["B"].count_ppm(rho_act_ppm, d_in)
+    assert len(o["out_idx"]) == env["B"].count_ppm(rho_q_ppm, d_in * d_out)
+    _compare_layer(env, r, o, bit_set, exact_levels=True)
+
+
 @pytest.mark.parametrize("from_prelim", [None, 5])
 @pytest.mark.parametrize("name,shrink,tokens", [("q7b", 8, 2048), ("block7b", 16, 1024),
                                                 ("block13b", 16, 1024), ("block70b", 32, 512)])
