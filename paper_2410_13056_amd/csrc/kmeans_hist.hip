@@ -78,7 +78,9 @@ __device__ __forceinline__ uint32_t elem_key(const uint32_t (&keys)[2 * G], int 
 // multiples of 4 and filler in the unused tail, how many are <= pl, and their sum.  Four
 // places per word are compared at once: a byte plus (127 - pl) reaches bit 7 exactly when
 // it is above pl (places and pl are at most 127, the filler is 128: no carry leaves a
-// byte).  Result valid in every lane of the group.
+// byte).  The inverted bits 7 are counted, and a dot product of the word's bytes with them
+// gives 128 times the sum of the places they mark (below 2^32 for any channel: at most
+// 32 768 places of at most 127).  Result valid in every lane of the group.
 template <int L>
 __device__ __forceinline__ void scan_bucket(const unsigned char *arr, uint32_t begin, uint32_t end,
                                             uint32_t pl, uint32_t &n, uint32_t &l) {
@@ -86,20 +88,20 @@ __device__ __forceinline__ void scan_bucket(const unsigned char *arr, uint32_t b
     const uint32_t *words = reinterpret_cast<const uint32_t *>(arr);
     const uint32_t w_end = end >> 2;
     const uint32_t bias = 0x7f7f7f7fu - pl * 0x01010101u;
-    uint32_t cn = 0, cl = 0;
+    uint32_t cn = 0, cl7 = 0;
     for (uint32_t j = (begin >> 2) + sub; j < w_end; j += 4 * L) {  // four reads in flight
         uint32_t x[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) x[u] = j + u * L < w_end ? words[j + u * L] : kFill4;
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            const uint32_t le = (~((x[u] + bias) >> 7)) & 0x01010101u;  // 1 per byte <= pl
-            cn = __builtin_amdgcn_sad_u8(le, 0u, cn);
-            cl = __builtin_amdgcn_sad_u8(x[u] & ((le << 8) - le), 0u, cl);  // le * 255: a full byte per flag
+            const uint32_t le7 = ~(x[u] + bias) & 0x80808080u;  // bit 7 per byte <= pl
+            cn += (uint32_t)__builtin_popcount(le7);
+            cl7 = __builtin_amdgcn_udot4(x[u], le7, cl7, false);
         }
     }
     n = group_sum<L>(cn);
-    l = group_sum<L>(cl);
+    l = group_sum<L>(cl7) >> 7;
 }
 
 // Counts the buckets and sums the places of the kept weights (packed 64-bit LDS atomics).
@@ -336,8 +338,7 @@ __device__ __forceinline__ void lloyd_bucket(const KmArgs &a, int64_t i, BucketS
                         const uint32_t bias = 0x7f7f7f7fu - (uint32_t)mid * 0x01010101u;
                         uint32_t cn = 0;
 #pragma unroll
-                        for (int u = 0; u < 4; ++u)
-                            cn = __builtin_amdgcn_sad_u8((~((x[u] + bias) >> 7)) & 0x01010101u, 0u, cn);
+                        for (int u = 0; u < 4; ++u) cn += (uint32_t)__builtin_popcount(~(x[u] + bias) & 0x80808080u);
                         n = group_sum<L>(cn);
                     } else {
                         scan_bucket<L>(arr, begin, end, (uint32_t)mid, n, l);
