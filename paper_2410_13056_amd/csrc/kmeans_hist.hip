@@ -150,6 +150,65 @@ __device__ __forceinline__ void scatter_places(const uint32_t (&keys)[2 * G], co
     }
 }
 
+// The coding table over the buckets (many levels, long channels): a bucket with no boundary
+// inside has one code; with one boundary, a code on either side of it; with more (rare) the
+// entry sends the weight to the search.  An entry: byte 0 the code at or below the boundary,
+// byte 1 the low byte of the boundary's key (0xff: nothing lies above it), byte 2 the code
+// above it, bit 24 the flag for more than one boundary.  A key and a boundary of the same
+// bucket share all bits above the place, so their low bytes compare like their places.
+constexpr uint32_t kTblMulti = 0x1000000u;
+
+template <int K, int T, int LB>
+__device__ __forceinline__ int build_code_table(const uint32_t (&thr)[CMPQ_KMAX], const uint32_t *code_of,
+                                                const uint32_t *tk, uint32_t *tbl) {
+    constexpr int kLows = 1 << LB, kBuckets = 1 << (16 - LB);
+    int multi = 0;
+    for (int bk = threadIdx.x; bk < kBuckets; bk += T) {
+        const uint32_t first = (uint32_t)bk << LB;
+        const uint32_t p0 = cell_of<K>(first, thr), p1 = cell_of<K>(first + kLows - 1, thr);
+        uint32_t ent = code_of[p0] | (code_of[p1] << 16);
+        if (p1 == p0) {
+            ent |= 0xff00u;
+        } else {
+            ent |= (tk[p0] & 0xffu) << 8;
+            if (p1 > p0 + 1) {
+                ent |= kTblMulti;
+                multi = 1;
+            }
+        }
+        tbl[bk] = ent;
+    }
+    return multi;
+}
+
+// (v << 2) + base in one instruction (the compiler's own form of extract-shift-add is a
+// shift, a mask and an add); base is the same in every lane.
+__device__ __forceinline__ uint32_t shl2_add(uint32_t v, uint32_t base) {
+    uint32_t r;
+    asm("v_lshl_add_u32 %0, %1, 2, %2" : "=v"(r) : "v"(v), "s"(base));
+    return r;
+}
+
+// LDS address (byte offset inside the workgroup's LDS) of a pointer into shared memory.
+__device__ __forceinline__ uint32_t lds_address(const void *p) {
+    return (uint32_t)reinterpret_cast<uintptr_t>(p);
+}
+
+// The table entry of the key in half `half` (0: low, 1: high) of the packed pair kk; the
+// table starts at LDS address tbl_at.
+template <int LB>
+__device__ __forceinline__ uint32_t table_entry(uint32_t tbl_at, uint32_t kk, int half) {
+    typedef const uint32_t __attribute__((address_space(3))) *LdsWord;
+    const uint32_t bucket = __builtin_amdgcn_ubfe(kk, 16 * half + LB, 16 - LB);
+    return *(LdsWord)(uintptr_t)shl2_add(bucket, tbl_at);
+}
+
+// The code that entry `ent` gives the same key (when its flag for several boundaries is clear).
+__device__ __forceinline__ uint32_t code_from_entry(uint32_t ent, uint32_t kk, int half) {
+    const uint32_t low = (kk >> (16 * half)) & 0xffu;
+    return low > ((ent >> 8) & 0xffu) ? (ent >> 16) & 0xffu : ent & 0xffu;
+}
+
 // The coding pass with the stored format and the error folded in (Sec. 5.1; App. B.3): every
 // lane takes groups g = tid, tid + T, ... of 4 weights (fetched again: the place array cannot
 // give a weight's position back), finds their codes, adds (w - level)^2 in fp64 - nothing for an
@@ -173,29 +232,12 @@ __device__ __forceinline__ double coding_pass_fused(const KmArgs &a, int64_t i, 
     const int row_bytes = (int)(((int64_t)a.d_out * B + 31) / 32) * 4;
     const int coded = B == 4 ? 2 * n_groups : (B == 2 ? n_groups : (B == 3 ? 3 * ((n_groups + 1) >> 1) : (n_groups + 1) >> 1));
     for (int x = coded + tid; x < row_bytes; x += T) arr[x] = 0;
-    // a table over the buckets replaces the search where there are many levels: a bucket with no
-    // boundary inside has one code; with one boundary, a code on either side of the boundary's
-    // place; with more (rare) the entry sends the weight to the search
+    // a table over the buckets replaces the search where there are many levels
     constexpr bool kTable = K >= 8 && G * T >= 2 * kBuckets;  // worth it for long channels only
     int multi = 0;
-    if constexpr (kTable) {
-        for (int bk = tid; bk < kBuckets; bk += T) {
-            const uint32_t first = (uint32_t)bk << kLowBits;
-            const uint32_t p0 = cell_of<K>(first, thr), p1 = cell_of<K>(first + kLows - 1, thr);
-            uint32_t ent = sm.code_of[p0] | (sm.code_of[p1] << 4);
-            if (p1 == p0) {
-                ent |= 0xff00u;  // no place lies above this one
-            } else {
-                ent |= (sm.tk[par][p0] & (kLows - 1)) << 8;
-                if (p1 > p0 + 1) {
-                    ent |= 0x10000u;
-                    multi = 1;
-                }
-            }
-            tbl[bk] = ent;
-        }
-    }
+    if constexpr (kTable) multi = build_code_table<K, T, LB>(thr, sm.code_of, sm.tk[par], tbl);
     const bool any_multi = __syncthreads_or(multi) != 0;  // also the barrier before the groups below
+    const uint32_t tbl_at = lds_address(tbl);
     const uint2 *wrow = reinterpret_cast<const uint2 *>(static_cast<const __half *>(a.W) + i * a.ldw);
     uint32_t *crow = a.codes ? reinterpret_cast<uint32_t *>(a.codes + i * a.d_out) : nullptr;
     double err = 0.0;
@@ -228,13 +270,13 @@ __device__ __forceinline__ double coding_pass_fused(const KmArgs &a, int64_t i, 
             uint32_t code[4];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                const uint32_t key = (kk[e >> 1] >> (16 * (e & 1))) & 0xffffu;
                 if constexpr (kTable) {
-                    const uint32_t ent = tbl[key >> kLowBits];
-                    code[e] = (key & (kLows - 1)) > ((ent >> 8) & 0xffu) ? (ent >> 4) & 15u : ent & 15u;
-                    if (any_multi && (ent & 0x10000u)) code[e] = sm.code_of[cell_of<K>(key, thr)];
+                    const uint32_t ent = table_entry<LB>(tbl_at, kk[e >> 1], e & 1);
+                    code[e] = code_from_entry(ent, kk[e >> 1], e & 1);
+                    if (any_multi && (ent & kTblMulti))
+                        code[e] = sm.code_of[cell_of<K>((kk[e >> 1] >> (16 * (e & 1))) & 0xffffu, thr)];
                 } else {
-                    code[e] = sm.code_of[cell_of<K>(key, thr)];
+                    code[e] = sm.code_of[cell_of<K>((kk[e >> 1] >> (16 * (e & 1))) & 0xffffu, thr)];
                 }
             }
             const uint32_t word = code[0] | (code[1] << 8) | (code[2] << 16) | (code[3] << 24);  // one code per byte
@@ -419,10 +461,8 @@ __device__ __forceinline__ void lloyd_bucket(const KmArgs &a, int64_t i, BucketS
         if (lane < K - 1 && tk != kKeyInf) {
             const uint32_t b = tk >> kLowBits;
             const uint32_t cnt = sm.part_n[par][lane];
-            long long q0, step;
-            bucket_affine<LB>(b, q0, step);
             n_below = sm.ncum[b] + cnt;
-            s_below = sm.scum[b] + (long long)cnt * q0 + step * (long long)sm.part_l[par][lane];
+            s_below = sm.scum[b] + bucket_sum<LB>(b, cnt, sm.part_l[par][lane]);
         }
         // sorted positions live in lanes 0..15, one DPP row: neighbours come by row shifts
         const uint32_t n_prev = row_from_below(n_below);
@@ -489,26 +529,14 @@ __device__ __forceinline__ void lloyd_bucket(const KmArgs &a, int64_t i, BucketS
         else return elem_key<G>(keys, k, e);
     };
     // Many weights per lane and many levels: a table over the buckets replaces the search.
-    // A bucket with no boundary inside has one code; with one boundary, a code on either
-    // side of the boundary's place; with more (rare) the entry sends the weight to the search.
     constexpr bool kTable = K >= 8 && G * T >= 2 * kBuckets;
     if constexpr (kTable) {
-        int multi = 0;
-        for (int bk = tid; bk < kBuckets; bk += T) {
-            const uint32_t first = (uint32_t)bk << kLowBits;
-            const uint32_t p0 = cell_of<K>(first, thr), p1 = cell_of<K>(first + kLows - 1, thr);
-            uint32_t ent = sm.code_of[p0] | (sm.code_of[p1] << 4);
-            if (p1 == p0) {
-                ent |= 0xff00u;  // no place lies above this one
-            } else {
-                ent |= (sm.tk[par][p0] & (kLows - 1)) << 8;
-                if (p1 > p0 + 1) {
-                    ent |= 0x10000u;
-                    multi = 1;
-                }
-            }
-            tbl[bk] = ent;
-        }
+        const int multi = build_code_table<K, T, LB>(thr, sm.code_of, sm.tk[par], tbl);
+        const uint32_t tbl_at = lds_address(tbl);
+        auto pair_at = [&](int k, int e) -> uint32_t {
+            if constexpr (kReload) return again[2 * k + (e >> 1)];
+            else return keys[2 * k + (e >> 1)];
+        };
         if (!__syncthreads_or(multi)) {
 #pragma unroll
             for (int k = 0; k < G; ++k) {
@@ -516,10 +544,8 @@ __device__ __forceinline__ void lloyd_bucket(const KmArgs &a, int64_t i, BucketS
                 uint32_t word = 0;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    const uint32_t key = key_at(k, e);
-                    const uint32_t ent = tbl[key >> kLowBits];
-                    const uint32_t code = (key & (kLows - 1)) > ((ent >> 8) & 0xffu) ? (ent >> 4) & 15u : ent & 15u;
-                    word |= code << (8 * e);
+                    const uint32_t kk = pair_at(k, e);
+                    word |= code_from_entry(table_entry<LB>(tbl_at, kk, e & 1), kk, e & 1) << (8 * e);
                 }
                 if (g < n_groups) crow[g] = word;
             }
@@ -530,10 +556,10 @@ __device__ __forceinline__ void lloyd_bucket(const KmArgs &a, int64_t i, BucketS
                 uint32_t word = 0;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    const uint32_t key = key_at(k, e);
-                    const uint32_t ent = tbl[key >> kLowBits];
-                    uint32_t code = (key & (kLows - 1)) > ((ent >> 8) & 0xffu) ? (ent >> 4) & 15u : ent & 15u;
-                    if (ent & 0x10000u) code = sm.code_of[cell_of<K>(key, thr)];
+                    const uint32_t kk = pair_at(k, e);
+                    const uint32_t ent = table_entry<LB>(tbl_at, kk, e & 1);
+                    uint32_t code = code_from_entry(ent, kk, e & 1);
+                    if (ent & kTblMulti) code = sm.code_of[cell_of<K>(key_at(k, e), thr)];
                     word |= code << (8 * e);
                 }
                 if (g < n_groups) crow[g] = word;
@@ -754,10 +780,8 @@ __global__ __launch_bounds__(T) __attribute__((amdgpu_waves_per_eu(6, 7))) void 
                     const unsigned long long packed = (unsigned long long)sm.scum[b0 + r];
                     const uint32_t n = (uint32_t)(packed >> 32);
                     const uint32_t n_place = MODE == kModeReuse ? n_orig[r] : n;
-                    long long q0, step;
-                    bucket_affine<LB>((uint32_t)(b0 + r), q0, step);
                     n_loc += n | (((n_place + 3) & ~3u) << 16);
-                    s_loc += (long long)n * q0 + step * (long long)(packed & 0xffffffffu);
+                    s_loc += bucket_sum<LB>((uint32_t)(b0 + r), n, (uint32_t)packed);
                     if (keep_tbl) keep_tbl[b0 + r] = packed;
                 }
             }
@@ -773,9 +797,7 @@ __global__ __launch_bounds__(T) __attribute__((amdgpu_waves_per_eu(6, 7))) void 
                     const unsigned long long packed = (unsigned long long)sm.scum[b0 + r];
                     const uint32_t n = (uint32_t)(packed >> 32);
                     const uint32_t n_place = MODE == kModeReuse ? n_orig[r] : n;
-                    long long q0, step;
-                    bucket_affine<LB>((uint32_t)(b0 + r), q0, step);
-                    const long long sb = (long long)n * q0 + step * (long long)(packed & 0xffffffffu);
+                    const long long sb = bucket_sum<LB>((uint32_t)(b0 + r), n, (uint32_t)packed);
                     sm.ncum[b0 + r] = (uint16_t)(n_run & 0xffffu);
                     sm.start[b0 + r] = (uint16_t)(n_run >> 16);
                     cursor[b0 + r] = n_run >> 16;  // where the next place of the bucket goes

@@ -44,6 +44,19 @@ __device__ __forceinline__ void bucket_affine(uint32_t b, long long &q0, long lo
     q0 = (h & 0x8000u) ? -mag : mag;
 }
 
+// Sum of x*2^24 over n keys of bucket b whose places add up to l (n <= 32768, places <= 127):
+// (n * q0 + step * l) of bucket_affine, formed as a 32-bit product and one 64-bit shift
+// (|mantissa * n| < 2^26 and l < 2^23, so their sum fits 32 bits).
+template <int LB>
+__device__ __forceinline__ long long bucket_sum(uint32_t b, uint32_t n, uint32_t l) {
+    const uint32_t h = half_of_key(b << LB);
+    const uint32_t e = (h >> 10) & 31u;
+    const uint32_t sh = (e > 1 ? e : 1) - 1;
+    const int mant = (int)((e ? 1024u : 0u) + (h & 1023u));
+    const int t = __mul24((h & 0x8000u) ? -mant : mant, (int)n) + (int)l;
+    return (long long)((unsigned long long)(long long)t << sh);
+}
+
 // Value of the lane below / above inside a row of 16 lanes; 0 at the row's edge.
 __device__ __forceinline__ uint32_t row_from_below(uint32_t v) {
     return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x111, 0xF, 0xF, true);  // row_shr:1
@@ -140,21 +153,34 @@ __device__ __forceinline__ uint32_t cell_of(uint32_t q, const uint32_t (&t)[CMPQ
     }
 }
 
+// The largest fp16 value that is not above x (x finite, |x| < 65504), as its bit pattern: the
+// two narrowing conversions run with the rounding mode set to "towards minus infinity" (both
+// precision groups of the mode register), which is put back to "nearest even" - the mode this
+// library's kernels run in - before the block ends.  Rounding down twice is rounding down once.
+__device__ __forceinline__ uint32_t floor_half_of_double(double x) {
+    uint32_t h;
+    float f;
+    asm volatile(
+        "s_setreg_imm32_b32 hwreg(HW_REG_MODE, 0, 4), 0xa\n\t"
+        "s_nop 1\n\t"
+        "v_cvt_f32_f64 %1, %2\n\t"
+        "s_nop 0\n\t"
+        "v_cvt_f16_f32 %0, %1\n\t"
+        "s_setreg_imm32_b32 hwreg(HW_REG_MODE, 0, 4), 0x0\n\t"
+        "s_nop 1"
+        : "=v"(h), "=&v"(f)
+        : "v"(x));
+    return h & 0xffffu;
+}
+
 // Key of the largest fp16 value that belongs to `lo` rather than `hi` (lo < hi): values
 // below the midpoint, and the midpoint itself when lo has the smaller level index.
 // Never the key of -0: a boundary there would part the two zeros.
 __device__ __forceinline__ uint32_t boundary_key(float lo, float hi, int owner_lo, int owner_hi) {
-    const double mid = ((double)lo + (double)hi) * 0.5;
-    float f = (float)mid;  // round down to fp32 ...: one step towards -infinity when the cast went up
-    {
-        const uint32_t u = __float_as_uint(f);
-        const uint32_t down = f > 0.0f ? u - 1u : (f == 0.0f ? 0x80000001u : u + 1u);
-        f = (double)f > mid ? __uint_as_float(down) : f;
-    }
-    uint32_t h = __half_as_ushort(__float2half_rn(f));  // ... then down to fp16
-    h = h == 0x8000u ? 0u : h;                          // -0 is +0 here; checked below against f
+    const double mid = ((double)lo + (double)hi) * 0.5;  // exact
+    uint32_t h = floor_half_of_double(mid);
+    h = h == 0x8000u ? 0u : h;  // -0 is +0 here
     uint32_t key = key_of_half(h);
-    key -= value_of_key(key) > f ? 1u : 0u;
     key -= ((double)value_of_key(key) == mid && owner_hi < owner_lo) ? 1u : 0u;
     return key == 0x7fffu ? 0x7ffeu : key;
 }
