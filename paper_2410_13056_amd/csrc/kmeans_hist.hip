@@ -75,13 +75,13 @@ __device__ __forceinline__ uint32_t elem_key(const uint32_t (&keys)[2 * G], int 
 }
 
 // A group of L lanes: among the places of one bucket, arr[begin, end) with begin and end
-// multiples of 4 and filler in the unused tail, how many are <= pl, and their sum.  Four
-// places per word are compared at once: a byte plus (127 - pl) reaches bit 7 exactly when
+// multiples of 4 and filler in the unused tail, how many are <= pl, and their sum (U words
+// per lane in flight).  Four places per word are compared at once: a byte plus (127 - pl) reaches bit 7 exactly when
 // it is above pl (places and pl are at most 127, the filler is 128: no carry leaves a
 // byte).  The inverted bits 7 are counted, and a dot product of the word's bytes with them
 // gives 128 times the sum of the places they mark (below 2^32 for any channel: at most
 // 32 768 places of at most 127).  Result valid in every lane of the group.
-template <int L>
+template <int L, int U = 4>
 __device__ __forceinline__ void scan_bucket(const unsigned char *arr, uint32_t begin, uint32_t end,
                                             uint32_t pl, uint32_t &n, uint32_t &l) {
     const int sub = threadIdx.x & (L - 1);
@@ -89,12 +89,12 @@ __device__ __forceinline__ void scan_bucket(const unsigned char *arr, uint32_t b
     const uint32_t w_end = end >> 2;
     const uint32_t bias = 0x7f7f7f7fu - pl * 0x01010101u;
     uint32_t cn = 0, cl7 = 0;
-    for (uint32_t j = (begin >> 2) + sub; j < w_end; j += 4 * L) {  // four reads in flight
-        uint32_t x[4];
+    for (uint32_t j = (begin >> 2) + sub; j < w_end; j += U * L) {  // U reads in flight
+        uint32_t x[U];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) x[u] = j + u * L < w_end ? words[j + u * L] : kFill4;
+        for (int u = 0; u < U; ++u) x[u] = j + u * L < w_end ? words[j + u * L] : kFill4;
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < U; ++u) {
             const uint32_t le7 = ~(x[u] + bias) & 0x80808080u;  // bit 7 per byte <= pl
             cn += (uint32_t)__builtin_popcount(le7);
             cl7 = __builtin_amdgcn_udot4(x[u], le7, cl7, false);
@@ -418,7 +418,12 @@ __device__ __forceinline__ void lloyd_bucket(const KmArgs &a, int64_t i, BucketS
         }
     }
     uint32_t tk_prev = 0xffffffffu;
-    const int p_mine = tid / L;  // the boundary this lane helps with
+    // lanes per boundary in the rounds, and words each of them has in flight: the 512-lane
+    // workgroups give a boundary 16 lanes with 8 words (fewer wavefronts then execute the scan;
+    // measured 2 % faster there, 3 % slower for 256 lanes)
+    constexpr int LR = T >= 512 ? T / 32 : L;
+    constexpr int UR = 4 * (L / LR);
+    const int p_mine = tid / LR;  // the boundary this lane helps with
     int par = 0;
 
     for (int round = 0;; ++round) {
@@ -445,9 +450,9 @@ __device__ __forceinline__ void lloyd_bucket(const KmArgs &a, int64_t i, BucketS
             uint32_t n = 0, l = 0;
             if (t != kKeyInf) {
                 const uint32_t b = t >> kLowBits;
-                scan_bucket<L>(arr, sm.start[b], sm.start[b + 1], t & (kLows - 1), n, l);
+                scan_bucket<LR, UR>(arr, sm.start[b], sm.start[b + 1], t & (kLows - 1), n, l);
             }
-            if ((tid & (L - 1)) == 0) {
+            if ((tid & (LR - 1)) == 0) {
                 sm.part_n[par][p_mine] = n;
                 sm.part_l[par][p_mine] = l;
             }
