@@ -134,6 +134,21 @@ def deployed_matvec(P, B, torch, out, layers, wl, acts, reps):
         return (time.perf_counter() - t0) / reps
 
     dt_layer, dt, dt_whole = timed(per_layer), timed(grouped), timed(one_group)
+    # the variant that adds the packed rows up in FP16, same grouping (its own outputs)
+    ys_h = {name: torch.empty_like(ys[name]) for name, _ in layers}
+    groups_h = [(P.group_products([deps[n] for n in names], fp16acc=True), [xs[n] for n in names],
+                 [ys_h[n] for n in names]) for names in by_input.values()]
+    whole_h = (P.group_products([deps[n] for n, _ in layers], fp16acc=True), [xs[n] for n, _ in layers],
+               [ys_h[n] for n, _ in layers])
+
+    def grouped_h():
+        for call, gx, gy in groups_h:
+            call(gx, gy, ws)
+
+    dt_h, dt_whole_h = timed(grouped_h), timed(lambda: whole_h[0](whole_h[1], whole_h[2], ws))
+    torch.cuda.synchronize()
+    num = sum(float((ys_h[n].double() - ys[n].double()).pow(2).sum()) for n, _ in layers)
+    den = sum(float(ys[n].double().pow(2).sum()) for n, _ in layers)
     graph = P.capture_products(groups, ws)      # the same launches as `grouped`, submitted as one HIP graph
     dt_graph = timed(graph.replay)
     return {"what": "Y = x W_hat for one token through all layers of the block, from the stored format; "
@@ -145,7 +160,12 @@ def deployed_matvec(P, B, torch, out, layers, wl, acts, reps):
             "ms_per_token_all_products_in_one_group": dt_whole * 1e3,
             "roofline": {"bound": "hbm", "achieved": algo_bytes / dt / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                          "frac": algo_bytes / dt / 1e9 / HBM_PEAK_GBS,
-                         "algorithmic_bytes_per_token": algo_bytes}}
+                         "algorithmic_bytes_per_token": algo_bytes},
+            "fp16_sums": {"what": "the same products with the packed rows added up in FP16 "
+                                  "(cmpq_lut_matvec_group_fp16acc), same grouping",
+                          "ms_per_token": dt_h * 1e3, "ms_per_token_all_products_in_one_group": dt_whole_h * 1e3,
+                          "hbm_frac": algo_bytes / dt_h / 1e9 / HBM_PEAK_GBS,
+                          "relative_rms_difference_from_fp32_sums": (num / den) ** 0.5 if den > 0 else None}}
 
 
 def rtn_variant(P, B, torch, out, layers, wl, reps):

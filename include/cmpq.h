@@ -546,6 +546,26 @@ int cmpq_lut_matvec_group(const cmpq_deployed_layer *layers, int n_layers, int64
                           size_t ws_bytes, void *stream);
 
 /*
+ * The same products with the packed rows added up in FP16 (Sec. 6 / Fig. 4: the paper's
+ * kernel keeps FP16 throughout; cmpq_lut_matvec_group above adds in fp32).  Arguments, limits,
+ * workspace and errors are those of cmpq_lut_matvec_group.  What differs:
+ *   - a product X[t,i] * level is rounded to FP16 (to nearest even);
+ *   - the products of a run of R consecutive packed rows of one width (in the order of that
+ *     width's chan_idx; R = 32, halved while that leaves fewer than 512 workgroups, down to
+ *     8: the run length of the launch) are added in FP16, one after the other, starting from 0;
+ *   - the run sums, the rows of O_act (fp32 products) and the entries of O_q are then added
+ *     in fp32 in a fixed order, as in cmpq_lut_matvec_group: results are reproducible bit for
+ *     bit, and equal an emulation of the three steps up to the fp32 rounding of the last one.
+ * Against the exact product: |Y - Y_exact| <= (R + 1) * 2^-11 * sum_i |X[t,i] * W_hat[i,o]| over
+ * the packed rows, plus the fp32 rounding of cmpq_lut_matvec_group (a worst-case bound; errors of
+ * either sign mostly cancel).  There is no overflow check: a run whose partial sum leaves the
+ * FP16 range (|sum| > 65504) gives infinities, as FP16 arithmetic does - callers keep
+ * 32 * max|X| * max|level| below that.
+ */
+int cmpq_lut_matvec_group_fp16acc(const cmpq_deployed_layer *layers, int n_layers, int64_t m, void *ws,
+                                  size_t ws_bytes, void *stream);
+
+/*
  * Measurement hook (for a benchmark that wants the duration of one kernel rather than of an
  * entry point, which may launch several).  Arms the CALLING THREAD: the next launch of the
  * named kernel from this thread records event_begin (a hipEvent_t passed as void*) on the

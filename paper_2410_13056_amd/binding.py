@@ -40,7 +40,7 @@ EXPORTS = ("cmpq_workspace_bytes", "cmpq_strerror", "cmpq_count_ppm", "cmpq_act_
            "cmpq_gather_channels", "cmpq_outliers_by_column", "cmpq_lut_matvec", "cmpq_act_stats_norm",
            "cmpq_rtn_quantize", "cmpq_select_by_width", "cmpq_lut_matvec_group", "cmpq_lut4_quantize",
            "cmpq_pack_with_error", "cmpq_time_kernel", "cmpq_act_stats_static", "cmpq_kmeans_launch_shape",
-           "cmpq_shader_clock_probe")
+           "cmpq_shader_clock_probe", "cmpq_lut_matvec_group_fp16acc")
 
 _i64, _i32, _int, _vp, _dbl, _sz = (ctypes.c_int64, ctypes.c_int32, ctypes.c_int, ctypes.c_void_p,
                                     ctypes.c_double, ctypes.c_size_t)
@@ -113,6 +113,7 @@ def lib() -> ctypes.CDLL:
         L.cmpq_rtn_quantize.argtypes = [_vp, _int, _i64, _i64, _i64, _vp, _i64, _vp, _vp, _vp, _vp, _vp, _vp]
         L.cmpq_lut4_quantize.argtypes = [_int, _vp, _vp, _i64, _int, _vp, _vp, _vp, _vp, _sz, _vp]
         L.cmpq_lut_matvec_group.argtypes = [_vp, _int, _i64, _vp, _sz, _vp]
+        L.cmpq_lut_matvec_group_fp16acc.argtypes = [_vp, _int, _i64, _vp, _sz, _vp]
         L.cmpq_select_by_width.argtypes = [_vp, _i64, _i64, _vp, _int, _vp, _vp, _vp, _vp, _vp]
         for name in EXPORTS[3:]:
             getattr(L, name).restype = _int
@@ -436,10 +437,11 @@ class LutMatvecCall:
 
 
 class LutMatvecGroupCall:
-    """``cmpq_lut_matvec_group`` for a fixed set of deployed layers (`LutMatvecCall` objects):
-    the array of layer descriptions is built once; a call fills in inputs and outputs."""
+    """``cmpq_lut_matvec_group`` (``cmpq_lut_matvec_group_fp16acc`` with `fp16acc`) for a fixed set
+    of deployed layers (`LutMatvecCall` objects): the array of layer descriptions is built once; a
+    call fills in inputs and outputs."""
 
-    def __init__(self, calls: Sequence[LutMatvecCall]):
+    def __init__(self, calls: Sequence[LutMatvecCall], fp16acc: bool = False):
         if not 1 <= len(calls) <= MAX_GROUP:
             raise ValueError(f"a group holds 1..{MAX_GROUP} layers")
         self._calls = list(calls)
@@ -451,7 +453,7 @@ class LutMatvecGroupCall:
             L.packed, L.chan_idx, L.lut = ctypes.addressof(pk), ctypes.addressof(ci), ctypes.addressof(lt)
             L.act_idx, L.W_act, L.colptr, L.row_idx, L.delta = act_idx, W_act, colptr, row_idx, delta
         self._ws_bytes = {}
-        self._fn = lib().cmpq_lut_matvec_group
+        self._fn = lib().cmpq_lut_matvec_group_fp16acc if fp16acc else lib().cmpq_lut_matvec_group
 
     def __call__(self, Xs: Sequence[torch.Tensor], Ys: Sequence[torch.Tensor], ws: Workspace) -> None:
         if len(Xs) != len(self._calls) or len(Ys) != len(self._calls):

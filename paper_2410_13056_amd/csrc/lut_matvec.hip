@@ -165,19 +165,23 @@ __device__ __forceinline__ void lut_slab(const LmArgs &a, const LmWidth &wd, int
     };
 
     if (r0 < r1) {
+        // The tables of a group are written one group ahead, into the buffer the look-ups of the
+        // group before have just left, so that the write has a whole group of look-ups to land
+        // in; the table entries themselves are fetched two groups ahead, the words one.
         uint32_t w[kGroup][B], wn[kGroup][B];
-        float e = table_entry(r0), en = 0.f;
+        const bool fills = kGroup * K >= CMPQ_WAVE || lane < kGroup * K;
+        if (fills) tbl[wave][0][lane % (kGroup * K)] = table_entry(r0);
+        float e = r0 + kGroup < r1 ? table_entry(r0 + kGroup) : 0.f, en = 0.f;
         load_words(r0, w);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
         int buf = 0;
         for (int64_t r = r0; r < r1; r += kGroup) {
-            // publish this group's tables, fetch the next group's words and table entry
-            if (kGroup * K >= CMPQ_WAVE || lane < kGroup * K) tbl[wave][buf][lane % (kGroup * K)] = e;
             if (r + kGroup < r1) {
-                en = table_entry(r + kGroup);
+                if (fills) tbl[wave][buf ^ 1][lane % (kGroup * K)] = e;
                 load_words(r + kGroup, wn);
             }
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
+            if (r + 2 * kGroup < r1) en = table_entry(r + 2 * kGroup);
             // byte offset of this wavefront's current buffer; code * 4 is added to it with one
             // shift-and-add
             const char *base = reinterpret_cast<const char *>(&tbl[0][0][0]);
@@ -189,6 +193,7 @@ __device__ __forceinline__ void lut_slab(const LmArgs &a, const LmWidth &wd, int
                 for (int k = 0; k < kOutPerLane; ++k)
                     acc[k] += *reinterpret_cast<const float *>(base + g * K * 4 + entry_offset(code_at<B>(w[g], k), wb));
             }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
             buf ^= 1;
             e = en;
@@ -321,6 +326,134 @@ __device__ __forceinline__ void lut_slab_pairs(const LmArgs &a, const LmWidth &w
     store_partial(acc, red, a.partial + (token * a.n_rows_total + wd.slab0 + slab) * d_out, d_out);
 }
 
+// The variant that adds up in FP16 (the paper's product keeps FP16 throughout, Sec. 6): the
+// products x * level are rounded to FP16, and a wavefront adds those of its run of at most 32
+// rows of a slab in FP16, two outputs per packed addition; the run's sums are then widened
+// to fp32 and take the same way as in lut_slab (added over wavefronts, slabs, O_act and O_q in
+// fp32, in a fixed order).  Every width looks two neighbouring codes up at once: per row a
+// table of 2^(2B) pairs (product of the even output's code, product of the odd one's), 4
+// bytes an entry, built from the row's 2^B products with two LDS reads per entry (for width
+// 4: four entries per lane and row from one 8-byte read, one 2-byte read and one 16-byte
+// store).  A weight then costs half an extract, half a shift-and-add, half an LDS read and
+// half a packed addition.  Tables of 64 and 256 entries wrap around the LDS banks, so their
+// reads collide; with 4-byte entries that costs less than the instructions saved (with the
+// 8-byte entries of fp32 pairs it did not).  Same slab shape, prefetch and double buffering
+// as lut_slab.
+constexpr int kHalfPairBytes = kGroup * 256 * 4;               // pair tables of a group of rows at width 4
+constexpr int kHalfBufBytes = kHalfPairBytes + kGroup * 16 * 2;  // + the rows' own products
+constexpr int kHalfLdsBytes = kWaves * 2 * kHalfBufBytes;
+
+template <int B>
+__device__ __forceinline__ void lut_slab_half(const LmArgs &a, const LmWidth &wd, int slab, unsigned char *smem,
+                                              float (*red)[kRedFloats]) {
+    constexpr int K = 1 << B, PB = 2 * B, KP = 1 << PB;
+    const __half *__restrict__ X = a.X;
+    const int64_t d_out = a.d_out;
+    const int lane = threadIdx.x & (CMPQ_WAVE - 1), wave = wave_index();
+    const int64_t token = blockIdx.z;
+    const __half *x = X + token * a.ldx;
+    const int64_t word0 = (int64_t)blockIdx.x * (kTileOut / 32) * B + (int64_t)lane * B;
+    const int64_t r0 = ((int64_t)slab * kWaves + wave) * a.rows_per_wave;
+    const int64_t r1 = min(wd.rows, r0 + a.rows_per_wave);
+    __half2 acc2[kOutPerLane / 2];
+#pragma unroll
+    for (int p = 0; p < kOutPerLane / 2; ++p) acc2[p] = __half2{__ushort_as_half(0), __ushort_as_half(0)};
+
+    // product (row g, level c) of a group is formed by lane g * K + c
+    const int fill_g = lane / K, fill_c = lane % K;
+    auto product = [&](int64_t r) -> uint32_t {
+        if (fill_g >= kGroup || r + fill_g >= r1) return 0u;  // rows past the end: tables of zeros
+        const int64_t row = r + fill_g;
+        const float xi = __half2float(x[wd.chan_idx[row]]);
+        return __half_as_ushort(__float2half_rn(xi * __half2float(__ushort_as_half(wd.lut[row * K + fill_c]))));
+    };
+    const bool full = word0 + B <= wd.words_per_row;
+    auto load_words = [&](int64_t r, uint32_t (&w)[kGroup][B]) {
+#pragma unroll
+        for (int g = 0; g < kGroup; ++g) {
+            const uint32_t *p = wd.packed + (r + g) * wd.words_per_row + word0;
+            if (r + g < r1 && full) {
+                typedef uint32_t WordsB __attribute__((ext_vector_type(B), aligned(4)));
+                const WordsB v = *reinterpret_cast<const WordsB *>(p);
+#pragma unroll
+                for (int j = 0; j < B; ++j) w[g][j] = v[j];
+            } else {
+#pragma unroll
+                for (int j = 0; j < B; ++j) w[g][j] = (r + g < r1 && word0 + j < wd.words_per_row) ? p[j] : 0u;
+            }
+        }
+    };
+
+    if (r0 < r1) {
+        uint32_t w[kGroup][B], wn[kGroup][B];
+        uint32_t e = product(r0), en = 0u;
+        load_words(r0, w);
+        int buf = 0;
+        for (int64_t r = r0; r < r1; r += kGroup) {
+            unsigned char *mine = smem + (wave * 2 + buf) * kHalfBufBytes;
+            uint32_t *pair = reinterpret_cast<uint32_t *>(mine);
+            uint16_t *own = reinterpret_cast<uint16_t *>(mine + kHalfPairBytes);  // [row of the group][level]
+            if (kGroup * K >= CMPQ_WAVE || lane < kGroup * K) own[lane % (kGroup * K)] = (uint16_t)e;
+            if (r + kGroup < r1) {
+                en = product(r + kGroup);
+                load_words(r + kGroup, wn);
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            if constexpr (B == 4) {
+                // lane: odd output's code c1 = lane / 4, even output's codes 4 (lane % 4) .. + 3
+                const int c1 = lane >> 2, c0 = (lane & 3) * 4;
+#pragma unroll
+                for (int g = 0; g < kGroup; ++g) {
+                    const uint32_t hi = (uint32_t)own[g * K + c1] << 16;
+                    const uint2 q = *reinterpret_cast<const uint2 *>(own + g * K + c0);
+                    uint4 v;
+                    v.x = (q.x & 0xffffu) | hi;
+                    v.y = (q.x >> 16) | hi;
+                    v.z = (q.y & 0xffffu) | hi;
+                    v.w = (q.y >> 16) | hi;
+                    *reinterpret_cast<uint4 *>(pair + g * KP + c1 * K + c0) = v;
+                }
+            } else {
+#pragma unroll
+                for (int t0 = 0; t0 < kGroup * KP; t0 += CMPQ_WAVE) {
+                    const int t = t0 + lane;
+                    if (kGroup * KP % CMPQ_WAVE == 0 || t < kGroup * KP) {
+                        const int g = t / KP, ent = t % KP;
+                        pair[t] = (uint32_t)own[g * K + (ent & (K - 1))] | ((uint32_t)own[g * K + (ent >> B)] << 16);
+                    }
+                }
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            const char *base = reinterpret_cast<const char *>(smem);
+            const uint32_t wb = (uint32_t)((wave * 2 + buf) * kHalfBufBytes);
+#pragma unroll
+            for (int g = 0; g < kGroup; ++g) {
+#pragma unroll
+                for (int p = 0; p < kOutPerLane / 2; ++p) {
+                    const uint32_t v = *reinterpret_cast<const uint32_t *>(base + g * (KP * 4) + entry_offset(field_at<B, PB>(w[g], p), wb));
+                    acc2[p] = __hadd2(acc2[p], __half2{__ushort_as_half((unsigned short)(v & 0xffffu)), __ushort_as_half((unsigned short)(v >> 16))});
+                }
+            }
+            __builtin_amdgcn_wave_barrier();
+            buf ^= 1;
+            e = en;
+#pragma unroll
+            for (int g = 0; g < kGroup; ++g)
+#pragma unroll
+                for (int j = 0; j < B; ++j) w[g][j] = wn[g][j];
+        }
+    }
+    float acc[kOutPerLane];
+#pragma unroll
+    for (int p = 0; p < kOutPerLane / 2; ++p) {
+        acc[2 * p] = __low2float(acc2[p]);
+        acc[2 * p + 1] = __high2float(acc2[p]);
+    }
+    store_partial(acc, red, a.partial + (token * a.n_rows_total + wd.slab0 + slab) * d_out, d_out);
+}
+
 // A slab of O_act: 8 rows of FP16 weights per wavefront times their inputs (few rows, so
 // short slabs: the loop over rows is bound by latency).  A lane reads its 32 outputs of a
 // row as four 16-byte pieces, two rows in flight; the rows' inputs are fetched up front,
@@ -413,6 +546,34 @@ __global__ __launch_bounds__(kThreads) void lut_matvec_kernel(LmGroup g) {
         case 2: lut_slab_pairs<2>(a, wd, slab, smem, red); break;
         case 3: lut_slab<3>(a, wd, slab, tbl, red); break;
         default: lut_slab<4>(a, wd, slab, tbl, red); break;
+    }
+}
+
+// The same launch with the packed rows added up in FP16 (lut_slab_half); the O_act slabs are
+// the fp32 ones.
+__global__ __launch_bounds__(kThreads) void lut_matvec_half_kernel(LmGroup g) {
+    __shared__ __align__(16) unsigned char smem[kHalfLdsBytes];
+    static_assert(kHalfLdsBytes >= kWaves * kRedFloats * (int)sizeof(float), "the wavefronts' sums fit the shared piece");
+    float(*red)[kRedFloats] = reinterpret_cast<float(*)[kRedFloats]>(smem);
+    int l = 0;
+    while (l + 1 < g.n_layers && (int)blockIdx.y >= g.l[l + 1].y0) ++l;
+    const LmArgs &a = g.l[l];
+    if ((int)blockIdx.x >= a.tiles) return;
+    int y = (int)blockIdx.y - a.y0;
+    if (y < a.n_act_slabs) {
+        act_slab(a, y, red);
+        return;
+    }
+    y -= a.n_act_slabs;
+    int j = 0;
+    while (j + 1 < a.n_widths && y >= a.w[j + 1].slab0) ++j;
+    const LmWidth &wd = a.w[j];
+    const int slab = y - wd.slab0;
+    switch (wd.bits) {
+        case 1: lut_slab_half<1>(a, wd, slab, smem, red); break;
+        case 2: lut_slab_half<2>(a, wd, slab, smem, red); break;
+        case 3: lut_slab_half<3>(a, wd, slab, smem, red); break;
+        default: lut_slab_half<4>(a, wd, slab, smem, red); break;
     }
 }
 
@@ -719,7 +880,7 @@ int check_layer(const cmpq_deployed_layer &L, int64_t m) {
 }
 
 int launch_group(const cmpq_deployed_layer *layers, int n_layers, int64_t m, void *ws, size_t ws_bytes,
-                 void *stream) {
+                 void *stream, bool half_sums = false) {
     if (n_layers < 0 || n_layers > kMaxLayers || m < 0 || (n_layers > 0 && !layers)) return CMPQ_EINVAL;
     for (int i = 0; i < n_layers; ++i) {
         const int rc = check_layer(layers[i], m);
@@ -812,7 +973,8 @@ int launch_group(const cmpq_deployed_layer *layers, int n_layers, int64_t m, voi
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (y_total > 0) {
         const dim3 grid((unsigned)max_tiles, (unsigned)y_total, (unsigned)m);
-        lut_matvec_kernel<<<grid, kThreads, 0, st>>>(g);
+        if (half_sums) lut_matvec_half_kernel<<<grid, kThreads, 0, st>>>(g);
+        else lut_matvec_kernel<<<grid, kThreads, 0, st>>>(g);
     }
     const dim3 fgrid((unsigned)x_total, (unsigned)m);
     lut_matvec_finish_kernel<<<fgrid, kThreads, 0, st>>>(f);
@@ -825,6 +987,11 @@ int launch_group(const cmpq_deployed_layer *layers, int n_layers, int64_t m, voi
 extern "C" int cmpq_lut_matvec_group(const cmpq_deployed_layer *layers, int n_layers, int64_t m, void *ws,
                                      size_t ws_bytes, void *stream) {
     return launch_group(layers, n_layers, m, ws, ws_bytes, stream);
+}
+
+extern "C" int cmpq_lut_matvec_group_fp16acc(const cmpq_deployed_layer *layers, int n_layers, int64_t m, void *ws,
+                                             size_t ws_bytes, void *stream) {
+    return launch_group(layers, n_layers, m, ws, ws_bytes, stream, true);
 }
 
 extern "C" int cmpq_lut_matvec(const void *X, int64_t m, int64_t d_in, int64_t ldx, int64_t d_out,

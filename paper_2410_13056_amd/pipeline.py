@@ -431,11 +431,12 @@ def lut_matvec(dep: Deployed, X: torch.Tensor, ws: Optional[B.Workspace] = None,
     return Y
 
 
-def group_products(deps: Sequence[Deployed]) -> B.LutMatvecGroupCall:
+def group_products(deps: Sequence[Deployed], fp16acc: bool = False) -> B.LutMatvecGroupCall:
     """Sec. 6: several deployed layers whose products may run side by side (the projections that
     read the same input, or any independent ones) as one pair of launches:
-    ``group_products(deps)(Xs, Ys, ws)``.  Same results as one `lut_matvec` per layer."""
-    return B.LutMatvecGroupCall([d.call() for d in deps])
+    ``group_products(deps)(Xs, Ys, ws)``.  Same results as one `lut_matvec` per layer.
+    `fp16acc`: the packed rows are added up in FP16 (``cmpq_lut_matvec_group_fp16acc``)."""
+    return B.LutMatvecGroupCall([d.call() for d in deps], fp16acc=fp16acc)
 
 
 def capture_products(steps: Sequence[tuple], ws: B.Workspace):

@@ -126,6 +126,84 @@ def test_lut_matvec_parity_end_to_end(env, bit_set, avg, d_in, d_out):
     assert np.array_equal(_np(Yw[:, :d_out]), Y[:2]) and (_np(Yw[:, d_out:]) == 7.0).all()
 
 
+def _fp16_run_sums(X, cent, codes, bits, bit_set, run):
+    """The packed part of the FP16-sum product as its entry point defines it: products rounded
+    to FP16, runs of `run` consecutive rows of a width added in FP16 one after the other; the
+    run sums are returned added up exactly, with the sum of their magnitudes."""
+    m, d_out = X.shape[0], codes.shape[1]
+    lut16 = cent.astype(np.float16)
+    total = np.zeros((m, d_out)); mag = np.zeros((m, d_out))
+    for b in bit_set:
+        chans = np.flatnonzero(bits == b)
+        for s in range(0, len(chans), run):
+            acc = np.zeros((m, d_out), np.float16)
+            for i in chans[s:s + run]:
+                lv = lut16[i, codes[i].astype(np.int64)]
+                prod = (X[:, i:i + 1].astype(np.float32) * lv[None, :].astype(np.float32)).astype(np.float16)
+                acc = (acc.astype(np.float64) + prod.astype(np.float64)).astype(np.float16)   # one rounding
+            total += acc.astype(np.float64)
+            mag += np.abs(acc.astype(np.float64))
+    return total, mag
+
+
+@pytest.mark.parametrize("bit_set,avg,d_in,d_out", [((2, 3, 4), 3.0, 300, 2048 + 40), ((3, 4), 3.5, 520, 4096 + 8),
+                                                    ((1, 2, 3, 4), 2.5, 260, 33), ((2, 3, 4), 3.3, 1100, 2000)])
+def test_lut_matvec_fp16_sums(env, bit_set, avg, d_in, d_out):
+    """cmpq_lut_matvec_group_fp16acc: equal to the emulation of its three steps (FP16 products,
+    FP16 run sums at one of the three run lengths, fp32 after that) up to the fp32 rounding of
+    the last step - one wrong, missing or doubled term of typical size exceeds that bar -, within
+    its documented bound of the exact product, and reproducible."""
+    B, P, ws, orc = env["B"], env["P"], env["ws"], env["orc"]
+    rng = np.random.default_rng(7 * d_in + d_out)
+    W = rng.normal(0, 0.02, (d_in, d_out))
+    W[rng.random(W.shape) < 0.01] *= 10
+    W = W.astype(np.float16)
+    Xcal = (rng.normal(0, 1, (256, d_in)) * np.exp(rng.normal(0, 0.5, d_in))).astype(np.float16)
+    _, sumsq = P.activation_stats(_dev(Xcal), ws)
+    r = P.quantize_layer(_dev(W), sumsq, bit_set, avg, rho_act_ppm=20000, rho_q_ppm=10000, iters=5, ws=ws,
+                         transposed=True)
+    dep = P.prepare_deployment(r, ws)
+    bits, cent, codes, out_idx = _np(r.bits), _np(r.centroids), _np(r.codes), _np(r.out_idx).astype(np.int64)
+    What = _what(W, cent, codes, bits, out_idx)
+    lut16 = cent.astype(np.float16).astype(np.float64)
+    level = np.take_along_axis(np.where(np.isfinite(lut16), lut16, 0.0), codes.astype(np.int64), axis=1)
+    packed_rows = (bits >= 1) & (bits <= 4)
+    # what O_act and O_q add to the packed part: the FP16 rows, and weight minus level per entry
+    extra = np.zeros(W.shape)
+    extra[~packed_rows] = W[~packed_rows].astype(np.float64)
+    if len(out_idx):
+        extra.reshape(-1)[out_idx] = (W.astype(np.float64) - level).reshape(-1)[out_idx]
+    call = P.group_products([dep], fp16acc=True)
+    for m in (1, 3):
+        X = rng.normal(0, 1, (m, d_in)).astype(np.float16)
+        Y = torch.empty((m, d_out), dtype=torch.float32, device=DEV)
+        call([_dev(X)], [Y], ws)
+        Yg = _np(Y).astype(np.float64)
+        X64 = X.astype(np.float64)
+        rest = X64 @ extra
+        rest_mag = np.abs(X64) @ np.abs(extra)
+        best = None
+        for run in (32, 16, 8):
+            total, mag = _fp16_run_sums(X, cent, codes, bits, bit_set, run)
+            bound = 2e-6 * (mag + rest_mag) + 1e-30
+            ratio = float((np.abs(Yg - (total + rest)) / bound).max())
+            best = ratio if best is None else min(best, ratio)
+            if ratio <= 1.0:
+                # the documented bound against the exact product, for this run length
+                Yref = orc.lut_matvec(X, W, cent, codes, bits, out_idx)
+                packed_mag = np.abs(X64[:, packed_rows]) @ np.abs(level[packed_rows])
+                loose = (run + 1) * 2.0 ** -11 * packed_mag + 2e-6 * (np.abs(X64) @ np.abs(What)) + 1e-30
+                assert (np.abs(Yg - Yref) <= loose).all()
+                break
+        assert best is not None and best <= 1.0, best
+        Y2 = torch.empty_like(Y)
+        call([_dev(X)], [Y2], ws)
+        assert np.array_equal(_np(Y), _np(Y2))                                  # reproducible
+    # the fp32 product of the same layer is untouched by the variant's existence
+    Yf = _np(P.lut_matvec(dep, _dev(X), ws))
+    _check_product(Yf, orc.lut_matvec(X, W, cent, codes, bits, out_idx), X, What)
+
+
 def test_lut_matvec_without_outliers_and_all_protected(env):
     B, P, ws, orc = env["B"], env["P"], env["ws"], env["orc"]
     rng = np.random.default_rng(3)
