@@ -252,14 +252,17 @@ struct Raw8<float> {
     uint2 c;
 };
 
-__device__ __forceinline__ uint2 fetch_codes8(const WselArgs &a, int64_t i, int64_t o0, bool vec) {
+// (o0, a lane's first output of the wave-chunk, is a 32-bit offset from the channel's row, whose
+// address is the same in every lane: loads take that address from scalar registers)
+__device__ __forceinline__ uint2 fetch_codes8(const WselArgs &a, int64_t i, int o0, bool vec) {
     uint2 c = make_uint2(0, 0);
     if (!a.codes) return c;
     const uint8_t *crow = a.codes + i * a.d_out;
+    const int d_out = (int)a.d_out;
     if (vec) return *reinterpret_cast<const uint2 *>(crow + o0);
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-        if (o0 + j < a.d_out) {
+        if (o0 + j < d_out) {
             const uint32_t b = crow[o0 + j];
             if (j < 4) c.x |= b << (8 * j); else c.y |= b << (8 * (j - 4));
         }
@@ -267,30 +270,32 @@ __device__ __forceinline__ uint2 fetch_codes8(const WselArgs &a, int64_t i, int6
     return c;
 }
 
-__device__ __forceinline__ void fetch8(const WselArgs &a, int64_t i, int64_t o0, Raw8<__half> &r) {
+__device__ __forceinline__ void fetch8(const WselArgs &a, int64_t i, int o0, Raw8<__half> &r) {
     const uint16_t *wrow = static_cast<const uint16_t *>(a.W) + i * a.ldw;
-    const bool vec = a.vec_ok && o0 + 8 <= a.d_out;
+    const int d_out = (int)a.d_out;
+    const bool vec = a.vec_ok && o0 + 8 <= d_out;
     if (vec) {
         r.w = *reinterpret_cast<const uint4 *>(wrow + o0);
     } else {
         uint32_t h[8];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) h[j] = o0 + j < a.d_out ? wrow[o0 + j] : 0u;
+        for (int j = 0; j < 8; ++j) h[j] = o0 + j < d_out ? wrow[o0 + j] : 0u;
         r.w = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
     }
     r.c = fetch_codes8(a, i, o0, vec);
 }
 
-__device__ __forceinline__ void fetch8(const WselArgs &a, int64_t i, int64_t o0, Raw8<float> &r) {
+__device__ __forceinline__ void fetch8(const WselArgs &a, int64_t i, int o0, Raw8<float> &r) {
     const float *wrow = static_cast<const float *>(a.W) + i * a.ldw;
-    const bool vec = a.vec_ok && o0 + 8 <= a.d_out;
+    const int d_out = (int)a.d_out;
+    const bool vec = a.vec_ok && o0 + 8 <= d_out;
     if (vec) {
         r.w0 = *reinterpret_cast<const float4 *>(wrow + o0);
         r.w1 = *reinterpret_cast<const float4 *>(wrow + o0 + 4);
     } else {
         float f[8];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) f[j] = o0 + j < a.d_out ? wrow[o0 + j] : 0.f;
+        for (int j = 0; j < 8; ++j) f[j] = o0 + j < d_out ? wrow[o0 + j] : 0.f;
         r.w0 = make_float4(f[0], f[1], f[2], f[3]);
         r.w1 = make_float4(f[4], f[5], f[6], f[7]);
     }
@@ -339,9 +344,10 @@ __device__ __forceinline__ void score_keys8(const WselArgs &a, const Raw8<TW> &r
     for (int j = 0; j < 8; ++j) key[j] = __float_as_uint(fabsf(wv[j] - level[j]));
 }
 
-__device__ __forceinline__ uint32_t valid8(int64_t o0, int64_t d_out) {
+__device__ __forceinline__ uint32_t valid8(int o0, int64_t d_out64) {
+    const int d_out = (int)d_out64;
     if (o0 + 8 <= d_out) return 0xffu;
-    return o0 < d_out ? (1u << (int)(d_out - o0)) - 1u : 0u;
+    return o0 < d_out ? (1u << (d_out - o0)) - 1u : 0u;
 }
 
 __device__ __forceinline__ bool channel_live(const WselArgs &a, int64_t i) {
@@ -357,16 +363,19 @@ template <typename TW, typename F>
 __device__ __forceinline__ void for_each_raw_chunk(const WselArgs &a, int64_t q0, int64_t q1, F &&body) {
     if (q0 >= q1) return;
     const int lane = threadIdx.x & (CMPQ_WAVE - 1);
-    int64_t i = q0 / a.wc_per_channel, c = q0 % a.wc_per_channel;
+    int64_t i = q0 / a.wc_per_channel;
+    int c = (int)(q0 % a.wc_per_channel);  // a channel has at most 2^31 / 512 wave-chunks
+    const int wc_per_channel = (int)a.wc_per_channel, lane0 = lane * kWPerLane;
     bool live = channel_live(a, i);
     float cent = live && a.centroids ? a.centroids[i * CMPQ_KMAX + (lane & 15)] : 0.f;
     Raw8<TW> cur = {}, nxt = {};
-    if (live) fetch8(a, i, c * kWaveChunk + lane * kWPerLane, cur);
+    if (live) fetch8(a, i, c * kWaveChunk + lane0, cur);
     for (int64_t q = q0; q < q1; ++q) {
-        int64_t ni = i, nc = c + 1;
+        int64_t ni = i;
+        int nc = c + 1;
         bool live_n = live;
         float cent_n = cent;
-        if (nc == a.wc_per_channel) {
+        if (nc == wc_per_channel) {
             nc = 0;
             ++ni;
         }
@@ -375,9 +384,9 @@ __device__ __forceinline__ void for_each_raw_chunk(const WselArgs &a, int64_t q0
                 live_n = channel_live(a, ni);
                 cent_n = live_n && a.centroids ? a.centroids[ni * CMPQ_KMAX + (lane & 15)] : 0.f;
             }
-            if (live_n) fetch8(a, ni, nc * kWaveChunk + lane * kWPerLane, nxt);
+            if (live_n) fetch8(a, ni, nc * kWaveChunk + lane0, nxt);
         }
-        if (live) body(i, c * kWaveChunk + lane * kWPerLane, cur, cent);
+        if (live) body(i, c * kWaveChunk + lane0, cur, cent);
         cur = nxt;
         i = ni;
         c = nc;
@@ -389,7 +398,7 @@ __device__ __forceinline__ void for_each_raw_chunk(const WselArgs &a, int64_t q0
 // The same with the score keys formed: body(i, o0, key, wv, valid).
 template <typename TW, typename F>
 __device__ __forceinline__ void for_each_wave_chunk(const WselArgs &a, int64_t q0, int64_t q1, F &&body) {
-    for_each_raw_chunk<TW>(a, q0, q1, [&](int64_t i, int64_t o0, const Raw8<TW> &raw, float cent) {
+    for_each_raw_chunk<TW>(a, q0, q1, [&](int64_t i, int o0, const Raw8<TW> &raw, float cent) {
         uint32_t key[8];
         float wv[8];
         score_keys8<TW>(a, raw, cent, key, wv);
@@ -439,7 +448,7 @@ __device__ __forceinline__ void signed_scores8(const WselArgs &a, const Raw8<__h
 // the unit's staging list, in index order: a lane's entries follow those of the lanes
 // below it.  Few lanes hold any and hardly one holds two: every lane with entries left
 // stores its next one, until none is left.  Called by all lanes of the wavefront.
-__device__ __forceinline__ void stage_chunk(uint32_t cand, int64_t i, int64_t o0, int64_t d_out,
+__device__ __forceinline__ void stage_chunk(uint32_t cand, int64_t i, int o0, int64_t d_out,
                                             const uint32_t (&key)[8], const float (&wv)[8],
                                             unsigned long long *__restrict__ stage_ik,
                                             uint16_t *__restrict__ stage_val, uint32_t cap,
@@ -472,7 +481,7 @@ __device__ __forceinline__ void stage_chunk(uint32_t cand, int64_t i, int64_t o0
                         wj = wv[t];
                     }
                 }
-                stage_ik[pos] = ((unsigned long long)(uint32_t)(i * d_out + o0 + j) << 32) | kj;
+                stage_ik[pos] = ((unsigned long long)((uint32_t)(i * d_out) + (uint32_t)(o0 + j)) << 32) | kj;
                 stage_val[pos] = __half_as_ushort(__float2half_rn(wj));
                 ++pos;
             }
@@ -485,7 +494,7 @@ __device__ __forceinline__ void stage_chunk(uint32_t cand, int64_t i, int64_t o0
 
 // stage_chunk for FP16 input: the key of a candidate is the magnitude of its signed score d,
 // its value the packed FP16 weight itself.
-__device__ __forceinline__ void stage_chunk_half(uint32_t cand, int64_t i, int64_t o0, int64_t d_out,
+__device__ __forceinline__ void stage_chunk_half(uint32_t cand, int64_t i, int o0, int64_t d_out,
                                                  const float (&d)[8], const uint4 &w,
                                                  unsigned long long *__restrict__ stage_ik,
                                                  uint16_t *__restrict__ stage_val, uint32_t cap,
@@ -516,7 +525,7 @@ __device__ __forceinline__ void stage_chunk_half(uint32_t cand, int64_t i, int64
                     if (j == t) dj = d[t];
                     if ((t & 1) == 0 && (j >> 1) == (t >> 1)) wj = w4[t >> 1];
                 }
-                stage_ik[pos] = ((unsigned long long)(uint32_t)(i * d_out + o0 + j) << 32) | __float_as_uint(fabsf(dj));
+                stage_ik[pos] = ((unsigned long long)((uint32_t)(i * d_out) + (uint32_t)(o0 + j)) << 32) | __float_as_uint(fabsf(dj));
                 stage_val[pos] = (uint16_t)(wj >> (16 * (j & 1)));
                 ++pos;
             }
@@ -686,7 +695,7 @@ __global__ __launch_bounds__(kWThreads) void wsel_stage_kernel(WselArgs a, WselS
         // candidate, as its bit pattern would be), the conversion of a weight is folded into the
         // subtraction, and only a candidate's key and value are formed
         const float reach_f = __uint_as_float(reach);
-        for_each_raw_chunk<TW>(a, q0, q1, [&](int64_t i, int64_t o0, const Raw8<TW> &raw, float cent) {
+        for_each_raw_chunk<TW>(a, q0, q1, [&](int64_t i, int o0, const Raw8<TW> &raw, float cent) {
             float d[8];
             signed_scores8(a, raw, cent, d);
             uint32_t cand = 0;  // bit j: entry j reaches the guess
@@ -696,7 +705,7 @@ __global__ __launch_bounds__(kWThreads) void wsel_stage_kernel(WselArgs a, WselS
             stage_chunk_half(cand, i, o0, a.d_out, d, raw.w, stage_ik, stage_val, a.cap, n_staged, over);
         });
     } else {
-        for_each_wave_chunk<TW>(a, q0, q1, [&](int64_t i, int64_t o0, const uint32_t (&key)[8], const float (&wv)[8], uint32_t valid) {
+        for_each_wave_chunk<TW>(a, q0, q1, [&](int64_t i, int o0, const uint32_t (&key)[8], const float (&wv)[8], uint32_t valid) {
             // bit j of cand: entry j exists and reaches the guess
             uint32_t cand = 0;
 #pragma unroll
@@ -803,7 +812,7 @@ __global__ __launch_bounds__(kWThreads) void wsel_hist_kernel(WselArgs a, WselSt
     bool over = false;
     unsigned long long *stage_ik = a.stage_ik + unit * a.cap;
     uint16_t *stage_val = a.stage_val + unit * a.cap;
-    for_each_wave_chunk<TW>(a, q0, q1, [&](int64_t i, int64_t o0, const uint32_t (&key)[8], const float (&wv)[8], uint32_t valid) {
+    for_each_wave_chunk<TW>(a, q0, q1, [&](int64_t i, int o0, const uint32_t (&key)[8], const float (&wv)[8], uint32_t valid) {
         uint32_t cand = 0;  // bit j: entry j reaches the 22-bit prefix
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
