@@ -32,6 +32,8 @@
 // runs on one wavefront while the others sleep at barriers, and several workgroups share
 // a compute unit.  A channel with NaN or infinity raises the status flag and gets levels 0
 // and codes 0.
+#include <type_traits>
+
 #include "kmeans_args.h"
 #include "kmeans_keys.h"
 
@@ -245,6 +247,10 @@ __device__ __forceinline__ double coding_pass_fused(const KmArgs &a, int64_t i, 
     // the weights of the next few groups are fetched while the current ones are worked on: this
     // pass may be the first to touch the row (when the tables came from an earlier run)
     constexpr int kAhead = 4;
+    // two copies of the loop: only a channel that has a bucket with several boundaries (rare)
+    // pays for looking at each entry's flag
+    auto all_groups = [&](auto with_search) {
+    constexpr bool kSearch = decltype(with_search)::value;
     uint2 nxt[kAhead];
 #pragma unroll
     for (int u = 0; u < kAhead; ++u) {
@@ -273,7 +279,7 @@ __device__ __forceinline__ double coding_pass_fused(const KmArgs &a, int64_t i, 
                 if constexpr (kTable) {
                     const uint32_t ent = table_entry<LB>(tbl_at, kk[e >> 1], e & 1);
                     code[e] = code_from_entry(ent, kk[e >> 1], e & 1);
-                    if (any_multi && (ent & kTblMulti))
+                    if (kSearch && (ent & kTblMulti))
                         code[e] = sm.code_of[cell_of<K>((kk[e >> 1] >> (16 * (e & 1))) & 0xffffu, thr)];
                 } else {
                     code[e] = sm.code_of[cell_of<K>((kk[e >> 1] >> (16 * (e & 1))) & 0xffffu, thr)];
@@ -318,6 +324,9 @@ __device__ __forceinline__ double coding_pass_fused(const KmArgs &a, int64_t i, 
             }
         }
     }
+    };
+    if (any_multi) all_groups(std::true_type{});
+    else all_groups(std::false_type{});
     __syncthreads();
     return err;
 }
