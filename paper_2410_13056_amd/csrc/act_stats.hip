@@ -24,7 +24,9 @@ template <>
 struct Vec<__half> {
     static constexpr int N = 8;
     __device__ static void load(const __half *p, float (&f)[8]) {
-        const uint4 raw = *reinterpret_cast<const uint4 *>(p);
+        typedef uint32_t U4 __attribute__((ext_vector_type(4)));
+        const U4 nt = __builtin_nontemporal_load(reinterpret_cast<const U4 *>(p));  // X is read once
+        const uint4 raw = make_uint4(nt.x, nt.y, nt.z, nt.w);
         const __half2 *h = reinterpret_cast<const __half2 *>(&raw);
 #pragma unroll
         for (int j = 0; j < 4; ++j) {

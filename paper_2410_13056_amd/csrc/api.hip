@@ -164,7 +164,11 @@ __global__ __launch_bounds__(256) void transpose16_vec_kernel(const uint16_t *__
     for (int k = 0; k < 4; ++k) {
         const int64_t r = r0 + p + 16 * k, c = c0 + 4 * q;
         v[k] = make_uint2(0, 0);
-        if (r < rows && c < cols) v[k] = *reinterpret_cast<const uint2 *>(src + r * ld_src + c);
+        if (r < rows && c < cols) {  // the source is read once
+            typedef uint32_t U2 __attribute__((ext_vector_type(2)));
+            const U2 nt = __builtin_nontemporal_load(reinterpret_cast<const U2 *>(src + r * ld_src + c));
+            v[k] = make_uint2(nt.x, nt.y);
+        }
     }
 #pragma unroll
     for (int k = 0; k < 4; ++k) {

@@ -21,7 +21,7 @@ __device__ __forceinline__ uint32_t load8(const TW *__restrict__ wrow, const uin
                                           uint32_t (&c)[8]) {
     if (vec_ok && o0 + 8 <= d_out) {
         if constexpr (sizeof(TW) == 2) {
-            const uint4 raw = *reinterpret_cast<const uint4 *>(wrow + o0);
+            const uint4 raw = load16_stream(wrow + o0);
             const __half2 *h = reinterpret_cast<const __half2 *>(&raw);
 #pragma unroll
             for (int j = 0; j < 4; ++j) {

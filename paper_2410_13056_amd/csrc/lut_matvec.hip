@@ -154,7 +154,7 @@ __device__ __forceinline__ void lut_slab(const LmArgs &a, const LmWidth &wd, int
             const uint32_t *p = wd.packed + (r + g) * wd.words_per_row + word0;
             if (r + g < r1 && full) {
                 typedef uint32_t WordsB __attribute__((ext_vector_type(B), aligned(4)));
-                const WordsB v = *reinterpret_cast<const WordsB *>(p);  // dword-aligned vector load
+                const WordsB v = __builtin_nontemporal_load(reinterpret_cast<const WordsB *>(p));  // dword-aligned vector load; a token reads the codes once
 #pragma unroll
                 for (int j = 0; j < B; ++j) w[g][j] = v[j];
             } else {
@@ -266,7 +266,7 @@ __device__ __forceinline__ void lut_slab_pairs(const LmArgs &a, const LmWidth &w
             const uint32_t *p = wd.packed + (r + g) * wd.words_per_row + word0;
             if (r + g < r1 && full) {
                 typedef uint32_t WordsB __attribute__((ext_vector_type(B), aligned(4)));
-                const WordsB v = *reinterpret_cast<const WordsB *>(p);
+                const WordsB v = __builtin_nontemporal_load(reinterpret_cast<const WordsB *>(p));
 #pragma unroll
                 for (int j = 0; j < B; ++j) w[g][j] = v[j];
             } else {
@@ -374,7 +374,7 @@ __device__ __forceinline__ void lut_slab_half(const LmArgs &a, const LmWidth &wd
             const uint32_t *p = wd.packed + (r + g) * wd.words_per_row + word0;
             if (r + g < r1 && full) {
                 typedef uint32_t WordsB __attribute__((ext_vector_type(B), aligned(4)));
-                const WordsB v = *reinterpret_cast<const WordsB *>(p);
+                const WordsB v = __builtin_nontemporal_load(reinterpret_cast<const WordsB *>(p));
 #pragma unroll
                 for (int j = 0; j < B; ++j) w[g][j] = v[j];
             } else {

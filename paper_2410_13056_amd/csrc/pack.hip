@@ -54,8 +54,8 @@ __device__ void pack_row(const uint8_t *__restrict__ crow, int64_t d_out, uint32
         const int64_t o0 = g * 32;
         uint8_t c[32];
         if (vec_ok && o0 + 32 <= d_out) {
-            const uint4 r0 = *reinterpret_cast<const uint4 *>(crow + o0);
-            const uint4 r1 = *reinterpret_cast<const uint4 *>(crow + o0 + 16);
+            const uint4 r0 = load16_stream(crow + o0);
+            const uint4 r1 = load16_stream(crow + o0 + 16);
             const uint32_t r[8] = {r0.x, r0.y, r0.z, r0.w, r1.x, r1.y, r1.z, r1.w};
 #pragma unroll
             for (int j = 0; j < 32; ++j) c[j] = (r[j >> 2] >> (8 * (j & 3))) & 0xffu;
@@ -141,11 +141,11 @@ template <typename TW>
 __device__ __forceinline__ void pe_fetch(PeStep<TW> &st, const TW *__restrict__ wrow,
                                          const uint8_t *__restrict__ crow, int64_t g) {
     const int64_t o0 = g * 32;
-    st.code[0] = *reinterpret_cast<const uint4 *>(crow + o0);
-    st.code[1] = *reinterpret_cast<const uint4 *>(crow + o0 + 16);
+    st.code[0] = load16_stream(crow + o0);
+    st.code[1] = load16_stream(crow + o0 + 16);
 #pragma unroll
     for (int q = 0; q < 32 / PeStep<TW>::kPer; ++q)
-        st.raw[q] = *reinterpret_cast<const uint4 *>(wrow + o0 + PeStep<TW>::kPer * q);
+        st.raw[q] = load16_stream(wrow + o0 + PeStep<TW>::kPer * q);
 }
 
 // The 32 codes of r[0..8), four to a word, as B whole words of the bit stream.

@@ -28,7 +28,7 @@ __device__ __forceinline__ uint32_t load8w(const TW *__restrict__ wrow, int64_t 
     }
     if (vec_ok && o0 + kPer <= d_out) {
         if constexpr (sizeof(TW) == 2) {
-            const uint4 raw = *reinterpret_cast<const uint4 *>(wrow + o0);
+            const uint4 raw = load16_stream(wrow + o0);
             const __half2 *h = reinterpret_cast<const __half2 *>(&raw);
 #pragma unroll
             for (int j = 0; j < 4; ++j) {

@@ -259,7 +259,11 @@ __device__ __forceinline__ uint2 fetch_codes8(const WselArgs &a, int64_t i, int 
     if (!a.codes) return c;
     const uint8_t *crow = a.codes + i * a.d_out;
     const int d_out = (int)a.d_out;
-    if (vec) return *reinterpret_cast<const uint2 *>(crow + o0);
+    if (vec) {  // streamed: every pass over the layer reads it once
+        typedef uint32_t U2 __attribute__((ext_vector_type(2)));
+        const U2 nt = __builtin_nontemporal_load(reinterpret_cast<const U2 *>(crow + o0));
+        return make_uint2(nt.x, nt.y);
+    }
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
         if (o0 + j < d_out) {
@@ -275,7 +279,9 @@ __device__ __forceinline__ void fetch8(const WselArgs &a, int64_t i, int o0, Raw
     const int d_out = (int)a.d_out;
     const bool vec = a.vec_ok && o0 + 8 <= d_out;
     if (vec) {
-        r.w = *reinterpret_cast<const uint4 *>(wrow + o0);
+        typedef uint32_t U4 __attribute__((ext_vector_type(4)));
+        const U4 nt = __builtin_nontemporal_load(reinterpret_cast<const U4 *>(wrow + o0));
+        r.w = make_uint4(nt.x, nt.y, nt.z, nt.w);
     } else {
         uint32_t h[8];
 #pragma unroll
