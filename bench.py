@@ -311,9 +311,9 @@ def main():
     ap.add_argument("--two-calls", action="store_true",
                     help="final K-means and stored format + error as two calls (cmpq_kmeans_quantize, then "
                          "cmpq_pack_with_error) instead of the one call whose coding pass writes them")
-    ap.add_argument("--shared-tables", action="store_true",
-                    help="the final K-means starts from the per-channel tables the preliminary one kept "
-                         "instead of building them again (same results; not the default)")
+    ap.add_argument("--no-shared-tables", dest="shared_tables", action="store_false",
+                    help="the final K-means builds its per-channel tables again instead of starting from "
+                         "the ones the preliminary K-means kept (same results; sharing is the default)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (outside the timed region): under "
                          "rocprofv3 --pmc it gives the HBM counters a kernel of known traffic to scale by")

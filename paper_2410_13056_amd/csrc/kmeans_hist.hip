@@ -616,18 +616,41 @@ constexpr int kModeReuse = 2;  // starts from a kept arrangement; codes like kMo
 // Lanes that remove equal values race for the bytes: compare-and-swap, try the next on a loss.
 __device__ __forceinline__ void blank_one_place(uint32_t *words, uint32_t w0, uint32_t w1, uint32_t place) {
     const uint32_t pat = place * 0x01010101u;
-    for (uint32_t j = w0; j < w1; ++j) {
-        uint32_t x = words[j];
+    uint32_t j = w0;
+    while (j < w1) {
+        // The search and the exchange are separate loops: lanes of a wavefront find their
+        // words after different numbers of steps, and an exchange inside the search would put
+        // its round trip into every step that any lane ends on.
+        uint32_t x = 0, zero = 0;
+        for (; j < w1; j += 4) {  // four words per step, the last one again past the end
+            uint32_t xs[4], zs[4];
+#pragma unroll
+            for (uint32_t u = 0; u < 4; ++u) xs[u] = words[min(j + u, w1 - 1)];
+#pragma unroll
+            for (uint32_t u = 0; u < 4; ++u) {
+                const uint32_t t = xs[u] ^ pat;
+                zs[u] = (t - 0x01010101u) & ~t & 0x80808080u;  // lowest flag marks a byte that matches
+            }
+            if (zs[0] | zs[1] | zs[2] | zs[3]) {
+                const uint32_t u = zs[0] ? 0u : (zs[1] ? 1u : (zs[2] ? 2u : 3u));
+                x = zs[0] ? xs[0] : (zs[1] ? xs[1] : (zs[2] ? xs[2] : xs[3]));
+                zero = zs[0] ? zs[0] : (zs[1] ? zs[1] : (zs[2] ? zs[2] : zs[3]));
+                j = min(j + u, w1 - 1);
+                break;
+            }
+        }
+        if (!zero) return;
         for (;;) {
-            const uint32_t t = x ^ pat;
-            const uint32_t zero = (t - 0x01010101u) & ~t & 0x80808080u;  // lowest flag marks a byte that matches
-            if (!zero) break;
-            const uint32_t sh = (uint32_t)(__ffs(zero) - 8);             // bit offset of that byte
+            const uint32_t sh = (uint32_t)(__ffs(zero) - 8);  // bit offset of that byte
             const uint32_t nw = (x & ~(0xffu << sh)) | (0x80u << sh);
             const uint32_t old = atomicCAS(&words[j], x, nw);
             if (old == x) return;
-            x = old;
+            x = old;  // another lane changed the word: look at it again
+            const uint32_t t = x ^ pat;
+            zero = (t - 0x01010101u) & ~t & 0x80808080u;
+            if (!zero) break;
         }
+        ++j;
     }
 }
 
@@ -759,6 +782,7 @@ __global__ __launch_bounds__(T) __attribute__((amdgpu_waves_per_eu(6, 7))) void 
         return;
     }
     const int n_ex = sm.n_excl;
+    uint32_t first_key = 0;  // reuse: the key of entry `tid` of O_q, for the second visit below
     if (n_ex > 0) {  // entries of O_q do not take part in the clustering
         const int32_t *ex_idx = a.out_idx + sm.seg_lo;
         const int32_t chan_base = (int32_t)(i * a.d_out);
@@ -767,6 +791,7 @@ __global__ __launch_bounds__(T) __attribute__((amdgpu_waves_per_eu(6, 7))) void 
             atomicOr(&removed[o >> 5], 1u << (o & 31));
             if constexpr (MODE == kModeReuse) {  // out of its bucket's count and sum of places
                 const uint32_t key = key_of_half(__half_as_ushort(wrow_h[o]));
+                if (e == tid) first_key = key;
                 atomicAdd(reinterpret_cast<unsigned long long *>(&sm.scum[key >> LB]),
                           0ull - ((1ull << 32) | (key & ((1u << LB) - 1))));
             }
@@ -835,7 +860,8 @@ __global__ __launch_bounds__(T) __attribute__((amdgpu_waves_per_eu(6, 7))) void 
             const int32_t *ex_idx = a.out_idx + sm.seg_lo;
             const int32_t chan_base = (int32_t)(i * a.d_out);
             for (int e = tid; e < n_ex; e += T) {
-                const uint32_t key = key_of_half(__half_as_ushort(wrow_h[ex_idx[e] - chan_base]));
+                const uint32_t key =
+                    e == tid ? first_key : key_of_half(__half_as_ushort(wrow_h[ex_idx[e] - chan_base]));
                 const uint32_t bk = key >> LB;
                 blank_one_place(reinterpret_cast<uint32_t *>(arr), sm.start[bk] >> 2, sm.start[bk + 1] >> 2,
                                 key & ((1u << LB) - 1));

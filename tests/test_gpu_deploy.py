@@ -126,6 +126,37 @@ def test_lut_matvec_parity_end_to_end(env, bit_set, avg, d_in, d_out):
     assert np.array_equal(_np(Yw[:, :d_out]), Y[:2]) and (_np(Yw[:, d_out:]) == 7.0).all()
 
 
+@pytest.mark.parametrize("bit_set,avg,d_in,d_out,per_channel", [((2, 3, 4), 3.0, 300, 2048 + 40, False),
+                                                                ((1, 2, 3, 4), 2.5, 130, 28672, False),
+                                                                ((3, 4), 3.5, 520, 4096 + 8, True),
+                                                                ((2, 3), 2.5, 96, 50, False)])
+def test_shared_tables_route_equals_rebuilt_tables(env, bit_set, avg, d_in, d_out, per_channel):
+    """The layer quantized with the preliminary K-means handing its per-channel tables to the
+    final one (the default) and with the final one building them again: every output the same
+    bit for bit (levels, codes, O_q, stored format, errors).  d_out = 50 is a shape the shared
+    route does not take (rows not whole groups of 4): both calls then run the same kernels."""
+    P, ws = env["P"], env["ws"]
+    rng = np.random.default_rng(3 * d_in + d_out)
+    W = rng.normal(0, 0.02, (d_in, d_out))
+    W[rng.random(W.shape) < 0.01] *= 10
+    W = _dev(W.astype(np.float16))
+    Xcal = (rng.normal(0, 1, (128, d_in)) * np.exp(rng.normal(0, 0.5, d_in))).astype(np.float16)
+    _, sumsq = P.activation_stats(_dev(Xcal), ws)
+    runs = [P.quantize_layer(W, sumsq, bit_set, avg, rho_act_ppm=20000, rho_q_ppm=10000, iters=4, ws=ws,
+                             transposed=True, with_error=True, oq_per_channel=per_channel, share_tables=share)
+            for share in (True, False)]
+    a, b = runs
+    for name in ("bits", "centroids", "codes", "out_idx", "out_val", "err_ch", "err_total"):
+        x, y = _np(getattr(a, name)), _np(getattr(b, name))
+        assert x.tobytes() == y.tobytes(), name
+    assert a.counts == b.counts
+    for name in ("packed", "chan_idx", "lut"):
+        for x, y in zip(getattr(a, name), getattr(b, name)):
+            assert (x is None) == (y is None)
+            if x is not None:
+                assert _np(x).tobytes() == _np(y).tobytes(), name
+
+
 def _fp16_run_sums(X, cent, codes, bits, bit_set, run):
     """The packed part of the FP16-sum product as its entry point defines it: products rounded
     to FP16, runs of `run` consecutive rows of a width added in FP16 one after the other; the
