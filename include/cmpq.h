@@ -187,8 +187,11 @@ int cmpq_allocate_bits(const float *sumsq, int64_t d_in, const uint8_t *chan_mas
  *
  * mode CMPQ_OUTLIER_WEIGHTS (O_q): candidates are the entries of channels with bits in
  *   1..4 (W' = W - O_act).  Key = fp32 |w - centroids[i][codes[i,o]]| for
- *   CMPQ_SCORE_RESIDUAL (needs centroids [d_in,16] and codes [d_in,d_out] from a first
- *   cmpq_kmeans_quantize), or fp32 |w| for CMPQ_SCORE_MAGNITUDE.
+ *   CMPQ_SCORE_RESIDUAL (needs centroids [d_in,16] from a first cmpq_kmeans_quantize, and
+ *   its codes [d_in,d_out] or null), or fp32 |w| for CMPQ_SCORE_MAGNITUDE.  With codes
+ *   null the key is the smallest fp32 |w - centroids[i][j]| over the channel's 2^bits[i]
+ *   levels: the preliminary quantization codes every weight by its nearest level (Sec. 3
+ *   eq. Q(x)), so this is the same key, and the first run need not write codes at all.
  *   scope CMPQ_SCOPE_LAYER (the paper's rule): the k largest keys of the whole layer.
  *     idx_out [k] int32 linear indices i*d_out+o, ascending; val_out [k] (nullable) the
  *     weights as FP16 bit patterns.  k > d_in*d_out: CMPQ_ECOUNT.  The number of candidates
@@ -227,7 +230,11 @@ int cmpq_extract_outliers(int mode, int score, int scope, const float *sumsq, co
  *               quantization can so continue from the preliminary one's levels.
  *   centroids   [d_in, 16] fp32 out (in/out with CMPQ_INIT_GIVEN): K levels, then +infinity;
  *               all +infinity for a channel with bits outside 1..4.
- *   codes       [d_in, d_out] uint8 out (0 for such a channel).
+ *   codes       [d_in, d_out] uint8 out (0 for such a channel).  May be null for inputs the
+ *               histogram kernel takes (fp16, unit importance, rows of whole groups of 4
+ *               entries, 8-byte aligned): the call then leaves the levels alone and skips the
+ *               last assignment, which is all the preliminary quantization of Sec. 3.2.2
+ *               needs when cmpq_extract_outliers is given no codes.  Null otherwise: CMPQ_EINVAL.
  * Assignment: the nearest level in exact arithmetic, equal distances to the smaller level
  * index.  Update: level = sum(m*x)/sum(m) of its members, accumulated in fp64 and rounded
  * once to fp32; a level without members keeps its value.  -0.0 reads as +0.0.
@@ -284,10 +291,10 @@ int cmpq_select_by_width(const uint8_t *bits, int64_t d_in, int64_t d_out, const
  *               err_ch / err_total equal up to the order of the fp64 additions - and, where the
  *               histogram kernel runs, writes them from its coding pass instead of reading
  *               weights and codes again.  Every one of the fields must then be given as for
- *               that call (sumsq nullable).  `codes` may be null only in this case and only
- *               for inputs the histogram kernel takes (fp16, unit importance, rows of whole
- *               groups of 4 entries, 8-byte aligned; CMPQ_KMEANS_HISTOGRAM): the dense codes
- *               are then not written at all.
+ *               that call (sumsq nullable).  `codes` may be null, here as in a call without these
+ *               fields, only for inputs the histogram kernel takes (fp16, unit importance, rows
+ *               of whole groups of 4 entries, 8-byte aligned; CMPQ_KMEANS_HISTOGRAM): the dense
+ *               codes are then not written at all.
  *   arrangement, arrangement_use   (null / CMPQ_ARRANGEMENT_NONE: not used.)  Sec. 3.2.2 runs
  *               the quantizer twice on the same channels: the final quantization differs from
  *               the preliminary one only by the entries of O_q (0.05 % - 1 % of a layer).  The

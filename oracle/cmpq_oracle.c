@@ -396,16 +396,28 @@ int orc_kmeans(const void *W, int dtype, int64_t d_in, int64_t d_out, int64_t ld
 #define ORC_SCORE_MAGNITUDE 1 /* |W'|, the "conventional approach" it contrasts */
 
 /*
+ * |W' - W'_q| of one entry (Sec. 3.2.2).  With the codes of the preliminary quantization:
+ * the distance to the level of its code.  Without (codes null): W'_q is Q(W') of Sec. 3,
+ * every weight on its nearest level, so the distance to the nearest of the channel's
+ * 2^bits levels.
+ */
+static double residual_of(double w, const float *c, const uint8_t *code, int bits) {
+    if (code) return fabs(w - (double)c[*code]);
+    return fabs(w - (double)c[nearest_level(w, c, 1 << bits)]);
+}
+
+/*
  * The k entries of W' (channels with bits in 1..4, i.e. outside O_act) with the
  * largest score, over the whole layer.  Score = |w - q_code| rounded to fp32
  * (its bit pattern is the ranking key); larger first, equal scores by smaller
  * linear index i*d_out+o.  idx_out[k] ascending, val_out[k] = the weight in FP16.
+ * codes may be null: see residual_of.
  */
 int orc_weight_outliers(const void *W, int dtype, int64_t d_in, int64_t d_out, int64_t ldw,
                         const float *centroids, const uint8_t *codes, const uint8_t *bits,
                         int score, int64_t k, int64_t *idx_out, uint16_t *val_out) {
     if (!W || !bits || k < 0) return -1;
-    if (score == ORC_SCORE_RESIDUAL && (!centroids || !codes)) return -1;
+    if (score == ORC_SCORE_RESIDUAL && !centroids) return -1;
     int64_t cap = d_in * d_out, cnt = 0;
     keyidx_t *r = (keyidx_t *)malloc(sizeof(keyidx_t) * (size_t)(cap ? cap : 1));
     for (int64_t i = 0; i < d_in; ++i) {
@@ -413,7 +425,8 @@ int orc_weight_outliers(const void *W, int dtype, int64_t d_in, int64_t d_out, i
         for (int64_t o = 0; o < d_out; ++o) {
             double w = load_elem(W, dtype, i * ldw + o);
             double s = score == ORC_SCORE_RESIDUAL
-                           ? fabs(w - (double)centroids[i * ORC_KMAX + codes[i * d_out + o]])
+                           ? residual_of(w, centroids + i * ORC_KMAX,
+                                         codes ? codes + i * d_out + o : NULL, bits[i])
                            : fabs(w);
             r[cnt].key = float_bits((float)s);
             r[cnt].idx = i * d_out + o;
@@ -453,7 +466,7 @@ int64_t orc_weight_outliers_per_channel(const void *W, int dtype, int64_t d_in, 
                                         const uint8_t *bits, int score, int64_t k,
                                         int64_t *idx_out, uint16_t *val_out) {
     if (!W || !bits || k < 0) return -1;
-    if (score == ORC_SCORE_RESIDUAL && (!centroids || !codes)) return -1;
+    if (score == ORC_SCORE_RESIDUAL && !centroids) return -1;
     if (k > d_out) return -3;
     keyidx_t *r = (keyidx_t *)malloc(sizeof(keyidx_t) * (size_t)(d_out ? d_out : 1));
     int64_t *sel = (int64_t *)malloc(sizeof(int64_t) * (size_t)(k ? k : 1));
@@ -463,7 +476,8 @@ int64_t orc_weight_outliers_per_channel(const void *W, int dtype, int64_t d_in, 
         for (int64_t o = 0; o < d_out; ++o) {
             double w = load_elem(W, dtype, i * ldw + o);
             double s = score == ORC_SCORE_RESIDUAL
-                           ? fabs(w - (double)centroids[i * ORC_KMAX + codes[i * d_out + o]])
+                           ? residual_of(w, centroids + i * ORC_KMAX,
+                                         codes ? codes + i * d_out + o : NULL, bits[i])
                            : fabs(w);
             r[o].key = float_bits((float)s);
             r[o].idx = o;

@@ -403,7 +403,7 @@ extern "C" int cmpq_kmeans_quantize_job(const cmpq_kmeans_job *job, void *ws, si
     const bool want_format = j.bit_set || j.n_set || j.counts_host || j.packed || j.chan_idx || j.lut || j.err_ch ||
                              j.err_total || j.sumsq;
     if (want_format && (!j.bit_set || !j.counts_host || !j.err_ch || !j.err_total)) return CMPQ_EINVAL;
-    if (d_in > 0 && d_out > 0 && (!j.W || (!j.codes && !want_format))) return CMPQ_EINVAL;
+    if (d_in > 0 && d_out > 0 && !j.W) return CMPQ_EINVAL;
     if (j.ldw < d_out) return CMPQ_ESHAPE;
     if (d_out > (j.dtype == CMPQ_F16 ? 32768 : 16384)) return CMPQ_ESHAPE;
     if (d_in > 0 && d_out > ((int64_t)1 << 31) / d_in) return CMPQ_ESHAPE;
@@ -438,6 +438,8 @@ extern "C" int cmpq_kmeans_quantize_job(const cmpq_kmeans_job *job, void *ws, si
     char *ws_row_of = static_cast<char *>(ws) + ws_kmeans_base(d_in);
     char *ws_tail = ws_row_of + align_up((size_t)d_in * sizeof(int32_t), 256);
     const bool hist_takes_it = kmeans_fast_eligible(a, j.dtype) && (j.algorithm != CMPQ_KMEANS_DIRECT || a.start_given);
+    // levels alone (no codes, no stored format): only the histogram kernel leaves the coding pass out
+    if (d_out > 0 && !j.codes && !want_format && !hist_takes_it) return CMPQ_EINVAL;
     if (j.arrangement_use != CMPQ_ARRANGEMENT_NONE) {
         // only the histogram kernel builds and reads arrangements; one is kept from all weights
         if (!j.arrangement || !hist_takes_it || reinterpret_cast<uintptr_t>(j.arrangement) % 16 != 0) return CMPQ_EINVAL;

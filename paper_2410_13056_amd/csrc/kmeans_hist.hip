@@ -515,6 +515,10 @@ __device__ __forceinline__ void lloyd_bucket(const KmArgs &a, int64_t i, BucketS
         err_out = coding_pass_fused<G, K, T, LB>(a, i, sm, arr, tbl, removed, n_ex, n_groups, par);
         return;
     }
+    if (!a.codes) {  // the caller wants the levels alone
+        __syncthreads();
+        return;
+    }
     // ---- final coding: 4 codes per lane and store.  Every wavefront fetches the final
     //      boundaries and the position -> level map left by wavefront 0.
     const uint32_t tk_fin = sm.tk[par][lane & (CMPQ_KMAX - 1)];

@@ -324,6 +324,41 @@ __device__ __forceinline__ void unpack8(const Raw8<float> &r, float (&wv)[8]) {
     wv[4] = r.w1.x, wv[5] = r.w1.y, wv[6] = r.w1.z, wv[7] = r.w1.w;
 }
 
+// Residual scores without codes (Sec. 3.2.2 with Q(x) of Sec. 3: the preliminary quantization
+// puts every weight on its nearest level, so |w - Q(w)| is the smallest |w - level| over the
+// channel's levels; rounding to fp32 keeps the order, so the smallest rounded difference is the
+// rounded difference to the nearest level).  `cent` holds level (lane & 15), +inf past the
+// channel's K levels: the number of finite lanes among the first 16 is K.
+__device__ __forceinline__ int levels_in(float cent) {
+    return (int)__popcll(__ballot(cent < INFINITY) & 0xffffull);
+}
+__device__ __forceinline__ float min3_abs(float x, float y, float m) {
+    asm("v_min3_f32 %0, |%1|, |%2|, %0" : "+v"(m) : "v"(x), "v"(y));
+    return m;
+}
+__device__ __forceinline__ float level_of_lane(float cent, int k) {
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(cent), k));
+}
+template <int K>
+__device__ __forceinline__ void nearest_abs8(const float (&wv)[8], float cent, float (&m)[8]) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) m[j] = INFINITY;
+#pragma unroll
+    for (int k = 0; k < K; k += 2) {
+        const float s0 = level_of_lane(cent, k), s1 = level_of_lane(cent, k + 1);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) m[j] = min3_abs(wv[j] - s0, wv[j] - s1, m[j]);
+    }
+}
+__device__ __forceinline__ void nearest_abs8(const float (&wv)[8], float cent, float (&m)[8]) {
+    switch (levels_in(cent)) {  // uniform over the wavefront
+        case 2: nearest_abs8<2>(wv, cent, m); break;
+        case 4: nearest_abs8<4>(wv, cent, m); break;
+        case 8: nearest_abs8<8>(wv, cent, m); break;
+        default: nearest_abs8<16>(wv, cent, m); break;  // lanes past K hold +inf and never win
+    }
+}
+
 // Score keys of the 8 entries.  `cent` holds level (lane & 15) of the channel: the level
 // of a code comes from the lane of that number (all lanes of the wavefront take part).
 template <typename TW>
@@ -333,6 +368,13 @@ __device__ __forceinline__ void score_keys8(const WselArgs &a, const Raw8<TW> &r
     if (a.score != CMPQ_SCORE_RESIDUAL) {
 #pragma unroll
         for (int j = 0; j < 8; ++j) key[j] = __float_as_uint(fabsf(wv[j]));
+        return;
+    }
+    if (!a.codes) {
+        float m[8];
+        nearest_abs8(wv, cent, m);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) key[j] = __float_as_uint(m[j]);
         return;
     }
     // One branch for the whole piece, so that the eight lane exchanges below are issued back to
@@ -430,6 +472,12 @@ __device__ __forceinline__ float half_minus(uint32_t packed, float level) {
 __device__ __forceinline__ void signed_scores8(const WselArgs &a, const Raw8<__half> &r, float cent, float (&d)[8]) {
     const uint32_t w4[4] = {r.w.x, r.w.y, r.w.z, r.w.w};
     float level[8];
+    if (a.score == CMPQ_SCORE_RESIDUAL && !a.codes) {  // no codes: the magnitude itself, from the nearest level
+        float wv[8];
+        unpack8(r, wv);
+        nearest_abs8(wv, cent, d);
+        return;
+    }
     if (a.score == CMPQ_SCORE_RESIDUAL) {
         // one branch for the whole piece, so that the eight lane exchanges are issued back to back
         const uint32_t c4[2] = {(r.c.x & 0x0f0f0f0fu) << 2, (r.c.y & 0x0f0f0f0fu) << 2};
@@ -1320,7 +1368,7 @@ extern "C" int cmpq_extract_outliers(int mode, int score, int scope, const float
     if (dtype != CMPQ_F16 && dtype != CMPQ_F32) return CMPQ_EINVAL;
     if (d_out < 0 || !bits || (k > 0 && !idx_out)) return CMPQ_EINVAL;
     if (d_in > 0 && d_out > 0 && !W) return CMPQ_EINVAL;
-    if (score == CMPQ_SCORE_RESIDUAL && d_in > 0 && d_out > 0 && (!centroids || !codes)) return CMPQ_EINVAL;
+    if (score == CMPQ_SCORE_RESIDUAL && d_in > 0 && d_out > 0 && !centroids) return CMPQ_EINVAL;
     if (ldw < d_out) return CMPQ_ESHAPE;
     if (d_in > 0 && d_out > ((int64_t)1 << 31) / d_in) return CMPQ_ESHAPE;  // linear index in int32
     if (scope == CMPQ_SCOPE_CHANNEL ? k > d_out : k > d_in * d_out) return CMPQ_ECOUNT;

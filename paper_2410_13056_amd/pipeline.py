@@ -125,15 +125,23 @@ def _channels_and_widths(sumsq, d_in, bit_set, avg_bits, rho_act_ppm, ws, timer)
     return act_idx, chan_mask, bits, counts
 
 
+def _histogram_kernel_takes(Wt: torch.Tensor) -> bool:
+    """Whether the histogram K-means kernel runs on this input (fp16, rows of whole groups of 4
+    entries, 8-byte aligned, a length it has a launch shape for): only it keeps per-channel
+    tables and leaves the coding pass out when no codes are asked for."""
+    d_in, d_out = Wt.shape
+    if Wt.dtype != torch.float16 or d_out % 4 or Wt.data_ptr() % 8 or (d_in > 1 and Wt.stride(0) % 4):
+        return False
+    return B.arrangement_bytes(d_in, d_out) > 0
+
+
 def _shared_tables(Wt: torch.Tensor) -> Optional[torch.Tensor]:
     """The buffer through which the preliminary K-means of a layer hands its per-channel tables
     to the final one (`cmpq_kmeans_job.arrangement`), or None where the histogram kernel would
-    not take the input (other than fp16, rows not whole groups of 4 or not 8-byte aligned)."""
-    d_in, d_out = Wt.shape
-    if Wt.dtype != torch.float16 or d_out % 4 or Wt.data_ptr() % 8 or (d_in > 1 and Wt.stride(0) % 4):
+    not take the input."""
+    if not _histogram_kernel_takes(Wt):
         return None
-    n = B.arrangement_bytes(d_in, d_out)
-    return torch.empty(n, dtype=torch.uint8, device=Wt.device) if n > 0 else None
+    return torch.empty(B.arrangement_bytes(*Wt.shape), dtype=torch.uint8, device=Wt.device)
 
 
 def _after_first_pass(Wt, sumsq, bit_set, counts, act_idx, chan_mask, bits, cent1, codes1, rho_q_ppm, iters,
@@ -228,9 +236,13 @@ def quantize_layer(W: torch.Tensor, sumsq: torch.Tensor, bit_set: Sequence[int],
     Wt = _oriented(W, transposed, timer)
     d_in, d_out = Wt.shape
     act_idx, chan_mask, bits, counts = _channels_and_widths(sumsq, d_in, bit_set, avg_bits, rho_act_ppm, ws, timer)
-    # preliminary quantization W'_q
+    # preliminary quantization W'_q.  Only its levels are needed further on: O_q ranks
+    # |w - nearest level|, which is |W' - W'_q| (Sec. 3 eq. Q(x)), so where the kernel can leave
+    # the codes out they are neither written nor read.
     cent1 = torch.empty((d_in, B.KMAX), dtype=torch.float32, device=dev)
-    codes1 = torch.empty((d_in, d_out), dtype=torch.uint8, device=dev)
+    codes1 = None
+    if keep_prelim or not _histogram_kernel_takes(Wt):
+        codes1 = torch.empty((d_in, d_out), dtype=torch.uint8, device=dev)
     tables = _shared_tables(Wt) if share_tables else None
     with _stage(timer, "kmeans_prelim"):
         B.kmeans_quantize(Wt, bits, None, 0, None, iters, cent1, codes1, ws, status, arrangement=tables,

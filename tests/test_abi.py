@@ -160,7 +160,10 @@ def test_host_side_argument_errors(L):
     assert L.cmpq_kmeans_quantize_job(job(d_out=40000, ldw=40000), fake, 1 << 20, None) == -2
     assert L.cmpq_kmeans_quantize_job(job(), fake, 16, None) == -5
     assert L.cmpq_kmeans_quantize_job(job(d_in=0), None, 0, None) == 0
-    assert L.cmpq_kmeans_quantize_job(job(codes=None), fake, 1 << 20, None) == -1               # codes only optional with the stored format
+    # no codes: only where the histogram kernel runs (fp16, unit importance, rows of whole groups of 4)
+    assert L.cmpq_kmeans_quantize_job(job(codes=None, dtype=1), fake, 1 << 20, None) == -1
+    assert L.cmpq_kmeans_quantize_job(job(codes=None, d_out=66, ldw=66), fake, 1 << 20, None) == -1
+    assert L.cmpq_kmeans_quantize_job(job(codes=None, elem_weight=256), fake, 1 << 20, None) == -1
     assert L.cmpq_kmeans_quantize_job(job(err_ch=256), fake, 1 << 20, None) == -1               # the stored format asked for in part
     bs3, one3 = (i32 * 3)(2, 3, 4), (i64 * 3)(1, 1, 1)
     nul3 = (ctypes.c_void_p * 3)(None, None, None)

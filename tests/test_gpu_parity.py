@@ -420,6 +420,56 @@ def test_kmeans_from_given_levels_weighted_and_flags(env):
     assert np.array_equal(c[ok], good[ok]) and np.array_equal(k[ok], gk[ok]) and k[2].max() < 16
 
 
+@pytest.mark.parametrize("d_in,d_out", [(40, 512), (9, 4096 + 8), (5, 28672), (33, 1024 + 4)])
+def test_kmeans_levels_alone(env, d_in, d_out):
+    """cmpq_kmeans_quantize without codes (what the preliminary quantization of Sec. 3.2.2 asks
+    for): the levels the call with codes leaves, bit for bit, on every launch shape of the
+    histogram kernel, with entries removed, from given levels, and with tables kept; the status
+    word still reports a non-finite weight; inputs other kernels take are refused."""
+    B, ws, orc = env["B"], env["ws"], env["orc"]
+    rng = np.random.default_rng(d_in + d_out)
+    W = rng.normal(0, 0.02, (d_in, d_out))
+    W[rng.random(W.shape) < 0.01] *= 8
+    W = W.astype(np.float16)
+    bits = rng.integers(1, 5, d_in).astype(np.uint8)
+    bits[1] = 16
+    dW, db = _dev(W), _dev(bits)
+    ocent, _ = orc.kmeans(W, bits, iters=4)
+    want, _ = _kmeans_gpu(env, W, bits, iters=4)
+    cent = torch.full((d_in, 16), -3.0, dtype=torch.float32, device=DEV)
+    B.kmeans_quantize(dW, db, None, 0, None, 4, cent, None, ws)
+    assert _np(cent).tobytes() == want.tobytes()
+    assert _rel(_np(cent)[bits <= 4][:, :2], ocent[bits <= 4][:, :2]) <= 1e-5
+    # with removed entries, from given levels
+    excl = np.sort(rng.choice(d_in * d_out, d_in * d_out // 50, replace=False)).astype(np.int32)
+    want2, _ = _kmeans_gpu(env, W, bits, out_idx=excl, iters=3, start=want)
+    cent2 = _dev(want.copy())
+    B.kmeans_quantize(dW, db, _dev(excl), len(excl), None, 3, cent2, None, ws, init=B.INIT_GIVEN)
+    assert _np(cent2).tobytes() == want2.tobytes()
+    # tables kept by a run without codes serve a later run
+    tables = torch.zeros(B.arrangement_bytes(d_in, d_out), dtype=torch.uint8, device=DEV)
+    cent3 = torch.empty_like(cent)
+    B.kmeans_quantize(dW, db, None, 0, None, 4, cent3, None, ws, arrangement=tables, arrangement_use=B.ARRANGEMENT_KEEP)
+    assert _np(cent3).tobytes() == want.tobytes()
+    want4, codes4 = _kmeans_gpu(env, W, bits, out_idx=excl, iters=4)
+    cent4 = torch.empty_like(cent)
+    k4 = torch.empty((d_in, d_out), dtype=torch.uint8, device=DEV)
+    B.kmeans_quantize(dW, db, _dev(excl), len(excl), None, 4, cent4, k4, ws, arrangement=tables,
+                      arrangement_use=B.ARRANGEMENT_REUSE)
+    assert _np(cent4).tobytes() == want4.tobytes() and np.array_equal(_np(k4), codes4)
+    # a non-finite weight is still reported
+    Wbad = W.copy()
+    Wbad[0, 3] = np.inf
+    st = torch.zeros(1, dtype=torch.int32, device=DEV)
+    B.kmeans_quantize(_dev(Wbad), db, None, 0, None, 2, cent, None, ws, st)
+    assert st.item() & B.STATUS_NONFINITE
+    # fp32 weights and importance weights go to kernels that always code
+    with pytest.raises(B.CmpqError):
+        B.kmeans_quantize(_dev(W.astype(np.float32)), db, None, 0, None, 2, cent, None, ws)
+    with pytest.raises(B.CmpqError):
+        B.kmeans_quantize(dW, db, None, 0, _dev(np.ones((d_in, d_out), np.float32)), 2, cent, None, ws)
+
+
 # ------------------------------------------------------------------ O_q
 
 @pytest.mark.parametrize("dtype", [np.float16, np.float32])
@@ -441,6 +491,11 @@ def test_weight_outliers_parity(env, dtype, d_in, d_out):
             oidx, oval = orc.weight_outliers(W, ocent, ocodes, bits, k, score)
             assert np.array_equal(_np(idx)[:k].astype(np.int64), oidx), (score, k)
             assert np.array_equal(_np(val)[:k].view(np.uint16), oval)
+            if score == B.SCORE_RESIDUAL:        # without codes: the distance to the nearest level
+                idx.fill_(-7)
+                B.extract_weight_outliers(Wd, cd, None, bd, k, idx, val, ws, score)
+                assert np.array_equal(_np(idx)[:k].astype(np.int64), oidx), ("no codes", k)
+                assert np.array_equal(_np(val)[:k].view(np.uint16), oval)
     # asking for more than the candidates: every candidate, then -1
     k = live + 5
     idx = torch.full((k,), -7, dtype=torch.int32, device=DEV)
@@ -475,6 +530,11 @@ def test_weight_outliers_staging_and_full_path(env, case):
             oidx, oval = orc.weight_outliers(W, ocent, ocodes, bits, k, score)
             assert np.array_equal(_np(idx).astype(np.int64), oidx), (case, score, k)
             assert np.array_equal(_np(val).view(np.uint16), oval)
+            if score == B.SCORE_RESIDUAL:
+                idx.fill_(-7)
+                B.extract_weight_outliers(Wd, cd, None, bd, k, idx, val, ws, score)
+                assert np.array_equal(_np(idx).astype(np.int64), oidx), (case, "no codes", k)
+                assert np.array_equal(_np(val).view(np.uint16), oval)
 
 
 @pytest.mark.parametrize("dtype", [np.float16, np.float32])
@@ -500,6 +560,11 @@ def test_weight_outliers_sampled_guess(env, dtype):
             oidx, oval = orc.weight_outliers(W, ocent, ocodes, bits, k, score)
             assert np.array_equal(_np(idx).astype(np.int64), oidx), (score, k)
             assert np.array_equal(_np(val).view(np.uint16), oval)
+            if score == B.SCORE_RESIDUAL:
+                idx.fill_(-7)
+                B.extract_weight_outliers(Wd, cd, None, bd, k, idx, val, ws, score)
+                assert np.array_equal(_np(idx).astype(np.int64), oidx), ("no codes", k)
+                assert np.array_equal(_np(val).view(np.uint16), oval)
 
 
 @pytest.mark.parametrize("dtype", [np.float16, np.float32])
@@ -524,6 +589,11 @@ def test_weight_outliers_per_channel_parity(env, dtype, d_in, d_out):
             oidx, oval = orc.weight_outliers_per_channel(W, ocent, ocodes, bits, k, score)
             assert np.array_equal(_np(idx)[:k * n_live].astype(np.int64), oidx), (score, k)
             assert np.array_equal(_np(val)[:k * n_live].view(np.uint16), oval)
+            if score == B.SCORE_RESIDUAL:
+                idx.fill_(-7)
+                B.extract_weight_outliers(Wd, cd, None, bd, k, idx, val, ws, score, B.SCOPE_CHANNEL)
+                assert np.array_equal(_np(idx)[:k * n_live].astype(np.int64), oidx), ("no codes", k)
+                assert np.array_equal(_np(val)[:k * n_live].view(np.uint16), oval)
 
 
 def test_layer_with_per_channel_outliers_end_to_end(env):

@@ -410,6 +410,46 @@ def test_weight_outliers_equal_full_sort(orc):
         orc.weight_outliers(W, cent, codes, bits, len(cand) + 1)
 
 
+def test_weight_outliers_without_codes_rank_distance_to_nearest_level(orc):
+    """Sec. 3.2.2 with Q(x) of Sec. 3: the preliminary quantization puts each weight on its
+    nearest level, so the residual is the distance to the nearest level.  With codes left out
+    both selections rank exactly that: equal to a full sort of min_j |w - q_j| (levels that did
+    not come from a clustering, so that nothing but the definition is used), and equal to the
+    selection with the clustering's own codes."""
+    rng = np.random.default_rng(131)
+    d_in, d_out = 14, 120
+    W = (rng.integers(-30, 30, (d_in, d_out)) / 64.0).astype(np.float16)
+    bits = rng.integers(1, 5, d_in).astype(np.uint8)
+    bits[[3, 9]] = orc.PROTECTED
+    live = [i for i in range(d_in) if bits[i] <= 4]
+    cent = np.full((d_in, 16), np.inf, np.float32)
+    for i in live:                                      # arbitrary levels, unsorted, some repeated
+        K = 1 << bits[i]
+        cent[i, :K] = rng.choice(np.arange(-28, 28) / 64.0 + 1 / 256.0, K).astype(np.float32)
+    dist = np.abs(W.astype(np.float64)[:, :, None] - cent.astype(np.float64)[:, None, :])
+    key = np.where(np.isfinite(cent)[:, None, :], dist, np.inf).min(axis=2).astype(np.float32)
+    cand = [i * d_out + o for i in live for o in range(d_out)]
+    flat = key.reshape(-1)
+    order = sorted(cand, key=lambda t: (-float(flat[t]), t))
+    for k in (0, 1, 33, len(cand) // 2, len(cand)):
+        idx, val = orc.weight_outliers(W, cent, None, bits, k)
+        assert list(idx) == sorted(order[:k])
+        assert np.array_equal(val, W.reshape(-1)[idx].view(np.uint16))
+    for k in (0, 1, 7, d_out):
+        idx, _ = orc.weight_outliers_per_channel(W, cent, None, bits, k)
+        want = []
+        for i in live:
+            row = sorted(range(d_out), key=lambda o: (-float(key[i, o]), o))
+            want += [i * d_out + o for o in sorted(row[:k])]
+        assert list(idx) == want
+    # with a clustering's levels and codes: the same selection either way
+    c1, k1 = orc.kmeans(W, bits, iters=4)
+    for k in (1, 50, len(cand) // 3):
+        assert np.array_equal(orc.weight_outliers(W, c1, None, bits, k)[0], orc.weight_outliers(W, c1, k1, bits, k)[0])
+    assert np.array_equal(orc.weight_outliers_per_channel(W, c1, None, bits, 5)[0],
+                          orc.weight_outliers_per_channel(W, c1, k1, bits, 5)[0])
+
+
 def test_residual_score_finds_planted_distorters_not_just_big_weights(orc):
     """Sec. 3.2.2: the criterion is the quantization residual, not the magnitude.  A lone
     far value in a tight channel has a large residual; a channel whose values are
