@@ -314,6 +314,9 @@ def main():
     ap.add_argument("--no-shared-tables", dest="shared_tables", action="store_false",
                     help="the final K-means builds its per-channel tables again instead of starting from "
                          "the ones the preliminary K-means kept (same results; sharing is the default)")
+    ap.add_argument("--prelim-codes", action="store_true",
+                    help="the preliminary K-means writes its codes and O_q reads them, instead of ranking the "
+                         "distance to the nearest level (same results; not the default)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (outside the timed region): under "
                          "rocprofv3 --pmc it gives the HBM counters a kernel of known traffic to scale by")
@@ -341,7 +344,7 @@ def main():
         return P.quantize_block(weights, acts, layers, wl.bit_set, wl.avg_bits, wl.rho_act_ppm,
                                 wl.rho_q_ppm, wl.iters, ws, with_error=True, status=status, timer=timer,
                                 streams=args.streams, join=join, fused=not args.two_calls,
-                                share_tables=args.shared_tables)
+                                share_tables=args.shared_tables, prelim_codes=args.prelim_codes)
 
     if args.calibration_copy:
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
@@ -400,7 +403,7 @@ def main():
     for _ in range(n_serial):
         o1 = P.quantize_block(weights, acts, layers, wl.bit_set, wl.avg_bits, wl.rho_act_ppm,
                               wl.rho_q_ppm, wl.iters, ws1, with_error=True, status=status, timer=t1,
-                              fused=not args.two_calls, share_tables=args.shared_tables)
+                              fused=not args.two_calls, share_tables=args.shared_tables, prelim_codes=args.prelim_codes)
         del o1
     serial = t1.totals()
     kern = t1.kernel_totals()
@@ -511,7 +514,7 @@ def main():
             return P.quantize_block(weights, acts, layers, wl.bit_set, wl.avg_bits, wl.rho_act_ppm,
                                     wl.rho_q_ppm, wl.iters, ws, with_error=True, status=status,
                                     streams=args.streams, join=False, iters_final_from_prelim=r,
-                                    fused=not args.two_calls, share_tables=args.shared_tables)
+                                    fused=not args.two_calls, share_tables=args.shared_tables, prelim_codes=args.prelim_codes)
         line["final_pass_continued_from_prelim"] = continued_final_pass(
             P, torch, step_variant, out, layers, wl, (5, wl.iters), args.continued_reps, args.streams, dev)
     if args.rtn_reps > 0:

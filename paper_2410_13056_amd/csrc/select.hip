@@ -403,6 +403,12 @@ __device__ __forceinline__ bool channel_live(const WselArgs &a, int64_t i) {
     return b >= 1 && b <= 4;
 }
 
+__device__ __forceinline__ int64_t uniform_i64(int64_t v) {
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)v);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)((uint64_t)v >> 32));
+    return (int64_t)(((uint64_t)hi << 32) | lo);
+}
+
 // Calls body(i, o0, raw, cent) for every wave-chunk in [q0, q1) of a live channel, in order;
 // o0 is this lane's first output, raw its 8 entries as loaded, cent level (lane & 15) of the
 // channel.  The loads of the next wave-chunk are issued before the current one is worked on
@@ -411,8 +417,10 @@ template <typename TW, typename F>
 __device__ __forceinline__ void for_each_raw_chunk(const WselArgs &a, int64_t q0, int64_t q1, F &&body) {
     if (q0 >= q1) return;
     const int lane = threadIdx.x & (CMPQ_WAVE - 1);
-    int64_t i = q0 / a.wc_per_channel;
-    int c = (int)(q0 % a.wc_per_channel);  // a channel has at most 2^31 / 512 wave-chunks
+    // (the same in every lane, but out of a division the compiler does per lane: taken back into
+    // scalar registers, so that the walk over channels and wave-chunks below is scalar work)
+    int64_t i = uniform_i64(q0 / a.wc_per_channel);
+    int c = __builtin_amdgcn_readfirstlane((int)(q0 % a.wc_per_channel));  // a channel has at most 2^31 / 512 wave-chunks
     const int wc_per_channel = (int)a.wc_per_channel, lane0 = lane * kWPerLane;
     bool live = channel_live(a, i);
     float cent = live && a.centroids ? a.centroids[i * CMPQ_KMAX + (lane & 15)] : 0.f;
@@ -590,6 +598,219 @@ __device__ __forceinline__ void stage_chunk_half(uint32_t cand, int64_t i, int o
     n_staged += tot;
 }
 
+// ---- staging without codes, FP16 weights: which weights can reach the threshold at all
+//
+// A weight stays below the threshold t iff it is closer than t to SOME level: the weights that do
+// are, level by level, a run of consecutive FP16 values around the level (the rounded difference
+// grows with the distance), and the runs of a channel's levels merge into a few intervals - one,
+// where the levels lie closer together than 2t.  The intervals are found once per channel, by
+// bisection on the very comparison the ranking makes (|fp32(w - level)| < t), so a weight is
+// inside one exactly when its score is below t; a wave-chunk is then tested with three packed
+// FP16 instructions per pair of weights and interval, and only the few weights outside every
+// interval get a score.
+
+// FP16 bit pattern <-> position in the order of the values (-0 just below +0).
+__device__ __forceinline__ uint32_t ord_of_half(uint32_t h) { return (h & 0x8000u) ? (~h & 0xffffu) : (h | 0x8000u); }
+__device__ __forceinline__ uint32_t half_of_ord(uint32_t o) { return (o & 0x8000u) ? (o & 0x7fffu) : (~o & 0xffffu); }
+constexpr uint32_t kOrdLo = 0x0400u, kOrdHi = 0xfbffu;  // -65504 and +65504: the finite values
+
+// What safe_intervals leaves for a channel: in lanes g < n the bounds of interval g (an FP16
+// pattern in both halves of a word) and the smallest and largest level whose run it holds.
+struct SafeIntervals {
+    int n;       // intervals; 0: none (then every weight is a candidate)
+    bool whole;  // every level has a run: a weight outside the intervals has one of the levels
+                 // lo_level / hi_level as its nearest
+    uint32_t lo_pk, hi_pk;
+    float lo_level, hi_level;
+};
+
+// The intervals of channel levels `cent` (level lane & 15 in every lane; K of them) for threshold
+// t (none when t is not positive: then every weight reaches it).  Called by all lanes of the
+// wavefront.
+__device__ __forceinline__ SafeIntervals safe_intervals(float cent, int K, float t) {
+    const int lane = threadIdx.x & (CMPQ_WAVE - 1), k = lane & 15;
+    // lanes 0-15: the lower end of level k's run; lanes 16-31: its upper end, searched in
+    // mirrored positions (0xffff - position) so that both searches look for a first position
+    const bool upper = (lane & 16) != 0, mine = lane < 32 && k < K;
+    auto reached = [&](uint32_t pos) -> bool {  // at or past the end searched for
+        const float v = __half2float(__ushort_as_half((uint16_t)half_of_ord(upper ? 0xffffu - pos : pos)));
+        return fabsf(v - cent) < t || (upper ? v <= cent : v >= cent);
+    };
+    // reached(a) false or a before the finite values; reached(b) true or b past them
+    uint32_t a = kOrdLo - 1, b = kOrdHi + 1;
+    uint32_t guess = ord_of_half(__half_as_ushort(__float2half_rn(upper ? cent + t : cent - t)));
+    if (upper) guess = 0xffffu - guess;
+    guess = min(max(guess, kOrdLo + 2), kOrdHi - 2);
+    if (mine) {  // two positions either side of the rounded end bracket it, but for rare roundings
+        if (!reached(guess - 2)) a = guess - 2;
+        if (reached(guess + 2)) b = guess + 2;
+    }
+    while (__ballot(mine && b - a > 1) != 0ull) {
+        if (mine && b - a > 1) {
+            const uint32_t mid = (a + b) >> 1;
+            if (reached(mid)) b = mid; else a = mid;
+        }
+    }
+    const uint32_t end = upper ? 0xffffu - b : b;  // first position of the run / its last
+    const uint32_t first = end, last = (uint32_t)__shfl((int)end, k + 16, CMPQ_WAVE);
+    // (a level that is itself an FP16 value would be "inside" at t <= 0 by the second clause above)
+    const bool valid = lane < 16 && k < K && first <= last && t > 0.f;
+    SafeIntervals r;
+    r.whole = (int)__popcll(__ballot(valid)) == K;
+    // runs in ascending order of their levels (first and last positions ascend with the level):
+    // rank by counting, send to the lane of the rank
+    const uint32_t cb = __float_as_uint(cent);
+    const uint32_t key = valid ? cb ^ ((cb >> 31) ? 0xffffffffu : 0x80000000u) : 0xffffffffu;
+    uint32_t rank = 0;
+    for (int j = 0; j < K; ++j) {  // (lanes past K hold the largest key and keep their places)
+        const uint32_t kj = (uint32_t)__builtin_amdgcn_readlane((int)key, j);
+        rank += (kj < key || (kj == key && j < k)) ? 1u : 0u;
+    }
+    if (k >= K) rank = (uint32_t)k;
+    const int to = (lane < 16 ? (int)rank : lane) << 2;  // a permutation of the lanes
+    const uint32_t sf = (uint32_t)__builtin_amdgcn_ds_permute(to, valid ? (int)first : 0x10000);
+    const uint32_t sl = (uint32_t)__builtin_amdgcn_ds_permute(to, valid ? (int)last : 0);
+    const float sc = __int_as_float(__builtin_amdgcn_ds_permute(to, __float_as_int(cent)));
+    const bool svalid = lane < 16 && sf <= 0xffffu;
+    // running largest last position; a run starts a new interval when an FP16 value lies between
+    uint32_t run_max = svalid ? sl : 0u;
+#pragma unroll
+    for (int d = 1; d < 16; d <<= 1) {
+        const uint32_t up = (uint32_t)__shfl_up((int)run_max, d, 16);
+        if (k >= d) run_max = max(run_max, up);
+    }
+    const uint32_t before = (uint32_t)__shfl_up((int)run_max, 1, 16);
+    const bool start = svalid && (lane == 0 || sf > before + 1u);
+    const uint32_t smask = (uint32_t)__ballot(start) & 0xffffu, vmask = (uint32_t)__ballot(svalid) & 0xffffu;
+    r.n = (int)__popc(smask);
+    const int gid = (int)__popc(smask & ((2u << k) - 1u)) - 1;
+    const bool stop = svalid && (((smask >> (k + 1)) & 1u) || !((vmask >> (k + 1)) & 1u));
+    const int to_lo = (start ? gid : 63) << 2, to_hi = (stop ? gid : 63) << 2;
+    r.lo_pk = half_of_ord((uint32_t)__builtin_amdgcn_ds_permute(to_lo, (int)sf)) * 0x10001u;
+    r.hi_pk = half_of_ord((uint32_t)__builtin_amdgcn_ds_permute(to_hi, (int)run_max)) * 0x10001u;
+    r.lo_level = __int_as_float(__builtin_amdgcn_ds_permute(to_lo, __float_as_int(sc)));
+    r.hi_level = __int_as_float(__builtin_amdgcn_ds_permute(to_hi, __float_as_int(sc)));
+    return r;
+}
+
+// The entries of the lane outside every interval: bit q for entry 2q, bit 16 + q for entry
+// 2q + 1 (the two halves of word q).  0 in every lane of the wavefront in many wave-chunks.
+__device__ __forceinline__ uint32_t outside_intervals8(const uint4 &w, const SafeIntervals &iv) {
+    const uint32_t w4[4] = {w.x, w.y, w.z, w.w};
+    uint32_t acc[4] = {~0u, ~0u, ~0u, ~0u};  // a half stays non-zero while no interval holds it
+    for (int g = 0; g < iv.n; ++g) {
+        const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)iv.lo_pk, g);
+        const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)iv.hi_pk, g);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            uint32_t c;  // the pair clamped into the interval: unchanged halves are inside
+            asm("v_pk_max_f16 %0, %1, %2" : "=v"(c) : "v"(w4[q]), "s"(lo));
+            asm("v_pk_min_f16 %0, %1, %2" : "=v"(c) : "v"(c), "s"(hi));
+            const uint32_t moved = c ^ w4[q];
+            if (g == 0) acc[q] = moved;
+            else asm("v_pk_min_u16 %0, %1, %2" : "=v"(acc[q]) : "v"(acc[q]), "v"(moved));
+        }
+    }
+    if (__ballot((acc[0] | acc[1] | acc[2] | acc[3]) != 0u) == 0ull) return 0u;
+    uint32_t out = 0;
+#pragma unroll
+    for (int q = 3; q >= 0; --q) {
+        uint32_t one;  // 1 in each half that is not zero
+        asm("v_pk_min_u16 %0, %1, %2" : "=v"(one) : "v"(acc[q]), "v"(0x00010001u));
+        out = out + out + one;
+    }
+    return out;
+}
+
+// The same layout for "entry j exists" (bit j of valid8).
+__device__ __forceinline__ uint32_t pairs_layout(uint32_t valid) {
+    uint32_t out = 0;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) out |= (((valid >> (2 * q)) & 1u) << q) | (((valid >> (2 * q + 1)) & 1u) << (16 + q));
+    return out;
+}
+
+// The smallest |w - level| over the K levels in the first lanes of `cent` (K uniform).
+__device__ __forceinline__ float nearest_abs1(float w, float cent, int K) {
+    float m = INFINITY;
+    for (int k = 0; k < K; k += 2) m = min3_abs(w - level_of_lane(cent, k), w - level_of_lane(cent, k + 1), m);
+    return m;
+}
+
+// The score of a weight outside every interval, formed by all lanes of the wavefront (the levels
+// cross lanes): such a weight lies below all levels of the interval above it and above all
+// levels of the one below, so its nearest level is among the intervals' end levels.
+__device__ __forceinline__ float outside_score(float wf, float cent, int K, const SafeIntervals &iv) {
+    if (iv.whole && iv.n > 0) {
+        float key = INFINITY;
+        for (int g = 0; g < iv.n; ++g)
+            key = min3_abs(wf - level_of_lane(iv.lo_level, g), wf - level_of_lane(iv.hi_level, g), key);
+        return key;
+    }
+    return nearest_abs1(wf, cent, K);
+}
+
+// stage_chunk_half for staging without codes: `cand` in the layout of outside_intervals8; the
+// key of a candidate is formed here.
+__device__ __forceinline__ void stage_chunk_nearest(uint32_t cand, int64_t i, int o0, int64_t d_out, const uint4 &w,
+                                                    float cent, int K, const SafeIntervals &iv,
+                                                    unsigned long long *__restrict__ stage_ik,
+                                                    uint16_t *__restrict__ stage_val, uint32_t cap,
+                                                    uint32_t &n_staged, bool &over) {
+    const unsigned long long has = __ballot(cand != 0);
+    if (has == 0ull) return;
+    const uint32_t w4[4] = {w.x, w.y, w.z, w.w};
+    auto half_at = [&](int q, int hi) -> uint16_t {  // half `hi` of word q
+        uint32_t wq = w4[0];
+#pragma unroll
+        for (int t = 1; t < 4; ++t)
+            if (q == t) wq = w4[t];
+        return (uint16_t)(wq >> (16 * hi));
+    };
+    const uint32_t base = (uint32_t)(i * d_out) + (uint32_t)o0;
+    if (__ballot((cand & (cand - 1)) != 0) == 0ull) {  // usual case: no lane holds two
+        const uint32_t tot = (uint32_t)__popcll(has);
+        if (n_staged + tot <= cap) {
+            const uint32_t pos = n_staged + __builtin_amdgcn_mbcnt_hi((uint32_t)(has >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)has, 0u));
+            const int bit = cand ? __ffs(cand) - 1 : 0, q = bit & 15, hi = bit >> 4;
+            const uint16_t hj = half_at(q, hi);
+            const float key = outside_score(__half2float(__ushort_as_half(hj)), cent, K, iv);
+            if (cand) {
+                stage_ik[pos] = ((unsigned long long)(base + (uint32_t)(2 * q + hi)) << 32) | __float_as_uint(key);
+                stage_val[pos] = hj;
+            }
+        } else {
+            over = true;
+        }
+        n_staged += tot;
+        return;
+    }
+    const uint32_t n_cand = __popc(cand);
+    const uint32_t incl = wave_scan_incl_u32(n_cand);
+    const uint32_t tot = __shfl(incl, CMPQ_WAVE - 1, CMPQ_WAVE);
+    if (n_staged + tot <= cap) {
+        // index order inside the lane: entry 2q before 2q + 1 before 2q + 2
+        uint32_t order = 0;  // bit j: entry j
+#pragma unroll
+        for (int q = 0; q < 4; ++q) order |= (((cand >> q) & 1u) << (2 * q)) | (((cand >> (16 + q)) & 1u) << (2 * q + 1));
+        uint32_t pos = n_staged + incl - n_cand;
+        while (__ballot(order != 0) != 0ull) {
+            const int j = order ? __ffs(order) - 1 : 0;
+            const uint16_t hj = half_at(j >> 1, j & 1);
+            const float key = outside_score(__half2float(__ushort_as_half(hj)), cent, K, iv);
+            if (order) {
+                order &= order - 1;
+                stage_ik[pos] = ((unsigned long long)(base + (uint32_t)j) << 32) | __float_as_uint(key);
+                stage_val[pos] = hj;
+                ++pos;
+            }
+        }
+    } else {
+        over = true;
+    }
+    n_staged += tot;
+}
+
 struct PickShared {
     uint32_t scan[17];
     uint32_t bin, total;
@@ -721,7 +942,8 @@ __global__ __launch_bounds__(kWThreads) void wsel_sample_kernel(WselArgs a, uint
 
 // Fast chain, the one pass over the data: stages every entry whose top 22 bits reach the
 // guess read off the sample's histograms.
-template <typename TW>
+// NEAR (FP16 weights, residual score, no codes): candidates by the channel's intervals.
+template <typename TW, bool NEAR>
 __global__ __launch_bounds__(kWThreads) void wsel_stage_kernel(WselArgs a, WselState *st,
                                                                 const uint32_t *__restrict__ hist) {
     __shared__ PickShared ps;
@@ -749,6 +971,24 @@ __global__ __launch_bounds__(kWThreads) void wsel_stage_kernel(WselArgs a, WselS
         // candidate, as its bit pattern would be), the conversion of a weight is folded into the
         // subtraction, and only a candidate's key and value are formed
         const float reach_f = __uint_as_float(reach);
+        if constexpr (NEAR) {
+            // no codes: per channel the intervals of weights that stay below the guess, per
+            // wave-chunk the weights outside them
+            int64_t have = -1;
+            int K = 0;
+            SafeIntervals iv = {};
+            for_each_raw_chunk<TW>(a, q0, q1, [&](int64_t i, int o0, const Raw8<TW> &raw, float cent) {
+                if (i != have) {
+                    have = i;
+                    K = levels_in(cent);
+                    iv = safe_intervals(cent, K, reach_f);
+                }
+                uint32_t cand = outside_intervals8(raw.w, iv);
+                if (o0 - lane * kWPerLane + kWaveChunk > (int)a.d_out)  // the ragged end of a channel (uniform)
+                    cand &= pairs_layout(valid8(o0, a.d_out));
+                stage_chunk_nearest(cand, i, o0, a.d_out, raw.w, cent, K, iv, stage_ik, stage_val, a.cap, n_staged, over);
+            });
+        } else
         for_each_raw_chunk<TW>(a, q0, q1, [&](int64_t i, int o0, const Raw8<TW> &raw, float cent) {
             float d[8];
             signed_scores8(a, raw, cent, d);
@@ -1253,7 +1493,10 @@ int launch_weight_select(WselArgs a, const WselPlan &p, int64_t k, int32_t *idx_
     wsel_sample_kernel<TW, 0><<<(unsigned)sample_blocks, kWThreads, 0, s>>>(a, w.hist);
     wsel_sample_kernel<TW, 1><<<(unsigned)sample_blocks, kWThreads, 0, s>>>(a, w.hist);
     cmpq_timing_before(CMPQ_KERNEL_OUTLIER_STAGE, s);
-    wsel_stage_kernel<TW><<<p.nblocks, kWThreads, 0, s>>>(a, w.st, w.hist);
+    if (std::is_same<TW, __half>::value && a.score == CMPQ_SCORE_RESIDUAL && !a.codes)
+        wsel_stage_kernel<TW, true><<<p.nblocks, kWThreads, 0, s>>>(a, w.st, w.hist);
+    else
+        wsel_stage_kernel<TW, false><<<p.nblocks, kWThreads, 0, s>>>(a, w.st, w.hist);
     cmpq_timing_after(CMPQ_KERNEL_OUTLIER_STAGE, s);
     const int list_blocks = p.nblocks < 256 ? p.nblocks : 256;  // few: each ends with a flush into shared counters
     wsel_list_kernel<0><<<list_blocks, kWThreads, 0, s>>>(a, w.st, p.nunits, w.hist, (uint64_t)k);

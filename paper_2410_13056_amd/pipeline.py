@@ -212,7 +212,7 @@ def quantize_layer(W: torch.Tensor, sumsq: torch.Tensor, bit_set: Sequence[int],
                    status: Optional[torch.Tensor] = None, transposed: bool = False,
                    timer: Optional[StageTimer] = None,
                    iters_final_from_prelim: Optional[int] = None, oq_per_channel: bool = False,
-                   fused: bool = True, share_tables: bool = True) -> LayerResult:
+                   fused: bool = True, share_tables: bool = True, prelim_codes: bool = False) -> LayerResult:
     """Quantizes one layer.  `W` is the framework's [d_out, d_in] weight (or already
     d_in x d_out with ``transposed=True``); `sumsq` comes from `activation_stats`.
 
@@ -222,6 +222,11 @@ def quantize_layer(W: torch.Tensor, sumsq: torch.Tensor, bit_set: Sequence[int],
     ``fused`` (with ``with_error``): the final K-means writes the stored format and the error
     from its coding pass (`cmpq_kmeans_quantize_job`); ``fused=False`` runs `cmpq_kmeans_quantize`
     and `cmpq_pack_with_error` one after the other.  Same results.
+
+    ``prelim_codes`` (off by default): the preliminary K-means also writes its codes and O_q reads
+    them, as the calls were first laid out.  Same results; off, the preliminary run leaves only
+    its levels and O_q ranks the distance to the nearest level (one byte per weight less written
+    and read again), where the histogram kernel runs.
 
     ``share_tables`` (on by default): the preliminary K-means leaves its per-channel tables for
     the final one (`cmpq_kmeans_job.arrangement`), which then does not build them again.  Same
@@ -241,7 +246,7 @@ def quantize_layer(W: torch.Tensor, sumsq: torch.Tensor, bit_set: Sequence[int],
     # the codes out they are neither written nor read.
     cent1 = torch.empty((d_in, B.KMAX), dtype=torch.float32, device=dev)
     codes1 = None
-    if keep_prelim or not _histogram_kernel_takes(Wt):
+    if keep_prelim or prelim_codes or not _histogram_kernel_takes(Wt):
         codes1 = torch.empty((d_in, d_out), dtype=torch.uint8, device=dev)
     tables = _shared_tables(Wt) if share_tables else None
     with _stage(timer, "kmeans_prelim"):
@@ -501,7 +506,8 @@ def quantize_block(weights: Dict[str, torch.Tensor], acts: Dict[str, torch.Tenso
                    ws=None, with_error: bool = False, status: Optional[torch.Tensor] = None,
                    timer: Optional[StageTimer] = None, streams: int = 1,
                    join: bool = True, iters_final_from_prelim: Optional[int] = None,
-                   fused: bool = True, share_tables: bool = True) -> Dict[str, LayerResult]:
+                   fused: bool = True, share_tables: bool = True,
+                   prelim_codes: bool = False) -> Dict[str, LayerResult]:
     """One pass of the whole path over a decoder block: statistics once per distinct
     input, then every linear layer.  `layers` lists (name, x_key) pairs.
 
@@ -528,7 +534,7 @@ def quantize_block(weights: Dict[str, torch.Tensor], acts: Dict[str, torch.Tenso
             out[name] = quantize_layer(weights[name], stats[x_key], bit_set, avg_bits, rho_act_ppm,
                                        rho_q_ppm, iters, ws, with_error=with_error, status=status,
                                        timer=timer, iters_final_from_prelim=iters_final_from_prelim, fused=fused,
-                                       share_tables=share_tables)
+                                       share_tables=share_tables, prelim_codes=prelim_codes)
         return out
     if ws is None:
         ws = [B.Workspace(dev) for _ in range(streams)]
@@ -557,7 +563,7 @@ def quantize_block(weights: Dict[str, torch.Tensor], acts: Dict[str, torch.Tenso
                                            rho_q_ppm, iters, ws[j], with_error=with_error,
                                            status=status, timer=timer,
                                            iters_final_from_prelim=iters_final_from_prelim, fused=fused,
-                                           share_tables=share_tables)
+                                           share_tables=share_tables, prelim_codes=prelim_codes)
     if join:
         for st in side:
             main.wait_stream(st)

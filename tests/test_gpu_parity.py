@@ -567,6 +567,52 @@ def test_weight_outliers_sampled_guess(env, dtype):
                 assert np.array_equal(_np(val).view(np.uint16), oval)
 
 
+@pytest.mark.parametrize("d_in,d_out", [(1536, 8192 + 8), (600, 28672), (96, 1000), (130, 1001)])
+def test_weight_outliers_without_codes_edge_values(env, d_in, d_out):
+    """O_q without codes on FP16 weights, where the staging pass tells candidates from the
+    channel's intervals of "close to some level": levels that did not come from a clustering
+    (unsorted, repeated, outside the weights' range, not FP16 values, equal to weights), weights
+    at the ends of the FP16 range, zeros of both signs and subnormals, channel lengths with a
+    ragged last wave-chunk and rows that rule out vector loads; from a handful of outliers
+    (a threshold wider than the gaps between levels: one interval) to a tenth of the layer (a
+    threshold below the FP16 spacing at some levels: no interval there).  Bit-exact against the
+    oracle's ranking of the distance to the nearest level."""
+    B, ws, orc = env["B"], env["ws"], env["orc"]
+    rng = np.random.default_rng(d_in + 3 * d_out)
+    W = rng.normal(0, 0.02, (d_in, d_out))
+    W[rng.random(W.shape) < 0.005] *= 8
+    W = W.astype(np.float16)
+    flat = W.reshape(-1)
+    special = np.array([65504, -65504, 0.0, -0.0, 6e-8, -6e-8, 6e-5, -6.1e-5, 1.0, -2.5], np.float16)
+    flat[rng.choice(flat.size, 400, replace=False)] = rng.choice(special, 400)
+    bits = rng.integers(1, 5, d_in).astype(np.uint8)
+    bits[[5, d_in - 1]] = 16
+    cent = np.full((d_in, 16), np.inf, np.float32)
+    for i in range(d_in):
+        if bits[i] > 4:
+            continue
+        K = 1 << bits[i]
+        lv = rng.normal(0, 0.03, K).astype(np.float32)
+        if i % 7 == 0:
+            lv[0] = lv[K - 1]                                   # a repeated level
+        if i % 11 == 0:
+            lv[K // 2] = np.float32(W[i, 3])                    # a level that is one of the weights
+        if i % 13 == 0:
+            lv[0] = np.float32(3.0e4)                           # far outside the weights
+        if i % 17 == 0:
+            lv[K - 1] = np.float32(-1e-7)                       # among the subnormals
+        cent[i, :K] = lv
+    live = int((bits <= 4).sum()) * d_out
+    Wd, cd, bd = _dev(W), _dev(cent), _dev(bits)
+    for k in (7, live // 2000, live // 100, live // 10):
+        idx = torch.full((k,), -7, dtype=torch.int32, device=DEV)
+        val = torch.zeros(k, dtype=torch.float16, device=DEV)
+        B.extract_weight_outliers(Wd, cd, None, bd, k, idx, val, ws)
+        oidx, oval = orc.weight_outliers(W, cent, None, bits, k)
+        assert np.array_equal(_np(idx).astype(np.int64), oidx), k
+        assert np.array_equal(_np(val).view(np.uint16), oval)
+
+
 @pytest.mark.parametrize("dtype", [np.float16, np.float32])
 @pytest.mark.parametrize("d_in,d_out", [(3, 5), (20, 96), (16, 2048 + 40), (70, 333), (40, 8192)])
 def test_weight_outliers_per_channel_parity(env, dtype, d_in, d_out):
