@@ -658,11 +658,18 @@ __device__ __forceinline__ void blank_one_place(uint32_t *words, uint32_t w0, ui
     }
 }
 
-// Occupancy: 6 wavefronts per SIMD for the 16-group variant (77 registers: 3 workgroups of
-// 512 lanes per compute unit, which is also what LDS allows at d_out = 28 672), 7 for the
-// shorter multi-wavefront variants (at most 72 registers: 7 workgroups of 256 lanes).
+// Registers: at most 64 per lane (8 wavefronts per SIMD), 72 for the two variants that would spill
+// at 64.  LDS, not registers, bounds the longest channels (3 workgroups of 512 lanes = 6
+// wavefronts per SIMD at d_out = 28 672), but what these leave free decides whether a wavefront
+// of a memory-bound kernel on another stream fits beside them; the 256-lane workgroups run 8 to
+// a compute unit instead of 7.  Measured against a budget of 77 / 72 registers: the kernel
+// alone 4-6 % shorter, the whole step with three streams 6 %.
+constexpr int min_waves_per_simd(int G, int T, int MODE) {
+    return (G == 16 && MODE == kModeFused) || (G == 8 && T == 128 && MODE == kModePlain) ? 7 : 8;
+}
 template <int G, int T, int LB, int MODE>
-__global__ __launch_bounds__(T) __attribute__((amdgpu_waves_per_eu(6, 7))) void kmeans_bucket_kernel(KmArgs a) {
+__global__ __launch_bounds__(T) __attribute__((amdgpu_waves_per_eu(min_waves_per_simd(G, T, MODE), 8)))
+void kmeans_bucket_kernel(KmArgs a) {
     constexpr int kBuckets = 1 << (16 - LB);
     constexpr bool kCodesFused = MODE != kModePlain;
     // dynamic LDS: places of the kept weights, ordered by bucket (a byte each; the bucket
