@@ -33,8 +33,8 @@ HBM_PEAK_GBS = 8000.0
 # Constants taken from the kept rocprofv3 --pmc summaries (bench.py cannot collect counters):
 # mean HBM bytes per k-means launch (FETCH_SIZE + WRITE_SIZE scaled by a plain copy of known
 # size) and mean vector-ALU instructions per k-means launch (SQ_INSTS_VALU, per wavefront).
-KMEANS_TRAFFIC_BYTES = {"block70b": 579.5e6}
-KMEANS_VALU_WAVE_INSTS_PER_STEP = {"block70b": 2.20e9}     # 14 launches
+KMEANS_TRAFFIC_BYTES = {"block70b": 584.8e6}
+KMEANS_VALU_WAVE_INSTS_PER_STEP = {"block70b": 1.86e9}     # 14 launches
 KMEANS_COUNTERS_FILE = "profiles/kmeans_bucket_block70b_counters.txt"
 
 
@@ -52,13 +52,14 @@ def measured_shader_clock(B, dev):
     return float((t[:, 0] / t[:, 1]).mean() * khz * 1e3 / 1e9)
 
 
-def credited_kmeans_flops(result, iters):
+def credited_kmeans_flops(result, iters, coded=True):
     """Per weight and Lloyd round: K-1 nearest-level compares and 2 accumulations; the
-    final coding K-1 compares.  Summed over the channels that are quantized."""
+    final coding (where the pass writes codes) K-1 compares.  Summed over the channels that
+    are quantized."""
     total = 0
     for b, c in zip(result.bit_set, result.counts):
         K = 1 << b
-        total += c * result.d_out * (iters * (K + 1) + (K - 1))
+        total += c * result.d_out * (iters * (K + 1) + (K - 1 if coded else 0))
     return total
 
 
@@ -413,7 +414,9 @@ def main():
         return n // steps, ms / steps
 
     # ---- k-means: the dominant kernel
-    flops = sum(credited_kmeans_flops(r, wl.iters) for r in out.values()) * 2      # two passes per layer
+    # two passes per layer; the preliminary one codes only on the route that hands codes to O_q
+    flops = sum(credited_kmeans_flops(r, wl.iters) + credited_kmeans_flops(r, wl.iters, coded=args.prelim_codes)
+                for r in out.values())
     n_km = per_step(kern, "kmeans_prelim", n_serial)[0] + per_step(kern, "kmeans_final", n_serial)[0]
     ms_km = per_step(kern, "kmeans_prelim", n_serial)[1] + per_step(kern, "kmeans_final", n_serial)[1]
     avg_launch_s = ms_km / 1e3 / max(n_km, 1)
@@ -422,8 +425,8 @@ def main():
     roofline = {"kernel": "kmeans_bucket_kernel", "bound": "alu", "achieved": achieved, "peak": FP32_PEAK_TFLOPS,
                 "unit": "TFLOP/s", "frac": achieved / FP32_PEAK_TFLOPS,
                 "traffic": KMEANS_TRAFFIC_BYTES.get(wl.name),
-                "what": "credited work (per weight and round K-1 compares + 2 accumulations, K-1 for the final "
-                        "coding: what a brute-force Lloyd executes) / mean duration of the kernel on one stream, "
+                "what": "credited work (per weight and round K-1 compares + 2 accumulations, K-1 for the coding "
+                        "of the final pass: what a brute-force Lloyd executes) / mean duration of the kernel on one stream, "
                         "against the published fp32 vector peak; the kernel reaches the same bits with fewer "
                         "operations, see `executed`",
                 "launches_per_step": n_km, "avg_launch_ms": avg_launch_s * 1e3,
@@ -461,7 +464,8 @@ def main():
     for kernel, stage, nbytes, what in (
             ("act_stats_vec_kernel", "act_stats", x_bytes, "X read once"),
             ("transpose16_vec_kernel", "transpose", 2 * esz * wl.params, "W read and written once"),
-            ("wsel_stage_kernel", "outlier_weights", live * (esz + 1), "weight and code of every candidate read once"),
+            ("wsel_stage_kernel", "outlier_weights", live * (esz + (1 if args.prelim_codes else 0)),
+             "weight and code of every candidate read once" if args.prelim_codes else "weight of every candidate read once"),
             ("pack_error_kernel", "pack_with_error", pe_bytes, "weight and code read once, packed words written")):
         n_k, ms_k = per_step(kern, stage, n_serial)
         if n_k == 0 or ms_k <= 0:
@@ -491,6 +495,9 @@ def main():
         "stages_note": "entry-point durations from events on the launch streams, in a repeat of the timed steps "
                        "(%.3f ms per step with the events in place)" % (dt_ev / args.steps * 1e3),
         "streams": args.streams,
+        "preliminary_pass": ("levels and codes; O_q reads the codes" if args.prelim_codes else
+                             "levels only; O_q ranks the distance to the nearest level") +
+                            ("; per-channel tables kept for the final pass" if args.shared_tables else ""),
         "final_pass": "two calls: cmpq_kmeans_quantize, cmpq_pack_with_error" if args.two_calls else
                       "one call: cmpq_kmeans_quantize_job writes the stored format and the error from its coding pass",
         "serial": {
