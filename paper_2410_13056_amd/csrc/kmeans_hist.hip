@@ -658,17 +658,19 @@ __device__ __forceinline__ void blank_one_place(uint32_t *words, uint32_t w0, ui
     }
 }
 
-// Registers: at most 64 per lane (8 wavefronts per SIMD), 72 for the two variants that would spill
-// at 64.  LDS, not registers, bounds the longest channels (3 workgroups of 512 lanes = 6
-// wavefronts per SIMD at d_out = 28 672), but what these leave free decides whether a wavefront
-// of a memory-bound kernel on another stream fits beside them; the 256-lane workgroups run 8 to
-// a compute unit instead of 7.  Measured against a budget of 77 / 72 registers: the kernel
-// alone 4-6 % shorter, the whole step with three streams 6 %.
-constexpr int min_waves_per_simd(int G, int T, int MODE) {
-    return (G == 16 && MODE == kModeFused) || (G == 8 && T == 128 && MODE == kModePlain) ? 7 : 8;
+// Registers and occupancy.  The longest channels (16 groups a lane, 512 lanes) are bound by LDS:
+// 3 workgroups = 6 wavefronts per SIMD at d_out = 28 672 whatever the registers; their budget is
+// 64 per lane (72 for the fused final pass, which would spill at 64), so that what they leave
+// free lets a wavefront of a memory-bound kernel on another stream in beside them.  Every other
+// variant keeps the occupancy it has always run at, 7 wavefronts per SIMD (72 registers; 7
+// workgroups of 256 lanes per compute unit).  Measured against budgets of 77 / 72 registers: the
+// kernel alone 3-4 % shorter, the whole step with three streams 5 %.
+constexpr int waves_per_simd(int G, int T, int MODE) {
+    return G == 16 && T == 512 && MODE != kModeFused ? 8 : 7;
 }
 template <int G, int T, int LB, int MODE>
-__global__ __launch_bounds__(T) __attribute__((amdgpu_waves_per_eu(min_waves_per_simd(G, T, MODE), 8)))
+__global__ __launch_bounds__(T)
+    __attribute__((amdgpu_waves_per_eu(waves_per_simd(G, T, MODE), waves_per_simd(G, T, MODE))))
 void kmeans_bucket_kernel(KmArgs a) {
     constexpr int kBuckets = 1 << (16 - LB);
     constexpr bool kCodesFused = MODE != kModePlain;
