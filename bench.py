@@ -33,8 +33,8 @@ HBM_PEAK_GBS = 8000.0
 # Constants taken from the kept rocprofv3 --pmc summaries (bench.py cannot collect counters):
 # mean HBM bytes per k-means launch (FETCH_SIZE + WRITE_SIZE scaled by a plain copy of known
 # size) and mean vector-ALU instructions per k-means launch (SQ_INSTS_VALU, per wavefront).
-KMEANS_TRAFFIC_BYTES = {"block70b": 584.8e6}
-KMEANS_VALU_WAVE_INSTS_PER_STEP = {"block70b": 1.86e9}     # 14 launches
+KMEANS_TRAFFIC_BYTES = {"block70b": 583.6e6}
+KMEANS_VALU_WAVE_INSTS_PER_STEP = {"block70b": 1.85e9}     # 14 launches
 KMEANS_COUNTERS_FILE = "profiles/kmeans_bucket_block70b_counters.txt"
 
 
