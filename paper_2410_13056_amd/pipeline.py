@@ -112,7 +112,8 @@ def _oriented(W: torch.Tensor, transposed: bool, timer):
 
 
 def _channels_and_widths(sumsq, d_in, bit_set, avg_bits, rho_act_ppm, ws, timer):
-    """O_act (Sec. 3.2.2), then Algorithm 1 on W' = W - O_act."""
+    """O_act (Sec. 3.2.2), then Algorithm 1 on W' = W - O_act.  Both depend on the statistic of
+    the layer's input only, not on its weights."""
     dev = sumsq.device
     k_act = B.count_ppm(rho_act_ppm, d_in)
     act_idx = torch.empty(k_act, dtype=torch.int32, device=dev)
@@ -212,7 +213,8 @@ def quantize_layer(W: torch.Tensor, sumsq: torch.Tensor, bit_set: Sequence[int],
                    status: Optional[torch.Tensor] = None, transposed: bool = False,
                    timer: Optional[StageTimer] = None,
                    iters_final_from_prelim: Optional[int] = None, oq_per_channel: bool = False,
-                   fused: bool = True, share_tables: bool = True, prelim_codes: bool = False) -> LayerResult:
+                   fused: bool = True, share_tables: bool = True, prelim_codes: bool = False,
+                   widths=None) -> LayerResult:
     """Quantizes one layer.  `W` is the framework's [d_out, d_in] weight (or already
     d_in x d_out with ``transposed=True``); `sumsq` comes from `activation_stats`.
 
@@ -228,6 +230,10 @@ def quantize_layer(W: torch.Tensor, sumsq: torch.Tensor, bit_set: Sequence[int],
     its levels and O_q ranks the distance to the nearest level (one byte per weight less written
     and read again), where the histogram kernel runs.
 
+    ``widths``: what `channels_and_widths` returned for this statistic, channel count, bit set,
+    average width and share of O_act - layers that read the same input have the same O_act and
+    the same widths, so a block ranks and allocates once per input.
+
     ``share_tables`` (on by default): the preliminary K-means leaves its per-channel tables for
     the final one (`cmpq_kmeans_job.arrangement`), which then does not build them again.  Same
     results, one buffer of about `d_in * (d_out + 8 KiB)` bytes more while the layer is in work;
@@ -240,7 +246,9 @@ def quantize_layer(W: torch.Tensor, sumsq: torch.Tensor, bit_set: Sequence[int],
     dev = W.device
     Wt = _oriented(W, transposed, timer)
     d_in, d_out = Wt.shape
-    act_idx, chan_mask, bits, counts = _channels_and_widths(sumsq, d_in, bit_set, avg_bits, rho_act_ppm, ws, timer)
+    if widths is None:
+        widths = _channels_and_widths(sumsq, d_in, bit_set, avg_bits, rho_act_ppm, ws, timer)
+    act_idx, chan_mask, bits, counts = widths
     # preliminary quantization W'_q.  Only its levels are needed further on: O_q ranks
     # |w - nearest level|, which is |W' - W'_q| (Sec. 3 eq. Q(x)), so where the kernel can leave
     # the codes out they are neither written nor read.
@@ -530,11 +538,14 @@ def quantize_block(weights: Dict[str, torch.Tensor], acts: Dict[str, torch.Tenso
         out = {}
         for name, x_key in layers:
             if x_key not in stats:
-                stats[x_key] = activation_stats(acts[x_key], ws, status=status, timer=timer)[1]
-            out[name] = quantize_layer(weights[name], stats[x_key], bit_set, avg_bits, rho_act_ppm,
+                sumsq = activation_stats(acts[x_key], ws, status=status, timer=timer)[1]
+                stats[x_key] = (sumsq, _channels_and_widths(sumsq, sumsq.numel(), bit_set, avg_bits, rho_act_ppm,
+                                                            ws, timer))
+            sumsq, widths = stats[x_key]
+            out[name] = quantize_layer(weights[name], sumsq, bit_set, avg_bits, rho_act_ppm,
                                        rho_q_ppm, iters, ws, with_error=with_error, status=status,
                                        timer=timer, iters_final_from_prelim=iters_final_from_prelim, fused=fused,
-                                       share_tables=share_tables, prelim_codes=prelim_codes)
+                                       share_tables=share_tables, prelim_codes=prelim_codes, widths=widths)
         return out
     if ws is None:
         ws = [B.Workspace(dev) for _ in range(streams)]
@@ -545,25 +556,28 @@ def quantize_block(weights: Dict[str, torch.Tensor], acts: Dict[str, torch.Tenso
     for st in side:
         st.wait_stream(main)
     x_of = dict(layers)
-    stats: Dict[str, tuple] = {}          # x_key -> (sumsq, event, stream index)
+    stats: Dict[str, tuple] = {}          # x_key -> (sumsq, O_act and widths, event, stream index)
     results: Dict[str, LayerResult] = {}
     for name, j in assign_layers({n: weights[n].numel() for n, _ in layers}, streams):
         x_key = x_of[name]
         with torch.cuda.stream(side[j]):
             if x_key not in stats:
                 sumsq = activation_stats(acts[x_key], ws[j], status=status, timer=timer)[1]
+                # O_act and the widths follow from the statistic alone: once per input, not per layer
+                widths = _channels_and_widths(sumsq, sumsq.numel(), bit_set, avg_bits, rho_act_ppm, ws[j], timer)
                 ev = torch.cuda.Event()
                 ev.record()
-                stats[x_key] = (sumsq, ev, j)
-            sumsq, ev, owner = stats[x_key]
+                stats[x_key] = (sumsq, widths, ev, j)
+            sumsq, widths, ev, owner = stats[x_key]
             if owner != j:
                 side[j].wait_event(ev)
-                sumsq.record_stream(side[j])      # its memory is not reused before this stream is done with it
+                for t in (sumsq,) + tuple(widths[:3]):
+                    t.record_stream(side[j])      # its memory is not reused before this stream is done with it
             results[name] = quantize_layer(weights[name], sumsq, bit_set, avg_bits, rho_act_ppm,
                                            rho_q_ppm, iters, ws[j], with_error=with_error,
                                            status=status, timer=timer,
                                            iters_final_from_prelim=iters_final_from_prelim, fused=fused,
-                                           share_tables=share_tables, prelim_codes=prelim_codes)
+                                           share_tables=share_tables, prelim_codes=prelim_codes, widths=widths)
     if join:
         for st in side:
             main.wait_stream(st)
