@@ -63,6 +63,27 @@ def test_q7b_layer_full_size(env):
         assert np.array_equal(_np(r.lut[j]).view(np.uint16), olut)
     tot = _np(r.err_total)
     assert abs(tot[0] - o["totals"][0]) <= 1e-4 * o["totals"][0]
+    # the call as the pipeline makes it by default: the preliminary run leaves levels and its
+    # per-channel tables but no codes, and O_q ranks the distance to the nearest level
+    r2 = P.quantize_layer(W, sumsq, wl.bit_set, wl.avg_bits, wl.rho_act_ppm, wl.rho_q_ppm, wl.iters, ws,
+                          with_error=True, status=status)
+    assert status.item() == 0 and r2.codes_prelim is None
+    _same_outputs(r, r2)
+
+
+def _same_outputs(a, b):
+    """Two runs of a layer left the same results, bit for bit (what is checked on one holds for the other)."""
+    assert a.counts == b.counts
+    for name in ("act_idx", "bits", "out_idx", "out_val", "centroids", "codes", "err_ch", "err_total"):
+        x, y = getattr(a, name), getattr(b, name)
+        assert (x is None) == (y is None), name
+        if x is not None:
+            assert torch.equal(x.view(torch.uint8), y.view(torch.uint8)), name
+    for name in ("packed", "chan_idx", "lut"):
+        for x, y in zip(getattr(a, name), getattr(b, name)):
+            assert (x is None) == (y is None), name
+            if x is not None:
+                assert torch.equal(x.view(torch.uint8), y.view(torch.uint8)), name
 
 
 def _selection_properties(Wt, cent1, codes1, bits, out_idx, out_val, k):
@@ -158,6 +179,17 @@ def test_block_layers_full_size(env, workload, layer):
     tot = _np(r.err_total)
     ref_w = float((r.err_ch * sumsq.double()).sum())
     assert abs(tot[0] - ref_w) <= 1e-9 * ref_w
+    # the call as the pipeline makes it by default (no preliminary codes: O_q from the distance to
+    # the nearest level), and the route that builds the final run's tables again: the same results
+    r2 = P.quantize_layer(W, sumsq, wl.bit_set, wl.avg_bits, wl.rho_act_ppm, wl.rho_q_ppm, wl.iters, ws,
+                          with_error=True, status=status)
+    assert status.item() == 0 and r2.codes_prelim is None
+    _same_outputs(r, r2)
+    del r2
+    r3 = P.quantize_layer(W, sumsq, wl.bit_set, wl.avg_bits, wl.rho_act_ppm, wl.rho_q_ppm, wl.iters, ws,
+                          with_error=True, status=status, share_tables=False, prelim_codes=True)
+    assert status.item() == 0
+    _same_outputs(r, r3)
 
 
 @pytest.mark.parametrize("join", [False, True])
