@@ -9,26 +9,36 @@
 
 namespace {
 
-// row_of[i] = row of channel i inside its width group, -1 when it stores no row.
+// row_of[i] = row of channel i inside its width group, -1 when it stores no row.  One pass: the
+// flags of up to four widths are scanned together, two 16-bit fields to a word (a step covers
+// 1024 channels, so no field overflows).
 __global__ __launch_bounds__(1024) void pack_index_kernel(const uint8_t *__restrict__ bits,
                                                           int64_t d_in, PackPtrs p,
                                                           int32_t *__restrict__ row_of) {
-    __shared__ uint32_t scan[17];
-    for (int64_t i = threadIdx.x; i < d_in; i += blockDim.x) row_of[i] = -1;
-    __syncthreads();
-    for (int j = 0; j < p.n_set; ++j) {
-        uint32_t run = 0;
-        for (int64_t base = 0; base < d_in; base += blockDim.x) {
-            const int64_t i = base + threadIdx.x;
-            const uint32_t f = i < d_in && bits[i] == p.width[j];
-            uint32_t total;
-            const uint32_t row = run + block_scan_excl_u32(f, scan, &total);
-            if (f) {
-                row_of[i] = (int32_t)row;
-                if (p.chan_idx[j]) p.chan_idx[j][row] = (int32_t)i;
-            }
-            run += total;
+    __shared__ uint32_t scan[34];
+    uint32_t run[4] = {0, 0, 0, 0};
+    for (int64_t base = 0; base < d_in; base += blockDim.x) {
+        const int64_t i = base + threadIdx.x;
+        int j = -1;
+        if (i < d_in) {
+            const int w = bits[i];
+            for (int t = 0; t < p.n_set; ++t)
+                if (w == p.width[t]) j = t;
         }
+        const uint32_t a = j == 0 ? 1u : (j == 1 ? 0x10000u : 0u), b = j == 2 ? 1u : (j == 3 ? 0x10000u : 0u);
+        uint32_t a_excl, b_excl, a_total, b_total;
+        block_scan_excl_2xu32(a, b, scan, a_excl, b_excl, a_total, b_total);
+        if (j >= 0) {
+            const uint32_t field = j < 2 ? a_excl : b_excl;
+            const uint32_t before = j == 0 ? run[0] : (j == 1 ? run[1] : (j == 2 ? run[2] : run[3]));
+            const uint32_t row = before + ((j & 1) ? field >> 16 : field & 0xffffu);
+            int32_t *list = j == 0 ? p.chan_idx[0] : (j == 1 ? p.chan_idx[1] : (j == 2 ? p.chan_idx[2] : p.chan_idx[3]));
+            row_of[i] = (int32_t)row;
+            if (list) list[row] = (int32_t)i;
+        } else if (i < d_in) {
+            row_of[i] = -1;
+        }
+        run[0] += a_total & 0xffffu, run[1] += a_total >> 16, run[2] += b_total & 0xffffu, run[3] += b_total >> 16;
     }
 }
 
