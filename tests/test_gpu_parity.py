@@ -613,6 +613,38 @@ def test_weight_outliers_without_codes_edge_values(env, d_in, d_out):
         assert np.array_equal(_np(val).view(np.uint16), oval)
 
 
+@pytest.mark.parametrize("seed", range(12))
+def test_weight_outliers_without_codes_random_levels_and_counts(env, seed):
+    """The same route over random draws: weight scale, number and spread of the levels (from
+    levels packed closer than the FP16 spacing to levels whole binades apart), channel length and
+    the count asked for all vary, so the threshold falls anywhere from far above the gaps
+    between levels (one interval per channel) to below them (one per level, or none)."""
+    B, ws, orc = env["B"], env["ws"], env["orc"]
+    rng = np.random.default_rng(1000 + seed)
+    d_in = int(rng.integers(40, 200))
+    d_out = int(rng.choice([512, 1000, 2048 + 24, 4096, 5000]))
+    scale = float(10.0 ** rng.uniform(-4, 1))
+    W = (rng.standard_t(3, (d_in, d_out)) * scale).astype(np.float16)
+    bits = rng.integers(1, 5, d_in).astype(np.uint8)
+    bits[rng.integers(0, d_in)] = 16
+    cent = np.full((d_in, 16), np.inf, np.float32)
+    for i in range(d_in):
+        if bits[i] <= 4:
+            K = 1 << bits[i]
+            spread = float(10.0 ** rng.uniform(-3, 1))
+            cent[i, :K] = (rng.normal(0, scale * spread, K)).astype(np.float32)
+    live = int((bits <= 4).sum()) * d_out
+    Wd, cd, bd = _dev(W), _dev(cent), _dev(bits)
+    for frac in (1e-4, 3e-3, 0.05, 0.4):
+        k = max(1, int(live * frac))
+        idx = torch.full((k,), -7, dtype=torch.int32, device=DEV)
+        val = torch.zeros(k, dtype=torch.float16, device=DEV)
+        B.extract_weight_outliers(Wd, cd, None, bd, k, idx, val, ws)
+        oidx, oval = orc.weight_outliers(W, cent, None, bits, k)
+        assert np.array_equal(_np(idx).astype(np.int64), oidx), (seed, k)
+        assert np.array_equal(_np(val).view(np.uint16), oval)
+
+
 @pytest.mark.parametrize("dtype", [np.float16, np.float32])
 @pytest.mark.parametrize("d_in,d_out", [(3, 5), (20, 96), (16, 2048 + 40), (70, 333), (40, 8192)])
 def test_weight_outliers_per_channel_parity(env, dtype, d_in, d_out):
